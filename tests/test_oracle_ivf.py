@@ -1,0 +1,308 @@
+"""Pins for the oracle's encode, search, reconstruction and ground truth (CPU only).
+
+The encode/search arithmetic is checked against (i) identities the paper states,
+(ii) pure-Python re-derivations through a different route (reconstruct the vector in
+the original frame, then take the inner product), (iii) brute force on tiny inputs,
+(iv) the paper's printed numbers, and (v) planted mistakes that each pin must catch.
+"""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import ivftq_oracle as orc
+from workloads import synth
+
+
+def _small_problem(n=600, d=16, L=6, b=3, nq=12, seed=5):
+    rng = np.random.default_rng(seed)
+    means = rng.normal(size=(L, d))
+    X = (means[rng.integers(0, L, n)] + 0.4 * rng.normal(size=(n, d))).astype(np.float32)
+    Q = (means[rng.integers(0, L, nq)] + 0.4 * rng.normal(size=(nq, d))).astype(np.float32)
+    init = synth.kmeans_init_indices(seed, n, L)
+    C, _ = orc.train_coarse(X, L, 5, init)
+    C = C.astype(np.float32)
+    Pi = orc.haar_rotation_from_gaussian(synth.gaussian_matrix(seed, d)).astype(np.float32)
+    c, tau = orc.codebook_fp32(b, d)
+    return X, Q, C, Pi, c, tau
+
+
+# ---------------------------------------------------------------- paper's printed numbers
+
+
+def test_bit_accounting_worked_examples(paper_numbers):
+    assert orc.bits_per_vector(4, 96, True) == paper_numbers["bits_deep_b4_sign"]
+    assert orc.bits_per_vector(4, 128, True) == paper_numbers["bits_sift_b4_sign"]
+    assert orc.bits_per_vector(4, 200, True) == paper_numbers["bits_t2i_b4_sign"]
+    # Stage-1-only storage at B bits has the same total as (B-1)+sign: the matched-memory column
+    for key, d in (("sift1m", 128), ("deep1m", 96)):
+        for B in (4, 5, 6):
+            mib = (1_000_000 * orc.bits_per_vector(B, d, False) / 8 + 1000 * d * 4) / 2 ** 20
+            assert abs(mib - paper_numbers[f"mem_mb_{key}_B{B}"]) <= 0.6
+            assert orc.bits_per_vector(B, d, False) == orc.bits_per_vector(B - 1, d, True)
+    assert abs(1000 * 128 * 4 / 2 ** 20 - paper_numbers["centroid_table_mb_L1000_d128"]) < 0.02
+
+
+def test_theorem_two_term_by_term(paper_numbers):
+    p = paper_numbers
+    D, bias, rand, tail = orc.theorem2_terms(p["t2_D4"], 4, 128, 1e-2)
+    assert abs(math.sqrt(2 * 4 * math.log(2)) - p["t2_M"]) < 1e-3
+    assert abs(math.log(2 / 1e-2) - p["t2_log2delta"]) < 1e-3
+    assert abs(math.log(3 * 128) - p["t2_log3d"]) < 1e-3
+    assert abs(bias - p["t2_bias"]) < 5e-3
+    assert abs(rand - p["t2_random"]) < 1e-3
+    assert abs(tail - p["t2_tail"]) < 5e-4
+    assert abs(D + bias + rand + tail - p["t2_total"]) < 6e-3
+    cs = orc.theorem1_bound(p["t2_D4"], 0.0, 128, 1e-2)
+    assert abs(cs - p["cs_total"]) < 5e-3
+    assert abs(cs - math.sqrt(p["t2_D4"]) - p["cs_conc"]) < 1e-3
+
+
+# ---------------------------------------------------------------- quantiser on the sphere
+
+
+@pytest.mark.parametrize("b,d", [(2, 64), (4, 64), (4, 128)])
+def test_flat_tq_error_matches_distortion_and_bounds(b, d):
+    """E||v^ - v||^2 = D_b(f_d) and E<v, v^> = 1 - D_b over the rotation; Theorems 1 and 2 hold."""
+    c, tau = orc.lloyd_max_codebook(b, d)
+    D = orc.codebook_distortion(c, tau, d)
+    Pi = orc.haar_rotation_from_gaussian(synth.gaussian_matrix(11, d))
+    V = synth.random_unit_vectors(1, 4000, d)
+    Vh = orc.tq_reconstruct(V, Pi, c, tau)
+    err2 = np.sum((Vh - V) ** 2, axis=1)
+    assert abs(err2.mean() - D) < 4 * err2.std() / math.sqrt(len(V)) + 1e-4
+    ip = np.sum(Vh * V, axis=1)
+    assert abs(ip.mean() - (1.0 - D)) < 4 * ip.std() / math.sqrt(len(V)) + 1e-4
+    # Lemma 2: per-coordinate error at most half the widest bin (outer bins end at +-1)
+    edges = np.concatenate(([-1.0], tau, [1.0]))
+    U = V @ Pi.T
+    assert np.max(np.abs(U - c[orc.quantize(U, tau)])) <= np.max(np.diff(edges))
+    # Theorem 1 (delta = 1e-2, R_d >= 0): no violation expected among 4000 vectors
+    assert np.all(np.sqrt(err2) <= orc.theorem1_bound(D, 0.0, d, 1e-2))
+    # Theorem 2: |<q,v> - <q,v^>| under the printed bound for random unit queries
+    Qs = synth.random_unit_vectors(2, 64, d, stream=101)
+    gap = np.abs(Qs @ (V - Vh).T)
+    assert gap.max() <= sum(orc.theorem2_terms(D, b, d, 1e-2))
+
+
+# ---------------------------------------------------------------- encode
+
+
+def test_encode_identities():
+    X, Q, C, Pi, c, tau = _small_problem()
+    enc = orc.encode(X, C, Pi, tau)
+    Xn = orc.normalize_rows(X)
+    Cd = C.astype(np.float64)
+    # assignment = brute-force argmax of the inner product, smallest index on ties
+    for i in range(0, len(X), 37):
+        best, arg = -np.inf, -1
+        for l in range(C.shape[0]):
+            s = float(np.dot(Xn[i], Cd[l]))
+            if s > best:
+                best, arg = s, l
+        assert arg == enc["assign"][i]
+        assert abs(best - enc["coarse"][i]) < 1e-15
+    # for unit vectors ||x - c||^2 = 2 - 2<x,c>  (the amplification identity, per vector)
+    cn = np.linalg.norm(Cd, axis=1)
+    g2 = 1.0 + cn[enc["assign"]] ** 2 - 2.0 * enc["coarse"]
+    np.testing.assert_allclose(enc["gamma"] ** 2, g2, atol=1e-12)
+    assert np.all(enc["gamma"] <= 2.0 + 1e-6)
+    # rho is a unit vector and is the rotated residual direction
+    np.testing.assert_allclose(np.linalg.norm(enc["rho"], axis=1), 1.0, atol=1e-12)
+    r = Xn - Cd[enc["assign"]]
+    back = enc["rho"] @ Pi.astype(np.float64) * enc["gamma"][:, None]      # Pi^T (gamma rho) = r
+    np.testing.assert_allclose(back, r, atol=1e-6)                         # Pi is fp32-rounded
+    # codes: rho_j lies in [tau_{code-1}, tau_code)
+    t = np.concatenate(([-np.inf], tau.astype(np.float64), [np.inf]))
+    assert np.all(enc["rho"] >= t[enc["codes"]]) and np.all(enc["rho"] < t[enc["codes"].astype(int) + 1])
+    # float16 norm is the nearest representable value
+    g16 = enc["gamma16"].astype(np.float64)
+    up = np.nextafter(enc["gamma16"], np.float16(np.inf)).astype(np.float64)
+    dn = np.nextafter(enc["gamma16"], np.float16(-np.inf)).astype(np.float64)
+    assert np.all(np.abs(g16 - enc["gamma"]) <= np.abs(up - enc["gamma"]))
+    assert np.all(np.abs(g16 - enc["gamma"]) <= np.abs(dn - enc["gamma"]))
+    # distance to the nearest boundary
+    assert np.all(enc["bdist"] >= 0) and enc["bdist"].max() <= 1.0
+    assert np.all(enc["gap"] >= 0)
+
+
+def test_zero_residual_and_zero_norm_rows():
+    X, Q, C, Pi, c, tau = _small_problem()
+    enc = orc.encode(C[:2] * 3.0, C, Pi, tau)     # inputs that are centroids themselves (scaled)
+    assert list(enc["assign"]) == [0, 1]
+    assert np.all(enc["gamma"] < 1e-7)
+    with pytest.raises(ValueError):
+        orc.encode(np.zeros((1, C.shape[1]), np.float32), C, Pi, tau)
+
+
+def test_reconstruction_error_is_gamma_squared_times_distortion():
+    """||x^ - x~||^2 = gamma^2 ||C(rho) - rho||^2, on average gamma^2 D_b: fails for a transposed
+    rotation, a wrong residual sign or a mis-indexed codebook."""
+    w = synth.scaled(synth.config_tiny(), 4000, 10)
+    X = synth.database(w, 0, 4000)
+    d, b = w.d, 4
+    init = synth.kmeans_init_indices(0, len(X), 32)
+    C, _ = orc.train_coarse(X, 32, 6, init)
+    Pi = orc.haar_rotation_from_gaussian(synth.gaussian_matrix(0, d))
+    c, tau = orc.lloyd_max_codebook(b, d)
+    D = orc.codebook_distortion(c, tau, d)
+    idx = orc.ListIndex(C, Pi, c, tau)
+    enc = idx.add(X)
+    Xn = orc.normalize_rows(X)
+    num, den = 0.0, 0.0
+    for l in range(32):
+        if len(idx.ids[l]) == 0:
+            continue
+        xh = orc.reconstruct(idx, l)
+        num += np.sum((xh - Xn[idx.ids[l]]) ** 2)
+        den += np.sum(idx.gamma16[l].astype(np.float64) ** 2)
+    assert abs(num / den - D) < 0.08 * D
+    # amplification: E||r||^2 = 2 (1 - E<x~, c~>)
+    assert abs(np.mean(enc["gamma"] ** 2) - 2 * (1 - np.mean(enc["coarse"]))) < 1e-12
+
+
+# ---------------------------------------------------------------- search
+
+
+def _python_search(X, Q, C, Pi, c, tau, lists, nprobe, k):
+    """Search re-derived in the original frame with explicit loops:
+    score = <q~, c~_l + gamma16 * Pi^T c[code]>."""
+    Qn = orc.normalize_rows(Q)
+    Cd, Pid, cd = C.astype(np.float64), Pi.astype(np.float64), c.astype(np.float64)
+    out = []
+    for q in Qn:
+        coarse = [(float(np.dot(q, Cd[l])), l) for l in range(len(Cd))]
+        coarse.sort(key=lambda t: (-t[0], t[1]))
+        cand = []
+        for _, l in coarse[:nprobe]:
+            ids, codes, g16 = lists[l]
+            for i in range(len(ids)):
+                xhat = Cd[l] + float(g16[i]) * (Pid.T @ cd[codes[i]])
+                cand.append((float(np.dot(q, xhat)), int(ids[i])))
+        cand.sort(key=lambda t: (-t[0], t[1]))
+        out.append(cand[:k])
+    return out
+
+
+def test_search_matches_original_frame_rederivation():
+    X, Q, C, Pi, c, tau = _small_problem()
+    idx = orc.ListIndex(C, Pi, c, tau)
+    idx.add(X)
+    assert idx.ntotal == len(X) and sum(len(i) for i in idx.ids) == len(X)
+    sc, ids, probes, S = orc.search(idx, Q, nprobe=3, k=7)
+    ref = _python_search(X, Q, C, Pi, c, tau,
+                         [(idx.ids[l], idx.codes[l], idx.gamma16[l]) for l in range(len(idx.ids))], 3, 7)
+    for qi, row in enumerate(ref):
+        assert [r[1] for r in row] == list(ids[qi])
+        np.testing.assert_allclose([r[0] for r in row], sc[qi], atol=1e-6)
+    assert np.all(np.diff(sc, axis=1) <= 0)
+
+
+def test_decomposition_is_exact_with_unquantised_residual():
+    """s_l + gamma <Pi q~, rho> = <q~, x~>: only the quantiser makes the estimate approximate."""
+    X, Q, C, Pi, c, tau = _small_problem(d=32)
+    Pi64 = orc.haar_rotation_from_gaussian(synth.gaussian_matrix(5, 32))
+    enc = orc.encode(X, C, Pi64, tau)
+    Xn, Qn = orc.normalize_rows(X), orc.normalize_rows(Q)
+    Z = Qn @ Pi64.T
+    S = Qn @ C.astype(np.float64).T
+    est = S[:, enc["assign"]] + (Z @ enc["rho"].T) * enc["gamma"][None, :]
+    np.testing.assert_allclose(est, Qn @ Xn.T, atol=1e-12)
+
+
+def test_search_padding_and_small_lists():
+    X, Q, C, Pi, c, tau = _small_problem()
+    idx = orc.ListIndex(C, Pi, c, tau)
+    idx.add(X[:5], ids=[10, 11, 12, 13, 14])
+    sc, ids, probes, _ = orc.search(idx, Q, nprobe=C.shape[0], k=8)
+    assert np.all(ids[:, 5:] == -1) and np.all(np.isneginf(sc[:, 5:]))
+    assert all(sorted(row[:5]) == [10, 11, 12, 13, 14] for row in ids)
+    assert np.all(np.sort(probes, axis=1) == np.arange(C.shape[0]))
+
+
+def test_recall_rises_with_probes_and_bits_and_reaches_ground_truth():
+    w = synth.scaled(synth.config_tiny(), 5000, 60)
+    X, Q = synth.database(w, 0, 5000), synth.queries(w, 60)
+    L = 32
+    C, _ = orc.train_coarse(X, L, 8, synth.kmeans_init_indices(0, len(X), L))
+    Pi = orc.haar_rotation_from_gaussian(synth.gaussian_matrix(0, w.d))
+    gt_sc, gt = orc.exact_topk(X, Q, 10)
+    rec = {}
+    for b in (2, 4, 6):
+        c, tau = orc.lloyd_max_codebook(b, w.d)
+        idx = orc.ListIndex(C, Pi, c, tau)
+        idx.add(X)
+        for p in (1, 4, L):
+            _, ids, _, _ = orc.search(idx, Q, p, 10)
+            rec[b, p] = orc.recall_at_k(ids, gt)
+    for b in (2, 4, 6):
+        assert rec[b, 1] <= rec[b, 4] <= rec[b, L]
+    assert rec[2, L] < rec[4, L] < rec[6, L]
+    # isotropic 64-d clusters make near neighbours almost equidistant, so recall is modest
+    assert rec[6, L] > 0.85
+    assert rec[4, L] > 0.6
+
+
+def test_exact_topk_against_python_loops():
+    rng = np.random.default_rng(3)
+    X = rng.normal(size=(70, 5)).astype(np.float32)
+    Q = rng.normal(size=(4, 5)).astype(np.float32)
+    sc, ids = orc.exact_topk(X, Q, 6)
+    for qi in range(4):
+        qn = Q[qi].astype(np.float64) / math.sqrt(sum(float(v) ** 2 for v in Q[qi]))
+        rows = []
+        for i in range(70):
+            xn = X[i].astype(np.float64) / math.sqrt(sum(float(v) ** 2 for v in X[i]))
+            rows.append((-sum(a * b for a, b in zip(qn, xn)), i))
+        rows.sort()
+        assert [r[1] for r in rows[:6]] == list(ids[qi])
+    assert orc.recall_at_k(ids, ids) == 1.0
+    assert orc.recall_at_k(np.full_like(ids, -1), ids) == 0.0
+
+
+# ---------------------------------------------------------------- k-means invariants
+
+
+def test_kmeans_invariants():
+    w = synth.scaled(synth.config_tiny(), 3000, 1)
+    X = synth.database(w, 0, 3000)
+    init = synth.kmeans_init_indices(0, len(X), 16)
+    prev = None
+    for it in (1, 3, 6):
+        C, inertia = orc.train_coarse(X, 16, it, init)
+        np.testing.assert_allclose(np.linalg.norm(C, axis=1), 1.0, atol=1e-12)
+        if prev is not None:
+            assert inertia <= prev + 1e-9          # Lloyd iterations never increase the objective
+        prev = inertia
+    # an initial centre that captures nothing is re-seeded rather than left empty
+    far = np.vstack([X, -X[:1]])
+    C, _ = orc.train_coarse(far, 4, 3, np.array([0, 1, 2, len(far) - 1]))
+    assert np.all(np.isfinite(C))
+
+
+# ---------------------------------------------------------------- planted mistakes
+
+
+@pytest.mark.parametrize("mistake", ["transpose_pi", "residual_sign", "codebook_shift", "drop_coarse"])
+def test_pins_catch_planted_mistakes(mistake):
+    """Each plausible slip must break the original-frame re-derivation pin."""
+    X, Q, C, Pi, c, tau = _small_problem()
+    idx = orc.ListIndex(C, Pi, c, tau)
+    idx.add(X)
+    lists = [(idx.ids[l], idx.codes[l], idx.gamma16[l]) for l in range(len(idx.ids))]
+    bad = orc.ListIndex(C, Pi, c, tau)
+    for l, (i, cd, g) in enumerate(lists):
+        bad.set_list(l, i, cd, g)
+    if mistake == "transpose_pi":
+        bad.Pi = bad.Pi.T.copy()
+    elif mistake == "residual_sign":
+        bad.gamma16 = [(-g.astype(np.float32)).astype(np.float16) for g in bad.gamma16]
+    elif mistake == "codebook_shift":
+        bad.c = np.roll(bad.c, 1)
+    elif mistake == "drop_coarse":
+        bad.centroids = bad.centroids * 0.0
+    sc, ids, _, _ = orc.search(bad, Q, nprobe=3, k=7)
+    ref = _python_search(X, Q, C, Pi, c, tau, lists, 3, 7)
+    same = all([r[1] for r in row] == list(ids[qi]) for qi, row in enumerate(ref))
+    close = all(np.allclose([r[0] for r in row], sc[qi], atol=1e-6) for qi, row in enumerate(ref))
+    assert not (same and close)
