@@ -1,0 +1,157 @@
+/*
+ * ivftq.h -- C ABI of the IVF-TQ hot path for AMD MI355X (gfx950).
+ *
+ * IVF-TQ (arxiv 2605.17415, Section "IVF-TQ / Architecture") is an inverted-file index whose
+ * residual layer needs no training: a fixed Haar rotation Pi followed by a Lloyd-Max scalar
+ * quantiser that depends only on (b, d).  This library holds the two data-parallel halves of
+ * that method as hand-written HIP kernels:
+ *
+ *   encode : x~ = x/|x| ; l = argmax_l <x~, c~_l> ; r = x~ - c~_l ; gamma = |r| ;
+ *            rho = Pi r / |Pi r| ; code_j = bin of rho_j ; append (id, codes, fp16 gamma) to list l
+ *   search : q~ = q/|q| ; s_l = <q~, c~_l> for all l ; probe the nprobe best cells ; z = Pi q~ ;
+ *            score_i = s_l + gamma_i * sum_j z_j * C[code_ij] ; k best scores per query
+ *
+ * Conventions
+ *   - "host" pointers are ordinary CPU memory, "device" pointers are HIP device memory on the
+ *     current device.  The caller owns every buffer it passes; the library owns the index.
+ *   - All matrices are dense row-major float32 unless stated.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Device work is
+ *     queued on it.  Calls that hand data back to the host, and ivftq_encode_add /
+ *     ivftq_train_coarse (which size storage from device results), synchronise that stream
+ *     before returning; ivftq_search and ivftq_encode_only return with work still queued.
+ *   - Every call returns an ivftq_status; nothing throws or aborts across this boundary.
+ *     Arguments are validated before any kernel is launched.  ivftq_last_error() gives a
+ *     thread-local message for the most recent failure.
+ *   - An index is not thread-safe: one call at a time per index.
+ *   - Limits: 1 <= b <= 8, 8 <= d <= 256, 1 <= nlist <= 16384, 1 <= nprobe <= min(nlist, 2048),
+ *     1 <= k <= 2048.
+ */
+#ifndef IVFTQ_H
+#define IVFTQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ivftq_index ivftq_index; /* opaque, library-owned */
+
+typedef int ivftq_status;
+enum {
+    IVFTQ_OK = 0,
+    IVFTQ_INVALID_ARG = 1,   /* NULL pointer, size or parameter out of range */
+    IVFTQ_BAD_STATE = 2,     /* e.g. encode or search before the coarse centroids exist */
+    IVFTQ_OOM = 3,           /* device or host allocation failed */
+    IVFTQ_HIP_ERROR = 4,     /* a HIP runtime call failed */
+    IVFTQ_ZERO_NORM = 5,     /* an input row has zero or non-finite norm; nothing was appended */
+    IVFTQ_UNSUPPORTED = 6    /* a size beyond the limits listed above */
+};
+
+/* ---- constants fixed by (b, d, seed): no device needed -------------------------------- */
+
+/* Lloyd-Max codebook for the coordinate density of a uniform point on the unit sphere in R^d,
+ * f_d(t) ~ (1 - t^2)^((d-3)/2)  (Appendix "Proofs of the rate-distortion bounds", Lemma 1).
+ * centroids_out: host, 2^b floats, ascending.  boundaries_out: host, 2^b - 1 floats, the
+ * midpoints of neighbouring centroids; coordinate value v gets code #{i : v >= boundary_i},
+ * i.e. bins are [tau_i, tau_{i+1}) (Appendix "Sign-bit refinement").  Computed in double and
+ * rounded to float. */
+ivftq_status ivftq_build_codebook(int b, int d, float* centroids_out, float* boundaries_out);
+
+/* Haar-distributed orthogonal matrix (same appendix, Setup): QR of a d x d Gaussian matrix with
+ * the sign of each column fixed so that diag(R) > 0.  pi_out: host, d*d floats, row-major, acting
+ * as u = Pi r.  The first form draws the Gaussian matrix from `seed`; the second takes it from
+ * the caller (g: host, d*d doubles, row-major) so that two implementations can be compared. */
+ivftq_status ivftq_haar_rotation(int d, uint64_t seed, float* pi_out);
+ivftq_status ivftq_haar_from_gaussian(int d, const double* g, float* pi_out);
+
+/* ---- index life cycle ------------------------------------------------------------------ */
+
+/* New empty index on the current HIP device: builds the (b, d) codebook and a Haar rotation from
+ * rotation_seed.  Coarse centroids must be trained or set before encoding or searching. */
+ivftq_status ivftq_create(int d, int b, int nlist, uint64_t rotation_seed, ivftq_index** out);
+ivftq_status ivftq_destroy(ivftq_index* index);
+
+/* Coarse partition (Section "Architecture", Indexing): Lloyd k-means on the L2-normalised rows of
+ * x_dev (device, n x d), `niter` iterations, nearest mean in Euclidean distance; the final
+ * centroids are L2-normalised.  init_rows_host: host, nlist distinct row numbers used as initial
+ * centres, or NULL to draw them from `seed`.  An empty cell is re-seeded from a member of the
+ * largest cell.  Needs n >= nlist.  inertia_out (host, may be NULL) receives the k-means
+ * objective of the last assignment step.  Synchronises. */
+ivftq_status ivftq_train_coarse(ivftq_index* index, const float* x_dev, int64_t n, int niter,
+                                const int64_t* init_rows_host, uint64_t seed, double* inertia_out,
+                                void* stream);
+
+/* Inject / read back constants (host pointers).  centroids: nlist x d, rows are used as given
+ * (they should be unit vectors).  pi: d x d.  Setting either on a non-empty index is BAD_STATE. */
+ivftq_status ivftq_set_coarse(ivftq_index* index, const float* centroids_host);
+ivftq_status ivftq_get_coarse(const ivftq_index* index, float* centroids_host);
+ivftq_status ivftq_set_rotation(ivftq_index* index, const float* pi_host);
+ivftq_status ivftq_get_rotation(const ivftq_index* index, float* pi_host);
+/* centroids_out: 2^b floats, boundaries_out: 2^b - 1 floats (either may be NULL). */
+ivftq_status ivftq_get_codebook(const ivftq_index* index, float* centroids_out, float* boundaries_out);
+
+/* ---- encode (Section "Architecture", Indexing and Bit accounting) ---------------------- */
+
+/* Encode the n rows of x_dev (device, n x d) and append each to the inverted list of its coarse
+ * cell, in input order.  ids_dev: device, n int64 labels, or NULL for consecutive labels
+ * continuing from ivftq_ntotal().  Stored per vector: b*d code bits, a float16 residual norm and
+ * the label.  On IVFTQ_ZERO_NORM nothing is appended.  Synchronises. */
+ivftq_status ivftq_encode_add(ivftq_index* index, const float* x_dev, int64_t n,
+                              const int64_t* ids_dev, void* stream);
+
+/* Append vectors that are already encoded (the storage half of encode on its own, e.g. to import
+ * an index built elsewhere).  assign_dev: n int32 cell numbers in [0, nlist); codes_dev: n x d
+ * uint8 bin numbers in [0, 2^b); gamma_dev: n float16 bit patterns; ids_dev: n int64 labels or NULL
+ * for consecutive labels.  All device pointers.  Rows are appended in input order.  A cell number
+ * out of range gives IVFTQ_INVALID_ARG and nothing is appended.  Synchronises. */
+ivftq_status ivftq_add_encoded(ivftq_index* index, int64_t n, const int32_t* assign_dev,
+                               const uint8_t* codes_dev, const uint16_t* gamma_dev,
+                               const int64_t* ids_dev, void* stream);
+
+/* Encode without storing.  Any output may be NULL.  assign_dev: n int32 cell numbers;
+ * codes_dev: n x d uint8 bin numbers (one per byte); gamma_dev: n float16 bit patterns of |r|.
+ * Rows with zero norm get cell -1.  Asynchronous. */
+ivftq_status ivftq_encode_only(ivftq_index* index, const float* x_dev, int64_t n,
+                               int32_t* assign_dev, uint8_t* codes_dev, uint16_t* gamma_dev,
+                               void* stream);
+
+/* ---- search (Section "Architecture", Search) ------------------------------------------- */
+
+/* For each of the nq rows of q_dev (device, nq x d): scores_dev[nq x k] (float32, descending)
+ * and ids_dev[nq x k] (int64 labels) of the k largest estimated inner products <q~, x~> among the
+ * vectors of the nprobe cells with the largest <q~, c~_l>.  Equal scores are ordered by label.
+ * Queries with fewer than k candidates are padded with label -1 and score -infinity.
+ * Asynchronous on `stream`; uses workspace owned by the index. */
+ivftq_status ivftq_search(ivftq_index* index, const float* q_dev, int64_t nq, int nprobe, int k,
+                          float* scores_dev, int64_t* ids_dev, void* stream);
+
+/* The first two steps of search on their own: probe_dev[nq x nprobe] int32 cell numbers ordered
+ * by decreasing <q~, c~_l> (ties: smaller cell first) and coarse_dev[nq x nprobe] those inner
+ * products.  Either output may be NULL.  Asynchronous. */
+ivftq_status ivftq_coarse_probe(ivftq_index* index, const float* q_dev, int64_t nq, int nprobe,
+                                int32_t* probe_dev, float* coarse_dev, void* stream);
+
+/* ---- inspection ------------------------------------------------------------------------ */
+
+int64_t ivftq_ntotal(const ivftq_index* index);
+ivftq_status ivftq_list_size(const ivftq_index* index, int list, int64_t* n_out);
+/* Copy one inverted list to the host in stored order.  ids_host: n int64; codes_host: n x d uint8
+ * (unpacked bin numbers); gamma_host: n float16 bit patterns.  Any may be NULL.  Synchronises the
+ * device. */
+ivftq_status ivftq_export_list(const ivftq_index* index, int list, int64_t* ids_host,
+                               uint8_t* codes_host, uint16_t* gamma_host);
+/* Bytes of device memory the stored vectors occupy (codes + norms + labels, without slack). */
+int64_t ivftq_index_bytes(const ivftq_index* index);
+/* Upper limit, in bytes, of the per-search score workspace (default 4 GiB); queries are processed
+ * in as many passes as that allows. */
+ivftq_status ivftq_set_workspace_limit(ivftq_index* index, int64_t bytes);
+
+const char* ivftq_last_error(void);
+const char* ivftq_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* IVFTQ_H */

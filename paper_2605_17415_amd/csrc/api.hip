@@ -1,0 +1,695 @@
+// C ABI of libivftq: argument checking, index life cycle, storage growth and the launch
+// sequences of encode (Section "Architecture", Indexing) and search (same section, Search).
+// All arithmetic of the hot path happens in the kernels; the host only sizes buffers and orders
+// launches.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <numeric>
+#include <string>
+#include <unordered_set>
+#include <vector>
+
+#include "../../include/ivftq.h"
+#include "host_math.h"
+#include "kernels.h"
+
+using namespace ivftq;
+
+namespace {
+
+thread_local std::string g_error;
+
+ivftq_status fail(ivftq_status code, const char* fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_error = buf;
+    return code;
+}
+
+#define HIP_TRY(expr)                                                                         \
+    do {                                                                                      \
+        hipError_t e_ = (expr);                                                               \
+        if (e_ != hipSuccess)                                                                 \
+            return fail(e_ == hipErrorOutOfMemory ? IVFTQ_OOM : IVFTQ_HIP_ERROR, "%s: %s",    \
+                        #expr, hipGetErrorString(e_));                                        \
+    } while (0)
+
+// Grow-only device buffer.
+struct DevBuf {
+    void* p = nullptr;
+    size_t bytes = 0;
+    hipError_t ensure(size_t need) {
+        if (need <= bytes) return hipSuccess;
+        if (p) { (void)hipFree(p); p = nullptr; bytes = 0; }
+        hipError_t e = hipMalloc(&p, need);
+        if (e == hipSuccess) bytes = need; else p = nullptr;
+        return e;
+    }
+    void release() { if (p) (void)hipFree(p); p = nullptr; bytes = 0; }
+    template <class T> T* as() const { return static_cast<T*>(p); }
+};
+
+uint64_t splitmix(uint64_t& s) {
+    uint64_t z = (s += 0x9E3779B97F4A7C15ull);
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+}  // namespace
+
+struct ivftq_index {
+    int d = 0, b = 0, nlist = 0, K = 0, dp = 0, lpad = 0, words = 0;
+    bool has_coarse = false;
+    std::vector<float> h_cent, h_pi, h_cb, h_tau;
+    // device constants
+    DevBuf cent, bias, pi, cb, tau;
+    // list storage
+    DevBuf codes, gamma, ids, d_off, d_size;
+    std::vector<int64_t> h_off, h_cap;
+    std::vector<int32_t> h_size;
+    int64_t pool_slots = 0;
+    int64_t ntotal = 0;
+    // workspace
+    DevBuf w_assign, w_slot, w_hist, w_count, w_base, w_flag, w_best;
+    DevBuf w_S, w_probe, w_coarse, w_z, w_candoff, w_scores;
+    DevBuf w_sums, w_counts, w_zero, w_rows, w_dst, w_obj;
+    int64_t ws_limit = (int64_t)4 << 30;
+
+    ListStore store() const {
+        ListStore s;
+        s.codes = codes.as<uint32_t>();
+        s.gamma = gamma.as<uint16_t>();
+        s.ids = ids.as<int64_t>();
+        s.list_off = d_off.as<int64_t>();
+        s.list_size = d_size.as<int32_t>();
+        s.words = words;
+        return s;
+    }
+    ~ivftq_index() {
+        for (DevBuf* bfr : {&cent, &bias, &pi, &cb, &tau, &codes, &gamma, &ids, &d_off, &d_size, &w_assign,
+                            &w_slot, &w_hist, &w_count, &w_base, &w_flag, &w_best, &w_S, &w_probe, &w_coarse,
+                            &w_z, &w_candoff, &w_scores, &w_sums, &w_counts, &w_zero, &w_rows, &w_dst, &w_obj})
+            bfr->release();
+    }
+};
+
+namespace {
+
+ivftq_status upload_coarse(ivftq_index* ix) {
+    std::vector<float> padded((size_t)ix->lpad * ix->dp, 0.f);
+    for (int l = 0; l < ix->nlist; ++l)
+        std::memcpy(&padded[(size_t)l * ix->dp], &ix->h_cent[(size_t)l * ix->d], sizeof(float) * ix->d);
+    HIP_TRY(hipMemcpy(ix->cent.p, padded.data(), padded.size() * sizeof(float), hipMemcpyHostToDevice));
+    std::vector<float> zero(ix->lpad, 0.f);
+    HIP_TRY(hipMemcpy(ix->bias.p, zero.data(), zero.size() * sizeof(float), hipMemcpyHostToDevice));
+    return IVFTQ_OK;
+}
+
+ivftq_status upload_rotation(ivftq_index* ix) {
+    std::vector<float> padded((size_t)ix->dp * ix->dp, 0.f);
+    for (int i = 0; i < ix->d; ++i)
+        std::memcpy(&padded[(size_t)i * ix->dp], &ix->h_pi[(size_t)i * ix->d], sizeof(float) * ix->d);
+    HIP_TRY(hipMemcpy(ix->pi.p, padded.data(), padded.size() * sizeof(float), hipMemcpyHostToDevice));
+    return IVFTQ_OK;
+}
+
+// Make every list able to hold need[l] vectors.  Lists keep their contents; the pool is rebuilt
+// with a quarter of slack per list whenever one list would overflow.
+ivftq_status ensure_capacity(ivftq_index* ix, const std::vector<int64_t>& need, hipStream_t st) {
+    bool ok = ix->pool_slots > 0;
+    for (int l = 0; ok && l < ix->nlist; ++l) ok = need[l] <= ix->h_cap[l];
+    if (ok) return IVFTQ_OK;
+
+    std::vector<int64_t> cap(ix->nlist), off(ix->nlist);
+    int64_t total = 0;
+    for (int l = 0; l < ix->nlist; ++l) {
+        int64_t want = need[l] + need[l] / 4 + kSlotsPerBlock;
+        cap[l] = round_up64(std::max(ix->h_cap.empty() ? 0 : ix->h_cap[l], want), kSlotsPerBlock);
+        off[l] = total;
+        total += cap[l];
+    }
+    DevBuf ncodes, ngamma, nids, noff;
+    hipError_t e = ncodes.ensure((size_t)total * ix->words * sizeof(uint32_t));
+    if (e == hipSuccess) e = ngamma.ensure((size_t)total * sizeof(uint16_t));
+    if (e == hipSuccess) e = nids.ensure((size_t)total * sizeof(int64_t));
+    if (e == hipSuccess) e = noff.ensure((size_t)ix->nlist * sizeof(int64_t));
+    if (e != hipSuccess) {
+        ncodes.release(); ngamma.release(); nids.release(); noff.release();
+        return fail(IVFTQ_OOM, "growing list storage to %lld slots: %s", (long long)total, hipGetErrorString(e));
+    }
+    HIP_TRY(hipMemcpyAsync(noff.p, off.data(), off.size() * sizeof(int64_t), hipMemcpyHostToDevice, st));
+    if (ix->ntotal > 0) {
+        ListStore from = ix->store(), to = from;
+        to.codes = ncodes.as<uint32_t>();
+        to.gamma = ngamma.as<uint16_t>();
+        to.ids = nids.as<int64_t>();
+        to.list_off = noff.as<int64_t>();
+        HIP_TRY(launch_copy_lists(from, to, ix->nlist, st));
+    }
+    HIP_TRY(hipStreamSynchronize(st));   // `off` is pageable host memory; old pool is about to be freed
+    ix->codes.release(); ix->gamma.release(); ix->ids.release(); ix->d_off.release();
+    ix->codes = ncodes; ix->gamma = ngamma; ix->ids = nids; ix->d_off = noff;
+    ix->h_cap = cap;
+    ix->h_off = off;
+    ix->pool_slots = total;
+    return IVFTQ_OK;
+}
+
+ivftq_status check_index(const ivftq_index* ix) {
+    if (!ix) return fail(IVFTQ_INVALID_ARG, "index is NULL");
+    return IVFTQ_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* ivftq_last_error(void) { return g_error.c_str(); }
+const char* ivftq_version(void) { return "ivftq-gfx950 0.1"; }
+
+ivftq_status ivftq_build_codebook(int b, int d, float* centroids_out, float* boundaries_out) {
+    if (b < 1 || b > 8 || d < 3) return fail(IVFTQ_INVALID_ARG, "need 1 <= b <= 8 and d >= 3 (b=%d d=%d)", b, d);
+    if (!centroids_out && !boundaries_out) return fail(IVFTQ_INVALID_ARG, "both outputs NULL");
+    std::vector<double> c, t;
+    if (!build_codebook(b, d, c, t)) return fail(IVFTQ_INVALID_ARG, "codebook construction failed");
+    if (centroids_out) for (size_t i = 0; i < c.size(); ++i) centroids_out[i] = (float)c[i];
+    if (boundaries_out) for (size_t i = 0; i < t.size(); ++i) boundaries_out[i] = (float)t[i];
+    return IVFTQ_OK;
+}
+
+ivftq_status ivftq_haar_from_gaussian(int d, const double* g, float* pi_out) {
+    if (d < 1 || !g || !pi_out) return fail(IVFTQ_INVALID_ARG, "bad argument to ivftq_haar_from_gaussian");
+    std::vector<double> q;
+    if (!haar_from_gaussian(d, g, q)) return fail(IVFTQ_INVALID_ARG, "matrix is rank deficient");
+    for (size_t i = 0; i < q.size(); ++i) pi_out[i] = (float)q[i];
+    return IVFTQ_OK;
+}
+
+ivftq_status ivftq_haar_rotation(int d, uint64_t seed, float* pi_out) {
+    if (d < 1 || !pi_out) return fail(IVFTQ_INVALID_ARG, "bad argument to ivftq_haar_rotation");
+    std::vector<double> g;
+    gaussian_matrix(d, seed, g);
+    return ivftq_haar_from_gaussian(d, g.data(), pi_out);
+}
+
+ivftq_status ivftq_create(int d, int b, int nlist, uint64_t rotation_seed, ivftq_index** out) {
+    if (!out) return fail(IVFTQ_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    if (b < 1 || b > 8) return fail(IVFTQ_INVALID_ARG, "b=%d outside [1, 8]", b);
+    if (d < 8) return fail(IVFTQ_INVALID_ARG, "d=%d below 8", d);
+    if (nlist < 1) return fail(IVFTQ_INVALID_ARG, "nlist=%d below 1", nlist);
+    if (d > kMaxD) return fail(IVFTQ_UNSUPPORTED, "d=%d above %d", d, kMaxD);
+    if (nlist > kMaxList) return fail(IVFTQ_UNSUPPORTED, "nlist=%d above %d", nlist, kMaxList);
+    ivftq_index* ix = new (std::nothrow) ivftq_index();
+    if (!ix) return fail(IVFTQ_OOM, "host allocation failed");
+    ix->d = d; ix->b = b; ix->nlist = nlist; ix->K = 1 << b;
+    ix->dp = rot_dp(d);
+    ix->lpad = round_up(nlist, 64);
+    ix->words = code_words(b, d);
+    ix->h_cb.resize(ix->K);
+    ix->h_tau.resize(ix->K - 1);
+    ix->h_pi.resize((size_t)d * d);
+    ix->h_cent.assign((size_t)nlist * d, 0.f);
+    ix->h_size.assign(nlist, 0);
+    ix->h_cap.assign(nlist, 0);
+    ix->h_off.assign(nlist, 0);
+    ivftq_status s = ivftq_build_codebook(b, d, ix->h_cb.data(), ix->h_tau.data());
+    if (s == IVFTQ_OK) s = ivftq_haar_rotation(d, rotation_seed, ix->h_pi.data());
+    if (s != IVFTQ_OK) { delete ix; return s; }
+    auto guard = [&](hipError_t e, const char* what) -> ivftq_status {
+        if (e == hipSuccess) return IVFTQ_OK;
+        ivftq_status code = fail(e == hipErrorOutOfMemory ? IVFTQ_OOM : IVFTQ_HIP_ERROR, "%s: %s", what,
+                                 hipGetErrorString(e));
+        return code;
+    };
+    std::vector<float> tau_pad(256, 0.f);
+    std::copy(ix->h_tau.begin(), ix->h_tau.end(), tau_pad.begin());
+    std::vector<int32_t> zeros(nlist, 0);
+    hipError_t e = ix->cent.ensure((size_t)ix->lpad * ix->dp * sizeof(float));
+    if (e == hipSuccess) e = ix->bias.ensure((size_t)ix->lpad * sizeof(float));
+    if (e == hipSuccess) e = ix->pi.ensure((size_t)ix->dp * ix->dp * sizeof(float));
+    if (e == hipSuccess) e = ix->cb.ensure(256 * sizeof(float));
+    if (e == hipSuccess) e = ix->tau.ensure(256 * sizeof(float));
+    if (e == hipSuccess) e = ix->d_size.ensure((size_t)nlist * sizeof(int32_t));
+    if (e == hipSuccess) e = ix->d_off.ensure((size_t)nlist * sizeof(int64_t));
+    if (e == hipSuccess) e = ix->w_flag.ensure(64);
+    if (e == hipSuccess) e = hipMemcpy(ix->cb.p, ix->h_cb.data(), ix->K * sizeof(float), hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(ix->tau.p, tau_pad.data(), 256 * sizeof(float), hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(ix->d_size.p, zeros.data(), nlist * sizeof(int32_t), hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemset(ix->d_off.p, 0, (size_t)nlist * sizeof(int64_t));
+    if ((s = guard(e, "device set-up")) != IVFTQ_OK) { delete ix; return s; }
+    if ((s = upload_rotation(ix)) != IVFTQ_OK) { delete ix; return s; }
+    *out = ix;
+    return IVFTQ_OK;
+}
+
+ivftq_status ivftq_destroy(ivftq_index* index) {
+    if (!index) return IVFTQ_OK;
+    (void)hipDeviceSynchronize();
+    delete index;
+    return IVFTQ_OK;
+}
+
+ivftq_status ivftq_set_coarse(ivftq_index* ix, const float* centroids_host) {
+    if (check_index(ix)) return IVFTQ_INVALID_ARG;
+    if (!centroids_host) return fail(IVFTQ_INVALID_ARG, "centroids_host is NULL");
+    if (ix->ntotal > 0) return fail(IVFTQ_BAD_STATE, "centroids cannot change once vectors are stored");
+    for (size_t i = 0; i < (size_t)ix->nlist * ix->d; ++i)
+        if (!std::isfinite(centroids_host[i])) return fail(IVFTQ_INVALID_ARG, "non-finite centroid value");
+    std::copy(centroids_host, centroids_host + (size_t)ix->nlist * ix->d, ix->h_cent.begin());
+    ivftq_status s = upload_coarse(ix);
+    if (s == IVFTQ_OK) ix->has_coarse = true;
+    return s;
+}
+
+ivftq_status ivftq_get_coarse(const ivftq_index* ix, float* centroids_host) {
+    if (check_index(ix)) return IVFTQ_INVALID_ARG;
+    if (!centroids_host) return fail(IVFTQ_INVALID_ARG, "centroids_host is NULL");
+    if (!ix->has_coarse) return fail(IVFTQ_BAD_STATE, "no coarse centroids yet");
+    std::copy(ix->h_cent.begin(), ix->h_cent.end(), centroids_host);
+    return IVFTQ_OK;
+}
+
+ivftq_status ivftq_set_rotation(ivftq_index* ix, const float* pi_host) {
+    if (check_index(ix)) return IVFTQ_INVALID_ARG;
+    if (!pi_host) return fail(IVFTQ_INVALID_ARG, "pi_host is NULL");
+    if (ix->ntotal > 0) return fail(IVFTQ_BAD_STATE, "rotation cannot change once vectors are stored");
+    std::copy(pi_host, pi_host + (size_t)ix->d * ix->d, ix->h_pi.begin());
+    return upload_rotation(ix);
+}
+
+ivftq_status ivftq_get_rotation(const ivftq_index* ix, float* pi_host) {
+    if (check_index(ix)) return IVFTQ_INVALID_ARG;
+    if (!pi_host) return fail(IVFTQ_INVALID_ARG, "pi_host is NULL");
+    std::copy(ix->h_pi.begin(), ix->h_pi.end(), pi_host);
+    return IVFTQ_OK;
+}
+
+ivftq_status ivftq_get_codebook(const ivftq_index* ix, float* centroids_out, float* boundaries_out) {
+    if (check_index(ix)) return IVFTQ_INVALID_ARG;
+    if (centroids_out) std::copy(ix->h_cb.begin(), ix->h_cb.end(), centroids_out);
+    if (boundaries_out) std::copy(ix->h_tau.begin(), ix->h_tau.end(), boundaries_out);
+    return IVFTQ_OK;
+}
+
+ivftq_status ivftq_set_workspace_limit(ivftq_index* ix, int64_t bytes) {
+    if (check_index(ix)) return IVFTQ_INVALID_ARG;
+    if (bytes < (1 << 20)) return fail(IVFTQ_INVALID_ARG, "workspace limit below 1 MiB");
+    ix->ws_limit = bytes;
+    return IVFTQ_OK;
+}
+
+int64_t ivftq_ntotal(const ivftq_index* ix) { return ix ? ix->ntotal : -1; }
+
+int64_t ivftq_index_bytes(const ivftq_index* ix) {
+    if (!ix) return -1;
+    return ix->ntotal * ((int64_t)ix->words * 4 + 2 + 8);
+}
+
+ivftq_status ivftq_list_size(const ivftq_index* ix, int list, int64_t* n_out) {
+    if (check_index(ix)) return IVFTQ_INVALID_ARG;
+    if (list < 0 || list >= ix->nlist || !n_out) return fail(IVFTQ_INVALID_ARG, "bad list number or NULL output");
+    *n_out = ix->h_size[list];
+    return IVFTQ_OK;
+}
+
+ivftq_status ivftq_export_list(const ivftq_index* ix, int list, int64_t* ids_host, uint8_t* codes_host,
+                               uint16_t* gamma_host) {
+    if (check_index(ix)) return IVFTQ_INVALID_ARG;
+    if (list < 0 || list >= ix->nlist) return fail(IVFTQ_INVALID_ARG, "list %d outside [0, %d)", list, ix->nlist);
+    const int64_t n = ix->h_size[list];
+    if (n == 0) return IVFTQ_OK;
+    HIP_TRY(hipDeviceSynchronize());
+    const int64_t off = ix->h_off[list];
+    if (ids_host)
+        HIP_TRY(hipMemcpy(ids_host, ix->ids.as<int64_t>() + off, n * sizeof(int64_t), hipMemcpyDeviceToHost));
+    if (gamma_host)
+        HIP_TRY(hipMemcpy(gamma_host, ix->gamma.as<uint16_t>() + off, n * sizeof(uint16_t), hipMemcpyDeviceToHost));
+    if (codes_host) {
+        const int64_t nblk = (n + 63) / 64;
+        std::vector<uint32_t> raw((size_t)nblk * ix->words * 64);
+        HIP_TRY(hipMemcpy(raw.data(), ix->codes.as<uint32_t>() + (off / 64) * ix->words * 64,
+                          raw.size() * sizeof(uint32_t), hipMemcpyDeviceToHost));
+        const uint32_t maskK = (uint32_t)ix->K - 1;
+        for (int64_t v = 0; v < n; ++v) {
+            const uint32_t* blk = &raw[(size_t)(v / 64) * ix->words * 64 + (v % 64)];
+            for (int j = 0; j < ix->d; ++j) {
+                const int bit = j * ix->b, w = bit >> 5, sh = bit & 31;
+                uint64_t two = blk[(size_t)w * 64];
+                if (w + 1 < ix->words) two |= (uint64_t)blk[(size_t)(w + 1) * 64] << 32;
+                codes_host[v * ix->d + j] = (uint8_t)((two >> sh) & maskK);
+            }
+        }
+    }
+    return IVFTQ_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+
+ivftq_status ivftq_train_coarse(ivftq_index* ix, const float* x_dev, int64_t n, int niter,
+                                const int64_t* init_rows_host, uint64_t seed, double* inertia_out,
+                                void* stream) {
+    if (check_index(ix)) return IVFTQ_INVALID_ARG;
+    if (!x_dev) return fail(IVFTQ_INVALID_ARG, "x_dev is NULL");
+    if (n < ix->nlist) return fail(IVFTQ_INVALID_ARG, "need at least nlist=%d training rows, got %lld", ix->nlist, (long long)n);
+    if (niter < 0) return fail(IVFTQ_INVALID_ARG, "niter=%d is negative", niter);
+    if (ix->ntotal > 0) return fail(IVFTQ_BAD_STATE, "centroids cannot change once vectors are stored");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int L = ix->nlist, d = ix->d, pitch = ix->dp;
+
+    std::vector<int64_t> init(L);
+    if (init_rows_host) {
+        std::unordered_set<int64_t> seen;
+        for (int l = 0; l < L; ++l) {
+            init[l] = init_rows_host[l];
+            if (init[l] < 0 || init[l] >= n) return fail(IVFTQ_INVALID_ARG, "initial row %lld outside [0, n)", (long long)init[l]);
+            if (!seen.insert(init[l]).second) return fail(IVFTQ_INVALID_ARG, "initial rows are not distinct");
+        }
+    } else {
+        std::unordered_set<int64_t> seen;
+        uint64_t s = seed ^ 0xA5A5A5A55A5A5A5Aull;
+        for (int l = 0; l < L;) {
+            const int64_t r = (int64_t)(splitmix(s) % (uint64_t)n);
+            if (seen.insert(r).second) init[l++] = r;
+        }
+    }
+    std::vector<int32_t> dst(L);
+    std::iota(dst.begin(), dst.end(), 0);
+
+    HIP_TRY(ix->w_rows.ensure((size_t)L * sizeof(int64_t)));
+    HIP_TRY(ix->w_dst.ensure((size_t)L * sizeof(int32_t)));
+    HIP_TRY(ix->w_sums.ensure((size_t)ix->lpad * pitch * sizeof(float)));
+    HIP_TRY(ix->w_counts.ensure((size_t)ix->lpad * sizeof(uint32_t)));
+    HIP_TRY(ix->w_zero.ensure((size_t)ix->lpad * sizeof(uint32_t)));
+    HIP_TRY(ix->w_assign.ensure((size_t)n * sizeof(int32_t)));
+    HIP_TRY(ix->w_best.ensure((size_t)n * sizeof(float)));
+    HIP_TRY(ix->w_obj.ensure(sizeof(double)));
+
+    HIP_TRY(launch_fill_u32(ix->cent.as<uint32_t>(), (int64_t)ix->lpad * pitch, 0u, st));
+    HIP_TRY(launch_fill_u32(ix->w_zero.as<uint32_t>(), ix->lpad, 0u, st));
+    HIP_TRY(launch_fill_u32(ix->w_flag.as<uint32_t>(), 1, 0u, st));
+    HIP_TRY(hipMemcpyAsync(ix->w_rows.p, init.data(), L * sizeof(int64_t), hipMemcpyHostToDevice, st));
+    HIP_TRY(hipMemcpyAsync(ix->w_dst.p, dst.data(), L * sizeof(int32_t), hipMemcpyHostToDevice, st));
+    HIP_TRY(launch_copy_rows_normalised(x_dev, d, ix->w_rows.as<int64_t>(), ix->w_dst.as<int32_t>(), L,
+                                        ix->cent.as<float>(), pitch, st));
+    HIP_TRY(launch_kmeans_update(ix->cent.as<float>(), pitch, ix->w_sums.as<float>(), ix->w_zero.as<uint32_t>(),
+                                 ix->bias.as<float>(), L, ix->lpad, d, st));
+    HIP_TRY(hipStreamSynchronize(st));
+
+    std::vector<uint32_t> counts(L);
+    std::vector<int32_t> h_assign;
+    uint64_t rs = seed ^ 0x1234567887654321ull;
+    double inertia = std::nan("");
+    for (int it = 0; it < niter; ++it) {
+        HIP_TRY(launch_fill_u32(ix->w_sums.as<uint32_t>(), (int64_t)ix->lpad * pitch, 0u, st));
+        HIP_TRY(launch_fill_u32(ix->w_counts.as<uint32_t>(), ix->lpad, 0u, st));
+        HIP_TRY(launch_coarse(0, x_dev, n, d, ix->cent.as<float>(), pitch, ix->bias.as<float>(), L, ix->lpad,
+                              ix->w_assign.as<int32_t>(), ix->w_best.as<float>(), nullptr, 0,
+                              ix->w_flag.as<int>(), st));
+        HIP_TRY(launch_kmeans_accumulate(x_dev, n, d, ix->w_assign.as<int32_t>(), ix->w_sums.as<float>(), pitch,
+                                         ix->w_counts.as<uint32_t>(), st));
+        HIP_TRY(launch_kmeans_update(ix->cent.as<float>(), pitch, ix->w_sums.as<float>(),
+                                     ix->w_counts.as<uint32_t>(), ix->bias.as<float>(), L, ix->lpad, d, st));
+        if (it == niter - 1) HIP_TRY(launch_inertia(ix->w_best.as<float>(), n, ix->w_obj.as<double>(), st));
+        HIP_TRY(hipMemcpyAsync(counts.data(), ix->w_counts.p, L * sizeof(uint32_t), hipMemcpyDeviceToHost, st));
+        int flag = 0;
+        HIP_TRY(hipMemcpyAsync(&flag, ix->w_flag.p, sizeof(int), hipMemcpyDeviceToHost, st));
+        HIP_TRY(hipStreamSynchronize(st));
+        if (flag) return fail(IVFTQ_ZERO_NORM, "a training row has zero or non-finite norm");
+        if (it == niter - 1) HIP_TRY(hipMemcpy(&inertia, ix->w_obj.p, sizeof(double), hipMemcpyDeviceToHost));
+
+        std::vector<int32_t> empty;
+        for (int l = 0; l < L; ++l) if (counts[l] == 0) empty.push_back(l);
+        if (!empty.empty()) {
+            // re-seed each empty cell from a member of the largest cell
+            const int big = (int)(std::max_element(counts.begin(), counts.end()) - counts.begin());
+            h_assign.resize(n);
+            HIP_TRY(hipMemcpy(h_assign.data(), ix->w_assign.p, n * sizeof(int32_t), hipMemcpyDeviceToHost));
+            std::vector<int64_t> members;
+            for (int64_t i = 0; i < n; ++i) if (h_assign[i] == big) members.push_back(i);
+            std::vector<int64_t> rows(empty.size());
+            for (size_t t = 0; t < empty.size(); ++t) rows[t] = members[splitmix(rs) % members.size()];
+            HIP_TRY(hipMemcpy(ix->w_rows.p, rows.data(), rows.size() * sizeof(int64_t), hipMemcpyHostToDevice));
+            HIP_TRY(hipMemcpy(ix->w_dst.p, empty.data(), empty.size() * sizeof(int32_t), hipMemcpyHostToDevice));
+            HIP_TRY(launch_copy_rows_normalised(x_dev, d, ix->w_rows.as<int64_t>(), ix->w_dst.as<int32_t>(),
+                                                (int)empty.size(), ix->cent.as<float>(), pitch, st));
+            HIP_TRY(launch_kmeans_update(ix->cent.as<float>(), pitch, ix->w_sums.as<float>(),
+                                         ix->w_zero.as<uint32_t>(), ix->bias.as<float>(), L, ix->lpad, d, st));
+            HIP_TRY(hipStreamSynchronize(st));
+        }
+    }
+    HIP_TRY(launch_normalise_centroids(ix->cent.as<float>(), pitch, ix->bias.as<float>(), L, d, st));
+    std::vector<float> padded((size_t)L * pitch);
+    HIP_TRY(hipMemcpyAsync(padded.data(), ix->cent.p, padded.size() * sizeof(float), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    for (int l = 0; l < L; ++l)
+        std::memcpy(&ix->h_cent[(size_t)l * d], &padded[(size_t)l * pitch], sizeof(float) * d);
+    ix->has_coarse = true;
+    if (inertia_out) *inertia_out = inertia;
+    return IVFTQ_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+
+namespace {
+
+// Steps shared by every append: count the rows of each list, make room, and give each row its
+// slot (list order = arrival order).  `assign` holds a cell number per row; with zero_norm_flag
+// the flag word written by the coarse kernel is checked too.  Nothing is modified on failure.
+ivftq_status place_rows(ivftq_index* ix, const int32_t* assign, int64_t n, bool zero_norm_flag,
+                        std::vector<int64_t>& need, hipStream_t st) {
+    const int L = ix->nlist;
+    int64_t seg_len = round_up64((n + 1023) / 1024, 64);
+    const int nseg = (int)((n + seg_len - 1) / seg_len);
+    HIP_TRY(ix->w_hist.ensure((size_t)nseg * L * sizeof(uint32_t)));
+    HIP_TRY(ix->w_count.ensure((size_t)L * sizeof(uint32_t)));
+    HIP_TRY(ix->w_base.ensure((size_t)L * sizeof(int64_t)));
+    HIP_TRY(launch_segment_hist(assign, n, seg_len, nseg, L, ix->w_hist.as<uint32_t>(), st));
+    HIP_TRY(launch_segment_scan(ix->w_hist.as<uint32_t>(), nseg, L, ix->w_count.as<uint32_t>(), st));
+    std::vector<uint32_t> count(L);
+    int flag = 0;
+    HIP_TRY(hipMemcpyAsync(count.data(), ix->w_count.p, L * sizeof(uint32_t), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipMemcpyAsync(&flag, ix->w_flag.p, sizeof(int), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    if (zero_norm_flag && flag)
+        return fail(IVFTQ_ZERO_NORM, "an input row has zero or non-finite norm; nothing was appended");
+    int64_t placed = 0;
+    for (int l = 0; l < L; ++l) placed += count[l];
+    if (placed != n) return fail(IVFTQ_INVALID_ARG, "%lld rows carry a cell number outside [0, nlist)", (long long)(n - placed));
+
+    need.resize(L);
+    std::vector<int64_t> base(L);
+    for (int l = 0; l < L; ++l) need[l] = (int64_t)ix->h_size[l] + count[l];
+    for (int l = 0; l < L; ++l)
+        if (need[l] > INT32_MAX) return fail(IVFTQ_UNSUPPORTED, "list %d would exceed 2^31-1 vectors", l);
+    ivftq_status s = ensure_capacity(ix, need, st);
+    if (s != IVFTQ_OK) return s;
+    for (int l = 0; l < L; ++l) base[l] = ix->h_off[l] + ix->h_size[l];
+    HIP_TRY(hipMemcpyAsync(ix->w_base.p, base.data(), L * sizeof(int64_t), hipMemcpyHostToDevice, st));
+    HIP_TRY(launch_stable_rank(assign, n, seg_len, nseg, L, ix->w_hist.as<uint32_t>(), ix->w_base.as<int64_t>(),
+                               ix->w_slot.as<int64_t>(), st));
+    HIP_TRY(hipStreamSynchronize(st));   // `base` is pageable host memory
+    return IVFTQ_OK;
+}
+
+ivftq_status commit_rows(ivftq_index* ix, const std::vector<int64_t>& need, int64_t n, hipStream_t st) {
+    for (int l = 0; l < ix->nlist; ++l) ix->h_size[l] = (int32_t)need[l];
+    HIP_TRY(hipMemcpyAsync(ix->d_size.p, ix->h_size.data(), ix->nlist * sizeof(int32_t), hipMemcpyHostToDevice, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    ix->ntotal += n;
+    return IVFTQ_OK;
+}
+
+}  // namespace
+
+ivftq_status ivftq_encode_only(ivftq_index* ix, const float* x_dev, int64_t n, int32_t* assign_dev,
+                               uint8_t* codes_dev, uint16_t* gamma_dev, void* stream) {
+    if (check_index(ix)) return IVFTQ_INVALID_ARG;
+    if (n < 0) return fail(IVFTQ_INVALID_ARG, "n=%lld is negative", (long long)n);
+    if (n == 0) return IVFTQ_OK;
+    if (!x_dev) return fail(IVFTQ_INVALID_ARG, "x_dev is NULL");
+    if (!ix->has_coarse) return fail(IVFTQ_BAD_STATE, "coarse centroids not trained or set");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    HIP_TRY(ix->w_assign.ensure((size_t)n * sizeof(int32_t)));
+    int32_t* assign = assign_dev ? assign_dev : ix->w_assign.as<int32_t>();
+    HIP_TRY(launch_fill_u32(ix->w_flag.as<uint32_t>(), 1, 0u, st));
+    HIP_TRY(launch_coarse(0, x_dev, n, ix->d, ix->cent.as<float>(), ix->dp, nullptr, ix->nlist, ix->lpad, assign,
+                          nullptr, nullptr, 0, ix->w_flag.as<int>(), st));
+    if (codes_dev || gamma_dev) {
+        EncodeArgs a{};
+        a.x = x_dev; a.n = n; a.d = ix->d; a.b = ix->b;
+        a.cent = ix->cent.as<float>(); a.cent_pitch = ix->dp;
+        a.pi = ix->pi.as<float>(); a.tau = ix->tau.as<float>();
+        a.assign = assign;
+        a.codes_flat = codes_dev; a.gamma_flat = gamma_dev;
+        HIP_TRY(launch_encode(1, a, st));
+    }
+    return IVFTQ_OK;
+}
+
+ivftq_status ivftq_encode_add(ivftq_index* ix, const float* x_dev, int64_t n, const int64_t* ids_dev,
+                              void* stream) {
+    if (check_index(ix)) return IVFTQ_INVALID_ARG;
+    if (n < 0) return fail(IVFTQ_INVALID_ARG, "n=%lld is negative", (long long)n);
+    if (n == 0) return IVFTQ_OK;
+    if (!x_dev) return fail(IVFTQ_INVALID_ARG, "x_dev is NULL");
+    if (!ix->has_coarse) return fail(IVFTQ_BAD_STATE, "coarse centroids not trained or set");
+    if (n > ((int64_t)1 << 31) - 1) return fail(IVFTQ_UNSUPPORTED, "more than 2^31-1 rows in one call");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int L = ix->nlist;
+
+    // 1. coarse assignment
+    HIP_TRY(ix->w_assign.ensure((size_t)n * sizeof(int32_t)));
+    HIP_TRY(ix->w_slot.ensure((size_t)n * sizeof(int64_t)));
+    HIP_TRY(launch_fill_u32(ix->w_flag.as<uint32_t>(), 1, 0u, st));
+    HIP_TRY(launch_coarse(0, x_dev, n, ix->d, ix->cent.as<float>(), ix->dp, nullptr, L, ix->lpad,
+                          ix->w_assign.as<int32_t>(), nullptr, nullptr, 0, ix->w_flag.as<int>(), st));
+
+    // 2.-4. room for the new vectors and the stable position of every row
+    std::vector<int64_t> need;
+    ivftq_status s = place_rows(ix, ix->w_assign.as<int32_t>(), n, true, need, st);
+    if (s != IVFTQ_OK) return s;
+    // 5. rotate / quantise / pack straight into the lists
+    EncodeArgs a{};
+    a.x = x_dev; a.n = n; a.d = ix->d; a.b = ix->b;
+    a.cent = ix->cent.as<float>(); a.cent_pitch = ix->dp;
+    a.pi = ix->pi.as<float>(); a.tau = ix->tau.as<float>();
+    a.assign = ix->w_assign.as<int32_t>();
+    a.store = ix->store();
+    a.slot = ix->w_slot.as<int64_t>();
+    a.labels = ids_dev; a.label_base = ix->ntotal;
+    HIP_TRY(launch_encode(0, a, st));
+    return commit_rows(ix, need, n, st);
+}
+
+ivftq_status ivftq_add_encoded(ivftq_index* ix, int64_t n, const int32_t* assign_dev, const uint8_t* codes_dev,
+                               const uint16_t* gamma_dev, const int64_t* ids_dev, void* stream) {
+    if (check_index(ix)) return IVFTQ_INVALID_ARG;
+    if (n < 0) return fail(IVFTQ_INVALID_ARG, "n=%lld is negative", (long long)n);
+    if (n == 0) return IVFTQ_OK;
+    if (!assign_dev || !codes_dev || !gamma_dev) return fail(IVFTQ_INVALID_ARG, "input pointer is NULL");
+    if (!ix->has_coarse) return fail(IVFTQ_BAD_STATE, "coarse centroids not trained or set");
+    if (n > ((int64_t)1 << 31) - 1) return fail(IVFTQ_UNSUPPORTED, "more than 2^31-1 rows in one call");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    HIP_TRY(ix->w_slot.ensure((size_t)n * sizeof(int64_t)));
+    HIP_TRY(launch_fill_u32(ix->w_flag.as<uint32_t>(), 1, 0u, st));
+    std::vector<int64_t> need;
+    ivftq_status s = place_rows(ix, assign_dev, n, false, need, st);
+    if (s != IVFTQ_OK) return s;
+    HIP_TRY(launch_pack_scatter(codes_dev, gamma_dev, ids_dev, ix->ntotal, ix->w_slot.as<int64_t>(), n, ix->d,
+                                ix->b, ix->store(), st));
+    return commit_rows(ix, need, n, st);
+}
+
+// ---------------------------------------------------------------------------------------------
+
+namespace {
+
+ivftq_status check_query_args(const ivftq_index* ix, const float* q_dev, int64_t nq, int nprobe) {
+    if (check_index(ix)) return IVFTQ_INVALID_ARG;
+    if (nq < 0) return fail(IVFTQ_INVALID_ARG, "nq=%lld is negative", (long long)nq);
+    if (nq > 0 && !q_dev) return fail(IVFTQ_INVALID_ARG, "q_dev is NULL");
+    if (nprobe < 1 || nprobe > ix->nlist) return fail(IVFTQ_INVALID_ARG, "nprobe=%d outside [1, nlist=%d]", nprobe, ix->nlist);
+    if (nprobe > kMaxK) return fail(IVFTQ_UNSUPPORTED, "nprobe=%d above %d", nprobe, kMaxK);
+    if (!ix->has_coarse) return fail(IVFTQ_BAD_STATE, "coarse centroids not trained or set");
+    return IVFTQ_OK;
+}
+
+// coarse scores for `count` queries starting at q, then the nprobe best cells of each
+ivftq_status coarse_and_probe(ivftq_index* ix, const float* q, int64_t count, int nprobe, int32_t* probe,
+                              float* coarse, hipStream_t st) {
+    const int64_t ldS = round_up(ix->nlist, 4);
+    HIP_TRY(launch_coarse(1, q, count, ix->d, ix->cent.as<float>(), ix->dp, nullptr, ix->nlist, ix->lpad, nullptr,
+                          nullptr, ix->w_S.as<float>(), ldS, ix->w_flag.as<int>(), st));
+    SelectArgs sa{};
+    sa.vals = ix->w_S.as<float>(); sa.stride = ldS; sa.rows = count; sa.k = nprobe; sa.m_fixed = ix->nlist;
+    sa.out_vals = coarse; sa.out_i32 = probe;
+    HIP_TRY(launch_select(0, sa, st));
+    return IVFTQ_OK;
+}
+
+}  // namespace
+
+ivftq_status ivftq_coarse_probe(ivftq_index* ix, const float* q_dev, int64_t nq, int nprobe,
+                                int32_t* probe_dev, float* coarse_dev, void* stream) {
+    ivftq_status s = check_query_args(ix, q_dev, nq, nprobe);
+    if (s != IVFTQ_OK) return s;
+    if (nq == 0) return IVFTQ_OK;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int64_t ldS = round_up(ix->nlist, 4);
+    const int64_t qc = std::max<int64_t>(1, std::min<int64_t>(nq, ix->ws_limit / (ldS * 4)));
+    HIP_TRY(ix->w_S.ensure((size_t)qc * ldS * sizeof(float)));
+    for (int64_t q0 = 0; q0 < nq; q0 += qc) {
+        const int64_t cnt = std::min(qc, nq - q0);
+        s = coarse_and_probe(ix, q_dev + q0 * ix->d, cnt, nprobe, probe_dev ? probe_dev + q0 * nprobe : nullptr,
+                             coarse_dev ? coarse_dev + q0 * nprobe : nullptr, st);
+        if (s != IVFTQ_OK) return s;
+    }
+    return IVFTQ_OK;
+}
+
+ivftq_status ivftq_search(ivftq_index* ix, const float* q_dev, int64_t nq, int nprobe, int k,
+                          float* scores_dev, int64_t* ids_dev, void* stream) {
+    ivftq_status s = check_query_args(ix, q_dev, nq, nprobe);
+    if (s != IVFTQ_OK) return s;
+    if (k < 1) return fail(IVFTQ_INVALID_ARG, "k=%d below 1", k);
+    if (k > kMaxK) return fail(IVFTQ_UNSUPPORTED, "k=%d above %d", k, kMaxK);
+    if (nq == 0) return IVFTQ_OK;
+    if (!scores_dev || !ids_dev) return fail(IVFTQ_INVALID_ARG, "output pointer is NULL");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+
+    // upper bound of candidates per query: the nprobe largest lists
+    std::vector<int32_t> sizes(ix->h_size);
+    std::partial_sort(sizes.begin(), sizes.begin() + nprobe, sizes.end(), std::greater<int32_t>());
+    int64_t m_bound = 0;
+    for (int p = 0; p < nprobe; ++p) m_bound += sizes[p];
+    if (m_bound > INT32_MAX - 4) return fail(IVFTQ_UNSUPPORTED, "more than 2^31 candidates per query");
+    const int64_t m_stride = std::max<int64_t>(4, round_up64(m_bound, 4));
+    const int64_t ldS = round_up(ix->nlist, 4);
+    int64_t qc = ix->ws_limit / (4 * std::max(m_stride, ldS));
+    qc = std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(qc, nq), 32768));
+
+    HIP_TRY(ix->w_S.ensure((size_t)qc * ldS * sizeof(float)));
+    HIP_TRY(ix->w_scores.ensure((size_t)qc * m_stride * sizeof(float)));
+    HIP_TRY(ix->w_probe.ensure((size_t)qc * nprobe * sizeof(int32_t)));
+    HIP_TRY(ix->w_coarse.ensure((size_t)qc * nprobe * sizeof(float)));
+    HIP_TRY(ix->w_candoff.ensure((size_t)qc * (nprobe + 1) * sizeof(int32_t)));
+    HIP_TRY(ix->w_z.ensure((size_t)qc * ix->dp * sizeof(float)));
+
+    for (int64_t q0 = 0; q0 < nq; q0 += qc) {
+        const int64_t cnt = std::min(qc, nq - q0);
+        const float* q = q_dev + q0 * ix->d;
+        s = coarse_and_probe(ix, q, cnt, nprobe, ix->w_probe.as<int32_t>(), ix->w_coarse.as<float>(), st);
+        if (s != IVFTQ_OK) return s;
+        EncodeArgs ea{};
+        ea.x = q; ea.n = cnt; ea.d = ix->d; ea.b = ix->b;
+        ea.pi = ix->pi.as<float>(); ea.zout = ix->w_z.as<float>();
+        HIP_TRY(launch_encode(2, ea, st));
+        HIP_TRY(launch_cand_offsets(ix->w_probe.as<int32_t>(), cnt, nprobe, ix->d_size.as<int32_t>(),
+                                    ix->w_candoff.as<int32_t>(), st));
+        HIP_TRY(launch_list_scan(ix->w_z.as<float>(), ix->dp, ix->d, ix->b, ix->cb.as<float>(),
+                                 ix->w_probe.as<int32_t>(), ix->w_coarse.as<float>(),
+                                 ix->w_candoff.as<int32_t>(), nprobe, ix->store(), 0, cnt,
+                                 ix->w_scores.as<float>(), m_stride, st));
+        SelectArgs sa{};
+        sa.vals = ix->w_scores.as<float>(); sa.stride = m_stride; sa.rows = cnt; sa.k = k;
+        sa.cand_off = ix->w_candoff.as<int32_t>(); sa.probe = ix->w_probe.as<int32_t>(); sa.np = nprobe;
+        sa.q_begin = 0;
+        sa.list_off = ix->d_off.as<int64_t>(); sa.ids = ix->ids.as<int64_t>();
+        sa.out_vals = scores_dev + q0 * k; sa.out_i64 = ids_dev + q0 * k;
+        HIP_TRY(launch_select(1, sa, st));
+    }
+    return IVFTQ_OK;
+}
+
+}  // extern "C"

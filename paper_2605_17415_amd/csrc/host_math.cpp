@@ -1,0 +1,170 @@
+// Host-side constants of IVF-TQ: the (b, d) Lloyd-Max codebook and the Haar rotation.
+// Both depend on no data (Section "TurboQuant: data-independent scalar quantization";
+// Appendix "Proofs of the rate-distortion bounds", Setup and Lemma 1).  Double precision.
+#include "host_math.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstdint>
+#include <vector>
+
+namespace ivftq {
+
+namespace {
+
+// Nodes and weights of n-point Gauss-Legendre quadrature on [-1, 1] by Newton iteration on P_n.
+void gauss_legendre(int n, std::vector<double>& x, std::vector<double>& w) {
+    x.assign(n, 0.0);
+    w.assign(n, 0.0);
+    const double pi = 3.14159265358979323846;
+    for (int i = 0; i < (n + 1) / 2; ++i) {
+        double z = std::cos(pi * (i + 0.75) / (n + 0.5));
+        double pp = 0.0;
+        for (int it = 0; it < 100; ++it) {
+            double p1 = 1.0, p2 = 0.0;
+            for (int j = 0; j < n; ++j) {
+                double p3 = p2;
+                p2 = p1;
+                p1 = ((2.0 * j + 1.0) * z * p2 - j * p3) / (j + 1.0);
+            }
+            pp = n * (z * p1 - p2) / (z * z - 1.0);
+            double dz = p1 / pp;
+            z -= dz;
+            if (std::fabs(dz) < 1e-16) break;
+        }
+        x[i] = -z;
+        x[n - 1 - i] = z;
+        w[i] = w[n - 1 - i] = 2.0 / ((1.0 - z * z) * pp * pp);
+    }
+}
+
+// With t = sin(theta) the sphere-coordinate density becomes kappa * cos^(d-2)(theta) d(theta),
+// which is smooth on the whole interval; integrate it there.
+struct SphereMarginal {
+    int d;
+    double log_kappa;
+    std::vector<double> gx, gw;
+    explicit SphereMarginal(int d_) : d(d_) {
+        log_kappa = std::lgamma(0.5 * d) - 0.5 * std::log(3.14159265358979323846) - std::lgamma(0.5 * (d - 1));
+        gauss_legendre(48, gx, gw);
+    }
+    // P(a <= T <= b)
+    double mass(double a, double b) const {
+        double ta = std::asin(std::max(-1.0, std::min(1.0, a)));
+        double tb = std::asin(std::max(-1.0, std::min(1.0, b)));
+        const int pieces = 6;
+        double total = 0.0;
+        for (int p = 0; p < pieces; ++p) {
+            double lo = ta + (tb - ta) * p / pieces, hi = ta + (tb - ta) * (p + 1) / pieces;
+            double half = 0.5 * (hi - lo), mid = 0.5 * (hi + lo), s = 0.0;
+            for (size_t i = 0; i < gx.size(); ++i) {
+                double c = std::cos(mid + half * gx[i]);
+                s += gw[i] * std::exp(log_kappa + (d - 2) * std::log(std::max(c, 1e-300)));
+            }
+            total += half * s;
+        }
+        return total;
+    }
+    // E[T ; a <= T <= b] in closed form: kappa/(d-1) * [(1-a^2)^((d-1)/2) - (1-b^2)^((d-1)/2)]
+    double first_moment(double a, double b) const {
+        double k = std::exp(log_kappa) / (d - 1);
+        return k * (std::pow(std::max(0.0, 1.0 - a * a), 0.5 * (d - 1)) -
+                    std::pow(std::max(0.0, 1.0 - b * b), 0.5 * (d - 1)));
+    }
+};
+
+}  // namespace
+
+bool build_codebook(int b, int d, std::vector<double>& cent, std::vector<double>& bnd) {
+    if (b < 1 || b > 8 || d < 3) return false;
+    const int K = 1 << b;
+    SphereMarginal f(d);
+    cent.resize(K);
+    bnd.resize(K - 1);
+    const double sd = 1.0 / std::sqrt((double)d);
+    for (int i = 0; i < K; ++i) cent[i] = ((i + 0.5) / K * 6.0 - 3.0) * sd;
+    std::vector<double> edge(K + 1), next(K);
+    for (int it = 0; it < 200000; ++it) {
+        edge[0] = -1.0;
+        edge[K] = 1.0;
+        for (int i = 1; i < K; ++i) edge[i] = 0.5 * (cent[i - 1] + cent[i]);
+        double delta = 0.0;
+        // the density is even, so only the upper half needs integrating
+        for (int i = K / 2; i < K; ++i) {
+            next[i] = f.first_moment(edge[i], edge[i + 1]) / f.mass(edge[i], edge[i + 1]);
+            next[K - 1 - i] = -next[i];
+        }
+        for (int i = 0; i < K; ++i) delta = std::max(delta, std::fabs(next[i] - cent[i]));
+        cent = next;
+        if (delta < 1e-14) break;
+    }
+    for (int i = 1; i < K; ++i) bnd[i - 1] = 0.5 * (cent[i - 1] + cent[i]);
+    return true;
+}
+
+// ---- random numbers for the rotation draw ------------------------------------------------
+
+static inline uint64_t splitmix64(uint64_t& s) {
+    uint64_t z = (s += 0x9E3779B97F4A7C15ull);
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+void gaussian_matrix(int d, uint64_t seed, std::vector<double>& g) {
+    g.resize((size_t)d * d);
+    uint64_t s = seed ^ 0xD1B54A32D192ED03ull;
+    const double two_pi = 6.28318530717958647692;
+    for (size_t i = 0; i < g.size(); i += 2) {
+        double u1 = ((splitmix64(s) >> 11) + 1.0) * (1.0 / 9007199254740993.0);  // (0,1)
+        double u2 = (splitmix64(s) >> 11) * (1.0 / 9007199254740992.0);          // [0,1)
+        double r = std::sqrt(-2.0 * std::log(u1));
+        g[i] = r * std::cos(two_pi * u2);
+        if (i + 1 < g.size()) g[i + 1] = r * std::sin(two_pi * u2);
+    }
+}
+
+// Householder QR of the d x d row-major matrix g; returns Q with column j multiplied by
+// sign(R_jj), the factor of the unique QR decomposition with positive diagonal.
+bool haar_from_gaussian(int d, const double* g, std::vector<double>& q) {
+    std::vector<double> a(g, g + (size_t)d * d);       // becomes R
+    std::vector<std::vector<double>> vs(d);
+    std::vector<double> rdiag(d);
+    for (int k = 0; k < d; ++k) {
+        double nrm = 0.0;
+        for (int i = k; i < d; ++i) nrm += a[(size_t)i * d + k] * a[(size_t)i * d + k];
+        nrm = std::sqrt(nrm);
+        if (nrm == 0.0) return false;
+        double alpha = a[(size_t)k * d + k] >= 0 ? -nrm : nrm;
+        std::vector<double> v(d - k);
+        for (int i = k; i < d; ++i) v[i - k] = a[(size_t)i * d + k];
+        v[0] -= alpha;
+        double vn = 0.0;
+        for (double t : v) vn += t * t;
+        vn = std::sqrt(vn);
+        if (vn > 0) for (double& t : v) t /= vn;
+        for (int j = k; j < d; ++j) {                  // a <- (I - 2 v v^T) a
+            double dot = 0.0;
+            for (int i = k; i < d; ++i) dot += v[i - k] * a[(size_t)i * d + j];
+            for (int i = k; i < d; ++i) a[(size_t)i * d + j] -= 2.0 * v[i - k] * dot;
+        }
+        rdiag[k] = a[(size_t)k * d + k];
+        vs[k] = std::move(v);
+    }
+    q.assign((size_t)d * d, 0.0);
+    for (int i = 0; i < d; ++i) q[(size_t)i * d + i] = 1.0;
+    for (int k = d - 1; k >= 0; --k) {                 // Q = H_0 H_1 ... H_{d-1}
+        const std::vector<double>& v = vs[k];
+        for (int j = 0; j < d; ++j) {
+            double dot = 0.0;
+            for (int i = k; i < d; ++i) dot += v[i - k] * q[(size_t)i * d + j];
+            for (int i = k; i < d; ++i) q[(size_t)i * d + j] -= 2.0 * v[i - k] * dot;
+        }
+    }
+    for (int j = 0; j < d; ++j)
+        if (rdiag[j] < 0)
+            for (int i = 0; i < d; ++i) q[(size_t)i * d + j] = -q[(size_t)i * d + j];
+    return true;
+}
+
+}  // namespace ivftq

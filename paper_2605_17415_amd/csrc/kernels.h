@@ -1,0 +1,125 @@
+// Internal launcher declarations shared by the HIP translation units of libivftq.
+// Nothing here is part of the public ABI (see include/ivftq.h for that).
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+namespace ivftq {
+
+constexpr int kSlotsPerBlock = 64;   // vectors interleaved in one storage block (= one wavefront)
+constexpr int kRowsPerWG = 128;      // data rows one workgroup of the contraction kernels owns
+constexpr int kMaxD = 256;
+constexpr int kMaxList = 16384;
+constexpr int kMaxK = 2048;
+
+inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
+inline int64_t round_up64(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
+
+// Padded dimension used by the coarse-scoring kernel (smallest instantiated size >= d).
+int coarse_dp(int d);
+// Padded dimension used by the rotation kernel (multiple of 32).
+inline int rot_dp(int d) { return round_up(d, 32); }
+// 32-bit words of packed codes per vector.
+inline int code_words(int b, int d) { return (b * d + 31) / 32; }
+
+// Inverted-list storage as the kernels see it.  Slot s of the pool lives in storage block s/64,
+// lane s%64; word w of its code sits at codes[(s/64 * words + w) * 64 + s%64], so a wavefront
+// reading word w of 64 neighbouring vectors touches 256 contiguous bytes.
+struct ListStore {
+    uint32_t* codes;
+    uint16_t* gamma;          // float16 bit patterns, one per slot
+    int64_t* ids;             // labels, one per slot
+    const int64_t* list_off;  // [nlist] first slot of each list (multiple of 64)
+    const int32_t* list_size; // [nlist] vectors stored in each list
+    int words;
+};
+
+// ---- contraction kernels (MFMA fp32) --------------------------------------------------------
+
+// mode 0: assign[i] = argmax_c (<x~_i, cent_c> + bias_c), best[i] that value (either may be null)
+// mode 1: scores[i*ld_scores + c] = <x~_i, cent_c> for c < L
+// x: n x d raw rows (normalised inside).  cent: [Lpad][cent_pitch] zero padded, Lpad % 64 == 0.
+// flag: set to 1 when a row has zero or non-finite norm (that row gets assign -1).
+hipError_t launch_coarse(int mode, const float* x, int64_t n, int d, const float* cent, int cent_pitch,
+                         const float* bias, int L, int Lpad, int32_t* assign, float* best,
+                         float* scores, int64_t ld_scores, int* flag, hipStream_t st);
+
+// Rotation family.  pi: [DP][DP] zero padded with DP = rot_dp(d); tau: 2^b - 1 boundaries.
+// mode 0: residual -> rotate -> normalise -> quantise -> pack into the list store at slot[i]
+// mode 1: same, but write unpacked codes / fp16 norms to flat arrays (any may be null)
+// mode 2: z_i = Pi x~_i written to zout[i*DP + j] (no centroid, no quantiser)
+struct EncodeArgs {
+    const float* x; int64_t n; int d; int b;
+    const float* cent; int cent_pitch;
+    const float* pi; const float* tau;
+    const int32_t* assign;
+    // mode 0
+    ListStore store; const int64_t* slot; const int64_t* labels; int64_t label_base;
+    // mode 1
+    uint8_t* codes_flat; uint16_t* gamma_flat;
+    // mode 2
+    float* zout;
+};
+hipError_t launch_encode(int mode, const EncodeArgs& a, hipStream_t st);
+
+// ---- list bookkeeping -------------------------------------------------------------------------
+
+// seg_hist[s*L + l] = number of rows of segment s assigned to list l (rows with assign < 0 skipped)
+hipError_t launch_segment_hist(const int32_t* assign, int64_t n, int64_t seg_len, int nseg, int L,
+                               uint32_t* seg_hist, hipStream_t st);
+// in place: seg_hist[s][l] <- sum_{s'<s} seg_hist[s'][l];  batch_count[l] <- column total
+hipError_t launch_segment_scan(uint32_t* seg_hist, int nseg, int L, uint32_t* batch_count, hipStream_t st);
+// slot[i] = list_base[l] + (rank of row i among the batch rows of list l, in input order)
+hipError_t launch_stable_rank(const int32_t* assign, int64_t n, int64_t seg_len, int nseg, int L,
+                              const uint32_t* seg_hist, const int64_t* list_base, int64_t* slot,
+                              hipStream_t st);
+// pack already-quantised rows (codes: n x d bytes, one bin number each) into their storage slots
+hipError_t launch_pack_scatter(const uint8_t* codes, const uint16_t* gamma, const int64_t* labels,
+                               int64_t label_base, const int64_t* slot, int64_t n, int d, int b,
+                               const ListStore& store, hipStream_t st);
+// copy every list from one pool layout to another (same words per vector)
+hipError_t launch_copy_lists(const ListStore& from, const ListStore& to, int L, hipStream_t st);
+hipError_t launch_fill_u32(uint32_t* p, int64_t n, uint32_t v, hipStream_t st);
+
+// ---- k-means pieces ---------------------------------------------------------------------------
+
+// sums[l][j] += x~_ij, counts[l] += 1 over rows with assign l (atomics); obj += best terms
+hipError_t launch_kmeans_accumulate(const float* x, int64_t n, int d, const int32_t* assign,
+                                    float* sums, int pitch, uint32_t* counts, hipStream_t st);
+// cent[l] = sums[l]/counts[l] for non-empty cells; bias[l] = -|cent_l|^2/2 (padding rows: bias -inf)
+hipError_t launch_kmeans_update(float* cent, int pitch, const float* sums, const uint32_t* counts,
+                                float* bias, int L, int Lpad, int d, hipStream_t st);
+// cent[dst[t]] = normalised row src_row[t] of x
+hipError_t launch_copy_rows_normalised(const float* x, int d, const int64_t* src_row, const int32_t* dst,
+                                       int count, float* cent, int pitch, hipStream_t st);
+// normalise centroid rows in place; bias <- 0 for real rows
+hipError_t launch_normalise_centroids(float* cent, int pitch, float* bias, int L, int d, hipStream_t st);
+// sum over rows of (1 - 2*best_i) in double
+hipError_t launch_inertia(const float* best, int64_t n, double* out, hipStream_t st);
+
+// ---- search -----------------------------------------------------------------------------------
+
+// cand_off[q*(np+1) + p] = sum_{p'<p} list_size[probe[q][p']]
+hipError_t launch_cand_offsets(const int32_t* probe, int64_t nq, int np, const int32_t* list_size,
+                               int32_t* cand_off, hipStream_t st);
+// scores[qi*m_stride + cand_off[q][p] + i] = coarse[q][p] + gamma_i * sum_j z_qj * C[code_ij]
+hipError_t launch_list_scan(const float* z, int z_pitch, int d, int b, const float* cb,
+                            const int32_t* probe, const float* coarse, const int32_t* cand_off,
+                            int np, const ListStore& store, int64_t q_begin, int64_t q_count,
+                            float* scores, int64_t m_stride, hipStream_t st);
+
+// Per row: the k largest of m values, sorted by (value desc, label asc).
+// mode 0 (probe selection): m = m_fixed for every row, label = column; writes int32 labels.
+// mode 1 (results): row q has m = cand_off[q][np] values; column -> (probe p, position) -> label
+//                   ids[list_off[probe[q][p]] + position]; writes int64 labels.
+struct SelectArgs {
+    const float* vals; int64_t stride; int64_t rows; int k;
+    int m_fixed;
+    const int32_t* cand_off; const int32_t* probe; int np; int64_t q_begin;
+    const int64_t* list_off; const int64_t* ids;
+    float* out_vals; int32_t* out_i32; int64_t* out_i64;
+};
+hipError_t launch_select(int mode, const SelectArgs& a, hipStream_t st);
+
+}  // namespace ivftq

@@ -1,0 +1,282 @@
+// Inverted-list bookkeeping for appends (Section "Architecture": "new vectors enter at any
+// time"; Section "Streaming Experiments": append-only ingest with constant coarse parameters) and
+// the centroid-update half of coarse k-means (Section "Architecture", Indexing).
+//
+// An append must place row i of the batch at position (old size of its list) + (number of earlier
+// batch rows of the same list), so that list order equals arrival order and results never depend
+// on scheduling.  That is a stable counting sort by cell number, done in three small kernels:
+// per-segment histograms, a column-wise running sum over segments, and an in-order rank inside
+// each segment by one wavefront.
+#include "kernels.h"
+
+namespace ivftq {
+
+namespace {
+
+__global__ __launch_bounds__(256) void k_segment_hist(const int32_t* __restrict__ assign, int64_t n,
+                                                      int64_t seg_len, int L, uint32_t* __restrict__ seg_hist) {
+    extern __shared__ uint32_t hist[];
+    for (int l = threadIdx.x; l < L; l += 256) hist[l] = 0;
+    __syncthreads();
+    const int64_t begin = (int64_t)blockIdx.x * seg_len;
+    const int64_t end = begin + seg_len < n ? begin + seg_len : n;
+    for (int64_t i = begin + threadIdx.x; i < end; i += 256) {
+        const int a = assign[i];
+        if (a >= 0 && a < L) atomicAdd(&hist[a], 1u);
+    }
+    __syncthreads();
+    for (int l = threadIdx.x; l < L; l += 256) seg_hist[(int64_t)blockIdx.x * L + l] = hist[l];
+}
+
+__global__ __launch_bounds__(256) void k_segment_scan(uint32_t* __restrict__ seg_hist, int nseg, int L,
+                                                      uint32_t* __restrict__ batch_count) {
+    const int l = blockIdx.x * 256 + threadIdx.x;
+    if (l >= L) return;
+    uint32_t run = 0;
+    for (int s = 0; s < nseg; ++s) {
+        const uint32_t t = seg_hist[(int64_t)s * L + l];
+        seg_hist[(int64_t)s * L + l] = run;
+        run += t;
+    }
+    batch_count[l] = run;
+}
+
+// One wavefront walks its segment 64 rows at a time, in order.
+__global__ __launch_bounds__(64) void k_stable_rank(const int32_t* __restrict__ assign, int64_t n,
+                                                    int64_t seg_len, int L,
+                                                    const uint32_t* __restrict__ seg_hist,
+                                                    const int64_t* __restrict__ list_base,
+                                                    int64_t* __restrict__ slot) {
+    extern __shared__ uint32_t cnt[];
+    const int lane = threadIdx.x;
+    for (int l = lane; l < L; l += 64) cnt[l] = seg_hist[(int64_t)blockIdx.x * L + l];
+    __syncthreads();
+    const int64_t begin = (int64_t)blockIdx.x * seg_len;
+    const int64_t end = begin + seg_len < n ? begin + seg_len : n;
+    for (int64_t g = begin; g < end; g += 64) {
+        const int64_t i = g + lane;
+        int key = (i < end) ? assign[i] : -1;
+        if (key >= L) key = -1;
+        int lower = 0;
+        bool later = false;
+        for (int t = 0; t < 64; ++t) {
+            const int kt = __shfl(key, t);
+            const bool same = (kt == key);
+            lower += (same && t < lane) ? 1 : 0;
+            later = later || (same && t > lane);
+        }
+        uint32_t base = 0;
+        if (key >= 0) {
+            base = cnt[key];
+            slot[i] = list_base[key] + (int64_t)(base + lower);
+        } else if (i < end) {
+            slot[i] = -1;
+        }
+        __syncthreads();
+        if (key >= 0 && !later) cnt[key] = base + lower + 1;
+        __syncthreads();
+    }
+}
+
+__global__ __launch_bounds__(256) void k_copy_lists(ListStore from, ListStore to) {
+    const int l = blockIdx.x;
+    const int64_t size = from.list_size[l];
+    if (size == 0) return;
+    const int64_t src = from.list_off[l], dst = to.list_off[l];
+    const int words = from.words;
+    const int64_t nblk = (size + 63) / 64;
+    const int64_t total_words = nblk * words * 64;
+    const uint32_t* s = from.codes + (src >> 6) * words * 64;
+    uint32_t* t = to.codes + (dst >> 6) * words * 64;
+    for (int64_t e = (int64_t)blockIdx.y * 256 + threadIdx.x; e < total_words; e += (int64_t)gridDim.y * 256)
+        t[e] = s[e];
+    for (int64_t e = (int64_t)blockIdx.y * 256 + threadIdx.x; e < size; e += (int64_t)gridDim.y * 256) {
+        to.gamma[dst + e] = from.gamma[src + e];
+        to.ids[dst + e] = from.ids[src + e];
+    }
+}
+
+__global__ __launch_bounds__(256) void k_pack_scatter(const uint8_t* __restrict__ codes,
+                                                      const uint16_t* __restrict__ gamma,
+                                                      const int64_t* __restrict__ labels, int64_t label_base,
+                                                      const int64_t* __restrict__ slot, int64_t n, int d,
+                                                      int b, ListStore store) {
+    const int words = store.words;
+    const int64_t item = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (item >= n * words) return;
+    const int64_t row = item / words;
+    const int w = (int)(item % words);
+    const int64_t s = slot[row];
+    if (s < 0) return;
+    const uint8_t* c = codes + row * d;
+    uint32_t word = 0;
+    for (int j = (32 * w) / b; j < d; ++j) {        // coordinate j occupies bits [j*b, j*b + b)
+        const int sh = j * b - 32 * w;
+        if (sh >= 32) break;
+        const uint32_t code = c[j];
+        word |= sh >= 0 ? (code << sh) : (code >> (-sh));
+    }
+    store.codes[((s >> 6) * words + w) * 64 + (s & 63)] = word;
+    if (w == 0) {
+        store.gamma[s] = gamma[row];
+        store.ids[s] = labels ? labels[row] : label_base + row;
+    }
+}
+
+__global__ void k_fill_u32(uint32_t* p, int64_t n, uint32_t v) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
+        p[i] = v;
+}
+
+// ---- k-means ------------------------------------------------------------------------------------
+
+// One wavefront per row: normalise and add into the cell's running sum.
+__global__ __launch_bounds__(256) void k_kmeans_accumulate(const float* __restrict__ x, int64_t n, int d,
+                                                           const int32_t* __restrict__ assign,
+                                                           float* __restrict__ sums, int pitch,
+                                                           uint32_t* __restrict__ counts) {
+    const int lane = threadIdx.x & 63;
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= n) return;
+    const int a = assign[row];
+    if (a < 0) return;
+    float n2 = 0.f;
+    for (int j = lane; j < d; j += 64) { const float v = x[row * d + j]; n2 += v * v; }
+    for (int o = 32; o > 0; o >>= 1) n2 += __shfl_xor(n2, o);
+    const float nrm = sqrtf(n2);
+    for (int j = lane; j < d; j += 64) atomicAdd(&sums[(int64_t)a * pitch + j], x[row * d + j] / nrm);
+    if (lane == 0) atomicAdd(&counts[a], 1u);
+}
+
+__global__ __launch_bounds__(64) void k_kmeans_update(float* __restrict__ cent, int pitch,
+                                                      const float* __restrict__ sums,
+                                                      const uint32_t* __restrict__ counts,
+                                                      float* __restrict__ bias, int L, int d) {
+    const int l = blockIdx.x, lane = threadIdx.x;
+    if (l >= L) { if (lane == 0) bias[l] = -__builtin_inff(); return; }
+    const uint32_t c = counts[l];
+    float n2 = 0.f;
+    for (int j = lane; j < d; j += 64) {
+        float v = cent[(int64_t)l * pitch + j];
+        if (c > 0) { v = sums[(int64_t)l * pitch + j] / (float)c; cent[(int64_t)l * pitch + j] = v; }
+        n2 += v * v;
+    }
+    for (int o = 32; o > 0; o >>= 1) n2 += __shfl_xor(n2, o);
+    if (lane == 0) bias[l] = -0.5f * n2;
+}
+
+__global__ __launch_bounds__(64) void k_copy_rows_normalised(const float* __restrict__ x, int d,
+                                                             const int64_t* __restrict__ src_row,
+                                                             const int32_t* __restrict__ dst,
+                                                             float* __restrict__ cent, int pitch) {
+    const int lane = threadIdx.x;
+    const int64_t row = src_row[blockIdx.x];
+    const int l = dst[blockIdx.x];
+    float n2 = 0.f;
+    for (int j = lane; j < d; j += 64) { const float v = x[row * d + j]; n2 += v * v; }
+    for (int o = 32; o > 0; o >>= 1) n2 += __shfl_xor(n2, o);
+    const float nrm = sqrtf(n2);
+    for (int j = lane; j < d; j += 64) cent[(int64_t)l * pitch + j] = nrm > 0.f ? x[row * d + j] / nrm : 0.f;
+}
+
+__global__ __launch_bounds__(64) void k_normalise_centroids(float* __restrict__ cent, int pitch,
+                                                            float* __restrict__ bias, int d) {
+    const int l = blockIdx.x, lane = threadIdx.x;
+    float n2 = 0.f;
+    for (int j = lane; j < d; j += 64) { const float v = cent[(int64_t)l * pitch + j]; n2 += v * v; }
+    for (int o = 32; o > 0; o >>= 1) n2 += __shfl_xor(n2, o);
+    const float nrm = sqrtf(n2);
+    for (int j = lane; j < d; j += 64)
+        if (nrm > 0.f) cent[(int64_t)l * pitch + j] /= nrm;
+    if (lane == 0) bias[l] = 0.f;
+}
+
+// Deterministic: one workgroup, fixed summation order.
+__global__ __launch_bounds__(256) void k_inertia(const float* __restrict__ best, int64_t n, double* out) {
+    __shared__ double part[256];
+    double s = 0.0;
+    for (int64_t i = threadIdx.x; i < n; i += 256) s += 1.0 - 2.0 * (double)best[i];
+    part[threadIdx.x] = s;
+    __syncthreads();
+    for (int o = 128; o > 0; o >>= 1) {
+        if (threadIdx.x < o) part[threadIdx.x] += part[threadIdx.x + o];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *out = part[0];
+}
+
+}  // namespace
+
+hipError_t launch_segment_hist(const int32_t* assign, int64_t n, int64_t seg_len, int nseg, int L,
+                               uint32_t* seg_hist, hipStream_t st) {
+    hipLaunchKernelGGL(k_segment_hist, dim3(nseg), dim3(256), (size_t)L * 4, st, assign, n, seg_len, L, seg_hist);
+    return hipGetLastError();
+}
+
+hipError_t launch_segment_scan(uint32_t* seg_hist, int nseg, int L, uint32_t* batch_count, hipStream_t st) {
+    hipLaunchKernelGGL(k_segment_scan, dim3((L + 255) / 256), dim3(256), 0, st, seg_hist, nseg, L, batch_count);
+    return hipGetLastError();
+}
+
+hipError_t launch_stable_rank(const int32_t* assign, int64_t n, int64_t seg_len, int nseg, int L,
+                              const uint32_t* seg_hist, const int64_t* list_base, int64_t* slot,
+                              hipStream_t st) {
+    hipLaunchKernelGGL(k_stable_rank, dim3(nseg), dim3(64), (size_t)L * 4, st, assign, n, seg_len, L,
+                       seg_hist, list_base, slot);
+    return hipGetLastError();
+}
+
+hipError_t launch_copy_lists(const ListStore& from, const ListStore& to, int L, hipStream_t st) {
+    hipLaunchKernelGGL(k_copy_lists, dim3(L, 8), dim3(256), 0, st, from, to);
+    return hipGetLastError();
+}
+
+hipError_t launch_pack_scatter(const uint8_t* codes, const uint16_t* gamma, const int64_t* labels,
+                               int64_t label_base, const int64_t* slot, int64_t n, int d, int b,
+                               const ListStore& store, hipStream_t st) {
+    if (n <= 0) return hipSuccess;
+    const int64_t items = n * store.words;
+    hipLaunchKernelGGL(k_pack_scatter, dim3((unsigned)((items + 255) / 256)), dim3(256), 0, st, codes, gamma,
+                       labels, label_base, slot, n, d, b, store);
+    return hipGetLastError();
+}
+
+hipError_t launch_fill_u32(uint32_t* p, int64_t n, uint32_t v, hipStream_t st) {
+    if (n <= 0) return hipSuccess;
+    int64_t blocks = (n + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(k_fill_u32, dim3((unsigned)blocks), dim3(256), 0, st, p, n, v);
+    return hipGetLastError();
+}
+
+hipError_t launch_kmeans_accumulate(const float* x, int64_t n, int d, const int32_t* assign,
+                                    float* sums, int pitch, uint32_t* counts, hipStream_t st) {
+    hipLaunchKernelGGL(k_kmeans_accumulate, dim3((unsigned)((n + 3) / 4)), dim3(256), 0, st, x, n, d,
+                       assign, sums, pitch, counts);
+    return hipGetLastError();
+}
+
+hipError_t launch_kmeans_update(float* cent, int pitch, const float* sums, const uint32_t* counts,
+                                float* bias, int L, int Lpad, int d, hipStream_t st) {
+    hipLaunchKernelGGL(k_kmeans_update, dim3(Lpad), dim3(64), 0, st, cent, pitch, sums, counts, bias, L, d);
+    return hipGetLastError();
+}
+
+hipError_t launch_copy_rows_normalised(const float* x, int d, const int64_t* src_row, const int32_t* dst,
+                                       int count, float* cent, int pitch, hipStream_t st) {
+    if (count <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_copy_rows_normalised, dim3(count), dim3(64), 0, st, x, d, src_row, dst, cent, pitch);
+    return hipGetLastError();
+}
+
+hipError_t launch_normalise_centroids(float* cent, int pitch, float* bias, int L, int d, hipStream_t st) {
+    hipLaunchKernelGGL(k_normalise_centroids, dim3(L), dim3(64), 0, st, cent, pitch, bias, d);
+    return hipGetLastError();
+}
+
+hipError_t launch_inertia(const float* best, int64_t n, double* out, hipStream_t st) {
+    hipLaunchKernelGGL(k_inertia, dim3(1), dim3(256), 0, st, best, n, out);
+    return hipGetLastError();
+}
+
+}  // namespace ivftq

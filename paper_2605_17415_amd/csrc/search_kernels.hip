@@ -1,0 +1,308 @@
+// Search-side kernels (Section "Architecture", Search): the scan of the probed lists, which adds
+// the residual estimate gamma * <Pi q~, C[code]> to the exact coarse term, and the per-query
+// selection of the best k (also used to pick the nprobe best cells).
+#include <hip/hip_fp16.h>
+
+#include "kernels.h"
+
+namespace ivftq {
+
+namespace {
+
+// ---- candidate offsets -----------------------------------------------------------------------
+
+__global__ void k_cand_offsets(const int32_t* __restrict__ probe, int64_t nq, int np,
+                               const int32_t* __restrict__ list_size, int32_t* __restrict__ cand_off) {
+    const int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (q >= nq) return;
+    int32_t run = 0;
+    for (int p = 0; p < np; ++p) {
+        cand_off[q * (np + 1) + p] = run;
+        run += list_size[probe[q * np + p]];
+    }
+    cand_off[q * (np + 1) + np] = run;
+}
+
+// ---- list scan: one workgroup per (query, probed list) ---------------------------------------
+//
+// The query's rotated coordinates and the 2^b centroid values are combined once per workgroup
+// into a table lut[j][e] = z_j * C[e] in LDS (the per-query ADC table the paper's own scan uses,
+// Appendix "Why cascade does not yield a speedup"); a lane then owns one stored vector at a time,
+// reads its packed words with 256-byte-per-wavefront coalesced loads and sums d table entries.
+// When the table would not fit LDS (large b and d) DIRECT keeps z and C separately and multiplies
+// per coordinate instead.
+template <int B, bool DIRECT>
+__global__ __launch_bounds__(256) void k_list_scan(const float* __restrict__ z, int z_pitch, int d,
+                                                   const float* __restrict__ cb,
+                                                   const int32_t* __restrict__ probe,
+                                                   const float* __restrict__ coarse,
+                                                   const int32_t* __restrict__ cand_off, int np,
+                                                   ListStore store, int64_t q_begin,
+                                                   float* __restrict__ scores, int64_t m_stride) {
+    constexpr int K = 1 << B;
+    extern __shared__ float lut[];     // [d][K], or z[d] followed by C[K] when DIRECT
+    const int p = blockIdx.x;
+    const int64_t qi = blockIdx.y;     // index inside this pass
+    const int64_t q = q_begin + qi;
+    const int l = probe[q * np + p];
+    const int n_l = store.list_size[l];
+    if (n_l == 0) return;
+
+    if constexpr (DIRECT) {
+        for (int e = threadIdx.x; e < d; e += 256) lut[e] = z[q * z_pitch + e];
+        for (int e = threadIdx.x; e < K; e += 256) lut[d + e] = cb[e];
+    } else {
+        for (int e = threadIdx.x; e < d * K; e += 256) lut[e] = z[q * z_pitch + (e >> B)] * cb[e & (K - 1)];
+    }
+    __syncthreads();
+    auto term = [&](int j, uint32_t code) -> float {
+        if constexpr (DIRECT) return lut[j] * lut[d + code];
+        else return lut[j * K + code];
+    };
+
+    const float s_l = coarse[q * np + p];
+    const int words = store.words;
+    const int64_t base_slot = store.list_off[l];
+    float* out = scores + qi * m_stride + cand_off[q * (np + 1) + p];
+
+    for (int v = threadIdx.x; v < n_l; v += 256) {
+        const int64_t slot = base_slot + v;
+        const uint32_t* wp = store.codes + (slot >> 6) * words * 64 + (slot & 63);
+        float acc = 0.f;
+        if constexpr (32 % B == 0) {
+            constexpr int per = 32 / B;
+            int j = 0;
+            for (int w = 0; w < words; ++w) {
+                uint32_t word = wp[w * 64];
+                if (j + per <= d) {
+#pragma unroll
+                    for (int t = 0; t < per; ++t) {
+                        acc += term(j + t, word & (K - 1));
+                        word >>= B;
+                    }
+                } else {
+                    for (int t = 0; t < per && j + t < d; ++t) {
+                        acc += term(j + t, word & (K - 1));
+                        word >>= B;
+                    }
+                }
+                j += per;
+            }
+        } else {
+            uint64_t buf = 0;
+            int nb = 0, j = 0;
+            for (int w = 0; w < words; ++w) {
+                buf |= (uint64_t)wp[w * 64] << nb;
+                nb += 32;
+                while (nb >= B && j < d) {
+                    acc += term(j, (uint32_t)(buf & (K - 1)));
+                    buf >>= B;
+                    nb -= B;
+                    ++j;
+                }
+            }
+        }
+        const float g = __half2float(__ushort_as_half(store.gamma[slot]));
+        out[v] = s_l + g * acc;
+    }
+}
+
+// ---- selection: k largest of a row ------------------------------------------------------------
+//
+// Exact radix selection on an order-preserving 32-bit key (four 8-bit digits, most significant
+// first), then the survivors are labelled and sorted by (value desc, label asc) with a bitonic
+// network in LDS.  Among values equal to the k-th one, those with the smallest column are kept.
+
+__device__ __forceinline__ uint32_t order_key(float f) {
+    const uint32_t u = __float_as_uint(f);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+template <int MODE>
+__global__ __launch_bounds__(256) void k_select(SelectArgs a) {
+    extern __shared__ unsigned char smem[];
+    int kpad = 1;
+    while (kpad < a.k) kpad <<= 1;
+    uint32_t* hist = reinterpret_cast<uint32_t*>(smem);               // [256]
+    uint32_t* ctrl = hist + 256;                                      // [8]
+    uint32_t* wave_cnt = ctrl + 8;                                    // [4]
+    uint32_t* s_key = wave_cnt + 4;                                   // [kpad]
+    uint32_t* s_col = s_key + kpad;                                   // [kpad]
+    int64_t* s_lab = reinterpret_cast<int64_t*>(s_col + kpad);   // [kpad], 8-byte aligned: 268 + 2*kpad words
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t row = blockIdx.x;
+    const float* vals = a.vals + row * a.stride;
+    const int64_t q = a.q_begin + row;
+    const int m = (MODE == 0) ? a.m_fixed : a.cand_off[q * (a.np + 1) + a.np];
+    const int k = a.k;
+    const int take = m < k ? m : k;
+
+    for (int i = tid; i < kpad; i += 256) { s_key[i] = 0u; s_col[i] = 0xFFFFFFFFu; s_lab[i] = INT64_MAX; }
+
+    uint32_t prefix = 0, mask = 0;
+    uint32_t need = (uint32_t)take;
+    if (take > 0 && m > k) {
+        for (int pass = 0; pass < 4; ++pass) {
+            const int shift = 24 - 8 * pass;
+            hist[tid] = 0;
+            __syncthreads();
+            for (int i = tid; i < m; i += 256) {
+                const uint32_t key = order_key(vals[i]);
+                if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+            }
+            __syncthreads();
+            if (tid == 0) {
+                uint32_t cum = 0;
+                int dgt = 255;
+                for (; dgt > 0; --dgt) {
+                    if (cum + hist[dgt] >= need) break;
+                    cum += hist[dgt];
+                }
+                ctrl[0] = (uint32_t)dgt;
+                ctrl[1] = need - cum;
+            }
+            __syncthreads();
+            prefix |= ctrl[0] << shift;
+            mask |= 255u << shift;
+            need = ctrl[1];
+            __syncthreads();
+        }
+    } else {
+        need = 0;   // everything is taken (m <= k): threshold below every key
+    }
+    // now: keys > prefix are all kept (take - need of them); `need` of the keys == prefix are kept
+    const bool all = !(take > 0 && m > k);
+    if (tid == 0) { ctrl[2] = 0; ctrl[3] = 0; }
+    __syncthreads();
+    const uint32_t n_above = (uint32_t)take - need;
+    if (take > 0) {
+        for (int base = 0; base < m; base += 256) {
+            const int i = base + tid;
+            uint32_t key = 0;
+            bool above = false, tie = false;
+            if (i < m) {
+                key = order_key(vals[i]);
+                above = all || key > prefix;
+                tie = !all && key == prefix;
+            }
+            if (above) {
+                const uint32_t pos = atomicAdd(&ctrl[2], 1u);
+                s_key[pos] = key;
+                s_col[pos] = (uint32_t)i;
+            }
+            // ties in column order: ordered compaction across the workgroup
+            const uint64_t bal = __ballot(tie);
+            if (lane == 0) wave_cnt[wave] = (uint32_t)__popcll(bal);
+            __syncthreads();
+            uint32_t before = ctrl[3];
+            for (int w = 0; w < wave; ++w) before += wave_cnt[w];
+            const uint32_t rank = before + (uint32_t)__popcll(bal & ((1ull << lane) - 1ull));
+            if (tie && rank < need) {
+                s_key[n_above + rank] = key;
+                s_col[n_above + rank] = (uint32_t)i;
+            }
+            __syncthreads();
+            if (tid == 0) ctrl[3] += wave_cnt[0] + wave_cnt[1] + wave_cnt[2] + wave_cnt[3];
+            __syncthreads();
+        }
+    }
+    __syncthreads();
+
+    // labels
+    for (int i = tid; i < take; i += 256) {
+        const uint32_t col = s_col[i];
+        if (MODE == 0) {
+            s_lab[i] = (int64_t)col;
+        } else {
+            const int32_t* off = a.cand_off + q * (a.np + 1);
+            int lo = 0, hi = a.np;          // largest p with off[p] <= col
+            while (hi - lo > 1) {
+                const int mid = (lo + hi) >> 1;
+                if (off[mid] <= (int32_t)col) lo = mid; else hi = mid;
+            }
+            const int l = a.probe[q * a.np + lo];
+            s_lab[i] = a.ids[a.list_off[l] + ((int32_t)col - off[lo])];
+        }
+    }
+    __syncthreads();
+
+    // bitonic sort, descending key then ascending label; empty entries (key 0, label max) sink
+    for (int size = 2; size <= kpad; size <<= 1) {
+        for (int stride = size >> 1; stride > 0; stride >>= 1) {
+            for (int i = tid; i < kpad / 2; i += 256) {
+                const int lo_i = 2 * i - (i & (stride - 1));
+                const int hi_i = lo_i + stride;
+                const bool up = ((lo_i & size) == 0);
+                const uint32_t k0 = s_key[lo_i], k1 = s_key[hi_i];
+                const int64_t l0 = s_lab[lo_i], l1 = s_lab[hi_i];
+                const bool first_before = (k0 > k1) || (k0 == k1 && l0 <= l1);   // lo already precedes hi
+                if (first_before != up) {
+                    s_key[lo_i] = k1; s_key[hi_i] = k0;
+                    s_lab[lo_i] = l1; s_lab[hi_i] = l0;
+                    const uint32_t c0 = s_col[lo_i]; s_col[lo_i] = s_col[hi_i]; s_col[hi_i] = c0;
+                }
+            }
+            __syncthreads();
+        }
+    }
+
+    for (int i = tid; i < k; i += 256) {
+        const bool real = i < take;
+        const float v = real ? vals[s_col[i]] : -__builtin_inff();
+        if (a.out_vals) a.out_vals[row * k + i] = v;
+        if (MODE == 0) { if (a.out_i32) a.out_i32[row * k + i] = real ? (int32_t)s_lab[i] : -1; }
+        else { if (a.out_i64) a.out_i64[row * k + i] = real ? s_lab[i] : -1; }
+    }
+}
+
+}  // namespace
+
+hipError_t launch_cand_offsets(const int32_t* probe, int64_t nq, int np, const int32_t* list_size,
+                               int32_t* cand_off, hipStream_t st) {
+    if (nq <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_cand_offsets, dim3((unsigned)((nq + 127) / 128)), dim3(128), 0, st, probe, nq, np,
+                       list_size, cand_off);
+    return hipGetLastError();
+}
+
+hipError_t launch_list_scan(const float* z, int z_pitch, int d, int b, const float* cb,
+                            const int32_t* probe, const float* coarse, const int32_t* cand_off,
+                            int np, const ListStore& store, int64_t q_begin, int64_t q_count,
+                            float* scores, int64_t m_stride, hipStream_t st) {
+    if (q_count <= 0) return hipSuccess;
+    const size_t lut_bytes = (size_t)d * (1u << b) * sizeof(float);
+    const bool direct = lut_bytes > 64 * 1024;
+    const size_t lds = direct ? (size_t)(d + (1 << b)) * sizeof(float) : lut_bytes;
+    dim3 grid((unsigned)np, (unsigned)q_count);
+#define IVFTQ_SCAN(BV)                                                                              \
+    case BV:                                                                                        \
+        if (direct)                                                                                 \
+            hipLaunchKernelGGL((k_list_scan<BV, true>), grid, dim3(256), lds, st, z, z_pitch, d, cb, probe, \
+                               coarse, cand_off, np, store, q_begin, scores, m_stride);             \
+        else                                                                                        \
+            hipLaunchKernelGGL((k_list_scan<BV, false>), grid, dim3(256), lds, st, z, z_pitch, d, cb, probe, \
+                               coarse, cand_off, np, store, q_begin, scores, m_stride);             \
+        break;
+    switch (b) {
+        IVFTQ_SCAN(1) IVFTQ_SCAN(2) IVFTQ_SCAN(3) IVFTQ_SCAN(4)
+        IVFTQ_SCAN(5) IVFTQ_SCAN(6) IVFTQ_SCAN(7) IVFTQ_SCAN(8)
+        default: return hipErrorInvalidValue;
+    }
+#undef IVFTQ_SCAN
+    return hipGetLastError();
+}
+
+hipError_t launch_select(int mode, const SelectArgs& a, hipStream_t st) {
+    if (a.rows <= 0) return hipSuccess;
+    int kpad = 1;
+    while (kpad < a.k) kpad <<= 1;
+    const size_t lds = (256 + 8 + 4) * 4 + (size_t)kpad * 8 + 8 + (size_t)kpad * 8;
+    if (mode == 0)
+        hipLaunchKernelGGL(k_select<0>, dim3((unsigned)a.rows), dim3(256), lds, st, a);
+    else
+        hipLaunchKernelGGL(k_select<1>, dim3((unsigned)a.rows), dim3(256), lds, st, a);
+    return hipGetLastError();
+}
+
+}  // namespace ivftq

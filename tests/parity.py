@@ -1,0 +1,100 @@
+"""Comparison rules between the HIP path and the oracle (used by the GPU tests and the smoke check).
+
+Agreement is defined as:
+  * coarse assignments and codes are bit-exact, except where the oracle's double-precision value
+    lies within 1e-5 of a decision boundary (coarse: best-minus-second gap below 1e-5); those
+    cases are counted and reported;
+  * the float16 norm is bit-exact unless the double-precision norm sits within 2e-6 (relative) of
+    the midpoint between two neighbouring float16 values, where float32 and float64 may round apart;
+  * estimated inner products agree within 1e-4 relative (plus 1e-6 absolute);
+  * top-k label sets are identical up to ties within that tolerance.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+BOUNDARY_TOL = 1e-5
+SCORE_RTOL = 1e-4
+SCORE_ATOL = 1e-6
+
+
+def compare_encode(enc, g_assign, g_codes, g_gamma16):
+    """enc: oracle encode dict.  Returns a report dict; raises AssertionError on a real mismatch."""
+    n = len(enc["assign"])
+    a_bad = np.flatnonzero(g_assign != enc["assign"])
+    unexplained = [int(i) for i in a_bad if enc["gap"][i] >= BOUNDARY_TOL]
+    assert not unexplained, f"coarse assignment differs away from a near-tie at rows {unexplained[:8]}"
+    same = np.ones(n, bool)
+    same[a_bad] = False
+
+    report = dict(rows=n, assign_near_tie_mismatch=len(a_bad),
+                  assign_near_tie_total=int(np.sum(enc["gap"] < BOUNDARY_TOL)))
+    if g_codes is not None:
+        diff = (g_codes != enc["codes"]) & same[:, None]
+        rows, cols = np.nonzero(diff)
+        far = enc["bdist"][rows, cols] >= BOUNDARY_TOL
+        assert not np.any(far), (f"{int(far.sum())} codes differ away from a decision boundary, first at "
+                                 f"row {rows[far][0]} coord {cols[far][0]}")
+        step = np.abs(g_codes[rows, cols].astype(int) - enc["codes"][rows, cols].astype(int))
+        assert np.all(step <= 1), "a near-boundary code differs by more than one bin"
+        report["code_near_boundary_mismatch"] = int(len(rows))
+        report["code_near_boundary_total"] = int(np.sum(enc["bdist"] < BOUNDARY_TOL))
+    if g_gamma16 is not None:
+        g = np.asarray(g_gamma16).view(np.float16) if g_gamma16.dtype != np.float16 else g_gamma16
+        bad = np.flatnonzero((g.view(np.uint16) != enc["gamma16"].view(np.uint16)) & same)
+        for i in bad:
+            lo, hi = sorted((float(g[i]), float(enc["gamma16"][i])))
+            assert abs(int(g[i].view(np.uint16)) - int(enc["gamma16"][i].view(np.uint16))) == 1, \
+                f"float16 norm of row {i} off by more than one step"
+            mid = 0.5 * (lo + hi)
+            assert abs(enc["gamma"][i] - mid) <= 2e-6 * mid, \
+                f"float16 norm of row {i} differs although the norm is not at a rounding midpoint"
+        report["gamma_midpoint_mismatch"] = int(len(bad))
+    return report
+
+
+def compare_search(g_scores, g_ids, o_scores, o_ids, o_all, probe_gap=None):
+    """o_all: per query (candidate ids, candidate scores) from the oracle.  Returns a report."""
+    nq, k = o_ids.shape
+    excused_probe = 0
+    tie_swaps = 0
+    for q in range(nq):
+        cid, csc = o_all[q]
+        lookup = dict(zip(cid.tolist(), csc.tolist()))
+        near_probe_tie = probe_gap is not None and probe_gap[q] < BOUNDARY_TOL
+        n_real = min(k, len(cid))
+        gi, gs = g_ids[q], g_scores[q]
+        assert np.all(gi[n_real:] == -1) and np.all(np.isneginf(gs[n_real:])), f"query {q}: bad padding"
+        assert np.all(np.diff(gs[:n_real]) <= 0), f"query {q}: scores not descending"
+        assert len(set(gi[:n_real].tolist())) == n_real, f"query {q}: duplicate labels"
+        kth = o_scores[q, n_real - 1] if n_real else 0.0
+        tol = SCORE_RTOL * abs(kth) + SCORE_ATOL
+        missing = False
+        for lab, sc in zip(gi[:n_real].tolist(), gs[:n_real].tolist()):
+            if lab not in lookup:
+                missing = True
+                continue
+            ref = lookup[lab]
+            assert abs(sc - ref) <= SCORE_RTOL * abs(ref) + SCORE_ATOL, \
+                f"query {q} label {lab}: score {sc} vs oracle {ref}"
+        if missing:
+            assert near_probe_tie, f"query {q}: a returned label is outside the oracle's probed lists"
+            excused_probe += 1
+            continue
+        gset, oset = set(gi[:n_real].tolist()), set(o_ids[q, :n_real].tolist())
+        if gset != oset:
+            for lab in gset - oset:
+                assert lookup[lab] >= kth - 2 * tol, f"query {q}: label {lab} is not a tie of the k-th score"
+            for lab in oset - gset:
+                assert lookup[lab] <= kth + 2 * tol or near_probe_tie, \
+                    f"query {q}: oracle label {lab} (score {lookup[lab]}, k-th {kth}) missing"
+            tie_swaps += 1
+    return dict(queries=nq, probe_near_tie_excused=excused_probe, tie_swaps=tie_swaps)
+
+
+def probe_cut_gap(S, nprobe):
+    """Gap between the nprobe-th and (nprobe+1)-th coarse score of each query (inf if none)."""
+    if nprobe >= S.shape[1]:
+        return np.full(S.shape[0], np.inf)
+    part = -np.sort(-S, axis=1)
+    return part[:, nprobe - 1] - part[:, nprobe]

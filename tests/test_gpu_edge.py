@@ -1,0 +1,188 @@
+"""GPU edge cases through the C ABI: empty and ragged inputs, error paths, streaming appends,
+storage growth, custom labels, workspace passes, determinism, and coarse training."""
+import numpy as np
+import pytest
+
+import gpu_cases
+import parity
+from oracle import ivftq_oracle as orc
+from workloads import synth
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+
+def _pkg():
+    import paper_2605_17415_amd as pkg
+    return pkg
+
+
+DEV = "cuda:0"
+
+
+def _index(cs):
+    ix = _pkg().Index(cs.d, cs.b, cs.nlist)
+    ix.set_coarse(cs.cent)
+    ix.set_rotation(cs.Pi)
+    return ix
+
+
+def test_error_paths_do_not_launch_or_append():
+    pkg = _pkg()
+    cs = gpu_cases.get_case("d8_b1")
+    ix = pkg.Index(cs.d, cs.b, cs.nlist)
+    x = torch.from_numpy(cs.X[:100]).to(DEV)
+    with pytest.raises(pkg.IvftqError) as e:
+        ix.encode_add(x)                                   # no centroids yet
+    assert e.value.status == 2
+    with pytest.raises(pkg.IvftqError) as e:
+        ix.search(x, 1, 1)
+    assert e.value.status == 2
+    ix.set_coarse(cs.cent)
+    ix.set_rotation(cs.Pi)
+    for bad in (dict(nprobe=0, k=1), dict(nprobe=cs.nlist + 1, k=1), dict(nprobe=1, k=0), dict(nprobe=1, k=5000)):
+        with pytest.raises(pkg.IvftqError) as e:
+            ix.search(x, **bad)
+        assert e.value.status in (1, 6)
+    # a zero row: error, nothing appended
+    xz = x.clone()
+    xz[17] = 0
+    with pytest.raises(pkg.IvftqError) as e:
+        ix.encode_add(xz)
+    assert e.value.status == 5 and ix.ntotal() == 0
+    xz[17] = float("nan")
+    with pytest.raises(pkg.IvftqError) as e:
+        ix.encode_add(xz)
+    assert e.value.status == 5 and ix.ntotal() == 0
+    a, _, _ = ix.encode_only(xz, want_codes=False)
+    torch.cuda.synchronize()
+    assert a[17].item() == -1 and (a[:17] >= 0).all()
+    # cell numbers out of range in add_encoded
+    enc = gpu_cases.oracle_encode("d8_b1")
+    assign = torch.from_numpy(enc["assign"][:50].copy()).to(DEV)
+    assign[3] = cs.nlist
+    with pytest.raises(pkg.IvftqError) as e:
+        ix.add_encoded(assign, torch.from_numpy(enc["codes"][:50]).to(DEV), torch.from_numpy(enc["gamma16"][:50]).to(DEV))
+    assert e.value.status == 1 and ix.ntotal() == 0
+    # constants are frozen once vectors are stored
+    ix.encode_add(x)
+    with pytest.raises(pkg.IvftqError) as e:
+        ix.set_coarse(cs.cent)
+    assert e.value.status == 2
+    ix.close()
+
+
+def test_empty_inputs_and_empty_index():
+    cs = gpu_cases.get_case("d8_b1")
+    ix = _index(cs)
+    q = torch.from_numpy(cs.Q).to(DEV)
+    sc, ids = ix.search(q, cs.nlist, 4)                    # nothing stored
+    torch.cuda.synchronize()
+    assert (ids == -1).all() and torch.isneginf(sc).all()
+    ix.encode_add(torch.empty((0, cs.d), dtype=torch.float32, device=DEV))
+    assert ix.ntotal() == 0
+    sc0, ids0 = ix.search(torch.empty((0, cs.d), dtype=torch.float32, device=DEV), 1, 3)
+    assert sc0.shape == (0, 3)
+    # two vectors, k larger than the candidates
+    ix.encode_add(torch.from_numpy(cs.X[:2]).to(DEV), ids=torch.tensor([41, 7], device=DEV))
+    sc, ids = ix.search(q, cs.nlist, 5)
+    torch.cuda.synchronize()
+    ids = ids.cpu().numpy()
+    assert np.all(np.sort(ids[:, :2], axis=1) == np.array([7, 41])) and np.all(ids[:, 2:] == -1)
+    assert torch.isneginf(sc[:, 2:]).all() and torch.isfinite(sc[:, :2]).all()
+    ix.close()
+
+
+def test_streaming_appends_equal_one_bulk_add_and_survive_growth():
+    cs = gpu_cases.get_case("d96_b3")
+    x = torch.from_numpy(cs.X).to(DEV)
+    bulk = _index(cs)
+    bulk.encode_add(x)
+    stream = _index(cs)
+    cuts = [0, 1, 65, 700, 701, 5000, 12000, len(cs.X)]     # ragged batches force several regrowths
+    for a, b in zip(cuts[:-1], cuts[1:]):
+        stream.encode_add(x[a:b])
+    assert stream.ntotal() == bulk.ntotal() == len(cs.X)
+    for l in range(cs.nlist):
+        for u, v in zip(bulk.export_list(l), stream.export_list(l)):
+            np.testing.assert_array_equal(u.view(np.uint16) if u.dtype == np.float16 else u,
+                                          v.view(np.uint16) if v.dtype == np.float16 else v)
+    q = torch.from_numpy(cs.Q).to(DEV)
+    s1, i1 = bulk.search(q, cs.nprobe, cs.k)
+    s2, i2 = stream.search(q, cs.nprobe, cs.k)
+    torch.cuda.synchronize()
+    assert torch.equal(i1, i2) and torch.equal(s1, s2)
+    assert bulk.index_bytes() == len(cs.X) * (4 * ((cs.b * cs.d + 31) // 32) + 2 + 8)
+    bulk.close()
+    stream.close()
+
+
+def test_custom_labels_workspace_passes_and_determinism():
+    cs = gpu_cases.get_case("d128")
+    x = torch.from_numpy(cs.X).to(DEV)
+    labels = torch.arange(len(cs.X), device=DEV, dtype=torch.int64) * 3 + 1_000_000_007
+    ix = _index(cs)
+    ix.encode_add(x, ids=labels)
+    q = torch.from_numpy(cs.Q).to(DEV)
+    s1, i1 = ix.search(q, cs.nprobe, cs.k)
+    torch.cuda.synchronize()
+    assert ((i1 - 1_000_000_007) % 3 == 0).all()
+    ix.set_workspace_limit(1 << 20)                          # forces many small query passes
+    s2, i2 = ix.search(q, cs.nprobe, cs.k)
+    torch.cuda.synchronize()
+    assert torch.equal(i1, i2) and torch.equal(s1, s2)
+    for _ in range(2):                                       # same inputs, same bits
+        s3, i3 = ix.search(q, cs.nprobe, cs.k)
+        torch.cuda.synchronize()
+        assert torch.equal(i1, i3) and torch.equal(s1, s3)
+    # a side stream works like the default one
+    st = torch.cuda.Stream()
+    with torch.cuda.stream(st):
+        s4, i4 = ix.search(q, cs.nprobe, cs.k, stream=st)
+    st.synchronize()
+    assert torch.equal(i1, i4) and torch.equal(s1, s4)
+    ix.close()
+
+
+def test_duplicate_vectors_tie_break_by_label():
+    cs = gpu_cases.get_case("d8_b1")
+    ix = _index(cs)
+    x = torch.from_numpy(np.repeat(cs.X[:3], 40, axis=0)).to(DEV)      # 3 distinct vectors, 40 copies each
+    ix.encode_add(x)
+    sc, ids = ix.search(torch.from_numpy(cs.X[:1]).to(DEV), cs.nlist, 50)
+    torch.cuda.synchronize()
+    sc, ids = sc.cpu().numpy()[0], ids.cpu().numpy()[0]
+    for v in np.unique(sc):
+        grp = ids[sc == v]
+        assert np.all(np.diff(grp) > 0)                                 # equal scores: ascending labels
+    assert len(set(ids.tolist())) == 50
+    ix.close()
+
+
+def test_train_coarse_tracks_oracle_kmeans():
+    """k-means is not pinned bit for bit (the paper leaves its details open): same initial rows,
+    same iteration count, objective within 1e-3 relative, unit centroids, every cell used."""
+    w = synth.scaled(synth.config_tiny(), 20_000, 10)
+    X = synth.database(w, 0, w.n)
+    L, iters = 64, 10
+    init = synth.kmeans_init_indices(w.seed, w.n, L)
+    _, o_inertia = orc.train_coarse(X, L, iters, init)
+    ix = _pkg().Index(w.d, 4, L)
+    inertia = ix.train_coarse(torch.from_numpy(X).to(DEV), iters, init_rows=init)
+    cent = ix.get_coarse()
+    print(f"inertia gpu={inertia:.6f} oracle={o_inertia:.6f}", flush=True)
+    assert abs(inertia - o_inertia) <= 1e-3 * o_inertia
+    np.testing.assert_allclose(np.linalg.norm(cent.astype(np.float64), axis=1), 1.0, atol=1e-6)
+    ix.encode_add(torch.from_numpy(X).to(DEV))
+    sizes = np.array([ix.list_size(l) for l in range(L)])
+    assert sizes.sum() == w.n and (sizes > 0).all()
+    # seeded initialisation without explicit rows, and re-seeding of empty cells
+    ix2 = _pkg().Index(w.d, 4, L)
+    in2 = ix2.train_coarse(torch.from_numpy(X).to(DEV), 5, seed=3)
+    assert np.isfinite(in2) and in2 < 1.3 * o_inertia
+    dup = np.repeat(X[:40], 5, axis=0)                                   # 40 distinct points, 64 cells
+    ix3 = _pkg().Index(w.d, 4, L)
+    ix3.train_coarse(torch.from_numpy(dup).to(DEV), 3, seed=1)
+    assert np.all(np.isfinite(ix3.get_coarse()))
+    for i in (ix, ix2, ix3):
+        i.close()

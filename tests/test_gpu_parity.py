@@ -1,0 +1,121 @@
+"""GPU parity: the HIP path through the C ABI against the CPU oracle, element by element."""
+import numpy as np
+import pytest
+
+import gpu_cases
+import parity
+from oracle import ivftq_oracle as orc
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+
+def _pkg():
+    import paper_2605_17415_amd as pkg
+    return pkg
+
+
+def _dev():
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    return torch.device("cuda:0")
+
+
+def _make_index(cs):
+    ix = _pkg().Index(cs.d, cs.b, cs.nlist)
+    ix.set_coarse(cs.cent)
+    ix.set_rotation(cs.Pi)
+    # the library's own (b, d) codebook must be the oracle's
+    c, tau = ix.get_codebook()
+    np.testing.assert_allclose(c, cs.c, rtol=0, atol=2e-8)
+    np.testing.assert_allclose(tau, cs.tau, rtol=0, atol=2e-8)
+    return ix
+
+
+@pytest.mark.parametrize("name", gpu_cases.ALL_CASES)
+def test_encode_matches_oracle(name):
+    cs = gpu_cases.get_case(name)
+    enc = gpu_cases.oracle_encode(name)
+    print(f"[case {name}] n={len(cs.X)} d={cs.d} L={cs.nlist} b={cs.b}", flush=True)
+    ix = _make_index(cs)
+    x = torch.from_numpy(cs.X).to(_dev())
+    assign, codes, gamma = ix.encode_only(x)
+    torch.cuda.synchronize()
+    rep = parity.compare_encode(enc, assign.cpu().numpy(), codes.cpu().numpy(), gamma.cpu().numpy())
+    print("encode_only:", rep, flush=True)
+    assert rep["code_near_boundary_mismatch"] <= rep["code_near_boundary_total"]
+
+    # the stored index holds the same thing, list by list, in arrival order
+    ix.encode_add(x)
+    assert ix.ntotal() == len(cs.X)
+    ga, gc, gg = assign.cpu().numpy(), codes.cpu().numpy(), gamma.cpu().numpy()
+    total = 0
+    for l in range(cs.nlist):
+        ids, lc, lg = ix.export_list(l)
+        members = np.flatnonzero(ga == l)
+        np.testing.assert_array_equal(ids, members)              # stable: arrival order, default labels
+        np.testing.assert_array_equal(lc, gc[members])
+        np.testing.assert_array_equal(lg.view(np.uint16), gg[members].view(np.uint16))
+        total += len(ids)
+    assert total == len(cs.X)
+    ix.close()
+
+
+@pytest.mark.parametrize("name", gpu_cases.ALL_CASES)
+def test_search_matches_oracle_on_the_same_codes(name):
+    cs = gpu_cases.get_case(name)
+    enc = gpu_cases.oracle_encode(name)
+    oidx = gpu_cases.oracle_index(name)
+    print(f"[case {name}] nq={len(cs.Q)} nprobe={cs.nprobe} k={cs.k}", flush=True)
+    dev = _dev()
+    ix = _make_index(cs)
+    ix.add_encoded(torch.from_numpy(enc["assign"]).to(dev), torch.from_numpy(enc["codes"]).to(dev),
+                   torch.from_numpy(enc["gamma16"]).to(dev))
+    for l in range(0, cs.nlist, max(1, cs.nlist // 7)):          # storage round trip
+        ids, lc, lg = ix.export_list(l)
+        np.testing.assert_array_equal(ids, oidx.ids[l])
+        np.testing.assert_array_equal(lc, oidx.codes[l])
+        np.testing.assert_array_equal(lg.view(np.uint16), oidx.gamma16[l].view(np.uint16))
+
+    q = torch.from_numpy(cs.Q).to(dev)
+    o_sc, o_ids, o_probe, S, o_all = orc.search(oidx, cs.Q, cs.nprobe, cs.k, return_all=True)
+    gap = parity.probe_cut_gap(S, cs.nprobe)
+
+    probe, coarse = ix.coarse_probe(q, cs.nprobe)
+    torch.cuda.synchronize()
+    probe, coarse = probe.cpu().numpy(), coarse.cpu().numpy()
+    rows = np.arange(len(cs.Q))[:, None]
+    np.testing.assert_allclose(coarse, S[rows, probe], rtol=1e-5, atol=1e-6)   # exact coarse term
+    assert np.all(np.diff(coarse, axis=1) <= 0)
+    for qi in range(len(cs.Q)):
+        if not np.array_equal(probe[qi], o_probe[qi]):
+            ordered = np.sort(S[qi])[::-1]
+            close = np.min(np.abs(np.diff(ordered[:cs.nprobe + 1]))) < parity.BOUNDARY_TOL
+            assert close and set(probe[qi]) ^ set(o_probe[qi]) <= set(np.argsort(-S[qi])[:cs.nprobe + 1]), \
+                f"query {qi}: probe list differs from the oracle's away from a near-tie"
+
+    scores, ids = ix.search(q, cs.nprobe, cs.k)
+    torch.cuda.synchronize()
+    rep = parity.compare_search(scores.cpu().numpy(), ids.cpu().numpy(), o_sc, o_ids, o_all, gap)
+    print("search:", rep, flush=True)
+    assert rep["probe_near_tie_excused"] <= max(1, len(cs.Q) // 20)
+    ix.close()
+
+
+def test_end_to_end_recall_matches_oracle_pipeline():
+    """GPU encode + GPU search against oracle encode + oracle search and exact ground truth."""
+    cs = gpu_cases.get_case("tiny")
+    oidx = gpu_cases.oracle_index("tiny")
+    dev = _dev()
+    ix = _make_index(cs)
+    ix.encode_add(torch.from_numpy(cs.X).to(dev))
+    scores, ids = ix.search(torch.from_numpy(cs.Q).to(dev), cs.nprobe, cs.k)
+    torch.cuda.synchronize()
+    _, gt = orc.exact_topk(cs.X, cs.Q, cs.k)
+    _, o_ids, _, _ = orc.search(oidx, cs.Q, cs.nprobe, cs.k)
+    r_gpu = orc.recall_at_k(ids.cpu().numpy(), gt)
+    r_orc = orc.recall_at_k(o_ids, gt)
+    print(f"recall@10 gpu={r_gpu:.4f} oracle={r_orc:.4f}", flush=True)
+    assert abs(r_gpu - r_orc) <= 0.005
+    overlap = np.mean([len(set(a) & set(b)) / cs.k for a, b in zip(ids.cpu().numpy(), o_ids)])
+    assert overlap > 0.995
+    ix.close()

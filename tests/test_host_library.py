@@ -1,0 +1,100 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol the header declares,
+and its host-side constants (codebook, rotation) agree with the oracle and with the mathematics.
+No kernel is launched here."""
+import ctypes
+import math
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2605_17415_amd as pkg
+from oracle import ivftq_oracle as orc
+from workloads import synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _header_symbols():
+    text = open(os.path.join(ROOT, "include", "ivftq.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ivftq_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = pkg.load_library()
+    declared = _header_symbols()
+    assert len(declared) >= 20
+    for name in declared:
+        assert hasattr(lib, name), f"{name} is declared in ivftq.h but not exported"
+    assert sorted(pkg.declared_symbols()) == declared       # the binding covers the whole header
+    assert pkg.ivftq_version().startswith("ivftq")
+
+
+@pytest.mark.parametrize("b,d", [(1, 64), (2, 96), (3, 96), (4, 64), (4, 96), (4, 128), (4, 200), (5, 128)])
+def test_codebook_matches_oracle(b, d):
+    c, tau = pkg.ivftq_build_codebook(b, d)
+    oc, otau = orc.lloyd_max_codebook(b, d)
+    assert c.dtype == np.float32 and c.shape == (1 << b,) and tau.shape == ((1 << b) - 1,)
+    np.testing.assert_allclose(c, oc, rtol=0, atol=2e-8)
+    np.testing.assert_allclose(tau, otau, rtol=0, atol=2e-8)
+    assert np.all(np.diff(c) > 0)
+    assert tau[len(tau) // 2] == 0.0                        # the middle boundary is exactly zero
+    np.testing.assert_array_equal(c, -c[::-1])
+
+
+def test_one_bit_codebook_closed_form():
+    for d in (64, 96, 128, 200):
+        c, tau = pkg.ivftq_build_codebook(1, d)
+        closed = math.exp(math.lgamma(d / 2) - 0.5 * math.log(math.pi) - math.lgamma((d + 1) / 2))
+        assert abs(c[1] - closed) < 1e-8 and abs(c[0] + closed) < 1e-8
+
+
+def test_codebook_argument_errors():
+    lib = pkg.load_library()
+    buf = np.empty(256, np.float32)
+    p = buf.ctypes.data_as(ctypes.c_void_p)
+    assert lib.ivftq_build_codebook(0, 64, p, p) == 1
+    assert lib.ivftq_build_codebook(9, 64, p, p) == 1
+    assert lib.ivftq_build_codebook(4, 2, p, p) == 1
+    assert lib.ivftq_build_codebook(4, 64, None, None) == 1
+    assert b"b" in lib.ivftq_last_error() or len(lib.ivftq_last_error()) > 0
+    with pytest.raises(pkg.IvftqError):
+        pkg.ivftq_build_codebook(0, 64)
+
+
+@pytest.mark.parametrize("d", (8, 64, 200))
+def test_rotation_from_shared_gaussian_matches_oracle(d):
+    G = synth.gaussian_matrix(7, d)
+    Pi = pkg.ivftq_haar_from_gaussian(G)
+    ref = orc.haar_rotation_from_gaussian(G)
+    np.testing.assert_allclose(Pi, ref, atol=2e-7)
+
+
+def test_own_rotation_is_orthogonal_and_seeded():
+    d = 96
+    P1, P2, P3 = pkg.ivftq_haar_rotation(d, 1), pkg.ivftq_haar_rotation(d, 1), pkg.ivftq_haar_rotation(d, 2)
+    np.testing.assert_array_equal(P1, P2)
+    assert np.max(np.abs(P1 - P3)) > 0.01
+    P = P1.astype(np.float64)
+    assert np.max(np.abs(P @ P.T - np.eye(d))) < 1e-6
+    # entries of a Haar matrix have variance 1/d and are far from a permutation or identity
+    assert abs(P.var() - 1.0 / d) < 0.05 / d
+    assert np.max(np.abs(P)) < 0.6
+    cols = np.array([pkg.ivftq_haar_rotation(16, s)[:, 0] for s in range(300)], dtype=np.float64)
+    assert abs(cols.mean()) < 0.02 and abs(cols.var() - 1 / 16) < 0.1 / 16
+
+
+def test_create_rejects_bad_arguments_before_touching_a_device():
+    lib = pkg.load_library()
+    h = ctypes.c_void_p()
+    assert lib.ivftq_create(64, 0, 8, 0, ctypes.byref(h)) == 1       # b out of range
+    assert lib.ivftq_create(4, 4, 8, 0, ctypes.byref(h)) == 1        # d too small
+    assert lib.ivftq_create(64, 4, 0, 0, ctypes.byref(h)) == 1       # nlist too small
+    assert lib.ivftq_create(64, 4, 8, 0, None) == 1                  # NULL out pointer
+    assert lib.ivftq_create(4096, 4, 8, 0, ctypes.byref(h)) == 6     # d beyond the limit
+    assert lib.ivftq_create(64, 4, 1 << 20, 0, ctypes.byref(h)) == 6 # nlist beyond the limit
+    assert not h.value
+    assert lib.ivftq_ntotal(None) == -1
+    assert lib.ivftq_destroy(None) == 0
