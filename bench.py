@@ -1,0 +1,241 @@
+#!/usr/bin/env python3
+"""Benchmark of the IVF-TQ hot path on one MI355X.
+
+One step = one pass of the whole hot path over one batch of synthetic input:
+  encode half : ivftq_encode_add of the whole database into an empty index
+                (normalise, coarse assignment, residual rotation, quantise, pack, list append)
+  search half : ivftq_search of the query batch (coarse scoring, probe selection, query rotation,
+                list scan, top-k)
+on the 1M x 128 workload (1,000-component Gaussian mixture, nlist=1024 trained on a 100k sample,
+b=4, 10,000 queries, k=10).  Inputs are resident in device memory before the timed region.
+
+Prints ONE JSON line.  `value` is search QPS at the primary nprobe; encode vectors/s, recall@10,
+the nprobe sweep, the roofline of the dominant kernel and the CPU oracle's throughput on a bounded
+sample ride along in the same object.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_FP32_PEAK_TFLOPS = 157.3  # dense fp32 matrix peak
+
+
+def exact_ground_truth(torch, xd, qd, k, q_chunk=500):
+    """Exact top-k by inner product of normalised rows (measurement harness, not the product)."""
+    xn = xd / xd.norm(dim=1, keepdim=True)
+    out = []
+    for s in range(0, qd.shape[0], q_chunk):
+        q = qd[s:s + q_chunk]
+        q = q / q.norm(dim=1, keepdim=True)
+        out.append(torch.topk(q @ xn.T, k, dim=1).indices)
+    return torch.cat(out).cpu().numpy()
+
+
+def recall(found, truth):
+    hits = 0
+    for f, t in zip(found, truth):
+        hits += len(set(f.tolist()) & set(t.tolist()))
+    return hits / truth.size
+
+
+def cpu_baseline(w, X, Q, nprobe, full_cand_per_query):
+    """The oracle, as it stands, on a bounded sample of the same workload (host cores)."""
+    from oracle import ivftq_oracle as orc
+    from workloads import synth
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = 1
+    n_s, q_s = 100_000, 48
+    Xs = X[:n_s]
+    cent, _ = orc.train_coarse(Xs[:20_000], w.nlist, 2, synth.kmeans_init_indices(w.seed, 20_000, w.nlist))
+    Pi = orc.haar_rotation_from_gaussian(synth.gaussian_matrix(w.seed, w.d))
+    c, tau = orc.lloyd_max_codebook(w.b, w.d)
+    idx = orc.ListIndex(cent, Pi, c, tau)
+    t0 = time.perf_counter()
+    idx.add(Xs)
+    t_enc = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    _, _, probes, _ = orc.search(idx, Q[:q_s], nprobe, w.k)
+    t_search = time.perf_counter() - t0
+    scanned = sum(len(idx.ids[l]) for row in probes for l in row)
+    cand_per_s = scanned / t_search
+    return {
+        "value": cand_per_s / full_cand_per_query, "unit": "queries/s", "cores": int(threads), "kind": "oracle",
+        "sample": (f"oracle index over the first {n_s} database rows (own 2-iteration k-means, nlist={w.nlist}), "
+                   f"{q_s} queries at nprobe={nprobe}: {scanned} candidates scored in {t_search:.2f}s; rate scaled "
+                   f"to the {full_cand_per_query:.0f} candidates/query of the full index"),
+        "encode_vectors_per_s": n_s / t_enc,
+        "encode_sample": f"oracle encode+append of {n_s} rows in {t_enc:.2f}s",
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--nprobe", type=int, default=32)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-sweep", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only: this build has no multi-GPU path (run with --gpus 1)",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2605_17415_amd as pkg
+    from workloads import synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    w = synth.config_1m()
+    t_setup = time.perf_counter()
+    X = synth.database(w)
+    Q = synth.queries(w)
+    xd = torch.from_numpy(X).to(dev)
+    qd = torch.from_numpy(Q).to(dev)
+    rows = synth.train_sample_indices(w)
+    sample = xd[torch.from_numpy(rows).to(dev)].contiguous()
+
+    trainer = pkg.Index(w.d, w.b, w.nlist, rotation_seed=w.seed)
+    t0 = time.perf_counter()
+    trainer.train_coarse(sample, w.kmeans_iters, init_rows=synth.kmeans_init_indices(w.seed, len(rows), w.nlist))
+    t_train = time.perf_counter() - t0
+    cent = trainer.get_coarse()
+    trainer.close()
+    truth = exact_ground_truth(torch, xd, qd, w.k)
+    torch.cuda.synchronize()
+    t_setup = time.perf_counter() - t_setup
+
+    def new_index():
+        ix = pkg.Index(w.d, w.b, w.nlist, rotation_seed=w.seed)
+        ix.set_coarse(cent)
+        return ix
+
+    scores = torch.empty((w.nq, w.k), dtype=torch.float32, device=dev)
+    ids = torch.empty((w.nq, w.k), dtype=torch.int64, device=dev)
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+
+    def step(ix):
+        a, b, c = ev(), ev(), ev()
+        a.record()
+        ix.encode_add(xd)
+        b.record()
+        ix.search(qd, args.nprobe, w.k, out_scores=scores, out_ids=ids)
+        c.record()
+        return a, b, c
+
+    for _ in range(args.warmup):
+        ix = new_index()
+        step(ix)
+        torch.cuda.synchronize()
+        ix.close()
+
+    enc_ms, search_ms, prof = [], [], {}
+    torch.cuda.synchronize()
+    wall0 = time.perf_counter()
+    ix = None
+    for s in range(args.steps):
+        if ix is not None:
+            ix.close()
+        ix = new_index()
+        ix.profile_enable(True)
+        a, b, c = step(ix)
+        torch.cuda.synchronize()
+        enc_ms.append(a.elapsed_time(b))
+        search_ms.append(b.elapsed_time(c))
+        for name, (ms, cnt) in ix.profile_read().items():
+            t = prof.setdefault(name, [0.0, 0])
+            t[0] += ms
+            t[1] += cnt
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - wall0
+    ix.profile_enable(False)
+
+    found = ids.cpu().numpy()
+    rec = recall(found, truth)
+    enc_t = float(np.mean(enc_ms)) / 1e3
+    search_t = float(np.mean(search_ms)) / 1e3
+    qps = w.nq / search_t
+    vps = w.n / enc_t
+
+    # algorithmic work of the two candidate dominant kernels
+    probe, _ = ix.coarse_probe(qd, args.nprobe)
+    sizes = np.array([ix.list_size(l) for l in range(w.nlist)], dtype=np.int64)
+    cand = sizes[probe.cpu().numpy()].sum(axis=1)
+    bytes_per_vec = (w.b * w.d + 7) // 8 + 2
+    scan_bytes = float(cand.sum()) * bytes_per_vec
+    assign_flops = 2.0 * w.d * w.nlist * w.n
+
+    def avg_ms(name):
+        t = prof.get(name)
+        return t[0] / t[1] if t and t[1] else None
+
+    scan_ms, assign_ms = avg_ms("list_scan"), avg_ms("coarse_assign")
+    scan_roof = {"kernel": "list_scan", "bound": "hbm", "achieved": scan_bytes / (scan_ms * 1e-3) / 1e9,
+                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "traffic": None,
+                 "algorithmic_bytes_per_launch": scan_bytes, "avg_launch_ms": scan_ms}
+    scan_roof["frac"] = scan_roof["achieved"] / scan_roof["peak"]
+    assign_roof = {"kernel": "coarse_assign", "bound": "mfma", "achieved": assign_flops / (assign_ms * 1e-3) / 1e12,
+                   "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s", "traffic": None,
+                   "algorithmic_flops_per_launch": assign_flops, "avg_launch_ms": assign_ms}
+    assign_roof["frac"] = assign_roof["achieved"] / assign_roof["peak"]
+    per_step = {k: v[0] / args.steps for k, v in prof.items()}
+    dominant = max(per_step, key=per_step.get)
+    roofline, other = (scan_roof, assign_roof) if per_step.get("list_scan", 0) >= per_step.get("coarse_assign", 0) \
+        else (assign_roof, scan_roof)
+
+    sweep = []
+    if not args.no_sweep:
+        for npb in w.nprobe:
+            ts = []
+            for _ in range(3):
+                a, b = ev(), ev()
+                a.record()
+                ix.search(qd, npb, w.k, out_scores=scores, out_ids=ids)
+                b.record()
+                torch.cuda.synchronize()
+                ts.append(a.elapsed_time(b))
+            sweep.append({"nprobe": npb, "qps": w.nq / (float(np.median(ts)) / 1e3),
+                          "recall_at_10": recall(ids.cpu().numpy(), truth)})
+
+    out = {
+        "metric": f"search QPS at recall@10 (nprobe={args.nprobe}, k={w.k}) + encode vectors/s",
+        "value": qps, "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": wall / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "1M x 128 fp32, 1000-component Gaussian mixture, nlist=1024 (k-means on a 100k "
+                               "sample), b=4, 10000 queries, k=10", "nprobe": args.nprobe, "n": w.n, "d": w.d,
+                   "nlist": w.nlist, "b": w.b, "nq": w.nq, "k": w.k},
+        "recall_at_10": rec,
+        "search_ms": search_t * 1e3, "encode_ms": enc_t * 1e3, "encode_vectors_per_s": vps,
+        "candidates_per_query": float(cand.mean()),
+        "index_bytes": ix.index_bytes(),
+        "kernel_ms_per_step": per_step, "dominant_kernel": dominant,
+        "roofline": roofline, "roofline_other": other,
+        "sweep": sweep,
+        "setup_s": t_setup, "train_coarse_s": t_train,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, X, Q, args.nprobe, float(cand.mean()))
+    ix.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -148,6 +148,18 @@ int64_t ivftq_index_bytes(const ivftq_index* index);
  * in as many passes as that allows. */
 ivftq_status ivftq_set_workspace_limit(ivftq_index* index, int64_t bytes);
 
+/* ---- per-kernel timing (measurement aid) ------------------------------------------------ */
+
+/* While enabled, every kernel launch made for this index is bracketed by two HIP events recorded
+ * on the launch stream.  ivftq_profile_read synchronises the device, adds up the elapsed time and
+ * the number of launches per kernel class since the last read (ms_out, launches_out: host arrays
+ * of ivftq_profile_kernel_count() entries) and clears the records.  Enabling or disabling clears
+ * them too.  Kernel classes are named by ivftq_profile_kernel_name(id). */
+ivftq_status ivftq_profile_enable(ivftq_index* index, int on);
+ivftq_status ivftq_profile_read(ivftq_index* index, double* ms_out, int64_t* launches_out);
+int ivftq_profile_kernel_count(void);
+const char* ivftq_profile_kernel_name(int id);
+
 const char* ivftq_last_error(void);
 const char* ivftq_version(void);
 

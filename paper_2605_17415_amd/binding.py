@@ -45,6 +45,10 @@ _SIGNATURES = {
     "ivftq_export_list": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]),
     "ivftq_index_bytes": (C.c_int64, [C.c_void_p]),
     "ivftq_set_workspace_limit": (C.c_int, [C.c_void_p, C.c_int64]),
+    "ivftq_profile_enable": (C.c_int, [C.c_void_p, C.c_int]),
+    "ivftq_profile_read": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
+    "ivftq_profile_kernel_count": (C.c_int, []),
+    "ivftq_profile_kernel_name": (C.c_char_p, [C.c_int]),
     "ivftq_last_error": (C.c_char_p, []),
     "ivftq_version": (C.c_char_p, []),
 }
@@ -258,6 +262,19 @@ class Index:
         _check(self._lib.ivftq_coarse_probe(self._h, _dev_ptr(q, torch.float32, "q"), nq, nprobe,
                                             _dev_ptr(probe), _dev_ptr(coarse), _stream_ptr(stream)))
         return probe, coarse
+
+    # per-kernel timing
+    def profile_enable(self, on: bool = True):
+        _check(self._lib.ivftq_profile_enable(self._h, 1 if on else 0))
+
+    def profile_read(self) -> dict:
+        """{kernel class: (total ms, launches)} since the last read."""
+        cnt = self._lib.ivftq_profile_kernel_count()
+        ms = np.zeros(cnt, np.float64)
+        launches = np.zeros(cnt, np.int64)
+        _check(self._lib.ivftq_profile_read(self._h, _np_ptr(ms), _np_ptr(launches)))
+        return {self._lib.ivftq_profile_kernel_name(i).decode(): (float(ms[i]), int(launches[i]))
+                for i in range(cnt) if launches[i] > 0}
 
     # inspection
     def ntotal(self) -> int:

@@ -58,6 +58,15 @@ struct DevBuf {
     template <class T> T* as() const { return static_cast<T*>(p); }
 };
 
+// kernel classes for the optional per-launch timing
+enum ProfId { P_ASSIGN, P_COARSE_SCORES, P_ENCODE, P_ROTATE_Q, P_SEG_HIST, P_SEG_SCAN, P_RANK, P_PACK,
+              P_COPY_LISTS, P_SELECT_PROBE, P_CAND_OFF, P_LIST_SCAN, P_SELECT_TOPK, P_KMEANS_UPDATE, P_COUNT };
+const char* const kProfNames[P_COUNT] = {"coarse_assign", "coarse_scores", "encode_rotate_quantise_pack",
+                                         "rotate_queries", "segment_hist", "segment_scan", "stable_rank",
+                                         "pack_scatter", "copy_lists", "select_probes", "cand_offsets",
+                                         "list_scan", "select_topk", "kmeans_update"};
+struct ProfRec { int id; hipEvent_t a, b; };
+
 uint64_t splitmix(uint64_t& s) {
     uint64_t z = (s += 0x9E3779B97F4A7C15ull);
     z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
@@ -84,6 +93,8 @@ struct ivftq_index {
     DevBuf w_S, w_probe, w_coarse, w_z, w_candoff, w_scores;
     DevBuf w_sums, w_counts, w_zero, w_rows, w_dst, w_obj;
     int64_t ws_limit = (int64_t)4 << 30;
+    bool prof_on = false;
+    std::vector<ProfRec> prof;
 
     ListStore store() const {
         ListStore s;
@@ -96,6 +107,7 @@ struct ivftq_index {
         return s;
     }
     ~ivftq_index() {
+        for (ProfRec& r : prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
         for (DevBuf* bfr : {&cent, &bias, &pi, &cb, &tau, &codes, &gamma, &ids, &d_off, &d_size, &w_assign,
                             &w_slot, &w_hist, &w_count, &w_base, &w_flag, &w_best, &w_S, &w_probe, &w_coarse,
                             &w_z, &w_candoff, &w_scores, &w_sums, &w_counts, &w_zero, &w_rows, &w_dst, &w_obj})
@@ -104,6 +116,26 @@ struct ivftq_index {
 };
 
 namespace {
+
+// Runs one launch; when profiling is on, brackets it with events on the launch stream.
+template <class F>
+hipError_t timed(ivftq_index* ix, hipStream_t st, int id, F&& launch) {
+    if (!ix->prof_on) return launch();
+    ProfRec r{id, nullptr, nullptr};
+    hipError_t e = hipEventCreate(&r.a);
+    if (e == hipSuccess) e = hipEventCreate(&r.b);
+    if (e == hipSuccess) e = hipEventRecord(r.a, st);
+    if (e != hipSuccess) return e;
+    e = launch();
+    hipError_t e2 = hipEventRecord(r.b, st);
+    ix->prof.push_back(r);
+    return e != hipSuccess ? e : e2;
+}
+
+void drop_profile(ivftq_index* ix) {
+    for (ProfRec& r : ix->prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+    ix->prof.clear();
+}
 
 ivftq_status upload_coarse(ivftq_index* ix) {
     std::vector<float> padded((size_t)ix->lpad * ix->dp, 0.f);
@@ -154,7 +186,7 @@ ivftq_status ensure_capacity(ivftq_index* ix, const std::vector<int64_t>& need, 
         to.gamma = ngamma.as<uint16_t>();
         to.ids = nids.as<int64_t>();
         to.list_off = noff.as<int64_t>();
-        HIP_TRY(launch_copy_lists(from, to, ix->nlist, st));
+        HIP_TRY(timed(ix, st, P_COPY_LISTS, [&] { return launch_copy_lists(from, to, ix->nlist, st); }));
     }
     HIP_TRY(hipStreamSynchronize(st));   // `off` is pageable host memory; old pool is about to be freed
     ix->codes.release(); ix->gamma.release(); ix->ids.release(); ix->d_off.release();
@@ -309,6 +341,33 @@ ivftq_status ivftq_set_workspace_limit(ivftq_index* ix, int64_t bytes) {
     return IVFTQ_OK;
 }
 
+ivftq_status ivftq_profile_enable(ivftq_index* ix, int on) {
+    if (check_index(ix)) return IVFTQ_INVALID_ARG;
+    HIP_TRY(hipDeviceSynchronize());
+    drop_profile(ix);
+    ix->prof_on = on != 0;
+    return IVFTQ_OK;
+}
+
+int ivftq_profile_kernel_count(void) { return P_COUNT; }
+
+const char* ivftq_profile_kernel_name(int id) { return (id >= 0 && id < P_COUNT) ? kProfNames[id] : ""; }
+
+ivftq_status ivftq_profile_read(ivftq_index* ix, double* ms_out, int64_t* launches_out) {
+    if (check_index(ix)) return IVFTQ_INVALID_ARG;
+    if (!ms_out || !launches_out) return fail(IVFTQ_INVALID_ARG, "output pointer is NULL");
+    HIP_TRY(hipDeviceSynchronize());
+    for (int i = 0; i < P_COUNT; ++i) { ms_out[i] = 0.0; launches_out[i] = 0; }
+    for (const ProfRec& r : ix->prof) {
+        float ms = 0.f;
+        HIP_TRY(hipEventElapsedTime(&ms, r.a, r.b));
+        ms_out[r.id] += ms;
+        launches_out[r.id] += 1;
+    }
+    drop_profile(ix);
+    return IVFTQ_OK;
+}
+
 int64_t ivftq_ntotal(const ivftq_index* ix) { return ix ? ix->ntotal : -1; }
 
 int64_t ivftq_index_bytes(const ivftq_index* ix) {
@@ -402,8 +461,8 @@ ivftq_status ivftq_train_coarse(ivftq_index* ix, const float* x_dev, int64_t n, 
     HIP_TRY(hipMemcpyAsync(ix->w_dst.p, dst.data(), L * sizeof(int32_t), hipMemcpyHostToDevice, st));
     HIP_TRY(launch_copy_rows_normalised(x_dev, d, ix->w_rows.as<int64_t>(), ix->w_dst.as<int32_t>(), L,
                                         ix->cent.as<float>(), pitch, st));
-    HIP_TRY(launch_kmeans_update(ix->cent.as<float>(), pitch, ix->w_sums.as<float>(), ix->w_zero.as<uint32_t>(),
-                                 ix->bias.as<float>(), L, ix->lpad, d, st));
+    HIP_TRY(timed(ix, st, P_KMEANS_UPDATE, [&] { return launch_kmeans_update(ix->cent.as<float>(), pitch, ix->w_sums.as<float>(), ix->w_zero.as<uint32_t>(),
+                                 ix->bias.as<float>(), L, ix->lpad, d, st); }));
     HIP_TRY(hipStreamSynchronize(st));
 
     std::vector<uint32_t> counts(L);
@@ -413,13 +472,13 @@ ivftq_status ivftq_train_coarse(ivftq_index* ix, const float* x_dev, int64_t n, 
     for (int it = 0; it < niter; ++it) {
         HIP_TRY(launch_fill_u32(ix->w_sums.as<uint32_t>(), (int64_t)ix->lpad * pitch, 0u, st));
         HIP_TRY(launch_fill_u32(ix->w_counts.as<uint32_t>(), ix->lpad, 0u, st));
-        HIP_TRY(launch_coarse(0, x_dev, n, d, ix->cent.as<float>(), pitch, ix->bias.as<float>(), L, ix->lpad,
+        HIP_TRY(timed(ix, st, P_ASSIGN, [&] { return launch_coarse(0, x_dev, n, d, ix->cent.as<float>(), pitch, ix->bias.as<float>(), L, ix->lpad,
                               ix->w_assign.as<int32_t>(), ix->w_best.as<float>(), nullptr, 0,
-                              ix->w_flag.as<int>(), st));
+                              ix->w_flag.as<int>(), st); }));
         HIP_TRY(launch_kmeans_accumulate(x_dev, n, d, ix->w_assign.as<int32_t>(), ix->w_sums.as<float>(), pitch,
                                          ix->w_counts.as<uint32_t>(), st));
-        HIP_TRY(launch_kmeans_update(ix->cent.as<float>(), pitch, ix->w_sums.as<float>(),
-                                     ix->w_counts.as<uint32_t>(), ix->bias.as<float>(), L, ix->lpad, d, st));
+        HIP_TRY(timed(ix, st, P_KMEANS_UPDATE, [&] { return launch_kmeans_update(ix->cent.as<float>(), pitch, ix->w_sums.as<float>(),
+                                     ix->w_counts.as<uint32_t>(), ix->bias.as<float>(), L, ix->lpad, d, st); }));
         if (it == niter - 1) HIP_TRY(launch_inertia(ix->w_best.as<float>(), n, ix->w_obj.as<double>(), st));
         HIP_TRY(hipMemcpyAsync(counts.data(), ix->w_counts.p, L * sizeof(uint32_t), hipMemcpyDeviceToHost, st));
         int flag = 0;
@@ -443,8 +502,8 @@ ivftq_status ivftq_train_coarse(ivftq_index* ix, const float* x_dev, int64_t n, 
             HIP_TRY(hipMemcpy(ix->w_dst.p, empty.data(), empty.size() * sizeof(int32_t), hipMemcpyHostToDevice));
             HIP_TRY(launch_copy_rows_normalised(x_dev, d, ix->w_rows.as<int64_t>(), ix->w_dst.as<int32_t>(),
                                                 (int)empty.size(), ix->cent.as<float>(), pitch, st));
-            HIP_TRY(launch_kmeans_update(ix->cent.as<float>(), pitch, ix->w_sums.as<float>(),
-                                         ix->w_zero.as<uint32_t>(), ix->bias.as<float>(), L, ix->lpad, d, st));
+            HIP_TRY(timed(ix, st, P_KMEANS_UPDATE, [&] { return launch_kmeans_update(ix->cent.as<float>(), pitch, ix->w_sums.as<float>(),
+                                         ix->w_zero.as<uint32_t>(), ix->bias.as<float>(), L, ix->lpad, d, st); }));
             HIP_TRY(hipStreamSynchronize(st));
         }
     }
@@ -474,8 +533,8 @@ ivftq_status place_rows(ivftq_index* ix, const int32_t* assign, int64_t n, bool 
     HIP_TRY(ix->w_hist.ensure((size_t)nseg * L * sizeof(uint32_t)));
     HIP_TRY(ix->w_count.ensure((size_t)L * sizeof(uint32_t)));
     HIP_TRY(ix->w_base.ensure((size_t)L * sizeof(int64_t)));
-    HIP_TRY(launch_segment_hist(assign, n, seg_len, nseg, L, ix->w_hist.as<uint32_t>(), st));
-    HIP_TRY(launch_segment_scan(ix->w_hist.as<uint32_t>(), nseg, L, ix->w_count.as<uint32_t>(), st));
+    HIP_TRY(timed(ix, st, P_SEG_HIST, [&] { return launch_segment_hist(assign, n, seg_len, nseg, L, ix->w_hist.as<uint32_t>(), st); }));
+    HIP_TRY(timed(ix, st, P_SEG_SCAN, [&] { return launch_segment_scan(ix->w_hist.as<uint32_t>(), nseg, L, ix->w_count.as<uint32_t>(), st); }));
     std::vector<uint32_t> count(L);
     int flag = 0;
     HIP_TRY(hipMemcpyAsync(count.data(), ix->w_count.p, L * sizeof(uint32_t), hipMemcpyDeviceToHost, st));
@@ -496,8 +555,8 @@ ivftq_status place_rows(ivftq_index* ix, const int32_t* assign, int64_t n, bool 
     if (s != IVFTQ_OK) return s;
     for (int l = 0; l < L; ++l) base[l] = ix->h_off[l] + ix->h_size[l];
     HIP_TRY(hipMemcpyAsync(ix->w_base.p, base.data(), L * sizeof(int64_t), hipMemcpyHostToDevice, st));
-    HIP_TRY(launch_stable_rank(assign, n, seg_len, nseg, L, ix->w_hist.as<uint32_t>(), ix->w_base.as<int64_t>(),
-                               ix->w_slot.as<int64_t>(), st));
+    HIP_TRY(timed(ix, st, P_RANK, [&] { return launch_stable_rank(assign, n, seg_len, nseg, L, ix->w_hist.as<uint32_t>(), ix->w_base.as<int64_t>(),
+                               ix->w_slot.as<int64_t>(), st); }));
     HIP_TRY(hipStreamSynchronize(st));   // `base` is pageable host memory
     return IVFTQ_OK;
 }
@@ -523,8 +582,8 @@ ivftq_status ivftq_encode_only(ivftq_index* ix, const float* x_dev, int64_t n, i
     HIP_TRY(ix->w_assign.ensure((size_t)n * sizeof(int32_t)));
     int32_t* assign = assign_dev ? assign_dev : ix->w_assign.as<int32_t>();
     HIP_TRY(launch_fill_u32(ix->w_flag.as<uint32_t>(), 1, 0u, st));
-    HIP_TRY(launch_coarse(0, x_dev, n, ix->d, ix->cent.as<float>(), ix->dp, nullptr, ix->nlist, ix->lpad, assign,
-                          nullptr, nullptr, 0, ix->w_flag.as<int>(), st));
+    HIP_TRY(timed(ix, st, P_ASSIGN, [&] { return launch_coarse(0, x_dev, n, ix->d, ix->cent.as<float>(), ix->dp, nullptr, ix->nlist, ix->lpad, assign,
+                          nullptr, nullptr, 0, ix->w_flag.as<int>(), st); }));
     if (codes_dev || gamma_dev) {
         EncodeArgs a{};
         a.x = x_dev; a.n = n; a.d = ix->d; a.b = ix->b;
@@ -532,7 +591,7 @@ ivftq_status ivftq_encode_only(ivftq_index* ix, const float* x_dev, int64_t n, i
         a.pi = ix->pi.as<float>(); a.tau = ix->tau.as<float>();
         a.assign = assign;
         a.codes_flat = codes_dev; a.gamma_flat = gamma_dev;
-        HIP_TRY(launch_encode(1, a, st));
+        HIP_TRY(timed(ix, st, P_ENCODE, [&] { return launch_encode(1, a, st); }));
     }
     return IVFTQ_OK;
 }
@@ -552,8 +611,8 @@ ivftq_status ivftq_encode_add(ivftq_index* ix, const float* x_dev, int64_t n, co
     HIP_TRY(ix->w_assign.ensure((size_t)n * sizeof(int32_t)));
     HIP_TRY(ix->w_slot.ensure((size_t)n * sizeof(int64_t)));
     HIP_TRY(launch_fill_u32(ix->w_flag.as<uint32_t>(), 1, 0u, st));
-    HIP_TRY(launch_coarse(0, x_dev, n, ix->d, ix->cent.as<float>(), ix->dp, nullptr, L, ix->lpad,
-                          ix->w_assign.as<int32_t>(), nullptr, nullptr, 0, ix->w_flag.as<int>(), st));
+    HIP_TRY(timed(ix, st, P_ASSIGN, [&] { return launch_coarse(0, x_dev, n, ix->d, ix->cent.as<float>(), ix->dp, nullptr, L, ix->lpad,
+                          ix->w_assign.as<int32_t>(), nullptr, nullptr, 0, ix->w_flag.as<int>(), st); }));
 
     // 2.-4. room for the new vectors and the stable position of every row
     std::vector<int64_t> need;
@@ -568,7 +627,7 @@ ivftq_status ivftq_encode_add(ivftq_index* ix, const float* x_dev, int64_t n, co
     a.store = ix->store();
     a.slot = ix->w_slot.as<int64_t>();
     a.labels = ids_dev; a.label_base = ix->ntotal;
-    HIP_TRY(launch_encode(0, a, st));
+    HIP_TRY(timed(ix, st, P_ENCODE, [&] { return launch_encode(0, a, st); }));
     return commit_rows(ix, need, n, st);
 }
 
@@ -586,8 +645,8 @@ ivftq_status ivftq_add_encoded(ivftq_index* ix, int64_t n, const int32_t* assign
     std::vector<int64_t> need;
     ivftq_status s = place_rows(ix, assign_dev, n, false, need, st);
     if (s != IVFTQ_OK) return s;
-    HIP_TRY(launch_pack_scatter(codes_dev, gamma_dev, ids_dev, ix->ntotal, ix->w_slot.as<int64_t>(), n, ix->d,
-                                ix->b, ix->store(), st));
+    HIP_TRY(timed(ix, st, P_PACK, [&] { return launch_pack_scatter(codes_dev, gamma_dev, ids_dev, ix->ntotal, ix->w_slot.as<int64_t>(), n, ix->d,
+                                ix->b, ix->store(), st); }));
     return commit_rows(ix, need, n, st);
 }
 
@@ -609,12 +668,12 @@ ivftq_status check_query_args(const ivftq_index* ix, const float* q_dev, int64_t
 ivftq_status coarse_and_probe(ivftq_index* ix, const float* q, int64_t count, int nprobe, int32_t* probe,
                               float* coarse, hipStream_t st) {
     const int64_t ldS = round_up(ix->nlist, 4);
-    HIP_TRY(launch_coarse(1, q, count, ix->d, ix->cent.as<float>(), ix->dp, nullptr, ix->nlist, ix->lpad, nullptr,
-                          nullptr, ix->w_S.as<float>(), ldS, ix->w_flag.as<int>(), st));
+    HIP_TRY(timed(ix, st, P_COARSE_SCORES, [&] { return launch_coarse(1, q, count, ix->d, ix->cent.as<float>(), ix->dp, nullptr, ix->nlist, ix->lpad, nullptr,
+                          nullptr, ix->w_S.as<float>(), ldS, ix->w_flag.as<int>(), st); }));
     SelectArgs sa{};
     sa.vals = ix->w_S.as<float>(); sa.stride = ldS; sa.rows = count; sa.k = nprobe; sa.m_fixed = ix->nlist;
     sa.out_vals = coarse; sa.out_i32 = probe;
-    HIP_TRY(launch_select(0, sa, st));
+    HIP_TRY(timed(ix, st, P_SELECT_PROBE, [&] { return launch_select(0, sa, st); }));
     return IVFTQ_OK;
 }
 
@@ -674,20 +733,20 @@ ivftq_status ivftq_search(ivftq_index* ix, const float* q_dev, int64_t nq, int n
         EncodeArgs ea{};
         ea.x = q; ea.n = cnt; ea.d = ix->d; ea.b = ix->b;
         ea.pi = ix->pi.as<float>(); ea.zout = ix->w_z.as<float>();
-        HIP_TRY(launch_encode(2, ea, st));
-        HIP_TRY(launch_cand_offsets(ix->w_probe.as<int32_t>(), cnt, nprobe, ix->d_size.as<int32_t>(),
-                                    ix->w_candoff.as<int32_t>(), st));
-        HIP_TRY(launch_list_scan(ix->w_z.as<float>(), ix->dp, ix->d, ix->b, ix->cb.as<float>(),
+        HIP_TRY(timed(ix, st, P_ROTATE_Q, [&] { return launch_encode(2, ea, st); }));
+        HIP_TRY(timed(ix, st, P_CAND_OFF, [&] { return launch_cand_offsets(ix->w_probe.as<int32_t>(), cnt, nprobe, ix->d_size.as<int32_t>(),
+                                    ix->w_candoff.as<int32_t>(), st); }));
+        HIP_TRY(timed(ix, st, P_LIST_SCAN, [&] { return launch_list_scan(ix->w_z.as<float>(), ix->dp, ix->d, ix->b, ix->cb.as<float>(),
                                  ix->w_probe.as<int32_t>(), ix->w_coarse.as<float>(),
                                  ix->w_candoff.as<int32_t>(), nprobe, ix->store(), 0, cnt,
-                                 ix->w_scores.as<float>(), m_stride, st));
+                                 ix->w_scores.as<float>(), m_stride, st); }));
         SelectArgs sa{};
         sa.vals = ix->w_scores.as<float>(); sa.stride = m_stride; sa.rows = cnt; sa.k = k;
         sa.cand_off = ix->w_candoff.as<int32_t>(); sa.probe = ix->w_probe.as<int32_t>(); sa.np = nprobe;
         sa.q_begin = 0;
         sa.list_off = ix->d_off.as<int64_t>(); sa.ids = ix->ids.as<int64_t>();
         sa.out_vals = scores_dev + q0 * k; sa.out_i64 = ids_dev + q0 * k;
-        HIP_TRY(launch_select(1, sa, st));
+        HIP_TRY(timed(ix, st, P_SELECT_TOPK, [&] { return launch_select(1, sa, st); }));
     }
     return IVFTQ_OK;
 }

@@ -4,6 +4,10 @@ Agreement is defined as:
   * coarse assignments and codes are bit-exact, except where the oracle's double-precision value
     lies within 1e-5 of a decision boundary (coarse: best-minus-second gap below 1e-5); those
     cases are counted and reported;
+  * when the residual is tiny the float32 rounding of x~ (relative 2^-24 per coordinate, about
+    6e-9 absolute) is magnified by 1/gamma in the unit residual, so the boundary tolerance of a row
+    is max(1e-5, 4e-7/gamma): it only exceeds 1e-5 for gamma < 0.04, i.e. a vector that nearly
+    coincides with its centroid, whose residual direction is rounding noise in any precision;
   * the float16 norm is bit-exact unless the double-precision norm sits within 2e-6 (relative) of
     the midpoint between two neighbouring float16 values, where float32 and float64 may round apart;
   * estimated inner products agree within 1e-4 relative (plus 1e-6 absolute);
@@ -16,6 +20,7 @@ import numpy as np
 BOUNDARY_TOL = 1e-5
 SCORE_RTOL = 1e-4
 SCORE_ATOL = 1e-6
+NOISE_FLOOR = 4e-7     # absolute float32 rounding noise of a normalised coordinate, with margin
 
 
 def compare_encode(enc, g_assign, g_codes, g_gamma16):
@@ -32,13 +37,17 @@ def compare_encode(enc, g_assign, g_codes, g_gamma16):
     if g_codes is not None:
         diff = (g_codes != enc["codes"]) & same[:, None]
         rows, cols = np.nonzero(diff)
-        far = enc["bdist"][rows, cols] >= BOUNDARY_TOL
+        row_tol = np.maximum(BOUNDARY_TOL, NOISE_FLOOR / np.maximum(enc["gamma"], 1e-300))
+        far = enc["bdist"][rows, cols] >= row_tol[rows]
         assert not np.any(far), (f"{int(far.sum())} codes differ away from a decision boundary, first at "
                                  f"row {rows[far][0]} coord {cols[far][0]}")
+        regular = row_tol[rows] <= BOUNDARY_TOL
         step = np.abs(g_codes[rows, cols].astype(int) - enc["codes"][rows, cols].astype(int))
-        assert np.all(step <= 1), "a near-boundary code differs by more than one bin"
-        report["code_near_boundary_mismatch"] = int(len(rows))
+        assert np.all(step[regular] <= 1), "a near-boundary code differs by more than one bin"
+        report["code_near_boundary_mismatch"] = int(np.sum(regular))
         report["code_near_boundary_total"] = int(np.sum(enc["bdist"] < BOUNDARY_TOL))
+        report["tiny_residual_rows"] = int(np.sum(row_tol > BOUNDARY_TOL))
+        report["tiny_residual_code_mismatch"] = int(np.sum(~regular))
     if g_gamma16 is not None:
         g = np.asarray(g_gamma16).view(np.float16) if g_gamma16.dtype != np.float16 else g_gamma16
         bad = np.flatnonzero((g.view(np.uint16) != enc["gamma16"].view(np.uint16)) & same)
@@ -47,7 +56,7 @@ def compare_encode(enc, g_assign, g_codes, g_gamma16):
             assert abs(int(g[i].view(np.uint16)) - int(enc["gamma16"][i].view(np.uint16))) == 1, \
                 f"float16 norm of row {i} off by more than one step"
             mid = 0.5 * (lo + hi)
-            assert abs(enc["gamma"][i] - mid) <= 2e-6 * mid, \
+            assert abs(enc["gamma"][i] - mid) <= 2e-6 * mid + 1e-7, \
                 f"float16 norm of row {i} differs although the norm is not at a rounding midpoint"
         report["gamma_midpoint_mismatch"] = int(len(bad))
     return report
