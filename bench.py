@@ -42,6 +42,20 @@ def exact_ground_truth(torch, xd, qd, k, q_chunk=500):
     return torch.cat(out).cpu().numpy()
 
 
+def stored_traffic(kernel: str, nprobe: int):
+    """HBM-side bytes per launch of `kernel`, as measured by the rocprofv3 --pmc runs whose summary
+    is committed under profiles/ (FETCH_SIZE and WRITE_SIZE, scaled by a plain copy); None if that
+    summary does not cover this kernel and nprobe."""
+    path = os.path.join(ROOT, "profiles", f"{kernel}_1m_d128_nprobe{nprobe}_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        parts = line.split()
+        if len(parts) == 2 and parts[0] == "traffic_bytes":
+            return float(parts[1])
+    return None
+
+
 def recall(found, truth):
     hits = 0
     for f, t in zip(found, truth):
@@ -58,7 +72,7 @@ def cpu_baseline(w, X, Q, nprobe, full_cand_per_query):
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
         threads = 1
-    n_s, q_s = 100_000, 48
+    n_s, q_s = 500_000, 3000
     Xs = X[:n_s]
     cent, _ = orc.train_coarse(Xs[:20_000], w.nlist, 2, synth.kmeans_init_indices(w.seed, 20_000, w.nlist))
     Pi = orc.haar_rotation_from_gaussian(synth.gaussian_matrix(w.seed, w.d))
@@ -90,6 +104,8 @@ def main():
     ap.add_argument("--nprobe", type=int, default=32)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain 1 GiB device-to-device copy 5 times (reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only: this build has no multi-GPU path (run with --gpus 1)",
@@ -103,6 +119,14 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": 1 << 30, "copy_bytes_written": 1 << 30, "launches": 5}))
+        return
     w = synth.config_1m()
     t_setup = time.perf_counter()
     X = synth.database(w)
@@ -188,7 +212,7 @@ def main():
 
     scan_ms, assign_ms = avg_ms("list_scan"), avg_ms("coarse_assign")
     scan_roof = {"kernel": "list_scan", "bound": "hbm", "achieved": scan_bytes / (scan_ms * 1e-3) / 1e9,
-                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "traffic": None,
+                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "traffic": stored_traffic("list_scan", args.nprobe),
                  "algorithmic_bytes_per_launch": scan_bytes, "avg_launch_ms": scan_ms}
     scan_roof["frac"] = scan_roof["achieved"] / scan_roof["peak"]
     assign_roof = {"kernel": "coarse_assign", "bound": "mfma", "achieved": assign_flops / (assign_ms * 1e-3) / 1e12,
