@@ -45,6 +45,7 @@ _SIGNATURES = {
     "ivftq_export_list": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]),
     "ivftq_index_bytes": (C.c_int64, [C.c_void_p]),
     "ivftq_set_workspace_limit": (C.c_int, [C.c_void_p, C.c_int64]),
+    "ivftq_set_search_mode": (C.c_int, [C.c_void_p, C.c_int]),
     "ivftq_profile_enable": (C.c_int, [C.c_void_p, C.c_int]),
     "ivftq_profile_read": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
     "ivftq_profile_kernel_count": (C.c_int, []),
@@ -197,6 +198,9 @@ class Index:
         t = np.empty(max(K - 1, 1), np.float32)
         _check(self._lib.ivftq_get_codebook(self._h, _np_ptr(c), _np_ptr(t)))
         return c, t[:K - 1]
+
+    def set_search_mode(self, mode: int):
+        _check(self._lib.ivftq_set_search_mode(self._h, mode))
 
     def set_workspace_limit(self, nbytes: int):
         _check(self._lib.ivftq_set_workspace_limit(self._h, nbytes))

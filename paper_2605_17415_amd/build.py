@@ -12,7 +12,7 @@ LIB = os.path.join(HERE, "libivftq.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 
 SOURCES = ["host_math.cpp", "coarse_kernels.hip", "encode_kernels.hip", "list_kernels.hip",
-           "search_kernels.hip", "api.hip"]
+           "search_kernels.hip", "batch_kernels.hip", "api.hip"]
 
 # packed-fp32 instruction selection is switched off for every device compile
 DEVICE_FLAGS = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -60,11 +60,13 @@ struct DevBuf {
 
 // kernel classes for the optional per-launch timing
 enum ProfId { P_ASSIGN, P_COARSE_SCORES, P_ENCODE, P_ROTATE_Q, P_SEG_HIST, P_SEG_SCAN, P_RANK, P_PACK,
-              P_COPY_LISTS, P_SELECT_PROBE, P_CAND_OFF, P_LIST_SCAN, P_SELECT_TOPK, P_KMEANS_UPDATE, P_COUNT };
+              P_COPY_LISTS, P_SELECT_PROBE, P_CAND_OFF, P_LIST_SCAN, P_SELECT_TOPK, P_KMEANS_UPDATE,
+              P_PAIR_GROUP, P_BATCH_SCAN, P_MERGE, P_COUNT };
 const char* const kProfNames[P_COUNT] = {"coarse_assign", "coarse_scores", "encode_rotate_quantise_pack",
                                          "rotate_queries", "segment_hist", "segment_scan", "stable_rank",
                                          "pack_scatter", "copy_lists", "select_probes", "cand_offsets",
-                                         "list_scan", "select_topk", "kmeans_update"};
+                                         "list_scan", "select_topk", "kmeans_update", "pair_grouping",
+                                         "batch_scan", "merge_topk"};
 struct ProfRec { int id; hipEvent_t a, b; };
 
 uint64_t splitmix(uint64_t& s) {
@@ -92,6 +94,8 @@ struct ivftq_index {
     DevBuf w_assign, w_slot, w_hist, w_count, w_base, w_flag, w_best;
     DevBuf w_S, w_probe, w_coarse, w_z, w_candoff, w_scores;
     DevBuf w_sums, w_counts, w_zero, w_rows, w_dst, w_obj;
+    DevBuf w_first, w_fscores, w_fids, w_key, w_pairs, w_pairoff, w_tileoff, w_cscore, w_cslot, w_ccnt, w_gate;
+    int search_mode = 0;   // 0 auto, 1 streaming scan only, 2 batched scan whenever the shape allows
     int64_t ws_limit = (int64_t)4 << 30;
     bool prof_on = false;
     std::vector<ProfRec> prof;
@@ -110,7 +114,9 @@ struct ivftq_index {
         for (ProfRec& r : prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
         for (DevBuf* bfr : {&cent, &bias, &pi, &cb, &tau, &codes, &gamma, &ids, &d_off, &d_size, &w_assign,
                             &w_slot, &w_hist, &w_count, &w_base, &w_flag, &w_best, &w_S, &w_probe, &w_coarse,
-                            &w_z, &w_candoff, &w_scores, &w_sums, &w_counts, &w_zero, &w_rows, &w_dst, &w_obj})
+                            &w_z, &w_candoff, &w_scores, &w_sums, &w_counts, &w_zero, &w_rows, &w_dst, &w_obj,
+                            &w_first, &w_fscores, &w_fids, &w_key, &w_pairs, &w_pairoff, &w_tileoff, &w_cscore,
+                            &w_cslot, &w_ccnt, &w_gate})
             bfr->release();
     }
 };
@@ -331,6 +337,13 @@ ivftq_status ivftq_get_codebook(const ivftq_index* ix, float* centroids_out, flo
     if (check_index(ix)) return IVFTQ_INVALID_ARG;
     if (centroids_out) std::copy(ix->h_cb.begin(), ix->h_cb.end(), centroids_out);
     if (boundaries_out) std::copy(ix->h_tau.begin(), ix->h_tau.end(), boundaries_out);
+    return IVFTQ_OK;
+}
+
+ivftq_status ivftq_set_search_mode(ivftq_index* ix, int mode) {
+    if (check_index(ix)) return IVFTQ_INVALID_ARG;
+    if (mode < 0 || mode > 2) return fail(IVFTQ_INVALID_ARG, "search mode %d outside [0, 2]", mode);
+    ix->search_mode = mode;
     return IVFTQ_OK;
 }
 
@@ -718,12 +731,40 @@ ivftq_status ivftq_search(ivftq_index* ix, const float* q_dev, int64_t nq, int n
     int64_t qc = ix->ws_limit / (4 * std::max(m_stride, ldS));
     qc = std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(qc, nq), 32768));
 
+    // Scan strategy.  Streaming: one workgroup per (query, probed list), every score written, exact
+    // selection.  Batched: pairs regrouped by list and scanned on the matrix cores against a
+    // threshold from the streaming scan of each query's nearest lists; pays off when each list is
+    // probed by many queries of the batch.
+    const int tq = batch_tile_queries(ix->d, ix->b);
+    const bool batched = tq > 0 && nprobe > 1 &&
+                         (ix->search_mode == 2 || (ix->search_mode == 0 && qc * nprobe >= (int64_t)16 * ix->nlist));
+    const int cap = std::min(2048, std::max(512, 8 * k));
+
     HIP_TRY(ix->w_S.ensure((size_t)qc * ldS * sizeof(float)));
     HIP_TRY(ix->w_scores.ensure((size_t)qc * m_stride * sizeof(float)));
     HIP_TRY(ix->w_probe.ensure((size_t)qc * nprobe * sizeof(int32_t)));
     HIP_TRY(ix->w_coarse.ensure((size_t)qc * nprobe * sizeof(float)));
     HIP_TRY(ix->w_candoff.ensure((size_t)qc * (nprobe + 1) * sizeof(int32_t)));
     HIP_TRY(ix->w_z.ensure((size_t)qc * ix->dp * sizeof(float)));
+    const int64_t n_pairs = qc * nprobe;
+    const int64_t seg_len = round_up64((n_pairs + 1023) / 1024, 64);
+    const int nseg = (int)((n_pairs + seg_len - 1) / seg_len);
+    if (batched) {
+        HIP_TRY(ix->w_first.ensure((size_t)qc * sizeof(int32_t)));
+        HIP_TRY(ix->w_fscores.ensure((size_t)qc * k * sizeof(float)));
+        HIP_TRY(ix->w_fids.ensure((size_t)qc * k * sizeof(int64_t)));
+        HIP_TRY(ix->w_key.ensure((size_t)n_pairs * sizeof(int32_t)));
+        HIP_TRY(ix->w_pairs.ensure((size_t)n_pairs * sizeof(int32_t)));
+        HIP_TRY(ix->w_slot.ensure((size_t)n_pairs * sizeof(int64_t)));
+        HIP_TRY(ix->w_hist.ensure((size_t)nseg * ix->nlist * sizeof(uint32_t)));
+        HIP_TRY(ix->w_count.ensure((size_t)ix->nlist * sizeof(uint32_t)));
+        HIP_TRY(ix->w_pairoff.ensure((size_t)(ix->nlist + 1) * sizeof(int64_t)));
+        HIP_TRY(ix->w_tileoff.ensure((size_t)(ix->nlist + 1) * sizeof(int32_t)));
+        HIP_TRY(ix->w_cscore.ensure((size_t)qc * cap * sizeof(float)));
+        HIP_TRY(ix->w_cslot.ensure((size_t)qc * cap * sizeof(int64_t)));
+        HIP_TRY(ix->w_ccnt.ensure((size_t)qc * sizeof(int32_t)));
+        HIP_TRY(ix->w_gate.ensure((size_t)qc * sizeof(int32_t)));
+    }
 
     for (int64_t q0 = 0; q0 < nq; q0 += qc) {
         const int64_t cnt = std::min(qc, nq - q0);
@@ -734,19 +775,71 @@ ivftq_status ivftq_search(ivftq_index* ix, const float* q_dev, int64_t nq, int n
         ea.x = q; ea.n = cnt; ea.d = ix->d; ea.b = ix->b;
         ea.pi = ix->pi.as<float>(); ea.zout = ix->w_z.as<float>();
         HIP_TRY(timed(ix, st, P_ROTATE_Q, [&] { return launch_encode(2, ea, st); }));
-        HIP_TRY(timed(ix, st, P_CAND_OFF, [&] { return launch_cand_offsets(ix->w_probe.as<int32_t>(), cnt, nprobe, ix->d_size.as<int32_t>(),
-                                    ix->w_candoff.as<int32_t>(), st); }));
-        HIP_TRY(timed(ix, st, P_LIST_SCAN, [&] { return launch_list_scan(ix->w_z.as<float>(), ix->dp, ix->d, ix->b, ix->cb.as<float>(),
-                                 ix->w_probe.as<int32_t>(), ix->w_coarse.as<float>(),
-                                 ix->w_candoff.as<int32_t>(), nprobe, ix->store(), 0, cnt,
-                                 ix->w_scores.as<float>(), m_stride, st); }));
+        int32_t* first = batched ? ix->w_first.as<int32_t>() : nullptr;
+        HIP_TRY(timed(ix, st, P_CAND_OFF, [&] {
+            return launch_cand_offsets(ix->w_probe.as<int32_t>(), cnt, nprobe, ix->d_size.as<int32_t>(),
+                                       ix->w_candoff.as<int32_t>(), k, first, st); }));
+        auto stream_scan = [&](const int32_t* p_limit, const int32_t* gate, int blocks_per_query) {
+            return launch_list_scan(ix->w_z.as<float>(), ix->dp, ix->d, ix->b, ix->cb.as<float>(),
+                                    ix->w_probe.as<int32_t>(), ix->w_coarse.as<float>(),
+                                    ix->w_candoff.as<int32_t>(), nprobe, ix->store(), 0, cnt,
+                                    ix->w_scores.as<float>(), m_stride, p_limit, gate, blocks_per_query, st);
+        };
         SelectArgs sa{};
         sa.vals = ix->w_scores.as<float>(); sa.stride = m_stride; sa.rows = cnt; sa.k = k;
         sa.cand_off = ix->w_candoff.as<int32_t>(); sa.probe = ix->w_probe.as<int32_t>(); sa.np = nprobe;
         sa.q_begin = 0;
         sa.list_off = ix->d_off.as<int64_t>(); sa.ids = ix->ids.as<int64_t>();
         sa.out_vals = scores_dev + q0 * k; sa.out_i64 = ids_dev + q0 * k;
-        HIP_TRY(timed(ix, st, P_SELECT_TOPK, [&] { return launch_select(1, sa, st); }));
+
+        if (!batched) {
+            HIP_TRY(timed(ix, st, P_LIST_SCAN, [&] { return stream_scan(nullptr, nullptr, 0); }));
+            HIP_TRY(timed(ix, st, P_SELECT_TOPK, [&] { return launch_select(1, sa, st); }));
+            continue;
+        }
+
+        // 1. exact scan of each query's nearest lists: their top-k and, from it, the threshold
+        HIP_TRY(timed(ix, st, P_LIST_SCAN, [&] { return stream_scan(first, nullptr, 2); }));
+        SelectArgs s1 = sa;
+        s1.p_limit = first; s1.out_vals = ix->w_fscores.as<float>(); s1.out_i64 = ix->w_fids.as<int64_t>();
+        HIP_TRY(timed(ix, st, P_SELECT_TOPK, [&] { return launch_select(1, s1, st); }));
+        // 2. remaining (query, probe) pairs grouped by list, in a fixed order
+        const int64_t np_items = cnt * nprobe;
+        const int64_t sl = round_up64((np_items + 1023) / 1024, 64);
+        const int ns = (int)((np_items + sl - 1) / sl);
+        HIP_TRY(timed(ix, st, P_PAIR_GROUP, [&] {
+            hipError_t e = launch_pair_keys(ix->w_probe.as<int32_t>(), first, cnt, nprobe, ix->w_key.as<int32_t>(), st);
+            if (e == hipSuccess) e = launch_segment_hist(ix->w_key.as<int32_t>(), np_items, sl, ns, ix->nlist, ix->w_hist.as<uint32_t>(), st);
+            if (e == hipSuccess) e = launch_segment_scan(ix->w_hist.as<uint32_t>(), ns, ix->nlist, ix->w_count.as<uint32_t>(), st);
+            if (e == hipSuccess) e = launch_pair_prefix(ix->w_count.as<uint32_t>(), ix->nlist, tq, ix->w_pairoff.as<int64_t>(), ix->w_tileoff.as<int32_t>(), st);
+            if (e == hipSuccess) e = launch_stable_rank(ix->w_key.as<int32_t>(), np_items, sl, ns, ix->nlist, ix->w_hist.as<uint32_t>(), ix->w_pairoff.as<int64_t>(), ix->w_slot.as<int64_t>(), st);
+            if (e == hipSuccess) e = launch_scatter_pairs(ix->w_slot.as<int64_t>(), np_items, ix->w_pairs.as<int32_t>(), st);
+            if (e == hipSuccess) e = launch_fill_u32(ix->w_ccnt.as<uint32_t>(), cnt, 0u, st);
+            return e; }));
+        // 3. matrix-core scan of those pairs against the thresholds
+        BatchScanArgs ba{};
+        ba.z = ix->w_z.as<float>(); ba.z_pitch = ix->dp; ba.cb = ix->cb.as<float>();
+        ba.pairs = ix->w_pairs.as<int32_t>(); ba.pair_off = ix->w_pairoff.as<int64_t>();
+        ba.tile_off = ix->w_tileoff.as<int32_t>();
+        ba.coarse = ix->w_coarse.as<float>();
+        ba.thresh = ix->w_fscores.as<float>() + (k - 1); ba.thresh_stride = k;
+        ba.store = ix->store(); ba.np = nprobe; ba.L = ix->nlist;
+        ba.cand_score = ix->w_cscore.as<float>(); ba.cand_slot = ix->w_cslot.as<int64_t>();
+        ba.cand_cnt = ix->w_ccnt.as<int32_t>(); ba.cap = cap;
+        const int max_tiles = (int)(np_items / tq) + ix->nlist;
+        HIP_TRY(timed(ix, st, P_BATCH_SCAN, [&] { return launch_batch_scan(ba, ix->d, ix->b, max_tiles, st); }));
+        // 4. merge; a query whose candidate list overflowed is redone by the exact streaming scan
+        MergeArgs ma{};
+        ma.first_scores = ix->w_fscores.as<float>(); ma.first_ids = ix->w_fids.as<int64_t>();
+        ma.cand_score = ix->w_cscore.as<float>(); ma.cand_slot = ix->w_cslot.as<int64_t>();
+        ma.cand_cnt = ix->w_ccnt.as<int32_t>(); ma.cap = cap; ma.ids = ix->ids.as<int64_t>();
+        ma.k = k; ma.out_scores = scores_dev + q0 * k; ma.out_ids = ids_dev + q0 * k;
+        ma.gate = ix->w_gate.as<int32_t>();
+        HIP_TRY(timed(ix, st, P_MERGE, [&] { return launch_merge(ma, cnt, st); }));
+        HIP_TRY(timed(ix, st, P_LIST_SCAN, [&] { return stream_scan(nullptr, ix->w_gate.as<int32_t>(), 8); }));
+        SelectArgs s2 = sa;
+        s2.gate = ix->w_gate.as<int32_t>();
+        HIP_TRY(timed(ix, st, P_SELECT_TOPK, [&] { return launch_select(1, s2, st); }));
     }
     return IVFTQ_OK;
 }

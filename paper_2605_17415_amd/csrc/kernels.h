@@ -101,13 +101,17 @@ hipError_t launch_inertia(const float* best, int64_t n, double* out, hipStream_t
 // ---- search -----------------------------------------------------------------------------------
 
 // cand_off[q*(np+1) + p] = sum_{p'<p} list_size[probe[q][p']]
+// first (may be null): first[q] = shortest probe prefix (>= 1 cell) holding >= k vectors, else np
 hipError_t launch_cand_offsets(const int32_t* probe, int64_t nq, int np, const int32_t* list_size,
-                               int32_t* cand_off, hipStream_t st);
+                               int32_t* cand_off, int k, int32_t* first, hipStream_t st);
 // scores[qi*m_stride + cand_off[q][p] + i] = coarse[q][p] + gamma_i * sum_j z_qj * C[code_ij]
 hipError_t launch_list_scan(const float* z, int z_pitch, int d, int b, const float* cb,
                             const int32_t* probe, const float* coarse, const int32_t* cand_off,
                             int np, const ListStore& store, int64_t q_begin, int64_t q_count,
-                            float* scores, int64_t m_stride, hipStream_t st);
+                            float* scores, int64_t m_stride, const int32_t* p_limit, const int32_t* gate,
+                            int blocks_per_query, hipStream_t st);
+// p_limit (may be null): only probes p < p_limit[q] are scanned.  gate (may be null): only queries
+// with gate[q] != 0 are processed.  blocks_per_query: workgroups per query (0 = one per probe).
 
 // Per row: the k largest of m values, sorted by (value desc, label asc).
 // mode 0 (probe selection): m = m_fixed for every row, label = column; writes int32 labels.
@@ -117,9 +121,45 @@ struct SelectArgs {
     const float* vals; int64_t stride; int64_t rows; int k;
     int m_fixed;
     const int32_t* cand_off; const int32_t* probe; int np; int64_t q_begin;
+    const int32_t* p_limit;   // mode 1: row q only has the candidates of probes p < p_limit[q] (null = all)
+    const int32_t* gate;      // only rows with gate[q] != 0 are processed (null = all)
     const int64_t* list_off; const int64_t* ids;
     float* out_vals; int32_t* out_i32; int64_t* out_i64;
 };
 hipError_t launch_select(int mode, const SelectArgs& a, hipStream_t st);
+
+// ---- query-batched scan ------------------------------------------------------------------------
+
+// Queries one workgroup of the batched scan takes per tile for this (d, b); 0 = shape not covered
+// (the streaming scan is used instead).
+int batch_tile_queries(int d, int b);
+
+// key[q*np + p] = probed list, or -1 when p < first[q]
+hipError_t launch_pair_keys(const int32_t* probe, const int32_t* first, int64_t nq, int np, int32_t* key,
+                            hipStream_t st);
+// exclusive prefixes over lists of the pair counts and of ceil(count / tq); both arrays have L+1 entries
+hipError_t launch_pair_prefix(const uint32_t* count, int L, int tq, int64_t* pair_off, int32_t* tile_off,
+                              hipStream_t st);
+// pairs[slot[it]] = it for every item with slot >= 0
+hipError_t launch_scatter_pairs(const int64_t* slot, int64_t n, int32_t* pairs, hipStream_t st);
+
+struct BatchScanArgs {
+    const float* z; int z_pitch; const float* cb;
+    const int32_t* pairs; const int64_t* pair_off; const int32_t* tile_off;
+    const float* coarse;                 // [nq*np] coarse term of each (query, probe)
+    const float* thresh; int thresh_stride;   // threshold of query q at thresh[q*thresh_stride]
+    ListStore store; int np; int L;
+    float* cand_score; int64_t* cand_slot; int32_t* cand_cnt; int cap;
+};
+hipError_t launch_batch_scan(const BatchScanArgs& a, int d, int b, int max_tiles, hipStream_t st);
+
+struct MergeArgs {
+    const float* first_scores; const int64_t* first_ids;     // [nq][k] from the streaming pass
+    const float* cand_score; const int64_t* cand_slot; const int32_t* cand_cnt; int cap;
+    const int64_t* ids;                                       // labels by slot
+    int k; float* out_scores; int64_t* out_ids;
+    int32_t* gate;                                            // [nq] 1 when the candidate list overflowed
+};
+hipError_t launch_merge(const MergeArgs& a, int64_t nq, hipStream_t st);
 
 }  // namespace ivftq

@@ -11,16 +11,22 @@ namespace {
 
 // ---- candidate offsets -----------------------------------------------------------------------
 
+// Also, when asked: first[q] = the shortest prefix of the probe list (at least one cell) that holds
+// at least k vectors, or np when all probed cells together hold fewer.
 __global__ void k_cand_offsets(const int32_t* __restrict__ probe, int64_t nq, int np,
-                               const int32_t* __restrict__ list_size, int32_t* __restrict__ cand_off) {
+                               const int32_t* __restrict__ list_size, int32_t* __restrict__ cand_off,
+                               int k, int32_t* __restrict__ first) {
     const int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (q >= nq) return;
     int32_t run = 0;
+    int p1 = np;
     for (int p = 0; p < np; ++p) {
         cand_off[q * (np + 1) + p] = run;
         run += list_size[probe[q * np + p]];
+        if (p1 == np && run >= k) p1 = p + 1;
     }
     cand_off[q * (np + 1) + np] = run;
+    if (first) first[q] = p1;
 }
 
 // ---- list scan: one workgroup per (query, probed list) ---------------------------------------
@@ -38,15 +44,16 @@ __global__ __launch_bounds__(256) void k_list_scan(const float* __restrict__ z, 
                                                    const float* __restrict__ coarse,
                                                    const int32_t* __restrict__ cand_off, int np,
                                                    ListStore store, int64_t q_begin,
-                                                   float* __restrict__ scores, int64_t m_stride) {
+                                                   float* __restrict__ scores, int64_t m_stride,
+                                                   const int32_t* __restrict__ p_limit,
+                                                   const int32_t* __restrict__ gate) {
     constexpr int K = 1 << B;
     extern __shared__ float lut[];     // [d][K], or z[d] followed by C[K] when DIRECT
-    const int p = blockIdx.x;
     const int64_t qi = blockIdx.y;     // index inside this pass
     const int64_t q = q_begin + qi;
-    const int l = probe[q * np + p];
-    const int n_l = store.list_size[l];
-    if (n_l == 0) return;
+    if (gate && !gate[q]) return;      // only queries marked for this pass
+    const int p_end = p_limit ? p_limit[q] : np;
+    if ((int)blockIdx.x >= p_end) return;
 
     if constexpr (DIRECT) {
         for (int e = threadIdx.x; e < d; e += 256) lut[e] = z[q * z_pitch + e];
@@ -60,8 +67,11 @@ __global__ __launch_bounds__(256) void k_list_scan(const float* __restrict__ z, 
         else return lut[j * K + code];
     };
 
-    const float s_l = coarse[q * np + p];
     const int words = store.words;
+    for (int p = blockIdx.x; p < p_end; p += gridDim.x) {
+    const int l = probe[q * np + p];
+    const int n_l = store.list_size[l];
+    const float s_l = coarse[q * np + p];
     const int64_t base_slot = store.list_off[l];
     float* out = scores + qi * m_stride + cand_off[q * (np + 1) + p];
 
@@ -105,6 +115,7 @@ __global__ __launch_bounds__(256) void k_list_scan(const float* __restrict__ z, 
         const float g = __half2float(__ushort_as_half(store.gamma[slot]));
         out[v] = s_l + g * acc;
     }
+    }
 }
 
 // ---- selection: k largest of a row ------------------------------------------------------------
@@ -134,7 +145,9 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a) {
     const int64_t row = blockIdx.x;
     const float* vals = a.vals + row * a.stride;
     const int64_t q = a.q_begin + row;
-    const int m = (MODE == 0) ? a.m_fixed : a.cand_off[q * (a.np + 1) + a.np];
+    if (a.gate && !a.gate[q]) return;
+    const int m = (MODE == 0) ? a.m_fixed
+                              : a.cand_off[q * (a.np + 1) + (a.p_limit ? a.p_limit[q] : a.np)];
     const int k = a.k;
     const int take = m < k ? m : k;
 
@@ -259,30 +272,31 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a) {
 }  // namespace
 
 hipError_t launch_cand_offsets(const int32_t* probe, int64_t nq, int np, const int32_t* list_size,
-                               int32_t* cand_off, hipStream_t st) {
+                               int32_t* cand_off, int k, int32_t* first, hipStream_t st) {
     if (nq <= 0) return hipSuccess;
     hipLaunchKernelGGL(k_cand_offsets, dim3((unsigned)((nq + 127) / 128)), dim3(128), 0, st, probe, nq, np,
-                       list_size, cand_off);
+                       list_size, cand_off, k, first);
     return hipGetLastError();
 }
 
 hipError_t launch_list_scan(const float* z, int z_pitch, int d, int b, const float* cb,
                             const int32_t* probe, const float* coarse, const int32_t* cand_off,
                             int np, const ListStore& store, int64_t q_begin, int64_t q_count,
-                            float* scores, int64_t m_stride, hipStream_t st) {
+                            float* scores, int64_t m_stride, const int32_t* p_limit, const int32_t* gate,
+                            int blocks_per_query, hipStream_t st) {
     if (q_count <= 0) return hipSuccess;
     const size_t lut_bytes = (size_t)d * (1u << b) * sizeof(float);
     const bool direct = lut_bytes > 64 * 1024;
     const size_t lds = direct ? (size_t)(d + (1 << b)) * sizeof(float) : lut_bytes;
-    dim3 grid((unsigned)np, (unsigned)q_count);
+    dim3 grid((unsigned)(blocks_per_query > 0 ? blocks_per_query : np), (unsigned)q_count);
 #define IVFTQ_SCAN(BV)                                                                              \
     case BV:                                                                                        \
         if (direct)                                                                                 \
             hipLaunchKernelGGL((k_list_scan<BV, true>), grid, dim3(256), lds, st, z, z_pitch, d, cb, probe, \
-                               coarse, cand_off, np, store, q_begin, scores, m_stride);             \
+                               coarse, cand_off, np, store, q_begin, scores, m_stride, p_limit, gate); \
         else                                                                                        \
             hipLaunchKernelGGL((k_list_scan<BV, false>), grid, dim3(256), lds, st, z, z_pitch, d, cb, probe, \
-                               coarse, cand_off, np, store, q_begin, scores, m_stride);             \
+                               coarse, cand_off, np, store, q_begin, scores, m_stride, p_limit, gate); \
         break;
     switch (b) {
         IVFTQ_SCAN(1) IVFTQ_SCAN(2) IVFTQ_SCAN(3) IVFTQ_SCAN(4)

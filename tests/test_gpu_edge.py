@@ -131,6 +131,17 @@ def test_custom_labels_workspace_passes_and_determinism():
     s2, i2 = ix.search(q, cs.nprobe, cs.k)
     torch.cuda.synchronize()
     assert torch.equal(i1, i2) and torch.equal(s1, s2)
+    ix.set_search_mode(2)                                    # batched scan: same labels, scores to rounding
+    for limit in (1 << 20, 1 << 32):
+        ix.set_workspace_limit(limit)
+        s5, i5 = ix.search(q, cs.nprobe, cs.k)
+        s6, i6 = ix.search(q, cs.nprobe, cs.k)
+        torch.cuda.synchronize()
+        assert torch.equal(i5, i6) and torch.equal(s5, s6)   # deterministic despite atomics
+        assert (i5 == i1).float().mean() > 0.99
+        assert torch.allclose(s5, s1, rtol=1e-5, atol=1e-6)
+    ix.set_search_mode(1)
+    ix.set_workspace_limit(1 << 20)
     for _ in range(2):                                       # same inputs, same bits
         s3, i3 = ix.search(q, cs.nprobe, cs.k)
         torch.cuda.synchronize()

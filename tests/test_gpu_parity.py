@@ -60,14 +60,20 @@ def test_encode_matches_oracle(name):
     ix.close()
 
 
-@pytest.mark.parametrize("name", gpu_cases.ALL_CASES)
-def test_search_matches_oracle_on_the_same_codes(name):
+BATCHED_CASES = ["tiny", "d128", "d96_b2", "d96_b3", "d96_b4", "d200"]    # shapes the batched scan covers
+SEARCH_CASES = [(n, 1) for n in gpu_cases.ALL_CASES] + [(n, 2) for n in BATCHED_CASES]
+
+
+@pytest.mark.parametrize("name,mode", SEARCH_CASES)
+def test_search_matches_oracle_on_the_same_codes(name, mode):
+    """mode 1: streaming scan; mode 2: query-batched matrix-core scan."""
     cs = gpu_cases.get_case(name)
     enc = gpu_cases.oracle_encode(name)
     oidx = gpu_cases.oracle_index(name)
-    print(f"[case {name}] nq={len(cs.Q)} nprobe={cs.nprobe} k={cs.k}", flush=True)
+    print(f"[case {name}] mode={mode} nq={len(cs.Q)} nprobe={cs.nprobe} k={cs.k}", flush=True)
     dev = _dev()
     ix = _make_index(cs)
+    ix.set_search_mode(mode)
     ix.add_encoded(torch.from_numpy(enc["assign"]).to(dev), torch.from_numpy(enc["codes"]).to(dev),
                    torch.from_numpy(enc["gamma16"]).to(dev))
     for l in range(0, cs.nlist, max(1, cs.nlist // 7)):          # storage round trip
@@ -99,6 +105,44 @@ def test_search_matches_oracle_on_the_same_codes(name):
     print("search:", rep, flush=True)
     assert rep["probe_near_tie_excused"] <= max(1, len(cs.Q) // 20)
     ix.close()
+
+
+def test_batched_scan_overflow_falls_back_to_the_exact_scan():
+    """More candidates beat the nearest list's k-th score than the per-query candidate list holds:
+    the query must be redone by the streaming scan and still match the oracle."""
+    cs = gpu_cases.get_case("tiny")
+    dev = _dev()
+    K = 1 << cs.b
+    qn = orc.normalize_rows(cs.Q[:3])
+    S = qn @ cs.cent.astype(np.float64).T
+    z = qn @ cs.Pi.astype(np.float64).T
+    order = np.argsort(-S[0])
+    rng = np.random.default_rng(0)
+    assign, codes, gamma = [], [], []
+    # nearest cell of query 0: 20 vectors whose residual estimate is as negative as it can be
+    worst = np.where(z[0] > 0, 0, K - 1).astype(np.uint8)
+    for _ in range(20):
+        assign.append(order[0]); codes.append(worst); gamma.append(1.0)
+    # next cells: 300 vectors each with zero residual norm, so every score equals the coarse term
+    for l in order[1:8]:
+        for _ in range(300):
+            assign.append(l); codes.append(rng.integers(0, K, cs.d).astype(np.uint8)); gamma.append(0.0)
+    assign = np.array(assign, np.int32)
+    codes = np.stack(codes)
+    gamma = np.array(gamma, np.float16)
+    ref = orc.ListIndex(cs.cent, cs.Pi, cs.c, cs.tau)
+    ref.add_encoded(assign, np.arange(len(assign), dtype=np.int64), codes, gamma)
+    o_sc, o_ids, _, S_all, o_all = orc.search(ref, cs.Q[:3], 8, 10, return_all=True)
+    for mode in (1, 2):
+        ix = _make_index(cs)
+        ix.set_search_mode(mode)
+        ix.add_encoded(torch.from_numpy(assign).to(dev), torch.from_numpy(codes).to(dev), torch.from_numpy(gamma).to(dev))
+        sc, ids = ix.search(torch.from_numpy(cs.Q[:3]).to(dev), 8, 10)
+        torch.cuda.synchronize()
+        rep = parity.compare_search(sc.cpu().numpy(), ids.cpu().numpy(), o_sc, o_ids, o_all,
+                                    parity.probe_cut_gap(S_all, 8))
+        print(f"mode {mode}:", rep, flush=True)
+        ix.close()
 
 
 def test_end_to_end_recall_matches_oracle_pipeline():
