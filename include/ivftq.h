@@ -72,6 +72,9 @@ ivftq_status ivftq_haar_from_gaussian(int d, const double* g, float* pi_out);
  * rotation_seed.  Coarse centroids must be trained or set before encoding or searching. */
 ivftq_status ivftq_create(int d, int b, int nlist, uint64_t rotation_seed, ivftq_index** out);
 ivftq_status ivftq_destroy(ivftq_index* index);
+/* Remove every stored vector.  Constants, the capacity already reserved for the lists and the
+ * search workspace are kept, so the index can be filled again without allocating.  Synchronises. */
+ivftq_status ivftq_reset(ivftq_index* index);
 
 /* Coarse partition (Section "Architecture", Indexing): Lloyd k-means on the L2-normalised rows of
  * x_dev (device, n x d), `niter` iterations, nearest mean in Euclidean distance; the final

@@ -24,6 +24,7 @@ _SIGNATURES = {
     "ivftq_haar_from_gaussian": (C.c_int, [C.c_int, C.c_void_p, C.c_void_p]),
     "ivftq_create": (C.c_int, [C.c_int, C.c_int, C.c_int, C.c_uint64, C.POINTER(C.c_void_p)]),
     "ivftq_destroy": (C.c_int, [C.c_void_p]),
+    "ivftq_reset": (C.c_int, [C.c_void_p]),
     "ivftq_train_coarse": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_int, C.c_void_p, C.c_uint64,
                                      C.POINTER(C.c_double), C.c_void_p]),
     "ivftq_set_coarse": (C.c_int, [C.c_void_p, C.c_void_p]),
@@ -162,6 +163,9 @@ class Index:
         if getattr(self, "_h", None) is not None and self._h.value:
             self._lib.ivftq_destroy(self._h)
             self._h = C.c_void_p()
+
+    def reset(self):
+        _check(self._lib.ivftq_reset(self._h))
 
     def __del__(self):
         try:

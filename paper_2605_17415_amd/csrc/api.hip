@@ -9,6 +9,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <numeric>
 #include <string>
@@ -68,6 +69,9 @@ const char* const kProfNames[P_COUNT] = {"coarse_assign", "coarse_scores", "enco
                                          "list_scan", "select_topk", "kmeans_update", "pair_grouping",
                                          "batch_scan", "merge_topk"};
 struct ProfRec { int id; hipEvent_t a, b; };
+// Timing events are recycled process-wide: creating one per launch costs more than the launch.
+std::mutex g_event_mutex;
+std::vector<hipEvent_t> g_event_pool;
 
 uint64_t splitmix(uint64_t& s) {
     uint64_t z = (s += 0x9E3779B97F4A7C15ull);
@@ -128,9 +132,15 @@ template <class F>
 hipError_t timed(ivftq_index* ix, hipStream_t st, int id, F&& launch) {
     if (!ix->prof_on) return launch();
     ProfRec r{id, nullptr, nullptr};
-    hipError_t e = hipEventCreate(&r.a);
-    if (e == hipSuccess) e = hipEventCreate(&r.b);
-    if (e == hipSuccess) e = hipEventRecord(r.a, st);
+    hipError_t e = hipSuccess;
+    {
+        std::lock_guard<std::mutex> lock(g_event_mutex);
+        for (hipEvent_t* ev : {&r.a, &r.b}) {
+            if (!g_event_pool.empty()) { *ev = g_event_pool.back(); g_event_pool.pop_back(); }
+            else if ((e = hipEventCreate(ev)) != hipSuccess) return e;
+        }
+    }
+    e = hipEventRecord(r.a, st);
     if (e != hipSuccess) return e;
     e = launch();
     hipError_t e2 = hipEventRecord(r.b, st);
@@ -139,7 +149,8 @@ hipError_t timed(ivftq_index* ix, hipStream_t st, int id, F&& launch) {
 }
 
 void drop_profile(ivftq_index* ix) {
-    for (ProfRec& r : ix->prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+    std::lock_guard<std::mutex> lock(g_event_mutex);
+    for (ProfRec& r : ix->prof) { g_event_pool.push_back(r.a); g_event_pool.push_back(r.b); }
     ix->prof.clear();
 }
 
@@ -295,6 +306,15 @@ ivftq_status ivftq_destroy(ivftq_index* index) {
     if (!index) return IVFTQ_OK;
     (void)hipDeviceSynchronize();
     delete index;
+    return IVFTQ_OK;
+}
+
+ivftq_status ivftq_reset(ivftq_index* ix) {
+    if (check_index(ix)) return IVFTQ_INVALID_ARG;
+    HIP_TRY(hipDeviceSynchronize());
+    std::fill(ix->h_size.begin(), ix->h_size.end(), 0);
+    HIP_TRY(hipMemcpy(ix->d_size.p, ix->h_size.data(), ix->nlist * sizeof(int32_t), hipMemcpyHostToDevice));
+    ix->ntotal = 0;
     return IVFTQ_OK;
 }
 

@@ -113,6 +113,16 @@ def test_streaming_appends_equal_one_bulk_add_and_survive_growth():
     torch.cuda.synchronize()
     assert torch.equal(i1, i2) and torch.equal(s1, s2)
     assert bulk.index_bytes() == len(cs.X) * (4 * ((cs.b * cs.d + 31) // 32) + 2 + 8)
+    # emptying the index keeps its storage; filling it again gives the same index
+    stream.reset()
+    assert stream.ntotal() == 0 and all(stream.list_size(l) == 0 for l in range(cs.nlist))
+    s0, i0 = stream.search(q, cs.nprobe, cs.k)
+    torch.cuda.synchronize()
+    assert (i0 == -1).all()
+    stream.encode_add(x)
+    s3, i3 = stream.search(q, cs.nprobe, cs.k)
+    torch.cuda.synchronize()
+    assert torch.equal(i1, i3) and torch.equal(s1, s3)
     bulk.close()
     stream.close()
 
