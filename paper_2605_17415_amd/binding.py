@@ -12,7 +12,7 @@ import os
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libivftq.so")
+LIB_PATH = os.environ.get("IVFTQ_LIB") or os.path.join(_HERE, "libivftq.so")   # IVFTQ_LIB: load another build
 
 OK, INVALID_ARG, BAD_STATE, OOM, HIP_ERROR, ZERO_NORM, UNSUPPORTED = range(7)
 STATUS_NAMES = ["OK", "INVALID_ARG", "BAD_STATE", "OOM", "HIP_ERROR", "ZERO_NORM", "UNSUPPORTED"]

@@ -29,7 +29,7 @@ def _hipcc() -> str:
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ_DIR, os.path.splitext(src)[0] + ".o")
     path = os.path.join(CSRC, src)
-    cmd = [_hipcc(), *COMMON, "-c", path, "-o", obj]
+    cmd = [_hipcc(), *COMMON, *os.environ.get("IVFTQ_EXTRA_FLAGS", "").split(), "-c", path, "-o", obj]
     if src.endswith(".hip"):
         cmd[1:1] = DEVICE_FLAGS
     else:
@@ -40,12 +40,12 @@ def _compile(src: str) -> str:
     return obj
 
 
-def build_library(verbose: bool = True) -> str:
-    """Compile every source and link libivftq.so; always rebuilds."""
+def build_library(verbose: bool = True, out: str | None = None) -> str:
+    """Compile every source and link libivftq.so (or `out`); always rebuilds."""
     os.makedirs(OBJ_DIR, exist_ok=True)
     with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as pool:
         objs = list(pool.map(_compile, SOURCES))
-    cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
+    cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", out or LIB, *objs]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError(f"linking libivftq.so failed:\n{res.stdout}\n{res.stderr}")

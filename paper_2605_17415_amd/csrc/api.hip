@@ -98,6 +98,7 @@ struct ivftq_index {
     DevBuf w_assign, w_slot, w_hist, w_count, w_base, w_flag, w_best;
     DevBuf w_S, w_probe, w_coarse, w_z, w_candoff, w_scores;
     DevBuf w_sums, w_counts, w_zero, w_rows, w_dst, w_obj;
+    DevBuf w_zh, w_zl;
     DevBuf w_first, w_fscores, w_fids, w_key, w_pairs, w_pairoff, w_tileoff, w_cscore, w_cslot, w_ccnt, w_gate;
     int search_mode = 0;   // 0 auto, 1 streaming scan only, 2 batched scan whenever the shape allows
     int64_t ws_limit = (int64_t)4 << 30;
@@ -120,7 +121,7 @@ struct ivftq_index {
                             &w_slot, &w_hist, &w_count, &w_base, &w_flag, &w_best, &w_S, &w_probe, &w_coarse,
                             &w_z, &w_candoff, &w_scores, &w_sums, &w_counts, &w_zero, &w_rows, &w_dst, &w_obj,
                             &w_first, &w_fscores, &w_fids, &w_key, &w_pairs, &w_pairoff, &w_tileoff, &w_cscore,
-                            &w_cslot, &w_ccnt, &w_gate})
+                            &w_cslot, &w_ccnt, &w_gate, &w_zh, &w_zl})
             bfr->release();
     }
 };
@@ -770,6 +771,8 @@ ivftq_status ivftq_search(ivftq_index* ix, const float* q_dev, int64_t nq, int n
     const int64_t seg_len = round_up64((n_pairs + 1023) / 1024, 64);
     const int nseg = (int)((n_pairs + seg_len - 1) / seg_len);
     if (batched) {
+        HIP_TRY(ix->w_zh.ensure((size_t)qc * ix->dp * sizeof(uint16_t)));
+        HIP_TRY(ix->w_zl.ensure((size_t)qc * ix->dp * sizeof(uint16_t)));
         HIP_TRY(ix->w_first.ensure((size_t)qc * sizeof(int32_t)));
         HIP_TRY(ix->w_fscores.ensure((size_t)qc * k * sizeof(float)));
         HIP_TRY(ix->w_fids.ensure((size_t)qc * k * sizeof(int64_t)));
@@ -794,6 +797,7 @@ ivftq_status ivftq_search(ivftq_index* ix, const float* q_dev, int64_t nq, int n
         EncodeArgs ea{};
         ea.x = q; ea.n = cnt; ea.d = ix->d; ea.b = ix->b;
         ea.pi = ix->pi.as<float>(); ea.zout = ix->w_z.as<float>();
+        if (batched) { ea.zh_out = ix->w_zh.as<uint16_t>(); ea.zl_out = ix->w_zl.as<uint16_t>(); }
         HIP_TRY(timed(ix, st, P_ROTATE_Q, [&] { return launch_encode(2, ea, st); }));
         int32_t* first = batched ? ix->w_first.as<int32_t>() : nullptr;
         HIP_TRY(timed(ix, st, P_CAND_OFF, [&] {
@@ -838,7 +842,8 @@ ivftq_status ivftq_search(ivftq_index* ix, const float* q_dev, int64_t nq, int n
             return e; }));
         // 3. matrix-core scan of those pairs against the thresholds
         BatchScanArgs ba{};
-        ba.z = ix->w_z.as<float>(); ba.z_pitch = ix->dp; ba.cb = ix->cb.as<float>();
+        ba.zh = ix->w_zh.as<uint16_t>(); ba.zl = ix->w_zl.as<uint16_t>(); ba.z_pitch = ix->dp;
+        ba.cb = ix->cb.as<float>();
         ba.pairs = ix->w_pairs.as<int32_t>(); ba.pair_off = ix->w_pairoff.as<int64_t>();
         ba.tile_off = ix->w_tileoff.as<int32_t>();
         ba.coarse = ix->w_coarse.as<float>();

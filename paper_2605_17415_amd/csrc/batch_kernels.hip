@@ -6,8 +6,8 @@
 // [vectors of the list] x [d] times [d] x [queries probing the list].  The (query, probe) pairs are
 // regrouped by list, and one workgroup takes one list and up to 32*NQ of its queries: the de-quantised
 // codes of 32 vectors are the left MFMA operand (held in registers and reused for every query tile),
-// the rotated queries are the right operand (a panel in LDS), fp32 in, fp32 accumulate, so the
-// estimate keeps float32 accuracy.  In the 32x32 result a lane holds one query's scores against 16
+// the rotated queries are the right operand (a panel in LDS); operands are split float16 pairs and
+// accumulation is float32, so the estimate keeps float32 accuracy (see below).  In the 32x32 result a lane holds one query's scores against 16
 // vectors; it adds the coarse term, scales by the stored norm and keeps only scores that reach the
 // query's threshold (the k-th best score of its nearest lists, found beforehand by the exact
 // streaming scan), appending them to a short per-query candidate list.
@@ -18,6 +18,7 @@
 namespace ivftq {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 
 namespace {
 
@@ -77,33 +78,40 @@ __global__ void k_scatter_pairs(const int64_t* __restrict__ slot, int64_t n, int
 }
 
 // ---- the batched scan ----------------------------------------------------------------------------
-
-template <int DP, int NQ>
-struct BatchCfg {
-    static constexpr int TQ = NQ * 32;
-    static constexpr int LDP = DP + 1;
-    static constexpr size_t lds_bytes = ((size_t)TQ * LDP + 3 * TQ + 256) * sizeof(float);
-};
-
-// Code of coordinate j from the packed words of one vector (coordinate j occupies bits [j*B, j*B+B)).
-template <int B, int W>
-__device__ __forceinline__ uint32_t code_at(const uint32_t (&w)[W], int j) {
-    const int bit = j * B, wi = bit >> 5, sh = bit & 31;
-    uint32_t v = w[wi] >> sh;
-    if (sh + B > 32 && wi + 1 < W) v |= w[wi + 1] << (32 - sh);
-    return v & ((1u << B) - 1u);
-}
+//
+// Arithmetic: both operands are used in split float16 form, 1024*v = hi + lo with hi = fp16(1024 v)
+// and lo = fp16(1024 v - hi), and the product is accumulated as hi*hi + hi*lo + lo*hi on
+// v_mfma_f32_32x32x16_f16 with float32 accumulation (the lo*lo term, below 2^-24 relative, is
+// dropped).  Each part carries 11 significant bits, so the result matches a float32 contraction to
+// about 2e-7 relative while running on the float16 matrix pipe; the 2^-20 of the two scale factors
+// is folded into the stored norm.
+//
+// v_mfma_f32_32x32x16_f16: A is 32x16 (lane = i + 32*(k/8), element k%8), B is 16x32 likewise,
+// D as for the 32x32 float32 form: D[i][j] in lane j + 32*((i/4)%2), register (i%4) + 4*(i/8).
 
 template <int DP, int B, int NQ>
-__global__ __launch_bounds__(256, 2) void k_batch_scan(BatchScanArgs a) {
-    using Cfg = BatchCfg<DP, NQ>;
-    constexpr int W = (B * DP + 31) / 32;        // words that can hold DP coordinates
-    extern __shared__ float lds[];
-    float* zp = lds;                              // [TQ][LDP] rotated queries of this tile
-    float* s_coarse = zp + Cfg::TQ * Cfg::LDP;    // [TQ] coarse term of each (query, this list)
-    float* s_thr = s_coarse + Cfg::TQ;            // [TQ] threshold of each query
-    int32_t* s_q = reinterpret_cast<int32_t*>(s_thr + Cfg::TQ);   // [TQ] query number
-    float* s_cb = reinterpret_cast<float*>(s_q + Cfg::TQ);        // [256] codebook
+struct BatchCfg {
+    static constexpr int TQ = NQ * 32;
+    static constexpr int LDH = DP + 8;            // halves per panel row: 16-byte pad keeps b128 reads conflict free
+    static constexpr int PT = 1 << (2 * B);       // entries of the code-pair tables
+    static constexpr size_t lds_bytes = (size_t)TQ * LDH * 2 * sizeof(uint16_t) + 3 * TQ * sizeof(float) + 2 * PT * 4;
+};
+
+// WAVES = wavefronts per workgroup, OCC = wavefronts per SIMD the register budget is set for.
+template <int DP, int B, int NQ, int WAVES, int OCC>
+__global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(OCC)))
+void k_batch_scan(BatchScanArgs a) {
+    using Cfg = BatchCfg<DP, B, NQ>;
+    constexpr int KB = DP / 16;                   // 16-coordinate blocks
+    constexpr int NT = WAVES * 64;
+    extern __shared__ unsigned char lds_raw[];
+    uint16_t* zh = reinterpret_cast<uint16_t*>(lds_raw);          // [TQ][LDH] hi parts of the rotated queries
+    uint16_t* zl = zh + Cfg::TQ * Cfg::LDH;                         // [TQ][LDH] lo parts
+    float* s_coarse = reinterpret_cast<float*>(zl + Cfg::TQ * Cfg::LDH);   // [TQ]
+    float* s_thr = s_coarse + Cfg::TQ;                              // [TQ]
+    int32_t* s_q = reinterpret_cast<int32_t*>(s_thr + Cfg::TQ);     // [TQ]
+    uint32_t* tab_h = reinterpret_cast<uint32_t*>(s_q + Cfg::TQ);   // [PT] hi parts of a code pair, packed
+    uint32_t* tab_l = tab_h + Cfg::PT;                              // [PT] lo parts
 
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63, half = lane >> 5, jl = lane & 31;
@@ -111,12 +119,12 @@ __global__ __launch_bounds__(256, 2) void k_batch_scan(BatchScanArgs a) {
     // which (list, query tile) this workgroup owns
     const int total_tiles = a.tile_off[a.L];
     if ((int)blockIdx.x >= total_tiles) return;
-    int lo = 0, hi = a.L;                         // largest l with tile_off[l] <= blockIdx.x
-    while (hi - lo > 1) {
-        const int mid = (lo + hi) >> 1;
-        if (a.tile_off[mid] <= (int)blockIdx.x) lo = mid; else hi = mid;
+    int lo_l = 0, hi_l = a.L;                     // largest l with tile_off[l] <= blockIdx.x
+    while (hi_l - lo_l > 1) {
+        const int mid = (lo_l + hi_l) >> 1;
+        if (a.tile_off[mid] <= (int)blockIdx.x) lo_l = mid; else hi_l = mid;
     }
-    const int l = lo;
+    const int l = lo_l;
     const int tile = blockIdx.x - a.tile_off[l];
     const int64_t pair0 = a.pair_off[l] + (int64_t)tile * Cfg::TQ;
     const int64_t pair_end = a.pair_off[l + 1];
@@ -124,8 +132,8 @@ __global__ __launch_bounds__(256, 2) void k_batch_scan(BatchScanArgs a) {
     const int n_l = a.store.list_size[l];
     if (n_l == 0 || nq_tile <= 0) return;
 
-    // stage the query panel
-    for (int e = tid; e < Cfg::TQ; e += 256) {
+    // stage the query panel and the code-pair tables
+    for (int e = tid; e < Cfg::TQ; e += NT) {
         int32_t q = -1;
         float sc = 0.f, th = __builtin_inff();
         if (e < nq_tile) {
@@ -138,15 +146,30 @@ __global__ __launch_bounds__(256, 2) void k_batch_scan(BatchScanArgs a) {
         s_coarse[e] = sc;
         s_thr[e] = th;
     }
-    if (tid < (1 << B)) s_cb[tid] = a.cb[tid];
+    for (int e = tid; e < Cfg::PT; e += NT) {
+        uint32_t hp = 0, lp = 0;
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const float V = a.cb[(e >> (t * B)) & ((1 << B) - 1)] * kSplitScale;
+            const _Float16 hi = (_Float16)V;
+            const _Float16 lo = (_Float16)(V - (float)hi);
+            hp |= (uint32_t)__builtin_bit_cast(uint16_t, hi) << (16 * t);
+            lp |= (uint32_t)__builtin_bit_cast(uint16_t, lo) << (16 * t);
+        }
+        tab_h[e] = hp;
+        tab_l[e] = lp;
+    }
     __syncthreads();
-    for (int e = tid; e < Cfg::TQ * (DP / 4); e += 256) {
-        const int r = e / (DP / 4), c4 = e % (DP / 4);
-        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int e = tid; e < Cfg::TQ * (DP / 8); e += NT) {           // 16-byte pieces
+        const int r = e / (DP / 8), c8 = e % (DP / 8);
+        uint4 vh = make_uint4(0, 0, 0, 0), vl = make_uint4(0, 0, 0, 0);
         const int32_t q = s_q[r];
-        if (q >= 0) v = *reinterpret_cast<const float4*>(a.z + (int64_t)q * a.z_pitch + c4 * 4);
-        float* dst = zp + r * Cfg::LDP + c4 * 4;
-        dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
+        if (q >= 0) {
+            vh = *reinterpret_cast<const uint4*>(a.zh + (int64_t)q * a.z_pitch + c8 * 8);
+            vl = *reinterpret_cast<const uint4*>(a.zl + (int64_t)q * a.z_pitch + c8 * 8);
+        }
+        *reinterpret_cast<uint4*>(zh + r * Cfg::LDH + c8 * 8) = vh;
+        *reinterpret_cast<uint4*>(zl + r * Cfg::LDH + c8 * 8) = vl;
     }
     __syncthreads();
 
@@ -154,53 +177,109 @@ __global__ __launch_bounds__(256, 2) void k_batch_scan(BatchScanArgs a) {
     const int64_t base_slot = a.store.list_off[l];
     const int nslab = (n_l + 31) / 32;
     const int n_qt = (nq_tile + 31) / 32;
-    const float* b_base = zp + jl * Cfg::LDP + half;
+    const uint16_t* bh_base = zh + jl * Cfg::LDH + 8 * half;
+    const uint16_t* bl_base = zl + jl * Cfg::LDH + 8 * half;
+    constexpr float kUnscale = 1.f / (kSplitScale * kSplitScale);
 
-    for (int slab = wave; slab < nslab; slab += 4) {
-        // de-quantise 32 vectors: this lane takes vector jl, coordinates of parity `half`
-        const int v_mine = slab * 32 + jl;
+    // Raw words and norms of a slab are fetched one slab ahead so that their latency hides behind
+    // the matrix work of the current slab.
+    constexpr int NW = (B == 3) ? 2 : 1;           // 24-bit chunks may straddle two words
+    auto fetch = [&](int slab, uint32_t (&w)[KB][NW], uint32_t (&gp)[8]) {
+        const int v_mine = slab * 32 + jl;         // this lane de-quantises vector jl of the slab
         const int64_t slot = base_slot + (v_mine < n_l ? v_mine : n_l - 1);
         const uint32_t* wp = a.store.codes + (slot >> 6) * words * 64 + (slot & 63);
-        uint32_t wv[W];
 #pragma unroll
-        for (int w = 0; w < W; ++w) wv[w] = (w < words) ? wp[(int64_t)w * 64] : 0u;
-        float av[DP / 2];
+        for (int kb = 0; kb < KB; ++kb) {
+            const int wi = ((16 * kb + 8 * half) * B) >> 5;
 #pragma unroll
-        for (int s = 0; s < DP / 2; ++s) {
-            const uint32_t c0 = code_at<B, W>(wv, 2 * s), c1 = code_at<B, W>(wv, 2 * s + 1);
-            av[s] = s_cb[half ? c1 : c0];
+            for (int e = 0; e < NW; ++e) w[kb][e] = (wi + e < words) ? wp[(int64_t)(wi + e) * 64] : 0u;
         }
-        // norms of the 16 rows this lane sees in the result
-        float g[16];
+#pragma unroll
+        for (int r = 0; r < 16; r += 2) {          // float16 norms of the lane's 16 result rows, in pairs
+            const int v = slab * 32 + 8 * (r / 4) + 4 * half + (r % 4);      // even: the pair is 4-byte aligned
+            uint32_t pr = 0x7E007E00u;                                       // two float16 NaNs
+            if (v + 1 < n_l) pr = *reinterpret_cast<const uint32_t*>(a.store.gamma + base_slot + v);
+            else if (v < n_l) pr = (uint32_t)a.store.gamma[base_slot + v] | 0x7E000000u;
+            gp[r / 2] = pr;
+        }
+    };
+
+    uint32_t cw[KB][NW], cg[8], nw[KB][NW], ng[8];
+    int slab = wave;
+    if (slab < nslab) fetch(slab, cw, cg);
+    while (slab < nslab) {
+        const int next = slab + WAVES;
+        if (next < nslab) fetch(next, nw, ng);
+
+        // de-quantise: coordinates 16*kb + 8*half + [0, 8) of vector jl, two codes per table look-up
+        half8 ah[KB], al[KB];
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb) {
+            const int sh = ((16 * kb + 8 * half) * B) & 31;
+            uint32_t chunk = cw[kb][0] >> sh;
+            if (NW == 2) chunk = (uint32_t)((((uint64_t)cw[kb][NW - 1] << 32) | cw[kb][0]) >> sh);
+            uint32_t hv[4], lv[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const uint32_t idx = (chunk >> (2 * B * t)) & (uint32_t)(Cfg::PT - 1);
+                hv[t] = tab_h[idx];
+                lv[t] = tab_l[idx];
+            }
+            ah[kb] = __builtin_bit_cast(half8, make_uint4(hv[0], hv[1], hv[2], hv[3]));
+            al[kb] = __builtin_bit_cast(half8, make_uint4(lv[0], lv[1], lv[2], lv[3]));
+        }
+        float g[16];                               // 2^-20 * norm per result row (NaN beyond the list)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            const int v = slab * 32 + 8 * (r / 4) + 4 * half + (r % 4);
-            g[r] = (v < n_l) ? __half2float(__ushort_as_half(a.store.gamma[base_slot + v])) : __builtin_nanf("");
+            const uint32_t pr = cg[r / 2];
+            g[r] = kUnscale * __half2float(__ushort_as_half((uint16_t)((r & 1) ? (pr >> 16) : (pr & 0xFFFFu))));
         }
+
         for (int qt = 0; qt < n_qt; ++qt) {
             floatx16 acc;
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-            const float* bq = b_base + qt * 32 * Cfg::LDP;
+            const uint16_t* bhq = bh_base + qt * 32 * Cfg::LDH;
+            const uint16_t* blq = bl_base + qt * 32 * Cfg::LDH;
 #pragma unroll
-            for (int s = 0; s < DP / 2; ++s)
-                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av[s], bq[2 * s], acc, 0, 0, 0);
+            for (int kb = 0; kb < KB; ++kb) {
+                const half8 bh = *reinterpret_cast<const half8*>(bhq + 16 * kb);
+                const half8 bl = *reinterpret_cast<const half8*>(blq + 16 * kb);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah[kb], bh, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah[kb], bl, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(al[kb], bh, acc, 0, 0, 0);
+            }
             const int e = qt * 32 + jl;
             const float sq = s_coarse[e], th = s_thr[e];
             const int32_t q = s_q[e];
+            float sc[16];
+            float best = -__builtin_inff();
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const float sc = fmaf(g[r], acc[r], sq);        // NaN (row beyond the list) fails the test
-                if (sc >= th && q >= 0) {
-                    const int v = slab * 32 + 8 * (r / 4) + 4 * half + (r % 4);
-                    const int pos = atomicAdd(&a.cand_cnt[q], 1);
-                    if (pos < a.cap) {
-                        a.cand_score[(int64_t)q * a.cap + pos] = sc;
-                        a.cand_slot[(int64_t)q * a.cap + pos] = base_slot + v;
+                sc[r] = fmaf(g[r], acc[r], sq);    // NaN (row beyond the list) never passes
+                best = fmaxf(best, sc[r]);         // fmaxf ignores NaN
+            }
+            if (best >= th && q >= 0) {            // rare: some row of this lane reaches the threshold
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    if (sc[r] >= th) {
+                        const int v = slab * 32 + 8 * (r / 4) + 4 * half + (r % 4);
+                        const int pos = atomicAdd(&a.cand_cnt[q], 1);
+                        if (pos < a.cap) {
+                            a.cand_score[(int64_t)q * a.cap + pos] = sc[r];
+                            a.cand_slot[(int64_t)q * a.cap + pos] = base_slot + v;
+                        }
                     }
                 }
             }
         }
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+            for (int e = 0; e < NW; ++e) cw[kb][e] = nw[kb][e];
+#pragma unroll
+        for (int r = 0; r < 8; ++r) cg[r] = ng[r];
+        slab = next;
     }
 }
 
@@ -266,17 +345,17 @@ __global__ __launch_bounds__(256) void k_merge(MergeArgs a) {
     }
 }
 
-template <int DP, int B, int NQ>
+template <int DP, int B, int NQ, int WAVES, int OCC>
 hipError_t run_batch(const BatchScanArgs& a, int max_tiles, hipStream_t st) {
     static bool attr_set = false;
-    const size_t lds = BatchCfg<DP, NQ>::lds_bytes;
+    const size_t lds = BatchCfg<DP, B, NQ>::lds_bytes;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_batch_scan<DP, B, NQ>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_batch_scan<DP, B, NQ, WAVES, OCC>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((k_batch_scan<DP, B, NQ>), dim3((unsigned)max_tiles), dim3(256), lds, st, a);
+    hipLaunchKernelGGL((k_batch_scan<DP, B, NQ, WAVES, OCC>), dim3((unsigned)max_tiles), dim3(WAVES * 64), lds, st, a);
     return hipGetLastError();
 }
 
@@ -311,13 +390,20 @@ hipError_t launch_scatter_pairs(const int64_t* slot, int64_t n, int32_t* pairs, 
 hipError_t launch_batch_scan(const BatchScanArgs& a, int d, int b, int max_tiles, hipStream_t st) {
     if (max_tiles <= 0) return hipSuccess;
     const int dp = rot_dp(d);
-#define IVFTQ_BATCH(DPV, NQV)                                              \
-    if (dp == DPV) {                                                       \
-        if (b == 2) return run_batch<DPV, 2, NQV>(a, max_tiles, st);       \
-        if (b == 3) return run_batch<DPV, 3, NQV>(a, max_tiles, st);       \
-        if (b == 4) return run_batch<DPV, 4, NQV>(a, max_tiles, st);       \
+#ifndef IVFTQ_BATCH_WAVES
+#define IVFTQ_BATCH_WAVES 8
+#endif
+#ifndef IVFTQ_BATCH_OCC
+#define IVFTQ_BATCH_OCC 2
+#endif
+#define IVFTQ_BATCH(DPV, NQV, OCCV)                                                            \
+    if (dp == DPV) {                                                                           \
+        if (b == 2) return run_batch<DPV, 2, NQV, IVFTQ_BATCH_WAVES, OCCV>(a, max_tiles, st);  \
+        if (b == 3) return run_batch<DPV, 3, NQV, IVFTQ_BATCH_WAVES, OCCV>(a, max_tiles, st);  \
+        if (b == 4) return run_batch<DPV, 4, NQV, IVFTQ_BATCH_WAVES, OCCV>(a, max_tiles, st);  \
     }
-    IVFTQ_BATCH(64, 4) IVFTQ_BATCH(96, 4) IVFTQ_BATCH(128, 4) IVFTQ_BATCH(224, 2)
+    IVFTQ_BATCH(64, 4, IVFTQ_BATCH_OCC) IVFTQ_BATCH(96, 4, IVFTQ_BATCH_OCC)
+    IVFTQ_BATCH(128, 4, IVFTQ_BATCH_OCC) IVFTQ_BATCH(224, 2, 2)
 #undef IVFTQ_BATCH
     return hipErrorInvalidValue;
 }

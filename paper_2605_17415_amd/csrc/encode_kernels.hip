@@ -129,7 +129,22 @@ __global__ __launch_bounds__(256, 2) void k_encode(int mode, EncodeArgs a, int v
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
                     float4 o = make_float4(acc[4 * g], acc[4 * g + 1], acc[4 * g + 2], acc[4 * g + 3]);
-                    *reinterpret_cast<float4*>(a.zout + row * (int64_t)DP + t * 32 + 8 * g + 4 * half) = o;
+                    const int64_t at = row * (int64_t)DP + t * 32 + 8 * g + 4 * half;
+                    *reinterpret_cast<float4*>(a.zout + at) = o;
+                    if (a.zh_out) {
+                        const float v[4] = {o.x, o.y, o.z, o.w};
+                        uint16_t h[4], l[4];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const float V = v[e] * kSplitScale;
+                            const _Float16 hi = (_Float16)V;
+                            const _Float16 lo = (_Float16)(V - (float)hi);
+                            h[e] = __builtin_bit_cast(uint16_t, hi);
+                            l[e] = __builtin_bit_cast(uint16_t, lo);
+                        }
+                        *reinterpret_cast<uint2*>(a.zh_out + at) = make_uint2(h[0] | ((uint32_t)h[1] << 16), h[2] | ((uint32_t)h[3] << 16));
+                        *reinterpret_cast<uint2*>(a.zl_out + at) = make_uint2(l[0] | ((uint32_t)l[1] << 16), l[2] | ((uint32_t)l[3] << 16));
+                    }
                 }
             }
         }

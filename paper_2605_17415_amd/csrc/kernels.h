@@ -60,7 +60,13 @@ struct EncodeArgs {
     uint8_t* codes_flat; uint16_t* gamma_flat;
     // mode 2
     float* zout;
+    uint16_t* zh_out; uint16_t* zl_out;   // optional: split float16 form of 1024*z (see split_scaled)
 };
+
+// Split float16 form used by the float16 matrix-core kernels: V = 1024*v, hi = fp16(V),
+// lo = fp16(V - hi).  hi + lo equals V to about 2^-22 relative; the factor keeps lo in the normal
+// float16 range for every |v| > 2.4e-4 (below that lo is at most 6e-8 of v's scale).
+constexpr float kSplitScale = 1024.f;
 hipError_t launch_encode(int mode, const EncodeArgs& a, hipStream_t st);
 
 // ---- list bookkeeping -------------------------------------------------------------------------
@@ -144,7 +150,8 @@ hipError_t launch_pair_prefix(const uint32_t* count, int L, int tq, int64_t* pai
 hipError_t launch_scatter_pairs(const int64_t* slot, int64_t n, int32_t* pairs, hipStream_t st);
 
 struct BatchScanArgs {
-    const float* z; int z_pitch; const float* cb;
+    const uint16_t* zh; const uint16_t* zl; int z_pitch;   // split rotated queries, [nq][z_pitch] halves
+    const float* cb;
     const int32_t* pairs; const int64_t* pair_off; const int32_t* tile_off;
     const float* coarse;                 // [nq*np] coarse term of each (query, probe)
     const float* thresh; int thresh_stride;   // threshold of query q at thresh[q*thresh_stride]
