@@ -87,7 +87,7 @@ struct ivftq_index {
     bool has_coarse = false;
     std::vector<float> h_cent, h_pi, h_cb, h_tau;
     // device constants
-    DevBuf cent, bias, pi, cb, tau;
+    DevBuf cent, cent_h, cent_l, bias, pi, cb, tau;   // cent_h/cent_l: split float16 form of cent
     // list storage
     DevBuf codes, gamma, ids, d_off, d_size;
     std::vector<int64_t> h_off, h_cap;
@@ -117,7 +117,7 @@ struct ivftq_index {
     }
     ~ivftq_index() {
         for (ProfRec& r : prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
-        for (DevBuf* bfr : {&cent, &bias, &pi, &cb, &tau, &codes, &gamma, &ids, &d_off, &d_size, &w_assign,
+        for (DevBuf* bfr : {&cent, &cent_h, &cent_l, &bias, &pi, &cb, &tau, &codes, &gamma, &ids, &d_off, &d_size, &w_assign,
                             &w_slot, &w_hist, &w_count, &w_base, &w_flag, &w_best, &w_S, &w_probe, &w_coarse,
                             &w_z, &w_candoff, &w_scores, &w_sums, &w_counts, &w_zero, &w_rows, &w_dst, &w_obj,
                             &w_first, &w_fscores, &w_fids, &w_key, &w_pairs, &w_pairoff, &w_tileoff, &w_cscore,
@@ -155,6 +155,12 @@ void drop_profile(ivftq_index* ix) {
     ix->prof.clear();
 }
 
+// The coarse kernel reads the centroid table in split float16 form; call after every change of it.
+hipError_t refresh_split(ivftq_index* ix, hipStream_t st) {
+    return launch_split_rows(ix->cent.as<float>(), (int64_t)ix->lpad * ix->dp, ix->cent_h.as<uint16_t>(),
+                             ix->cent_l.as<uint16_t>(), st);
+}
+
 ivftq_status upload_coarse(ivftq_index* ix) {
     std::vector<float> padded((size_t)ix->lpad * ix->dp, 0.f);
     for (int l = 0; l < ix->nlist; ++l)
@@ -162,6 +168,8 @@ ivftq_status upload_coarse(ivftq_index* ix) {
     HIP_TRY(hipMemcpy(ix->cent.p, padded.data(), padded.size() * sizeof(float), hipMemcpyHostToDevice));
     std::vector<float> zero(ix->lpad, 0.f);
     HIP_TRY(hipMemcpy(ix->bias.p, zero.data(), zero.size() * sizeof(float), hipMemcpyHostToDevice));
+    HIP_TRY(refresh_split(ix, nullptr));
+    HIP_TRY(hipDeviceSynchronize());
     return IVFTQ_OK;
 }
 
@@ -286,6 +294,8 @@ ivftq_status ivftq_create(int d, int b, int nlist, uint64_t rotation_seed, ivftq
     std::copy(ix->h_tau.begin(), ix->h_tau.end(), tau_pad.begin());
     std::vector<int32_t> zeros(nlist, 0);
     hipError_t e = ix->cent.ensure((size_t)ix->lpad * ix->dp * sizeof(float));
+    if (e == hipSuccess) e = ix->cent_h.ensure((size_t)ix->lpad * ix->dp * sizeof(uint16_t));
+    if (e == hipSuccess) e = ix->cent_l.ensure((size_t)ix->lpad * ix->dp * sizeof(uint16_t));
     if (e == hipSuccess) e = ix->bias.ensure((size_t)ix->lpad * sizeof(float));
     if (e == hipSuccess) e = ix->pi.ensure((size_t)ix->dp * ix->dp * sizeof(float));
     if (e == hipSuccess) e = ix->cb.ensure(256 * sizeof(float));
@@ -506,7 +516,8 @@ ivftq_status ivftq_train_coarse(ivftq_index* ix, const float* x_dev, int64_t n, 
     for (int it = 0; it < niter; ++it) {
         HIP_TRY(launch_fill_u32(ix->w_sums.as<uint32_t>(), (int64_t)ix->lpad * pitch, 0u, st));
         HIP_TRY(launch_fill_u32(ix->w_counts.as<uint32_t>(), ix->lpad, 0u, st));
-        HIP_TRY(timed(ix, st, P_ASSIGN, [&] { return launch_coarse(0, x_dev, n, d, ix->cent.as<float>(), pitch, ix->bias.as<float>(), L, ix->lpad,
+        HIP_TRY(refresh_split(ix, st));
+        HIP_TRY(timed(ix, st, P_ASSIGN, [&] { return launch_coarse(0, x_dev, n, d, ix->cent_h.as<uint16_t>(), ix->cent_l.as<uint16_t>(), pitch, ix->bias.as<float>(), L, ix->lpad,
                               ix->w_assign.as<int32_t>(), ix->w_best.as<float>(), nullptr, 0,
                               ix->w_flag.as<int>(), st); }));
         HIP_TRY(launch_kmeans_accumulate(x_dev, n, d, ix->w_assign.as<int32_t>(), ix->w_sums.as<float>(), pitch,
@@ -542,6 +553,7 @@ ivftq_status ivftq_train_coarse(ivftq_index* ix, const float* x_dev, int64_t n, 
         }
     }
     HIP_TRY(launch_normalise_centroids(ix->cent.as<float>(), pitch, ix->bias.as<float>(), L, d, st));
+    HIP_TRY(refresh_split(ix, st));
     std::vector<float> padded((size_t)L * pitch);
     HIP_TRY(hipMemcpyAsync(padded.data(), ix->cent.p, padded.size() * sizeof(float), hipMemcpyDeviceToHost, st));
     HIP_TRY(hipStreamSynchronize(st));
@@ -616,7 +628,7 @@ ivftq_status ivftq_encode_only(ivftq_index* ix, const float* x_dev, int64_t n, i
     HIP_TRY(ix->w_assign.ensure((size_t)n * sizeof(int32_t)));
     int32_t* assign = assign_dev ? assign_dev : ix->w_assign.as<int32_t>();
     HIP_TRY(launch_fill_u32(ix->w_flag.as<uint32_t>(), 1, 0u, st));
-    HIP_TRY(timed(ix, st, P_ASSIGN, [&] { return launch_coarse(0, x_dev, n, ix->d, ix->cent.as<float>(), ix->dp, nullptr, ix->nlist, ix->lpad, assign,
+    HIP_TRY(timed(ix, st, P_ASSIGN, [&] { return launch_coarse(0, x_dev, n, ix->d, ix->cent_h.as<uint16_t>(), ix->cent_l.as<uint16_t>(), ix->dp, nullptr, ix->nlist, ix->lpad, assign,
                           nullptr, nullptr, 0, ix->w_flag.as<int>(), st); }));
     if (codes_dev || gamma_dev) {
         EncodeArgs a{};
@@ -645,7 +657,7 @@ ivftq_status ivftq_encode_add(ivftq_index* ix, const float* x_dev, int64_t n, co
     HIP_TRY(ix->w_assign.ensure((size_t)n * sizeof(int32_t)));
     HIP_TRY(ix->w_slot.ensure((size_t)n * sizeof(int64_t)));
     HIP_TRY(launch_fill_u32(ix->w_flag.as<uint32_t>(), 1, 0u, st));
-    HIP_TRY(timed(ix, st, P_ASSIGN, [&] { return launch_coarse(0, x_dev, n, ix->d, ix->cent.as<float>(), ix->dp, nullptr, L, ix->lpad,
+    HIP_TRY(timed(ix, st, P_ASSIGN, [&] { return launch_coarse(0, x_dev, n, ix->d, ix->cent_h.as<uint16_t>(), ix->cent_l.as<uint16_t>(), ix->dp, nullptr, L, ix->lpad,
                           ix->w_assign.as<int32_t>(), nullptr, nullptr, 0, ix->w_flag.as<int>(), st); }));
 
     // 2.-4. room for the new vectors and the stable position of every row
@@ -702,7 +714,7 @@ ivftq_status check_query_args(const ivftq_index* ix, const float* q_dev, int64_t
 ivftq_status coarse_and_probe(ivftq_index* ix, const float* q, int64_t count, int nprobe, int32_t* probe,
                               float* coarse, hipStream_t st) {
     const int64_t ldS = round_up(ix->nlist, 4);
-    HIP_TRY(timed(ix, st, P_COARSE_SCORES, [&] { return launch_coarse(1, q, count, ix->d, ix->cent.as<float>(), ix->dp, nullptr, ix->nlist, ix->lpad, nullptr,
+    HIP_TRY(timed(ix, st, P_COARSE_SCORES, [&] { return launch_coarse(1, q, count, ix->d, ix->cent_h.as<uint16_t>(), ix->cent_l.as<uint16_t>(), ix->dp, nullptr, ix->nlist, ix->lpad, nullptr,
                           nullptr, ix->w_S.as<float>(), ldS, ix->w_flag.as<int>(), st); }));
     SelectArgs sa{};
     sa.vals = ix->w_S.as<float>(); sa.stride = ldS; sa.rows = count; sa.k = nprobe; sa.m_fixed = ix->nlist;

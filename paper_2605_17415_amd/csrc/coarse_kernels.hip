@@ -4,186 +4,263 @@
 // exactly", Section "Architecture", Search).
 //
 // Shape of the work: n x d times d x L with small d (96..200) and a result that is never kept
-// (argmax) or kept once (scores).  One wavefront owns 32 data rows for the whole kernel and holds
+// (argmax) or kept once (scores).  One wavefront owns 32*R data rows for the whole kernel and holds
 // them in registers as the right-hand MFMA operand; centroid tiles stream through LDS and are the
-// left-hand operand, so that in the 32x32 result each lane holds one data row's scores against 16
+// left-hand operand, so that in each 32x32 result a lane holds one data row's scores against 16
 // centroids and the argmax over centroids never crosses lanes until the very end.
 //
-// v_mfma_f32_32x32x2_f32: A is 32x2 (lane = i + 32k), B is 2x32 (lane = j + 32k), D is 32x32 with
-// D[i][j] in lane j + 32*((i/4)%2), register (i%4) + 4*(i/8).  The two k-slots of step s are
-// mapped to coordinates s and DP/2 + s, so each lane reads one contiguous half of its row.
+// Arithmetic: both operands are used in split float16 form (see kSplitScale): 1024 v = hi + lo, and
+// the product is accumulated as hi*hi + hi*lo + lo*hi on v_mfma_f32_32x32x16_f16 with float32
+// accumulation.  Each part carries 11 significant bits, so a score differs from the float32 dot
+// product by about 2e-7, well inside the 1e-5 near-tie allowance, at the float16 matrix rate.
+//
+// v_mfma_f32_32x32x16_f16: A is 32x16 (lane = i + 32*(k/8), element k%8), B is 16x32 likewise,
+// D[i][j] in lane j + 32*((i/4)%2), register (i%4) + 4*(i/8).
 #include "kernels.h"
 
 namespace ivftq {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 
 namespace {
 
+constexpr int kNT = 2;                       // 32-centroid tiles per LDS stage
+constexpr int kTN = kNT * 32;
+
 template <int DP>
 struct CoarseCfg {
-    static constexpr int NT = 2;                 // 32-centroid tiles per LDS stage
-    static constexpr int TN = NT * 32;
-    static constexpr int LDP = DP + 1;           // odd pitch: conflict-free column reads
-    static constexpr size_t lds_bytes = (size_t)TN * LDP * sizeof(float) + TN * sizeof(float);
+    static constexpr int KB = DP / 16;
+    static constexpr int LDH = DP + 8;       // halves per LDS row: the 16-byte pad keeps b128 reads conflict free
+    static constexpr size_t lds_bytes = (size_t)2 * kTN * LDH * sizeof(uint16_t) + kTN * sizeof(float);
 };
 
-// Coordinates half*DP/2 + [0, DP/2) of `row` into v, zero beyond d.  Loads are unconditional on
-// clamped indices (straight-line code); an invalid row reads row 0 and is zeroed.
+// hi[r][c], lo[r][c] = split float16 form of src[r][c]
+__global__ void k_split_rows(const float* __restrict__ src, int64_t count, uint16_t* __restrict__ hi,
+                             uint16_t* __restrict__ lo) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= count) return;
+    const float V = src[i] * kSplitScale;
+    const _Float16 h = (_Float16)V;
+    const _Float16 l = (_Float16)(V - (float)h);
+    hi[i] = __builtin_bit_cast(uint16_t, h);
+    lo[i] = __builtin_bit_cast(uint16_t, l);
+}
+
+// One 32-row tile of normalised data rows as the B operand: lane (j, half) takes coordinates
+// 16*kb + 8*half + [0, 8) of row j.  Returns whether the row's norm is usable.
 template <int DP>
-__device__ __forceinline__ void load_half_row(const float* __restrict__ x, int64_t row, bool valid,
-                                              int d, int vec4, int half, float (&v)[DP / 2]) {
-    const int k0 = half * (DP / 2);
+__device__ __forceinline__ bool load_rows(const float* __restrict__ x, int64_t row, bool valid, int d, int vec4,
+                                          int half, half8 (&bh)[DP / 16], half8 (&bl)[DP / 16]) {
+    constexpr int KB = DP / 16;
     const float* p = x + (valid ? row : 0) * (int64_t)d;
-    if (vec4) {   // d % 4 == 0 and x 16-byte aligned: whole float4s are in or out of range
+    float v[KB][8];
+    float n2 = 0.f;
+    if (vec4) {          // d % 4 == 0 and x 16-byte aligned: whole float4s are in or out of range
         const float4* q = reinterpret_cast<const float4*>(p);
         const int last4 = d / 4 - 1;
 #pragma unroll
-        for (int s = 0; s < DP / 2; s += 4) {
-            const int i4 = (k0 + s) / 4;
-            const float4 t = q[i4 < last4 ? i4 : last4];
-            const bool in = valid && (k0 + s < d);
-            v[s] = in ? t.x : 0.f; v[s + 1] = in ? t.y : 0.f; v[s + 2] = in ? t.z : 0.f; v[s + 3] = in ? t.w : 0.f;
-        }
+        for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                const int c = 16 * kb + 8 * half + 4 * e;
+                const int i4 = c / 4;
+                const float4 t = q[i4 < last4 ? i4 : last4];
+                const bool in = valid && c < d;
+                v[kb][4 * e] = in ? t.x : 0.f; v[kb][4 * e + 1] = in ? t.y : 0.f;
+                v[kb][4 * e + 2] = in ? t.z : 0.f; v[kb][4 * e + 3] = in ? t.w : 0.f;
+            }
     } else {
 #pragma unroll
-        for (int s = 0; s < DP / 2; ++s) {
-            const int i = k0 + s;
-            const float t = p[i < d ? i : d - 1];
-            v[s] = (valid && i < d) ? t : 0.f;
-        }
+        for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int c = 16 * kb + 8 * half + e;
+                const float t = p[c < d ? c : d - 1];
+                v[kb][e] = (valid && c < d) ? t : 0.f;
+            }
     }
+#pragma unroll
+    for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) n2 += v[kb][e] * v[kb][e];
+    n2 += __shfl_xor(n2, 32);
+    const bool good = (n2 > 0.f) && (n2 < __builtin_inff());
+    const float nrm = sqrtf(n2);
+#pragma unroll
+    for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float V = good ? (v[kb][e] / nrm) * kSplitScale : 0.f;
+            const _Float16 h = (_Float16)V;
+            bh[kb][e] = h;
+            bl[kb][e] = (_Float16)(V - (float)h);
+        }
+    return good;
 }
 
-template <int DP>
-__global__ __launch_bounds__(256, 2) void k_coarse(
-    int mode, const float* __restrict__ x, int64_t n, int d, int vec4, const float* __restrict__ cent,
-    int cent_pitch, const float* __restrict__ bias, int L, int Lpad, int32_t* __restrict__ assign,
-    float* __restrict__ best_out, float* __restrict__ scores, int64_t ld_scores, int* __restrict__ flag) {
+// R = 32-row tiles per wavefront.
+template <int DP, int R>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k_coarse(
+    int mode, const float* __restrict__ x, int64_t n, int d, int vec4, const uint16_t* __restrict__ cent_h,
+    const uint16_t* __restrict__ cent_l, int cent_pitch, const float* __restrict__ bias, int L, int Lpad,
+    int32_t* __restrict__ assign, float* __restrict__ best_out, float* __restrict__ scores,
+    int64_t ld_scores, int* __restrict__ flag) {
     using Cfg = CoarseCfg<DP>;
-    extern __shared__ float lds[];
-    float* tile = lds;
-    float* tile_bias = lds + Cfg::TN * Cfg::LDP;
+    constexpr int KB = Cfg::KB;
+    extern __shared__ unsigned char lds_raw[];
+    uint16_t* th = reinterpret_cast<uint16_t*>(lds_raw);            // [TN][LDH] hi parts of the centroid tile
+    uint16_t* tl = th + kTN * Cfg::LDH;                               // [TN][LDH] lo parts
+    float* tile_bias = reinterpret_cast<float*>(tl + kTN * Cfg::LDH); // [TN]
 
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63, half = lane >> 5, j = lane & 31;
-    const int64_t row = (int64_t)blockIdx.x * kRowsPerWG + wave * 32 + j;
-    const bool valid = row < n;
+    const int64_t row0 = ((int64_t)blockIdx.x * 4 + wave) * (32 * R);
 
-    float bx[DP / 2];
-    load_half_row<DP>(x, row, valid, d, vec4, half, bx);
-    float n2 = 0.f;
+    half8 bh[R][KB], bl[R][KB];
+    bool good[R];
 #pragma unroll
-    for (int s = 0; s < DP / 2; ++s) n2 += bx[s] * bx[s];
-    n2 += __shfl_xor(n2, 32);
-    const bool good = (n2 > 0.f) && (n2 < __builtin_inff());
-    if (valid && !good && half == 0) atomicOr(flag, 1);
-    const float nrm = sqrtf(n2);
+    for (int r = 0; r < R; ++r) {
+        const int64_t row = row0 + 32 * r + j;
+        good[r] = load_rows<DP>(x, row, row < n, d, vec4, half, bh[r], bl[r]);
+        if (row < n && !good[r] && half == 0) atomicOr(flag, 1);
+    }
+
+    float best[R];
+    int best_idx[R];
 #pragma unroll
-    for (int s = 0; s < DP / 2; ++s) bx[s] = good ? bx[s] / nrm : 0.f;
+    for (int r = 0; r < R; ++r) { best[r] = -__builtin_inff(); best_idx[r] = 0; }
+    const uint16_t* ah_base = th + j * Cfg::LDH + 8 * half;
+    const uint16_t* al_base = tl + j * Cfg::LDH + 8 * half;
+    constexpr float kUnscale = 1.f / (kSplitScale * kSplitScale);
 
-    float best = -__builtin_inff();
-    int best_idx = 0;
-    const float* a_base = tile + j * Cfg::LDP + half * (DP / 2);
-
-    for (int c0 = 0; c0 < Lpad; c0 += Cfg::TN) {
+    for (int c0 = 0; c0 < Lpad; c0 += kTN) {
         __syncthreads();
-        // stage TN centroid rows (DP columns of the padded table) into LDS
-        for (int e = tid; e < Cfg::TN * (DP / 4); e += 256) {
-            const int r = e / (DP / 4), q4 = e % (DP / 4);
-            const float4 t = *reinterpret_cast<const float4*>(cent + (int64_t)(c0 + r) * cent_pitch + q4 * 4);
-            float* dst = tile + r * Cfg::LDP + q4 * 4;
-            dst[0] = t.x; dst[1] = t.y; dst[2] = t.z; dst[3] = t.w;
+        // stage TN centroid rows (hi and lo) into LDS, 16 bytes at a time
+        for (int e = tid; e < kTN * (DP / 8); e += 256) {
+            const int r = e / (DP / 8), c8 = e % (DP / 8);
+            const int64_t src = (int64_t)(c0 + r) * cent_pitch + c8 * 8;
+            *reinterpret_cast<uint4*>(th + r * Cfg::LDH + c8 * 8) = *reinterpret_cast<const uint4*>(cent_h + src);
+            *reinterpret_cast<uint4*>(tl + r * Cfg::LDH + c8 * 8) = *reinterpret_cast<const uint4*>(cent_l + src);
         }
-        if (tid < Cfg::TN) tile_bias[tid] = bias ? bias[c0 + tid] : 0.f;
+        if (tid < kTN) tile_bias[tid] = bias ? bias[c0 + tid] : 0.f;
         __syncthreads();
 
-        floatx16 acc[Cfg::NT];
+        floatx16 acc[R][kNT];
 #pragma unroll
-        for (int t = 0; t < Cfg::NT; ++t)
+        for (int r = 0; r < R; ++r)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
+            for (int t = 0; t < kNT; ++t)
 #pragma unroll
-        for (int s = 0; s < DP / 2; ++s) {
+                for (int q = 0; q < 16; ++q) acc[r][t][q] = 0.f;
 #pragma unroll
-            for (int t = 0; t < Cfg::NT; ++t) {
-                const float a = a_base[t * 32 * Cfg::LDP + s];
-                acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, bx[s], acc[t], 0, 0, 0);
+        for (int kb = 0; kb < KB; ++kb) {
+#pragma unroll
+            for (int t = 0; t < kNT; ++t) {
+                const half8 ah = *reinterpret_cast<const half8*>(ah_base + t * 32 * Cfg::LDH + 16 * kb);
+                const half8 al = *reinterpret_cast<const half8*>(al_base + t * 32 * Cfg::LDH + 16 * kb);
+#pragma unroll
+                for (int r = 0; r < R; ++r) acc[r][t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah, bh[r][kb], acc[r][t], 0, 0, 0);
+#pragma unroll
+                for (int r = 0; r < R; ++r) acc[r][t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah, bl[r][kb], acc[r][t], 0, 0, 0);
+#pragma unroll
+                for (int r = 0; r < R; ++r) acc[r][t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(al, bh[r][kb], acc[r][t], 0, 0, 0);
             }
         }
 
         if (mode == 0) {
 #pragma unroll
-            for (int t = 0; t < Cfg::NT; ++t)
+            for (int t = 0; t < kNT; ++t)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int i = 8 * (r / 4) + 4 * half + (r % 4);
+                for (int q = 0; q < 16; ++q) {
+                    const int i = 8 * (q / 4) + 4 * half + (q % 4);
                     const int c = c0 + t * 32 + i;
-                    const float v = acc[t][r] + tile_bias[t * 32 + i];
-                    if (c < L && v > best) { best = v; best_idx = c; }   // ascending c: first maximum wins
-                }
-        } else if (valid) {
+                    const float bi = tile_bias[t * 32 + i];
 #pragma unroll
-            for (int t = 0; t < Cfg::NT; ++t)
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const int c = c0 + t * 32 + 8 * g + 4 * half;
-                    if (c < ld_scores) {
-                        float4 o = make_float4(acc[t][4 * g], acc[t][4 * g + 1], acc[t][4 * g + 2], acc[t][4 * g + 3]);
-                        *reinterpret_cast<float4*>(scores + row * ld_scores + c) = o;
+                    for (int r = 0; r < R; ++r) {
+                        const float v = fmaf(acc[r][t][q], kUnscale, bi);
+                        if (c < L && v > best[r]) { best[r] = v; best_idx[r] = c; }   // ascending c: first maximum wins
                     }
                 }
+        } else {
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const int64_t row = row0 + 32 * r + j;
+                if (row >= n) continue;
+#pragma unroll
+                for (int t = 0; t < kNT; ++t)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const int c = c0 + t * 32 + 8 * g + 4 * half;
+                        if (c < ld_scores) {
+                            float4 o = make_float4(acc[r][t][4 * g] * kUnscale, acc[r][t][4 * g + 1] * kUnscale,
+                                                   acc[r][t][4 * g + 2] * kUnscale, acc[r][t][4 * g + 3] * kUnscale);
+                            *reinterpret_cast<float4*>(scores + row * ld_scores + c) = o;
+                        }
+                    }
+            }
         }
     }
 
     if (mode == 0) {
-        const float ob = __shfl_xor(best, 32);
-        const int oi = __shfl_xor(best_idx, 32);
-        if (ob > best || (ob == best && oi < best_idx)) { best = ob; best_idx = oi; }
-        if (valid && half == 0) {
-            if (assign) assign[row] = good ? best_idx : -1;
-            if (best_out) best_out[row] = best;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const float ob = __shfl_xor(best[r], 32);
+            const int oi = __shfl_xor(best_idx[r], 32);
+            if (ob > best[r] || (ob == best[r] && oi < best_idx[r])) { best[r] = ob; best_idx[r] = oi; }
+            const int64_t row = row0 + 32 * r + j;
+            if (row < n && half == 0) {
+                if (assign) assign[row] = good[r] ? best_idx[r] : -1;
+                if (best_out) best_out[row] = best[r];
+            }
         }
     }
 }
 
-template <int DP>
-hipError_t run(int mode, const float* x, int64_t n, int d, const float* cent, int cent_pitch,
-               const float* bias, int L, int Lpad, int32_t* assign, float* best, float* scores,
+template <int DP, int R>
+hipError_t run(int mode, const float* x, int64_t n, int d, const uint16_t* cent_h, const uint16_t* cent_l,
+               int cent_pitch, const float* bias, int L, int Lpad, int32_t* assign, float* best, float* scores,
                int64_t ld_scores, int* flag, hipStream_t st) {
     static bool attr_set = false;
     const size_t lds = CoarseCfg<DP>::lds_bytes;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_coarse<DP>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_coarse<DP, R>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    const int64_t blocks = (n + kRowsPerWG - 1) / kRowsPerWG;
+    const int64_t rows_per_wg = 4 * 32 * R;
+    const int64_t blocks = (n + rows_per_wg - 1) / rows_per_wg;
     const int vec4 = (d % 4 == 0) && (reinterpret_cast<uintptr_t>(x) % 16 == 0);
-    hipLaunchKernelGGL(k_coarse<DP>, dim3((unsigned)blocks), dim3(256), lds, st, mode, x, n, d, vec4, cent,
-                       cent_pitch, bias, L, Lpad, assign, best, scores, ld_scores, flag);
+    hipLaunchKernelGGL((k_coarse<DP, R>), dim3((unsigned)blocks), dim3(256), lds, st, mode, x, n, d, vec4, cent_h,
+                       cent_l, cent_pitch, bias, L, Lpad, assign, best, scores, ld_scores, flag);
     return hipGetLastError();
 }
 
 }  // namespace
 
 int coarse_dp(int d) {
-    static const int sizes[] = {32, 64, 96, 128, 160, 192, 200, 224, 256};
+    static const int sizes[] = {32, 64, 96, 128, 160, 192, 208, 224, 256};
     for (int s : sizes)
         if (d <= s) return s;
     return -1;
 }
 
-hipError_t launch_coarse(int mode, const float* x, int64_t n, int d, const float* cent, int cent_pitch,
-                         const float* bias, int L, int Lpad, int32_t* assign, float* best,
+hipError_t launch_split_rows(const float* src, int64_t count, uint16_t* hi, uint16_t* lo, hipStream_t st) {
+    if (count <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_split_rows, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st, src, count, hi, lo);
+    return hipGetLastError();
+}
+
+hipError_t launch_coarse(int mode, const float* x, int64_t n, int d, const uint16_t* cent_h, const uint16_t* cent_l,
+                         int cent_pitch, const float* bias, int L, int Lpad, int32_t* assign, float* best,
                          float* scores, int64_t ld_scores, int* flag, hipStream_t st) {
     if (n <= 0) return hipSuccess;
     switch (coarse_dp(d)) {
-#define IVFTQ_CASE(DPV) \
-    case DPV: return run<DPV>(mode, x, n, d, cent, cent_pitch, bias, L, Lpad, assign, best, scores, ld_scores, flag, st);
-        IVFTQ_CASE(32) IVFTQ_CASE(64) IVFTQ_CASE(96) IVFTQ_CASE(128) IVFTQ_CASE(160)
-        IVFTQ_CASE(192) IVFTQ_CASE(200) IVFTQ_CASE(224) IVFTQ_CASE(256)
+#define IVFTQ_CASE(DPV, RV) \
+    case DPV: return run<DPV, RV>(mode, x, n, d, cent_h, cent_l, cent_pitch, bias, L, Lpad, assign, best, scores, ld_scores, flag, st);
+        IVFTQ_CASE(32, 2) IVFTQ_CASE(64, 2) IVFTQ_CASE(96, 2) IVFTQ_CASE(128, 2) IVFTQ_CASE(160, 1)
+        IVFTQ_CASE(192, 1) IVFTQ_CASE(208, 1) IVFTQ_CASE(224, 1) IVFTQ_CASE(256, 1)
 #undef IVFTQ_CASE
         default: return hipErrorInvalidValue;
     }

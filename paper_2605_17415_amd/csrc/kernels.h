@@ -13,6 +13,11 @@ constexpr int kMaxD = 256;
 constexpr int kMaxList = 16384;
 constexpr int kMaxK = 2048;
 
+// Split float16 form used by the float16 matrix-core kernels: V = 1024*v, hi = fp16(V),
+// lo = fp16(V - hi).  hi + lo equals V to about 2^-22 relative; the factor keeps lo in the normal
+// float16 range for every |v| > 2.4e-4 (below that lo is at most 6e-8 of v's scale).
+constexpr float kSplitScale = 1024.f;
+
 inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
 inline int64_t round_up64(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
 
@@ -39,11 +44,14 @@ struct ListStore {
 
 // mode 0: assign[i] = argmax_c (<x~_i, cent_c> + bias_c), best[i] that value (either may be null)
 // mode 1: scores[i*ld_scores + c] = <x~_i, cent_c> for c < L
-// x: n x d raw rows (normalised inside).  cent: [Lpad][cent_pitch] zero padded, Lpad % 64 == 0.
+// x: n x d raw rows (normalised inside).  cent_h / cent_l: split float16 form of the centroid table
+// [Lpad][cent_pitch], zero padded, Lpad % 64 == 0 (made by launch_split_rows).
 // flag: set to 1 when a row has zero or non-finite norm (that row gets assign -1).
-hipError_t launch_coarse(int mode, const float* x, int64_t n, int d, const float* cent, int cent_pitch,
-                         const float* bias, int L, int Lpad, int32_t* assign, float* best,
+hipError_t launch_coarse(int mode, const float* x, int64_t n, int d, const uint16_t* cent_h, const uint16_t* cent_l,
+                         int cent_pitch, const float* bias, int L, int Lpad, int32_t* assign, float* best,
                          float* scores, int64_t ld_scores, int* flag, hipStream_t st);
+// hi[i], lo[i] = split float16 form of src[i]
+hipError_t launch_split_rows(const float* src, int64_t count, uint16_t* hi, uint16_t* lo, hipStream_t st);
 
 // Rotation family.  pi: [DP][DP] zero padded with DP = rot_dp(d); tau: 2^b - 1 boundaries.
 // mode 0: residual -> rotate -> normalise -> quantise -> pack into the list store at slot[i]
@@ -63,10 +71,7 @@ struct EncodeArgs {
     uint16_t* zh_out; uint16_t* zl_out;   // optional: split float16 form of 1024*z (see split_scaled)
 };
 
-// Split float16 form used by the float16 matrix-core kernels: V = 1024*v, hi = fp16(V),
-// lo = fp16(V - hi).  hi + lo equals V to about 2^-22 relative; the factor keeps lo in the normal
-// float16 range for every |v| > 2.4e-4 (below that lo is at most 6e-8 of v's scale).
-constexpr float kSplitScale = 1024.f;
+
 hipError_t launch_encode(int mode, const EncodeArgs& a, hipStream_t st);
 
 // ---- list bookkeeping -------------------------------------------------------------------------
