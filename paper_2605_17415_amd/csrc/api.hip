@@ -87,7 +87,7 @@ struct ivftq_index {
     bool has_coarse = false;
     std::vector<float> h_cent, h_pi, h_cb, h_tau;
     // device constants
-    DevBuf cent, cent_h, cent_l, bias, pi, cb, tau;   // cent_h/cent_l: split float16 form of cent
+    DevBuf cent, cent_h, cent_l, bias, pi, pi_h, pi_l, cb, tau;   // cent_h/cent_l: split float16 form of cent
     // list storage
     DevBuf codes, gamma, ids, d_off, d_size;
     std::vector<int64_t> h_off, h_cap;
@@ -117,7 +117,7 @@ struct ivftq_index {
     }
     ~ivftq_index() {
         for (ProfRec& r : prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
-        for (DevBuf* bfr : {&cent, &cent_h, &cent_l, &bias, &pi, &cb, &tau, &codes, &gamma, &ids, &d_off, &d_size, &w_assign,
+        for (DevBuf* bfr : {&cent, &cent_h, &cent_l, &pi_h, &pi_l, &bias, &pi, &cb, &tau, &codes, &gamma, &ids, &d_off, &d_size, &w_assign,
                             &w_slot, &w_hist, &w_count, &w_base, &w_flag, &w_best, &w_S, &w_probe, &w_coarse,
                             &w_z, &w_candoff, &w_scores, &w_sums, &w_counts, &w_zero, &w_rows, &w_dst, &w_obj,
                             &w_first, &w_fscores, &w_fids, &w_key, &w_pairs, &w_pairoff, &w_tileoff, &w_cscore,
@@ -178,6 +178,9 @@ ivftq_status upload_rotation(ivftq_index* ix) {
     for (int i = 0; i < ix->d; ++i)
         std::memcpy(&padded[(size_t)i * ix->dp], &ix->h_pi[(size_t)i * ix->d], sizeof(float) * ix->d);
     HIP_TRY(hipMemcpy(ix->pi.p, padded.data(), padded.size() * sizeof(float), hipMemcpyHostToDevice));
+    HIP_TRY(launch_split_rows(ix->pi.as<float>(), (int64_t)ix->dp * ix->dp, ix->pi_h.as<uint16_t>(),
+                              ix->pi_l.as<uint16_t>(), nullptr));
+    HIP_TRY(hipDeviceSynchronize());
     return IVFTQ_OK;
 }
 
@@ -298,6 +301,8 @@ ivftq_status ivftq_create(int d, int b, int nlist, uint64_t rotation_seed, ivftq
     if (e == hipSuccess) e = ix->cent_l.ensure((size_t)ix->lpad * ix->dp * sizeof(uint16_t));
     if (e == hipSuccess) e = ix->bias.ensure((size_t)ix->lpad * sizeof(float));
     if (e == hipSuccess) e = ix->pi.ensure((size_t)ix->dp * ix->dp * sizeof(float));
+    if (e == hipSuccess) e = ix->pi_h.ensure((size_t)ix->dp * ix->dp * sizeof(uint16_t));
+    if (e == hipSuccess) e = ix->pi_l.ensure((size_t)ix->dp * ix->dp * sizeof(uint16_t));
     if (e == hipSuccess) e = ix->cb.ensure(256 * sizeof(float));
     if (e == hipSuccess) e = ix->tau.ensure(256 * sizeof(float));
     if (e == hipSuccess) e = ix->d_size.ensure((size_t)nlist * sizeof(int32_t));
@@ -634,7 +639,7 @@ ivftq_status ivftq_encode_only(ivftq_index* ix, const float* x_dev, int64_t n, i
         EncodeArgs a{};
         a.x = x_dev; a.n = n; a.d = ix->d; a.b = ix->b;
         a.cent = ix->cent.as<float>(); a.cent_pitch = ix->dp;
-        a.pi = ix->pi.as<float>(); a.tau = ix->tau.as<float>();
+        a.pi_h = ix->pi_h.as<uint16_t>(); a.pi_l = ix->pi_l.as<uint16_t>(); a.tau = ix->tau.as<float>();
         a.assign = assign;
         a.codes_flat = codes_dev; a.gamma_flat = gamma_dev;
         HIP_TRY(timed(ix, st, P_ENCODE, [&] { return launch_encode(1, a, st); }));
@@ -668,7 +673,7 @@ ivftq_status ivftq_encode_add(ivftq_index* ix, const float* x_dev, int64_t n, co
     EncodeArgs a{};
     a.x = x_dev; a.n = n; a.d = ix->d; a.b = ix->b;
     a.cent = ix->cent.as<float>(); a.cent_pitch = ix->dp;
-    a.pi = ix->pi.as<float>(); a.tau = ix->tau.as<float>();
+    a.pi_h = ix->pi_h.as<uint16_t>(); a.pi_l = ix->pi_l.as<uint16_t>(); a.tau = ix->tau.as<float>();
     a.assign = ix->w_assign.as<int32_t>();
     a.store = ix->store();
     a.slot = ix->w_slot.as<int64_t>();
@@ -808,7 +813,7 @@ ivftq_status ivftq_search(ivftq_index* ix, const float* q_dev, int64_t nq, int n
         if (s != IVFTQ_OK) return s;
         EncodeArgs ea{};
         ea.x = q; ea.n = cnt; ea.d = ix->d; ea.b = ix->b;
-        ea.pi = ix->pi.as<float>(); ea.zout = ix->w_z.as<float>();
+        ea.pi_h = ix->pi_h.as<uint16_t>(); ea.pi_l = ix->pi_l.as<uint16_t>(); ea.zout = ix->w_z.as<float>();
         if (batched) { ea.zh_out = ix->w_zh.as<uint16_t>(); ea.zl_out = ix->w_zl.as<uint16_t>(); }
         HIP_TRY(timed(ix, st, P_ROTATE_Q, [&] { return launch_encode(2, ea, st); }));
         int32_t* first = batched ? ix->w_first.as<int32_t>() : nullptr;

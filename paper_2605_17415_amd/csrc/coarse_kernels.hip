@@ -9,19 +9,13 @@
 // left-hand operand, so that in each 32x32 result a lane holds one data row's scores against 16
 // centroids and the argmax over centroids never crosses lanes until the very end.
 //
-// Arithmetic: both operands are used in split float16 form (see kSplitScale): 1024 v = hi + lo, and
-// the product is accumulated as hi*hi + hi*lo + lo*hi on v_mfma_f32_32x32x16_f16 with float32
-// accumulation.  Each part carries 11 significant bits, so a score differs from the float32 dot
+// Arithmetic: both operands are used in split float16 form (split_f16.h) on
+// v_mfma_f32_32x32x16_f16 with float32 accumulation, so a score differs from the float32 dot
 // product by about 2e-7, well inside the 1e-5 near-tie allowance, at the float16 matrix rate.
-//
-// v_mfma_f32_32x32x16_f16: A is 32x16 (lane = i + 32*(k/8), element k%8), B is 16x32 likewise,
-// D[i][j] in lane j + 32*((i/4)%2), register (i%4) + 4*(i/8).
 #include "kernels.h"
+#include "split_f16.h"
 
 namespace ivftq {
-
-typedef float floatx16 __attribute__((ext_vector_type(16)));
-typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 
 namespace {
 
@@ -40,61 +34,31 @@ __global__ void k_split_rows(const float* __restrict__ src, int64_t count, uint1
                              uint16_t* __restrict__ lo) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= count) return;
-    const float V = src[i] * kSplitScale;
-    const _Float16 h = (_Float16)V;
-    const _Float16 l = (_Float16)(V - (float)h);
+    _Float16 h, l;
+    split_scaled(src[i], h, l);
     hi[i] = __builtin_bit_cast(uint16_t, h);
     lo[i] = __builtin_bit_cast(uint16_t, l);
 }
 
-// One 32-row tile of normalised data rows as the B operand: lane (j, half) takes coordinates
-// 16*kb + 8*half + [0, 8) of row j.  Returns whether the row's norm is usable.
+// One 32-row tile of normalised data rows as the B operand (split form).  Returns whether the
+// row's norm is usable.
 template <int DP>
 __device__ __forceinline__ bool load_rows(const float* __restrict__ x, int64_t row, bool valid, int d, int vec4,
                                           int half, half8 (&bh)[DP / 16], half8 (&bl)[DP / 16]) {
     constexpr int KB = DP / 16;
-    const float* p = x + (valid ? row : 0) * (int64_t)d;
     float v[KB][8];
-    float n2 = 0.f;
-    if (vec4) {          // d % 4 == 0 and x 16-byte aligned: whole float4s are in or out of range
-        const float4* q = reinterpret_cast<const float4*>(p);
-        const int last4 = d / 4 - 1;
-#pragma unroll
-        for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-            for (int e = 0; e < 2; ++e) {
-                const int c = 16 * kb + 8 * half + 4 * e;
-                const int i4 = c / 4;
-                const float4 t = q[i4 < last4 ? i4 : last4];
-                const bool in = valid && c < d;
-                v[kb][4 * e] = in ? t.x : 0.f; v[kb][4 * e + 1] = in ? t.y : 0.f;
-                v[kb][4 * e + 2] = in ? t.z : 0.f; v[kb][4 * e + 3] = in ? t.w : 0.f;
-            }
-    } else {
-#pragma unroll
-        for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int c = 16 * kb + 8 * half + e;
-                const float t = p[c < d ? c : d - 1];
-                v[kb][e] = (valid && c < d) ? t : 0.f;
-            }
-    }
-#pragma unroll
-    for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-        for (int e = 0; e < 8; ++e) n2 += v[kb][e] * v[kb][e];
-    n2 += __shfl_xor(n2, 32);
+    load_row_blocks<KB>(x + (valid ? row : 0) * (int64_t)d, valid, d, vec4, half, v);
+    const float n2 = row_norm2<KB>(v);
     const bool good = (n2 > 0.f) && (n2 < __builtin_inff());
     const float nrm = sqrtf(n2);
 #pragma unroll
     for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            const float V = good ? (v[kb][e] / nrm) * kSplitScale : 0.f;
-            const _Float16 h = (_Float16)V;
+            _Float16 h, l;
+            split_scaled(good ? v[kb][e] / nrm : 0.f, h, l);
             bh[kb][e] = h;
-            bl[kb][e] = (_Float16)(V - (float)h);
+            bl[kb][e] = l;
         }
     return good;
 }

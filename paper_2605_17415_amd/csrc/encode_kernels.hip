@@ -3,61 +3,40 @@
 // coordinate; Bit accounting: b*d code bits and a float16 norm per vector), plus the query-side
 // rotation z = Pi q~ (Section "Architecture", Search).
 //
-// The rotation is a d x d contraction on the matrix cores (v_mfma_f32_32x32x2_f32, see
-// coarse_kernels.hip for the operand layout).  A wavefront owns 32 rows; the residuals are the
-// right-hand operand held in registers, 32-row tiles of Pi stream through LDS as the left-hand
-// operand.  In tile t a lane holds, for one row, the rotated coordinates 32t + 8g + 4*half + {0..3}.
+// The rotation is a d x d contraction on the matrix cores (v_mfma_f32_32x32x16_f16 on split float16
+// operands with float32 accumulation, see split_f16.h).  A wavefront owns 32 rows; the unit residuals
+// are the right-hand operand held in registers, 32-row tiles of Pi stream through LDS as the
+// left-hand operand.  In tile t a lane holds, for one row, the rotated coordinates
+// 32t + 8g + 4*half + {0..3}; all tiles stay in registers until the norm of Pi r is known.
 #include <hip/hip_fp16.h>
 
 #include "kernels.h"
+#include "split_f16.h"
 
 namespace ivftq {
-
-typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 namespace {
 
 template <int DP>
 struct EncCfg {
+    static constexpr int KB = DP / 16;
     static constexpr int NT = DP / 32;
-    static constexpr int LDP = DP + 1;
-    static constexpr size_t pi_floats = 32 * LDP;
+    static constexpr int LDH = DP + 8;                     // halves per LDS row of the Pi tile
+    static constexpr size_t pi_bytes = (size_t)2 * 32 * LDH * sizeof(uint16_t);
     static constexpr size_t code_bytes = 4 * 32 * DP;      // per wave: 32 rows x DP bytes
-    static constexpr size_t lds_bytes = pi_floats * 4 + 256 * 4 + code_bytes;
+    static constexpr size_t lds_bytes = pi_bytes + 256 * 4 + code_bytes;
+    static constexpr int occupancy = DP <= 160 ? 2 : 1;    // wavefronts per SIMD the register budget allows
 };
 
-// Coordinates k0 + [0, DP/2) of the row at p (len valid floats) into v, zero beyond len.  Every
-// load is unconditional on a clamped index, so the compiler emits straight-line code; p must point
-// at a readable row even when `valid` is false.
 template <int DP>
-__device__ __forceinline__ void load_half(const float* __restrict__ p, bool valid, int len, int vec4,
-                                          int k0, float (&v)[DP / 2]) {
-    if (vec4) {
-        const float4* q = reinterpret_cast<const float4*>(p);
-        const int last4 = len / 4 - 1;
-#pragma unroll
-        for (int s = 0; s < DP / 2; s += 4) {
-            const int i4 = (k0 + s) / 4;
-            const float4 t = q[i4 < last4 ? i4 : last4];
-            const bool in = valid && (k0 + s < len);
-            v[s] = in ? t.x : 0.f; v[s + 1] = in ? t.y : 0.f; v[s + 2] = in ? t.z : 0.f; v[s + 3] = in ? t.w : 0.f;
-        }
-    } else {
-#pragma unroll
-        for (int s = 0; s < DP / 2; ++s) {
-            const int i = k0 + s;
-            const float t = p[i < len ? i : len - 1];
-            v[s] = (valid && i < len) ? t : 0.f;
-        }
-    }
-}
-
-template <int DP>
-__global__ __launch_bounds__(256, 2) void k_encode(int mode, EncodeArgs a, int vec4) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(EncCfg<DP>::occupancy)))
+void k_encode(int mode, EncodeArgs a, int vec4) {
     using Cfg = EncCfg<DP>;
-    extern __shared__ float lds[];
-    float* pi_tile = lds;                                   // [32][LDP]
-    float* tau_s = lds + Cfg::pi_floats;                    // [256]
+    constexpr int KB = Cfg::KB;
+    extern __shared__ unsigned char lds_raw[];
+    uint16_t* ph = reinterpret_cast<uint16_t*>(lds_raw);           // [32][LDH] hi parts of 32 rows of Pi
+    uint16_t* pl = ph + 32 * Cfg::LDH;                               // [32][LDH] lo parts
+    float* tau_s = reinterpret_cast<float*>(pl + 32 * Cfg::LDH);     // [256]
     uint8_t* code_s = reinterpret_cast<uint8_t*>(tau_s + 256);
 
     const int tid = threadIdx.x;
@@ -70,75 +49,91 @@ __global__ __launch_bounds__(256, 2) void k_encode(int mode, EncodeArgs a, int v
 
     if (mode != 2 && tid < K - 1) tau_s[tid] = a.tau[tid];
 
-    // x~ (and the residual against the assigned centroid)
-    float r[DP / 2];
-    load_half<DP>(a.x + (valid ? row : 0) * (int64_t)d, valid, d, vec4, half * (DP / 2), r);
-    float n2 = 0.f;
-#pragma unroll
-    for (int s = 0; s < DP / 2; ++s) n2 += r[s] * r[s];
-    n2 += __shfl_xor(n2, 32);
+    // x~, then the residual against the assigned centroid and its norm gamma.  The rotation acts on
+    // the unit residual r/gamma: Pi r / |Pi r| does not depend on the scale of r, and a unit vector
+    // keeps the split float16 form accurate however small the residual is.
+    float v[KB][8];
+    load_row_blocks<KB>(a.x + (valid ? row : 0) * (int64_t)d, valid, d, vec4, half, v);
+    const float n2 = row_norm2<KB>(v);
     const bool good = (n2 > 0.f) && (n2 < __builtin_inff());
     const float nrm = sqrtf(n2);
 #pragma unroll
-    for (int s = 0; s < DP / 2; ++s) r[s] = good ? r[s] / nrm : 0.f;
+    for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[kb][e] = good ? v[kb][e] / nrm : 0.f;
 
     int cell = -1;
     float gamma = 0.f;
     if (mode != 2) {
         cell = valid ? a.assign[row] : -1;
-        float c[DP / 2];
-        load_half<DP>(a.cent + (int64_t)(cell < 0 ? 0 : cell) * a.cent_pitch, cell >= 0, DP, 1,
-                      half * (DP / 2), c);
-        float g2 = 0.f;
+        float c[KB][8];
+        load_row_blocks<KB>(a.cent + (int64_t)(cell < 0 ? 0 : cell) * a.cent_pitch, cell >= 0, DP, 1, half, c);
 #pragma unroll
-        for (int s = 0; s < DP / 2; ++s) {
-            r[s] = r[s] - c[s];
-            g2 += r[s] * r[s];
-        }
-        g2 += __shfl_xor(g2, 32);
-        gamma = sqrtf(g2);
+        for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[kb][e] -= c[kb][e];
+        gamma = sqrtf(row_norm2<KB>(v));
+        const bool tiny = !(gamma > 1e-30f);
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[kb][e] = tiny ? 0.f : v[kb][e] / gamma;
     }
+    half8 bh[KB], bl[KB];
+#pragma unroll
+    for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            _Float16 h, l;
+            split_scaled(v[kb][e], h, l);
+            bh[kb][e] = h;
+            bl[kb][e] = l;
+        }
 
-    // u = Pi r, 32 output coordinates per tile.  The norm of the whole rotated vector is needed
-    // before any coordinate can be quantised, so the tiles are swept twice: once for |Pi r|^2 and
-    // once, bit-identically, to quantise.  That keeps one 32x32 accumulator live instead of d/32.
-    const float* a_base = pi_tile + j * Cfg::LDP + half * (DP / 2);
-    auto rotate_tile = [&](int t) -> floatx16 {
+    // u = Pi r^: 32 output coordinates per tile, every tile's accumulator kept until the norm is known
+    floatx16 acc[Cfg::NT];
+    const uint16_t* ah_base = ph + j * Cfg::LDH + 8 * half;
+    const uint16_t* al_base = pl + j * Cfg::LDH + 8 * half;
+#pragma unroll
+    for (int t = 0; t < Cfg::NT; ++t) {
         __syncthreads();
-        for (int e = tid; e < 32 * (DP / 4); e += 256) {
-            const int rr = e / (DP / 4), q4 = e % (DP / 4);
-            const float4 v = *reinterpret_cast<const float4*>(a.pi + (int64_t)(t * 32 + rr) * DP + q4 * 4);
-            float* dst = pi_tile + rr * Cfg::LDP + q4 * 4;
-            dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
+        for (int e = tid; e < 32 * (DP / 8); e += 256) {
+            const int rr = e / (DP / 8), c8 = e % (DP / 8);
+            const int64_t src = (int64_t)(t * 32 + rr) * DP + c8 * 8;
+            *reinterpret_cast<uint4*>(ph + rr * Cfg::LDH + c8 * 8) = *reinterpret_cast<const uint4*>(a.pi_h + src);
+            *reinterpret_cast<uint4*>(pl + rr * Cfg::LDH + c8 * 8) = *reinterpret_cast<const uint4*>(a.pi_l + src);
         }
         __syncthreads();
-        floatx16 acc;
 #pragma unroll
-        for (int q = 0; q < 16; ++q) acc[q] = 0.f;
+        for (int q = 0; q < 16; ++q) acc[t][q] = 0.f;
 #pragma unroll
-        for (int s = 0; s < DP / 2; ++s)
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a_base[s], r[s], acc, 0, 0, 0);
-        return acc;
-    };
+        for (int kb = 0; kb < KB; ++kb) {
+            const half8 ah = *reinterpret_cast<const half8*>(ah_base + 16 * kb);
+            const half8 al = *reinterpret_cast<const half8*>(al_base + 16 * kb);
+            acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah, bh[kb], acc[t], 0, 0, 0);
+            acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah, bl[kb], acc[t], 0, 0, 0);
+            acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(al, bh[kb], acc[t], 0, 0, 0);
+        }
+    }
+    constexpr float kUnscale = 1.f / (kSplitScale * kSplitScale);
 
     if (mode == 2) {
-#pragma unroll 1
-        for (int t = 0; t < Cfg::NT; ++t) {
-            const floatx16 acc = rotate_tile(t);
-            if (valid) {
+        if (valid) {
+#pragma unroll
+            for (int t = 0; t < Cfg::NT; ++t)
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
-                    float4 o = make_float4(acc[4 * g], acc[4 * g + 1], acc[4 * g + 2], acc[4 * g + 3]);
+                    const float4 o = make_float4(acc[t][4 * g] * kUnscale, acc[t][4 * g + 1] * kUnscale,
+                                                 acc[t][4 * g + 2] * kUnscale, acc[t][4 * g + 3] * kUnscale);
                     const int64_t at = row * (int64_t)DP + t * 32 + 8 * g + 4 * half;
                     *reinterpret_cast<float4*>(a.zout + at) = o;
                     if (a.zh_out) {
-                        const float v[4] = {o.x, o.y, o.z, o.w};
+                        const float z[4] = {o.x, o.y, o.z, o.w};
                         uint16_t h[4], l[4];
 #pragma unroll
                         for (int e = 0; e < 4; ++e) {
-                            const float V = v[e] * kSplitScale;
-                            const _Float16 hi = (_Float16)V;
-                            const _Float16 lo = (_Float16)(V - (float)hi);
+                            _Float16 hi, lo;
+                            split_scaled(z[e], hi, lo);
                             h[e] = __builtin_bit_cast(uint16_t, hi);
                             l[e] = __builtin_bit_cast(uint16_t, lo);
                         }
@@ -146,34 +141,30 @@ __global__ __launch_bounds__(256, 2) void k_encode(int mode, EncodeArgs a, int v
                         *reinterpret_cast<uint2*>(a.zl_out + at) = make_uint2(l[0] | ((uint32_t)l[1] << 16), l[2] | ((uint32_t)l[3] << 16));
                     }
                 }
-            }
         }
         return;
     }
 
-    // |Pi r| (rows of Pi beyond d are zero, so padded coordinates add nothing)
+    // |Pi r^| in the accumulators' scale (rows of Pi beyond d are zero, so padded coordinates add nothing)
     float u2 = 0.f;
-#pragma unroll 1
-    for (int t = 0; t < Cfg::NT; ++t) {
-        const floatx16 acc = rotate_tile(t);
 #pragma unroll
-        for (int q = 0; q < 16; ++q) u2 += acc[q] * acc[q];
-    }
+    for (int t = 0; t < Cfg::NT; ++t)
+#pragma unroll
+        for (int q = 0; q < 16; ++q) u2 += acc[t][q] * acc[t][q];
     u2 += __shfl_xor(u2, 32);
     const float un = sqrtf(u2);
     const bool degenerate = !(un > 1e-30f);
 
     // quantise: code = #{i : rho >= tau_i}, by bisection over the ascending boundaries
     uint8_t* my_codes = code_s + wave * (32 * DP) + j * DP;
-#pragma unroll 1
+#pragma unroll
     for (int t = 0; t < Cfg::NT; ++t) {
-        const floatx16 acc = rotate_tile(t);
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
             uint32_t packed = 0;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const float rho = degenerate ? 0.f : acc[4 * g + e] / un;
+                const float rho = degenerate ? 0.f : acc[t][4 * g + e] / un;
                 int code = 0;
 #pragma unroll
                 for (int lvl = 7; lvl >= 0; --lvl) {       // straight-line bisection, levels above b skipped

@@ -53,14 +53,15 @@ hipError_t launch_coarse(int mode, const float* x, int64_t n, int d, const uint1
 // hi[i], lo[i] = split float16 form of src[i]
 hipError_t launch_split_rows(const float* src, int64_t count, uint16_t* hi, uint16_t* lo, hipStream_t st);
 
-// Rotation family.  pi: [DP][DP] zero padded with DP = rot_dp(d); tau: 2^b - 1 boundaries.
+// Rotation family.  pi_h/pi_l: split form of Pi, [DP][DP] zero padded, DP = rot_dp(d); tau: 2^b - 1 boundaries.
 // mode 0: residual -> rotate -> normalise -> quantise -> pack into the list store at slot[i]
 // mode 1: same, but write unpacked codes / fp16 norms to flat arrays (any may be null)
 // mode 2: z_i = Pi x~_i written to zout[i*DP + j] (no centroid, no quantiser)
 struct EncodeArgs {
     const float* x; int64_t n; int d; int b;
     const float* cent; int cent_pitch;
-    const float* pi; const float* tau;
+    const uint16_t* pi_h; const uint16_t* pi_l;   // split float16 form of Pi, [DP][DP]
+    const float* tau;
     const int32_t* assign;
     // mode 0
     ListStore store; const int64_t* slot; const int64_t* labels; int64_t label_base;
