@@ -99,7 +99,7 @@ struct ivftq_index {
     DevBuf w_S, w_probe, w_coarse, w_z, w_candoff, w_scores;
     DevBuf w_sums, w_counts, w_zero, w_rows, w_dst, w_obj;
     DevBuf w_zh, w_zl;
-    DevBuf w_first, w_fscores, w_fids, w_key, w_pairs, w_pairoff, w_tileoff, w_cscore, w_cslot, w_ccnt, w_gate;
+    DevBuf w_first, w_fscores, w_fids, w_pairs, w_pairoff, w_tileoff, w_cscore, w_cslot, w_ccnt, w_gate;
     int search_mode = 0;   // 0 auto, 1 streaming scan only, 2 batched scan whenever the shape allows
     int64_t ws_limit = (int64_t)4 << 30;
     bool prof_on = false;
@@ -120,7 +120,7 @@ struct ivftq_index {
         for (DevBuf* bfr : {&cent, &cent_h, &cent_l, &pi_h, &pi_l, &bias, &pi, &cb, &tau, &codes, &gamma, &ids, &d_off, &d_size, &w_assign,
                             &w_slot, &w_hist, &w_count, &w_base, &w_flag, &w_best, &w_S, &w_probe, &w_coarse,
                             &w_z, &w_candoff, &w_scores, &w_sums, &w_counts, &w_zero, &w_rows, &w_dst, &w_obj,
-                            &w_first, &w_fscores, &w_fids, &w_key, &w_pairs, &w_pairoff, &w_tileoff, &w_cscore,
+                            &w_first, &w_fscores, &w_fids, &w_pairs, &w_pairoff, &w_tileoff, &w_cscore,
                             &w_cslot, &w_ccnt, &w_gate, &w_zh, &w_zl})
             bfr->release();
     }
@@ -785,19 +785,14 @@ ivftq_status ivftq_search(ivftq_index* ix, const float* q_dev, int64_t nq, int n
     HIP_TRY(ix->w_candoff.ensure((size_t)qc * (nprobe + 1) * sizeof(int32_t)));
     HIP_TRY(ix->w_z.ensure((size_t)qc * ix->dp * sizeof(float)));
     const int64_t n_pairs = qc * nprobe;
-    const int64_t seg_len = round_up64((n_pairs + 1023) / 1024, 64);
-    const int nseg = (int)((n_pairs + seg_len - 1) / seg_len);
     if (batched) {
         HIP_TRY(ix->w_zh.ensure((size_t)qc * ix->dp * sizeof(uint16_t)));
         HIP_TRY(ix->w_zl.ensure((size_t)qc * ix->dp * sizeof(uint16_t)));
         HIP_TRY(ix->w_first.ensure((size_t)qc * sizeof(int32_t)));
         HIP_TRY(ix->w_fscores.ensure((size_t)qc * k * sizeof(float)));
         HIP_TRY(ix->w_fids.ensure((size_t)qc * k * sizeof(int64_t)));
-        HIP_TRY(ix->w_key.ensure((size_t)n_pairs * sizeof(int32_t)));
         HIP_TRY(ix->w_pairs.ensure((size_t)n_pairs * sizeof(int32_t)));
-        HIP_TRY(ix->w_slot.ensure((size_t)n_pairs * sizeof(int64_t)));
-        HIP_TRY(ix->w_hist.ensure((size_t)nseg * ix->nlist * sizeof(uint32_t)));
-        HIP_TRY(ix->w_count.ensure((size_t)ix->nlist * sizeof(uint32_t)));
+        HIP_TRY(ix->w_count.ensure((size_t)2 * ix->nlist * sizeof(uint32_t)));
         HIP_TRY(ix->w_pairoff.ensure((size_t)(ix->nlist + 1) * sizeof(int64_t)));
         HIP_TRY(ix->w_tileoff.ensure((size_t)(ix->nlist + 1) * sizeof(int32_t)));
         HIP_TRY(ix->w_cscore.ensure((size_t)qc * cap * sizeof(float)));
@@ -832,6 +827,7 @@ ivftq_status ivftq_search(ivftq_index* ix, const float* q_dev, int64_t nq, int n
         sa.q_begin = 0;
         sa.list_off = ix->d_off.as<int64_t>(); sa.ids = ix->ids.as<int64_t>();
         sa.out_vals = scores_dev + q0 * k; sa.out_i64 = ids_dev + q0 * k;
+        sa.m_bound = (int)m_stride;
 
         if (!batched) {
             HIP_TRY(timed(ix, st, P_LIST_SCAN, [&] { return stream_scan(nullptr, nullptr, 0); }));
@@ -843,18 +839,15 @@ ivftq_status ivftq_search(ivftq_index* ix, const float* q_dev, int64_t nq, int n
         HIP_TRY(timed(ix, st, P_LIST_SCAN, [&] { return stream_scan(first, nullptr, 2); }));
         SelectArgs s1 = sa;
         s1.p_limit = first; s1.out_vals = ix->w_fscores.as<float>(); s1.out_i64 = ix->w_fids.as<int64_t>();
+        s1.m_bound = (int)std::min<int64_t>(m_stride, (int64_t)k + sizes[0]);   // shortest prefix with k vectors
         HIP_TRY(timed(ix, st, P_SELECT_TOPK, [&] { return launch_select(1, s1, st); }));
         // 2. remaining (query, probe) pairs grouped by list, in a fixed order
         const int64_t np_items = cnt * nprobe;
-        const int64_t sl = round_up64((np_items + 1023) / 1024, 64);
-        const int ns = (int)((np_items + sl - 1) / sl);
         HIP_TRY(timed(ix, st, P_PAIR_GROUP, [&] {
-            hipError_t e = launch_pair_keys(ix->w_probe.as<int32_t>(), first, cnt, nprobe, ix->w_key.as<int32_t>(), st);
-            if (e == hipSuccess) e = launch_segment_hist(ix->w_key.as<int32_t>(), np_items, sl, ns, ix->nlist, ix->w_hist.as<uint32_t>(), st);
-            if (e == hipSuccess) e = launch_segment_scan(ix->w_hist.as<uint32_t>(), ns, ix->nlist, ix->w_count.as<uint32_t>(), st);
-            if (e == hipSuccess) e = launch_pair_prefix(ix->w_count.as<uint32_t>(), ix->nlist, tq, ix->w_pairoff.as<int64_t>(), ix->w_tileoff.as<int32_t>(), st);
-            if (e == hipSuccess) e = launch_stable_rank(ix->w_key.as<int32_t>(), np_items, sl, ns, ix->nlist, ix->w_hist.as<uint32_t>(), ix->w_pairoff.as<int64_t>(), ix->w_slot.as<int64_t>(), st);
-            if (e == hipSuccess) e = launch_scatter_pairs(ix->w_slot.as<int64_t>(), np_items, ix->w_pairs.as<int32_t>(), st);
+            hipError_t e = launch_pair_grouping(ix->w_probe.as<int32_t>(), first, cnt, nprobe, ix->nlist, tq,
+                                                ix->w_count.as<uint32_t>(), ix->w_count.as<uint32_t>() + ix->nlist,
+                                                ix->w_pairoff.as<int64_t>(), ix->w_tileoff.as<int32_t>(),
+                                                ix->w_pairs.as<int32_t>(), st);
             if (e == hipSuccess) e = launch_fill_u32(ix->w_ccnt.as<uint32_t>(), cnt, 0u, st);
             return e; }));
         // 3. matrix-core scan of those pairs against the thresholds

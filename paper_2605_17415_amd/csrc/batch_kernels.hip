@@ -23,29 +23,32 @@ typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 namespace {
 
 // ---- regrouping (query, probe) pairs by list ---------------------------------------------------
+//
+// Pairs are bucketed by list with atomic counters.  The order of the pairs inside a bucket (and so
+// which tile a query lands in) may change from run to run; results do not, because a score depends
+// only on its own (query, vector) pair and the final merge orders candidates by (score, label).
 
-// key[q*np + p] = list probed, or -1 for the probes the streaming scan already covered
-__global__ void k_pair_keys(const int32_t* __restrict__ probe, const int32_t* __restrict__ first, int64_t nq,
-                            int np, int32_t* __restrict__ key) {
+// count[l] += 1 for every pair (q, p >= first[q]) probing list l
+__global__ void k_pair_count(const int32_t* __restrict__ probe, const int32_t* __restrict__ first, int64_t nq,
+                             int np, uint32_t* __restrict__ count) {
     const int64_t it = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (it >= nq * np) return;
-    const int64_t q = it / np;
-    const int p = (int)(it % np);
-    key[it] = (p >= first[q]) ? probe[it] : -1;
+    if ((int)(it % np) >= first[it / np]) atomicAdd(&count[probe[it]], 1u);
 }
 
-// pair_off[l] = first pair of list l (as int64, the form the ranking kernel takes);
-// tile_off[l] = first workgroup tile of list l, tile_off[L] = number of tiles.  One workgroup.
+// pair_off[l] = first pair of list l; tile_off[l] = first workgroup tile of list l (tile_off[L] =
+// number of tiles); cursor[l] = 0.  One workgroup.
 __global__ __launch_bounds__(1024) void k_pair_prefix(const uint32_t* __restrict__ count, int L, int tq,
                                                       int64_t* __restrict__ pair_off,
-                                                      int32_t* __restrict__ tile_off) {
+                                                      int32_t* __restrict__ tile_off,
+                                                      uint32_t* __restrict__ cursor) {
     __shared__ uint32_t part_c[1024], part_t[1024];
     const int tid = threadIdx.x;
     const int per = (L + 1023) / 1024;
     uint32_t c = 0, t = 0;
     for (int e = 0; e < per; ++e) {
         const int l = tid * per + e;
-        if (l < L) { c += count[l]; t += (count[l] + tq - 1) / tq; }
+        if (l < L) { c += count[l]; t += (count[l] + tq - 1) / tq; cursor[l] = 0; }
     }
     part_c[tid] = c;
     part_t[tid] = t;
@@ -70,11 +73,14 @@ __global__ __launch_bounds__(1024) void k_pair_prefix(const uint32_t* __restrict
     if (tid == 1023) { pair_off[L] = part_c[1023]; tile_off[L] = (int32_t)part_t[1023]; }
 }
 
-__global__ void k_scatter_pairs(const int64_t* __restrict__ slot, int64_t n, int32_t* __restrict__ pairs) {
+__global__ void k_pair_scatter(const int32_t* __restrict__ probe, const int32_t* __restrict__ first, int64_t nq,
+                               int np, const int64_t* __restrict__ pair_off, uint32_t* __restrict__ cursor,
+                               int32_t* __restrict__ pairs) {
     const int64_t it = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (it >= n) return;
-    const int64_t s = slot[it];
-    if (s >= 0) pairs[s] = (int32_t)it;
+    if (it >= nq * np) return;
+    if ((int)(it % np) < first[it / np]) return;
+    const int l = probe[it];
+    pairs[pair_off[l] + atomicAdd(&cursor[l], 1u)] = (int32_t)it;
 }
 
 // ---- the batched scan ----------------------------------------------------------------------------
@@ -369,21 +375,17 @@ int batch_tile_queries(int d, int b) {
     return 0;
 }
 
-hipError_t launch_pair_keys(const int32_t* probe, const int32_t* first, int64_t nq, int np, int32_t* key,
-                            hipStream_t st) {
+hipError_t launch_pair_grouping(const int32_t* probe, const int32_t* first, int64_t nq, int np, int L, int tq,
+                               uint32_t* count, uint32_t* cursor, int64_t* pair_off, int32_t* tile_off,
+                               int32_t* pairs, hipStream_t st) {
     const int64_t n = nq * np;
-    hipLaunchKernelGGL(k_pair_keys, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, probe, first, nq, np, key);
-    return hipGetLastError();
-}
-
-hipError_t launch_pair_prefix(const uint32_t* count, int L, int tq, int64_t* pair_off, int32_t* tile_off,
-                              hipStream_t st) {
-    hipLaunchKernelGGL(k_pair_prefix, dim3(1), dim3(1024), 0, st, count, L, tq, pair_off, tile_off);
-    return hipGetLastError();
-}
-
-hipError_t launch_scatter_pairs(const int64_t* slot, int64_t n, int32_t* pairs, hipStream_t st) {
-    hipLaunchKernelGGL(k_scatter_pairs, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, slot, n, pairs);
+    if (n <= 0) return hipSuccess;
+    hipError_t e = launch_fill_u32(count, L, 0u, st);
+    if (e != hipSuccess) return e;
+    const unsigned blocks = (unsigned)((n + 255) / 256);
+    hipLaunchKernelGGL(k_pair_count, dim3(blocks), dim3(256), 0, st, probe, first, nq, np, count);
+    hipLaunchKernelGGL(k_pair_prefix, dim3(1), dim3(1024), 0, st, count, L, tq, pair_off, tile_off, cursor);
+    hipLaunchKernelGGL(k_pair_scatter, dim3(blocks), dim3(256), 0, st, probe, first, nq, np, pair_off, cursor, pairs);
     return hipGetLastError();
 }
 

@@ -137,6 +137,8 @@ struct SelectArgs {
     const int32_t* gate;      // only rows with gate[q] != 0 are processed (null = all)
     const int64_t* list_off; const int64_t* ids;
     float* out_vals; int32_t* out_i32; int64_t* out_i64;
+    int m_bound;      // mode 1: host-side upper bound of any row's length (0 = unknown); picks the kernel
+    int small_cap;    // set by the launcher
 };
 hipError_t launch_select(int mode, const SelectArgs& a, hipStream_t st);
 
@@ -146,14 +148,12 @@ hipError_t launch_select(int mode, const SelectArgs& a, hipStream_t st);
 // (the streaming scan is used instead).
 int batch_tile_queries(int d, int b);
 
-// key[q*np + p] = probed list, or -1 when p < first[q]
-hipError_t launch_pair_keys(const int32_t* probe, const int32_t* first, int64_t nq, int np, int32_t* key,
-                            hipStream_t st);
-// exclusive prefixes over lists of the pair counts and of ceil(count / tq); both arrays have L+1 entries
-hipError_t launch_pair_prefix(const uint32_t* count, int L, int tq, int64_t* pair_off, int32_t* tile_off,
-                              hipStream_t st);
-// pairs[slot[it]] = it for every item with slot >= 0
-hipError_t launch_scatter_pairs(const int64_t* slot, int64_t n, int32_t* pairs, hipStream_t st);
+// Buckets the pairs (q, p >= first[q]) by probed list: pairs[pair_off[l] ...] holds the flat pair
+// numbers q*np + p of list l; tile_off[l] counts workgroup tiles of tq queries (both arrays have L+1
+// entries).  count and cursor are scratch arrays of L entries.
+hipError_t launch_pair_grouping(const int32_t* probe, const int32_t* first, int64_t nq, int np, int L, int tq,
+                                uint32_t* count, uint32_t* cursor, int64_t* pair_off, int32_t* tile_off,
+                                int32_t* pairs, hipStream_t st);
 
 struct BatchScanArgs {
     const uint16_t* zh; const uint16_t* zl; int z_pitch;   // split rotated queries, [nq][z_pitch] halves

@@ -28,17 +28,30 @@ __global__ __launch_bounds__(256) void k_segment_hist(const int32_t* __restrict_
     for (int l = threadIdx.x; l < L; l += 256) seg_hist[(int64_t)blockIdx.x * L + l] = hist[l];
 }
 
-__global__ __launch_bounds__(256) void k_segment_scan(uint32_t* __restrict__ seg_hist, int nseg, int L,
-                                                      uint32_t* __restrict__ batch_count) {
-    const int l = blockIdx.x * 256 + threadIdx.x;
-    if (l >= L) return;
+// Column-wise exclusive running sum over segments.  A workgroup takes 64 lists; its 16 wavefronts
+// each take a sixteenth of the segments, so the two passes over a column run 16-wide.
+__global__ __launch_bounds__(1024) void k_segment_scan(uint32_t* __restrict__ seg_hist, int nseg, int L,
+                                                       uint32_t* __restrict__ batch_count) {
+    __shared__ uint32_t part_sum[16][64];
+    const int li = threadIdx.x & 63, part = threadIdx.x >> 6;
+    const int l = blockIdx.x * 64 + li;
+    const int chunk = (nseg + 15) / 16;
+    const int s0 = part * chunk, s1 = (s0 + chunk < nseg) ? s0 + chunk : nseg;
+    uint32_t sum = 0;
+    if (l < L)
+        for (int s = s0; s < s1; ++s) sum += seg_hist[(int64_t)s * L + l];
+    part_sum[part][li] = sum;
+    __syncthreads();
     uint32_t run = 0;
-    for (int s = 0; s < nseg; ++s) {
-        const uint32_t t = seg_hist[(int64_t)s * L + l];
-        seg_hist[(int64_t)s * L + l] = run;
-        run += t;
+    for (int p = 0; p < part; ++p) run += part_sum[p][li];
+    if (l < L) {
+        for (int s = s0; s < s1; ++s) {
+            const uint32_t t = seg_hist[(int64_t)s * L + l];
+            seg_hist[(int64_t)s * L + l] = run;
+            run += t;
+        }
+        if (part == 15) batch_count[l] = run;
     }
-    batch_count[l] = run;
 }
 
 // One wavefront walks its segment 64 rows at a time, in order.
@@ -214,7 +227,7 @@ hipError_t launch_segment_hist(const int32_t* assign, int64_t n, int64_t seg_len
 }
 
 hipError_t launch_segment_scan(uint32_t* seg_hist, int nseg, int L, uint32_t* batch_count, hipStream_t st) {
-    hipLaunchKernelGGL(k_segment_scan, dim3((L + 255) / 256), dim3(256), 0, st, seg_hist, nseg, L, batch_count);
+    hipLaunchKernelGGL(k_segment_scan, dim3((L + 63) / 64), dim3(1024), 0, st, seg_hist, nseg, L, batch_count);
     return hipGetLastError();
 }
 

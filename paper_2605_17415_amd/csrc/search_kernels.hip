@@ -269,6 +269,104 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a) {
     }
 }
 
+// ---- selection for short rows: one wavefront per row ------------------------------------------
+//
+// For rows of at most kSmallM values and k <= 64 the k largest are taken one at a time: every lane
+// keeps the best of its own strided share in registers, a butterfly over the wavefront finds the
+// overall best (larger value, then smaller column), and only the lane that owned it rescans its
+// share.  The winners come out ordered by (value desc, column asc); a final bitonic pass over the
+// lanes re-orders equal values by label.
+
+constexpr int kSmallM = 4096;
+
+template <int MODE>
+__global__ __launch_bounds__(256) void k_select_small(SelectArgs a) {
+    extern __shared__ float s_vals[];                    // [4 waves][m_cap]
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t row = (int64_t)blockIdx.x * 4 + wave;
+    if (row >= a.rows) return;
+    const int64_t q = a.q_begin + row;
+    if (a.gate && !a.gate[q]) return;
+    const int m = (MODE == 0) ? a.m_fixed
+                              : a.cand_off[q * (a.np + 1) + (a.p_limit ? a.p_limit[q] : a.np)];
+    const int k = a.k;
+    const int take = m < k ? m : k;
+    const float* vals = a.vals + row * a.stride;
+    float* mine = s_vals + wave * a.small_cap;
+    const float ninf = -__builtin_inff();
+
+    float bv = ninf;
+    int bi = 0x7FFFFFFF;
+    for (int i = lane; i < m; i += 64) {
+        const float v = vals[i];
+        mine[i] = v;
+        if (v > bv) { bv = v; bi = i; }                  // ascending i: first maximum wins
+    }
+    __builtin_amdgcn_wave_barrier();
+
+    float out_v = ninf;                                  // lane r ends up with the r-th winner
+    int out_c = -1;
+    for (int r = 0; r < take; ++r) {
+        float wv = bv;
+        int wi = bi;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            const float ov = __shfl_xor(wv, o);
+            const int oi = __shfl_xor(wi, o);
+            if (ov > wv || (ov == wv && oi < wi)) { wv = ov; wi = oi; }
+        }
+        if (wi == 0x7FFFFFFF) break;                     // nothing left but NaNs
+        if (lane == r) { out_v = wv; out_c = wi; }
+        if ((wi & 63) == lane) {                         // the owner removes it and rescans its share
+            mine[wi] = ninf;
+            bv = ninf;
+            bi = 0x7FFFFFFF;
+            for (int i = lane; i < m; i += 64) {
+                const float v = mine[i];
+                if (v > bv) { bv = v; bi = i; }
+            }
+            if (bv == ninf) bi = 0x7FFFFFFF;             // share exhausted
+        }
+    }
+
+    // labels, then order equal values by label
+    int64_t lab = INT64_MAX;
+    if (out_c >= 0) {
+        if (MODE == 0) {
+            lab = out_c;
+        } else {
+            const int32_t* off = a.cand_off + q * (a.np + 1);
+            int lo = 0, hi = a.np;
+            while (hi - lo > 1) {
+                const int mid = (lo + hi) >> 1;
+                if (off[mid] <= out_c) lo = mid; else hi = mid;
+            }
+            lab = a.ids[a.list_off[a.probe[q * a.np + lo]] + (out_c - off[lo])];
+        }
+    }
+    uint32_t key = out_c >= 0 ? order_key(out_v) : 0u;
+#pragma unroll
+    for (int size = 2; size <= 64; size <<= 1) {
+#pragma unroll
+        for (int stride = size >> 1; stride > 0; stride >>= 1) {
+            const uint32_t ok = __shfl_xor(key, stride);
+            const int64_t ol = __shfl_xor(lab, stride);
+            const float ov = __shfl_xor(out_v, stride);
+            const bool lower = (lane & stride) == 0;     // this lane holds the earlier position of the pair
+            const bool up = (lane & size) == 0;          // block sorted into final order (best first)
+            const bool mine_first = (key > ok) || (key == ok && lab <= ol);
+            const bool keep = (lower == up) ? mine_first : !mine_first;
+            if (!keep) { key = ok; lab = ol; out_v = ov; }
+        }
+    }
+    if (lane < k) {
+        const bool real = key != 0u;
+        if (a.out_vals) a.out_vals[row * k + lane] = real ? out_v : ninf;
+        if (MODE == 0) { if (a.out_i32) a.out_i32[row * k + lane] = real ? (int32_t)lab : -1; }
+        else { if (a.out_i64) a.out_i64[row * k + lane] = real ? lab : -1; }
+    }
+}
+
 }  // namespace
 
 hipError_t launch_cand_offsets(const int32_t* probe, int64_t nq, int np, const int32_t* list_size,
@@ -307,8 +405,19 @@ hipError_t launch_list_scan(const float* z, int z_pitch, int d, int b, const flo
     return hipGetLastError();
 }
 
-hipError_t launch_select(int mode, const SelectArgs& a, hipStream_t st) {
-    if (a.rows <= 0) return hipSuccess;
+hipError_t launch_select(int mode, const SelectArgs& a_in, hipStream_t st) {
+    if (a_in.rows <= 0) return hipSuccess;
+    SelectArgs a = a_in;
+    // short rows and small k: the one-wavefront-per-row kernel
+    const int m_bound = mode == 0 ? a.m_fixed : a.m_bound;
+    if (a.k <= 64 && m_bound > 0 && m_bound <= kSmallM) {
+        a.small_cap = (m_bound + 3) & ~3;
+        const size_t lds = (size_t)4 * a.small_cap * sizeof(float);
+        const unsigned blocks = (unsigned)((a.rows + 3) / 4);
+        if (mode == 0) hipLaunchKernelGGL(k_select_small<0>, dim3(blocks), dim3(256), lds, st, a);
+        else hipLaunchKernelGGL(k_select_small<1>, dim3(blocks), dim3(256), lds, st, a);
+        return hipGetLastError();
+    }
     int kpad = 1;
     while (kpad < a.k) kpad <<= 1;
     const size_t lds = (256 + 8 + 4) * 4 + (size_t)kpad * 8 + 8 + (size_t)kpad * 8;
