@@ -62,12 +62,12 @@ struct DevBuf {
 // kernel classes for the optional per-launch timing
 enum ProfId { P_ASSIGN, P_COARSE_SCORES, P_ENCODE, P_ROTATE_Q, P_SEG_HIST, P_SEG_SCAN, P_RANK, P_PACK,
               P_COPY_LISTS, P_SELECT_PROBE, P_CAND_OFF, P_LIST_SCAN, P_SELECT_TOPK, P_KMEANS_UPDATE,
-              P_PAIR_GROUP, P_BATCH_SCAN, P_MERGE, P_COUNT };
+              P_PAIR_GROUP, P_BATCH_FIRST, P_BATCH_SCAN, P_MERGE, P_COUNT };
 const char* const kProfNames[P_COUNT] = {"coarse_assign", "coarse_scores", "encode_rotate_quantise_pack",
                                          "rotate_queries", "segment_hist", "segment_scan", "stable_rank",
                                          "pack_scatter", "copy_lists", "select_probes", "cand_offsets",
                                          "list_scan", "select_topk", "kmeans_update", "pair_grouping",
-                                         "batch_scan", "merge_topk"};
+                                         "batch_scan_nearest", "batch_scan", "merge_topk"};
 struct ProfRec { int id; hipEvent_t a, b; };
 // Timing events are recycled process-wide: creating one per launch costs more than the launch.
 std::mutex g_event_mutex;
@@ -792,9 +792,9 @@ ivftq_status ivftq_search(ivftq_index* ix, const float* q_dev, int64_t nq, int n
         HIP_TRY(ix->w_fscores.ensure((size_t)qc * k * sizeof(float)));
         HIP_TRY(ix->w_fids.ensure((size_t)qc * k * sizeof(int64_t)));
         HIP_TRY(ix->w_pairs.ensure((size_t)n_pairs * sizeof(int32_t)));
-        HIP_TRY(ix->w_count.ensure((size_t)2 * ix->nlist * sizeof(uint32_t)));
-        HIP_TRY(ix->w_pairoff.ensure((size_t)(ix->nlist + 1) * sizeof(int64_t)));
-        HIP_TRY(ix->w_tileoff.ensure((size_t)(ix->nlist + 1) * sizeof(int32_t)));
+        HIP_TRY(ix->w_count.ensure((size_t)4 * ix->nlist * sizeof(uint32_t)));
+        HIP_TRY(ix->w_pairoff.ensure((size_t)(2 * ix->nlist + 1) * sizeof(int64_t)));
+        HIP_TRY(ix->w_tileoff.ensure((size_t)(2 * ix->nlist + 1) * sizeof(int32_t)));
         HIP_TRY(ix->w_cscore.ensure((size_t)qc * cap * sizeof(float)));
         HIP_TRY(ix->w_cslot.ensure((size_t)qc * cap * sizeof(int64_t)));
         HIP_TRY(ix->w_ccnt.ensure((size_t)qc * sizeof(int32_t)));
@@ -835,33 +835,36 @@ ivftq_status ivftq_search(ivftq_index* ix, const float* q_dev, int64_t nq, int n
             continue;
         }
 
-        // 1. exact scan of each query's nearest lists: their top-k and, from it, the threshold
-        HIP_TRY(timed(ix, st, P_LIST_SCAN, [&] { return stream_scan(first, nullptr, 2); }));
-        SelectArgs s1 = sa;
-        s1.p_limit = first; s1.out_vals = ix->w_fscores.as<float>(); s1.out_i64 = ix->w_fids.as<int64_t>();
-        s1.m_bound = (int)std::min<int64_t>(m_stride, (int64_t)k + sizes[0]);   // shortest prefix with k vectors
-        HIP_TRY(timed(ix, st, P_SELECT_TOPK, [&] { return launch_select(1, s1, st); }));
-        // 2. remaining (query, probe) pairs grouped by list, in a fixed order
+        // 1. (query, probe) pairs bucketed by list; the nearest lists of each query in their own buckets
         const int64_t np_items = cnt * nprobe;
         HIP_TRY(timed(ix, st, P_PAIR_GROUP, [&] {
             hipError_t e = launch_pair_grouping(ix->w_probe.as<int32_t>(), first, cnt, nprobe, ix->nlist, tq,
-                                                ix->w_count.as<uint32_t>(), ix->w_count.as<uint32_t>() + ix->nlist,
+                                                ix->w_count.as<uint32_t>(), ix->w_count.as<uint32_t>() + 2 * ix->nlist,
                                                 ix->w_pairoff.as<int64_t>(), ix->w_tileoff.as<int32_t>(),
                                                 ix->w_pairs.as<int32_t>(), st);
             if (e == hipSuccess) e = launch_fill_u32(ix->w_ccnt.as<uint32_t>(), cnt, 0u, st);
             return e; }));
-        // 3. matrix-core scan of those pairs against the thresholds
         BatchScanArgs ba{};
         ba.zh = ix->w_zh.as<uint16_t>(); ba.zl = ix->w_zl.as<uint16_t>(); ba.z_pitch = ix->dp;
         ba.cb = ix->cb.as<float>();
         ba.pairs = ix->w_pairs.as<int32_t>(); ba.pair_off = ix->w_pairoff.as<int64_t>();
         ba.tile_off = ix->w_tileoff.as<int32_t>();
         ba.coarse = ix->w_coarse.as<float>();
-        ba.thresh = ix->w_fscores.as<float>() + (k - 1); ba.thresh_stride = k;
         ba.store = ix->store(); ba.np = nprobe; ba.L = ix->nlist;
         ba.cand_score = ix->w_cscore.as<float>(); ba.cand_slot = ix->w_cslot.as<int64_t>();
         ba.cand_cnt = ix->w_ccnt.as<int32_t>(); ba.cap = cap;
+        ba.scores = ix->w_scores.as<float>(); ba.m_stride = m_stride; ba.cand_off = ix->w_candoff.as<int32_t>();
         const int max_tiles = (int)(np_items / tq) + ix->nlist;
+        // 2. every score of the nearest lists, then their top-k: the k-th is the query's threshold
+        ba.dense = 1; ba.bucket_lo = 0; ba.bucket_hi = ix->nlist;
+        HIP_TRY(timed(ix, st, P_BATCH_FIRST, [&] { return launch_batch_scan(ba, ix->d, ix->b, max_tiles, st); }));
+        SelectArgs s1 = sa;
+        s1.p_limit = first; s1.out_vals = ix->w_fscores.as<float>(); s1.out_i64 = ix->w_fids.as<int64_t>();
+        s1.m_bound = (int)std::min<int64_t>(m_stride, (int64_t)k + sizes[0]);   // shortest prefix with k vectors
+        HIP_TRY(timed(ix, st, P_SELECT_TOPK, [&] { return launch_select(1, s1, st); }));
+        // 3. the other lists against the thresholds
+        ba.dense = 0; ba.bucket_lo = ix->nlist; ba.bucket_hi = 2 * ix->nlist;
+        ba.thresh = ix->w_fscores.as<float>() + (k - 1); ba.thresh_stride = k;
         HIP_TRY(timed(ix, st, P_BATCH_SCAN, [&] { return launch_batch_scan(ba, ix->d, ix->b, max_tiles, st); }));
         // 4. merge; a query whose candidate list overflowed is redone by the exact streaming scan
         MergeArgs ma{};

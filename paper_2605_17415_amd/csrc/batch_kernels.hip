@@ -24,20 +24,21 @@ namespace {
 
 // ---- regrouping (query, probe) pairs by list ---------------------------------------------------
 //
-// Pairs are bucketed by list with atomic counters.  The order of the pairs inside a bucket (and so
+// Pairs are bucketed with atomic counters: bucket l holds the pairs (q, p < first[q]) of list l
+// (each query's nearest lists, scanned first to find its threshold), bucket L + l the others.  The order of the pairs inside a bucket (and so
 // which tile a query lands in) may change from run to run; results do not, because a score depends
 // only on its own (query, vector) pair and the final merge orders candidates by (score, label).
 
-// count[l] += 1 for every pair (q, p >= first[q]) probing list l
 __global__ void k_pair_count(const int32_t* __restrict__ probe, const int32_t* __restrict__ first, int64_t nq,
-                             int np, uint32_t* __restrict__ count) {
+                             int np, int L, uint32_t* __restrict__ count) {
     const int64_t it = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (it >= nq * np) return;
-    if ((int)(it % np) >= first[it / np]) atomicAdd(&count[probe[it]], 1u);
+    const int late = (int)(it % np) >= first[it / np];
+    atomicAdd(&count[probe[it] + (late ? L : 0)], 1u);
 }
 
-// pair_off[l] = first pair of list l; tile_off[l] = first workgroup tile of list l (tile_off[L] =
-// number of tiles); cursor[l] = 0.  One workgroup.
+// Over the 2L buckets: pair_off[b] = first pair of bucket b; tile_off[b] = first workgroup tile of
+// bucket b (entry 2L = totals); cursor[b] = 0.  One workgroup; L here is the number of buckets.
 __global__ __launch_bounds__(1024) void k_pair_prefix(const uint32_t* __restrict__ count, int L, int tq,
                                                       int64_t* __restrict__ pair_off,
                                                       int32_t* __restrict__ tile_off,
@@ -74,13 +75,13 @@ __global__ __launch_bounds__(1024) void k_pair_prefix(const uint32_t* __restrict
 }
 
 __global__ void k_pair_scatter(const int32_t* __restrict__ probe, const int32_t* __restrict__ first, int64_t nq,
-                               int np, const int64_t* __restrict__ pair_off, uint32_t* __restrict__ cursor,
-                               int32_t* __restrict__ pairs) {
+                               int np, int L, const int64_t* __restrict__ pair_off,
+                               uint32_t* __restrict__ cursor, int32_t* __restrict__ pairs) {
     const int64_t it = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (it >= nq * np) return;
-    if ((int)(it % np) < first[it / np]) return;
-    const int l = probe[it];
-    pairs[pair_off[l] + atomicAdd(&cursor[l], 1u)] = (int32_t)it;
+    const int late = (int)(it % np) >= first[it / np];
+    const int bkt = probe[it] + (late ? L : 0);
+    pairs[pair_off[bkt] + atomicAdd(&cursor[bkt], 1u)] = (int32_t)it;
 }
 
 // ---- the batched scan ----------------------------------------------------------------------------
@@ -100,7 +101,7 @@ struct BatchCfg {
     static constexpr int TQ = NQ * 32;
     static constexpr int LDH = DP + 8;            // halves per panel row: 16-byte pad keeps b128 reads conflict free
     static constexpr int PT = 1 << (2 * B);       // entries of the code-pair tables
-    static constexpr size_t lds_bytes = (size_t)TQ * LDH * 2 * sizeof(uint16_t) + 3 * TQ * sizeof(float) + 2 * PT * 4;
+    static constexpr size_t lds_bytes = (size_t)TQ * LDH * 2 * sizeof(uint16_t) + 3 * TQ * sizeof(float) + 2 * PT * 4;   // panels + per-query words + pair tables
 };
 
 // WAVES = wavefronts per workgroup, OCC = wavefronts per SIMD the register budget is set for.
@@ -114,7 +115,7 @@ void k_batch_scan(BatchScanArgs a) {
     uint16_t* zh = reinterpret_cast<uint16_t*>(lds_raw);          // [TQ][LDH] hi parts of the rotated queries
     uint16_t* zl = zh + Cfg::TQ * Cfg::LDH;                         // [TQ][LDH] lo parts
     float* s_coarse = reinterpret_cast<float*>(zl + Cfg::TQ * Cfg::LDH);   // [TQ]
-    float* s_thr = s_coarse + Cfg::TQ;                              // [TQ]
+    float* s_thr = s_coarse + Cfg::TQ;                              // [TQ] threshold, or (dense) offset of the pair's scores
     int32_t* s_q = reinterpret_cast<int32_t*>(s_thr + Cfg::TQ);     // [TQ]
     uint32_t* tab_h = reinterpret_cast<uint32_t*>(s_q + Cfg::TQ);   // [PT] hi parts of a code pair, packed
     uint32_t* tab_l = tab_h + Cfg::PT;                              // [PT] lo parts
@@ -122,18 +123,19 @@ void k_batch_scan(BatchScanArgs a) {
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63, half = lane >> 5, jl = lane & 31;
 
-    // which (list, query tile) this workgroup owns
-    const int total_tiles = a.tile_off[a.L];
-    if ((int)blockIdx.x >= total_tiles) return;
-    int lo_l = 0, hi_l = a.L;                     // largest l with tile_off[l] <= blockIdx.x
+    // which (bucket, query tile) this workgroup owns, among the buckets [bucket_lo, bucket_hi)
+    const int my_tile = (int)blockIdx.x + a.tile_off[a.bucket_lo];
+    if (my_tile >= a.tile_off[a.bucket_hi]) return;
+    int lo_l = a.bucket_lo, hi_l = a.bucket_hi;   // largest bucket with tile_off[bucket] <= my_tile
     while (hi_l - lo_l > 1) {
         const int mid = (lo_l + hi_l) >> 1;
-        if (a.tile_off[mid] <= (int)blockIdx.x) lo_l = mid; else hi_l = mid;
+        if (a.tile_off[mid] <= my_tile) lo_l = mid; else hi_l = mid;
     }
-    const int l = lo_l;
-    const int tile = blockIdx.x - a.tile_off[l];
-    const int64_t pair0 = a.pair_off[l] + (int64_t)tile * Cfg::TQ;
-    const int64_t pair_end = a.pair_off[l + 1];
+    const int bkt = lo_l;
+    const int l = bkt >= a.L ? bkt - a.L : bkt;
+    const int tile = my_tile - a.tile_off[bkt];
+    const int64_t pair0 = a.pair_off[bkt] + (int64_t)tile * Cfg::TQ;
+    const int64_t pair_end = a.pair_off[bkt + 1];
     const int nq_tile = (int)((pair_end - pair0) < Cfg::TQ ? (pair_end - pair0) : Cfg::TQ);
     const int n_l = a.store.list_size[l];
     if (n_l == 0 || nq_tile <= 0) return;
@@ -146,7 +148,8 @@ void k_batch_scan(BatchScanArgs a) {
             const int32_t it = a.pairs[pair0 + e];
             q = it / a.np;
             sc = a.coarse[it];
-            th = a.thresh[(int64_t)q * a.thresh_stride];
+            if (a.dense) th = __int_as_float(a.cand_off[(int64_t)q * (a.np + 1) + (it - q * a.np)]);
+            else th = a.thresh[(int64_t)q * a.thresh_stride];
         }
         s_q[e] = q;
         s_coarse[e] = sc;
@@ -265,7 +268,16 @@ void k_batch_scan(BatchScanArgs a) {
                 sc[r] = fmaf(g[r], acc[r], sq);    // NaN (row beyond the list) never passes
                 best = fmaxf(best, sc[r]);         // fmaxf ignores NaN
             }
-            if (best >= th && q >= 0) {            // rare: some row of this lane reaches the threshold
+            if (a.dense) {                          // nearest lists: every score is kept, in list order
+                if (q >= 0) {
+                    float* out = a.scores + (int64_t)q * a.m_stride + __float_as_int(th);
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int v = slab * 32 + 8 * (r / 4) + 4 * half + (r % 4);
+                        if (v < n_l) out[v] = sc[r];
+                    }
+                }
+            } else if (best >= th && q >= 0) {     // rare: some row of this lane reaches the threshold
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     if (sc[r] >= th) {
@@ -380,12 +392,12 @@ hipError_t launch_pair_grouping(const int32_t* probe, const int32_t* first, int6
                                int32_t* pairs, hipStream_t st) {
     const int64_t n = nq * np;
     if (n <= 0) return hipSuccess;
-    hipError_t e = launch_fill_u32(count, L, 0u, st);
+    hipError_t e = launch_fill_u32(count, 2 * L, 0u, st);
     if (e != hipSuccess) return e;
     const unsigned blocks = (unsigned)((n + 255) / 256);
-    hipLaunchKernelGGL(k_pair_count, dim3(blocks), dim3(256), 0, st, probe, first, nq, np, count);
-    hipLaunchKernelGGL(k_pair_prefix, dim3(1), dim3(1024), 0, st, count, L, tq, pair_off, tile_off, cursor);
-    hipLaunchKernelGGL(k_pair_scatter, dim3(blocks), dim3(256), 0, st, probe, first, nq, np, pair_off, cursor, pairs);
+    hipLaunchKernelGGL(k_pair_count, dim3(blocks), dim3(256), 0, st, probe, first, nq, np, L, count);
+    hipLaunchKernelGGL(k_pair_prefix, dim3(1), dim3(1024), 0, st, count, 2 * L, tq, pair_off, tile_off, cursor);
+    hipLaunchKernelGGL(k_pair_scatter, dim3(blocks), dim3(256), 0, st, probe, first, nq, np, L, pair_off, cursor, pairs);
     return hipGetLastError();
 }
 

@@ -148,9 +148,10 @@ hipError_t launch_select(int mode, const SelectArgs& a, hipStream_t st);
 // (the streaming scan is used instead).
 int batch_tile_queries(int d, int b);
 
-// Buckets the pairs (q, p >= first[q]) by probed list: pairs[pair_off[l] ...] holds the flat pair
-// numbers q*np + p of list l; tile_off[l] counts workgroup tiles of tq queries (both arrays have L+1
-// entries).  count and cursor are scratch arrays of L entries.
+// Buckets the (query, probe) pairs: bucket l holds the pairs (q, p < first[q]) of list l, bucket
+// L + l the pairs (q, p >= first[q]).  pairs[pair_off[b] ...] holds the flat pair numbers q*np + p
+// of bucket b; tile_off[b] counts workgroup tiles of tq queries (both arrays have 2L+1 entries).
+// count and cursor are scratch arrays of 2L entries.
 hipError_t launch_pair_grouping(const int32_t* probe, const int32_t* first, int64_t nq, int np, int L, int tq,
                                 uint32_t* count, uint32_t* cursor, int64_t* pair_off, int32_t* tile_off,
                                 int32_t* pairs, hipStream_t st);
@@ -162,7 +163,10 @@ struct BatchScanArgs {
     const float* coarse;                 // [nq*np] coarse term of each (query, probe)
     const float* thresh; int thresh_stride;   // threshold of query q at thresh[q*thresh_stride]
     ListStore store; int np; int L;
+    int bucket_lo, bucket_hi;            // buckets this launch covers
     float* cand_score; int64_t* cand_slot; int32_t* cand_cnt; int cap;
+    // dense mode (the nearest lists): every score goes to scores[q*m_stride + cand_off[q][p] + v]
+    int dense; float* scores; int64_t m_stride; const int32_t* cand_off;
 };
 hipError_t launch_batch_scan(const BatchScanArgs& a, int d, int b, int max_tiles, hipStream_t st);
 
