@@ -50,13 +50,13 @@ __device__ __forceinline__ bool load_rows(const float* __restrict__ x, int64_t r
     load_row_blocks<KB>(x + (valid ? row : 0) * (int64_t)d, valid, d, vec4, half, v);
     const float n2 = row_norm2<KB>(v);
     const bool good = (n2 > 0.f) && (n2 < __builtin_inff());
-    const float nrm = sqrtf(n2);
+    const float inv = good ? 1.f / sqrtf(n2) : 0.f;     // one division per row, then multiplies
 #pragma unroll
     for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             _Float16 h, l;
-            split_scaled(good ? v[kb][e] / nrm : 0.f, h, l);
+            split_scaled(v[kb][e] * inv, h, l);
             bh[kb][e] = h;
             bl[kb][e] = l;
         }
@@ -132,18 +132,31 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
             }
         }
 
-        if (mode == 0) {
+        if (mode == 0 && !bias && c0 + kTN <= L) {
+            // plain inner products, whole stage inside the table: compare the raw accumulators
+            // (the argmax does not depend on the common 2^20 scale); ascending c, first maximum wins
+#pragma unroll
+            for (int t = 0; t < kNT; ++t)
+#pragma unroll
+                for (int q = 0; q < 16; ++q) {
+                    const int c = c0 + t * 32 + 8 * (q / 4) + 4 * half + (q % 4);
+#pragma unroll
+                    for (int r = 0; r < R; ++r)
+                        if (acc[r][t][q] > best[r]) { best[r] = acc[r][t][q]; best_idx[r] = c; }
+                }
+        } else if (mode == 0) {
 #pragma unroll
             for (int t = 0; t < kNT; ++t)
 #pragma unroll
                 for (int q = 0; q < 16; ++q) {
                     const int i = 8 * (q / 4) + 4 * half + (q % 4);
                     const int c = c0 + t * 32 + i;
+                    // with a bias the comparison is in true units; without, in accumulator units
                     const float bi = tile_bias[t * 32 + i];
 #pragma unroll
                     for (int r = 0; r < R; ++r) {
-                        const float v = fmaf(acc[r][t][q], kUnscale, bi);
-                        if (c < L && v > best[r]) { best[r] = v; best_idx[r] = c; }   // ascending c: first maximum wins
+                        const float v = bias ? fmaf(acc[r][t][q], kUnscale, bi) : acc[r][t][q];
+                        if (c < L && v > best[r]) { best[r] = v; best_idx[r] = c; }
                     }
                 }
         } else {
@@ -175,7 +188,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
             const int64_t row = row0 + 32 * r + j;
             if (row < n && half == 0) {
                 if (assign) assign[row] = good[r] ? best_idx[r] : -1;
-                if (best_out) best_out[row] = best[r];
+                if (best_out) best_out[row] = bias ? best[r] : best[r] * kUnscale;
             }
         }
     }

@@ -56,11 +56,11 @@ void k_encode(int mode, EncodeArgs a, int vec4) {
     load_row_blocks<KB>(a.x + (valid ? row : 0) * (int64_t)d, valid, d, vec4, half, v);
     const float n2 = row_norm2<KB>(v);
     const bool good = (n2 > 0.f) && (n2 < __builtin_inff());
-    const float nrm = sqrtf(n2);
+    const float inv_n = good ? 1.f / sqrtf(n2) : 0.f;   // one division per row, then multiplies
 #pragma unroll
     for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
-        for (int e = 0; e < 8; ++e) v[kb][e] = good ? v[kb][e] / nrm : 0.f;
+        for (int e = 0; e < 8; ++e) v[kb][e] *= inv_n;
 
     int cell = -1;
     float gamma = 0.f;
@@ -73,11 +73,11 @@ void k_encode(int mode, EncodeArgs a, int vec4) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) v[kb][e] -= c[kb][e];
         gamma = sqrtf(row_norm2<KB>(v));
-        const bool tiny = !(gamma > 1e-30f);
+        const float inv_g = (gamma > 1e-30f) ? 1.f / gamma : 0.f;
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
-            for (int e = 0; e < 8; ++e) v[kb][e] = tiny ? 0.f : v[kb][e] / gamma;
+            for (int e = 0; e < 8; ++e) v[kb][e] *= inv_g;
     }
     half8 bh[KB], bl[KB];
 #pragma unroll
@@ -153,7 +153,7 @@ void k_encode(int mode, EncodeArgs a, int vec4) {
         for (int q = 0; q < 16; ++q) u2 += acc[t][q] * acc[t][q];
     u2 += __shfl_xor(u2, 32);
     const float un = sqrtf(u2);
-    const bool degenerate = !(un > 1e-30f);
+    const float inv_u = (un > 1e-30f) ? 1.f / un : 0.f;   // a zero residual quantises as rho = 0
 
     // quantise: code = #{i : rho >= tau_i}, by bisection over the ascending boundaries
     uint8_t* my_codes = code_s + wave * (32 * DP) + j * DP;
@@ -164,7 +164,7 @@ void k_encode(int mode, EncodeArgs a, int vec4) {
             uint32_t packed = 0;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const float rho = degenerate ? 0.f : acc[t][4 * g + e] / un;
+                const float rho = acc[t][4 * g + e] * inv_u;
                 int code = 0;
 #pragma unroll
                 for (int lvl = 7; lvl >= 0; --lvl) {       // straight-line bisection, levels above b skipped
