@@ -32,14 +32,24 @@ MFMA_F16_PEAK_TFLOPS = 2500.0  # dense fp16 matrix peak: the contractions run on
 SPLIT_PASSES = 3               # each product is issued as hi*hi + hi*lo + lo*hi (fp32-accurate)
 
 
-def exact_ground_truth(torch, xd, qd, k, q_chunk=500):
+def exact_ground_truth(torch, xd, qd, k, q_chunk=1000, x_chunk=1 << 20):
     """Exact top-k by inner product of normalised rows (measurement harness, not the product)."""
-    xn = xd / xd.norm(dim=1, keepdim=True)
     out = []
     for s in range(0, qd.shape[0], q_chunk):
         q = qd[s:s + q_chunk]
         q = q / q.norm(dim=1, keepdim=True)
-        out.append(torch.topk(q @ xn.T, k, dim=1).indices)
+        best_v = best_i = None
+        for t in range(0, xd.shape[0], x_chunk):
+            xb = xd[t:t + x_chunk]
+            xb = xb / xb.norm(dim=1, keepdim=True)
+            v, i = torch.topk(q @ xb.T, k, dim=1)
+            i = i + t
+            if best_v is None:
+                best_v, best_i = v, i
+            else:
+                v2, sel = torch.topk(torch.cat([best_v, v], dim=1), k, dim=1)
+                best_v, best_i = v2, torch.gather(torch.cat([best_i, i], dim=1), 1, sel)
+        out.append(best_i)
     return torch.cat(out).cpu().numpy()
 
 
@@ -47,7 +57,7 @@ def stored_traffic(kernel: str, nprobe: int):
     """HBM-side bytes per launch of `kernel`, as measured by the rocprofv3 --pmc runs whose summary
     is committed under profiles/ (FETCH_SIZE and WRITE_SIZE, scaled by a plain copy); None if that
     summary does not cover this kernel and nprobe."""
-    path = os.path.join(ROOT, "profiles", f"{kernel}_1m_d128_nprobe{nprobe}_traffic.txt")
+    path = os.path.join(ROOT, "profiles", f"{kernel}_1m_d128_nprobe{nprobe}_traffic.txt")   # 1M workload only
     if not os.path.exists(path):
         return None
     for line in open(path):
@@ -102,7 +112,10 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--nprobe", type=int, default=32)
+    ap.add_argument("--nprobe", type=int, default=None, help="primary nprobe (default: 32, or the workload's second value)")
+    ap.add_argument("--workload", default="1m", choices=["1m", "10m_d96", "10m_d200"],
+                    help="1m is the benchmark workload; the 10M ones are for scale checks")
+    ap.add_argument("--bits", type=int, default=4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -128,7 +141,10 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"copy_bytes_read": 1 << 30, "copy_bytes_written": 1 << 30, "launches": 5}))
         return
-    w = synth.config_1m()
+    w = {"1m": synth.config_1m, "10m_d96": lambda: synth.config_10m_d96(args.bits),
+         "10m_d200": synth.config_10m_d200}[args.workload]()
+    if args.nprobe is None:
+        args.nprobe = 32 if args.workload == "1m" else w.nprobe[1]
     t_setup = time.perf_counter()
     X = synth.database(w)
     Q = synth.queries(w)
@@ -227,7 +243,7 @@ def main():
         if not ms:
             return None
         r = {"kernel": kernel, "bound": "mfma", "achieved": flops / (ms * 1e-3) / 1e12, "peak": MFMA_F16_PEAK_TFLOPS,
-             "unit": "TFLOP/s", "traffic": None, "algorithmic_flops_per_launch": flops, "avg_launch_ms": ms,
+             "unit": "TFLOP/s", "traffic": stored_traffic(kernel, args.nprobe) if args.workload == "1m" else None, "algorithmic_flops_per_launch": flops, "avg_launch_ms": ms,
              "mfma_dtype": "f16 (3 split passes per product, f32 accumulate)"}
         r["frac"] = r["achieved"] / r["peak"]
         r["issued_frac"] = SPLIT_PASSES * r["frac"]      # share of the fp16 pipe's peak actually issued
@@ -277,8 +293,10 @@ def main():
         "value": qps, "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": wall / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f16-split products, f32 accumulate (f32-accurate)", "data": "synthetic",
-        "config": {"workload": "1M x 128 fp32, 1000-component Gaussian mixture, nlist=1024 (k-means on a 100k "
-                               "sample), b=4, 10000 queries, k=10", "nprobe": args.nprobe, "n": w.n, "d": w.d,
+        "config": {"workload": ("1M x 128 fp32, 1000-component Gaussian mixture, nlist=1024 (k-means on a 100k "
+                                "sample), b=4, 10000 queries, k=10") if args.workload == "1m" else
+                               f"{w.name}: {w.n} x {w.d}, nlist={w.nlist}, b={w.b}, {w.nq} queries, k={w.k}",
+                   "nprobe": args.nprobe, "n": w.n, "d": w.d,
                    "nlist": w.nlist, "b": w.b, "nq": w.nq, "k": w.k},
         "recall_at_10": rec,
         "search_ms": search_t * 1e3, "encode_ms": enc_t * 1e3, "encode_vectors_per_s": vps,
