@@ -100,20 +100,48 @@ def lloyd_max_codebook(b: int, d: int, density: str = "sphere",
     pdf = _pdf(density, d)
     lo, hi = _support(density, d)
     sd = 1.0 / math.sqrt(d)
-    # start from a uniform grid over +-3 standard deviations
-    c = (np.arange(K) + 0.5) / K * 6.0 * sd - 3.0 * sd
-    for _ in range(max_iter):
+    # start from a uniform grid over +-3 standard deviations, cut to the support of the density
+    # (for small d three standard deviations reach beyond [-1, 1], where every bin would be empty)
+    half_width = min(3.0 * sd, hi)
+    c = ((np.arange(K) + 0.5) / K * 2.0 - 1.0) * half_width
+    def lloyd_step(c):
         tau = 0.5 * (c[:-1] + c[1:])
         edges = np.concatenate(([lo], tau, [hi]))
         mass = _integrate_bins(pdf, edges)
         first = _integrate_bins(lambda t: t * pdf(t), edges)
-        new = first / mass
+        return first / mass, mass, edges
+
+    converged = False
+    for _ in range(min(max_iter, 3000)):
+        new, _, _ = lloyd_step(c)
         delta = float(np.max(np.abs(new - c)))
         c = new
         if delta < tol:
+            converged = True
             break
-    else:
-        raise RuntimeError("Lloyd iterations did not converge")
+    # For large K the Lloyd map contracts very slowly (rate -> 1), so what is left is removed by
+    # Newton's method on the same stationarity conditions c = T(c).  With m_i the mass of bin i and
+    # e_i, e_{i+1} its edges, dT_i/de_i = f(e_i)(T_i - e_i)/m_i and dT_i/de_{i+1} = f(e_{i+1})(e_{i+1} - T_i)/m_i,
+    # and an interior edge is the mean of the two centroids beside it.
+    for _ in range(0 if converged else 100):
+        T, mass, edges = lloyd_step(c)
+        resid = T - c
+        if float(np.max(np.abs(resid))) < tol:
+            converged = True
+            c = T
+            break
+        fe = pdf(edges)
+        d_lower = fe[:-1] * (T - edges[:-1]) / mass
+        d_upper = fe[1:] * (edges[1:] - T) / mass
+        d_lower[0] = 0.0      # the outer edges are fixed at the ends of the support
+        d_upper[-1] = 0.0
+        J = np.diag(0.5 * (d_lower + d_upper)) + np.diag(0.5 * d_lower[1:], -1) + np.diag(0.5 * d_upper[:-1], 1)
+        step = np.linalg.solve(np.eye(K) - J, resid)
+        trial = c + step
+        c = trial if np.all(np.diff(trial) > 0) and np.all(np.abs(trial) < max(abs(lo), abs(hi))) else T
+        c = 0.5 * (c - c[::-1])
+    if not converged:
+        raise RuntimeError("Lloyd-Max conditions not met")
     c = 0.5 * (c - c[::-1])  # the density is even: impose c_i = -c_{K-1-i} exactly
     tau = 0.5 * (c[:-1] + c[1:])
     return c, tau

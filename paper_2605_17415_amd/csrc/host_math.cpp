@@ -65,6 +65,10 @@ struct SphereMarginal {
         }
         return total;
     }
+    double pdf(double t) const {
+        const double c2 = 1.0 - t * t;
+        return c2 > 0.0 ? std::exp(log_kappa + 0.5 * (d - 3) * std::log(c2)) : 0.0;
+    }
     // E[T ; a <= T <= b] in closed form: kappa/(d-1) * [(1-a^2)^((d-1)/2) - (1-b^2)^((d-1)/2)]
     double first_moment(double a, double b) const {
         double k = std::exp(log_kappa) / (d - 1);
@@ -75,6 +79,22 @@ struct SphereMarginal {
 
 }  // namespace
 
+// One Lloyd step T(c): boundaries at the midpoints, centroids at the conditional means.  Only the
+// upper half is integrated (the density is even).  Also returns, per bin, the probability mass.
+static void lloyd_step(const SphereMarginal& f, const std::vector<double>& cent, std::vector<double>& edge,
+                       std::vector<double>& next, std::vector<double>& mass) {
+    const int K = (int)cent.size();
+    edge[0] = -1.0;
+    edge[K] = 1.0;
+    for (int i = 1; i < K; ++i) edge[i] = 0.5 * (cent[i - 1] + cent[i]);
+    for (int i = K / 2; i < K; ++i) {
+        mass[i] = f.mass(edge[i], edge[i + 1]);
+        next[i] = f.first_moment(edge[i], edge[i + 1]) / mass[i];
+        mass[K - 1 - i] = mass[i];
+        next[K - 1 - i] = -next[i];
+    }
+}
+
 bool build_codebook(int b, int d, std::vector<double>& cent, std::vector<double>& bnd) {
     if (b < 1 || b > 8 || d < 3) return false;
     const int K = 1 << b;
@@ -82,23 +102,67 @@ bool build_codebook(int b, int d, std::vector<double>& cent, std::vector<double>
     cent.resize(K);
     bnd.resize(K - 1);
     const double sd = 1.0 / std::sqrt((double)d);
-    for (int i = 0; i < K; ++i) cent[i] = ((i + 0.5) / K * 6.0 - 3.0) * sd;
-    std::vector<double> edge(K + 1), next(K);
-    for (int it = 0; it < 200000; ++it) {
-        edge[0] = -1.0;
-        edge[K] = 1.0;
-        for (int i = 1; i < K; ++i) edge[i] = 0.5 * (cent[i - 1] + cent[i]);
-        double delta = 0.0;
-        // the density is even, so only the upper half needs integrating
-        for (int i = K / 2; i < K; ++i) {
-            next[i] = f.first_moment(edge[i], edge[i + 1]) / f.mass(edge[i], edge[i + 1]);
-            next[K - 1 - i] = -next[i];
-        }
-        for (int i = 0; i < K; ++i) delta = std::max(delta, std::fabs(next[i] - cent[i]));
+    // start from a uniform grid over three standard deviations, kept inside the support (-1, 1)
+    const double span = std::min(3.0 * sd, 1.0);
+    for (int i = 0; i < K; ++i) cent[i] = ((i + 0.5) / K * 2.0 - 1.0) * span;
+    std::vector<double> edge(K + 1), next(K), mass(K);
+    // The Lloyd-Max quantiser is the solution of c = T(c).  Plain Lloyd iteration c <- T(c) converges
+    // linearly with a rate that approaches 1 as K grows (hundreds of thousands of steps at K = 256),
+    // so after a short warm-up the same equations are solved by Newton's method: the Jacobian of T is
+    // tridiagonal, dT_i/d(edge) = f(edge) * |T_i - edge| / mass_i at either edge of bin i, and each
+    // interior edge moves by half of either neighbouring centroid.
+    for (int it = 0; it < 64; ++it) {
+        lloyd_step(f, cent, edge, next, mass);
         cent = next;
-        if (delta < 1e-14) break;
+    }
+    std::vector<double> lo(K), di(K), up(K), rhs(K), trial(K);
+    double resid = 1e300;
+    for (int it = 0; it < 200; ++it) {
+        lloyd_step(f, cent, edge, next, mass);
+        double r = 0.0;
+        for (int i = 0; i < K; ++i) r = std::max(r, std::fabs(next[i] - cent[i]));
+        if (r < 1e-14 || (r < 1e-12 && r >= resid)) { cent = next; break; }   // at the rounding floor of the quadrature
+        resid = r;
+        // (I - J_T) delta = T(c) - c
+        for (int i = 0; i < K; ++i) {
+            const double dl = i > 0 ? f.pdf(edge[i]) * (next[i] - edge[i]) / mass[i] : 0.0;
+            const double du = i < K - 1 ? f.pdf(edge[i + 1]) * (edge[i + 1] - next[i]) / mass[i] : 0.0;
+            lo[i] = -0.5 * dl;
+            up[i] = -0.5 * du;
+            di[i] = 1.0 - 0.5 * (dl + du);
+            rhs[i] = next[i] - cent[i];
+        }
+        for (int i = 1; i < K; ++i) {                 // Thomas algorithm
+            const double m = lo[i] / di[i - 1];
+            di[i] -= m * up[i - 1];
+            rhs[i] -= m * rhs[i - 1];
+        }
+        trial[K - 1] = rhs[K - 1] / di[K - 1];
+        for (int i = K - 2; i >= 0; --i) trial[i] = (rhs[i] - up[i] * trial[i + 1]) / di[i];
+        bool ordered = true;
+        for (int i = 0; i < K; ++i) {
+            trial[i] += cent[i];
+            if (!std::isfinite(trial[i]) || std::fabs(trial[i]) >= 1.0 || (i > 0 && !(trial[i] > trial[i - 1]))) ordered = false;
+        }
+        cent = ordered ? trial : next;               // a Newton step that leaves the ordered cone is replaced by a Lloyd step
+        for (int i = 0; i < K / 2; ++i) {             // T is evaluated on the upper half only: keep c exactly antisymmetric
+            const double v = 0.5 * (cent[K - 1 - i] - cent[i]);
+            cent[K - 1 - i] = v;
+            cent[i] = -v;
+        }
+    }
+    for (int i = 0; i < K / 2; ++i) {                 // exact antisymmetry
+        const double v = 0.5 * (cent[K - 1 - i] - cent[i]);
+        cent[K - 1 - i] = v;
+        cent[i] = -v;
     }
     for (int i = 1; i < K; ++i) bnd[i - 1] = 0.5 * (cent[i - 1] + cent[i]);
+    for (int i = 0; i < K; ++i)
+        if (!std::isfinite(cent[i]) || (i > 0 && !(cent[i] > cent[i - 1]))) return false;
+    // the result must satisfy the Lloyd-Max conditions themselves
+    lloyd_step(f, cent, edge, next, mass);
+    for (int i = 0; i < K; ++i)
+        if (std::fabs(next[i] - cent[i]) > 1e-12) return false;
     return true;
 }
 

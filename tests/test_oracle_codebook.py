@@ -106,6 +106,24 @@ def test_stationarity_against_closed_forms(b, d):
     assert abs(np.dot(first, c) - (1.0 - D) / d) < 1e-12
 
 
+@pytest.mark.parametrize("b,d", [(6, 8), (8, 8), (7, 96), (8, 128)])
+def test_stationarity_at_many_levels_and_small_dimension(b, d):
+    """K up to 256 and d = 8 (three standard deviations reach beyond the support): the result still
+    meets the Lloyd-Max conditions, checked through the incomplete beta function and the closed-form
+    first moment rather than the oracle's own quadrature."""
+    c, tau = orc.lloyd_max_codebook(b, d)
+    K = 1 << b
+    assert np.all(np.isfinite(c)) and np.all(np.diff(c) > 0) and abs(c[-1]) < 1.0
+    np.testing.assert_allclose(c, -c[::-1], atol=1e-15)
+    edges = np.concatenate(([-1.0], tau, [1.0]))
+    mass = np.diff(_cdf_sphere(edges, d))
+    first = np.array([_first_moment_sphere(edges[i], edges[i + 1], d) for i in range(K)])
+    np.testing.assert_allclose(c, first / mass, rtol=0, atol=5e-10)
+    D = orc.codebook_distortion(c, tau, d)
+    assert D < math.sqrt(3) * math.pi / 2 * 4.0 ** (-b)          # high-resolution bound
+    assert abs(np.dot(mass, c * c) - (1.0 - D) / d) < 1e-12
+
+
 @pytest.mark.parametrize("d", DIMS)
 def test_distortion_decreases_with_bits_and_respects_high_resolution_bound(d):
     prev = None
