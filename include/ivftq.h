@@ -59,6 +59,16 @@ enum {
  * rounded to float. */
 ivftq_status ivftq_build_codebook(int b, int d, float* centroids_out, float* boundaries_out);
 
+/* The table through which the encode kernel evaluates  code = #{i : v >= boundary_i}  (same
+ * passage as above) with one lookup: the real line is cut into *cells_out equal cells (the two
+ * outermost open-ended), cell(v) = clamp((int)(v * *scale_out + *offset_out), 0, cells - 1) in float
+ * arithmetic, and  code = index_out[cell] + (v >= boundary_out[cell]).  For inspection and host-side
+ * tests; all pointers host.  boundary_out / index_out (either may be NULL) need `capacity` >= cells
+ * entries, else IVFTQ_INVALID_ARG; call with both NULL to learn the size.  IVFTQ_UNSUPPORTED if
+ * (b, d) would need more than 4096 cells (then ivftq_create fails the same way). */
+ivftq_status ivftq_quantiser_grid(int b, int d, int capacity, int* cells_out, float* scale_out,
+                                  float* offset_out, float* boundary_out, int32_t* index_out);
+
 /* Haar-distributed orthogonal matrix (same appendix, Setup): QR of a d x d Gaussian matrix with
  * the sign of each column fixed so that diag(R) > 0.  pi_out: host, d*d floats, row-major, acting
  * as u = Pi r.  The first form draws the Gaussian matrix from `seed`; the second takes it from
@@ -87,7 +97,9 @@ ivftq_status ivftq_train_coarse(ivftq_index* index, const float* x_dev, int64_t 
                                 void* stream);
 
 /* Inject / read back constants (host pointers).  centroids: nlist x d, rows are used as given
- * (they should be unit vectors).  pi: d x d.  Setting either on a non-empty index is BAD_STATE. */
+ * (they should be unit vectors).  pi: d x d, must be orthogonal to float32 rounding
+ * (|Pi Pi^T - I|_F <= 2e-6, else IVFTQ_INVALID_ARG and the index keeps its rotation): the encode uses
+ * |Pi r| = |r| (Section "Architecture", Indexing).  Setting either on a non-empty index is BAD_STATE. */
 ivftq_status ivftq_set_coarse(ivftq_index* index, const float* centroids_host);
 ivftq_status ivftq_get_coarse(const ivftq_index* index, float* centroids_host);
 ivftq_status ivftq_set_rotation(ivftq_index* index, const float* pi_host);

@@ -20,6 +20,8 @@ STATUS_NAMES = ["OK", "INVALID_ARG", "BAD_STATE", "OOM", "HIP_ERROR", "ZERO_NORM
 # every symbol include/ivftq.h declares, with its ctypes signature
 _SIGNATURES = {
     "ivftq_build_codebook": (C.c_int, [C.c_int, C.c_int, C.c_void_p, C.c_void_p]),
+    "ivftq_quantiser_grid": (C.c_int, [C.c_int, C.c_int, C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_float),
+                                       C.POINTER(C.c_float), C.c_void_p, C.c_void_p]),
     "ivftq_haar_rotation": (C.c_int, [C.c_int, C.c_uint64, C.c_void_p]),
     "ivftq_haar_from_gaussian": (C.c_int, [C.c_int, C.c_void_p, C.c_void_p]),
     "ivftq_create": (C.c_int, [C.c_int, C.c_int, C.c_int, C.c_uint64, C.POINTER(C.c_void_p)]),
@@ -125,6 +127,18 @@ def ivftq_build_codebook(b: int, d: int):
     t = np.empty(max(K - 1, 1), np.float32)
     _check(lib.ivftq_build_codebook(b, d, _np_ptr(c), _np_ptr(t)))
     return c, t[:K - 1]
+
+
+def ivftq_quantiser_grid(b: int, d: int):
+    """(cells, scale, offset, boundary [cells] f32, index [cells] i32)"""
+    lib = load_library()
+    cells, scale, offset = C.c_int(0), C.c_float(0), C.c_float(0)
+    _check(lib.ivftq_quantiser_grid(b, d, 0, C.byref(cells), C.byref(scale), C.byref(offset), None, None))
+    boundary = np.empty(cells.value, np.float32)
+    index = np.empty(cells.value, np.int32)
+    _check(lib.ivftq_quantiser_grid(b, d, cells.value, C.byref(cells), C.byref(scale), C.byref(offset),
+                                    _np_ptr(boundary), _np_ptr(index)))
+    return cells.value, np.float32(scale.value), np.float32(offset.value), boundary, index
 
 
 def ivftq_haar_rotation(d: int, seed: int) -> np.ndarray:

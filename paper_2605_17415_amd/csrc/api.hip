@@ -84,10 +84,11 @@ uint64_t splitmix(uint64_t& s) {
 
 struct ivftq_index {
     int d = 0, b = 0, nlist = 0, K = 0, dp = 0, lpad = 0, words = 0;
+    int q_cells = 0; float q_scale = 0.f, q_offset = 0.f;   // quantiser grid (host_math.h)
     bool has_coarse = false;
     std::vector<float> h_cent, h_pi, h_cb, h_tau;
     // device constants
-    DevBuf cent, cent_h, cent_l, bias, pi, pi_h, pi_l, cb, tau;   // cent_h/cent_l: split float16 form of cent
+    DevBuf cent, cent_h, cent_l, bias, pi, pi_h, pi_l, cb, q_grid;   // cent_h/cent_l: split float16 form of cent
     // list storage
     DevBuf codes, gamma, ids, d_off, d_size;
     std::vector<int64_t> h_off, h_cap;
@@ -117,7 +118,7 @@ struct ivftq_index {
     }
     ~ivftq_index() {
         for (ProfRec& r : prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
-        for (DevBuf* bfr : {&cent, &cent_h, &cent_l, &pi_h, &pi_l, &bias, &pi, &cb, &tau, &codes, &gamma, &ids, &d_off, &d_size, &w_assign,
+        for (DevBuf* bfr : {&cent, &cent_h, &cent_l, &pi_h, &pi_l, &bias, &pi, &cb, &q_grid, &codes, &gamma, &ids, &d_off, &d_size, &w_assign,
                             &w_slot, &w_hist, &w_count, &w_base, &w_flag, &w_best, &w_S, &w_probe, &w_coarse,
                             &w_z, &w_candoff, &w_scores, &w_sums, &w_counts, &w_zero, &w_rows, &w_dst, &w_obj,
                             &w_first, &w_fscores, &w_fids, &w_pairs, &w_pairoff, &w_tileoff, &w_cscore,
@@ -174,6 +175,11 @@ ivftq_status upload_coarse(ivftq_index* ix) {
 }
 
 ivftq_status upload_rotation(ivftq_index* ix) {
+    // The encode kernel quantises Pi r^ without dividing by |Pi r^| (= 1 for an orthogonal Pi), so
+    // the rotation has to be orthogonal to float32 rounding: the defect bounds | |Pi r^|^2 - 1 |.
+    const double defect = orthogonality_defect(ix->d, ix->h_pi.data());
+    if (!(defect <= 2e-6))
+        return fail(IVFTQ_INVALID_ARG, "rotation is not orthogonal: |Pi Pi^T - I|_F = %.3g (limit 2e-6)", defect);
     std::vector<float> padded((size_t)ix->dp * ix->dp, 0.f);
     for (int i = 0; i < ix->d; ++i)
         std::memcpy(&padded[(size_t)i * ix->dp], &ix->h_pi[(size_t)i * ix->d], sizeof(float) * ix->d);
@@ -248,6 +254,24 @@ ivftq_status ivftq_build_codebook(int b, int d, float* centroids_out, float* bou
     return IVFTQ_OK;
 }
 
+ivftq_status ivftq_quantiser_grid(int b, int d, int capacity, int* cells_out, float* scale_out, float* offset_out,
+                                  float* boundary_out, int32_t* index_out) {
+    if (!cells_out || !scale_out || !offset_out) return fail(IVFTQ_INVALID_ARG, "output pointer is NULL");
+    std::vector<float> c(1 << (b < 1 || b > 8 ? 1 : b)), tau((1 << (b < 1 || b > 8 ? 1 : b)) - 1);
+    ivftq_status s = ivftq_build_codebook(b, d, c.data(), tau.data());
+    if (s != IVFTQ_OK) return s;
+    QuantiserGrid grid;
+    if (!build_quantiser_grid(tau, kMaxGridCells, grid))
+        return fail(IVFTQ_UNSUPPORTED, "quantiser grid for b=%d d=%d needs more than %d cells", b, d, kMaxGridCells);
+    *cells_out = grid.cells; *scale_out = grid.scale; *offset_out = grid.offset;
+    if (boundary_out || index_out) {
+        if (capacity < grid.cells) return fail(IVFTQ_INVALID_ARG, "capacity %d below the %d cells of the grid", capacity, grid.cells);
+        if (boundary_out) std::copy(grid.boundary.begin(), grid.boundary.end(), boundary_out);
+        if (index_out) std::copy(grid.index.begin(), grid.index.end(), index_out);
+    }
+    return IVFTQ_OK;
+}
+
 ivftq_status ivftq_haar_from_gaussian(int d, const double* g, float* pi_out) {
     if (d < 1 || !g || !pi_out) return fail(IVFTQ_INVALID_ARG, "bad argument to ivftq_haar_from_gaussian");
     std::vector<double> q;
@@ -293,8 +317,17 @@ ivftq_status ivftq_create(int d, int b, int nlist, uint64_t rotation_seed, ivftq
                                  hipGetErrorString(e));
         return code;
     };
-    std::vector<float> tau_pad(256, 0.f);
-    std::copy(ix->h_tau.begin(), ix->h_tau.end(), tau_pad.begin());
+    QuantiserGrid grid;
+    if (!build_quantiser_grid(ix->h_tau, kMaxGridCells, grid)) {
+        delete ix;
+        return fail(IVFTQ_UNSUPPORTED, "quantiser grid for b=%d d=%d needs more than %d cells", b, d, kMaxGridCells);
+    }
+    ix->q_cells = grid.cells; ix->q_scale = grid.scale; ix->q_offset = grid.offset;
+    std::vector<uint32_t> grid_words((size_t)2 * grid.cells);
+    for (int i = 0; i < grid.cells; ++i) {
+        std::memcpy(&grid_words[2 * i], &grid.boundary[i], 4);
+        grid_words[2 * i + 1] = (uint32_t)grid.index[i];
+    }
     std::vector<int32_t> zeros(nlist, 0);
     hipError_t e = ix->cent.ensure((size_t)ix->lpad * ix->dp * sizeof(float));
     if (e == hipSuccess) e = ix->cent_h.ensure((size_t)ix->lpad * ix->dp * sizeof(uint16_t));
@@ -304,12 +337,12 @@ ivftq_status ivftq_create(int d, int b, int nlist, uint64_t rotation_seed, ivftq
     if (e == hipSuccess) e = ix->pi_h.ensure((size_t)ix->dp * ix->dp * sizeof(uint16_t));
     if (e == hipSuccess) e = ix->pi_l.ensure((size_t)ix->dp * ix->dp * sizeof(uint16_t));
     if (e == hipSuccess) e = ix->cb.ensure(256 * sizeof(float));
-    if (e == hipSuccess) e = ix->tau.ensure(256 * sizeof(float));
+    if (e == hipSuccess) e = ix->q_grid.ensure(grid_words.size() * sizeof(uint32_t));
+    if (e == hipSuccess) e = hipMemcpy(ix->q_grid.p, grid_words.data(), grid_words.size() * sizeof(uint32_t), hipMemcpyHostToDevice);
     if (e == hipSuccess) e = ix->d_size.ensure((size_t)nlist * sizeof(int32_t));
     if (e == hipSuccess) e = ix->d_off.ensure((size_t)nlist * sizeof(int64_t));
     if (e == hipSuccess) e = ix->w_flag.ensure(64);
     if (e == hipSuccess) e = hipMemcpy(ix->cb.p, ix->h_cb.data(), ix->K * sizeof(float), hipMemcpyHostToDevice);
-    if (e == hipSuccess) e = hipMemcpy(ix->tau.p, tau_pad.data(), 256 * sizeof(float), hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemcpy(ix->d_size.p, zeros.data(), nlist * sizeof(int32_t), hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemset(ix->d_off.p, 0, (size_t)nlist * sizeof(int64_t));
     if ((s = guard(e, "device set-up")) != IVFTQ_OK) { delete ix; return s; }
@@ -358,8 +391,13 @@ ivftq_status ivftq_set_rotation(ivftq_index* ix, const float* pi_host) {
     if (check_index(ix)) return IVFTQ_INVALID_ARG;
     if (!pi_host) return fail(IVFTQ_INVALID_ARG, "pi_host is NULL");
     if (ix->ntotal > 0) return fail(IVFTQ_BAD_STATE, "rotation cannot change once vectors are stored");
+    for (size_t i = 0; i < (size_t)ix->d * ix->d; ++i)
+        if (!std::isfinite(pi_host[i])) return fail(IVFTQ_INVALID_ARG, "non-finite rotation entry");
+    std::vector<float> previous = ix->h_pi;
     std::copy(pi_host, pi_host + (size_t)ix->d * ix->d, ix->h_pi.begin());
-    return upload_rotation(ix);
+    ivftq_status s = upload_rotation(ix);
+    if (s != IVFTQ_OK) ix->h_pi = previous;          // a rejected matrix leaves the index as it was
+    return s;
 }
 
 ivftq_status ivftq_get_rotation(const ivftq_index* ix, float* pi_host) {
@@ -639,7 +677,8 @@ ivftq_status ivftq_encode_only(ivftq_index* ix, const float* x_dev, int64_t n, i
         EncodeArgs a{};
         a.x = x_dev; a.n = n; a.d = ix->d; a.b = ix->b;
         a.cent = ix->cent.as<float>(); a.cent_pitch = ix->dp;
-        a.pi_h = ix->pi_h.as<uint16_t>(); a.pi_l = ix->pi_l.as<uint16_t>(); a.tau = ix->tau.as<float>();
+        a.pi_h = ix->pi_h.as<uint16_t>(); a.pi_l = ix->pi_l.as<uint16_t>();
+        a.q_grid = ix->q_grid.as<float2>(); a.q_cells = ix->q_cells; a.q_scale = ix->q_scale; a.q_offset = ix->q_offset;
         a.assign = assign;
         a.codes_flat = codes_dev; a.gamma_flat = gamma_dev;
         HIP_TRY(timed(ix, st, P_ENCODE, [&] { return launch_encode(1, a, st); }));
@@ -673,7 +712,8 @@ ivftq_status ivftq_encode_add(ivftq_index* ix, const float* x_dev, int64_t n, co
     EncodeArgs a{};
     a.x = x_dev; a.n = n; a.d = ix->d; a.b = ix->b;
     a.cent = ix->cent.as<float>(); a.cent_pitch = ix->dp;
-    a.pi_h = ix->pi_h.as<uint16_t>(); a.pi_l = ix->pi_l.as<uint16_t>(); a.tau = ix->tau.as<float>();
+    a.pi_h = ix->pi_h.as<uint16_t>(); a.pi_l = ix->pi_l.as<uint16_t>();
+        a.q_grid = ix->q_grid.as<float2>(); a.q_cells = ix->q_cells; a.q_scale = ix->q_scale; a.q_offset = ix->q_offset;
     a.assign = ix->w_assign.as<int32_t>();
     a.store = ix->store();
     a.slot = ix->w_slot.as<int64_t>();

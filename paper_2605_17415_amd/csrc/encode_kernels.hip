@@ -1,13 +1,25 @@
-// Residual rotation, normalisation, Lloyd-Max quantisation and bit-packing in one kernel
-// (Section "Architecture", Indexing: r = x~ - c~_l, rotate by Pi, normalise Pi r, quantise each
-// coordinate; Bit accounting: b*d code bits and a float16 norm per vector), plus the query-side
-// rotation z = Pi q~ (Section "Architecture", Search).
+// Residual rotation, Lloyd-Max quantisation and bit-packing in one kernel (Section "Architecture",
+// Indexing: r = x~ - c~_l, rotate by Pi, normalise Pi r, quantise each coordinate; Bit accounting:
+// b*d code bits and a float16 norm per vector), plus the query-side rotation z = Pi q~ (Section
+// "Architecture", Search).
 //
 // The rotation is a d x d contraction on the matrix cores (v_mfma_f32_32x32x16_f16 on split float16
-// operands with float32 accumulation, see split_f16.h).  A wavefront owns 32 rows; the unit residuals
-// are the right-hand operand held in registers, 32-row tiles of Pi stream through LDS as the
-// left-hand operand.  In tile t a lane holds, for one row, the rotated coordinates
-// 32t + 8g + 4*half + {0..3}; all tiles stay in registers until the norm of Pi r is known.
+// operands with float32 accumulation, see split_f16.h).  A wavefront owns 32*R rows; their unit
+// residuals r^ = r/|r| are the right-hand operand held in registers, 32-row tiles of Pi stream
+// through a double-buffered LDS stage as the left-hand operand (one barrier per tile, the next
+// tile's global loads in flight during the multiplies).  In tile t a lane holds, for one row, the
+// rotated coordinates 32t + 8g + 4*half + {0..3}.
+//
+// Pi is orthogonal, so |Pi r| = |r| and the quantiser input Pi r / |Pi r| is Pi r^ itself; the
+// library only accepts rotations whose defect |Pi Pi^T - I| is at float32 rounding level, which
+// bounds the difference at 1e-6 of the coordinate.  Each tile is therefore quantised as soon as its
+// multiplies are done and no rotated vector is ever held whole.
+//
+// Quantiser: code = #{i : rho >= tau_i} through the uniform-grid index of host_math.h (one
+// independent 8-byte LDS lookup and one comparison per coordinate, any b).  Codes are packed in
+// registers four at a time and merged into the row's words in LDS with ds_or, then written to the
+// row's storage slot.  Rows may be processed in list order (`order`), which makes the stores of a
+// wavefront land in consecutive slots.
 #include <hip/hip_fp16.h>
 
 #include "kernels.h"
@@ -22,110 +34,159 @@ struct EncCfg {
     static constexpr int KB = DP / 16;
     static constexpr int NT = DP / 32;
     static constexpr int LDH = DP + 8;                     // halves per LDS row of the Pi tile
-    static constexpr size_t pi_bytes = (size_t)2 * 32 * LDH * sizeof(uint16_t);
-    static constexpr size_t code_bytes = 4 * 32 * DP;      // per wave: 32 rows x DP bytes
-    static constexpr size_t lds_bytes = pi_bytes + 256 * 4 + code_bytes;
-    static constexpr int occupancy = DP <= 160 ? 2 : 1;    // wavefronts per SIMD the register budget allows
+#ifndef IVFTQ_ENC_R2_MAX_DP
+#define IVFTQ_ENC_R2_MAX_DP 96
+#endif
+    static constexpr int R = DP <= IVFTQ_ENC_R2_MAX_DP ? 2 : 1;   // 32-row tiles per wavefront (register budget)
+    static constexpr int stage_halves = 2 * 32 * LDH;      // hi and lo parts of one 32-row tile of Pi
+    static constexpr int PF = (32 * (DP / 8) + 255) / 256; // 16-byte pieces of one part a thread stages
+    static constexpr size_t pi_bytes = (size_t)2 * stage_halves * sizeof(uint16_t);
 };
 
+inline int pack_pitch(int words) { return (words + 1) | 1; }   // odd and > words: room for a spill word
+
 template <int DP>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(EncCfg<DP>::occupancy)))
-void k_encode(int mode, EncodeArgs a, int vec4) {
+size_t encode_lds_bytes(int mode, int cells, int words) {
+    size_t bytes = EncCfg<DP>::pi_bytes;
+    if (mode != 2) bytes += (size_t)cells * 8;
+    if (mode == 0) bytes += (size_t)4 * 32 * EncCfg<DP>::R * pack_pitch(words) * 4;
+    return bytes;
+}
+
+template <int DP>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2)))
+void k_encode(int mode, EncodeArgs a, int flags) {
     using Cfg = EncCfg<DP>;
-    constexpr int KB = Cfg::KB;
+    constexpr int KB = Cfg::KB, NT = Cfg::NT, R = Cfg::R, LDH = Cfg::LDH, PF = Cfg::PF;
     extern __shared__ unsigned char lds_raw[];
-    uint16_t* ph = reinterpret_cast<uint16_t*>(lds_raw);           // [32][LDH] hi parts of 32 rows of Pi
-    uint16_t* pl = ph + 32 * Cfg::LDH;                               // [32][LDH] lo parts
-    float* tau_s = reinterpret_cast<float*>(pl + 32 * Cfg::LDH);     // [256]
-    uint8_t* code_s = reinterpret_cast<uint8_t*>(tau_s + 256);
+    uint16_t* stage = reinterpret_cast<uint16_t*>(lds_raw);                    // [2][hi,lo][32][LDH]
+    float2* grid_s = reinterpret_cast<float2*>(lds_raw + Cfg::pi_bytes);        // [cells] (boundary, index bits)
+    uint32_t* pack_s = reinterpret_cast<uint32_t*>(lds_raw + Cfg::pi_bytes + (size_t)a.q_cells * 8);
 
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63, half = lane >> 5, j = lane & 31;
-    const int64_t row0 = (int64_t)blockIdx.x * kRowsPerWG + wave * 32;
-    const int64_t row = row0 + j;
-    const bool valid = row < a.n;
-    const int d = a.d;
-    const int K = 1 << a.b;
+    const int vec4 = flags & 1;          // rows of x can be read 16 bytes at a time
+    const bool codes4 = flags & 2;       // rows of codes_flat can be written 4 bytes at a time
+    const int d = a.d, b = a.b;
+    const int words = a.store.words;
+    const int pitch = (words + 1) | 1;
+    const int64_t pos0 = ((int64_t)blockIdx.x * 4 + wave) * (32 * R);
 
-    if (mode != 2 && tid < K - 1) tau_s[tid] = a.tau[tid];
-
-    // x~, then the residual against the assigned centroid and its norm gamma.  The rotation acts on
-    // the unit residual r/gamma: Pi r / |Pi r| does not depend on the scale of r, and a unit vector
-    // keeps the split float16 form accurate however small the residual is.
-    float v[KB][8];
-    load_row_blocks<KB>(a.x + (valid ? row : 0) * (int64_t)d, valid, d, vec4, half, v);
-    const float n2 = row_norm2<KB>(v);
-    const bool good = (n2 > 0.f) && (n2 < __builtin_inff());
-    const float inv_n = good ? 1.f / sqrtf(n2) : 0.f;   // one division per row, then multiplies
+    // ---- this lane's rows: x~, residual against the assigned centroid, gamma, split unit residual
+    half8 bh[R][KB], bl[R][KB];
+    int64_t row_of[R];
+    float gamma[R];
+    bool valid[R];
 #pragma unroll
-    for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-        for (int e = 0; e < 8; ++e) v[kb][e] *= inv_n;
-
-    int cell = -1;
-    float gamma = 0.f;
-    if (mode != 2) {
-        cell = valid ? a.assign[row] : -1;
-        float c[KB][8];
-        load_row_blocks<KB>(a.cent + (int64_t)(cell < 0 ? 0 : cell) * a.cent_pitch, cell >= 0, DP, 1, half, c);
+    for (int r = 0; r < R; ++r) {
+        const int64_t pos = pos0 + 32 * r + j;
+        valid[r] = pos < a.n;
+        row_of[r] = valid[r] ? (a.order ? (int64_t)a.order[pos] : pos) : 0;
+        float v[KB][8];
+        load_row_blocks<KB>(a.x + row_of[r] * (int64_t)d, valid[r], d, vec4, half, v);
+        const float n2 = row_norm2<KB>(v);
+        const bool good = (n2 > 0.f) && (n2 < __builtin_inff());
+        const float inv_n = good ? 1.f / sqrtf(n2) : 0.f;   // one division per row, then multiplies
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
-            for (int e = 0; e < 8; ++e) v[kb][e] -= c[kb][e];
-        gamma = sqrtf(row_norm2<KB>(v));
-        const float inv_g = (gamma > 1e-30f) ? 1.f / gamma : 0.f;
+            for (int e = 0; e < 8; ++e) v[kb][e] *= inv_n;
+        gamma[r] = 0.f;
+        if (mode != 2) {
+            const int cell = valid[r] ? a.assign[row_of[r]] : -1;
+            float c[KB][8];
+            load_row_blocks<KB>(a.cent + (int64_t)(cell < 0 ? 0 : cell) * a.cent_pitch, cell >= 0, DP, 1, half, c);
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[kb][e] -= c[kb][e];
+            const float g = sqrtf(row_norm2<KB>(v));
+            // The rotation acts on the unit residual: the quantiser input does not depend on the scale
+            // of r, and a unit vector keeps the split float16 form accurate however small r is.
+            const float inv_g = (g > 1e-30f) ? 1.f / g : 0.f;   // a zero residual quantises as rho = 0
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[kb][e] *= inv_g;
+            gamma[r] = cell >= 0 ? g : 0.f;
+        }
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
-            for (int e = 0; e < 8; ++e) v[kb][e] *= inv_g;
+            for (int e = 0; e < 8; ++e) {
+                _Float16 h, l;
+                split_scaled(v[kb][e], h, l);
+                bh[r][kb][e] = h;
+                bl[r][kb][e] = l;
+            }
     }
-    half8 bh[KB], bl[KB];
-#pragma unroll
-    for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            _Float16 h, l;
-            split_scaled(v[kb][e], h, l);
-            bh[kb][e] = h;
-            bl[kb][e] = l;
-        }
 
-    // u = Pi r^: 32 output coordinates per tile, every tile's accumulator kept until the norm is known
-    floatx16 acc[Cfg::NT];
-    const uint16_t* ah_base = ph + j * Cfg::LDH + 8 * half;
-    const uint16_t* al_base = pl + j * Cfg::LDH + 8 * half;
+    // ---- LDS set-up: quantiser grid, cleared packing words, first tile of Pi
+    if (mode != 2)
+        for (int e = tid; e < a.q_cells; e += 256) grid_s[e] = a.q_grid[e];
+    uint32_t* my_pack = pack_s + (size_t)wave * (32 * R) * pitch;
+    if (mode == 0)
+        for (int e = lane; e < 32 * R * pitch; e += 64) my_pack[e] = 0u;
+
+    // Staging of one 32-row tile of Pi: thread `tid` moves the 16-byte pieces tid, tid + 256, ...
+    uint4 pf_h[PF], pf_l[PF];
+#define IVFTQ_FETCH_TILE(T)                                                                          \
+    _Pragma("unroll") for (int p = 0; p < PF; ++p) {                                                 \
+        int e_ = tid + 256 * p;                                                                      \
+        e_ = e_ < 32 * (DP / 8) ? e_ : 32 * (DP / 8) - 1;      /* surplus threads re-read the last piece */ \
+        const int64_t src_ = (int64_t)((T) * 32 + e_ / (DP / 8)) * DP + (e_ % (DP / 8)) * 8;         \
+        pf_h[p] = *reinterpret_cast<const uint4*>(a.pi_h + src_);                                    \
+        pf_l[p] = *reinterpret_cast<const uint4*>(a.pi_l + src_);                                    \
+    }
+#define IVFTQ_STORE_TILE(BUF)                                                                        \
+    _Pragma("unroll") for (int p = 0; p < PF; ++p) {                                                 \
+        const int e_ = tid + 256 * p;                                                                \
+        if (PF * 256 == 32 * (DP / 8) || e_ < 32 * (DP / 8)) {                                       \
+            const int at_ = (BUF) * Cfg::stage_halves + (e_ / (DP / 8)) * LDH + (e_ % (DP / 8)) * 8; \
+            *reinterpret_cast<uint4*>(stage + at_) = pf_h[p];                                        \
+            *reinterpret_cast<uint4*>(stage + at_ + 32 * LDH) = pf_l[p];                             \
+        }                                                                                            \
+    }
+    IVFTQ_FETCH_TILE(0)
+    IVFTQ_STORE_TILE(0)
+    __syncthreads();
+
+    constexpr float kUnscale = 1.f / (kSplitScale * kSplitScale);
+    const float q_scale = a.q_scale * kUnscale, q_offset = a.q_offset;
+    const int q_last = a.q_cells - 1;
+
 #pragma unroll
-    for (int t = 0; t < Cfg::NT; ++t) {
-        __syncthreads();
-        for (int e = tid; e < 32 * (DP / 8); e += 256) {
-            const int rr = e / (DP / 8), c8 = e % (DP / 8);
-            const int64_t src = (int64_t)(t * 32 + rr) * DP + c8 * 8;
-            *reinterpret_cast<uint4*>(ph + rr * Cfg::LDH + c8 * 8) = *reinterpret_cast<const uint4*>(a.pi_h + src);
-            *reinterpret_cast<uint4*>(pl + rr * Cfg::LDH + c8 * 8) = *reinterpret_cast<const uint4*>(a.pi_l + src);
-        }
-        __syncthreads();
+    for (int t = 0; t < NT; ++t) {
+        if (t + 1 < NT) { IVFTQ_FETCH_TILE(t + 1) }   // in flight during this tile's multiplies
+        const uint16_t* ah_base = stage + (t & 1) * Cfg::stage_halves + j * LDH + 8 * half;
+        const uint16_t* al_base = ah_base + 32 * LDH;
+        floatx16 acc[R];
 #pragma unroll
-        for (int q = 0; q < 16; ++q) acc[t][q] = 0.f;
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int q = 0; q < 16; ++q) acc[r][q] = 0.f;
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb) {
             const half8 ah = *reinterpret_cast<const half8*>(ah_base + 16 * kb);
             const half8 al = *reinterpret_cast<const half8*>(al_base + 16 * kb);
-            acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah, bh[kb], acc[t], 0, 0, 0);
-            acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah, bl[kb], acc[t], 0, 0, 0);
-            acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(al, bh[kb], acc[t], 0, 0, 0);
-        }
-    }
-    constexpr float kUnscale = 1.f / (kSplitScale * kSplitScale);
-
-    if (mode == 2) {
-        if (valid) {
 #pragma unroll
-            for (int t = 0; t < Cfg::NT; ++t)
+            for (int r = 0; r < R; ++r) acc[r] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah, bh[r][kb], acc[r], 0, 0, 0);
+#pragma unroll
+            for (int r = 0; r < R; ++r) acc[r] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah, bl[r][kb], acc[r], 0, 0, 0);
+#pragma unroll
+            for (int r = 0; r < R; ++r) acc[r] = __builtin_amdgcn_mfma_f32_32x32x16_f16(al, bh[r][kb], acc[r], 0, 0, 0);
+        }
+        if (t + 1 < NT) { IVFTQ_STORE_TILE((t + 1) & 1) }   // that buffer was last read before the previous barrier
+
+        if (mode == 2) {
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                if (!valid[r]) continue;
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
-                    const float4 o = make_float4(acc[t][4 * g] * kUnscale, acc[t][4 * g + 1] * kUnscale,
-                                                 acc[t][4 * g + 2] * kUnscale, acc[t][4 * g + 3] * kUnscale);
-                    const int64_t at = row * (int64_t)DP + t * 32 + 8 * g + 4 * half;
+                    const float4 o = make_float4(acc[r][4 * g] * kUnscale, acc[r][4 * g + 1] * kUnscale,
+                                                 acc[r][4 * g + 2] * kUnscale, acc[r][4 * g + 3] * kUnscale);
+                    const int64_t at = row_of[r] * (int64_t)DP + t * 32 + 8 * g + 4 * half;
                     *reinterpret_cast<float4*>(a.zout + at) = o;
                     if (a.zh_out) {
                         const float z[4] = {o.x, o.y, o.z, o.w};
@@ -141,99 +202,106 @@ void k_encode(int mode, EncodeArgs a, int vec4) {
                         *reinterpret_cast<uint2*>(a.zl_out + at) = make_uint2(l[0] | ((uint32_t)l[1] << 16), l[2] | ((uint32_t)l[3] << 16));
                     }
                 }
-        }
-        return;
-    }
-
-    // |Pi r^| in the accumulators' scale (rows of Pi beyond d are zero, so padded coordinates add nothing)
-    float u2 = 0.f;
+            }
+        } else {
+            const bool ragged = 32 * t + 32 > d;      // some coordinates of this tile are padding
 #pragma unroll
-    for (int t = 0; t < Cfg::NT; ++t)
+            for (int r = 0; r < R; ++r) {
 #pragma unroll
-        for (int q = 0; q < 16; ++q) u2 += acc[t][q] * acc[t][q];
-    u2 += __shfl_xor(u2, 32);
-    const float un = sqrtf(u2);
-    const float inv_u = (un > 1e-30f) ? 1.f / un : 0.f;   // a zero residual quantises as rho = 0
-
-    // quantise: code = #{i : rho >= tau_i}, by bisection over the ascending boundaries
-    uint8_t* my_codes = code_s + wave * (32 * DP) + j * DP;
+                for (int g = 0; g < 4; ++g) {
+                    const int c0 = 32 * t + 8 * g + 4 * half;
+                    uint32_t code[4];
 #pragma unroll
-    for (int t = 0; t < Cfg::NT; ++t) {
+                    for (int e = 0; e < 4; ++e) {
+                        const float av = acc[r][4 * g + e];
+                        const float rho = av * kUnscale;
+                        int cell = (int)fmaf(av, q_scale, q_offset);
+                        cell = cell < 0 ? 0 : (cell > q_last ? q_last : cell);
+                        const float2 ent = grid_s[cell];
+                        code[e] = (uint32_t)__float_as_int(ent.y) + (rho >= ent.x ? 1u : 0u);
+                        if (ragged && c0 + e >= d) code[e] = 0u;
+                    }
+                    if (mode == 1) {
+                        if (a.codes_flat && valid[r]) {
+                            uint8_t* out = a.codes_flat + row_of[r] * (int64_t)d + c0;
+                            if (!ragged && codes4) {
+                                *reinterpret_cast<uint32_t*>(out) = code[0] | (code[1] << 8) | (code[2] << 16) | (code[3] << 24);
+                            } else {
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            uint32_t packed = 0;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const float rho = acc[t][4 * g + e] * inv_u;
-                int code = 0;
-#pragma unroll
-                for (int lvl = 7; lvl >= 0; --lvl) {       // straight-line bisection, levels above b skipped
-                    const int step = 1 << lvl;
-                    if (step < K && rho >= tau_s[code + step - 1]) code += step;
+                                for (int e = 0; e < 4; ++e)
+                                    if (c0 + e < d) out[e] = (uint8_t)code[e];
+                            }
+                        }
+                    } else {
+                        // four codes = 4b bits at bit c0*b of the row's little-endian bit string
+                        const uint32_t chunk = code[0] | (code[1] << b) | (code[2] << (2 * b)) | (code[3] << (3 * b));
+                        const int bit = c0 * b;
+                        const int sh = bit & 31;
+                        uint32_t* wp = my_pack + (32 * r + j) * pitch + (bit >> 5);
+                        const uint32_t lo = chunk << sh;
+                        const uint32_t hi = sh ? chunk >> (32 - sh) : 0u;
+                        if (lo) atomicOr(wp, lo);
+                        if (hi) atomicOr(wp + 1, hi);
+                    }
                 }
-                packed |= (uint32_t)code << (8 * e);
             }
-            *reinterpret_cast<uint32_t*>(my_codes + t * 32 + 8 * g + 4 * half) = packed;
         }
+        if (t + 1 < NT) __syncthreads();
     }
-    __syncthreads();
+    if (mode == 2) return;
 
-    const uint8_t* wave_codes = code_s + wave * (32 * DP);
     if (mode == 1) {
-        if (a.codes_flat) {
-            const int64_t rows_here = (a.n - row0) < 32 ? (a.n - row0) : 32;
-            for (int64_t e = lane; e < rows_here * d; e += 64) {
-                const int rl = (int)(e / d), c = (int)(e % d);
-                a.codes_flat[row0 * d + e] = wave_codes[rl * DP + c];
-            }
-        }
-        if (valid && half == 0 && a.gamma_flat)
-            a.gamma_flat[row] = __half_as_ushort(__float2half_rn(cell >= 0 ? gamma : 0.f));
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+            if (valid[r] && half == 0 && a.gamma_flat)
+                a.gamma_flat[row_of[r]] = __half_as_ushort(__float2half_rn(gamma[r]));
         return;
     }
 
-    // mode 0: pack b-bit codes into 32-bit words (coordinate j occupies bits [j*b, j*b+b) of the
-    // vector's little-endian bit string) and scatter them to the vector's storage slot.
-    const int words = a.store.words;
-    const int b = a.b;
-    for (int item = lane; item < 32 * words; item += 64) {
-        const int rl = item & 31, w = item >> 5;
-        const int64_t rrow = row0 + rl;
-        if (rrow >= a.n) continue;
-        const int64_t slot = a.slot[rrow];
-        if (slot < 0) continue;
-        const int first = (32 * w) / b;
-        uint32_t word = 0;
-        for (int c = first; c < d; ++c) {
-            const int sh = c * b - 32 * w;
-            if (sh >= 32) break;
-            const uint32_t code = wave_codes[rl * DP + c];
-            word |= sh >= 0 ? (code << sh) : (code >> (-sh));
+    // ---- mode 0: the wavefront's packed words go to the rows' storage slots.  Lane (j, half) stores
+    // row 32*half + j when R = 2 (every word), row j when R = 1 (words of parity `half`).
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+    const int my_r = (R == 2) ? half : 0;
+    const bool mine = (R == 2) ? (half ? valid[R - 1] : valid[0]) : valid[0];
+    const int64_t my_row = (R == 2 && half) ? row_of[R - 1] : row_of[0];
+    const float my_gamma = (R == 2 && half) ? gamma[R - 1] : gamma[0];
+    const int64_t slot = mine ? a.slot[my_row] : -1;
+    if (slot >= 0) {
+        const uint32_t* src = my_pack + (32 * my_r + j) * pitch;
+        uint32_t* dst = a.store.codes + (slot >> 6) * (int64_t)words * 64 + (slot & 63);
+        if (R == 2) {
+            for (int w = 0; w < words; ++w) dst[(int64_t)w * 64] = src[w];
+        } else {
+            for (int w = half; w < words; w += 2) dst[(int64_t)w * 64] = src[w];
         }
-        a.store.codes[((slot >> 6) * words + w) * 64 + (slot & 63)] = word;
-    }
-    if (valid && half == 0) {
-        const int64_t slot = a.slot[row];
-        if (slot >= 0) {
-            a.store.gamma[slot] = __half_as_ushort(__float2half_rn(gamma));
-            a.store.ids[slot] = a.labels ? a.labels[row] : a.label_base + row;
+        if (R == 2 || half == 0) {
+            a.store.gamma[slot] = __half_as_ushort(__float2half_rn(my_gamma));
+            a.store.ids[slot] = a.labels ? a.labels[my_row] : a.label_base + my_row;
         }
     }
 }
 
+#undef IVFTQ_FETCH_TILE
+#undef IVFTQ_STORE_TILE
+
 template <int DP>
 hipError_t run(int mode, const EncodeArgs& a, hipStream_t st) {
-    static bool attr_set = false;
-    const size_t lds = EncCfg<DP>::lds_bytes;
-    if (!attr_set) {
+    static size_t attr_lds = 0;
+    const size_t lds = encode_lds_bytes<DP>(mode, a.q_cells, a.store.words);
+    if (lds > 160 * 1024) return hipErrorInvalidValue;
+    if (lds > attr_lds) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_encode<DP>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
-        attr_set = true;
+        attr_lds = lds;
     }
-    const int64_t blocks = (a.n + kRowsPerWG - 1) / kRowsPerWG;
-    const int vec4 = (a.d % 4 == 0) && (reinterpret_cast<uintptr_t>(a.x) % 16 == 0);
-    hipLaunchKernelGGL(k_encode<DP>, dim3((unsigned)blocks), dim3(256), lds, st, mode, a, vec4);
+    const int rows_per_wg = 4 * 32 * EncCfg<DP>::R;
+    const int64_t blocks = (a.n + rows_per_wg - 1) / rows_per_wg;
+    int flags = 0;
+    if (a.d % 4 == 0 && reinterpret_cast<uintptr_t>(a.x) % 16 == 0) flags |= 1;
+    if (a.d % 4 == 0 && reinterpret_cast<uintptr_t>(a.codes_flat) % 4 == 0) flags |= 2;
+    hipLaunchKernelGGL(k_encode<DP>, dim3((unsigned)blocks), dim3(256), lds, st, mode, a, flags);
     return hipGetLastError();
 }
 
@@ -241,6 +309,7 @@ hipError_t run(int mode, const EncodeArgs& a, hipStream_t st) {
 
 hipError_t launch_encode(int mode, const EncodeArgs& a, hipStream_t st) {
     if (a.n <= 0) return hipSuccess;
+    if (mode != 2 && (a.q_cells < 1 || !a.q_grid)) return hipErrorInvalidValue;
     switch (rot_dp(a.d)) {
         case 32: return run<32>(mode, a, st);
         case 64: return run<64>(mode, a, st);

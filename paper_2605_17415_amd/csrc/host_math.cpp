@@ -231,4 +231,51 @@ bool haar_from_gaussian(int d, const double* g, std::vector<double>& q) {
     return true;
 }
 
+double orthogonality_defect(int d, const float* pi) {
+    double sum = 0.0;
+    for (int i = 0; i < d; ++i)
+        for (int j = i; j < d; ++j) {
+            double dot = 0.0;
+            for (int k = 0; k < d; ++k) dot += (double)pi[(size_t)i * d + k] * (double)pi[(size_t)j * d + k];
+            const double e = dot - (i == j ? 1.0 : 0.0);
+            sum += (i == j ? 1.0 : 2.0) * e * e;
+        }
+    return std::sqrt(sum);
+}
+
+bool build_quantiser_grid(const std::vector<float>& tau, int max_cells, QuantiserGrid& grid) {
+    const int nb = (int)tau.size();
+    if (nb < 1) return false;
+    if (nb == 1) {
+        grid.cells = 1;
+        grid.scale = 0.f;
+        grid.offset = 0.f;
+        grid.boundary.assign(1, tau[0]);
+        grid.index.assign(1, 0);
+        return true;
+    }
+    double gap = 1e300;
+    for (int i = 1; i < nb; ++i) {
+        if (!(tau[i] > tau[i - 1])) return false;
+        gap = std::min(gap, (double)tau[i] - (double)tau[i - 1]);
+    }
+    const double w = 0.5 * gap;
+    const double lo = (double)tau[0] - w;
+    const int cells = (int)std::ceil(((double)tau[nb - 1] + w - lo) / w) + 1;
+    if (cells > max_cells) return false;
+    grid.cells = cells;
+    grid.scale = (float)(1.0 / w);
+    grid.offset = (float)(-lo / w);
+    grid.boundary.resize(cells);
+    grid.index.resize(cells);
+    int near = 0;
+    for (int i = 0; i < cells; ++i) {
+        const double mid = lo + (i + 0.5) * w;
+        while (near + 1 < nb && std::fabs((double)tau[near + 1] - mid) < std::fabs((double)tau[near] - mid)) ++near;
+        grid.boundary[i] = tau[near];
+        grid.index[i] = near;
+    }
+    return true;
+}
+
 }  // namespace ivftq

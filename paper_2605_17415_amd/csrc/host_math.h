@@ -14,4 +14,22 @@ void gaussian_matrix(int d, uint64_t seed, std::vector<double>& g);
 // Orthogonal factor of g with the sign convention diag(R) > 0 (Haar when g is Gaussian).
 bool haar_from_gaussian(int d, const double* g, std::vector<double>& q);
 
+// Frobenius norm of pi * pi^T - I for a d x d row-major matrix.
+double orthogonality_defect(int d, const float* pi);
+
+// Uniform-grid index over the ascending quantiser boundaries tau (K-1 of them, K-1 >= 1).  The real
+// line is cut into `cells` intervals of equal width (the two outermost ones open-ended); entry i
+// holds the boundary nearest to the middle of cell i and that boundary's index, so that for a value v
+// falling in cell i  #{j : v >= tau_j} = index_i + (v >= boundary_i).  The cell width is half the
+// smallest gap between boundaries, which makes the identity hold also for values up to a quarter
+// cell outside the cell they were put in (rounding of the cell computation).
+//   cell(v) = clamp(int(v * scale + offset), 0, cells - 1)
+struct QuantiserGrid {
+    std::vector<float> boundary;   // [cells]
+    std::vector<int32_t> index;    // [cells]
+    float scale = 0.f, offset = 0.f;
+    int cells = 0;
+};
+bool build_quantiser_grid(const std::vector<float>& tau, int max_cells, QuantiserGrid& grid);
+
 }  // namespace ivftq

@@ -12,6 +12,7 @@ constexpr int kRowsPerWG = 128;      // data rows one workgroup of the contracti
 constexpr int kMaxD = 256;
 constexpr int kMaxList = 16384;
 constexpr int kMaxK = 2048;
+constexpr int kMaxGridCells = 4096;  // entries of the quantiser's uniform-grid index (32 KB of LDS)
 
 // Split float16 form used by the float16 matrix-core kernels: V = 1024*v, hi = fp16(V),
 // lo = fp16(V - hi).  hi + lo equals V to about 2^-22 relative; the factor keeps lo in the normal
@@ -40,7 +41,7 @@ struct ListStore {
     int words;
 };
 
-// ---- contraction kernels (MFMA fp32) --------------------------------------------------------
+// ---- contraction kernels (split float16 MFMA) --------------------------------------------------------
 
 // mode 0: assign[i] = argmax_c (<x~_i, cent_c> + bias_c), best[i] that value (either may be null)
 // mode 1: scores[i*ld_scores + c] = <x~_i, cent_c> for c < L
@@ -53,16 +54,20 @@ hipError_t launch_coarse(int mode, const float* x, int64_t n, int d, const uint1
 // hi[i], lo[i] = split float16 form of src[i]
 hipError_t launch_split_rows(const float* src, int64_t count, uint16_t* hi, uint16_t* lo, hipStream_t st);
 
-// Rotation family.  pi_h/pi_l: split form of Pi, [DP][DP] zero padded, DP = rot_dp(d); tau: 2^b - 1 boundaries.
-// mode 0: residual -> rotate -> normalise -> quantise -> pack into the list store at slot[i]
+// Rotation family.  pi_h/pi_l: split form of Pi, [DP][DP] zero padded, DP = rot_dp(d).
+// mode 0: residual -> rotate -> quantise -> pack into the list store at slot[row]
 // mode 1: same, but write unpacked codes / fp16 norms to flat arrays (any may be null)
 // mode 2: z_i = Pi x~_i written to zout[i*DP + j] (no centroid, no quantiser)
+// q_grid: the quantiser's uniform-grid index (host_math.h), q_cells entries of (boundary, index bits).
+// order (may be null): row processed at position p is order[p] (rows grouped by list, so that the
+// stores of neighbouring lanes fall into neighbouring slots); null = input order.
 struct EncodeArgs {
     const float* x; int64_t n; int d; int b;
     const float* cent; int cent_pitch;
     const uint16_t* pi_h; const uint16_t* pi_l;   // split float16 form of Pi, [DP][DP]
-    const float* tau;
+    const float2* q_grid; int q_cells; float q_scale, q_offset;
     const int32_t* assign;
+    const int32_t* order;
     // mode 0
     ListStore store; const int64_t* slot; const int64_t* labels; int64_t label_base;
     // mode 1

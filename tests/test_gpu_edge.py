@@ -44,6 +44,13 @@ def test_error_paths_do_not_launch_or_append():
         with pytest.raises(pkg.IvftqError) as e:
             ix.search(x, **bad)
         assert e.value.status in (1, 6)
+    # a rotation that is not orthogonal is refused and the index keeps the one it had
+    skew = cs.Pi.copy()
+    skew[0] *= 1.001
+    with pytest.raises(pkg.IvftqError) as e:
+        ix.set_rotation(skew)
+    assert e.value.status == 1
+    np.testing.assert_array_equal(ix.get_rotation(), cs.Pi)
     # a zero row: error, nothing appended
     xz = x.clone()
     xz[17] = 0

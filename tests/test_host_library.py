@@ -99,3 +99,31 @@ def test_create_rejects_bad_arguments_before_touching_a_device():
     assert not h.value
     assert lib.ivftq_ntotal(None) == -1
     assert lib.ivftq_destroy(None) == 0
+
+
+@pytest.mark.parametrize("b,d", [(1, 64), (2, 96), (3, 96), (4, 8), (4, 128), (4, 200), (5, 100), (6, 70), (7, 96), (8, 8),
+                                 (8, 256)])
+def test_quantiser_grid_counts_boundaries_exactly(b, d):
+    """The table the encode kernel quantises through gives code = #{i : v >= tau_i} (bins
+    [tau_i, tau_{i+1})) for every float32 value: at, just below and just above every boundary, at the
+    cell edges of the grid itself, far outside, and for random values; also when the cell number is
+    off by the rounding of its float32 computation."""
+    _, tau = pkg.ivftq_build_codebook(b, d)
+    cells, scale, offset, boundary, index = pkg.ivftq_quantiser_grid(b, d)
+    assert 1 <= cells <= 4096 and boundary.shape == (cells,) and index.shape == (cells,)
+    rng = np.random.default_rng(b * 1000 + d)
+    vals = [tau, np.nextafter(tau, np.float32(-2)), np.nextafter(tau, np.float32(2)),
+            np.float32([-1.0, 1.0, 0.0, -0.0, -3.0, 3.0, 1e-30, -1e-30]),
+            (rng.standard_normal(20000) / math.sqrt(d)).astype(np.float32),
+            rng.uniform(-1, 1, 20000).astype(np.float32)]
+    if cells > 1:
+        edges = ((np.arange(cells + 1, dtype=np.float64) - float(offset)) / float(scale)).astype(np.float32)
+        vals += [edges, np.nextafter(edges, np.float32(-2)), np.nextafter(edges, np.float32(2))]
+    v = np.concatenate(vals).astype(np.float32)
+    want = np.searchsorted(tau, v, side="right")            # number of boundaries <= v
+    x = v * scale + offset                                   # float32 arithmetic, as on the device
+    assert x.dtype == np.float32
+    for nudge in (0.0, -0.2, 0.2):                           # a fifth of a cell of slack either way
+        cell = np.clip(np.trunc(x.astype(np.float64) + nudge), 0, cells - 1).astype(np.int64)
+        got = index[cell] + (v >= boundary[cell])
+        np.testing.assert_array_equal(got, want)
