@@ -96,7 +96,7 @@ struct ivftq_index {
     int64_t pool_slots = 0;
     int64_t ntotal = 0;
     // workspace
-    DevBuf w_assign, w_slot, w_hist, w_count, w_base, w_flag, w_best;
+    DevBuf w_assign, w_slot, w_order, w_hist, w_count, w_base, w_flag, w_best;
     DevBuf w_S, w_probe, w_coarse, w_z, w_candoff, w_scores;
     DevBuf w_sums, w_counts, w_zero, w_rows, w_dst, w_obj;
     DevBuf w_zh, w_zl;
@@ -119,7 +119,7 @@ struct ivftq_index {
     ~ivftq_index() {
         for (ProfRec& r : prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
         for (DevBuf* bfr : {&cent, &cent_h, &cent_l, &pi_h, &pi_l, &bias, &pi, &cb, &q_grid, &codes, &gamma, &ids, &d_off, &d_size, &w_assign,
-                            &w_slot, &w_hist, &w_count, &w_base, &w_flag, &w_best, &w_S, &w_probe, &w_coarse,
+                            &w_slot, &w_order, &w_hist, &w_count, &w_base, &w_flag, &w_best, &w_S, &w_probe, &w_coarse,
                             &w_z, &w_candoff, &w_scores, &w_sums, &w_counts, &w_zero, &w_rows, &w_dst, &w_obj,
                             &w_first, &w_fscores, &w_fids, &w_pairs, &w_pairoff, &w_tileoff, &w_cscore,
                             &w_cslot, &w_ccnt, &w_gate, &w_zh, &w_zl})
@@ -614,14 +614,15 @@ namespace {
 // Steps shared by every append: count the rows of each list, make room, and give each row its
 // slot (list order = arrival order).  `assign` holds a cell number per row; with zero_norm_flag
 // the flag word written by the coarse kernel is checked too.  Nothing is modified on failure.
-ivftq_status place_rows(ivftq_index* ix, const int32_t* assign, int64_t n, bool zero_norm_flag,
+ivftq_status place_rows(ivftq_index* ix, const int32_t* assign, int64_t n, bool zero_norm_flag, bool want_order,
                         std::vector<int64_t>& need, hipStream_t st) {
     const int L = ix->nlist;
     int64_t seg_len = round_up64((n + 1023) / 1024, 64);
     const int nseg = (int)((n + seg_len - 1) / seg_len);
     HIP_TRY(ix->w_hist.ensure((size_t)nseg * L * sizeof(uint32_t)));
     HIP_TRY(ix->w_count.ensure((size_t)L * sizeof(uint32_t)));
-    HIP_TRY(ix->w_base.ensure((size_t)L * sizeof(int64_t)));
+    HIP_TRY(ix->w_base.ensure((size_t)2 * L * sizeof(int64_t)));
+    if (want_order) HIP_TRY(ix->w_order.ensure((size_t)n * sizeof(int32_t)));
     HIP_TRY(timed(ix, st, P_SEG_HIST, [&] { return launch_segment_hist(assign, n, seg_len, nseg, L, ix->w_hist.as<uint32_t>(), st); }));
     HIP_TRY(timed(ix, st, P_SEG_SCAN, [&] { return launch_segment_scan(ix->w_hist.as<uint32_t>(), nseg, L, ix->w_count.as<uint32_t>(), st); }));
     std::vector<uint32_t> count(L);
@@ -636,16 +637,22 @@ ivftq_status place_rows(ivftq_index* ix, const int32_t* assign, int64_t n, bool 
     if (placed != n) return fail(IVFTQ_INVALID_ARG, "%lld rows carry a cell number outside [0, nlist)", (long long)(n - placed));
 
     need.resize(L);
-    std::vector<int64_t> base(L);
+    std::vector<int64_t> base(2 * (size_t)L);     // [0, L): first free slot of each list; [L, 2L): first position in the batch order
     for (int l = 0; l < L; ++l) need[l] = (int64_t)ix->h_size[l] + count[l];
     for (int l = 0; l < L; ++l)
         if (need[l] > INT32_MAX) return fail(IVFTQ_UNSUPPORTED, "list %d would exceed 2^31-1 vectors", l);
     ivftq_status s = ensure_capacity(ix, need, st);
     if (s != IVFTQ_OK) return s;
-    for (int l = 0; l < L; ++l) base[l] = ix->h_off[l] + ix->h_size[l];
-    HIP_TRY(hipMemcpyAsync(ix->w_base.p, base.data(), L * sizeof(int64_t), hipMemcpyHostToDevice, st));
+    int64_t run = 0;
+    for (int l = 0; l < L; ++l) {
+        base[l] = ix->h_off[l] + ix->h_size[l];
+        base[L + l] = run;
+        run += count[l];
+    }
+    HIP_TRY(hipMemcpyAsync(ix->w_base.p, base.data(), base.size() * sizeof(int64_t), hipMemcpyHostToDevice, st));
     HIP_TRY(timed(ix, st, P_RANK, [&] { return launch_stable_rank(assign, n, seg_len, nseg, L, ix->w_hist.as<uint32_t>(), ix->w_base.as<int64_t>(),
-                               ix->w_slot.as<int64_t>(), st); }));
+                               ix->w_slot.as<int64_t>(), ix->w_base.as<int64_t>() + L,
+                               want_order ? ix->w_order.as<int32_t>() : nullptr, st); }));
     HIP_TRY(hipStreamSynchronize(st));   // `base` is pageable host memory
     return IVFTQ_OK;
 }
@@ -706,7 +713,7 @@ ivftq_status ivftq_encode_add(ivftq_index* ix, const float* x_dev, int64_t n, co
 
     // 2.-4. room for the new vectors and the stable position of every row
     std::vector<int64_t> need;
-    ivftq_status s = place_rows(ix, ix->w_assign.as<int32_t>(), n, true, need, st);
+    ivftq_status s = place_rows(ix, ix->w_assign.as<int32_t>(), n, true, true, need, st);
     if (s != IVFTQ_OK) return s;
     // 5. rotate / quantise / pack straight into the lists
     EncodeArgs a{};
@@ -717,6 +724,7 @@ ivftq_status ivftq_encode_add(ivftq_index* ix, const float* x_dev, int64_t n, co
     a.assign = ix->w_assign.as<int32_t>();
     a.store = ix->store();
     a.slot = ix->w_slot.as<int64_t>();
+    a.order = ix->w_order.as<int32_t>();       // rows in list order: neighbouring lanes store to neighbouring slots
     a.labels = ids_dev; a.label_base = ix->ntotal;
     HIP_TRY(timed(ix, st, P_ENCODE, [&] { return launch_encode(0, a, st); }));
     return commit_rows(ix, need, n, st);
@@ -734,7 +742,7 @@ ivftq_status ivftq_add_encoded(ivftq_index* ix, int64_t n, const int32_t* assign
     HIP_TRY(ix->w_slot.ensure((size_t)n * sizeof(int64_t)));
     HIP_TRY(launch_fill_u32(ix->w_flag.as<uint32_t>(), 1, 0u, st));
     std::vector<int64_t> need;
-    ivftq_status s = place_rows(ix, assign_dev, n, false, need, st);
+    ivftq_status s = place_rows(ix, assign_dev, n, false, false, need, st);
     if (s != IVFTQ_OK) return s;
     HIP_TRY(timed(ix, st, P_PACK, [&] { return launch_pack_scatter(codes_dev, gamma_dev, ids_dev, ix->ntotal, ix->w_slot.as<int64_t>(), n, ix->d,
                                 ix->b, ix->store(), st); }));

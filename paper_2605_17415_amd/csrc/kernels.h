@@ -87,10 +87,12 @@ hipError_t launch_segment_hist(const int32_t* assign, int64_t n, int64_t seg_len
                                uint32_t* seg_hist, hipStream_t st);
 // in place: seg_hist[s][l] <- sum_{s'<s} seg_hist[s'][l];  batch_count[l] <- column total
 hipError_t launch_segment_scan(uint32_t* seg_hist, int nseg, int L, uint32_t* batch_count, hipStream_t st);
-// slot[i] = list_base[l] + (rank of row i among the batch rows of list l, in input order)
+// slot[i] = list_base[l] + (rank of row i among the batch rows of list l, in input order).
+// order (may be null): the batch's rows grouped by list, lists ascending, input order inside a list:
+// order[batch_base[l] + rank] = i, with batch_base the exclusive running sum of the batch's rows per list.
 hipError_t launch_stable_rank(const int32_t* assign, int64_t n, int64_t seg_len, int nseg, int L,
                               const uint32_t* seg_hist, const int64_t* list_base, int64_t* slot,
-                              hipStream_t st);
+                              const int64_t* batch_base, int32_t* order, hipStream_t st);
 // pack already-quantised rows (codes: n x d bytes, one bin number each) into their storage slots
 hipError_t launch_pack_scatter(const uint8_t* codes, const uint16_t* gamma, const int64_t* labels,
                                int64_t label_base, const int64_t* slot, int64_t n, int d, int b,
