@@ -247,8 +247,13 @@ def main():
              "mfma_dtype": "f16 (3 split passes per product, f32 accumulate)"}
         r["frac"] = r["achieved"] / r["peak"]
         r["issued_frac"] = SPLIT_PASSES * r["frac"]      # share of the fp16 pipe's peak actually issued
+        r["issued_vs_measured_pipe_rate"] = SPLIT_PASSES * r["achieved"] / mfma_random
         return r
 
+    # what a loop of nothing but the fp16 MFMA instruction reaches on this device: with constant operands
+    # (close to the nominal peak) and with random operand bits (the chip lowers its clock under real data)
+    mfma_const = pkg.ivftq_measure_mfma_rate(False)
+    mfma_random = pkg.ivftq_measure_mfma_rate(True)
     batched = "batch_scan" in prof
     rooflines = {"coarse_assign": mfma_roof("coarse_assign", assign_flops),
                  "encode_rotate_quantise_pack": mfma_roof("encode_rotate_quantise_pack", 2.0 * w.d * w.d * w.n)}
@@ -305,6 +310,9 @@ def main():
         "search_ms_with_kernel_events": float(np.mean(search_ms_p)), "encode_ms_with_kernel_events": float(np.mean(enc_ms_p)),
         "kernel_ms_per_step": per_step, "dominant_kernel": dominant,
         "roofline": roofline, "rooflines": rooflines, "scan_stage_vs_streamed_bytes": scan_stage,
+        "mfma_pipe_measured": {"unit": "TFLOP/s", "instruction": "v_mfma_f32_32x32x16_f16", "constant_operands": mfma_const,
+                               "random_operands": mfma_random,
+                               "note": "pure MFMA loop, 2 wavefronts per SIMD; issued_vs_measured_pipe_rate compares with random_operands"},
         "sweep": sweep,
         "setup_s": t_setup, "train_coarse_s": t_train,
     }

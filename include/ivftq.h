@@ -179,6 +179,13 @@ ivftq_status ivftq_profile_read(ivftq_index* index, double* ms_out, int64_t* lau
 int ivftq_profile_kernel_count(void);
 const char* ivftq_profile_kernel_name(int id);
 
+/* Measurement aid: the rate (TFLOP/s, 2*32*32*16 flop per instruction) that a loop of nothing but
+ * v_mfma_f32_32x32x16_f16, the instruction every contraction of this library uses, reaches on the
+ * current device, two wavefronts per SIMD, operands in registers.  random_operands != 0: operands
+ * with random sign and mantissa bits (the switching activity of real data, under which the chip
+ * lowers its clock); 0: all operands 1.0.  Allocates and frees its own small buffers; synchronises. */
+ivftq_status ivftq_measure_mfma_rate(int random_operands, double* tflops_out);
+
 const char* ivftq_last_error(void);
 const char* ivftq_version(void);
 

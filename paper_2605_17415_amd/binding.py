@@ -53,6 +53,7 @@ _SIGNATURES = {
     "ivftq_profile_read": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
     "ivftq_profile_kernel_count": (C.c_int, []),
     "ivftq_profile_kernel_name": (C.c_char_p, [C.c_int]),
+    "ivftq_measure_mfma_rate": (C.c_int, [C.c_int, C.POINTER(C.c_double)]),
     "ivftq_last_error": (C.c_char_p, []),
     "ivftq_version": (C.c_char_p, []),
 }
@@ -155,6 +156,13 @@ def ivftq_haar_from_gaussian(g: np.ndarray) -> np.ndarray:
     pi = np.empty((d, d), np.float32)
     _check(lib.ivftq_haar_from_gaussian(d, _np_ptr(g), _np_ptr(pi)))
     return pi
+
+
+def ivftq_measure_mfma_rate(random_operands: bool = True) -> float:
+    """TFLOP/s of a pure v_mfma_f32_32x32x16_f16 loop on the current device."""
+    out = C.c_double(0)
+    _check(load_library().ivftq_measure_mfma_rate(1 if random_operands else 0, C.byref(out)))
+    return out.value
 
 
 def ivftq_version() -> str:

@@ -440,6 +440,43 @@ int ivftq_profile_kernel_count(void) { return P_COUNT; }
 
 const char* ivftq_profile_kernel_name(int id) { return (id >= 0 && id < P_COUNT) ? kProfNames[id] : ""; }
 
+ivftq_status ivftq_measure_mfma_rate(int random_operands, double* tflops_out) {
+    if (!tflops_out) return fail(IVFTQ_INVALID_ARG, "tflops_out is NULL");
+    int dev = 0, cus = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+    const int blocks = 2 * cus, iters = 2000;                 // two wavefronts per SIMD
+    std::vector<uint16_t> h(4096 * 8);
+    uint64_t s = 0x243F6A8885A308D3ull;
+    for (auto& v : h) {
+        s = s * 6364136223846793005ull + 1442695040888963407ull;
+        // random sign and mantissa, exponent of values in [1, 64): finite, no subnormals
+        const uint16_t bits = (uint16_t)(s >> 40);
+        v = random_operands ? (uint16_t)((bits & 0x83FF) | (uint16_t)((15 + ((bits >> 10) % 6)) << 10)) : (uint16_t)0x3C00;
+    }
+    struct Scratch { DevBuf operands, out; ~Scratch() { operands.release(); out.release(); } } scratch;
+    DevBuf& operands = scratch.operands;
+    DevBuf& out = scratch.out;
+    HIP_TRY(operands.ensure(h.size() * sizeof(uint16_t)));
+    HIP_TRY(out.ensure((size_t)blocks * 256 * sizeof(float)));
+    HIP_TRY(hipMemcpy(operands.p, h.data(), h.size() * sizeof(uint16_t), hipMemcpyHostToDevice));
+    hipEvent_t e0, e1;
+    HIP_TRY(hipEventCreate(&e0));
+    HIP_TRY(hipEventCreate(&e1));
+    HIP_TRY(launch_mfma_peak(operands.as<uint16_t>(), out.as<float>(), blocks, 20, nullptr));
+    HIP_TRY(hipEventRecord(e0, nullptr));
+    HIP_TRY(launch_mfma_peak(operands.as<uint16_t>(), out.as<float>(), blocks, iters, nullptr));
+    HIP_TRY(hipEventRecord(e1, nullptr));
+    HIP_TRY(hipEventSynchronize(e1));
+    float ms = 0.f;
+    HIP_TRY(hipEventElapsedTime(&ms, e0, e1));
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    const double flops = (double)blocks * 4 * iters * 32 * (2.0 * 32 * 32 * 16);
+    *tflops_out = flops / (ms * 1e-3) / 1e12;
+    return IVFTQ_OK;
+}
+
 ivftq_status ivftq_profile_read(ivftq_index* ix, double* ms_out, int64_t* launches_out) {
     if (check_index(ix)) return IVFTQ_INVALID_ARG;
     if (!ms_out || !launches_out) return fail(IVFTQ_INVALID_ARG, "output pointer is NULL");

@@ -214,7 +214,42 @@ hipError_t run(int mode, const float* x, int64_t n, int d, const uint16_t* cent_
     return hipGetLastError();
 }
 
+// Calibration of the float16 matrix pipe: nothing but v_mfma_f32_32x32x16_f16 on operands held in
+// registers, four independent accumulators per wavefront, two wavefronts per SIMD.  What this
+// reaches with random operand bits is the rate the contraction kernels can be compared with: the
+// chip lowers its clock under the switching activity of real data, so it is below the nominal peak.
+__global__ __launch_bounds__(256) void k_mfma_peak(const half8* __restrict__ src, float* __restrict__ out, int iters) {
+    half8 a[8], b[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        a[i] = src[(threadIdx.x * 16 + i) & 4095];
+        b[i] = src[(threadIdx.x * 16 + 8 + i) & 4095];
+    }
+    floatx16 acc[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+#pragma unroll
+        for (int q = 0; q < 16; ++q) acc[c][q] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[(i + c) & 7], b[i], acc[c], 0, 0, 0);
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+#pragma unroll
+        for (int q = 0; q < 16; ++q) s += acc[c][q];
+    out[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = s;
+}
+
 }  // namespace
+
+hipError_t launch_mfma_peak(const uint16_t* operands, float* out, int blocks, int iters, hipStream_t st) {
+    hipLaunchKernelGGL(k_mfma_peak, dim3(blocks), dim3(256), 0, st, reinterpret_cast<const half8*>(operands), out, iters);
+    return hipGetLastError();
+}
 
 int coarse_dp(int d) {
     static const int sizes[] = {32, 64, 96, 128, 160, 192, 208, 224, 256};

@@ -54,6 +54,10 @@ hipError_t launch_coarse(int mode, const float* x, int64_t n, int d, const uint1
 // hi[i], lo[i] = split float16 form of src[i]
 hipError_t launch_split_rows(const float* src, int64_t count, uint16_t* hi, uint16_t* lo, hipStream_t st);
 
+// Pure-MFMA calibration loop: `blocks` workgroups of 4 wavefronts, each wavefront issues 32*iters
+// v_mfma_f32_32x32x16_f16.  operands: 4096*8 float16 values (any finite bits); out: blocks*256 floats.
+hipError_t launch_mfma_peak(const uint16_t* operands, float* out, int blocks, int iters, hipStream_t st);
+
 // Rotation family.  pi_h/pi_l: split form of Pi, [DP][DP] zero padded, DP = rot_dp(d).
 // mode 0: residual -> rotate -> quantise -> pack into the list store at slot[row]
 // mode 1: same, but write unpacked codes / fp16 norms to flat arrays (any may be null)
