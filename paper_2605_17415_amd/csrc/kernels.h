@@ -149,7 +149,6 @@ struct SelectArgs {
     const int64_t* list_off; const int64_t* ids;
     float* out_vals; int32_t* out_i32; int64_t* out_i64;
     int m_bound;      // mode 1: host-side upper bound of any row's length (0 = unknown); picks the kernel
-    int small_cap;    // set by the launcher
 };
 hipError_t launch_select(int mode, const SelectArgs& a, hipStream_t st);
 

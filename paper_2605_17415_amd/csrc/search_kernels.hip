@@ -271,17 +271,19 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a) {
 
 // ---- selection for short rows: one wavefront per row ------------------------------------------
 //
-// For rows of at most kSmallM values and k <= 64 the k largest are taken one at a time: every lane
-// keeps the best of its own strided share in registers, a butterfly over the wavefront finds the
-// overall best (larger value, then smaller column), and only the lane that owned it rescans its
-// share.  The winners come out ordered by (value desc, column asc); a final bitonic pass over the
-// lanes re-orders equal values by label.
+// For rows of at most kSmallM values and k <= 64 a wavefront does the whole selection on its own,
+// without workgroup barriers: the k-th largest key is found by a four-pass radix search (8 bits per
+// pass, a 256-bin histogram private to the wavefront, a suffix sum over the lanes), then the values
+// above it and, in column order, as many equal to it as are still needed are compacted with
+// ballots.  The row is re-read from global memory in every pass (it is short and stays in cache),
+// so a wavefront needs little LDS and many rows are in flight per compute unit.  A final bitonic
+// pass over the lanes orders the winners by (value desc, label asc).
 
 constexpr int kSmallM = 4096;
 
 template <int MODE>
 __global__ __launch_bounds__(256) void k_select_small(SelectArgs a) {
-    extern __shared__ float s_vals[];                    // [4 waves][m_cap]
+    __shared__ uint32_t s_work[4][256 + 64];             // per wavefront: 256 bins, 64 winning columns
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t row = (int64_t)blockIdx.x * 4 + wave;
     if (row >= a.rows) return;
@@ -292,42 +294,77 @@ __global__ __launch_bounds__(256) void k_select_small(SelectArgs a) {
     const int k = a.k;
     const int take = m < k ? m : k;
     const float* vals = a.vals + row * a.stride;
-    float* mine = s_vals + wave * a.small_cap;
+    const float* mine = vals;
+    uint32_t* hist = s_work[wave];                                      // [256]
+    int* win_col = reinterpret_cast<int*>(hist + 256);                  // [64]
     const float ninf = -__builtin_inff();
+    auto key_of = [](float v) -> uint32_t { return v != v ? 0u : order_key(v); };   // NaN sorts last
 
-    float bv = ninf;
-    int bi = 0x7FFFFFFF;
-    for (int i = lane; i < m; i += 64) {
-        const float v = vals[i];
-        mine[i] = v;
-        if (v > bv) { bv = v; bi = i; }                  // ascending i: first maximum wins
-    }
-    __builtin_amdgcn_wave_barrier();
+    win_col[lane] = -1;
 
-    float out_v = ninf;                                  // lane r ends up with the r-th winner
-    int out_c = -1;
-    for (int r = 0; r < take; ++r) {
-        float wv = bv;
-        int wi = bi;
+    // radix search for the take-th largest key
+    uint32_t prefix = 0, mask = 0, need = (uint32_t)take;
+    if (take > 0) {
+        for (int shift = 24; shift >= 0; shift -= 8) {
 #pragma unroll
-        for (int o = 32; o > 0; o >>= 1) {
-            const float ov = __shfl_xor(wv, o);
-            const int oi = __shfl_xor(wi, o);
-            if (ov > wv || (ov == wv && oi < wi)) { wv = ov; wi = oi; }
-        }
-        if (wi == 0x7FFFFFFF) break;                     // nothing left but NaNs
-        if (lane == r) { out_v = wv; out_c = wi; }
-        if ((wi & 63) == lane) {                         // the owner removes it and rescans its share
-            mine[wi] = ninf;
-            bv = ninf;
-            bi = 0x7FFFFFFF;
+            for (int e = 0; e < 4; ++e) hist[lane * 4 + e] = 0u;
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
             for (int i = lane; i < m; i += 64) {
-                const float v = mine[i];
-                if (v > bv) { bv = v; bi = i; }
+                const uint32_t key = key_of(mine[i]);
+                if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
             }
-            if (bv == ninf) bi = 0x7FFFFFFF;             // share exhausted
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            // lane l owns digits 4l .. 4l+3; above = how many keys have a digit beyond this lane's
+            uint32_t h[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) h[e] = hist[lane * 4 + e];
+            const uint32_t own = h[0] + h[1] + h[2] + h[3];
+            uint32_t incl = own;                                     // inclusive suffix sum over lanes
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const uint32_t t = __shfl_down(incl, o);
+                if (lane + o < 64) incl += t;
+            }
+            uint32_t above = incl - own;
+            // the digit where the running count first reaches `need`, scanning digits downwards
+            int found = -1;
+            uint32_t before = 0;
+#pragma unroll
+            for (int e = 3; e >= 0; --e) {
+                if (found < 0 && above < need && above + h[e] >= need) { found = lane * 4 + e; before = above; }
+                above += h[e];
+            }
+            const uint64_t who = __ballot(found >= 0);               // exactly one lane while need >= 1
+            const int src = who ? (int)__builtin_ctzll(who) : 0;
+            const int dgt = __shfl(found, src);
+            before = __shfl(before, src);
+            need -= before;
+            prefix |= (uint32_t)dgt << shift;
+            mask |= 255u << shift;
         }
     }
+    // keys above the threshold, then `need` keys equal to it in column order
+    const uint32_t n_above = (uint32_t)take - need;
+    uint32_t base_gt = 0, base_eq = 0;
+    for (int i0 = 0; i0 < m && take > 0; i0 += 64) {
+        const int i = i0 + lane;
+        const uint32_t key = i < m ? key_of(mine[i]) : 0u;
+        const bool gt = i < m && key > prefix;
+        const bool eq = i < m && key == prefix;
+        const uint64_t bg = __ballot(gt), be = __ballot(eq);
+        const uint64_t below = ((uint64_t)1 << lane) - 1;
+        if (gt) win_col[base_gt + (uint32_t)__popcll(bg & below)] = i;
+        const uint32_t rank_eq = base_eq + (uint32_t)__popcll(be & below);
+        if (eq && rank_eq < need) win_col[n_above + rank_eq] = i;
+        base_gt += (uint32_t)__popcll(bg);
+        base_eq += (uint32_t)__popcll(be);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    const int out_c = lane < take ? win_col[lane] : -1;
+    float out_v = out_c >= 0 ? mine[out_c] : ninf;
 
     // labels, then order equal values by label
     int64_t lab = INT64_MAX;
@@ -335,16 +372,27 @@ __global__ __launch_bounds__(256) void k_select_small(SelectArgs a) {
         if (MODE == 0) {
             lab = out_c;
         } else {
-            const int32_t* off = a.cand_off + q * (a.np + 1);
-            int lo = 0, hi = a.np;
-            while (hi - lo > 1) {
-                const int mid = (lo + hi) >> 1;
-                if (off[mid] <= out_c) lo = mid; else hi = mid;
-            }
-            lab = a.ids[a.list_off[a.probe[q * a.np + lo]] + (out_c - off[lo])];
+            lab = 0;      // placeholder, resolved below by the whole wavefront
+
         }
     }
-    uint32_t key = out_c >= 0 ? order_key(out_v) : 0u;
+    if (MODE == 1) {
+        // probe rank of each winner: the last p with cand_off[p] <= column.  The offsets are read
+        // 64 at a time, one per lane, and handed round with shuffles (no dependent loads).
+        const int32_t* off = a.cand_off + q * (a.np + 1);
+        int rank = 0, rank_off = 0;
+        for (int base = 0; base < a.np; base += 64) {
+            const int p = base + lane;
+            const int32_t mine_off = p < a.np ? off[p] : INT32_MAX;
+            const int span = a.np - base < 64 ? a.np - base : 64;
+            for (int t = 0; t < span; ++t) {
+                const int32_t o = __shfl(mine_off, t);
+                if (o <= out_c) { rank = base + t; rank_off = o; }
+            }
+        }
+        if (out_c >= 0) lab = a.ids[a.list_off[a.probe[q * a.np + rank]] + (out_c - rank_off)];
+    }
+    uint32_t key = out_c >= 0 ? key_of(out_v) : 0u;
 #pragma unroll
     for (int size = 2; size <= 64; size <<= 1) {
 #pragma unroll
@@ -411,8 +459,7 @@ hipError_t launch_select(int mode, const SelectArgs& a_in, hipStream_t st) {
     // short rows and small k: the one-wavefront-per-row kernel
     const int m_bound = mode == 0 ? a.m_fixed : a.m_bound;
     if (a.k <= 64 && m_bound > 0 && m_bound <= kSmallM) {
-        a.small_cap = (m_bound + 3) & ~3;
-        const size_t lds = (size_t)4 * a.small_cap * sizeof(float);
+        const size_t lds = 0;
         const unsigned blocks = (unsigned)((a.rows + 3) / 4);
         if (mode == 0) hipLaunchKernelGGL(k_select_small<0>, dim3(blocks), dim3(256), lds, st, a);
         else hipLaunchKernelGGL(k_select_small<1>, dim3(blocks), dim3(256), lds, st, a);
