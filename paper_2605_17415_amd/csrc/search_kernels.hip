@@ -275,13 +275,13 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a) {
 // without workgroup barriers: the k-th largest key is found by a four-pass radix search (8 bits per
 // pass, a 256-bin histogram private to the wavefront, a suffix sum over the lanes), then the values
 // above it and, in column order, as many equal to it as are still needed are compacted with
-// ballots.  The row is re-read from global memory in every pass (it is short and stays in cache),
-// so a wavefront needs little LDS and many rows are in flight per compute unit.  A final bitonic
-// pass over the lanes orders the winners by (value desc, label asc).
+// ballots.  The first 64*NV columns of the row are loaded once, all loads in flight together, and
+// every pass takes them from registers; columns beyond that (long rows are rare) are re-read from
+// memory in each pass.  A wavefront needs little LDS, so many rows are in flight per compute unit.  A final bitonic pass over the lanes orders the winners by (value desc, label asc).
 
 constexpr int kSmallM = 4096;
 
-template <int MODE>
+template <int MODE, int NV>
 __global__ __launch_bounds__(256) void k_select_small(SelectArgs a) {
     __shared__ uint32_t s_work[4][256 + 64];             // per wavefront: 256 bins, 64 winning columns
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -294,13 +294,18 @@ __global__ __launch_bounds__(256) void k_select_small(SelectArgs a) {
     const int k = a.k;
     const int take = m < k ? m : k;
     const float* vals = a.vals + row * a.stride;
-    const float* mine = vals;
     uint32_t* hist = s_work[wave];                                      // [256]
     int* win_col = reinterpret_cast<int*>(hist + 256);                  // [64]
     const float ninf = -__builtin_inff();
     auto key_of = [](float v) -> uint32_t { return v != v ? 0u : order_key(v); };   // NaN sorts last
 
     win_col[lane] = -1;
+    uint32_t keys[NV];                                   // key of column e*64 + lane (unused beyond m)
+#pragma unroll
+    for (int e = 0; e < NV; ++e) {
+        const int i = e * 64 + lane;
+        keys[e] = key_of(vals[i < m ? i : 0]);
+    }
 
     // radix search for the take-th largest key
     uint32_t prefix = 0, mask = 0, need = (uint32_t)take;
@@ -310,8 +315,11 @@ __global__ __launch_bounds__(256) void k_select_small(SelectArgs a) {
             for (int e = 0; e < 4; ++e) hist[lane * 4 + e] = 0u;
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             __builtin_amdgcn_wave_barrier();
-            for (int i = lane; i < m; i += 64) {
-                const uint32_t key = key_of(mine[i]);
+#pragma unroll
+            for (int e = 0; e < NV; ++e)
+                if (e * 64 + lane < m && (keys[e] & mask) == prefix) atomicAdd(&hist[(keys[e] >> shift) & 255u], 1u);
+            for (int i = NV * 64 + lane; i < m; i += 64) {
+                const uint32_t key = key_of(vals[i]);
                 if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
             }
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -348,9 +356,7 @@ __global__ __launch_bounds__(256) void k_select_small(SelectArgs a) {
     // keys above the threshold, then `need` keys equal to it in column order
     const uint32_t n_above = (uint32_t)take - need;
     uint32_t base_gt = 0, base_eq = 0;
-    for (int i0 = 0; i0 < m && take > 0; i0 += 64) {
-        const int i = i0 + lane;
-        const uint32_t key = i < m ? key_of(mine[i]) : 0u;
+    auto place = [&](int i, uint32_t key) {
         const bool gt = i < m && key > prefix;
         const bool eq = i < m && key == prefix;
         const uint64_t bg = __ballot(gt), be = __ballot(eq);
@@ -360,11 +366,20 @@ __global__ __launch_bounds__(256) void k_select_small(SelectArgs a) {
         if (eq && rank_eq < need) win_col[n_above + rank_eq] = i;
         base_gt += (uint32_t)__popcll(bg);
         base_eq += (uint32_t)__popcll(be);
+    };
+    if (take > 0) {
+#pragma unroll
+        for (int e = 0; e < NV; ++e)
+            if (e * 64 < m) place(e * 64 + lane, keys[e]);
+        for (int i0 = NV * 64; i0 < m; i0 += 64) {
+            const int i = i0 + lane;
+            place(i, i < m ? key_of(vals[i]) : 0u);
+        }
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
     const int out_c = lane < take ? win_col[lane] : -1;
-    float out_v = out_c >= 0 ? mine[out_c] : ninf;
+    float out_v = out_c >= 0 ? vals[out_c] : ninf;
 
     // labels, then order equal values by label
     int64_t lab = INT64_MAX;
@@ -461,8 +476,11 @@ hipError_t launch_select(int mode, const SelectArgs& a_in, hipStream_t st) {
     if (a.k <= 64 && m_bound > 0 && m_bound <= kSmallM) {
         const size_t lds = 0;
         const unsigned blocks = (unsigned)((a.rows + 3) / 4);
-        if (mode == 0) hipLaunchKernelGGL(k_select_small<0>, dim3(blocks), dim3(256), lds, st, a);
-        else hipLaunchKernelGGL(k_select_small<1>, dim3(blocks), dim3(256), lds, st, a);
+#define IVFTQ_SMALL(NVV)                                                                            \
+        if (mode == 0) hipLaunchKernelGGL((k_select_small<0, NVV>), dim3(blocks), dim3(256), lds, st, a);  \
+        else hipLaunchKernelGGL((k_select_small<1, NVV>), dim3(blocks), dim3(256), lds, st, a);
+        IVFTQ_SMALL(16)
+#undef IVFTQ_SMALL
         return hipGetLastError();
     }
     int kpad = 1;
