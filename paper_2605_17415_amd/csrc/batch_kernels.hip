@@ -84,6 +84,56 @@ __global__ void k_pair_scatter(const int32_t* __restrict__ probe, const int32_t*
     pairs[pair_off[bkt] + atomicAdd(&cursor[bkt], 1u)] = (int32_t)it;
 }
 
+// The same two steps with the counters privatised in LDS: a workgroup takes kPairChunk consecutive
+// pairs, counts them per bucket in LDS, and touches each global counter once per bucket it met
+// (thousands of pairs hit the same few thousand counters, so per-pair global atomics serialise).
+// In the scatter step that one global atomic reserves the workgroup's range inside the bucket.
+constexpr int kPairChunk = 16384;
+constexpr int kPairLdsBuckets = 16384;      // 2L must not exceed this (64 KB of LDS)
+
+__global__ __launch_bounds__(1024) void k_pair_count_lds(const int32_t* __restrict__ probe,
+                                                         const int32_t* __restrict__ first, int64_t nq, int np,
+                                                         int L, uint32_t* __restrict__ count) {
+    extern __shared__ uint32_t bins[];                   // [2L]
+    for (int i = threadIdx.x; i < 2 * L; i += 1024) bins[i] = 0u;
+    __syncthreads();
+    const int64_t begin = (int64_t)blockIdx.x * kPairChunk, total = nq * np;
+    const int64_t end = begin + kPairChunk < total ? begin + kPairChunk : total;
+    for (int64_t it = begin + threadIdx.x; it < end; it += 1024) {
+        const int late = (int)(it % np) >= first[it / np];
+        atomicAdd(&bins[probe[it] + (late ? L : 0)], 1u);
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < 2 * L; i += 1024)
+        if (bins[i]) atomicAdd(&count[i], bins[i]);
+}
+
+__global__ __launch_bounds__(1024) void k_pair_scatter_lds(const int32_t* __restrict__ probe,
+                                                           const int32_t* __restrict__ first, int64_t nq, int np,
+                                                           int L, const int64_t* __restrict__ pair_off,
+                                                           uint32_t* __restrict__ cursor, int32_t* __restrict__ pairs) {
+    extern __shared__ uint32_t bins[];                   // [2L] count, then first position of this workgroup's range
+    for (int i = threadIdx.x; i < 2 * L; i += 1024) bins[i] = 0u;
+    __syncthreads();
+    const int64_t begin = (int64_t)blockIdx.x * kPairChunk, total = nq * np;
+    const int64_t end = begin + kPairChunk < total ? begin + kPairChunk : total;
+    for (int64_t it = begin + threadIdx.x; it < end; it += 1024) {
+        const int late = (int)(it % np) >= first[it / np];
+        atomicAdd(&bins[probe[it] + (late ? L : 0)], 1u);
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < 2 * L; i += 1024) {
+        const uint32_t c = bins[i];
+        bins[i] = c ? atomicAdd(&cursor[i], c) : 0u;      // this workgroup's pairs of bucket i start here
+    }
+    __syncthreads();
+    for (int64_t it = begin + threadIdx.x; it < end; it += 1024) {
+        const int late = (int)(it % np) >= first[it / np];
+        const int bkt = probe[it] + (late ? L : 0);
+        pairs[pair_off[bkt] + atomicAdd(&bins[bkt], 1u)] = (int32_t)it;
+    }
+}
+
 // ---- the batched scan ----------------------------------------------------------------------------
 //
 // Arithmetic: both operands are used in split float16 form, 1024*v = hi + lo with hi = fp16(1024 v)
@@ -394,6 +444,23 @@ hipError_t launch_pair_grouping(const int32_t* probe, const int32_t* first, int6
     if (n <= 0) return hipSuccess;
     hipError_t e = launch_fill_u32(count, 2 * L, 0u, st);
     if (e != hipSuccess) return e;
+    if (2 * L <= kPairLdsBuckets) {
+        static bool attr_set = false;
+        if (!attr_set) {
+            const int most = kPairLdsBuckets * (int)sizeof(uint32_t);
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_pair_count_lds), hipFuncAttributeMaxDynamicSharedMemorySize, most);
+            if (e == hipSuccess)
+                e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_pair_scatter_lds), hipFuncAttributeMaxDynamicSharedMemorySize, most);
+            if (e != hipSuccess) return e;
+            attr_set = true;
+        }
+        const unsigned blocks = (unsigned)((n + kPairChunk - 1) / kPairChunk);
+        const size_t lds = (size_t)2 * L * sizeof(uint32_t);
+        hipLaunchKernelGGL(k_pair_count_lds, dim3(blocks), dim3(1024), lds, st, probe, first, nq, np, L, count);
+        hipLaunchKernelGGL(k_pair_prefix, dim3(1), dim3(1024), 0, st, count, 2 * L, tq, pair_off, tile_off, cursor);
+        hipLaunchKernelGGL(k_pair_scatter_lds, dim3(blocks), dim3(1024), lds, st, probe, first, nq, np, L, pair_off, cursor, pairs);
+        return hipGetLastError();
+    }
     const unsigned blocks = (unsigned)((n + 255) / 256);
     hipLaunchKernelGGL(k_pair_count, dim3(blocks), dim3(256), 0, st, probe, first, nq, np, L, count);
     hipLaunchKernelGGL(k_pair_prefix, dim3(1), dim3(1024), 0, st, count, 2 * L, tq, pair_off, tile_off, cursor);
