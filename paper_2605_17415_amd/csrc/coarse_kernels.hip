@@ -98,7 +98,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
     const uint16_t* al_base = tl + j * Cfg::LDH + 8 * half;
     constexpr float kUnscale = 1.f / (kSplitScale * kSplitScale);
 
-    for (int c0 = 0; c0 < Lpad; c0 += kTN) {
+    // gridDim.y workgroups share the centroid stages of one row block (score mode with few rows)
+    const int stages = Lpad / kTN, per_y = (stages + (int)gridDim.y - 1) / (int)gridDim.y;
+    const int c_lo = (int)blockIdx.y * per_y * kTN;
+    const int c_hi = c_lo + per_y * kTN < Lpad ? c_lo + per_y * kTN : Lpad;
+    for (int c0 = c_lo; c0 < c_hi; c0 += kTN) {
         __syncthreads();
         // stage TN centroid rows (hi and lo) into LDS, 16 bytes at a time
         for (int e = tid; e < kTN * (DP / 8); e += 256) {
@@ -209,7 +213,12 @@ hipError_t run(int mode, const float* x, int64_t n, int d, const uint16_t* cent_
     const int64_t rows_per_wg = 4 * 32 * R;
     const int64_t blocks = (n + rows_per_wg - 1) / rows_per_wg;
     const int vec4 = (d % 4 == 0) && (reinterpret_cast<uintptr_t>(x) % 16 == 0);
-    hipLaunchKernelGGL((k_coarse<DP, R>), dim3((unsigned)blocks), dim3(256), lds, st, mode, x, n, d, vec4, cent_h,
+    // score mode: every (row, centroid) result is independent, so when the rows alone do not fill
+    // the chip the centroid stages are split over gridDim.y as well
+    int ysplit = 1;
+    if (mode == 1)
+        while (blocks * ysplit < 512 && ysplit * 2 <= Lpad / kTN) ysplit *= 2;
+    hipLaunchKernelGGL((k_coarse<DP, R>), dim3((unsigned)blocks, (unsigned)ysplit), dim3(256), lds, st, mode, x, n, d, vec4, cent_h,
                        cent_l, cent_pitch, bias, L, Lpad, assign, best, scores, ld_scores, flag);
     return hipGetLastError();
 }
