@@ -155,7 +155,11 @@ struct BatchCfg {
 };
 
 // WAVES = wavefronts per workgroup, OCC = wavefronts per SIMD the register budget is set for.
-template <int DP, int B, int NQ, int WAVES, int OCC>
+// DENSE (the nearest lists, every score stored): the queries are the row operand and the vectors the
+// column operand, so a lane holds one vector's scores against 16 queries and the stores of a
+// query's scores coalesce.  Otherwise (threshold pass) the roles are swapped: a lane holds one
+// query's scores against 16 vectors and needs that query's coarse term and threshold only once.
+template <int DP, int B, int NQ, int WAVES, int OCC, bool DENSE>
 __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(OCC)))
 void k_batch_scan(BatchScanArgs a) {
     using Cfg = BatchCfg<DP, B, NQ>;
@@ -198,7 +202,7 @@ void k_batch_scan(BatchScanArgs a) {
             const int32_t it = a.pairs[pair0 + e];
             q = it / a.np;
             sc = a.coarse[it];
-            if (a.dense) th = __int_as_float(a.cand_off[(int64_t)q * (a.np + 1) + (it - q * a.np)]);
+            if (DENSE) th = __int_as_float(a.cand_off[(int64_t)q * (a.np + 1) + (it - q * a.np)]);
             else th = a.thresh[(int64_t)q * a.thresh_stride];
         }
         s_q[e] = q;
@@ -253,13 +257,17 @@ void k_batch_scan(BatchScanArgs a) {
 #pragma unroll
             for (int e = 0; e < NW; ++e) w[kb][e] = (wi + e < words) ? wp[(int64_t)(wi + e) * 64] : 0u;
         }
+        if (DENSE) {                               // float16 norm of the lane's own vector (NaN beyond the list)
+            gp[0] = v_mine < n_l ? (uint32_t)a.store.gamma[slot] : 0x7E00u;
+        } else {
 #pragma unroll
-        for (int r = 0; r < 16; r += 2) {          // float16 norms of the lane's 16 result rows, in pairs
-            const int v = slab * 32 + 8 * (r / 4) + 4 * half + (r % 4);      // even: the pair is 4-byte aligned
-            uint32_t pr = 0x7E007E00u;                                       // two float16 NaNs
-            if (v + 1 < n_l) pr = *reinterpret_cast<const uint32_t*>(a.store.gamma + base_slot + v);
-            else if (v < n_l) pr = (uint32_t)a.store.gamma[base_slot + v] | 0x7E000000u;
-            gp[r / 2] = pr;
+            for (int r = 0; r < 16; r += 2) {      // float16 norms of the lane's 16 result rows, in pairs
+                const int v = slab * 32 + 8 * (r / 4) + 4 * half + (r % 4);      // even: the pair is 4-byte aligned
+                uint32_t pr = 0x7E007E00u;                                       // two float16 NaNs
+                if (v + 1 < n_l) pr = *reinterpret_cast<const uint32_t*>(a.store.gamma + base_slot + v);
+                else if (v < n_l) pr = (uint32_t)a.store.gamma[base_slot + v] | 0x7E000000u;
+                gp[r / 2] = pr;
+            }
         }
     };
 
@@ -290,8 +298,8 @@ void k_batch_scan(BatchScanArgs a) {
         float g[16];                               // 2^-20 * norm per result row (NaN beyond the list)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            const uint32_t pr = cg[r / 2];
-            g[r] = kUnscale * __half2float(__ushort_as_half((uint16_t)((r & 1) ? (pr >> 16) : (pr & 0xFFFFu))));
+            const uint32_t pr = cg[DENSE ? 0 : r / 2];
+            g[r] = kUnscale * __half2float(__ushort_as_half((uint16_t)((!DENSE && (r & 1)) ? (pr >> 16) : (pr & 0xFFFFu))));
         }
 
         for (int qt = 0; qt < n_qt; ++qt) {
@@ -304,9 +312,27 @@ void k_batch_scan(BatchScanArgs a) {
             for (int kb = 0; kb < KB; ++kb) {
                 const half8 bh = *reinterpret_cast<const half8*>(bhq + 16 * kb);
                 const half8 bl = *reinterpret_cast<const half8*>(blq + 16 * kb);
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah[kb], bh, acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah[kb], bl, acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(al[kb], bh, acc, 0, 0, 0);
+                if (DENSE) {
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(bh, ah[kb], acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(bl, ah[kb], acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(bh, al[kb], acc, 0, 0, 0);
+                } else {
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah[kb], bh, acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah[kb], bl, acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(al[kb], bh, acc, 0, 0, 0);
+                }
+            }
+            if (DENSE) {
+                // result row r of this lane: query 8*(r/4) + 4*half + r%4 of the tile, vector jl of the slab
+                const int v = slab * 32 + jl;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int e = qt * 32 + 8 * (r / 4) + 4 * half + (r % 4);
+                    const int32_t q = s_q[e];
+                    if (q >= 0 && v < n_l)
+                        a.scores[(int64_t)q * a.m_stride + __float_as_int(s_thr[e]) + v] = fmaf(g[r], acc[r], s_coarse[e]);
+                }
+                continue;
             }
             const int e = qt * 32 + jl;
             const float sq = s_coarse[e], th = s_thr[e];
@@ -318,16 +344,7 @@ void k_batch_scan(BatchScanArgs a) {
                 sc[r] = fmaf(g[r], acc[r], sq);    // NaN (row beyond the list) never passes
                 best = fmaxf(best, sc[r]);         // fmaxf ignores NaN
             }
-            if (a.dense) {                          // nearest lists: every score is kept, in list order
-                if (q >= 0) {
-                    float* out = a.scores + (int64_t)q * a.m_stride + __float_as_int(th);
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int v = slab * 32 + 8 * (r / 4) + 4 * half + (r % 4);
-                        if (v < n_l) out[v] = sc[r];
-                    }
-                }
-            } else if (best >= th && q >= 0) {     // rare: some row of this lane reaches the threshold
+            if (best >= th && q >= 0) {            // rare: some row of this lane reaches the threshold
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     if (sc[r] >= th) {
@@ -418,12 +435,18 @@ hipError_t run_batch(const BatchScanArgs& a, int max_tiles, hipStream_t st) {
     static bool attr_set = false;
     const size_t lds = BatchCfg<DP, B, NQ>::lds_bytes;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_batch_scan<DP, B, NQ, WAVES, OCC>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_batch_scan<DP, B, NQ, WAVES, OCC, false>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_batch_scan<DP, B, NQ, WAVES, OCC, true>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((k_batch_scan<DP, B, NQ, WAVES, OCC>), dim3((unsigned)max_tiles), dim3(WAVES * 64), lds, st, a);
+    if (a.dense)
+        hipLaunchKernelGGL((k_batch_scan<DP, B, NQ, WAVES, OCC, true>), dim3((unsigned)max_tiles), dim3(WAVES * 64), lds, st, a);
+    else
+        hipLaunchKernelGGL((k_batch_scan<DP, B, NQ, WAVES, OCC, false>), dim3((unsigned)max_tiles), dim3(WAVES * 64), lds, st, a);
     return hipGetLastError();
 }
 
