@@ -861,7 +861,7 @@ ivftq_status ivftq_search(ivftq_index* ix, const float* q_dev, int64_t nq, int n
     const int tq = batch_tile_queries(ix->d, ix->b);
     const bool batched = tq > 0 && nprobe > 1 &&
                          (ix->search_mode == 2 || (ix->search_mode == 0 && qc * nprobe >= (int64_t)16 * ix->nlist));
-    const int cap = std::min(2048, std::max(512, 8 * k));
+    const int cap = std::min(2048, std::max(512, 16 * k));
 
     HIP_TRY(ix->w_S.ensure((size_t)qc * ldS * sizeof(float)));
     HIP_TRY(ix->w_scores.ensure((size_t)qc * m_stride * sizeof(float)));
@@ -883,7 +883,7 @@ ivftq_status ivftq_search(ivftq_index* ix, const float* q_dev, int64_t nq, int n
         HIP_TRY(ix->w_cscore.ensure((size_t)qc * cap * sizeof(float)));
         HIP_TRY(ix->w_cslot.ensure((size_t)qc * cap * sizeof(int64_t)));
         HIP_TRY(ix->w_ccnt.ensure((size_t)qc * sizeof(int32_t)));
-        HIP_TRY(ix->w_gate.ensure((size_t)qc * sizeof(int32_t)));
+        HIP_TRY(ix->w_gate.ensure((size_t)(qc + 1) * sizeof(int32_t)));
     }
 
     for (int64_t q0 = 0; q0 < nq; q0 += qc) {
@@ -899,7 +899,7 @@ ivftq_status ivftq_search(ivftq_index* ix, const float* q_dev, int64_t nq, int n
         int32_t* first = batched ? ix->w_first.as<int32_t>() : nullptr;
         HIP_TRY(timed(ix, st, P_CAND_OFF, [&] {
             return launch_cand_offsets(ix->w_probe.as<int32_t>(), cnt, nprobe, ix->d_size.as<int32_t>(),
-                                       ix->w_candoff.as<int32_t>(), k, first, st); }));
+                                       ix->w_candoff.as<int32_t>(), k, cap, first, st); }));
         auto stream_scan = [&](const int32_t* p_limit, const int32_t* gate, int blocks_per_query) {
             return launch_list_scan(ix->w_z.as<float>(), ix->dp, ix->d, ix->b, ix->cb.as<float>(),
                                     ix->w_probe.as<int32_t>(), ix->w_coarse.as<float>(),
@@ -928,6 +928,7 @@ ivftq_status ivftq_search(ivftq_index* ix, const float* q_dev, int64_t nq, int n
                                                 ix->w_pairoff.as<int64_t>(), ix->w_tileoff.as<int32_t>(),
                                                 ix->w_pairs.as<int32_t>(), st);
             if (e == hipSuccess) e = launch_fill_u32(ix->w_ccnt.as<uint32_t>(), cnt, 0u, st);
+            if (e == hipSuccess) e = launch_fill_u32(ix->w_gate.as<uint32_t>(), 1, 0u, st);
             return e; }));
         BatchScanArgs ba{};
         ba.zh = ix->w_zh.as<uint16_t>(); ba.zl = ix->w_zl.as<uint16_t>(); ba.z_pitch = ix->dp;
@@ -945,7 +946,9 @@ ivftq_status ivftq_search(ivftq_index* ix, const float* q_dev, int64_t nq, int n
         HIP_TRY(timed(ix, st, P_BATCH_FIRST, [&] { return launch_batch_scan(ba, ix->d, ix->b, max_tiles, st); }));
         SelectArgs s1 = sa;
         s1.p_limit = first; s1.out_vals = ix->w_fscores.as<float>(); s1.out_i64 = ix->w_fids.as<int64_t>();
-        s1.m_bound = (int)std::min<int64_t>(m_stride, (int64_t)k + sizes[0]);   // shortest prefix with k vectors
+        // the dense prefix stops at the first list that brings it to max(k, 2*k*T/cap) vectors
+        const int64_t need_max = std::max<int64_t>(k, (kPrefixFactorX2 * (int64_t)k * m_bound + 2 * cap - 1) / (2 * cap));
+        s1.m_bound = (int)std::min<int64_t>(m_stride, need_max + sizes[0]);
         HIP_TRY(timed(ix, st, P_SELECT_TOPK, [&] { return launch_select(1, s1, st); }));
         // 3. the other lists against the thresholds
         ba.dense = 0; ba.bucket_lo = ix->nlist; ba.bucket_hi = 2 * ix->nlist;

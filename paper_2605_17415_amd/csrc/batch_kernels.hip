@@ -381,7 +381,7 @@ __global__ __launch_bounds__(256) void k_merge(MergeArgs a) {
     const int tid = threadIdx.x;
     const int cnt = a.cand_cnt[q];
     const bool overflow = cnt > a.cap;
-    if (tid == 0) a.gate[q] = overflow ? 1 : 0;
+    if (tid == 0 && overflow) a.gate[1 + atomicAdd(&a.gate[0], 1)] = (int32_t)q;   // listed for the exact pass
     if (overflow) return;                        // the exact streaming pass redoes this query
     const int total = a.k + cnt;
     int size = 1;

@@ -12,6 +12,10 @@ constexpr int kRowsPerWG = 128;      // data rows one workgroup of the contracti
 constexpr int kMaxD = 256;
 constexpr int kMaxList = 16384;
 constexpr int kMaxK = 2048;
+#ifndef IVFTQ_PREFIX_X2
+#define IVFTQ_PREFIX_X2 2
+#endif
+constexpr int kPrefixFactorX2 = IVFTQ_PREFIX_X2;   // twice the factor f in: dense prefix >= f * k * T / cap vectors
 constexpr int kMaxGridCells = 4096;  // entries of the quantiser's uniform-grid index (32 KB of LDS)
 
 // Split float16 form used by the float16 matrix-core kernels: V = 1024*v, hi = fp16(V),
@@ -124,17 +128,18 @@ hipError_t launch_inertia(const float* best, int64_t n, double* out, hipStream_t
 // ---- search -----------------------------------------------------------------------------------
 
 // cand_off[q*(np+1) + p] = sum_{p'<p} list_size[probe[q][p']]
-// first (may be null): first[q] = shortest probe prefix (>= 1 cell) holding >= k vectors, else np
+// first (may be null): first[q] = shortest probe prefix (>= 1 cell) holding at least
+// max(k, 2*k*T/cap) vectors, T the query's candidate total; np if there is none
 hipError_t launch_cand_offsets(const int32_t* probe, int64_t nq, int np, const int32_t* list_size,
-                               int32_t* cand_off, int k, int32_t* first, hipStream_t st);
+                               int32_t* cand_off, int k, int cap, int32_t* first, hipStream_t st);
 // scores[qi*m_stride + cand_off[q][p] + i] = coarse[q][p] + gamma_i * sum_j z_qj * C[code_ij]
 hipError_t launch_list_scan(const float* z, int z_pitch, int d, int b, const float* cb,
                             const int32_t* probe, const float* coarse, const int32_t* cand_off,
                             int np, const ListStore& store, int64_t q_begin, int64_t q_count,
                             float* scores, int64_t m_stride, const int32_t* p_limit, const int32_t* gate,
                             int blocks_per_query, hipStream_t st);
-// p_limit (may be null): only probes p < p_limit[q] are scanned.  gate (may be null): only queries
-// with gate[q] != 0 are processed.  blocks_per_query: workgroups per query (0 = one per probe).
+// p_limit (may be null): only probes p < p_limit[q] are scanned.  gate (may be null): only the
+// gate[0] queries listed in gate[1..] are processed.  blocks_per_query: workgroups per query (0 = one per probe).
 
 // Per row: the k largest of m values, sorted by (value desc, label asc).
 // mode 0 (probe selection): m = m_fixed for every row, label = column; writes int32 labels.
@@ -145,7 +150,7 @@ struct SelectArgs {
     int m_fixed;
     const int32_t* cand_off; const int32_t* probe; int np; int64_t q_begin;
     const int32_t* p_limit;   // mode 1: row q only has the candidates of probes p < p_limit[q] (null = all)
-    const int32_t* gate;      // only rows with gate[q] != 0 are processed (null = all)
+    const int32_t* gate;      // gate[0] rows listed in gate[1..] are processed instead of all (null = all)
     const int64_t* list_off; const int64_t* ids;
     float* out_vals; int32_t* out_i32; int64_t* out_i64;
     int m_bound;      // mode 1: host-side upper bound of any row's length (0 = unknown); picks the kernel
@@ -185,7 +190,7 @@ struct MergeArgs {
     const float* cand_score; const int64_t* cand_slot; const int32_t* cand_cnt; int cap;
     const int64_t* ids;                                       // labels by slot
     int k; float* out_scores; int64_t* out_ids;
-    int32_t* gate;                                            // [nq] 1 when the candidate list overflowed
+    int32_t* gate;                                            // [1 + nq]: count (cleared by the caller), then the queries whose candidate list overflowed
 };
 hipError_t launch_merge(const MergeArgs& a, int64_t nq, hipStream_t st);
 

@@ -3,6 +3,8 @@
 // selection of the best k (also used to pick the nprobe best cells).
 #include <hip/hip_fp16.h>
 
+#include <algorithm>
+
 #include "kernels.h"
 
 namespace ivftq {
@@ -11,22 +13,29 @@ namespace {
 
 // ---- candidate offsets -----------------------------------------------------------------------
 
-// Also, when asked: first[q] = the shortest prefix of the probe list (at least one cell) that holds
-// at least k vectors, or np when all probed cells together hold fewer.
+// Also, when asked: first[q] = the number of leading probes whose lists are scored densely to find
+// the query's threshold (see the kernel), or np when all probed cells together hold too few vectors.
 __global__ void k_cand_offsets(const int32_t* __restrict__ probe, int64_t nq, int np,
                                const int32_t* __restrict__ list_size, int32_t* __restrict__ cand_off,
-                               int k, int32_t* __restrict__ first) {
+                               int k, int cap, int32_t* __restrict__ first) {
     const int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (q >= nq) return;
     int32_t run = 0;
-    int p1 = np;
     for (int p = 0; p < np; ++p) {
         cand_off[q * (np + 1) + p] = run;
         run += list_size[probe[q * np + p]];
-        if (p1 == np && run >= k) p1 = p + 1;
     }
     cand_off[q * (np + 1) + np] = run;
-    if (first) first[q] = p1;
+    if (!first) return;
+    // The k-th score of a prefix holding P of the query's T candidates is beaten by about
+    // k*(T-P)/P of the others; the prefix is made long enough for that to be half the candidate
+    // list's capacity (and at least k vectors, so that a threshold exists).
+    int64_t need = (kPrefixFactorX2 * (int64_t)k * run + 2 * cap - 1) / (2 * cap);
+    if (need < k) need = k;
+    int p1 = np;
+    for (int p = 1; p <= np; ++p)
+        if (cand_off[q * (np + 1) + p] >= need) { p1 = p; break; }
+    first[q] = p1;
 }
 
 // ---- list scan: one workgroup per (query, probed list) ---------------------------------------
@@ -49,11 +58,15 @@ __global__ __launch_bounds__(256) void k_list_scan(const float* __restrict__ z, 
                                                    const int32_t* __restrict__ gate) {
     constexpr int K = 1 << B;
     extern __shared__ float lut[];     // [d][K], or z[d] followed by C[K] when DIRECT
-    const int64_t qi = blockIdx.y;     // index inside this pass
+    // gate (may be null): gate[0] queries, listed in gate[1..], are processed instead of all; the
+    // grid's y extent is then fixed and each workgroup row walks the list
+    const int64_t n_rows = gate ? gate[0] : gridDim.y;
+    for (int64_t row_i = blockIdx.y; row_i < n_rows; row_i += gridDim.y) {
+    const int64_t qi = gate ? gate[1 + row_i] : row_i;     // index inside this pass
     const int64_t q = q_begin + qi;
-    if (gate && !gate[q]) return;      // only queries marked for this pass
     const int p_end = p_limit ? p_limit[q] : np;
-    if ((int)blockIdx.x >= p_end) return;
+    if ((int)blockIdx.x >= p_end) continue;
+    __syncthreads();                   // the table of the previous query is no longer read
 
     if constexpr (DIRECT) {
         for (int e = threadIdx.x; e < d; e += 256) lut[e] = z[q * z_pitch + e];
@@ -116,6 +129,7 @@ __global__ __launch_bounds__(256) void k_list_scan(const float* __restrict__ z, 
         out[v] = s_l + g * acc;
     }
     }
+    }
 }
 
 // ---- selection: k largest of a row ------------------------------------------------------------
@@ -142,10 +156,13 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a) {
     int64_t* s_lab = reinterpret_cast<int64_t*>(s_col + kpad);   // [kpad], 8-byte aligned: 268 + 2*kpad words
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int64_t row = blockIdx.x;
+    // gate (may be null): a.gate[0] rows, listed in a.gate[1..], are processed instead of all
+    const int64_t n_rows = a.gate ? a.gate[0] : a.rows;
+    for (int64_t row_i = blockIdx.x; row_i < n_rows; row_i += gridDim.x) {
+    const int64_t row = a.gate ? a.gate[1 + row_i] : row_i;
     const float* vals = a.vals + row * a.stride;
     const int64_t q = a.q_begin + row;
-    if (a.gate && !a.gate[q]) return;
+    __syncthreads();                   // LDS of the previous row is no longer read
     const int m = (MODE == 0) ? a.m_fixed
                               : a.cand_off[q * (a.np + 1) + (a.p_limit ? a.p_limit[q] : a.np)];
     const int k = a.k;
@@ -267,11 +284,12 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a) {
         if (MODE == 0) { if (a.out_i32) a.out_i32[row * k + i] = real ? (int32_t)s_lab[i] : -1; }
         else { if (a.out_i64) a.out_i64[row * k + i] = real ? s_lab[i] : -1; }
     }
+    }
 }
 
 // ---- selection for short rows: one wavefront per row ------------------------------------------
 //
-// For rows of at most kSmallM values and k <= 64 a wavefront does the whole selection on its own,
+// For rows of at most kSmallM values (bound known to the host) and k <= 64 a wavefront does the whole selection on its own,
 // without workgroup barriers: the k-th largest key is found by a four-pass radix search (8 bits per
 // pass, a 256-bin histogram private to the wavefront, a suffix sum over the lanes), then the values
 // above it and, in column order, as many equal to it as are still needed are compacted with
@@ -279,16 +297,16 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a) {
 // every pass takes them from registers; columns beyond that (long rows are rare) are re-read from
 // memory in each pass.  A wavefront needs little LDS, so many rows are in flight per compute unit.  A final bitonic pass over the lanes orders the winners by (value desc, label asc).
 
-constexpr int kSmallM = 4096;
+constexpr int kSmallM = 16384;
 
 template <int MODE, int NV>
 __global__ __launch_bounds__(256) void k_select_small(SelectArgs a) {
     __shared__ uint32_t s_work[4][256 + 64];             // per wavefront: 256 bins, 64 winning columns
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int64_t row = (int64_t)blockIdx.x * 4 + wave;
-    if (row >= a.rows) return;
+    const int64_t n_rows = a.gate ? a.gate[0] : a.rows;
+    for (int64_t row_i = (int64_t)blockIdx.x * 4 + wave; row_i < n_rows; row_i += (int64_t)gridDim.x * 4) {
+    const int64_t row = a.gate ? a.gate[1 + row_i] : row_i;
     const int64_t q = a.q_begin + row;
-    if (a.gate && !a.gate[q]) return;
     const int m = (MODE == 0) ? a.m_fixed
                               : a.cand_off[q * (a.np + 1) + (a.p_limit ? a.p_limit[q] : a.np)];
     const int k = a.k;
@@ -428,15 +446,18 @@ __global__ __launch_bounds__(256) void k_select_small(SelectArgs a) {
         if (MODE == 0) { if (a.out_i32) a.out_i32[row * k + lane] = real ? (int32_t)lab : -1; }
         else { if (a.out_i64) a.out_i64[row * k + lane] = real ? lab : -1; }
     }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();   // the wavefront's LDS words are free for its next row
+    }
 }
 
 }  // namespace
 
 hipError_t launch_cand_offsets(const int32_t* probe, int64_t nq, int np, const int32_t* list_size,
-                               int32_t* cand_off, int k, int32_t* first, hipStream_t st) {
+                               int32_t* cand_off, int k, int cap, int32_t* first, hipStream_t st) {
     if (nq <= 0) return hipSuccess;
     hipLaunchKernelGGL(k_cand_offsets, dim3((unsigned)((nq + 127) / 128)), dim3(128), 0, st, probe, nq, np,
-                       list_size, cand_off, k, first);
+                       list_size, cand_off, k, cap, first);
     return hipGetLastError();
 }
 
@@ -449,7 +470,8 @@ hipError_t launch_list_scan(const float* z, int z_pitch, int d, int b, const flo
     const size_t lut_bytes = (size_t)d * (1u << b) * sizeof(float);
     const bool direct = lut_bytes > 64 * 1024;
     const size_t lds = direct ? (size_t)(d + (1 << b)) * sizeof(float) : lut_bytes;
-    dim3 grid((unsigned)(blocks_per_query > 0 ? blocks_per_query : np), (unsigned)q_count);
+    // gated: a fixed number of workgroup rows walks the list of marked queries
+    dim3 grid((unsigned)(blocks_per_query > 0 ? blocks_per_query : np), (unsigned)(gate ? std::min<int64_t>(q_count, 256) : q_count));
 #define IVFTQ_SCAN(BV)                                                                              \
     case BV:                                                                                        \
         if (direct)                                                                                 \
@@ -475,21 +497,22 @@ hipError_t launch_select(int mode, const SelectArgs& a_in, hipStream_t st) {
     const int m_bound = mode == 0 ? a.m_fixed : a.m_bound;
     if (a.k <= 64 && m_bound > 0 && m_bound <= kSmallM) {
         const size_t lds = 0;
-        const unsigned blocks = (unsigned)((a.rows + 3) / 4);
+        const unsigned blocks = (unsigned)((a.gate ? std::min<int64_t>(a.rows, 1024) : a.rows) + 3) / 4;
 #define IVFTQ_SMALL(NVV)                                                                            \
         if (mode == 0) hipLaunchKernelGGL((k_select_small<0, NVV>), dim3(blocks), dim3(256), lds, st, a);  \
         else hipLaunchKernelGGL((k_select_small<1, NVV>), dim3(blocks), dim3(256), lds, st, a);
-        IVFTQ_SMALL(16)
+        if (m_bound <= 1536) { IVFTQ_SMALL(16) } else { IVFTQ_SMALL(32) }
 #undef IVFTQ_SMALL
         return hipGetLastError();
     }
     int kpad = 1;
     while (kpad < a.k) kpad <<= 1;
     const size_t lds = (256 + 8 + 4) * 4 + (size_t)kpad * 8 + 8 + (size_t)kpad * 8;
+    const unsigned wgs = (unsigned)(a.gate ? std::min<int64_t>(a.rows, 256) : a.rows);
     if (mode == 0)
-        hipLaunchKernelGGL(k_select<0>, dim3((unsigned)a.rows), dim3(256), lds, st, a);
+        hipLaunchKernelGGL(k_select<0>, dim3(wgs), dim3(256), lds, st, a);
     else
-        hipLaunchKernelGGL(k_select<1>, dim3((unsigned)a.rows), dim3(256), lds, st, a);
+        hipLaunchKernelGGL(k_select<1>, dim3(wgs), dim3(256), lds, st, a);
     return hipGetLastError();
 }
 

@@ -119,12 +119,14 @@ def test_batched_scan_overflow_falls_back_to_the_exact_scan():
     order = np.argsort(-S[0])
     rng = np.random.default_rng(0)
     assign, codes, gamma = [], [], []
-    # nearest cell of query 0: 20 vectors whose residual estimate is as negative as it can be
+    # the two nearest cells of query 0 (the prefix its threshold comes from): 20 and 100 vectors whose
+    # residual estimate is as negative as it can be
     worst = np.where(z[0] > 0, 0, K - 1).astype(np.uint8)
-    for _ in range(20):
-        assign.append(order[0]); codes.append(worst); gamma.append(1.0)
+    for l, count in ((order[0], 20), (order[1], 100)):
+        for _ in range(count):
+            assign.append(l); codes.append(worst); gamma.append(1.0)
     # next cells: 300 vectors each with zero residual norm, so every score equals the coarse term
-    for l in order[1:8]:
+    for l in order[2:8]:
         for _ in range(300):
             assign.append(l); codes.append(rng.integers(0, K, cs.d).astype(np.uint8)); gamma.append(0.0)
     assign = np.array(assign, np.int32)
