@@ -107,14 +107,104 @@ def cpu_baseline(w, X, Q, nprobe, full_cand_per_query):
     }
 
 
+def run_streaming(args, torch, pkg, synth):
+    """Streaming ingest on the 10M x 96 distribution: coarse partition trained on the first 1M rows, those
+    rows encoded, then 100k-row batches appended with nothing retrained; after every batch the 10,000 queries
+    are searched (nprobe 32, k 10) against exact ground truth on everything inserted so far.  The mixture
+    draws are i.i.d., so consecutive slices of the database are an i.i.d. shuffle."""
+    dev = torch.device("cuda:0")
+    w = synth.config_10m_d96(args.bits)
+    nprobe = args.nprobe or 32
+    n0, bs = 1_000_000, 100_000
+    nb = min(args.stream_batches, (w.n - n0) // bs)
+    t0 = time.perf_counter()
+    X = synth.database(w, 0, n0 + nb * bs)
+    Q = synth.queries(w)
+    qd = torch.from_numpy(Q).to(dev)
+    qn = qd / qd.norm(dim=1, keepdim=True)
+    x0 = torch.from_numpy(X[:n0]).to(dev)
+    rows = synth.train_sample_indices(w, n_available=n0)
+    ix = pkg.Index(w.d, w.b, w.nlist, rotation_seed=w.seed)
+    ix.train_coarse(x0[torch.from_numpy(rows).to(dev)].contiguous(), w.kmeans_iters,
+                    init_rows=synth.kmeans_init_indices(w.seed, len(rows), w.nlist))
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+
+    def add(xb):
+        a, b = ev(), ev()
+        a.record()
+        ix.encode_add(xb)
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b)
+
+    best_v = torch.full((w.nq, w.k), -float("inf"), device=dev)
+    best_i = torch.full((w.nq, w.k), -1, dtype=torch.int64, device=dev)
+
+    def extend_truth(xb, base):
+        nonlocal best_v, best_i
+        for t in range(0, xb.shape[0], 1 << 19):
+            blk = xb[t:t + (1 << 19)]
+            blk = blk / blk.norm(dim=1, keepdim=True)
+            v, i = torch.topk(qn @ blk.T, w.k, dim=1)
+            v2, sel = torch.topk(torch.cat([best_v, v], dim=1), w.k, dim=1)
+            best_v, best_i = v2, torch.gather(torch.cat([best_i, i + base + t], dim=1), 1, sel)
+
+    scores = torch.empty((w.nq, w.k), dtype=torch.float32, device=dev)
+    ids = torch.empty((w.nq, w.k), dtype=torch.int64, device=dev)
+
+    def measure():
+        a, b = ev(), ev()
+        a.record()
+        ix.search(qd, nprobe, w.k, out_scores=scores, out_ids=ids)
+        b.record()
+        torch.cuda.synchronize()
+        return recall(ids.cpu().numpy(), best_i.cpu().numpy()), a.elapsed_time(b)
+
+    first_ms = add(x0)
+    extend_truth(x0, 0)
+    rec0, _ = measure()
+    recalls, insert_ms, search_ms = [rec0], [], []
+    for bi in range(nb):
+        lo = n0 + bi * bs
+        xb = torch.from_numpy(X[lo:lo + bs]).to(dev)
+        torch.cuda.synchronize()
+        insert_ms.append(add(xb))
+        extend_truth(xb, lo)
+        r, ms = measure()
+        recalls.append(r)
+        search_ms.append(ms)
+    total = ix.ntotal()
+    ix.close()
+    rate = [bs / (ms * 1e-3) for ms in insert_ms]
+    out = {
+        "metric": f"streaming insert vectors/s (100k-row batches, no retraining) + recall@10 drift (nprobe={nprobe}, k={w.k})",
+        "value": float(np.mean(rate)) if rate else None, "unit": "vectors/s", "n_gpus": 1, "steps": nb, "warmup": 0,
+        "ms_per_step": float(np.mean(insert_ms)) if insert_ms else None, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f16-split products, f32 accumulate (f32-accurate)", "data": "synthetic",
+        "config": {"workload": f"streaming ingest: {w.d}-d unit-norm mixture, nlist={w.nlist} trained on the first {n0} rows, "
+                               f"{nb} batches of {bs}, b={w.b}, {w.nq} queries after every batch", "nprobe": nprobe, "k": w.k},
+        "initial_encode_vectors_per_s": n0 / (first_ms * 1e-3), "ntotal": int(total),
+        "insert_vectors_per_s_min": float(np.min(rate)) if rate else None,
+        "insert_vectors_per_s_median": float(np.median(rate)) if rate else None,
+        "recall_at_10_first": recalls[0], "recall_at_10_last": recalls[-1], "recall_drift": recalls[-1] - recalls[0],
+        "recall_at_10_min": float(np.min(recalls)), "recall_at_10_per_batch": [round(r, 4) for r in recalls],
+        "search_qps_first": w.nq / (search_ms[0] * 1e-3) if search_ms else None,
+        "search_qps_last": w.nq / (search_ms[-1] * 1e-3) if search_ms else None,
+        "wall_s": time.perf_counter() - t0,
+    }
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--nprobe", type=int, default=None, help="primary nprobe (default: 32, or the workload's second value)")
-    ap.add_argument("--workload", default="1m", choices=["1m", "10m_d96", "10m_d200"],
-                    help="1m is the benchmark workload; the 10M ones are for scale checks")
+    ap.add_argument("--workload", default="1m", choices=["1m", "10m_d96", "10m_d200", "stream_d96"],
+                    help="1m is the benchmark workload; the 10M ones are for scale checks; stream_d96 is the "
+                         "streaming-ingest run (1M rows, then 100k-row batches)")
+    ap.add_argument("--stream-batches", type=int, default=90)
     ap.add_argument("--bits", type=int, default=4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true")
@@ -140,6 +230,9 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         print(json.dumps({"copy_bytes_read": 1 << 30, "copy_bytes_written": 1 << 30, "launches": 5}))
+        return
+    if args.workload == "stream_d96":
+        run_streaming(args, torch, pkg, synth)
         return
     w = {"1m": synth.config_1m, "10m_d96": lambda: synth.config_10m_d96(args.bits),
          "10m_d200": synth.config_10m_d200}[args.workload]()
