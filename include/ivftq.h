@@ -112,7 +112,10 @@ ivftq_status ivftq_get_codebook(const ivftq_index* index, float* centroids_out, 
 /* Encode the n rows of x_dev (device, n x d) and append each to the inverted list of its coarse
  * cell, in input order.  ids_dev: device, n int64 labels, or NULL for consecutive labels
  * continuing from ivftq_ntotal().  Stored per vector: b*d code bits, a float16 residual norm and
- * the label.  On IVFTQ_ZERO_NORM nothing is appended.  Synchronises. */
+ * the label.  On IVFTQ_ZERO_NORM nothing is appended.  Waits for the stream once (after the coarse
+ * assignment, to size the lists on the host); the encode kernel itself and the update of the list
+ * sizes are left running on the stream, so x_dev and ids_dev must stay valid until the stream has
+ * passed them.  Later calls on the same stream see the appended vectors. */
 ivftq_status ivftq_encode_add(ivftq_index* index, const float* x_dev, int64_t n,
                               const int64_t* ids_dev, void* stream);
 
@@ -120,7 +123,8 @@ ivftq_status ivftq_encode_add(ivftq_index* index, const float* x_dev, int64_t n,
  * an index built elsewhere).  assign_dev: n int32 cell numbers in [0, nlist); codes_dev: n x d
  * uint8 bin numbers in [0, 2^b); gamma_dev: n float16 bit patterns; ids_dev: n int64 labels or NULL
  * for consecutive labels.  All device pointers.  Rows are appended in input order.  A cell number
- * out of range gives IVFTQ_INVALID_ARG and nothing is appended.  Synchronises. */
+ * out of range gives IVFTQ_INVALID_ARG and nothing is appended.  Stream behaviour as for
+ * ivftq_encode_add: one wait, then the packing runs on the stream. */
 ivftq_status ivftq_add_encoded(ivftq_index* index, int64_t n, const int32_t* assign_dev,
                                const uint8_t* codes_dev, const uint16_t* gamma_dev,
                                const int64_t* ids_dev, void* stream);

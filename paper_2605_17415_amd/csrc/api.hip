@@ -59,6 +59,20 @@ struct DevBuf {
     template <class T> T* as() const { return static_cast<T*>(p); }
 };
 
+// Grow-only pinned host buffer (staging for small asynchronous copies in both directions).
+struct PinnedBuf {
+    void* p = nullptr;
+    size_t bytes = 0;
+    hipError_t ensure(size_t need) {
+        if (need <= bytes) return hipSuccess;
+        if (p) { (void)hipHostFree(p); p = nullptr; bytes = 0; }
+        hipError_t e = hipHostMalloc(&p, need, hipHostMallocDefault);
+        if (e == hipSuccess) bytes = need; else p = nullptr;
+        return e;
+    }
+    void release() { if (p) (void)hipHostFree(p); p = nullptr; bytes = 0; }
+};
+
 // kernel classes for the optional per-launch timing
 enum ProfId { P_ASSIGN, P_COARSE_SCORES, P_ENCODE, P_ROTATE_Q, P_SEG_HIST, P_SEG_SCAN, P_RANK, P_PACK,
               P_COPY_LISTS, P_SELECT_PROBE, P_CAND_OFF, P_LIST_SCAN, P_SELECT_TOPK, P_KMEANS_UPDATE,
@@ -94,6 +108,7 @@ struct ivftq_index {
     std::vector<int64_t> h_off, h_cap;
     std::vector<int32_t> h_size;
     int64_t pool_slots = 0;
+    PinnedBuf pin;   // [L u32 batch counts | 16 B flag | 2L i64 bases | L i32 sizes], see place_rows / commit_rows
     int64_t ntotal = 0;
     // workspace
     DevBuf w_assign, w_slot, w_order, w_hist, w_count, w_base, w_flag, w_best;
@@ -124,6 +139,7 @@ struct ivftq_index {
                             &w_first, &w_fscores, &w_fids, &w_pairs, &w_pairoff, &w_tileoff, &w_cscore,
                             &w_cslot, &w_ccnt, &w_gate, &w_zh, &w_zl})
             bfr->release();
+        pin.release();
     }
 };
 
@@ -662,19 +678,26 @@ ivftq_status place_rows(ivftq_index* ix, const int32_t* assign, int64_t n, bool 
     if (want_order) HIP_TRY(ix->w_order.ensure((size_t)n * sizeof(int32_t)));
     HIP_TRY(timed(ix, st, P_SEG_HIST, [&] { return launch_segment_hist(assign, n, seg_len, nseg, L, ix->w_hist.as<uint32_t>(), st); }));
     HIP_TRY(timed(ix, st, P_SEG_SCAN, [&] { return launch_segment_scan(ix->w_hist.as<uint32_t>(), nseg, L, ix->w_count.as<uint32_t>(), st); }));
-    std::vector<uint32_t> count(L);
-    int flag = 0;
-    HIP_TRY(hipMemcpyAsync(count.data(), ix->w_count.p, L * sizeof(uint32_t), hipMemcpyDeviceToHost, st));
-    HIP_TRY(hipMemcpyAsync(&flag, ix->w_flag.p, sizeof(int), hipMemcpyDeviceToHost, st));
+    // pinned staging: [L u32 batch counts | 16 B flag | 2L i64 bases | L i32 list sizes]
+    const size_t off_flag = (size_t)round_up(L, 4) * sizeof(uint32_t), off_base = off_flag + 16;
+    const size_t off_size = off_base + (size_t)2 * L * sizeof(int64_t);
+    HIP_TRY(ix->pin.ensure(off_size + (size_t)L * sizeof(int32_t)));
+    char* pin = static_cast<char*>(ix->pin.p);
+    const uint32_t* count = reinterpret_cast<const uint32_t*>(pin);
+    const int* flag = reinterpret_cast<const int*>(pin + off_flag);
+    int64_t* base = reinterpret_cast<int64_t*>(pin + off_base);   // [0, L): first free slot of each list; [L, 2L): first position in the batch order
+    HIP_TRY(hipMemcpyAsync(pin, ix->w_count.p, L * sizeof(uint32_t), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipMemcpyAsync(pin + off_flag, ix->w_flag.p, sizeof(int), hipMemcpyDeviceToHost, st));
+    // The one host synchronisation of an append: the host decides here whether the lists have room.
+    // It also means every earlier use of the staging buffer by this stream has completed.
     HIP_TRY(hipStreamSynchronize(st));
-    if (zero_norm_flag && flag)
+    if (zero_norm_flag && *flag)
         return fail(IVFTQ_ZERO_NORM, "an input row has zero or non-finite norm; nothing was appended");
     int64_t placed = 0;
     for (int l = 0; l < L; ++l) placed += count[l];
     if (placed != n) return fail(IVFTQ_INVALID_ARG, "%lld rows carry a cell number outside [0, nlist)", (long long)(n - placed));
 
     need.resize(L);
-    std::vector<int64_t> base(2 * (size_t)L);     // [0, L): first free slot of each list; [L, 2L): first position in the batch order
     for (int l = 0; l < L; ++l) need[l] = (int64_t)ix->h_size[l] + count[l];
     for (int l = 0; l < L; ++l)
         if (need[l] > INT32_MAX) return fail(IVFTQ_UNSUPPORTED, "list %d would exceed 2^31-1 vectors", l);
@@ -686,18 +709,20 @@ ivftq_status place_rows(ivftq_index* ix, const int32_t* assign, int64_t n, bool 
         base[L + l] = run;
         run += count[l];
     }
-    HIP_TRY(hipMemcpyAsync(ix->w_base.p, base.data(), base.size() * sizeof(int64_t), hipMemcpyHostToDevice, st));
+    HIP_TRY(hipMemcpyAsync(ix->w_base.p, base, (size_t)2 * L * sizeof(int64_t), hipMemcpyHostToDevice, st));
     HIP_TRY(timed(ix, st, P_RANK, [&] { return launch_stable_rank(assign, n, seg_len, nseg, L, ix->w_hist.as<uint32_t>(), ix->w_base.as<int64_t>(),
                                ix->w_slot.as<int64_t>(), ix->w_base.as<int64_t>() + L,
                                want_order ? ix->w_order.as<int32_t>() : nullptr, st); }));
-    HIP_TRY(hipStreamSynchronize(st));   // `base` is pageable host memory
     return IVFTQ_OK;
 }
 
+// Records the new list sizes; the device copy is updated in stream order (no host wait).
 ivftq_status commit_rows(ivftq_index* ix, const std::vector<int64_t>& need, int64_t n, hipStream_t st) {
-    for (int l = 0; l < ix->nlist; ++l) ix->h_size[l] = (int32_t)need[l];
-    HIP_TRY(hipMemcpyAsync(ix->d_size.p, ix->h_size.data(), ix->nlist * sizeof(int32_t), hipMemcpyHostToDevice, st));
-    HIP_TRY(hipStreamSynchronize(st));
+    const int L = ix->nlist;
+    const size_t off_size = (size_t)round_up(L, 4) * sizeof(uint32_t) + 16 + (size_t)2 * L * sizeof(int64_t);
+    int32_t* sizes = reinterpret_cast<int32_t*>(static_cast<char*>(ix->pin.p) + off_size);   // allocated by place_rows
+    for (int l = 0; l < L; ++l) sizes[l] = ix->h_size[l] = (int32_t)need[l];
+    HIP_TRY(hipMemcpyAsync(ix->d_size.p, sizes, (size_t)L * sizeof(int32_t), hipMemcpyHostToDevice, st));
     ix->ntotal += n;
     return IVFTQ_OK;
 }
