@@ -53,6 +53,8 @@ _SPECS = {
     "d100_b5":  ("gen100", 5_003, 64, 32, 5, 5, 7, 3, 5_003),          # d not a multiple of 32
     "d70_b6":   ("gen70", 3_001, 40, 20, 6, 3, 5, 3, 3_001),           # d not a multiple of 4
     "d8_b1":    ("gen8", 1_000, 33, 7, 1, 7, 3, 3, 1_000),             # smallest d, 1 bit, nprobe = nlist
+    "d256_b8":  ("gen256", 2_005, 32, 16, 8, 4, 10, 3, 2_005),         # largest d and b: biggest tiles, tables and words
+    "d16_b7":   ("gen16", 1_500, 32, 8, 7, 3, 5, 3, 1_500),            # 7-bit codes straddle word boundaries
 }
 
 
