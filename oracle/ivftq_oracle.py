@@ -171,6 +171,68 @@ def bin_masses(tau, d: int, density: str = "sphere"):
 
 
 # --------------------------------------------------------------------------
+# Stage 2: sign-bit refinement (Appendix "Sign-bit refinement")
+# --------------------------------------------------------------------------
+#
+# One more bit per coordinate says on which side of its bin's centroid the value lies,
+# s = 1[v >= c_i]; reconstruction uses the mean of the half-bin.  The half-bin means are taken
+# under the same coordinate density the codebook is designed for (the appendix writes
+# N(0, 1/d) there as it does for the codebook itself).
+
+
+def half_bin_means(c, tau, d: int, density: str = "sphere"):
+    """m[i, s] = E[T | T in half-bin (i, s)]: s = 0 is [tau_i, c_i), s = 1 is [c_i, tau_{i+1}).
+
+    Also returns the probability mass of every half-bin, same shape [K, 2]."""
+    pdf = _pdf(density, d)
+    lo, hi = _support(density, d)
+    c = np.asarray(c, dtype=np.float64)
+    edges = np.concatenate(([lo], np.asarray(tau, dtype=np.float64), [hi]))
+    K = len(c)
+    means = np.empty((K, 2))
+    mass = np.empty((K, 2))
+    for i in range(K):
+        for s, (a, b) in enumerate(((edges[i], c[i]), (c[i], edges[i + 1]))):
+            m0 = _integrate_bins(pdf, np.array([a, b]))[0]
+            m1 = _integrate_bins(lambda t: t * pdf(t), np.array([a, b]))[0]
+            mass[i, s] = m0
+            means[i, s] = m1 / m0
+    return means, mass
+
+
+def sign_bits(rho, codes, c):
+    """s_j = 1[rho_j >= c_{code_j}] for every coordinate (the stored refinement bit)."""
+    c = np.asarray(c)
+    return (np.asarray(rho) >= c[np.asarray(codes, dtype=np.int64)]).astype(np.uint8)
+
+
+def refined_tables(c, tau, d: int, density: str = "sphere"):
+    """The same refinement written as one quantiser with 2K levels: its 2K-1 boundaries are the
+    bin boundaries and the centroids interleaved (c_0 < tau_1 < c_1 < ...), its level 2i+s is the
+    mean of half-bin (i, s); then  #{boundaries <= v} = 2*code + s."""
+    means, _ = half_bin_means(c, tau, d, density)
+    c = np.asarray(c, dtype=np.float64)
+    tau = np.asarray(tau, dtype=np.float64)
+    K = len(c)
+    bnd = np.empty(2 * K - 1)
+    bnd[0::2] = c
+    bnd[1::2] = tau
+    return means.reshape(2 * K), bnd
+
+
+def refined_codebook_fp32(b: int, d: int, density: str = "sphere"):
+    """Stage 1 at b bits plus the sign bit, as stored: 2^(b+1) float32 levels and 2^(b+1) - 1
+    float32 boundaries.  Boundaries are the float32 Stage-1 centroids and boundaries themselves."""
+    c, tau = lloyd_max_codebook(b, d, density)
+    levels, _ = refined_tables(c, tau, d, density)
+    c32, tau32 = c.astype(np.float32), tau.astype(np.float32)
+    bnd = np.empty(2 * len(c) - 1, np.float32)
+    bnd[0::2] = c32
+    bnd[1::2] = tau32
+    return levels.astype(np.float32), bnd
+
+
+# --------------------------------------------------------------------------
 # Rotation
 # --------------------------------------------------------------------------
 

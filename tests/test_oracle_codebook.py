@@ -200,3 +200,77 @@ def test_rotation_entries_have_haar_moments():
     assert abs(first_col.var() - 1.0 / d) < 0.1 / d
     # fourth moment of a sphere coordinate: 3 / (d (d+2))
     assert abs((first_col ** 4).mean() - 3.0 / (d * (d + 2))) < 0.15 * 3.0 / (d * (d + 2))
+
+
+# ---- Stage 2: sign-bit refinement (Appendix "Sign-bit refinement") -------------------------------
+
+
+@pytest.mark.parametrize("b,d", [(1, 64), (2, 96), (3, 128), (4, 96), (4, 200)])
+def test_half_bin_means_split_each_bin_consistently(b, d):
+    c, tau = orc.lloyd_max_codebook(b, d)
+    means, mass = orc.half_bin_means(c, tau, d)
+    K = 1 << b
+    edges = np.concatenate(([-1.0], tau, [1.0]))
+    # each half-bin mean lies inside its half-bin
+    assert np.all(means[:, 0] > edges[:-1]) and np.all(means[:, 0] < c)
+    assert np.all(means[:, 1] > c) and np.all(means[:, 1] < edges[1:])
+    # law of total expectation: the two halves average back to the bin's centroid, masses add up
+    p = np.diff(_cdf_sphere(edges, d))                      # bin masses by the incomplete beta function
+    np.testing.assert_allclose(mass.sum(axis=1), p, atol=1e-12)
+    np.testing.assert_allclose((mass * means).sum(axis=1), p * c, atol=1e-12)
+    # half-bin masses and first moments against closed forms
+    for i in range(K):
+        for s, (a_, b_) in enumerate(((edges[i], c[i]), (c[i], edges[i + 1]))):
+            m0 = _cdf_sphere(np.array([a_, b_]), d)
+            assert abs(mass[i, s] - (m0[1] - m0[0])) < 1e-12
+            assert abs(means[i, s] - _first_moment_sphere(a_, b_, d) / (m0[1] - m0[0])) < 1e-10
+    # symmetry of the density
+    np.testing.assert_allclose(means[:, 0], -means[::-1, 1], atol=1e-13)
+
+
+def test_one_bit_gaussian_refinement_matches_truncated_normal_means():
+    """b = 1 under the Gaussian design: bins are the half-lines, the centroid is sigma*sqrt(2/pi), and
+    the half-bin means are means of a normal truncated to [0, m) and [m, inf) (textbook formulas)."""
+    d = 128
+    sg = 1.0 / math.sqrt(d)
+    c, tau = orc.lloyd_max_codebook(1, d, "gauss")
+    assert abs(c[1] - sg * math.sqrt(2 / math.pi)) < 1e-12
+    means, mass = orc.half_bin_means(c, tau, d, "gauss")
+    a = c[1] / sg
+    phi = lambda t: math.exp(-0.5 * t * t) / math.sqrt(2 * math.pi)
+    Phi = lambda t: 0.5 * (1 + math.erf(t / math.sqrt(2)))
+    inner = sg * (phi(0.0) - phi(a)) / (Phi(a) - Phi(0.0))
+    outer = sg * phi(a) / (1.0 - Phi(a))
+    assert abs(means[1, 0] - inner) < 1e-10 and abs(means[1, 1] - outer) < 1e-10
+    assert abs(mass[1, 0] - (Phi(a) - 0.5)) < 1e-12
+
+
+@pytest.mark.parametrize("b,d", [(2, 96), (3, 128), (4, 96)])
+def test_refinement_sits_between_b_and_b_plus_one_bits(b, d):
+    """The refined quantiser has 2^(b+1) levels but keeps the b-bit boundaries, so its distortion is
+    below the b-bit one and cannot beat the optimal (b+1)-bit Lloyd-Max quantiser."""
+    c, tau = orc.lloyd_max_codebook(b, d)
+    levels, bnd = orc.refined_tables(c, tau, d)
+    D_b = orc.codebook_distortion(c, tau, d)
+    D_ref = orc.codebook_distortion(levels, bnd, d)
+    c1, tau1 = orc.lloyd_max_codebook(b + 1, d)
+    D_b1 = orc.codebook_distortion(c1, tau1, d)
+    assert D_b1 < D_ref < D_b
+    assert D_ref < 0.45 * D_b                                # one extra bit is worth close to a factor 4
+
+
+@pytest.mark.parametrize("b,d", [(2, 64), (4, 128)])
+def test_merged_table_form_equals_the_literal_definition(b, d):
+    """code_refined = #{merged boundaries <= v} equals 2*code + 1[v >= c_code], and looking the level up
+    equals the half-bin mean, for random values and for values exactly on centroids and boundaries."""
+    c, tau = orc.lloyd_max_codebook(b, d)
+    means, _ = orc.half_bin_means(c, tau, d)
+    levels, bnd = orc.refined_tables(c, tau, d)
+    rng = np.random.default_rng(b * 100 + d)
+    v = np.concatenate([rng.standard_normal(20000) / math.sqrt(d), c, tau, np.nextafter(c, -1), np.nextafter(tau, -1), [-1, 1, 0]])
+    code = orc.quantize(v[None, :], tau)[0]
+    s = orc.sign_bits(v, code, c)
+    refined = orc.quantize(v[None, :], bnd)[0]
+    np.testing.assert_array_equal(refined, 2 * code.astype(np.int64) + s)
+    np.testing.assert_array_equal(levels[refined], means[code, s])
+    assert orc.bits_per_vector(4, 96, True) == 4 * 96 + 96 + 32    # the same total as (b+1)*d + 32
