@@ -206,6 +206,8 @@ def main():
                          "streaming-ingest run (1M rows, then 100k-row batches)")
     ap.add_argument("--stream-batches", type=int, default=90)
     ap.add_argument("--bits", type=int, default=4)
+    ap.add_argument("--sign-bit", action="store_true",
+                    help="store the sign-bit refinement as well (bits + 1 stored per coordinate; not the default workload)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -257,7 +259,7 @@ def main():
     t_setup = time.perf_counter() - t_setup
 
     def new_index():
-        ix = pkg.Index(w.d, w.b, w.nlist, rotation_seed=w.seed)
+        ix = pkg.Index(w.d, w.b, w.nlist, rotation_seed=w.seed, sign_bit=args.sign_bit)
         ix.set_coarse(cent)
         return ix
 
@@ -319,7 +321,8 @@ def main():
     sizes = np.array([ix.list_size(l) for l in range(w.nlist)], dtype=np.int64)
     per_probe = sizes[probe]                                   # [nq, nprobe] vectors behind each probe
     cand = per_probe.sum(axis=1)
-    bytes_per_vec = (w.b * w.d + 7) // 8 + 2
+    stored_bits = w.b + (1 if args.sign_bit else 0)
+    bytes_per_vec = (stored_bits * w.d + 7) // 8 + 2
     scan_bytes = float(cand.sum()) * bytes_per_vec             # every probed vector's codes + norm, once per query
     csum = np.cumsum(per_probe, axis=1)
     first = np.minimum((csum < w.k).sum(axis=1) + 1, args.nprobe)      # probes the streaming pass covers
@@ -395,7 +398,7 @@ def main():
                                 "sample), b=4, 10000 queries, k=10") if args.workload == "1m" else
                                f"{w.name}: {w.n} x {w.d}, nlist={w.nlist}, b={w.b}, {w.nq} queries, k={w.k}",
                    "nprobe": args.nprobe, "n": w.n, "d": w.d,
-                   "nlist": w.nlist, "b": w.b, "nq": w.nq, "k": w.k},
+                   "nlist": w.nlist, "b": w.b, "sign_bit": bool(args.sign_bit), "nq": w.nq, "k": w.k},
         "recall_at_10": rec,
         "search_ms": search_t * 1e3, "encode_ms": enc_t * 1e3, "encode_vectors_per_s": vps,
         "candidates_per_query": float(cand.mean()),

@@ -59,15 +59,25 @@ enum {
  * rounded to float. */
 ivftq_status ivftq_build_codebook(int b, int d, float* centroids_out, float* boundaries_out);
 
+/* Stage 1 at b bits plus the sign-bit refinement (Appendix "Sign-bit refinement": one more bit per
+ * coordinate, s = 1[v >= c_i] for the value's bin i, reconstruction by the mean of the half-bin) as
+ * one quantiser with 2^(b+1) levels, which is how the library stores and scans it:
+ * boundaries_out (2^(b+1) - 1 floats) = the Stage-1 centroids and boundaries interleaved,
+ * levels_out (2^(b+1) floats): entry 2i + s = E[T | T in half-bin (i, s)] under the density the
+ * codebook is designed for.  #{j : v >= boundaries_out[j]} = 2*code + s.  1 <= b <= 7.  Host. */
+ivftq_status ivftq_build_refined_codebook(int b, int d, float* levels_out, float* boundaries_out);
+
 /* The table through which the encode kernel evaluates  code = #{i : v >= boundary_i}  (same
  * passage as above) with one lookup: the real line is cut into *cells_out equal cells (the two
  * outermost open-ended), cell(v) = clamp((int)(v * *scale_out + *offset_out), 0, cells - 1) in float
  * arithmetic, and  code = index_out[cell] + (v >= boundary_out[cell]).  For inspection and host-side
  * tests; all pointers host.  boundary_out / index_out (either may be NULL) need `capacity` >= cells
  * entries, else IVFTQ_INVALID_ARG; call with both NULL to learn the size.  IVFTQ_UNSUPPORTED if
- * (b, d) would need more than 4096 cells (then ivftq_create fails the same way). */
-ivftq_status ivftq_quantiser_grid(int b, int d, int capacity, int* cells_out, float* scale_out,
-                                  float* offset_out, float* boundary_out, int32_t* index_out);
+ * (b, d) would need more than 4096 cells (then ivftq_create fails the same way).  sign_bit = 1:
+ * the table of the merged quantiser of ivftq_build_refined_codebook. */
+ivftq_status ivftq_quantiser_grid(int b, int sign_bit, int d, int capacity, int* cells_out,
+                                  float* scale_out, float* offset_out, float* boundary_out,
+                                  int32_t* index_out);
 
 /* Haar-distributed orthogonal matrix (same appendix, Setup): QR of a d x d Gaussian matrix with
  * the sign of each column fixed so that diag(R) > 0.  pi_out: host, d*d floats, row-major, acting
@@ -81,6 +91,12 @@ ivftq_status ivftq_haar_from_gaussian(int d, const double* g, float* pi_out);
 /* New empty index on the current HIP device: builds the (b, d) codebook and a Haar rotation from
  * rotation_seed.  Coarse centroids must be trained or set before encoding or searching. */
 ivftq_status ivftq_create(int d, int b, int nlist, uint64_t rotation_seed, ivftq_index** out);
+/* The same with the sign-bit refinement switched on (sign_bit = 1): b Stage-1 bits + 1 refinement
+ * bit are stored per coordinate, b + 1 <= 8.  Codes reported and accepted by the other calls are
+ * then the merged ones, 2*code + s in [0, 2^(b+1)), and ivftq_get_codebook returns the tables of
+ * ivftq_build_refined_codebook.  sign_bit = 0 is ivftq_create. */
+ivftq_status ivftq_create_refined(int d, int b, int sign_bit, int nlist, uint64_t rotation_seed,
+                                  ivftq_index** out);
 ivftq_status ivftq_destroy(ivftq_index* index);
 /* Remove every stored vector.  Constants, the capacity already reserved for the lists and the
  * search workspace are kept, so the index can be filled again without allocating.  Synchronises. */

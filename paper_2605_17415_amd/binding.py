@@ -20,11 +20,13 @@ STATUS_NAMES = ["OK", "INVALID_ARG", "BAD_STATE", "OOM", "HIP_ERROR", "ZERO_NORM
 # every symbol include/ivftq.h declares, with its ctypes signature
 _SIGNATURES = {
     "ivftq_build_codebook": (C.c_int, [C.c_int, C.c_int, C.c_void_p, C.c_void_p]),
-    "ivftq_quantiser_grid": (C.c_int, [C.c_int, C.c_int, C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_float),
+    "ivftq_quantiser_grid": (C.c_int, [C.c_int, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_float),
                                        C.POINTER(C.c_float), C.c_void_p, C.c_void_p]),
     "ivftq_haar_rotation": (C.c_int, [C.c_int, C.c_uint64, C.c_void_p]),
     "ivftq_haar_from_gaussian": (C.c_int, [C.c_int, C.c_void_p, C.c_void_p]),
     "ivftq_create": (C.c_int, [C.c_int, C.c_int, C.c_int, C.c_uint64, C.POINTER(C.c_void_p)]),
+    "ivftq_create_refined": (C.c_int, [C.c_int, C.c_int, C.c_int, C.c_int, C.c_uint64, C.POINTER(C.c_void_p)]),
+    "ivftq_build_refined_codebook": (C.c_int, [C.c_int, C.c_int, C.c_void_p, C.c_void_p]),
     "ivftq_destroy": (C.c_int, [C.c_void_p]),
     "ivftq_reset": (C.c_int, [C.c_void_p]),
     "ivftq_train_coarse": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_int, C.c_void_p, C.c_uint64,
@@ -130,14 +132,25 @@ def ivftq_build_codebook(b: int, d: int):
     return c, t[:K - 1]
 
 
-def ivftq_quantiser_grid(b: int, d: int):
+def ivftq_build_refined_codebook(b: int, d: int):
+    """(levels [2^(b+1)] f32, boundaries [2^(b+1) - 1] f32) of Stage 1 at b bits + sign bit"""
+    lib = load_library()
+    K2 = 2 << max(0, min(b, 15))
+    lv = np.empty(K2, np.float32)
+    bd = np.empty(K2 - 1, np.float32)
+    _check(lib.ivftq_build_refined_codebook(b, d, _np_ptr(lv), _np_ptr(bd)))
+    return lv, bd
+
+
+def ivftq_quantiser_grid(b: int, d: int, sign_bit: bool = False):
     """(cells, scale, offset, boundary [cells] f32, index [cells] i32)"""
+    sb = 1 if sign_bit else 0
     lib = load_library()
     cells, scale, offset = C.c_int(0), C.c_float(0), C.c_float(0)
-    _check(lib.ivftq_quantiser_grid(b, d, 0, C.byref(cells), C.byref(scale), C.byref(offset), None, None))
+    _check(lib.ivftq_quantiser_grid(b, sb, d, 0, C.byref(cells), C.byref(scale), C.byref(offset), None, None))
     boundary = np.empty(cells.value, np.float32)
     index = np.empty(cells.value, np.int32)
-    _check(lib.ivftq_quantiser_grid(b, d, cells.value, C.byref(cells), C.byref(scale), C.byref(offset),
+    _check(lib.ivftq_quantiser_grid(b, sb, d, cells.value, C.byref(cells), C.byref(scale), C.byref(offset),
                                     _np_ptr(boundary), _np_ptr(index)))
     return cells.value, np.float32(scale.value), np.float32(offset.value), boundary, index
 
@@ -175,11 +188,15 @@ def ivftq_version() -> str:
 class Index:
     """Owner of one ivftq_index handle.  Methods carry the C names minus the prefix."""
 
-    def __init__(self, d: int, b: int, nlist: int, rotation_seed: int = 0):
+    def __init__(self, d: int, b: int, nlist: int, rotation_seed: int = 0, sign_bit: bool = False):
         self._lib = load_library()
         self._h = C.c_void_p()
-        _check(self._lib.ivftq_create(d, b, nlist, rotation_seed, C.byref(self._h)))
-        self.d, self.b, self.nlist = d, b, nlist
+        if sign_bit:
+            _check(self._lib.ivftq_create_refined(d, b, 1, nlist, rotation_seed, C.byref(self._h)))
+        else:
+            _check(self._lib.ivftq_create(d, b, nlist, rotation_seed, C.byref(self._h)))
+        self.d, self.nlist = d, nlist
+        self.b = b + (1 if sign_bit else 0)      # bits stored per coordinate
 
     def close(self):
         if getattr(self, "_h", None) is not None and self._h.value:

@@ -97,7 +97,8 @@ uint64_t splitmix(uint64_t& s) {
 }  // namespace
 
 struct ivftq_index {
-    int d = 0, b = 0, nlist = 0, K = 0, dp = 0, lpad = 0, words = 0;
+    int d = 0, b = 0, nlist = 0, K = 0, dp = 0, lpad = 0, words = 0;   // b: bits stored per coordinate (Stage 1 + sign bit)
+    int sign_bit = 0;
     int q_cells = 0; float q_scale = 0.f, q_offset = 0.f;   // quantiser grid (host_math.h)
     bool has_coarse = false;
     std::vector<float> h_cent, h_pi, h_cb, h_tau;
@@ -270,15 +271,30 @@ ivftq_status ivftq_build_codebook(int b, int d, float* centroids_out, float* bou
     return IVFTQ_OK;
 }
 
-ivftq_status ivftq_quantiser_grid(int b, int d, int capacity, int* cells_out, float* scale_out, float* offset_out,
-                                  float* boundary_out, int32_t* index_out) {
+ivftq_status ivftq_build_refined_codebook(int b, int d, float* levels_out, float* boundaries_out) {
+    if (b < 1 || b > 7 || d < 3) return fail(IVFTQ_INVALID_ARG, "need 1 <= b <= 7 and d >= 3 (b=%d d=%d)", b, d);
+    if (!levels_out && !boundaries_out) return fail(IVFTQ_INVALID_ARG, "both outputs NULL");
+    std::vector<double> lv, bd, c, t;
+    if (!build_refined_codebook(b, d, lv, bd) || !build_codebook(b, d, c, t))
+        return fail(IVFTQ_INVALID_ARG, "codebook construction failed");
+    if (levels_out) for (size_t i = 0; i < lv.size(); ++i) levels_out[i] = (float)lv[i];
+    // the boundaries are the float32 Stage-1 centroids and boundaries themselves, interleaved
+    if (boundaries_out) for (size_t i = 0; i < bd.size(); ++i) boundaries_out[i] = (float)bd[i];
+    return IVFTQ_OK;
+}
+
+ivftq_status ivftq_quantiser_grid(int b, int sign_bit, int d, int capacity, int* cells_out, float* scale_out,
+                                  float* offset_out, float* boundary_out, int32_t* index_out) {
     if (!cells_out || !scale_out || !offset_out) return fail(IVFTQ_INVALID_ARG, "output pointer is NULL");
-    std::vector<float> c(1 << (b < 1 || b > 8 ? 1 : b)), tau((1 << (b < 1 || b > 8 ? 1 : b)) - 1);
-    ivftq_status s = ivftq_build_codebook(b, d, c.data(), tau.data());
+    if (sign_bit != 0 && sign_bit != 1) return fail(IVFTQ_INVALID_ARG, "sign_bit=%d is neither 0 nor 1", sign_bit);
+    if (b < 1 || b + sign_bit > 8) return fail(IVFTQ_INVALID_ARG, "b=%d (+%d sign bit) outside [1, 8]", b, sign_bit);
+    std::vector<float> c((size_t)1 << (b + sign_bit)), tau(((size_t)1 << (b + sign_bit)) - 1);
+    ivftq_status s = sign_bit ? ivftq_build_refined_codebook(b, d, c.data(), tau.data())
+                              : ivftq_build_codebook(b, d, c.data(), tau.data());
     if (s != IVFTQ_OK) return s;
     QuantiserGrid grid;
     if (!build_quantiser_grid(tau, kMaxGridCells, grid))
-        return fail(IVFTQ_UNSUPPORTED, "quantiser grid for b=%d d=%d needs more than %d cells", b, d, kMaxGridCells);
+        return fail(IVFTQ_UNSUPPORTED, "quantiser grid for b=%d+%d d=%d needs more than %d cells", b, sign_bit, d, kMaxGridCells);
     *cells_out = grid.cells; *scale_out = grid.scale; *offset_out = grid.offset;
     if (boundary_out || index_out) {
         if (capacity < grid.cells) return fail(IVFTQ_INVALID_ARG, "capacity %d below the %d cells of the grid", capacity, grid.cells);
@@ -304,9 +320,16 @@ ivftq_status ivftq_haar_rotation(int d, uint64_t seed, float* pi_out) {
 }
 
 ivftq_status ivftq_create(int d, int b, int nlist, uint64_t rotation_seed, ivftq_index** out) {
+    return ivftq_create_refined(d, b, 0, nlist, rotation_seed, out);
+}
+
+ivftq_status ivftq_create_refined(int d, int b_stage1, int sign_bit, int nlist, uint64_t rotation_seed, ivftq_index** out) {
     if (!out) return fail(IVFTQ_INVALID_ARG, "out is NULL");
     *out = nullptr;
-    if (b < 1 || b > 8) return fail(IVFTQ_INVALID_ARG, "b=%d outside [1, 8]", b);
+    if (sign_bit != 0 && sign_bit != 1) return fail(IVFTQ_INVALID_ARG, "sign_bit=%d is neither 0 nor 1", sign_bit);
+    if (b_stage1 < 1 || b_stage1 + sign_bit > 8)
+        return fail(IVFTQ_INVALID_ARG, "b=%d (+%d sign bit) outside [1, 8] bits per coordinate", b_stage1, sign_bit);
+    const int b = b_stage1 + sign_bit;       // bits stored per coordinate: everything below works on the merged quantiser
     if (d < 8) return fail(IVFTQ_INVALID_ARG, "d=%d below 8", d);
     if (nlist < 1) return fail(IVFTQ_INVALID_ARG, "nlist=%d below 1", nlist);
     if (d > kMaxD) return fail(IVFTQ_UNSUPPORTED, "d=%d above %d", d, kMaxD);
@@ -324,7 +347,9 @@ ivftq_status ivftq_create(int d, int b, int nlist, uint64_t rotation_seed, ivftq
     ix->h_size.assign(nlist, 0);
     ix->h_cap.assign(nlist, 0);
     ix->h_off.assign(nlist, 0);
-    ivftq_status s = ivftq_build_codebook(b, d, ix->h_cb.data(), ix->h_tau.data());
+    ix->sign_bit = sign_bit;
+    ivftq_status s = sign_bit ? ivftq_build_refined_codebook(b_stage1, d, ix->h_cb.data(), ix->h_tau.data())
+                              : ivftq_build_codebook(b, d, ix->h_cb.data(), ix->h_tau.data());
     if (s == IVFTQ_OK) s = ivftq_haar_rotation(d, rotation_seed, ix->h_pi.data());
     if (s != IVFTQ_OK) { delete ix; return s; }
     auto guard = [&](hipError_t e, const char* what) -> ivftq_status {

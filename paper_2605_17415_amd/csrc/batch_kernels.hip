@@ -13,6 +13,8 @@
 // streaming scan), appending them to a short per-query candidate list.
 #include <hip/hip_fp16.h>
 
+#include <type_traits>
+
 #include "kernels.h"
 
 namespace ivftq {
@@ -246,7 +248,7 @@ void k_batch_scan(BatchScanArgs a) {
 
     // Raw words and norms of a slab are fetched one slab ahead so that their latency hides behind
     // the matrix work of the current slab.
-    constexpr int NW = (B == 3) ? 2 : 1;           // 24-bit chunks may straddle two words
+    constexpr int NW = (B == 3 || B == 5) ? 2 : 1; // 24- and 40-bit chunks straddle two words
     auto fetch = [&](int slab, uint32_t (&w)[KB][NW], uint32_t (&gp)[8]) {
         const int v_mine = slab * 32 + jl;         // this lane de-quantises vector jl of the slab
         const int64_t slot = base_slot + (v_mine < n_l ? v_mine : n_l - 1);
@@ -283,12 +285,13 @@ void k_batch_scan(BatchScanArgs a) {
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb) {
             const int sh = ((16 * kb + 8 * half) * B) & 31;
-            uint32_t chunk = cw[kb][0] >> sh;
-            if (NW == 2) chunk = (uint32_t)((((uint64_t)cw[kb][NW - 1] << 32) | cw[kb][0]) >> sh);
+            // the 8 codes of this lane's block: 8*B bits starting at bit sh of the first word
+            typename std::conditional<(8 * B > 32), uint64_t, uint32_t>::type chunk = cw[kb][0] >> sh;
+            if (NW == 2) chunk = (decltype(chunk))((((uint64_t)cw[kb][NW - 1] << 32) | cw[kb][0]) >> sh);
             uint32_t hv[4], lv[4];
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
-                const uint32_t idx = (chunk >> (2 * B * t)) & (uint32_t)(Cfg::PT - 1);
+                const uint32_t idx = (uint32_t)(chunk >> (2 * B * t)) & (uint32_t)(Cfg::PT - 1);
                 hv[t] = tab_h[idx];
                 lv[t] = tab_l[idx];
             }
@@ -454,7 +457,7 @@ hipError_t run_batch(const BatchScanArgs& a, int max_tiles, hipStream_t st) {
 
 int batch_tile_queries(int d, int b) {
     const int dp = rot_dp(d);
-    if (b < 2 || b > 4) return 0;
+    if (b < 2 || b > 5) return 0;
     if (dp == 64 || dp == 96 || dp == 128) return 128;
     if (dp == 224) return 64;
     return 0;
@@ -505,6 +508,7 @@ hipError_t launch_batch_scan(const BatchScanArgs& a, int d, int b, int max_tiles
         if (b == 2) return run_batch<DPV, 2, NQV, IVFTQ_BATCH_WAVES, OCCV>(a, max_tiles, st);  \
         if (b == 3) return run_batch<DPV, 3, NQV, IVFTQ_BATCH_WAVES, OCCV>(a, max_tiles, st);  \
         if (b == 4) return run_batch<DPV, 4, NQV, IVFTQ_BATCH_WAVES, OCCV>(a, max_tiles, st);  \
+        if (b == 5) return run_batch<DPV, 5, NQV, IVFTQ_BATCH_WAVES, OCCV>(a, max_tiles, st);  \
     }
     IVFTQ_BATCH(64, 4, IVFTQ_BATCH_OCC) IVFTQ_BATCH(96, 4, IVFTQ_BATCH_OCC)
     IVFTQ_BATCH(128, 4, IVFTQ_BATCH_OCC) IVFTQ_BATCH(224, 2, 2)

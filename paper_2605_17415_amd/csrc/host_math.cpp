@@ -166,6 +166,29 @@ bool build_codebook(int b, int d, std::vector<double>& cent, std::vector<double>
     return true;
 }
 
+bool build_refined_codebook(int b, int d, std::vector<double>& levels, std::vector<double>& boundaries) {
+    std::vector<double> cent, bnd;
+    if (b < 1 || b > 7 || !build_codebook(b, d, cent, bnd)) return false;
+    const int K = 1 << b;
+    SphereMarginal f(d);
+    levels.resize(2 * (size_t)K);
+    boundaries.resize(2 * (size_t)K - 1);
+    for (int i = 0; i < K; ++i) {
+        const double lo = i == 0 ? -1.0 : bnd[i - 1], hi = i == K - 1 ? 1.0 : bnd[i];
+        const double edge[3] = {lo, cent[i], hi};
+        for (int s = 0; s < 2; ++s) {
+            const double m = f.mass(edge[s], edge[s + 1]);
+            if (!(m > 0.0)) return false;
+            levels[2 * i + s] = f.first_moment(edge[s], edge[s + 1]) / m;
+        }
+        boundaries[2 * i] = cent[i];
+        if (i < K - 1) boundaries[2 * i + 1] = bnd[i];
+    }
+    for (size_t i = 1; i < levels.size(); ++i)
+        if (!(levels[i] > levels[i - 1])) return false;
+    return true;
+}
+
 // ---- random numbers for the rotation draw ------------------------------------------------
 
 static inline uint64_t splitmix64(uint64_t& s) {

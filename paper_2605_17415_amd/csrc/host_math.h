@@ -8,6 +8,12 @@ namespace ivftq {
 // K = 2^b Lloyd-Max centroids (ascending) and K-1 midpoints for the sphere-coordinate density.
 bool build_codebook(int b, int d, std::vector<double>& centroids, std::vector<double>& boundaries);
 
+// Stage 1 at b bits plus the sign-bit refinement (Appendix "Sign-bit refinement") written as one
+// quantiser of 2K levels: boundaries[2K-1] = the Stage-1 centroids and boundaries interleaved
+// (c_0 < tau_1 < c_1 < ...), levels[2i + s] = E[T | T in half-bin (i, s)] under the same density, so
+// that #{boundaries <= v} = 2*code + 1[v >= c_code].
+bool build_refined_codebook(int b, int d, std::vector<double>& levels, std::vector<double>& boundaries);
+
 // d x d iid N(0,1), row-major, from a 64-bit seed.
 void gaussian_matrix(int d, uint64_t seed, std::vector<double>& g);
 

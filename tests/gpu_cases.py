@@ -20,9 +20,14 @@ class Case:
     Pi: np.ndarray        # float32 rotation [d, d]
     c: np.ndarray         # float32 codebook centroids
     tau: np.ndarray       # float32 boundaries
-    b: int
+    b: int                # bits stored per coordinate (Stage 1 + sign bit)
     nprobe: int
     k: int
+    sign_bit: bool = False
+
+    @property
+    def b_stage1(self):
+        return self.b - (1 if self.sign_bit else 0)
 
     @property
     def d(self):
@@ -55,6 +60,9 @@ _SPECS = {
     "d8_b1":    ("gen8", 1_000, 33, 7, 1, 7, 3, 3, 1_000),             # smallest d, 1 bit, nprobe = nlist
     "d256_b8":  ("gen256", 2_005, 32, 16, 8, 4, 10, 3, 2_005),         # largest d and b: biggest tiles, tables and words
     "d16_b7":   ("gen16", 1_500, 32, 8, 7, 3, 5, 3, 1_500),            # 7-bit codes straddle word boundaries
+    # Stage 1 + sign-bit refinement (b here is the Stage-1 width; one more bit is stored)
+    "d96_b3s":  ("d96", 20_037, 120, 128, 3, 16, 10, 3, 8_000),         # 4 stored bits: the batched scan covers it
+    "d128_b4s": ("1m", 12_007, 90, 128, 4, 16, 10, 3, 8_000),           # 5 stored bits
 }
 
 
@@ -84,6 +92,9 @@ def get_case(name: str) -> Case:
     d = X.shape[1]
     cent, _ = orc.train_coarse(X[:train], nlist, iters, synth.kmeans_init_indices(seed, train, nlist))
     Pi = orc.haar_rotation_from_gaussian(synth.gaussian_matrix(seed, d))
+    if name.endswith("s"):        # sign-bit refinement: the merged 2K-level tables
+        c, tau = orc.refined_codebook_fp32(b, d)
+        return Case(name, X, Q, cent.astype(np.float32), Pi.astype(np.float32), c, tau, b + 1, nprobe, k, sign_bit=True)
     c, tau = orc.codebook_fp32(b, d)
     return Case(name, X, Q, cent.astype(np.float32), Pi.astype(np.float32), c, tau, b, nprobe, k)
 

@@ -21,7 +21,7 @@ DEV = "cuda:0"
 
 
 def _index(cs):
-    ix = _pkg().Index(cs.d, cs.b, cs.nlist)
+    ix = _pkg().Index(cs.d, cs.b_stage1, cs.nlist, sign_bit=cs.sign_bit)
     ix.set_coarse(cs.cent)
     ix.set_rotation(cs.Pi)
     return ix
@@ -30,7 +30,7 @@ def _index(cs):
 def test_error_paths_do_not_launch_or_append():
     pkg = _pkg()
     cs = gpu_cases.get_case("d8_b1")
-    ix = pkg.Index(cs.d, cs.b, cs.nlist)
+    ix = pkg.Index(cs.d, cs.b_stage1, cs.nlist, sign_bit=cs.sign_bit)
     x = torch.from_numpy(cs.X[:100]).to(DEV)
     with pytest.raises(pkg.IvftqError) as e:
         ix.encode_add(x)                                   # no centroids yet

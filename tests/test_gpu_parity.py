@@ -21,7 +21,7 @@ def _dev():
 
 
 def _make_index(cs):
-    ix = _pkg().Index(cs.d, cs.b, cs.nlist)
+    ix = _pkg().Index(cs.d, cs.b_stage1, cs.nlist, sign_bit=cs.sign_bit)
     ix.set_coarse(cs.cent)
     ix.set_rotation(cs.Pi)
     # the library's own (b, d) codebook must be the oracle's
@@ -60,7 +60,7 @@ def test_encode_matches_oracle(name):
     ix.close()
 
 
-BATCHED_CASES = ["tiny", "d128", "d96_b2", "d96_b3", "d96_b4", "d200"]    # shapes the batched scan covers
+BATCHED_CASES = ["tiny", "d128", "d96_b2", "d96_b3", "d96_b4", "d200", "d96_b3s", "d128_b4s", "d100_b5"]    # shapes the batched scan covers
 SEARCH_CASES = [(n, 1) for n in gpu_cases.ALL_CASES] + [(n, 2) for n in BATCHED_CASES]
 
 

@@ -127,3 +127,26 @@ def test_quantiser_grid_counts_boundaries_exactly(b, d):
         cell = np.clip(np.trunc(x.astype(np.float64) + nudge), 0, cells - 1).astype(np.int64)
         got = index[cell] + (v >= boundary[cell])
         np.testing.assert_array_equal(got, want)
+
+
+@pytest.mark.parametrize("b,d", [(1, 64), (2, 96), (3, 128), (4, 8), (4, 96), (4, 200), (7, 256)])
+def test_refined_codebook_matches_oracle_and_its_grid_counts_exactly(b, d):
+    """Stage 1 + sign bit as one quantiser: levels and boundaries against the oracle, and the lookup
+    table built over the merged boundaries still counts them exactly."""
+    lv, bd = pkg.ivftq_build_refined_codebook(b, d)
+    olv, obd = orc.refined_codebook_fp32(b, d)
+    np.testing.assert_array_equal(bd, obd)                  # float32 Stage-1 centroids and boundaries, interleaved
+    np.testing.assert_allclose(lv, olv, rtol=6e-8, atol=2e-8)
+    assert np.all(np.diff(bd) > 0) and np.all(np.diff(lv) > 0)
+    c, tau = pkg.ivftq_build_codebook(b, d)
+    np.testing.assert_array_equal(bd[0::2], c)
+    np.testing.assert_array_equal(bd[1::2], tau)
+    cells, scale, offset, boundary, index = pkg.ivftq_quantiser_grid(b, d, sign_bit=True)
+    assert 1 <= cells <= 4096
+    rng = np.random.default_rng(b + d)
+    v = np.concatenate([bd, np.nextafter(bd, np.float32(-2)), np.nextafter(bd, np.float32(2)),
+                        (rng.standard_normal(20000) / math.sqrt(d)).astype(np.float32), np.float32([-1, 1, 0])]).astype(np.float32)
+    x = v * scale + offset
+    for nudge in (0.0, -0.2, 0.2):
+        cell = np.clip(np.trunc(x.astype(np.float64) + nudge), 0, cells - 1).astype(np.int64)
+        np.testing.assert_array_equal(index[cell] + (v >= boundary[cell]), np.searchsorted(bd, v, side="right"))
