@@ -449,6 +449,45 @@ def reconstruct(index: ListIndex, l: int):
     return index.centroids[l][None, :] + index.gamma16[l].astype(np.float64)[:, None] * (recon @ index.Pi)
 
 
+def stratified_positions(sizes, sample_n: int):
+    """Which stored vectors a refresh samples: list l contributes round(sample_n * n_l / N) of its n_l
+    vectors (at least one when it is not empty, never more than it holds), evenly spaced in storage
+    order: position floor(t * n_l / s_l), t = 0 .. s_l - 1.  Returns a list of position arrays."""
+    sizes = np.asarray(sizes, dtype=np.int64)
+    total = int(sizes.sum())
+    out = []
+    for n_l in sizes:
+        n_l = int(n_l)
+        if n_l == 0 or total == 0:
+            out.append(np.empty(0, np.int64))
+            continue
+        s_l = int(min(n_l, max(1, (2 * sample_n * n_l + total) // (2 * total))))   # round half up
+        out.append((np.arange(s_l, dtype=np.int64) * n_l) // s_l)
+    return out
+
+
+def refresh_coarse(index: ListIndex, sample_n: int, niter: int, init_idx=None, new_centroids=None):
+    """Adaptive coarse refresh (Section "Adaptive coarse refresh", Algorithm and Refresh
+    self-containedness): sample the stored vectors stratified across partitions, reconstruct them as
+    x^ = c~_old + gamma * Pi^T rho^, re-cluster the sample, then re-assign and re-encode every stored
+    vector from its reconstruction against the new centroids with the unchanged (Pi, C_b).
+
+    init_idx: rows of the sample used as initial k-means centres.  new_centroids: skip the clustering
+    and use these (lets a test give both implementations the same partition).
+    Returns (new index, reconstructions [N, d] in storage order, labels [N], sample [S, d])."""
+    L = len(index.ids)
+    recon = [reconstruct(index, l) if len(index.ids[l]) else np.empty((0, index.centroids.shape[1])) for l in range(L)]
+    pos = stratified_positions([len(index.ids[l]) for l in range(L)], sample_n)
+    sample = np.concatenate([recon[l][pos[l]] for l in range(L)], axis=0)
+    if new_centroids is None:
+        new_centroids, _ = train_coarse(sample, L, niter, init_idx)
+    xh = np.concatenate(recon, axis=0)
+    labels = np.concatenate([np.asarray(index.ids[l], dtype=np.int64) for l in range(L)])
+    fresh = ListIndex(new_centroids, index.Pi, index.c, index.tau)
+    fresh.add(xh, labels)
+    return fresh, xh, labels, sample
+
+
 def tq_reconstruct(V, Pi, c, tau):
     """v^ = Pi^T C_b(Pi v) for rows v (flat TQ; Theorem 1 setup)."""
     U = np.asarray(V, dtype=np.float64) @ np.asarray(Pi, dtype=np.float64).T

@@ -306,3 +306,67 @@ def test_pins_catch_planted_mistakes(mistake):
     same = all([r[1] for r in row] == list(ids[qi]) for qi, row in enumerate(ref))
     close = all(np.allclose([r[0] for r in row], sc[qi], atol=1e-6) for qi, row in enumerate(ref))
     assert not (same and close)
+
+
+# ---------------------------------------------------------------- adaptive coarse refresh
+
+
+def test_stratified_positions_cover_lists_proportionally():
+    sizes = [0, 1, 7, 100, 1000, 3]
+    pos = orc.stratified_positions(sizes, 111)
+    assert [len(p) for p in pos] == [0, 1, 1, 10, 100, 1]          # round(111 * n_l / 1111), at least 1 when non-empty
+    for n_l, p in zip(sizes, pos):
+        assert np.all(np.diff(p) > 0) and (len(p) == 0 or (p[0] == 0 and p[-1] < n_l))
+    np.testing.assert_array_equal(pos[3], np.arange(10) * 10)        # evenly spaced in storage order
+    # asking for more than is stored takes everything once
+    assert [len(p) for p in orc.stratified_positions([5, 0, 2], 1000)] == [5, 0, 2]
+
+
+def test_refresh_recovers_a_stale_partition_without_raw_vectors():
+    """Index built on centroids that ignore the data (random directions): the refresh re-clusters the
+    reconstructions and re-encodes everything from them.  Labels survive as a permutation, the
+    residuals shrink (E gamma^2 = 2(1 - E<x~, c~>)) and recall against the raw vectors' exact
+    neighbours goes up; the rotation and the codebook are untouched."""
+    w = synth.scaled(synth.config_tiny(), 6000, 60)
+    X, Q = synth.database(w, 0, 6000), synth.queries(w, 60)
+    d, L, b = w.d, 32, 4
+    Pi = orc.haar_rotation_from_gaussian(synth.gaussian_matrix(0, d))
+    c, tau = orc.lloyd_max_codebook(b, d)
+    stale = synth.random_unit_vectors(3, L, d)
+    idx = orc.ListIndex(stale, Pi, c, tau)
+    labels = np.arange(6000, dtype=np.int64) * 7 + 3
+    idx.add(X, labels)
+    _, truth = orc.exact_topk(X, Q, 10)
+    truth = labels[truth]
+    _, ids0, _, _ = orc.search(idx, Q, 4, 10)
+    rec0 = orc.recall_at_k(ids0, truth)
+    g0 = np.mean(np.concatenate([g.astype(np.float64) ** 2 for g in idx.gamma16]))
+
+    fresh, xh, lab, sample = orc.refresh_coarse(idx, 2000, 8, synth.kmeans_init_indices(0, 2000, L))
+    assert fresh.Pi is idx.Pi and fresh.c is idx.c and fresh.tau is idx.tau
+    assert 1990 <= len(sample) <= 2010 and xh.shape == (6000, d)
+    np.testing.assert_array_equal(np.sort(np.concatenate([np.asarray(i) for i in fresh.ids])), np.sort(labels))
+    np.testing.assert_array_equal(np.sort(lab), np.sort(labels))
+    # reconstructions are close to the unit vectors they stand for
+    Xn = orc.normalize_rows(X)
+    err = np.linalg.norm(xh - Xn[(lab - 3) // 7], axis=1)
+    assert np.mean(err ** 2) < 0.03
+    g1 = np.mean(np.concatenate([g.astype(np.float64) ** 2 for g in fresh.gamma16 if len(g)]))
+    _, ids1, _, _ = orc.search(fresh, Q, 4, 10)
+    rec1 = orc.recall_at_k(ids1, truth)
+    print(f"stale: recall {rec0:.3f}, E gamma^2 {g0:.3f}; refreshed: recall {rec1:.3f}, E gamma^2 {g1:.3f}")
+    assert g1 < 0.5 * g0
+    assert rec1 > rec0 + 0.15
+
+
+def test_refresh_with_the_same_centroids_keeps_almost_every_assignment():
+    w = synth.scaled(synth.config_tiny(), 3000, 10)
+    X = synth.database(w, 0, 3000)
+    C, _ = orc.train_coarse(X, 16, 5, synth.kmeans_init_indices(0, 3000, 16))
+    Pi = orc.haar_rotation_from_gaussian(synth.gaussian_matrix(0, w.d))
+    c, tau = orc.lloyd_max_codebook(4, w.d)
+    idx = orc.ListIndex(C, Pi, c, tau)
+    idx.add(X)
+    fresh, _, _, _ = orc.refresh_coarse(idx, 500, 0, new_centroids=C)
+    moved = sum(len(set(np.asarray(fresh.ids[l]).tolist()) - set(np.asarray(idx.ids[l]).tolist())) for l in range(16))
+    assert moved < 0.03 * 3000
