@@ -152,6 +152,30 @@ ivftq_status ivftq_encode_only(ivftq_index* index, const float* x_dev, int64_t n
                                int32_t* assign_dev, uint8_t* codes_dev, uint16_t* gamma_dev,
                                void* stream);
 
+/* ---- adaptive coarse refresh (Section "Adaptive coarse refresh") ------------------------ */
+
+/* Reconstructions of every stored vector, x^ = c~_l + |r| * Pi^T C[code] (Refresh
+ * self-containedness), in list order (list 0 first, storage order inside a list).  x_out_dev: device,
+ * ivftq_ntotal() x d floats; ids_out_dev: device, ivftq_ntotal() int64 labels in the same order, or
+ * NULL.  Synchronises. */
+ivftq_status ivftq_reconstruct(ivftq_index* index, float* x_out_dev, int64_t* ids_out_dev, void* stream);
+
+/* Replace the coarse centroids (host, nlist x d, unit rows) and re-assign and re-encode every stored
+ * vector from its reconstruction against them; rotation and codebook stay as they are.  Labels are
+ * kept; list order afterwards is the old list order filtered by new cell.  Allocates ntotal x d floats
+ * of device memory for the duration of the call.  If the re-append fails (out of memory) the index
+ * is left empty.  Synchronises. */
+ivftq_status ivftq_reencode(ivftq_index* index, const float* centroids_host, void* stream);
+
+/* The whole refresh (Algorithm of that section): reconstruct everything, take a sample stratified
+ * across the lists (list l gives round(sample_n * n_l / ntotal) of its vectors, at least one, evenly
+ * spaced in storage order), run ivftq_train_coarse on the sample (niter, init_rows_host -- rows of the
+ * sample -- or seed, inertia_out as there), then re-encode as ivftq_reencode does.  If the training
+ * fails the index is unchanged. */
+ivftq_status ivftq_refresh_coarse(ivftq_index* index, int64_t sample_n, int niter,
+                                  const int64_t* init_rows_host, uint64_t seed, double* inertia_out,
+                                  void* stream);
+
 /* ---- search (Section "Architecture", Search) ------------------------------------------- */
 
 /* For each of the nq rows of q_dev (device, nq x d): scores_dev[nq x k] (float32, descending)

@@ -41,6 +41,10 @@ _SIGNATURES = {
                                     C.c_void_p]),
     "ivftq_encode_only": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p,
                                     C.c_void_p]),
+    "ivftq_reconstruct": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "ivftq_reencode": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
+    "ivftq_refresh_coarse": (C.c_int, [C.c_void_p, C.c_int64, C.c_int, C.c_void_p, C.c_uint64, C.POINTER(C.c_double),
+                                       C.c_void_p]),
     "ivftq_search": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
                                C.c_void_p]),
     "ivftq_coarse_probe": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_int, C.c_void_p, C.c_void_p,
@@ -291,6 +295,32 @@ class Index:
         return assign, codes, gamma
 
     # search
+    def reconstruct(self, stream=None):
+        """(x^ [ntotal, d] f32, labels [ntotal] i64) on the device, list order"""
+        import torch
+        n = self.ntotal()
+        dev = torch.device("cuda", torch.cuda.current_device())
+        x = torch.empty((n, self.d), dtype=torch.float32, device=dev)
+        ids = torch.empty((n,), dtype=torch.int64, device=dev)
+        _check(self._lib.ivftq_reconstruct(self._h, _dev_ptr(x), _dev_ptr(ids), _stream_ptr(stream)))
+        return x, ids
+
+    def reencode(self, centroids: np.ndarray, stream=None):
+        c = np.ascontiguousarray(centroids, dtype=np.float32)
+        assert c.shape == (self.nlist, self.d)
+        _check(self._lib.ivftq_reencode(self._h, _np_ptr(c), _stream_ptr(stream)))
+
+    def refresh_coarse(self, sample_n: int, niter: int, init_rows: np.ndarray | None = None, seed: int = 0,
+                       stream=None) -> float:
+        inertia = C.c_double(0)
+        rows = None
+        if init_rows is not None:
+            rows = np.ascontiguousarray(init_rows, dtype=np.int64)
+            assert rows.shape == (self.nlist,)
+        _check(self._lib.ivftq_refresh_coarse(self._h, sample_n, niter, _np_ptr(rows) if rows is not None else None,
+                                              seed, C.byref(inertia), _stream_ptr(stream)))
+        return inertia.value
+
     def search(self, q, nprobe: int, k: int, out_scores=None, out_ids=None, stream=None):
         import torch
         nq = q.shape[0]

@@ -99,6 +99,7 @@ uint64_t splitmix(uint64_t& s) {
 struct ivftq_index {
     int d = 0, b = 0, nlist = 0, K = 0, dp = 0, lpad = 0, words = 0;   // b: bits stored per coordinate (Stage 1 + sign bit)
     int sign_bit = 0;
+    bool refreshing = false;   // set while ivftq_refresh_coarse re-trains the centroids of a non-empty index
     int q_cells = 0; float q_scale = 0.f, q_offset = 0.f;   // quantiser grid (host_math.h)
     bool has_coarse = false;
     std::vector<float> h_cent, h_pi, h_cb, h_tau;
@@ -587,7 +588,7 @@ ivftq_status ivftq_train_coarse(ivftq_index* ix, const float* x_dev, int64_t n, 
     if (!x_dev) return fail(IVFTQ_INVALID_ARG, "x_dev is NULL");
     if (n < ix->nlist) return fail(IVFTQ_INVALID_ARG, "need at least nlist=%d training rows, got %lld", ix->nlist, (long long)n);
     if (niter < 0) return fail(IVFTQ_INVALID_ARG, "niter=%d is negative", niter);
-    if (ix->ntotal > 0) return fail(IVFTQ_BAD_STATE, "centroids cannot change once vectors are stored");
+    if (ix->ntotal > 0 && !ix->refreshing) return fail(IVFTQ_BAD_STATE, "centroids cannot change once vectors are stored");
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int L = ix->nlist, d = ix->d, pitch = ix->dp;
 
@@ -837,6 +838,114 @@ ivftq_status ivftq_add_encoded(ivftq_index* ix, int64_t n, const int32_t* assign
 }
 
 // ---------------------------------------------------------------------------------------------
+
+// ---- adaptive coarse refresh (Section "Adaptive coarse refresh") ----------------------------------
+
+namespace {
+
+struct ScopedBuf {
+    DevBuf b;
+    ~ScopedBuf() { b.release(); }
+};
+
+// x_out[row] = reconstruction of the vector at list-order position row, ids_out its label
+ivftq_status reconstruct_all(ivftq_index* ix, float* x_out, int64_t* ids_out, hipStream_t st) {
+    const int L = ix->nlist;
+    std::vector<int64_t> off(L);
+    int64_t run = 0;
+    int max_list = 0;
+    for (int l = 0; l < L; ++l) { off[l] = run; run += ix->h_size[l]; max_list = std::max(max_list, (int)ix->h_size[l]); }
+    HIP_TRY(ix->w_base.ensure((size_t)2 * L * sizeof(int64_t)));
+    HIP_TRY(hipMemcpyAsync(ix->w_base.p, off.data(), (size_t)L * sizeof(int64_t), hipMemcpyHostToDevice, st));
+    HIP_TRY(launch_reconstruct(ix->store(), L, max_list, ix->cent.as<float>(), ix->dp, ix->pi.as<float>(), ix->dp,
+                               ix->cb.as<float>(), ix->d, ix->b, ix->w_base.as<int64_t>(), x_out, ids_out, st));
+    HIP_TRY(hipStreamSynchronize(st));      // `off` is pageable host memory
+    return IVFTQ_OK;
+}
+
+// Empties the lists and appends the n rows again (against whatever centroids the index now has).
+ivftq_status readd_all(ivftq_index* ix, const float* x, const int64_t* ids, int64_t n, hipStream_t st) {
+    std::fill(ix->h_size.begin(), ix->h_size.end(), 0);
+    HIP_TRY(launch_fill_u32(ix->d_size.as<uint32_t>(), ix->nlist, 0u, st));
+    ix->ntotal = 0;
+    ivftq_status s = ivftq_encode_add(ix, x, n, ids, st);
+    if (s == IVFTQ_OK) HIP_TRY(hipStreamSynchronize(st));   // x and ids are about to be freed by the caller
+    return s;
+}
+
+}  // namespace
+
+ivftq_status ivftq_reconstruct(ivftq_index* ix, float* x_out_dev, int64_t* ids_out_dev, void* stream) {
+    if (check_index(ix)) return IVFTQ_INVALID_ARG;
+    if (!x_out_dev) return fail(IVFTQ_INVALID_ARG, "x_out_dev is NULL");
+    if (ix->ntotal == 0) return IVFTQ_OK;
+    return reconstruct_all(ix, x_out_dev, ids_out_dev, static_cast<hipStream_t>(stream));
+}
+
+ivftq_status ivftq_reencode(ivftq_index* ix, const float* centroids_host, void* stream) {
+    if (check_index(ix)) return IVFTQ_INVALID_ARG;
+    if (!centroids_host) return fail(IVFTQ_INVALID_ARG, "centroids_host is NULL");
+    if (!ix->has_coarse) return fail(IVFTQ_BAD_STATE, "no coarse centroids yet");
+    for (size_t i = 0; i < (size_t)ix->nlist * ix->d; ++i)
+        if (!std::isfinite(centroids_host[i])) return fail(IVFTQ_INVALID_ARG, "non-finite centroid value");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int64_t n = ix->ntotal;
+    ScopedBuf xh, lab;
+    if (n > 0) {
+        HIP_TRY(xh.b.ensure((size_t)n * ix->d * sizeof(float)));
+        HIP_TRY(lab.b.ensure((size_t)n * sizeof(int64_t)));
+        ivftq_status s = reconstruct_all(ix, xh.b.as<float>(), lab.b.as<int64_t>(), st);
+        if (s != IVFTQ_OK) return s;
+    }
+    std::copy(centroids_host, centroids_host + (size_t)ix->nlist * ix->d, ix->h_cent.begin());
+    ivftq_status s = upload_coarse(ix);
+    if (s != IVFTQ_OK || n == 0) return s;
+    return readd_all(ix, xh.b.as<float>(), lab.b.as<int64_t>(), n, st);
+}
+
+ivftq_status ivftq_refresh_coarse(ivftq_index* ix, int64_t sample_n, int niter, const int64_t* init_rows_host,
+                                  uint64_t seed, double* inertia_out, void* stream) {
+    if (check_index(ix)) return IVFTQ_INVALID_ARG;
+    if (!ix->has_coarse || ix->ntotal == 0) return fail(IVFTQ_BAD_STATE, "nothing stored to refresh from");
+    if (sample_n < ix->nlist) return fail(IVFTQ_INVALID_ARG, "sample of %lld below nlist=%d", (long long)sample_n, ix->nlist);
+    if (niter < 0) return fail(IVFTQ_INVALID_ARG, "niter=%d is negative", niter);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int L = ix->nlist;
+    const int64_t n = ix->ntotal;
+    ScopedBuf xh, lab, sample, rows;
+    HIP_TRY(xh.b.ensure((size_t)n * ix->d * sizeof(float)));
+    HIP_TRY(lab.b.ensure((size_t)n * sizeof(int64_t)));
+    ivftq_status s = reconstruct_all(ix, xh.b.as<float>(), lab.b.as<int64_t>(), st);
+    if (s != IVFTQ_OK) return s;
+    // stratified sample: list l gives round(sample_n * n_l / n) of its vectors (at least one, at most
+    // all), evenly spaced in storage order
+    std::vector<int64_t> pick;
+    int64_t first = 0;
+    for (int l = 0; l < L; ++l) {
+        const int64_t n_l = ix->h_size[l];
+        if (n_l > 0) {
+            const int64_t s_l = std::min<int64_t>(n_l, std::max<int64_t>(1, (2 * sample_n * n_l + n) / (2 * n)));
+            for (int64_t t = 0; t < s_l; ++t) pick.push_back(first + (t * n_l) / s_l);
+        }
+        first += n_l;
+    }
+    if ((int64_t)pick.size() < L) return fail(IVFTQ_INVALID_ARG, "the sample holds %lld vectors, fewer than nlist=%d", (long long)pick.size(), L);
+    HIP_TRY(rows.b.ensure(pick.size() * sizeof(int64_t)));
+    HIP_TRY(sample.b.ensure(pick.size() * ix->d * sizeof(float)));
+    HIP_TRY(hipMemcpyAsync(rows.b.p, pick.data(), pick.size() * sizeof(int64_t), hipMemcpyHostToDevice, st));
+    HIP_TRY(launch_gather_rows(xh.b.as<float>(), ix->d, rows.b.as<int64_t>(), (int64_t)pick.size(), sample.b.as<float>(), st));
+    HIP_TRY(hipStreamSynchronize(st));
+    const std::vector<float> old_cent = ix->h_cent;
+    ix->refreshing = true;
+    s = ivftq_train_coarse(ix, sample.b.as<float>(), (int64_t)pick.size(), niter, init_rows_host, seed, inertia_out, st);
+    ix->refreshing = false;
+    if (s != IVFTQ_OK) {                      // keep the index as it was: old centroids, lists untouched
+        ix->h_cent = old_cent;
+        (void)upload_coarse(ix);
+        return s;
+    }
+    return readd_all(ix, xh.b.as<float>(), lab.b.as<int64_t>(), n, st);
+}
 
 namespace {
 

@@ -109,6 +109,14 @@ hipError_t launch_pack_scatter(const uint8_t* codes, const uint16_t* gamma, cons
 hipError_t launch_copy_lists(const ListStore& from, const ListStore& to, int L, hipStream_t st);
 hipError_t launch_fill_u32(uint32_t* p, int64_t n, uint32_t v, hipStream_t st);
 
+// x_out[out_off[l] + v] = cent_l + gamma * Pi^T C[code] for vector v of list l (rows of d floats, list
+// order), labels_out (may be null) the stored labels in the same order.  pi: fp32 [.][pi_pitch].
+hipError_t launch_reconstruct(const ListStore& store, int L, int max_list, const float* cent, int cent_pitch,
+                              const float* pi, int pi_pitch, const float* cb, int d, int b, const int64_t* out_off,
+                              float* x_out, int64_t* labels_out, hipStream_t st);
+// dst[t] = src[idx[t]], rows of d floats
+hipError_t launch_gather_rows(const float* src, int d, const int64_t* idx, int64_t count, float* dst, hipStream_t st);
+
 // ---- k-means pieces ---------------------------------------------------------------------------
 
 // sums[l][j] += x~_ij, counts[l] += 1 over rows with assign l (atomics); obj += best terms

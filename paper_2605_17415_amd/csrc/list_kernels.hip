@@ -7,6 +7,8 @@
 // on scheduling.  That is a stable counting sort by cell number, done in three small kernels:
 // per-segment histograms, a column-wise running sum over segments, and an in-order rank inside
 // each segment by one wavefront.
+#include <hip/hip_fp16.h>
+
 #include "kernels.h"
 
 namespace ivftq {
@@ -195,6 +197,74 @@ __global__ __launch_bounds__(64) void k_copy_rows_normalised(const float* __rest
     for (int j = lane; j < d; j += 64) cent[(int64_t)l * pitch + j] = nrm > 0.f ? x[row * d + j] / nrm : 0.f;
 }
 
+// Reconstruction of stored vectors (Section "Adaptive coarse refresh", Refresh self-containedness):
+// x^ = c~_l + gamma * Pi^T C[code].  A workgroup takes 32 consecutive vectors of one list: their
+// de-quantised coordinates go to LDS as rho[k][v], then thread j accumulates output coordinate j of
+// all 32 vectors, x^_j = sum_k Pi[k][j] rho_k (row k of Pi is read coalesced across the threads, the
+// 32 values of rho[k][.] are LDS broadcasts), and rows are written whole.  Rows come out in list
+// order: list l starts at row out_off[l]; labels_out gets the stored labels in the same order.
+__global__ __launch_bounds__(256) void k_reconstruct(ListStore store, const float* __restrict__ cent, int cent_pitch,
+                                                     const float* __restrict__ pi, int pi_pitch,
+                                                     const float* __restrict__ cb, int d, int b,
+                                                     const int64_t* __restrict__ out_off,
+                                                     float* __restrict__ x_out, int64_t* __restrict__ labels_out) {
+    extern __shared__ float rho[];                     // [d][32], then 32 norms
+    float* gam = rho + (size_t)d * 32;
+    const int l = blockIdx.y;
+    const int n_l = store.list_size[l];
+    const int v0 = blockIdx.x * 32;
+    if (v0 >= n_l) return;
+    const int tid = threadIdx.x;
+    const int64_t base_slot = store.list_off[l];
+    const int words = store.words;
+    const uint32_t mask = (1u << b) - 1u;
+    for (int e = tid; e < 32 * d; e += 256) {
+        const int v = e & 31, k = e >> 5;
+        float val = 0.f;
+        if (v0 + v < n_l) {
+            const int64_t slot = base_slot + v0 + v;
+            const uint32_t* wp = store.codes + (slot >> 6) * (int64_t)words * 64 + (slot & 63);
+            const int bit = k * b, w = bit >> 5, sh = bit & 31;
+            uint32_t code = wp[(int64_t)w * 64] >> sh;
+            if (sh + b > 32) code |= wp[(int64_t)(w + 1) * 64] << (32 - sh);
+            val = cb[code & mask];
+        }
+        rho[k * 32 + v] = val;
+    }
+    if (tid < 32) {
+        const bool in = v0 + tid < n_l;
+        gam[tid] = in ? __half2float(__ushort_as_half(store.gamma[base_slot + v0 + tid])) : 0.f;
+        if (in && labels_out) labels_out[out_off[l] + v0 + tid] = store.ids[base_slot + v0 + tid];
+    }
+    __syncthreads();
+    const int j = tid;
+    if (j >= d) return;
+    float acc[32];
+#pragma unroll
+    for (int v = 0; v < 32; ++v) acc[v] = 0.f;
+    for (int k = 0; k < d; ++k) {
+        const float p = pi[(int64_t)k * pi_pitch + j];
+        const float4* r4 = reinterpret_cast<const float4*>(rho + k * 32);
+#pragma unroll
+        for (int g = 0; g < 8; ++g) {
+            const float4 r = r4[g];
+            acc[4 * g] = fmaf(p, r.x, acc[4 * g]); acc[4 * g + 1] = fmaf(p, r.y, acc[4 * g + 1]);
+            acc[4 * g + 2] = fmaf(p, r.z, acc[4 * g + 2]); acc[4 * g + 3] = fmaf(p, r.w, acc[4 * g + 3]);
+        }
+    }
+    const float c = cent[(int64_t)l * cent_pitch + j];
+#pragma unroll
+    for (int v = 0; v < 32; ++v)
+        if (v0 + v < n_l) x_out[(out_off[l] + v0 + v) * (int64_t)d + j] = fmaf(gam[v], acc[v], c);
+}
+
+// dst[t] = src[idx[t]] for rows of d floats
+__global__ __launch_bounds__(64) void k_gather_rows(const float* __restrict__ src, int d,
+                                                    const int64_t* __restrict__ idx, float* __restrict__ dst) {
+    const int64_t row = idx[blockIdx.x];
+    for (int j = threadIdx.x; j < d; j += 64) dst[(int64_t)blockIdx.x * d + j] = src[row * d + j];
+}
+
 __global__ __launch_bounds__(64) void k_normalise_centroids(float* __restrict__ cent, int pitch,
                                                             float* __restrict__ bias, int d) {
     const int l = blockIdx.x, lane = threadIdx.x;
@@ -282,6 +352,22 @@ hipError_t launch_copy_rows_normalised(const float* x, int d, const int64_t* src
                                        int count, float* cent, int pitch, hipStream_t st) {
     if (count <= 0) return hipSuccess;
     hipLaunchKernelGGL(k_copy_rows_normalised, dim3(count), dim3(64), 0, st, x, d, src_row, dst, cent, pitch);
+    return hipGetLastError();
+}
+
+hipError_t launch_reconstruct(const ListStore& store, int L, int max_list, const float* cent, int cent_pitch,
+                              const float* pi, int pi_pitch, const float* cb, int d, int b, const int64_t* out_off,
+                              float* x_out, int64_t* labels_out, hipStream_t st) {
+    if (max_list <= 0) return hipSuccess;
+    const size_t lds = ((size_t)d * 32 + 32) * sizeof(float);
+    hipLaunchKernelGGL(k_reconstruct, dim3((unsigned)((max_list + 31) / 32), (unsigned)L), dim3(256), lds, st, store, cent,
+                       cent_pitch, pi, pi_pitch, cb, d, b, out_off, x_out, labels_out);
+    return hipGetLastError();
+}
+
+hipError_t launch_gather_rows(const float* src, int d, const int64_t* idx, int64_t count, float* dst, hipStream_t st) {
+    if (count <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_gather_rows, dim3((unsigned)count), dim3(64), 0, st, src, d, idx, dst);
     return hipGetLastError();
 }
 

@@ -9,7 +9,9 @@ Agreement is defined as:
     is max(1e-5, 4e-7/gamma): it only exceeds 1e-5 for gamma < 0.04, i.e. a vector that nearly
     coincides with its centroid, whose residual direction is rounding noise in any precision;
   * the float16 norm is bit-exact unless the double-precision norm sits within 2e-6 (relative) of
-    the midpoint between two neighbouring float16 values, where float32 and float64 may round apart;
+    the midpoint between two neighbouring float16 values, where float32 and float64 may round apart,
+    or the norm itself is at the float32 noise floor (a vector that coincides with its centroid: the
+    norm is then rounding noise of about 1e-7 in any precision) and the two agree to 4e-7 absolute;
   * estimated inner products agree within 1e-4 relative (plus 1e-6 absolute);
   * top-k label sets are identical up to ties within that tolerance.
 """
@@ -53,6 +55,8 @@ def compare_encode(enc, g_assign, g_codes, g_gamma16):
         bad = np.flatnonzero((g.view(np.uint16) != enc["gamma16"].view(np.uint16)) & same)
         for i in bad:
             lo, hi = sorted((float(g[i]), float(enc["gamma16"][i])))
+            if abs(float(g[i]) - enc["gamma"][i]) <= NOISE_FLOOR:
+                continue                                   # a norm at the rounding-noise floor
             assert abs(int(g[i].view(np.uint16)) - int(enc["gamma16"][i].view(np.uint16))) == 1, \
                 f"float16 norm of row {i} off by more than one step"
             mid = 0.5 * (lo + hi)
