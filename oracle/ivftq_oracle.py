@@ -514,6 +514,27 @@ def exact_topk(X, Q, k: int, chunk: int = 256):
     return sc, ids
 
 
+def rerank(X, Q, cand_ids, k: int):
+    """Re-ranking on raw vectors (Section "Architecture", Search: optional; "Bits vs. re-ranking"):
+    the candidates' exact inner products <q~, x~> replace the estimates and the k best are kept
+    (ties -> smaller id).  cand_ids: [nq, r] row numbers of X, -1 = no candidate."""
+    X = np.asarray(X)
+    Qn = normalize_rows(Q)
+    cand_ids = np.asarray(cand_ids, dtype=np.int64)
+    nq = cand_ids.shape[0]
+    scores = np.full((nq, k), -np.inf)
+    ids = np.full((nq, k), -1, dtype=np.int64)
+    for qi in range(nq):
+        c = np.unique(cand_ids[qi][cand_ids[qi] >= 0])
+        if len(c) == 0:
+            continue
+        s = normalize_rows(X[c]) @ Qn[qi]
+        top = np.lexsort((c, -s))[:k]
+        scores[qi, :len(top)] = s[top]
+        ids[qi, :len(top)] = c[top]
+    return scores, ids
+
+
 def recall_at_k(found_ids, true_ids) -> float:
     k = true_ids.shape[1]
     hits = 0
