@@ -152,6 +152,17 @@ ivftq_status ivftq_encode_only(ivftq_index* index, const float* x_dev, int64_t n
                                int32_t* assign_dev, uint8_t* codes_dev, uint16_t* gamma_dev,
                                void* stream);
 
+/* Re-ranking on raw vectors (same section: optional).  For each of the nq queries the r candidate
+ * labels cand_ids_dev[q*r ..] (e.g. the ids ivftq_search returned for k = r; -1 and labels outside
+ * [0, n_rows) are skipped, repeats count once) are scored exactly, <q~, x~> from the raw rows
+ * x_dev[label*d ..] normalised on the fly, and the k best are written in descending order, ties by
+ * smaller label, missing results as (-inf, -1).  The library keeps no raw vectors: x_dev is the
+ * caller's n_rows x d matrix addressed by label.  All pointers device; 1 <= k <= r <= 2048;
+ * asynchronous on the stream. */
+ivftq_status ivftq_rerank(int d, const float* q_dev, int64_t nq, const float* x_dev, int64_t n_rows,
+                          const int64_t* cand_ids_dev, int r, int k, float* scores_dev,
+                          int64_t* ids_dev, void* stream);
+
 /* ---- adaptive coarse refresh (Section "Adaptive coarse refresh") ------------------------ */
 
 /* Reconstructions of every stored vector, x^ = c~_l + |r| * Pi^T C[code] (Refresh

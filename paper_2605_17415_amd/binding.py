@@ -41,6 +41,8 @@ _SIGNATURES = {
                                     C.c_void_p]),
     "ivftq_encode_only": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p,
                                     C.c_void_p]),
+    "ivftq_rerank": (C.c_int, [C.c_int, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int, C.c_int,
+                               C.c_void_p, C.c_void_p, C.c_void_p]),
     "ivftq_reconstruct": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "ivftq_reencode": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
     "ivftq_refresh_coarse": (C.c_int, [C.c_void_p, C.c_int64, C.c_int, C.c_void_p, C.c_uint64, C.POINTER(C.c_double),
@@ -180,6 +182,19 @@ def ivftq_measure_mfma_rate(random_operands: bool = True) -> float:
     out = C.c_double(0)
     _check(load_library().ivftq_measure_mfma_rate(1 if random_operands else 0, C.byref(out)))
     return out.value
+
+
+def ivftq_rerank(q, x, cand_ids, k: int, stream=None):
+    """Exact re-ranking of candidate labels against raw rows x (all torch tensors on the device)."""
+    import torch
+    nq, d = q.shape
+    r = cand_ids.shape[1]
+    scores = torch.empty((nq, k), dtype=torch.float32, device=q.device)
+    ids = torch.empty((nq, k), dtype=torch.int64, device=q.device)
+    _check(load_library().ivftq_rerank(d, _dev_ptr(q, torch.float32, "q"), nq, _dev_ptr(x, torch.float32, "x"), x.shape[0],
+                                       _dev_ptr(cand_ids, torch.int64, "cand_ids"), r, k, _dev_ptr(scores), _dev_ptr(ids),
+                                       _stream_ptr(stream)))
+    return scores, ids
 
 
 def ivftq_version() -> str:

@@ -974,6 +974,19 @@ ivftq_status coarse_and_probe(ivftq_index* ix, const float* q, int64_t count, in
 
 }  // namespace
 
+ivftq_status ivftq_rerank(int d, const float* q_dev, int64_t nq, const float* x_dev, int64_t n_rows,
+                          const int64_t* cand_ids_dev, int r, int k, float* scores_dev, int64_t* ids_dev, void* stream) {
+    if (d < 1 || d > kMaxD) return fail(IVFTQ_INVALID_ARG, "d=%d outside [1, %d]", d, kMaxD);
+    if (nq < 0 || n_rows < 0) return fail(IVFTQ_INVALID_ARG, "negative count");
+    if (r < 1 || r > kMaxK) return fail(IVFTQ_INVALID_ARG, "r=%d outside [1, %d]", r, kMaxK);
+    if (k < 1 || k > r) return fail(IVFTQ_INVALID_ARG, "k=%d outside [1, r=%d]", k, r);
+    if (nq == 0) return IVFTQ_OK;
+    if (!q_dev || !x_dev || !cand_ids_dev || !scores_dev || !ids_dev) return fail(IVFTQ_INVALID_ARG, "pointer is NULL");
+    RerankArgs a{q_dev, x_dev, n_rows, d, cand_ids_dev, r, k, scores_dev, ids_dev};
+    HIP_TRY(launch_rerank(a, nq, static_cast<hipStream_t>(stream)));
+    return IVFTQ_OK;
+}
+
 ivftq_status ivftq_coarse_probe(ivftq_index* ix, const float* q_dev, int64_t nq, int nprobe,
                                 int32_t* probe_dev, float* coarse_dev, void* stream) {
     ivftq_status s = check_query_args(ix, q_dev, nq, nprobe);

@@ -165,6 +165,15 @@ struct SelectArgs {
 };
 hipError_t launch_select(int mode, const SelectArgs& a, hipStream_t st);
 
+// Exact re-ranking: out = the k candidates of each query with the largest <q~, x~> computed from raw
+// rows (x: n_rows x d, addressed by label), ordered by (score desc, label asc), repeats dropped.
+struct RerankArgs {
+    const float* q; const float* x; int64_t n_rows; int d;
+    const int64_t* cand; int r; int k;
+    float* out_scores; int64_t* out_ids;
+};
+hipError_t launch_rerank(const RerankArgs& a, int64_t nq, hipStream_t st);
+
 // ---- query-batched scan ------------------------------------------------------------------------
 
 // Queries one workgroup of the batched scan takes per tile for this (d, b); 0 = shape not covered

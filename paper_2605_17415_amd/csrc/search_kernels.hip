@@ -451,7 +451,96 @@ __global__ __launch_bounds__(256) void k_select_small(SelectArgs a) {
     }
 }
 
+// ---- re-ranking on raw vectors (Section "Architecture", Search: optional) -----------------------
+//
+// One workgroup per query: each wavefront takes candidates in turn and computes <q, x> / (|q| |x|)
+// from the raw rows, then the workgroup sorts (score desc, label asc) in LDS and emits the k best,
+// dropping repeated labels.
+__global__ __launch_bounds__(256) void k_rerank(RerankArgs a) {
+    extern __shared__ unsigned char smem[];
+    int size = 1;
+    while (size < a.r) size <<= 1;
+    uint32_t* s_key = reinterpret_cast<uint32_t*>(smem);
+    float* s_val = reinterpret_cast<float*>(s_key + size);
+    int64_t* s_lab = reinterpret_cast<int64_t*>(s_val + size);
+    const int64_t q = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const float* qv = a.q + q * a.d;
+    float qr[4];
+    float qq = 0.f;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const int j = lane + 64 * e;
+        qr[e] = j < a.d ? qv[j] : 0.f;
+        qq += qr[e] * qr[e];
+    }
+    for (int o = 32; o > 0; o >>= 1) qq += __shfl_xor(qq, o);
+    for (int c = wave; c < size; c += 4) {
+        const int64_t id = c < a.r ? a.cand[q * a.r + c] : -1;
+        float xy = 0.f, xx = 0.f;
+        if (id >= 0 && id < a.n_rows) {
+            const float* xv = a.x + id * a.d;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int j = lane + 64 * e;
+                const float v = j < a.d ? xv[j] : 0.f;
+                xy += v * qr[e];
+                xx += v * v;
+            }
+        }
+        for (int o = 32; o > 0; o >>= 1) { xy += __shfl_xor(xy, o); xx += __shfl_xor(xx, o); }
+        if (lane == 0) {
+            const bool ok = id >= 0 && id < a.n_rows && xx > 0.f && qq > 0.f;
+            const float sc = ok ? xy / sqrtf(xx * qq) : -__builtin_inff();
+            s_key[c] = (ok && sc == sc) ? order_key(sc) : 0u;
+            s_val[c] = sc;
+            s_lab[c] = ok ? id : INT64_MAX;
+        }
+    }
+    __syncthreads();
+    for (int sz = 2; sz <= size; sz <<= 1) {
+        for (int stride = sz >> 1; stride > 0; stride >>= 1) {
+            for (int i = tid; i < size / 2; i += 256) {
+                const int lo_i = 2 * i - (i & (stride - 1));
+                const int hi_i = lo_i + stride;
+                const bool up = ((lo_i & sz) == 0);
+                const uint32_t k0 = s_key[lo_i], k1 = s_key[hi_i];
+                const int64_t l0 = s_lab[lo_i], l1 = s_lab[hi_i];
+                const bool first_before = (k0 > k1) || (k0 == k1 && l0 <= l1);
+                if (first_before != up) {
+                    s_key[lo_i] = k1; s_key[hi_i] = k0;
+                    s_lab[lo_i] = l1; s_lab[hi_i] = l0;
+                    const float v0 = s_val[lo_i]; s_val[lo_i] = s_val[hi_i]; s_val[hi_i] = v0;
+                }
+            }
+            __syncthreads();
+        }
+    }
+    if (tid == 0) {
+        int out = 0;
+        int64_t prev = INT64_MAX;
+        for (int i = 0; i < size && out < a.k; ++i) {
+            if (s_key[i] == 0u) break;
+            if (s_lab[i] == prev) continue;                  // the same label again: equal score, adjacent
+            prev = s_lab[i];
+            a.out_scores[q * a.k + out] = s_val[i];
+            a.out_ids[q * a.k + out] = s_lab[i];
+            ++out;
+        }
+        for (; out < a.k; ++out) { a.out_scores[q * a.k + out] = -__builtin_inff(); a.out_ids[q * a.k + out] = -1; }
+    }
+}
+
 }  // namespace
+
+hipError_t launch_rerank(const RerankArgs& a, int64_t nq, hipStream_t st) {
+    if (nq <= 0) return hipSuccess;
+    int size = 1;
+    while (size < a.r) size <<= 1;
+    const size_t lds = (size_t)size * 16;
+    hipLaunchKernelGGL(k_rerank, dim3((unsigned)nq), dim3(256), lds, st, a);
+    return hipGetLastError();
+}
 
 hipError_t launch_cand_offsets(const int32_t* probe, int64_t nq, int np, const int32_t* list_size,
                                int32_t* cand_off, int k, int cap, int32_t* first, hipStream_t st) {
