@@ -234,6 +234,12 @@ ivftq_status ivftq_profile_read(ivftq_index* index, double* ms_out, int64_t* lau
 int ivftq_profile_kernel_count(void);
 const char* ivftq_profile_kernel_name(int id);
 
+/* Measurement aid: how many rows of the most recent ivftq_encode_add / ivftq_encode_only call on this
+ * index the screening pass of the coarse assignment (float16 leading parts only) left undecided and
+ * handed to the full-precision pass (Algorithm "Encode", coarse assignment step; the assignment is
+ * the full-precision one either way).  Waits for `stream`. */
+ivftq_status ivftq_assign_undecided(ivftq_index* index, int64_t* count_out, void* stream);
+
 /* Measurement aid: the rate (TFLOP/s, 2*32*32*16 flop per instruction) that a loop of nothing but
  * v_mfma_f32_32x32x16_f16, the instruction every contraction of this library uses, reaches on the
  * current device, two wavefronts per SIMD, operands in registers.  random_operands != 0: operands

@@ -61,6 +61,7 @@ _SIGNATURES = {
     "ivftq_profile_read": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
     "ivftq_profile_kernel_count": (C.c_int, []),
     "ivftq_profile_kernel_name": (C.c_char_p, [C.c_int]),
+    "ivftq_assign_undecided": (C.c_int, [C.c_void_p, C.POINTER(C.c_int64), C.c_void_p]),
     "ivftq_measure_mfma_rate": (C.c_int, [C.c_int, C.POINTER(C.c_double)]),
     "ivftq_last_error": (C.c_char_p, []),
     "ivftq_version": (C.c_char_p, []),
@@ -367,6 +368,12 @@ class Index:
         _check(self._lib.ivftq_profile_read(self._h, _np_ptr(ms), _np_ptr(launches)))
         return {self._lib.ivftq_profile_kernel_name(i).decode(): (float(ms[i]), int(launches[i]))
                 for i in range(cnt) if launches[i] > 0}
+
+    def assign_undecided(self, stream=None) -> int:
+        """Rows of the last encode call that the screening pass handed to the full-precision pass."""
+        out = C.c_int64(0)
+        _check(self._lib.ivftq_assign_undecided(self._h, C.byref(out), _stream_ptr(stream)))
+        return out.value
 
     # inspection
     def ntotal(self) -> int:

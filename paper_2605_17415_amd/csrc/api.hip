@@ -113,7 +113,7 @@ struct ivftq_index {
     PinnedBuf pin;   // [L u32 batch counts | 16 B flag | 2L i64 bases | L i32 sizes], see place_rows / commit_rows
     int64_t ntotal = 0;
     // workspace
-    DevBuf w_assign, w_slot, w_order, w_hist, w_count, w_base, w_flag, w_best;
+    DevBuf w_assign, w_slot, w_order, w_hist, w_count, w_base, w_flag, w_best, w_undecided;
     DevBuf w_S, w_probe, w_coarse, w_z, w_candoff, w_scores;
     DevBuf w_sums, w_counts, w_zero, w_rows, w_dst, w_obj;
     DevBuf w_zh, w_zl;
@@ -136,7 +136,7 @@ struct ivftq_index {
     ~ivftq_index() {
         for (ProfRec& r : prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
         for (DevBuf* bfr : {&cent, &cent_h, &cent_l, &pi_h, &pi_l, &bias, &pi, &cb, &q_grid, &codes, &gamma, &ids, &d_off, &d_size, &w_assign,
-                            &w_slot, &w_order, &w_hist, &w_count, &w_base, &w_flag, &w_best, &w_S, &w_probe, &w_coarse,
+                            &w_slot, &w_order, &w_hist, &w_count, &w_base, &w_flag, &w_best, &w_undecided, &w_S, &w_probe, &w_coarse,
                             &w_z, &w_candoff, &w_scores, &w_sums, &w_counts, &w_zero, &w_rows, &w_dst, &w_obj,
                             &w_first, &w_fscores, &w_fids, &w_pairs, &w_pairoff, &w_tileoff, &w_cscore,
                             &w_cslot, &w_ccnt, &w_gate, &w_zh, &w_zl})
@@ -753,7 +753,32 @@ ivftq_status commit_rows(ivftq_index* ix, const std::vector<int64_t>& need, int6
     return IVFTQ_OK;
 }
 
+// Coarse assignment of n rows (Algorithm "Encode", nearest centroid by inner product): screening pass
+// plus the exact pass over the rows it left undecided.  w_flag[0] = a row without a usable norm,
+// w_flag[1] = number of undecided rows.
+ivftq_status assign_rows(ivftq_index* ix, const float* x_dev, int64_t n, int32_t* assign, hipStream_t st) {
+    HIP_TRY(ix->w_undecided.ensure((size_t)n * sizeof(int32_t)));
+    HIP_TRY(launch_fill_u32(ix->w_flag.as<uint32_t>(), 2, 0u, st));
+    HIP_TRY(timed(ix, st, P_ASSIGN, [&] {
+        return launch_coarse_screened(x_dev, n, ix->d, ix->cent_h.as<uint16_t>(), ix->cent_l.as<uint16_t>(), ix->dp,
+                                      ix->nlist, ix->lpad, assign, ix->w_flag.as<int>(),
+                                      ix->w_undecided.as<int32_t>(), ix->w_flag.as<int>() + 1, st);
+    }));
+    return IVFTQ_OK;
+}
+
 }  // namespace
+
+ivftq_status ivftq_assign_undecided(ivftq_index* ix, int64_t* count_out, void* stream) {
+    if (check_index(ix)) return IVFTQ_INVALID_ARG;
+    if (!count_out) return fail(IVFTQ_INVALID_ARG, "count_out is NULL");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    int v = 0;
+    HIP_TRY(hipMemcpyAsync(&v, ix->w_flag.as<int>() + 1, sizeof(int), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    *count_out = v;
+    return IVFTQ_OK;
+}
 
 ivftq_status ivftq_encode_only(ivftq_index* ix, const float* x_dev, int64_t n, int32_t* assign_dev,
                                uint8_t* codes_dev, uint16_t* gamma_dev, void* stream) {
@@ -762,12 +787,11 @@ ivftq_status ivftq_encode_only(ivftq_index* ix, const float* x_dev, int64_t n, i
     if (n == 0) return IVFTQ_OK;
     if (!x_dev) return fail(IVFTQ_INVALID_ARG, "x_dev is NULL");
     if (!ix->has_coarse) return fail(IVFTQ_BAD_STATE, "coarse centroids not trained or set");
+    if (n > ((int64_t)1 << 31) - 1) return fail(IVFTQ_UNSUPPORTED, "more than 2^31-1 rows in one call");
     hipStream_t st = static_cast<hipStream_t>(stream);
     HIP_TRY(ix->w_assign.ensure((size_t)n * sizeof(int32_t)));
     int32_t* assign = assign_dev ? assign_dev : ix->w_assign.as<int32_t>();
-    HIP_TRY(launch_fill_u32(ix->w_flag.as<uint32_t>(), 1, 0u, st));
-    HIP_TRY(timed(ix, st, P_ASSIGN, [&] { return launch_coarse(0, x_dev, n, ix->d, ix->cent_h.as<uint16_t>(), ix->cent_l.as<uint16_t>(), ix->dp, nullptr, ix->nlist, ix->lpad, assign,
-                          nullptr, nullptr, 0, ix->w_flag.as<int>(), st); }));
+    { ivftq_status sa = assign_rows(ix, x_dev, n, assign, st); if (sa != IVFTQ_OK) return sa; }
     if (codes_dev || gamma_dev) {
         EncodeArgs a{};
         a.x = x_dev; a.n = n; a.d = ix->d; a.b = ix->b;
@@ -795,9 +819,7 @@ ivftq_status ivftq_encode_add(ivftq_index* ix, const float* x_dev, int64_t n, co
     // 1. coarse assignment
     HIP_TRY(ix->w_assign.ensure((size_t)n * sizeof(int32_t)));
     HIP_TRY(ix->w_slot.ensure((size_t)n * sizeof(int64_t)));
-    HIP_TRY(launch_fill_u32(ix->w_flag.as<uint32_t>(), 1, 0u, st));
-    HIP_TRY(timed(ix, st, P_ASSIGN, [&] { return launch_coarse(0, x_dev, n, ix->d, ix->cent_h.as<uint16_t>(), ix->cent_l.as<uint16_t>(), ix->dp, nullptr, L, ix->lpad,
-                          ix->w_assign.as<int32_t>(), nullptr, nullptr, 0, ix->w_flag.as<int>(), st); }));
+    { ivftq_status sa = assign_rows(ix, x_dev, n, ix->w_assign.as<int32_t>(), st); if (sa != IVFTQ_OK) return sa; }
 
     // 2.-4. room for the new vectors and the stable position of every row
     std::vector<int64_t> need;
@@ -1087,7 +1109,10 @@ ivftq_status ivftq_search(ivftq_index* ix, const float* q_dev, int64_t nq, int n
         sa.m_bound = (int)m_stride;
 
         if (!batched) {
-            HIP_TRY(timed(ix, st, P_LIST_SCAN, [&] { return stream_scan(nullptr, nullptr, 0); }));
+            // workgroups per query: each builds the query's table once and walks its share of the probes;
+            // fewer per query as the batch grows, as long as the launch still fills the chip
+            const int per_query = (int)std::min<int64_t>(nprobe, std::max<int64_t>(1, kStreamWorkgroups / cnt));
+            HIP_TRY(timed(ix, st, P_LIST_SCAN, [&] { return stream_scan(nullptr, nullptr, per_query); }));
             HIP_TRY(timed(ix, st, P_SELECT_TOPK, [&] { return launch_select(1, sa, st); }));
             continue;
         }

@@ -69,9 +69,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
     int mode, const float* __restrict__ x, int64_t n, int d, int vec4, const uint16_t* __restrict__ cent_h,
     const uint16_t* __restrict__ cent_l, int cent_pitch, const float* __restrict__ bias, int L, int Lpad,
     int32_t* __restrict__ assign, float* __restrict__ best_out, float* __restrict__ scores,
-    int64_t ld_scores, int* __restrict__ flag) {
+    int64_t ld_scores, int* __restrict__ flag, const int32_t* __restrict__ row_list,
+    const int* __restrict__ row_count) {
     using Cfg = CoarseCfg<DP>;
     constexpr int KB = Cfg::KB;
+    // row_list (may be null): only the *row_count rows listed there are processed (mode 0)
+    if (row_list) n = *row_count;
+    if ((int64_t)blockIdx.x * (4 * 32 * R) >= n) return;
     extern __shared__ unsigned char lds_raw[];
     uint16_t* th = reinterpret_cast<uint16_t*>(lds_raw);            // [TN][LDH] hi parts of the centroid tile
     uint16_t* tl = th + kTN * Cfg::LDH;                               // [TN][LDH] lo parts
@@ -83,11 +87,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
 
     half8 bh[R][KB], bl[R][KB];
     bool good[R];
+    int64_t rows[R];                                  // data row of position row0 + 32r + j (itself without a list)
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-        const int64_t row = row0 + 32 * r + j;
-        good[r] = load_rows<DP>(x, row, row < n, d, vec4, half, bh[r], bl[r]);
-        if (row < n && !good[r] && half == 0) atomicOr(flag, 1);
+        const int64_t pos = row0 + 32 * r + j;
+        rows[r] = (row_list && pos < n) ? (int64_t)row_list[pos] : pos;
+        good[r] = load_rows<DP>(x, rows[r], pos < n, d, vec4, half, bh[r], bl[r]);
+        if (pos < n && !good[r] && half == 0) atomicOr(flag, 1);
     }
 
     float best[R];
@@ -189,13 +195,207 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
             const float ob = __shfl_xor(best[r], 32);
             const int oi = __shfl_xor(best_idx[r], 32);
             if (ob > best[r] || (ob == best[r] && oi < best_idx[r])) { best[r] = ob; best_idx[r] = oi; }
-            const int64_t row = row0 + 32 * r + j;
-            if (row < n && half == 0) {
-                if (assign) assign[row] = good[r] ? best_idx[r] : -1;
-                if (best_out) best_out[row] = bias ? best[r] : best[r] * kUnscale;
+            if (row0 + 32 * r + j < n && half == 0) {
+                if (assign) assign[rows[r]] = good[r] ? best_idx[r] : -1;
+                if (best_out) best_out[rows[r]] = bias ? best[r] : best[r] * kUnscale;
             }
         }
     }
+}
+
+// Screening pass of the argmax: only the hi*hi products (one MFMA per block instead of three).  With
+// unit vectors the result is off by at most (2^-10 + 2^-22) * sum|a_j b_j| <= 9.8e-4 plus float32
+// summation error, so when the best screened score beats the second best by more than twice that, the
+// best is the exact argmax as well.  Rows where it does not (and rows without a usable norm) are
+// appended to row_list and redone by k_coarse with all three products; both kernels write assign.
+// Per score: best' = max(best, v), second' = med3(best, second, v).
+constexpr float kScreenMargin = 2.2e-3f;
+constexpr float kScreenNone = -3.0e38f;     // below every score, finite so that tagging its low bits keeps it a number
+
+#ifndef IVFTQ_SCREEN_NT
+#define IVFTQ_SCREEN_NT 4
+#endif
+#ifndef IVFTQ_SCREEN_WAVES
+#define IVFTQ_SCREEN_WAVES 2
+#endif
+// 32-centroid tiles per LDS stage of the screening pass (two stages are resident)
+template <int DP>
+constexpr int screen_nt() { return DP <= 128 ? IVFTQ_SCREEN_NT : 2; }
+
+template <int DP>
+constexpr size_t screen_lds_bytes() { return (size_t)2 * screen_nt<DP>() * 32 * CoarseCfg<DP>::LDH * sizeof(uint16_t); }
+
+// max(a, b, c) and the middle of (a, b, c) as single instructions.  Written as instructions because the
+// scores carry a tag in their low bits (below) and are never NaN, so the quieting that the compiler puts
+// in front of a float maximum of an unknown bit pattern would be one wasted operation per score.
+__device__ __forceinline__ float max3_raw(float a, float b, float c) {
+    float o;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(o) : "v"(a), "v"(b), "v"(c));
+    return o;
+}
+
+// The 16 scores of tile position t that a lane holds, four at a time.  The position (t, q) replaces
+// the low 6 bits of the float32 pattern (a change below 2^-17 of the score's size), so that maxima and
+// medians alone carry the index.  With b the running best and s the running second best, two new
+// scores u, w give  s' = max(s, med3(b, u, w)),  b' = max(b, u, w).
+#define IVFTQ_SCREEN_TAKE(MASKED)                                                                          \
+    _Pragma("unroll") for (int q = 0; q < 16; q += 4) {                                                     \
+        _Pragma("unroll") for (int r = 0; r < R; ++r) {                                                     \
+            float v[4];                                                                                     \
+            _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                                 \
+                v[i] = __uint_as_float((__float_as_uint(acc[r][q + i]) & ~63u) | (unsigned)(t * 16 + q + i)); \
+                /* columns q..q+3 of a lane are neighbouring centroids 8*(q/4) + 4*half + i */              \
+                if (MASKED) v[i] = (c0 + t * 32 + 2 * q + 4 * half + i < L) ? v[i] : kScreenNone;           \
+            }                                                                                               \
+            const float m0 = __builtin_amdgcn_fmed3f(best[r], v[0], v[1]);                                  \
+            const float b1 = max3_raw(best[r], v[0], v[1]);                                                 \
+            const float m1 = __builtin_amdgcn_fmed3f(b1, v[2], v[3]);                                       \
+            best[r] = max3_raw(b1, v[2], v[3]);                                                             \
+            second[r] = max3_raw(second[r], m0, m1);                                                        \
+        }                                                                                                   \
+    }
+
+template <int DP, int R>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(IVFTQ_SCREEN_WAVES))) void k_coarse_screen(
+    const float* __restrict__ x, int64_t n, int d, int vec4, const uint16_t* __restrict__ cent_h, int cent_pitch,
+    int L, int Lpad, int32_t* __restrict__ assign, int32_t* __restrict__ row_list, int* __restrict__ row_count) {
+    using Cfg = CoarseCfg<DP>;
+    constexpr int KB = Cfg::KB;
+    extern __shared__ unsigned char lds_raw[];
+    constexpr int NT = screen_nt<DP>(), TN = NT * 32;
+    uint16_t* th = reinterpret_cast<uint16_t*>(lds_raw);            // [2][TN][LDH] hi parts of the centroids
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6, lane = tid & 63, half = lane >> 5, j = lane & 31;
+    const int64_t row0 = ((int64_t)blockIdx.x * 4 + wave) * (32 * R);
+
+    half8 bh[R][KB];
+    bool good[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int64_t row = row0 + 32 * r + j;
+        half8 unused[KB];
+        good[r] = load_rows<DP>(x, row, row < n, d, vec4, half, bh[r], unused);
+        __builtin_amdgcn_sched_barrier(0);          // one tile's float32 values at a time in registers
+    }
+    float best[R], second[R];
+    int best_c0[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) { best[r] = kScreenNone; second[r] = kScreenNone; best_c0[r] = 0; }
+    // Stage s+1 travels global memory -> registers while stage s is multiplied, then registers -> the
+    // other LDS buffer; one barrier per stage.
+    constexpr int kChunks = TN * (DP / 8);                          // 16-byte pieces of one stage
+    constexpr int kPer = (kChunks + 255) / 256;
+    uint4 pre[kPer];
+#define IVFTQ_SCREEN_FETCH(C0)                                                                     \
+    _Pragma("unroll") for (int i = 0; i < kPer; ++i) {                                              \
+        int e = tid + 256 * i;                                                                      \
+        e = e < kChunks ? e : kChunks - 1;                                                          \
+        const int r = e / (DP / 8), c8 = e % (DP / 8);                                              \
+        const int c = (C0) + r < Lpad ? (C0) + r : Lpad - 1; /* a stage may reach past the padded rows */ \
+        pre[i] = *reinterpret_cast<const uint4*>(cent_h + (int64_t)c * cent_pitch + c8 * 8);        \
+    }
+#define IVFTQ_SCREEN_STORE(BUF)                                                                    \
+    _Pragma("unroll") for (int i = 0; i < kPer; ++i) {                                              \
+        const int e = tid + 256 * i;                                                                \
+        if (kChunks % 256 == 0 || e < kChunks)                                                      \
+            *reinterpret_cast<uint4*>((BUF) + (e / (DP / 8)) * Cfg::LDH + (e % (DP / 8)) * 8) = pre[i]; \
+    }
+    IVFTQ_SCREEN_FETCH(0)
+    IVFTQ_SCREEN_STORE(th)
+    __syncthreads();
+    int stage = 0;
+    for (int c0 = 0; c0 < Lpad; c0 += TN, stage ^= 1) {
+        IVFTQ_SCREEN_FETCH(c0 + TN)          // unconditional (indices are clamped): after the last stage it is unused
+        const uint16_t* ah_base = th + stage * (TN * Cfg::LDH) + j * Cfg::LDH + 8 * half;
+        float prev[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) prev[r] = best[r];
+        // The row operand of a tile is read from LDS a tile ahead: the reads of tile t+1 are issued
+        // after the products of tile t and complete while its scores are taken.
+        // (up to 128 coordinates; beyond that the registers do not reach and each block is read as it is used)
+        constexpr bool kAhead = KB <= 8;
+        half8 ah[kAhead ? KB : 1];
+        if (kAhead) {
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb) ah[kAhead ? kb : 0] = *reinterpret_cast<const half8*>(ah_base + 16 * kb);
+        }
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            floatx16 acc[R];
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int q = 0; q < 16; ++q) acc[r][q] = 0.f;
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb) {
+                const half8 a = kAhead ? ah[kAhead ? kb : 0]
+                                       : *reinterpret_cast<const half8*>(ah_base + t * 32 * Cfg::LDH + 16 * kb);
+#pragma unroll
+                for (int r = 0; r < R; ++r) acc[r] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, bh[r][kb], acc[r], 0, 0, 0);
+            }
+            if (kAhead && t + 1 < NT) {
+#pragma unroll
+                for (int kb = 0; kb < KB; ++kb)
+                    ah[kAhead ? kb : 0] = *reinterpret_cast<const half8*>(ah_base + (t + 1) * 32 * Cfg::LDH + 16 * kb);
+            }
+            if (c0 + (t + 1) * 32 <= L) {
+                IVFTQ_SCREEN_TAKE(false)
+            } else {
+                IVFTQ_SCREEN_TAKE(true)
+            }
+        }
+        // which stage the best came from is seen from whether the stage changed it
+#pragma unroll
+        for (int r = 0; r < R; ++r) best_c0[r] = best[r] != prev[r] ? c0 : best_c0[r];
+        IVFTQ_SCREEN_STORE(th + (stage ^ 1) * (TN * Cfg::LDH))
+        __syncthreads();
+    }
+#undef IVFTQ_SCREEN_FETCH
+#undef IVFTQ_SCREEN_STORE
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const unsigned code = __float_as_uint(best[r]) & 63u;
+        int idx = best_c0[r] + (int)(code >> 4) * 32 + 8 * (int)((code & 15u) >> 2) + 4 * half + (int)(code & 3u);
+        // the other half of the lane pair saw the other centroids of the same row
+        const float ob = __shfl_xor(best[r], 32), os = __shfl_xor(second[r], 32);
+        const int oi = __shfl_xor(idx, 32);
+        const float s2 = fmaxf(fmaxf(second[r], os), fminf(best[r], ob));
+        const float b2 = fmaxf(best[r], ob);
+        if (ob > best[r]) idx = oi;
+        const int64_t row = row0 + 32 * r + j;
+        if (row < n && half == 0) {
+            const bool sure = good[r] && (b2 - s2 > kScreenMargin * kSplitScale * kSplitScale);
+            assign[row] = idx;
+            if (!sure) row_list[atomicAdd(row_count, 1)] = (int32_t)row;
+        }
+    }
+}
+#undef IVFTQ_SCREEN_TAKE
+
+// RS, R = 32-row tiles per wavefront of the screening and of the exact kernel
+template <int DP, int RS, int R>
+hipError_t run_screened(const float* x, int64_t n, int d, const uint16_t* cent_h, const uint16_t* cent_l, int cent_pitch,
+                        int L, int Lpad, int32_t* assign, int* flag, int32_t* row_list, int* row_count, hipStream_t st) {
+    static bool attr_set = false;
+    const size_t lds = CoarseCfg<DP>::lds_bytes, lds_screen = screen_lds_bytes<DP>();
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_coarse_screen<DP, RS>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_screen);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_coarse<DP, R>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const int vec4 = (d % 4 == 0) && (reinterpret_cast<uintptr_t>(x) % 16 == 0);
+    const int64_t blocks_s = (n + 4 * 32 * RS - 1) / (4 * 32 * RS), blocks = (n + 4 * 32 * R - 1) / (4 * 32 * R);
+    hipLaunchKernelGGL((k_coarse_screen<DP, RS>), dim3((unsigned)blocks_s), dim3(256), lds_screen, st, x, n, d, vec4,
+                       cent_h, cent_pitch, L, Lpad, assign, row_list, row_count);
+    // the undecided rows, with all three products; workgroups beyond the list leave at once
+    hipLaunchKernelGGL((k_coarse<DP, R>), dim3((unsigned)blocks), dim3(256), lds, st, 0, x, n, d, vec4, cent_h,
+                       cent_l, cent_pitch, (const float*)nullptr, L, Lpad, assign, (float*)nullptr, (float*)nullptr,
+                       (int64_t)0, flag, (const int32_t*)row_list, (const int*)row_count);
+    return hipGetLastError();
 }
 
 template <int DP, int R>
@@ -219,7 +419,8 @@ hipError_t run(int mode, const float* x, int64_t n, int d, const uint16_t* cent_
     if (mode == 1)
         while (blocks * ysplit < 512 && ysplit * 2 <= Lpad / kTN) ysplit *= 2;
     hipLaunchKernelGGL((k_coarse<DP, R>), dim3((unsigned)blocks, (unsigned)ysplit), dim3(256), lds, st, mode, x, n, d, vec4, cent_h,
-                       cent_l, cent_pitch, bias, L, Lpad, assign, best, scores, ld_scores, flag);
+                       cent_l, cent_pitch, bias, L, Lpad, assign, best, scores, ld_scores, flag,
+                       (const int32_t*)nullptr, (const int*)nullptr);
     return hipGetLastError();
 }
 
@@ -271,6 +472,23 @@ hipError_t launch_split_rows(const float* src, int64_t count, uint16_t* hi, uint
     if (count <= 0) return hipSuccess;
     hipLaunchKernelGGL(k_split_rows, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st, src, count, hi, lo);
     return hipGetLastError();
+}
+
+hipError_t launch_coarse_screened(const float* x, int64_t n, int d, const uint16_t* cent_h, const uint16_t* cent_l,
+                                  int cent_pitch, int L, int Lpad, int32_t* assign, int* flag, int32_t* row_list,
+                                  int* row_count, hipStream_t st) {
+    if (n <= 0) return hipSuccess;
+    switch (coarse_dp(d)) {
+#ifndef IVFTQ_SCREEN_R128
+#define IVFTQ_SCREEN_R128 2
+#endif
+#define IVFTQ_CASE(DPV, RS, RV) \
+    case DPV: return run_screened<DPV, RS, RV>(x, n, d, cent_h, cent_l, cent_pitch, L, Lpad, assign, flag, row_list, row_count, st);
+        IVFTQ_CASE(32, 2, 2) IVFTQ_CASE(64, 2, 2) IVFTQ_CASE(96, 2, 2) IVFTQ_CASE(128, IVFTQ_SCREEN_R128, 2)
+        IVFTQ_CASE(160, 2, 1) IVFTQ_CASE(192, 2, 1) IVFTQ_CASE(208, 2, 1) IVFTQ_CASE(224, 2, 1) IVFTQ_CASE(256, 2, 1)
+#undef IVFTQ_CASE
+        default: return hipErrorInvalidValue;
+    }
 }
 
 hipError_t launch_coarse(int mode, const float* x, int64_t n, int d, const uint16_t* cent_h, const uint16_t* cent_l,

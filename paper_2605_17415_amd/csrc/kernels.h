@@ -16,6 +16,7 @@ constexpr int kMaxK = 2048;
 #define IVFTQ_PREFIX_X2 2
 #endif
 constexpr int kPrefixFactorX2 = IVFTQ_PREFIX_X2;   // twice the factor f in: dense prefix >= f * k * T / cap vectors
+constexpr int kStreamWorkgroups = 8192;             // workgroups the streaming scan aims to launch at least
 constexpr int kMaxGridCells = 4096;  // entries of the quantiser's uniform-grid index (32 KB of LDS)
 
 // Split float16 form used by the float16 matrix-core kernels: V = 1024*v, hi = fp16(V),
@@ -55,6 +56,12 @@ struct ListStore {
 hipError_t launch_coarse(int mode, const float* x, int64_t n, int d, const uint16_t* cent_h, const uint16_t* cent_l,
                          int cent_pitch, const float* bias, int L, int Lpad, int32_t* assign, float* best,
                          float* scores, int64_t ld_scores, int* flag, hipStream_t st);
+// The argmax of mode 0 (no bias) in two steps: a screening pass with the hi*hi products alone decides
+// every row whose best score is clearly ahead, the rest (listed in row_list, counted in *row_count,
+// which the caller clears) is redone with all three products.  assign as for launch_coarse.
+hipError_t launch_coarse_screened(const float* x, int64_t n, int d, const uint16_t* cent_h, const uint16_t* cent_l,
+                                  int cent_pitch, int L, int Lpad, int32_t* assign, int* flag, int32_t* row_list,
+                                  int* row_count, hipStream_t st);
 // hi[i], lo[i] = split float16 form of src[i]
 hipError_t launch_split_rows(const float* src, int64_t count, uint16_t* hi, uint16_t* lo, hipStream_t st);
 
