@@ -334,16 +334,16 @@ def main():
         t = prof.get(name)
         return t[0] / t[1] if t and t[1] else None
 
-    def mfma_roof(kernel, flops):
+    def mfma_roof(kernel, flops, passes=SPLIT_PASSES, dtype_note="f16 (3 split passes per product, f32 accumulate)"):
         ms = avg_ms(kernel)
         if not ms:
             return None
         r = {"kernel": kernel, "bound": "mfma", "achieved": flops / (ms * 1e-3) / 1e12, "peak": MFMA_F16_PEAK_TFLOPS,
              "unit": "TFLOP/s", "traffic": stored_traffic(kernel, args.nprobe) if args.workload == "1m" else None, "algorithmic_flops_per_launch": flops, "avg_launch_ms": ms,
-             "mfma_dtype": "f16 (3 split passes per product, f32 accumulate)"}
+             "mfma_dtype": dtype_note}
         r["frac"] = r["achieved"] / r["peak"]
-        r["issued_frac"] = SPLIT_PASSES * r["frac"]      # share of the fp16 pipe's peak actually issued
-        r["issued_vs_measured_pipe_rate"] = SPLIT_PASSES * r["achieved"] / mfma_random
+        r["issued_frac"] = passes * r["frac"]            # share of the fp16 pipe's peak actually issued
+        r["issued_vs_measured_pipe_rate"] = passes * r["achieved"] / mfma_random
         return r
 
     # what a loop of nothing but the fp16 MFMA instruction reaches on this device: with constant operands
@@ -351,7 +351,11 @@ def main():
     mfma_const = pkg.ivftq_measure_mfma_rate(False)
     mfma_random = pkg.ivftq_measure_mfma_rate(True)
     batched = "batch_scan" in prof
-    rooflines = {"coarse_assign": mfma_roof("coarse_assign", assign_flops),
+    # the assignment screens every row with one product and redoes the undecided rows with all three
+    undecided = ix.assign_undecided() / float(w.n)
+    rooflines = {"coarse_assign": mfma_roof("coarse_assign", assign_flops, 1.0 + SPLIT_PASSES * undecided,
+                                            "f16 (screening pass: leading parts, 1 product; undecided rows: 3 split "
+                                            "passes; f32 accumulate)"),
                  "encode_rotate_quantise_pack": mfma_roof("encode_rotate_quantise_pack", 2.0 * w.d * w.d * w.n)}
     if batched:
         rooflines["batch_scan"] = mfma_roof("batch_scan", 2.0 * w.d * (float(cand.sum()) - stream_cand))
@@ -423,7 +427,7 @@ def main():
         "candidates_per_query": float(cand.mean()),
         "index_bytes": ix.index_bytes(),
         "search_ms_with_kernel_events": float(np.mean(search_ms_p)), "encode_ms_with_kernel_events": float(np.mean(enc_ms_p)),
-        "kernel_ms_per_step": per_step, "dominant_kernel": dominant,
+        "kernel_ms_per_step": per_step, "dominant_kernel": dominant, "assign_undecided_fraction": undecided,
         "roofline": roofline, "rooflines": rooflines, "scan_stage_vs_streamed_bytes": scan_stage,
         "mfma_pipe_measured": {"unit": "TFLOP/s", "instruction": "v_mfma_f32_32x32x16_f16", "constant_operands": mfma_const,
                                "random_operands": mfma_random,

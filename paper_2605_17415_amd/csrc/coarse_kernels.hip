@@ -484,7 +484,7 @@ hipError_t launch_coarse_screened(const float* x, int64_t n, int d, const uint16
 #endif
 #define IVFTQ_CASE(DPV, RS, RV) \
     case DPV: return run_screened<DPV, RS, RV>(x, n, d, cent_h, cent_l, cent_pitch, L, Lpad, assign, flag, row_list, row_count, st);
-        IVFTQ_CASE(32, 2, 2) IVFTQ_CASE(64, 2, 2) IVFTQ_CASE(96, 2, 2) IVFTQ_CASE(128, IVFTQ_SCREEN_R128, 2)
+        IVFTQ_CASE(32, 2, 1) IVFTQ_CASE(64, 2, 1) IVFTQ_CASE(96, 2, 1) IVFTQ_CASE(128, IVFTQ_SCREEN_R128, 1)
         IVFTQ_CASE(160, 2, 1) IVFTQ_CASE(192, 2, 1) IVFTQ_CASE(208, 2, 1) IVFTQ_CASE(224, 2, 1) IVFTQ_CASE(256, 2, 1)
 #undef IVFTQ_CASE
         default: return hipErrorInvalidValue;

@@ -1,0 +1,75 @@
+"""GPU: the two-step coarse assignment (screening with float16 leading parts, full precision for the
+rows it leaves undecided) against the oracle's double-precision argmax on rows built to sit near ties.
+
+The rows are seeded and synthetic: mixtures of two or three centroids at weights that put the best and
+second-best score 1e-7 ... 1e-2 apart (on both sides of the screening margin), exact copies of
+centroids, and plain random directions.  Assignments must equal the oracle's except where its own
+best-minus-second gap is below 1e-5 (the rule of every other encode comparison).
+"""
+import numpy as np
+import pytest
+
+import parity
+from oracle import ivftq_oracle as orc
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+
+def _near_tie_rows(cent, rng, n_each):
+    L, d = cent.shape
+    rows = []
+    # two centroids, the first ahead by a controlled amount
+    for gap in (0.0, 1e-7, 1e-6, 1e-5, 1e-4, 5e-4, 1e-3, 2e-3, 3e-3, 1e-2):
+        a = rng.integers(0, L, n_each)
+        b = (a + 1 + rng.integers(0, L - 1, n_each)) % L
+        mid = cent[a] + cent[b]
+        mid /= np.linalg.norm(mid, axis=1, keepdims=True)
+        # moving along (c_a - c_b) by t changes the score difference by about t * |c_a - c_b|^2
+        diff = cent[a] - cent[b]
+        t = gap / np.maximum(np.sum(diff * diff, axis=1), 1e-12)
+        rows.append(mid + t[:, None] * diff)
+    # three centroids at equal weight
+    a = rng.integers(0, L, (n_each, 3))
+    rows.append(cent[a].sum(axis=1))
+    # the centroids themselves and random directions, some at a large or a tiny scale
+    rows.append(cent[rng.integers(0, L, n_each)] * 37.5)
+    g = rng.standard_normal((4 * n_each, d))
+    g[::3] *= 1e-3
+    rows.append(g)
+    X = np.concatenate(rows).astype(np.float32)
+    return X[rng.permutation(len(X))]
+
+
+@pytest.mark.parametrize("d,L,b", [(128, 300, 4), (96, 200, 3), (200, 130, 4), (30, 70, 4)])
+def test_assignment_near_ties_matches_oracle(d, L, b):
+    import paper_2605_17415_amd as pkg
+    rng = np.random.default_rng(1000 * d + L)
+    cent = rng.standard_normal((L, d))
+    cent[: L // 2] = cent[L // 2: 2 * (L // 2)] + 0.05 * rng.standard_normal((L // 2, d))   # close pairs
+    cent = orc.normalize_rows(cent)
+    X = _near_tie_rows(cent, rng, 331)          # 331 per group: every kernel tile size leaves a ragged tail
+    print(f"[screen] d={d} L={L} rows={len(X)}", flush=True)
+    Pi = orc.haar_rotation_from_gaussian(rng.standard_normal((d, d)))
+    _, tau = orc.codebook_fp32(b, d)
+    enc = orc.encode(X, cent.astype(np.float32), Pi.astype(np.float32), tau)
+
+    ix = pkg.Index(d, b, L)
+    ix.set_coarse(cent.astype(np.float32))
+    ix.set_rotation(Pi.astype(np.float32))
+    x = torch.from_numpy(X).to("cuda:0")
+    assign, _, _ = ix.encode_only(x, want_codes=False)
+    torch.cuda.synchronize()
+    undecided = ix.assign_undecided()
+    rep = parity.compare_encode(enc, assign.cpu().numpy(), None, None)
+    print("near-tie assignment:", rep, "undecided", undecided, flush=True)
+    # the construction puts rows on both sides of the screening margin
+    assert 0 < undecided < len(X)
+    assert rep["assign_near_tie_total"] > 0
+    # the same rows in a second call of a different size: the undecided list starts empty again
+    half = len(X) // 2 + 7
+    assign2, _, _ = ix.encode_only(x[:half].contiguous(), want_codes=False)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(assign2.cpu().numpy(), assign.cpu().numpy()[:half])
+    assert ix.assign_undecided() <= undecided
+    ix.close()
