@@ -757,12 +757,14 @@ ivftq_status commit_rows(ivftq_index* ix, const std::vector<int64_t>& need, int6
 // plus the exact pass over the rows it left undecided.  w_flag[0] = a row without a usable norm,
 // w_flag[1] = number of undecided rows.
 ivftq_status assign_rows(ivftq_index* ix, const float* x_dev, int64_t n, int32_t* assign, hipStream_t st) {
-    HIP_TRY(ix->w_undecided.ensure((size_t)n * sizeof(int32_t)));
+    // keys (8 bytes each) first, then the row numbers
+    HIP_TRY(ix->w_undecided.ensure((size_t)n * (sizeof(unsigned long long) + sizeof(int32_t))));
     HIP_TRY(launch_fill_u32(ix->w_flag.as<uint32_t>(), 2, 0u, st));
     HIP_TRY(timed(ix, st, P_ASSIGN, [&] {
         return launch_coarse_screened(x_dev, n, ix->d, ix->cent_h.as<uint16_t>(), ix->cent_l.as<uint16_t>(), ix->dp,
                                       ix->nlist, ix->lpad, assign, ix->w_flag.as<int>(),
-                                      ix->w_undecided.as<int32_t>(), ix->w_flag.as<int>() + 1, st);
+                                      reinterpret_cast<int32_t*>(ix->w_undecided.as<unsigned long long>() + n),
+                                      ix->w_undecided.as<unsigned long long>(), ix->w_flag.as<int>() + 1, st);
     }));
     return IVFTQ_OK;
 }

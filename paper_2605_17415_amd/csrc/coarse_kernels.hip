@@ -69,13 +69,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
     int mode, const float* __restrict__ x, int64_t n, int d, int vec4, const uint16_t* __restrict__ cent_h,
     const uint16_t* __restrict__ cent_l, int cent_pitch, const float* __restrict__ bias, int L, int Lpad,
     int32_t* __restrict__ assign, float* __restrict__ best_out, float* __restrict__ scores,
-    int64_t ld_scores, int* __restrict__ flag, const int32_t* __restrict__ row_list,
-    const int* __restrict__ row_count) {
+    int64_t ld_scores, int* __restrict__ flag) {
     using Cfg = CoarseCfg<DP>;
     constexpr int KB = Cfg::KB;
-    // row_list (may be null): only the *row_count rows listed there are processed (mode 0)
-    if (row_list) n = *row_count;
-    if ((int64_t)blockIdx.x * (4 * 32 * R) >= n) return;
     extern __shared__ unsigned char lds_raw[];
     uint16_t* th = reinterpret_cast<uint16_t*>(lds_raw);            // [TN][LDH] hi parts of the centroid tile
     uint16_t* tl = th + kTN * Cfg::LDH;                               // [TN][LDH] lo parts
@@ -87,13 +83,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
 
     half8 bh[R][KB], bl[R][KB];
     bool good[R];
-    int64_t rows[R];                                  // data row of position row0 + 32r + j (itself without a list)
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-        const int64_t pos = row0 + 32 * r + j;
-        rows[r] = (row_list && pos < n) ? (int64_t)row_list[pos] : pos;
-        good[r] = load_rows<DP>(x, rows[r], pos < n, d, vec4, half, bh[r], bl[r]);
-        if (pos < n && !good[r] && half == 0) atomicOr(flag, 1);
+        const int64_t row = row0 + 32 * r + j;
+        good[r] = load_rows<DP>(x, row, row < n, d, vec4, half, bh[r], bl[r]);
+        if (row < n && !good[r] && half == 0) atomicOr(flag, 1);
     }
 
     float best[R];
@@ -195,9 +189,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
             const float ob = __shfl_xor(best[r], 32);
             const int oi = __shfl_xor(best_idx[r], 32);
             if (ob > best[r] || (ob == best[r] && oi < best_idx[r])) { best[r] = ob; best_idx[r] = oi; }
-            if (row0 + 32 * r + j < n && half == 0) {
-                if (assign) assign[rows[r]] = good[r] ? best_idx[r] : -1;
-                if (best_out) best_out[rows[r]] = bias ? best[r] : best[r] * kUnscale;
+            const int64_t row = row0 + 32 * r + j;
+            if (row < n && half == 0) {
+                if (assign) assign[row] = good[r] ? best_idx[r] : -1;
+                if (best_out) best_out[row] = bias ? best[r] : best[r] * kUnscale;
             }
         }
     }
@@ -207,7 +202,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
 // unit vectors the result is off by at most (2^-10 + 2^-22) * sum|a_j b_j| <= 9.8e-4 plus float32
 // summation error, so when the best screened score beats the second best by more than twice that, the
 // best is the exact argmax as well.  Rows where it does not (and rows without a usable norm) are
-// appended to row_list and redone by k_coarse with all three products; both kernels write assign.
+// appended to row_list and redone by k_coarse_resolve with all three products; both write assign.
 // Per score: best' = max(best, v), second' = med3(best, second, v).
 constexpr float kScreenMargin = 2.2e-3f;
 constexpr float kScreenNone = -3.0e38f;     // below every score, finite so that tagging its low bits keeps it a number
@@ -258,7 +253,8 @@ __device__ __forceinline__ float max3_raw(float a, float b, float c) {
 template <int DP, int R>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(IVFTQ_SCREEN_WAVES))) void k_coarse_screen(
     const float* __restrict__ x, int64_t n, int d, int vec4, const uint16_t* __restrict__ cent_h, int cent_pitch,
-    int L, int Lpad, int32_t* __restrict__ assign, int32_t* __restrict__ row_list, int* __restrict__ row_count) {
+    int L, int Lpad, int32_t* __restrict__ assign, int32_t* __restrict__ row_list,
+    unsigned long long* __restrict__ row_key, int* __restrict__ row_count) {
     using Cfg = CoarseCfg<DP>;
     constexpr int KB = Cfg::KB;
     extern __shared__ unsigned char lds_raw[];
@@ -366,35 +362,133 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(IVFTQ_SCREE
         if (row < n && half == 0) {
             const bool sure = good[r] && (b2 - s2 > kScreenMargin * kSplitScale * kSplitScale);
             assign[row] = idx;
-            if (!sure) row_list[atomicAdd(row_count, 1)] = (int32_t)row;
+            if (!sure) {
+                const int pos = atomicAdd(row_count, 1);
+                row_list[pos] = (int32_t)row;
+                row_key[pos] = 0ull;
+            }
         }
     }
 }
 #undef IVFTQ_SCREEN_TAKE
 
-// RS, R = 32-row tiles per wavefront of the screening and of the exact kernel
-template <int DP, int RS, int R>
+// The undecided rows of the screening pass, with all three products.  Workgroup (x, y) walks the row
+// blocks x, x + gridDim.x, ... of the list (128 rows each, one tile per wavefront) against the y-th share of
+// the centroid stages, so that a short list still spreads over the chip; the shares of a row meet in
+// row_key[position] through a 64-bit atomic maximum of (order-preserving score bits, ~index), which keeps
+// the smallest index among equal scores like the single-kernel argmax does.  A row without a usable norm
+// leaves its key at 0.
+template <int DP>
+__global__ __launch_bounds__(256) void k_coarse_resolve(
+    const float* __restrict__ x, int d, int vec4, const uint16_t* __restrict__ cent_h,
+    const uint16_t* __restrict__ cent_l, int cent_pitch, int L, int Lpad, const int32_t* __restrict__ row_list,
+    const int* __restrict__ row_count, unsigned long long* __restrict__ row_key) {
+    using Cfg = CoarseCfg<DP>;
+    constexpr int KB = Cfg::KB;
+    extern __shared__ unsigned char lds_raw[];
+    uint16_t* th = reinterpret_cast<uint16_t*>(lds_raw);            // [TN][LDH] hi parts of the centroid tile
+    uint16_t* tl = th + kTN * Cfg::LDH;                               // [TN][LDH] lo parts
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6, lane = tid & 63, half = lane >> 5, j = lane & 31;
+    const int n = *row_count;
+    const int stages = Lpad / kTN, per_y = (stages + (int)gridDim.y - 1) / (int)gridDim.y;
+    const int c_lo = (int)blockIdx.y * per_y * kTN;
+    const int c_hi = c_lo + per_y * kTN < Lpad ? c_lo + per_y * kTN : Lpad;
+    if (c_lo >= c_hi) return;
+    const uint16_t* ah_base = th + j * Cfg::LDH + 8 * half;
+    const uint16_t* al_base = tl + j * Cfg::LDH + 8 * half;
+
+    for (int64_t rb = blockIdx.x; rb * 128 < n; rb += gridDim.x) {
+        const int pos = (int)(rb * 128) + wave * 32 + j;
+        half8 bh[KB], bl[KB];
+        const bool good = load_rows<DP>(x, pos < n ? (int64_t)row_list[pos] : 0, pos < n, d, vec4, half, bh, bl);
+        float best = -__builtin_inff();
+        int best_idx = 0;
+        for (int c0 = c_lo; c0 < c_hi; c0 += kTN) {
+            __syncthreads();                 // the previous stage (or row block) is no longer read
+            for (int e = tid; e < kTN * (DP / 8); e += 256) {
+                const int r = e / (DP / 8), c8 = e % (DP / 8);
+                const int64_t src = (int64_t)(c0 + r) * cent_pitch + c8 * 8;
+                *reinterpret_cast<uint4*>(th + r * Cfg::LDH + c8 * 8) = *reinterpret_cast<const uint4*>(cent_h + src);
+                *reinterpret_cast<uint4*>(tl + r * Cfg::LDH + c8 * 8) = *reinterpret_cast<const uint4*>(cent_l + src);
+            }
+            __syncthreads();
+            floatx16 acc[kNT];
+#pragma unroll
+            for (int t = 0; t < kNT; ++t)
+#pragma unroll
+                for (int q = 0; q < 16; ++q) acc[t][q] = 0.f;
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+                for (int t = 0; t < kNT; ++t) {
+                    const half8 ah = *reinterpret_cast<const half8*>(ah_base + t * 32 * Cfg::LDH + 16 * kb);
+                    const half8 al = *reinterpret_cast<const half8*>(al_base + t * 32 * Cfg::LDH + 16 * kb);
+                    acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah, bh[kb], acc[t], 0, 0, 0);
+                    acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah, bl[kb], acc[t], 0, 0, 0);
+                    acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(al, bh[kb], acc[t], 0, 0, 0);
+                }
+            // raw accumulators (the argmax does not depend on the common 2^20 scale); ascending c, first maximum wins
+#pragma unroll
+            for (int t = 0; t < kNT; ++t)
+#pragma unroll
+                for (int q = 0; q < 16; ++q) {
+                    const int c = c0 + t * 32 + 8 * (q / 4) + 4 * half + (q % 4);
+                    if (c < L && acc[t][q] > best) { best = acc[t][q]; best_idx = c; }
+                }
+        }
+        const float ob = __shfl_xor(best, 32);
+        const int oi = __shfl_xor(best_idx, 32);
+        if (ob > best || (ob == best && oi < best_idx)) { best = ob; best_idx = oi; }
+        if (pos < n && half == 0 && good) {
+            const unsigned u = __float_as_uint(best);
+            const unsigned mono = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+            atomicMax(row_key + pos, ((unsigned long long)mono << 32) | (unsigned long long)(0xFFFFFFFFu - (unsigned)best_idx));
+        }
+    }
+}
+
+__global__ void k_coarse_resolve_write(const int32_t* __restrict__ row_list, const int* __restrict__ row_count,
+                                       const unsigned long long* __restrict__ row_key, int32_t* __restrict__ assign,
+                                       int* __restrict__ flag) {
+    const int n = *row_count;
+    for (int pos = blockIdx.x * blockDim.x + threadIdx.x; pos < n; pos += gridDim.x * blockDim.x) {
+        const unsigned long long key = row_key[pos];
+        assign[row_list[pos]] = key ? (int32_t)(0xFFFFFFFFu - (unsigned)(key & 0xFFFFFFFFull)) : -1;
+        if (!key) atomicOr(flag, 1);
+    }
+}
+
+// RS = 32-row tiles per wavefront of the screening kernel
+template <int DP, int RS>
 hipError_t run_screened(const float* x, int64_t n, int d, const uint16_t* cent_h, const uint16_t* cent_l, int cent_pitch,
-                        int L, int Lpad, int32_t* assign, int* flag, int32_t* row_list, int* row_count, hipStream_t st) {
+                        int L, int Lpad, int32_t* assign, int* flag, int32_t* row_list, unsigned long long* row_key,
+                        int* row_count, hipStream_t st) {
     static bool attr_set = false;
-    const size_t lds = CoarseCfg<DP>::lds_bytes, lds_screen = screen_lds_bytes<DP>();
+    const size_t lds_screen = screen_lds_bytes<DP>();
+    const size_t lds = (size_t)2 * kTN * CoarseCfg<DP>::LDH * sizeof(uint16_t);
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_coarse_screen<DP, RS>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_screen);
         if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_coarse<DP, R>),
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_coarse_resolve<DP>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     const int vec4 = (d % 4 == 0) && (reinterpret_cast<uintptr_t>(x) % 16 == 0);
-    const int64_t blocks_s = (n + 4 * 32 * RS - 1) / (4 * 32 * RS), blocks = (n + 4 * 32 * R - 1) / (4 * 32 * R);
+    const int64_t blocks_s = (n + 4 * 32 * RS - 1) / (4 * 32 * RS);
     hipLaunchKernelGGL((k_coarse_screen<DP, RS>), dim3((unsigned)blocks_s), dim3(256), lds_screen, st, x, n, d, vec4,
-                       cent_h, cent_pitch, L, Lpad, assign, row_list, row_count);
-    // the undecided rows, with all three products; workgroups beyond the list leave at once
-    hipLaunchKernelGGL((k_coarse<DP, R>), dim3((unsigned)blocks), dim3(256), lds, st, 0, x, n, d, vec4, cent_h,
-                       cent_l, cent_pitch, (const float*)nullptr, L, Lpad, assign, (float*)nullptr, (float*)nullptr,
-                       (int64_t)0, flag, (const int32_t*)row_list, (const int*)row_count);
+                       cent_h, cent_pitch, L, Lpad, assign, row_list, row_key, row_count);
+    // the undecided rows: about four centroid stages per workgroup, at most 512 x 16 workgroups
+    const int stages = Lpad / kTN;
+    const int ysplit = std::min(16, (stages + 3) / 4);
+    const int64_t row_blocks = (n + 127) / 128;
+    hipLaunchKernelGGL((k_coarse_resolve<DP>), dim3((unsigned)std::min<int64_t>(row_blocks, 512), (unsigned)ysplit),
+                       dim3(256), lds, st, x, d, vec4, cent_h, cent_l, cent_pitch, L, Lpad,
+                       (const int32_t*)row_list, (const int*)row_count, row_key);
+    hipLaunchKernelGGL(k_coarse_resolve_write, dim3((unsigned)std::min<int64_t>((n + 255) / 256, 256)), dim3(256), 0, st,
+                       (const int32_t*)row_list, (const int*)row_count, (const unsigned long long*)row_key, assign, flag);
     return hipGetLastError();
 }
 
@@ -419,8 +513,7 @@ hipError_t run(int mode, const float* x, int64_t n, int d, const uint16_t* cent_
     if (mode == 1)
         while (blocks * ysplit < 512 && ysplit * 2 <= Lpad / kTN) ysplit *= 2;
     hipLaunchKernelGGL((k_coarse<DP, R>), dim3((unsigned)blocks, (unsigned)ysplit), dim3(256), lds, st, mode, x, n, d, vec4, cent_h,
-                       cent_l, cent_pitch, bias, L, Lpad, assign, best, scores, ld_scores, flag,
-                       (const int32_t*)nullptr, (const int*)nullptr);
+                       cent_l, cent_pitch, bias, L, Lpad, assign, best, scores, ld_scores, flag);
     return hipGetLastError();
 }
 
@@ -476,16 +569,13 @@ hipError_t launch_split_rows(const float* src, int64_t count, uint16_t* hi, uint
 
 hipError_t launch_coarse_screened(const float* x, int64_t n, int d, const uint16_t* cent_h, const uint16_t* cent_l,
                                   int cent_pitch, int L, int Lpad, int32_t* assign, int* flag, int32_t* row_list,
-                                  int* row_count, hipStream_t st) {
+                                  unsigned long long* row_key, int* row_count, hipStream_t st) {
     if (n <= 0) return hipSuccess;
     switch (coarse_dp(d)) {
-#ifndef IVFTQ_SCREEN_R128
-#define IVFTQ_SCREEN_R128 2
-#endif
-#define IVFTQ_CASE(DPV, RS, RV) \
-    case DPV: return run_screened<DPV, RS, RV>(x, n, d, cent_h, cent_l, cent_pitch, L, Lpad, assign, flag, row_list, row_count, st);
-        IVFTQ_CASE(32, 2, 1) IVFTQ_CASE(64, 2, 1) IVFTQ_CASE(96, 2, 1) IVFTQ_CASE(128, IVFTQ_SCREEN_R128, 1)
-        IVFTQ_CASE(160, 2, 1) IVFTQ_CASE(192, 2, 1) IVFTQ_CASE(208, 2, 1) IVFTQ_CASE(224, 2, 1) IVFTQ_CASE(256, 2, 1)
+#define IVFTQ_CASE(DPV) \
+    case DPV: return run_screened<DPV, 2>(x, n, d, cent_h, cent_l, cent_pitch, L, Lpad, assign, flag, row_list, row_key, row_count, st);
+        IVFTQ_CASE(32) IVFTQ_CASE(64) IVFTQ_CASE(96) IVFTQ_CASE(128) IVFTQ_CASE(160)
+        IVFTQ_CASE(192) IVFTQ_CASE(208) IVFTQ_CASE(224) IVFTQ_CASE(256)
 #undef IVFTQ_CASE
         default: return hipErrorInvalidValue;
     }
