@@ -443,6 +443,78 @@ def search(index: ListIndex, Q, nprobe: int, k: int, return_all: bool = False):
     return scores, ids, probes, S
 
 
+# --------------------------------------------------------------------------
+# Cascade search (Appendix "Cascade search via Lloyd-Max bin ordinality")
+# --------------------------------------------------------------------------
+#
+# Pass 1 scores every candidate from the top beta bits of each stored code alone, with a codebook of
+# 2^beta values; the n_keep best go to pass 2, which scores them with the full codes.  The appendix
+# does not spell the coarsened codebook out.  Reading taken here: dropping the low bits of a code
+# merges 2^(bits-beta) neighbouring bins into one, and the value of a merged bin is what a Lloyd-Max
+# codebook would put there, the mean of the coordinate density over it, i.e. the mass-weighted mean
+# of the member levels (each of which is the mean of its own bin).
+
+
+def coarsened_codebook(levels, boundaries, d: int, beta: int, density: str = "sphere"):
+    """2^beta values for the top beta bits of a code whose full table is (levels, boundaries)."""
+    levels = np.asarray(levels, dtype=np.float64)
+    K = len(levels)
+    bits = int(round(np.log2(K)))
+    if not (1 <= beta <= bits) or (1 << bits) != K:
+        raise ValueError("beta must lie between 1 and the stored bits")
+    mass = bin_masses(boundaries, d, density)
+    group = 1 << (bits - beta)
+    m = mass.reshape(-1, group)
+    return (m * levels.reshape(-1, group)).sum(axis=1) / m.sum(axis=1)
+
+
+def cascade_search(index: ListIndex, Q, nprobe: int, k: int, beta: int, n_keep: int, c_coarse,
+                   return_kept: bool = False):
+    """Two-pass search.  Probes as in search(); then per query
+
+      pass 1: s1 = s_l + float(gamma16_i) * sum_j z_j * c_coarse[code_ij >> (bits - beta)]
+              keep the n_keep candidates with the largest s1 (ties -> smaller id)
+      pass 2: score = s_l + float(gamma16_i) * sum_j z_j * c[code_ij]  for the kept ones
+      result: k largest scores (ties -> smaller id), padded with (-1, -inf)
+
+    return_kept adds, per query, (ids, pass-1 scores) of every candidate and the kept ids.
+    """
+    c_coarse = np.asarray(c_coarse, dtype=np.float64)
+    bits = int(round(np.log2(len(index.c))))
+    shift = bits - beta
+    assert len(c_coarse) == 1 << beta
+    Qn = normalize_rows(Q)
+    nq = Qn.shape[0]
+    S = Qn @ index.centroids.T
+    Z = Qn @ index.Pi.T
+    L = index.centroids.shape[0]
+    scores = np.full((nq, k), -np.inf)
+    ids = np.full((nq, k), -1, dtype=np.int64)
+    kept_all = []
+    for qi in range(nq):
+        order = np.lexsort((np.arange(L), -S[qi]))[:nprobe]
+        cid, s1, s2 = [], [], []
+        for l in order:
+            if len(index.ids[l]) == 0:
+                continue
+            g = index.gamma16[l].astype(np.float64)
+            cid.append(index.ids[l])
+            s1.append(S[qi, l] + g * (c_coarse[index.codes[l] >> shift] @ Z[qi]))
+            s2.append(S[qi, l] + g * (index.c[index.codes[l]] @ Z[qi]))
+        if not cid:
+            kept_all.append((np.empty(0, np.int64), np.empty(0), np.empty(0, np.int64)))
+            continue
+        cid, s1, s2 = np.concatenate(cid), np.concatenate(s1), np.concatenate(s2)
+        keep = np.lexsort((cid, -s1))[:n_keep]
+        top = keep[np.lexsort((cid[keep], -s2[keep]))[:k]]
+        scores[qi, :len(top)] = s2[top]
+        ids[qi, :len(top)] = cid[top]
+        kept_all.append((cid, s1, cid[keep]))
+    if return_kept:
+        return scores, ids, kept_all
+    return scores, ids
+
+
 def reconstruct(index: ListIndex, l: int):
     """x^ = c~_l + gamma * Pi^T c[code]  for every vector of list l (Adaptive refresh, Sec. 3.3)."""
     recon = index.c[index.codes[l]]

@@ -404,3 +404,79 @@ def test_rerank_is_exact_on_its_candidates_and_lifts_recall():
     dup = np.array([[7, 7, -1, 3, 3, 9]])
     s2, i2 = orc.rerank(X, Q[:1], dup, 4)
     assert sorted(i2[0][:3].tolist()) == [3, 7, 9] and i2[0][3] == -1 and np.isneginf(s2[0][3])
+
+
+# ---------------------------------------------------------------- cascade (Appendix "Cascade search")
+
+
+@pytest.mark.parametrize("b,d,beta", [(4, 32, 2), (5, 96, 4), (3, 16, 1)])
+def test_coarsened_codebook_is_the_conditional_mean_of_the_merged_bins(b, d, beta):
+    from scipy import integrate
+    c, tau = orc.lloyd_max_codebook(b, d)
+    cc = orc.coarsened_codebook(c, tau, d, beta)
+    assert cc.shape == (1 << beta,) and np.all(np.diff(cc) > 0)
+    np.testing.assert_allclose(cc, -cc[::-1], atol=1e-12)          # the density is even
+    # straight from the definition: E[T | T in the union of the 2^(b-beta) bins], by adaptive quadrature
+    # on the density formula itself (the oracle goes through per-bin masses and the level table)
+    kappa = math.gamma(d / 2) / (math.sqrt(math.pi) * math.gamma((d - 1) / 2))
+    f = lambda t: kappa * (1 - t * t) ** ((d - 3) / 2)
+    edges = np.concatenate(([-1.0], tau, [1.0]))
+    g = 1 << (b - beta)
+    for i in range(1 << beta):
+        lo, hi = edges[i * g], edges[(i + 1) * g]
+        m0 = integrate.quad(f, lo, hi, epsabs=1e-14, epsrel=1e-12)[0]
+        m1 = integrate.quad(lambda t: t * f(t), lo, hi, epsabs=1e-14, epsrel=1e-12)[0]
+        assert abs(cc[i] - m1 / m0) < 1e-9
+        # ordinality: a merged value lies between its outermost member levels
+        assert c[i * g] <= cc[i] <= c[(i + 1) * g - 1]
+    # all bits kept: nothing is merged
+    np.testing.assert_allclose(orc.coarsened_codebook(c, tau, d, b), c, atol=1e-12)
+    # one bit: the two half-line means +-E|T|, in closed form kappa / ((d-1)/2) ... = 2*kappa/(d-1)
+    np.testing.assert_allclose(orc.coarsened_codebook(c, tau, d, 1), [-2 * kappa / (d - 1), 2 * kappa / (d - 1)], rtol=1e-9)
+
+
+def test_cascade_reduces_to_the_plain_search_and_keeps_recall():
+    w = synth.scaled(synth.config_tiny(), 6000, 60)
+    X, Q = synth.database(w, 0, 6000), synth.queries(w, 60)
+    C, _ = orc.train_coarse(X, 24, 5, synth.kmeans_init_indices(0, 6000, 24))
+    Pi = orc.haar_rotation_from_gaussian(synth.gaussian_matrix(0, w.d))
+    c, tau = orc.lloyd_max_codebook(4, w.d)
+    idx = orc.ListIndex(C, Pi, c, tau)
+    idx.add(X)
+    base_sc, base_ids, _, _, everything = orc.search(idx, Q, 6, 10, return_all=True)
+    # (i) pass 1 keeps everything: pass 2 alone decides, so the result is the plain search's
+    sc, ids = orc.cascade_search(idx, Q, 6, 10, 2, 10 ** 6, orc.coarsened_codebook(c, tau, w.d, 2))
+    np.testing.assert_array_equal(ids, base_ids)
+    np.testing.assert_allclose(sc, base_sc, atol=1e-12)
+    # (ii) all bits in pass 1: its ranking is the final one, any n_keep >= k gives the plain search
+    sc, ids = orc.cascade_search(idx, Q, 6, 10, 4, 10, c)
+    np.testing.assert_array_equal(ids, base_ids)
+    # (iii) the kept set is the pass-1 top n_keep, and every returned score is the full-code score of its id
+    cc = orc.coarsened_codebook(c, tau, w.d, 3)
+    sc, ids, kept = orc.cascade_search(idx, Q, 6, 10, 3, 100, cc, return_kept=True)
+    for qi in range(5):
+        cid, s1, keep_ids = kept[qi]
+        assert len(keep_ids) == min(100, len(cid))
+        cut = np.sort(s1)[::-1][len(keep_ids) - 1]
+        assert np.all(s1[np.isin(cid, keep_ids)] >= cut)
+        full = dict(zip(everything[qi][0].tolist(), everything[qi][1].tolist()))
+        for s, i in zip(sc[qi], ids[qi]):
+            assert abs(full[int(i)] - s) < 1e-12 and int(i) in set(keep_ids.tolist())
+    # (iv) the appendix's observation: top bits + 100 kept preserve recall@10 (there: 5+1 bits, beta 4, N 100)
+    _, truth = orc.exact_topk(X, Q, 10)
+    r_base, r_casc = orc.recall_at_k(base_ids, truth), orc.recall_at_k(ids, truth)
+    print(f"recall@10 plain {r_base:.4f}, cascade beta=3 N=100 {r_casc:.4f}")
+    assert abs(r_casc - r_base) <= 0.01
+    # and a pass 1 that is too coarse with too few kept does lose recall (the pin is not vacuous)
+    _, ids_bad = orc.cascade_search(idx, Q, 6, 10, 1, 10, orc.coarsened_codebook(c, tau, w.d, 1))
+    assert orc.recall_at_k(ids_bad, truth) < r_base - 0.02
+
+
+def test_cascade_on_the_refined_table_uses_primary_bits():
+    """With the sign bit stored, the merged (b+1)-bit code's top beta bits are the primary's top beta bits."""
+    b, d = 3, 24
+    c, tau = orc.lloyd_max_codebook(b, d)
+    levels, bnd = orc.refined_tables(c, tau, d)
+    for beta in (1, 2, 3):
+        np.testing.assert_allclose(orc.coarsened_codebook(levels, bnd, d, beta),
+                                   orc.coarsened_codebook(c, tau, d, beta), atol=1e-12)
