@@ -234,6 +234,23 @@ ivftq_status ivftq_profile_read(ivftq_index* index, double* ms_out, int64_t* lau
 int ivftq_profile_kernel_count(void);
 const char* ivftq_profile_kernel_name(int id);
 
+/* Cascade search (Appendix "Cascade search via Lloyd-Max bin ordinality"): pass 1 ranks every
+ * candidate of the probed lists from the top `beta` bits of each stored Stage-1 code, reconstructed
+ * with the coarsened codebook below, and keeps the n_keep best per query; pass 2 scores those with
+ * the full stored codes (Stage 1 and, if the index has it, the sign bit) and returns the k best,
+ * outputs as ivftq_search.  1 <= beta <= Stage-1 bits, k <= n_keep <= 2048.  Pass 1 reads the same
+ * packed words as the ordinary scan (the layout is not bit-sliced), so on this library it costs what
+ * ivftq_search costs at k = n_keep: a statement of the method, not a shortcut.  With n_keep at least
+ * the number of candidates, or beta equal to the Stage-1 bits, the result is that of ivftq_search.
+ * Candidates that tie in pass 1 at the n_keep-th place are kept in slot order. */
+ivftq_status ivftq_search_cascade(ivftq_index* index, const float* q_dev, int64_t nq, int nprobe, int k,
+                                  int beta, int n_keep, float* scores_dev, int64_t* ids_dev, void* stream);
+
+/* The coarsened codebook of pass 1 (host only): values_out[g], g < 2^beta, is the mean of the
+ * sphere-coordinate density over the union of the 2^(b-beta) Stage-1 bins whose codes start with g
+ * (with sign_bit != 0: computed from the merged 2^(b+1)-level table, the same numbers). */
+ivftq_status ivftq_build_coarsened_codebook(int b, int sign_bit, int d, int beta, float* values_out);
+
 /* Measurement aid: how many rows of the most recent ivftq_encode_add / ivftq_encode_only call on this
  * index the screening pass of the coarse assignment (float16 leading parts only) left undecided and
  * handed to the full-precision pass (Algorithm "Encode", coarse assignment step; the assignment is

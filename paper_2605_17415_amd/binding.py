@@ -61,6 +61,9 @@ _SIGNATURES = {
     "ivftq_profile_read": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
     "ivftq_profile_kernel_count": (C.c_int, []),
     "ivftq_profile_kernel_name": (C.c_char_p, [C.c_int]),
+    "ivftq_search_cascade": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_int,
+                                       C.c_void_p, C.c_void_p, C.c_void_p]),
+    "ivftq_build_coarsened_codebook": (C.c_int, [C.c_int, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_float)]),
     "ivftq_assign_undecided": (C.c_int, [C.c_void_p, C.POINTER(C.c_int64), C.c_void_p]),
     "ivftq_measure_mfma_rate": (C.c_int, [C.c_int, C.POINTER(C.c_double)]),
     "ivftq_last_error": (C.c_char_p, []),
@@ -147,6 +150,14 @@ def ivftq_build_refined_codebook(b: int, d: int):
     bd = np.empty(K2 - 1, np.float32)
     _check(lib.ivftq_build_refined_codebook(b, d, _np_ptr(lv), _np_ptr(bd)))
     return lv, bd
+
+
+def ivftq_build_coarsened_codebook(b: int, d: int, beta: int, sign_bit: bool = False):
+    """[2^beta] f32: values of the Stage-1 codebook cut down to its top beta bits (cascade pass 1)"""
+    out = np.empty(1 << max(0, min(beta, 15)), np.float32)
+    _check(load_library().ivftq_build_coarsened_codebook(b, 1 if sign_bit else 0, d, beta,
+                                                         out.ctypes.data_as(C.POINTER(C.c_float))))
+    return out
 
 
 def ivftq_quantiser_grid(b: int, d: int, sign_bit: bool = False):
@@ -345,6 +356,17 @@ class Index:
         _check(self._lib.ivftq_search(self._h, _dev_ptr(q, torch.float32, "q"), nq, nprobe, k,
                                       _dev_ptr(scores, torch.float32, "scores"), _dev_ptr(ids, torch.int64, "ids"),
                                       _stream_ptr(stream)))
+        return scores, ids
+
+    def search_cascade(self, q, nprobe: int, k: int, beta: int, n_keep: int, stream=None):
+        """Two-pass search: top-beta-bit scores keep n_keep candidates, full codes rank them."""
+        import torch
+        nq = q.shape[0]
+        scores = torch.empty((nq, k), dtype=torch.float32, device=q.device)
+        ids = torch.empty((nq, k), dtype=torch.int64, device=q.device)
+        _check(self._lib.ivftq_search_cascade(self._h, _dev_ptr(q, torch.float32, "q"), nq, nprobe, k, beta, n_keep,
+                                              _dev_ptr(scores, torch.float32, "scores"), _dev_ptr(ids, torch.int64, "ids"),
+                                              _stream_ptr(stream)))
         return scores, ids
 
     def coarse_probe(self, q, nprobe: int, stream=None):

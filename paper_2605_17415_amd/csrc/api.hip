@@ -76,12 +76,12 @@ struct PinnedBuf {
 // kernel classes for the optional per-launch timing
 enum ProfId { P_ASSIGN, P_COARSE_SCORES, P_ENCODE, P_ROTATE_Q, P_SEG_HIST, P_SEG_SCAN, P_RANK, P_PACK,
               P_COPY_LISTS, P_SELECT_PROBE, P_CAND_OFF, P_LIST_SCAN, P_SELECT_TOPK, P_KMEANS_UPDATE,
-              P_PAIR_GROUP, P_BATCH_FIRST, P_BATCH_SCAN, P_MERGE, P_COUNT };
+              P_PAIR_GROUP, P_BATCH_FIRST, P_BATCH_SCAN, P_MERGE, P_CASCADE, P_COUNT };
 const char* const kProfNames[P_COUNT] = {"coarse_assign", "coarse_scores", "encode_rotate_quantise_pack",
                                          "rotate_queries", "segment_hist", "segment_scan", "stable_rank",
                                          "pack_scatter", "copy_lists", "select_probes", "cand_offsets",
                                          "list_scan", "select_topk", "kmeans_update", "pair_grouping",
-                                         "batch_scan_nearest", "batch_scan", "merge_topk"};
+                                         "batch_scan_nearest", "batch_scan", "merge_topk", "cascade_rescore"};
 struct ProfRec { int id; hipEvent_t a, b; };
 // Timing events are recycled process-wide: creating one per launch costs more than the launch.
 std::mutex g_event_mutex;
@@ -114,6 +114,8 @@ struct ivftq_index {
     int64_t ntotal = 0;
     // workspace
     DevBuf w_assign, w_slot, w_order, w_hist, w_count, w_base, w_flag, w_best, w_undecided;
+    DevBuf cb_cascade, w_keep, w_keep_scores;   // cascade search: pass-1 table (for cascade_beta), kept slots and their pass-1 scores
+    int cascade_beta = 0;
     DevBuf w_S, w_probe, w_coarse, w_z, w_candoff, w_scores;
     DevBuf w_sums, w_counts, w_zero, w_rows, w_dst, w_obj;
     DevBuf w_zh, w_zl;
@@ -136,7 +138,7 @@ struct ivftq_index {
     ~ivftq_index() {
         for (ProfRec& r : prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
         for (DevBuf* bfr : {&cent, &cent_h, &cent_l, &pi_h, &pi_l, &bias, &pi, &cb, &q_grid, &codes, &gamma, &ids, &d_off, &d_size, &w_assign,
-                            &w_slot, &w_order, &w_hist, &w_count, &w_base, &w_flag, &w_best, &w_undecided, &w_S, &w_probe, &w_coarse,
+                            &w_slot, &w_order, &w_hist, &w_count, &w_base, &w_flag, &w_best, &w_undecided, &cb_cascade, &w_keep, &w_keep_scores, &w_S, &w_probe, &w_coarse,
                             &w_z, &w_candoff, &w_scores, &w_sums, &w_counts, &w_zero, &w_rows, &w_dst, &w_obj,
                             &w_first, &w_fscores, &w_fids, &w_pairs, &w_pairoff, &w_tileoff, &w_cscore,
                             &w_cslot, &w_ccnt, &w_gate, &w_zh, &w_zl})
@@ -1029,8 +1031,14 @@ ivftq_status ivftq_coarse_probe(ivftq_index* ix, const float* q_dev, int64_t nq,
     return IVFTQ_OK;
 }
 
-ivftq_status ivftq_search(ivftq_index* ix, const float* q_dev, int64_t nq, int nprobe, int k,
-                          float* scores_dev, int64_t* ids_dev, void* stream) {
+}  // extern "C"
+
+namespace {
+
+// The search proper.  cb: the 2^b reconstruction values the scans use; labels: label of every slot, or
+// null to return slot numbers instead (pass 1 of the cascade search, which needs to find the codes again).
+ivftq_status search_core(ivftq_index* ix, const float* q_dev, int64_t nq, int nprobe, int k, const float* cb,
+                         const int64_t* labels, float* scores_dev, int64_t* ids_dev, void* stream) {
     ivftq_status s = check_query_args(ix, q_dev, nq, nprobe);
     if (s != IVFTQ_OK) return s;
     if (k < 1) return fail(IVFTQ_INVALID_ARG, "k=%d below 1", k);
@@ -1097,7 +1105,7 @@ ivftq_status ivftq_search(ivftq_index* ix, const float* q_dev, int64_t nq, int n
             return launch_cand_offsets(ix->w_probe.as<int32_t>(), cnt, nprobe, ix->d_size.as<int32_t>(),
                                        ix->w_candoff.as<int32_t>(), k, cap, first, st); }));
         auto stream_scan = [&](const int32_t* p_limit, const int32_t* gate, int blocks_per_query) {
-            return launch_list_scan(ix->w_z.as<float>(), ix->dp, ix->d, ix->b, ix->cb.as<float>(),
+            return launch_list_scan(ix->w_z.as<float>(), ix->dp, ix->d, ix->b, cb,
                                     ix->w_probe.as<int32_t>(), ix->w_coarse.as<float>(),
                                     ix->w_candoff.as<int32_t>(), nprobe, ix->store(), 0, cnt,
                                     ix->w_scores.as<float>(), m_stride, p_limit, gate, blocks_per_query, st);
@@ -1106,7 +1114,7 @@ ivftq_status ivftq_search(ivftq_index* ix, const float* q_dev, int64_t nq, int n
         sa.vals = ix->w_scores.as<float>(); sa.stride = m_stride; sa.rows = cnt; sa.k = k;
         sa.cand_off = ix->w_candoff.as<int32_t>(); sa.probe = ix->w_probe.as<int32_t>(); sa.np = nprobe;
         sa.q_begin = 0;
-        sa.list_off = ix->d_off.as<int64_t>(); sa.ids = ix->ids.as<int64_t>();
+        sa.list_off = ix->d_off.as<int64_t>(); sa.ids = labels;
         sa.out_vals = scores_dev + q0 * k; sa.out_i64 = ids_dev + q0 * k;
         sa.m_bound = (int)m_stride;
 
@@ -1131,7 +1139,7 @@ ivftq_status ivftq_search(ivftq_index* ix, const float* q_dev, int64_t nq, int n
             return e; }));
         BatchScanArgs ba{};
         ba.zh = ix->w_zh.as<uint16_t>(); ba.zl = ix->w_zl.as<uint16_t>(); ba.z_pitch = ix->dp;
-        ba.cb = ix->cb.as<float>();
+        ba.cb = cb;
         ba.pairs = ix->w_pairs.as<int32_t>(); ba.pair_off = ix->w_pairoff.as<int64_t>();
         ba.tile_off = ix->w_tileoff.as<int32_t>();
         ba.coarse = ix->w_coarse.as<float>();
@@ -1157,7 +1165,7 @@ ivftq_status ivftq_search(ivftq_index* ix, const float* q_dev, int64_t nq, int n
         MergeArgs ma{};
         ma.first_scores = ix->w_fscores.as<float>(); ma.first_ids = ix->w_fids.as<int64_t>();
         ma.cand_score = ix->w_cscore.as<float>(); ma.cand_slot = ix->w_cslot.as<int64_t>();
-        ma.cand_cnt = ix->w_ccnt.as<int32_t>(); ma.cap = cap; ma.ids = ix->ids.as<int64_t>();
+        ma.cand_cnt = ix->w_ccnt.as<int32_t>(); ma.cap = cap; ma.ids = labels;
         ma.k = k; ma.out_scores = scores_dev + q0 * k; ma.out_ids = ids_dev + q0 * k;
         ma.gate = ix->w_gate.as<int32_t>();
         HIP_TRY(timed(ix, st, P_MERGE, [&] { return launch_merge(ma, cnt, st); }));
@@ -1166,6 +1174,86 @@ ivftq_status ivftq_search(ivftq_index* ix, const float* q_dev, int64_t nq, int n
         s2.gate = ix->w_gate.as<int32_t>();
         HIP_TRY(timed(ix, st, P_SELECT_TOPK, [&] { return launch_select(1, s2, st); }));
     }
+    return IVFTQ_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+ivftq_status ivftq_search(ivftq_index* ix, const float* q_dev, int64_t nq, int nprobe, int k,
+                          float* scores_dev, int64_t* ids_dev, void* stream) {
+    if (check_index(ix)) return IVFTQ_INVALID_ARG;
+    return search_core(ix, q_dev, nq, nprobe, k, ix->cb.as<float>(), ix->ids.as<int64_t>(), scores_dev, ids_dev, stream);
+}
+
+ivftq_status ivftq_build_coarsened_codebook(int b, int sign_bit, int d, int beta, float* values_out) {
+    if (!values_out) return fail(IVFTQ_INVALID_ARG, "values_out is NULL");
+    std::vector<double> lv, bd;
+    const bool ok = sign_bit ? build_refined_codebook(b, d, lv, bd) : build_codebook(b, d, lv, bd);
+    if (!ok) return fail(IVFTQ_INVALID_ARG, "no codebook for b=%d d=%d", b, d);
+    if (beta < 1 || beta > b) return fail(IVFTQ_INVALID_ARG, "beta=%d outside [1, %d]", beta, b);
+    std::vector<double> out;
+    if (!build_coarsened_levels(d, lv, bd, beta, out)) return fail(IVFTQ_INVALID_ARG, "no coarsened codebook for these parameters");
+    for (size_t i = 0; i < out.size(); ++i) values_out[i] = (float)out[i];
+    return IVFTQ_OK;
+}
+
+ivftq_status ivftq_search_cascade(ivftq_index* ix, const float* q_dev, int64_t nq, int nprobe, int k, int beta,
+                                  int n_keep, float* scores_dev, int64_t* ids_dev, void* stream) {
+    ivftq_status s = check_query_args(ix, q_dev, nq, nprobe);
+    if (s != IVFTQ_OK) return s;
+    const int b1 = ix->b - (ix->sign_bit ? 1 : 0);
+    if (beta < 1 || beta > b1) return fail(IVFTQ_INVALID_ARG, "beta=%d outside [1, %d]", beta, b1);
+    if (k < 1 || k > n_keep) return fail(IVFTQ_INVALID_ARG, "k=%d outside [1, n_keep=%d]", k, n_keep);
+    if (n_keep > kMaxK) return fail(IVFTQ_UNSUPPORTED, "n_keep=%d above %d", n_keep, kMaxK);
+    if (nq == 0) return IVFTQ_OK;
+    if (!scores_dev || !ids_dev) return fail(IVFTQ_INVALID_ARG, "output pointer is NULL");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+
+    // pass-1 table over the full code: entry e holds the value of the merged bin e >> (bits - beta)
+    if (ix->cascade_beta != beta) {
+        std::vector<double> lv(ix->h_cb.begin(), ix->h_cb.end()), bd(ix->h_tau.begin(), ix->h_tau.end()), cc;
+        if (!build_coarsened_levels(ix->d, lv, bd, beta, cc)) return fail(IVFTQ_INVALID_ARG, "no coarsened codebook for these parameters");
+        std::vector<float> table(ix->K);
+        for (int e = 0; e < ix->K; ++e) table[e] = (float)cc[e >> (ix->b - beta)];
+        HIP_TRY(ix->cb_cascade.ensure((size_t)ix->K * sizeof(float)));
+        HIP_TRY(hipMemcpyAsync(ix->cb_cascade.p, table.data(), table.size() * sizeof(float), hipMemcpyHostToDevice, st));
+        HIP_TRY(hipStreamSynchronize(st));       // table is a local
+        ix->cascade_beta = beta;
+    }
+    HIP_TRY(ix->w_keep.ensure((size_t)nq * n_keep * sizeof(int64_t)));
+    HIP_TRY(ix->w_keep_scores.ensure((size_t)nq * n_keep * sizeof(float)));
+    // pass 1: the ordinary search on the coarsened values, n_keep slots per query
+    s = search_core(ix, q_dev, nq, nprobe, n_keep, ix->cb_cascade.as<float>(), nullptr,
+                    ix->w_keep_scores.as<float>(), ix->w_keep.as<int64_t>(), stream);
+    if (s != IVFTQ_OK) return s;
+    // pass 2: the kept candidates on the full codes.  Probes, coarse terms and rotated queries are
+    // recomputed per chunk by search_core, so they are produced once more here for all queries.
+    HIP_TRY(ix->w_probe.ensure((size_t)nq * nprobe * sizeof(int32_t)));
+    HIP_TRY(ix->w_coarse.ensure((size_t)nq * nprobe * sizeof(float)));
+    HIP_TRY(ix->w_z.ensure((size_t)nq * ix->dp * sizeof(float)));
+    const int64_t ldS = round_up(ix->nlist, 4);
+    int64_t qc = std::max<int64_t>(1, std::min<int64_t>(ix->ws_limit / (4 * ldS), std::min<int64_t>(nq, 32768)));
+    HIP_TRY(ix->w_S.ensure((size_t)qc * ldS * sizeof(float)));
+    for (int64_t q0 = 0; q0 < nq; q0 += qc) {
+        const int64_t cnt = std::min(qc, nq - q0);
+        s = coarse_and_probe(ix, q_dev + q0 * ix->d, cnt, nprobe, ix->w_probe.as<int32_t>() + q0 * nprobe,
+                             ix->w_coarse.as<float>() + q0 * nprobe, st);
+        if (s != IVFTQ_OK) return s;
+    }
+    EncodeArgs ea{};
+    ea.x = q_dev; ea.n = nq; ea.d = ix->d; ea.b = ix->b;
+    ea.pi_h = ix->pi_h.as<uint16_t>(); ea.pi_l = ix->pi_l.as<uint16_t>(); ea.zout = ix->w_z.as<float>();
+    HIP_TRY(timed(ix, st, P_ROTATE_Q, [&] { return launch_encode(2, ea, st); }));
+    CascadeArgs ca{};
+    ca.z = ix->w_z.as<float>(); ca.z_pitch = ix->dp; ca.d = ix->d; ca.b = ix->b;
+    ca.cb = ix->cb.as<float>();
+    ca.probe = ix->w_probe.as<int32_t>(); ca.coarse = ix->w_coarse.as<float>(); ca.np = nprobe;
+    ca.store = ix->store(); ca.ids = ix->ids.as<int64_t>();
+    ca.cand = ix->w_keep.as<int64_t>(); ca.n_keep = n_keep; ca.k = k;
+    ca.out_scores = scores_dev; ca.out_ids = ids_dev;
+    HIP_TRY(timed(ix, st, P_CASCADE, [&] { return launch_cascade_rescore(ca, nq, st); }));
     return IVFTQ_OK;
 }
 

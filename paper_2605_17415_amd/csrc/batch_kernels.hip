@@ -402,7 +402,8 @@ __global__ __launch_bounds__(256) void k_merge(MergeArgs a) {
             if (lab >= 0) key = okey(v); else lab = INT64_MAX;
         } else if (i < total) {
             v = a.cand_score[q * a.cap + (i - a.k)];
-            lab = a.ids[a.cand_slot[q * a.cap + (i - a.k)]];
+            const int64_t slot = a.cand_slot[q * a.cap + (i - a.k)];
+            lab = a.ids ? a.ids[slot] : slot;
             key = okey(v);
         }
         s_key[i] = key; s_val[i] = v; s_lab[i] = lab;

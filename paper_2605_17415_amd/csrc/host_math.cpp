@@ -189,6 +189,29 @@ bool build_refined_codebook(int b, int d, std::vector<double>& levels, std::vect
     return true;
 }
 
+bool build_coarsened_levels(int d, const std::vector<double>& levels, const std::vector<double>& boundaries,
+                            int beta, std::vector<double>& out) {
+    const size_t K = levels.size();
+    int bits = 0;
+    while (((size_t)1 << bits) < K) ++bits;
+    if (K < 2 || ((size_t)1 << bits) != K || boundaries.size() != K - 1 || beta < 1 || beta > bits || d < 3) return false;
+    SphereMarginal f(d);
+    const size_t group = (size_t)1 << (bits - beta);
+    out.assign((size_t)1 << beta, 0.0);
+    for (size_t g = 0; g < out.size(); ++g) {
+        double m0 = 0.0, m1 = 0.0;
+        for (size_t i = g * group; i < (g + 1) * group; ++i) {
+            const double lo = i == 0 ? -1.0 : boundaries[i - 1], hi = i == K - 1 ? 1.0 : boundaries[i];
+            const double m = f.mass(lo, hi);
+            m0 += m;
+            m1 += m * levels[i];
+        }
+        if (!(m0 > 0.0)) return false;
+        out[g] = m1 / m0;
+    }
+    return true;
+}
+
 // ---- random numbers for the rotation draw ------------------------------------------------
 
 static inline uint64_t splitmix64(uint64_t& s) {

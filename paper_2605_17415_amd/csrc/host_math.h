@@ -14,6 +14,13 @@ bool build_codebook(int b, int d, std::vector<double>& centroids, std::vector<do
 // that #{boundaries <= v} = 2*code + 1[v >= c_code].
 bool build_refined_codebook(int b, int d, std::vector<double>& levels, std::vector<double>& boundaries);
 
+// Codebook for the top beta bits of a code whose full table is (levels, boundaries), 2^bits levels
+// (Appendix "Cascade search via Lloyd-Max bin ordinality", pass 1): dropping the low bits merges
+// 2^(bits-beta) neighbouring bins, and a merged bin takes the mean of the sphere-coordinate density
+// over it, the mass-weighted mean of its members' levels.  out has 2^beta entries.
+bool build_coarsened_levels(int d, const std::vector<double>& levels, const std::vector<double>& boundaries,
+                            int beta, std::vector<double>& out);
+
 // d x d iid N(0,1), row-major, from a 64-bit seed.
 void gaussian_matrix(int d, uint64_t seed, std::vector<double>& g);
 

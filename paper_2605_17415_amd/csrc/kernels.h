@@ -182,6 +182,20 @@ struct RerankArgs {
 };
 hipError_t launch_rerank(const RerankArgs& a, int64_t nq, hipStream_t st);
 
+// Pass 2 of the cascade search: the candidates of each query (slot numbers, -1 = none) are scored
+// with the full codes, score = coarse term of the candidate's list + gamma * sum_j z_j cb[code_j],
+// and the k best by (score desc, label asc) are written out.
+struct CascadeArgs {
+    const float* z; int z_pitch; int d; int b;
+    const float* cb;                       // 2^b levels
+    const int32_t* probe; const float* coarse; int np;     // [nq][np]
+    ListStore store;
+    const int64_t* ids;                    // label of a slot
+    const int64_t* cand; int n_keep; int k;
+    float* out_scores; int64_t* out_ids;
+};
+hipError_t launch_cascade_rescore(const CascadeArgs& a, int64_t nq, hipStream_t st);
+
 // ---- query-batched scan ------------------------------------------------------------------------
 
 // Queries one workgroup of the batched scan takes per tile for this (d, b); 0 = shape not covered

@@ -252,7 +252,8 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a) {
                 if (off[mid] <= (int32_t)col) lo = mid; else hi = mid;
             }
             const int l = a.probe[q * a.np + lo];
-            s_lab[i] = a.ids[a.list_off[l] + ((int32_t)col - off[lo])];
+            const int64_t slot = a.list_off[l] + ((int32_t)col - off[lo]);
+            s_lab[i] = a.ids ? a.ids[slot] : slot;       // without a label table the slot itself is the result
         }
     }
     __syncthreads();
@@ -423,7 +424,10 @@ __global__ __launch_bounds__(256) void k_select_small(SelectArgs a) {
                 if (o <= out_c) { rank = base + t; rank_off = o; }
             }
         }
-        if (out_c >= 0) lab = a.ids[a.list_off[a.probe[q * a.np + rank]] + (out_c - rank_off)];
+        if (out_c >= 0) {
+            const int64_t slot = a.list_off[a.probe[q * a.np + rank]] + (out_c - rank_off);
+            lab = a.ids ? a.ids[slot] : slot;
+        }
     }
     uint32_t key = out_c >= 0 ? key_of(out_v) : 0u;
 #pragma unroll
@@ -531,7 +535,103 @@ __global__ __launch_bounds__(256) void k_rerank(RerankArgs a) {
     }
 }
 
+// ---- cascade search, pass 2 (Appendix "Cascade search via Lloyd-Max bin ordinality") ------------
+//
+// One workgroup per query.  Each wavefront takes kept candidates in turn: finds the probed list that
+// holds the slot (lanes over the query's probes), then lane j sums the coordinates j, j+64, ... from
+// the packed words; the workgroup sorts (score desc, label asc) in LDS and emits the k best.
+__global__ __launch_bounds__(256) void k_cascade_rescore(CascadeArgs a) {
+    extern __shared__ unsigned char smem[];
+    int size = 1;
+    while (size < a.n_keep) size <<= 1;
+    uint32_t* s_key = reinterpret_cast<uint32_t*>(smem);
+    float* s_val = reinterpret_cast<float*>(s_key + size);
+    int64_t* s_lab = reinterpret_cast<int64_t*>(s_val + size);
+    const int64_t q = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint32_t mask = (1u << a.b) - 1u;
+    float zr[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const int j = lane + 64 * e;
+        zr[e] = j < a.d ? a.z[q * a.z_pitch + j] : 0.f;
+    }
+    for (int c = wave; c < size; c += 4) {
+        const int64_t slot = c < a.n_keep ? a.cand[q * a.n_keep + c] : -1;
+        int p_found = -1;
+        if (slot >= 0) {
+            for (int base = 0; base < a.np && p_found < 0; base += 64) {
+                const int p = base + lane;
+                bool hit = false;
+                if (p < a.np) {
+                    const int l = a.probe[q * a.np + p];
+                    const int64_t off = a.store.list_off[l];
+                    hit = slot >= off && slot < off + a.store.list_size[l];
+                }
+                const unsigned long long m = __ballot(hit);
+                if (m) p_found = base + __ffsll((long long)m) - 1;
+            }
+        }
+        float acc = 0.f;
+        if (p_found >= 0) {
+            const uint32_t* wp = a.store.codes + (slot >> 6) * a.store.words * 64 + (slot & 63);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int j = lane + 64 * e;
+                if (j < a.d) {
+                    const int bit = j * a.b, w = bit >> 5, o = bit & 31;
+                    uint32_t v = wp[(int64_t)w * 64] >> o;
+                    if (o + a.b > 32) v |= wp[(int64_t)(w + 1) * 64] << (32 - o);
+                    acc += zr[e] * a.cb[v & mask];
+                }
+            }
+        }
+        for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
+        if (lane == 0) {
+            const bool ok = p_found >= 0;
+            float sc = -__builtin_inff();
+            if (ok) sc = a.coarse[q * a.np + p_found] + __half2float(__ushort_as_half(a.store.gamma[slot])) * acc;
+            s_key[c] = (ok && sc == sc) ? order_key(sc) : 0u;
+            s_val[c] = sc;
+            s_lab[c] = ok ? a.ids[slot] : INT64_MAX;
+        }
+    }
+    __syncthreads();
+    for (int sz = 2; sz <= size; sz <<= 1) {
+        for (int stride = sz >> 1; stride > 0; stride >>= 1) {
+            for (int i = tid; i < size / 2; i += 256) {
+                const int lo_i = 2 * i - (i & (stride - 1));
+                const int hi_i = lo_i + stride;
+                const bool up = ((lo_i & sz) == 0);
+                const uint32_t k0 = s_key[lo_i], k1 = s_key[hi_i];
+                const int64_t l0 = s_lab[lo_i], l1 = s_lab[hi_i];
+                const bool first_before = (k0 > k1) || (k0 == k1 && l0 <= l1);
+                if (first_before != up) {
+                    s_key[lo_i] = k1; s_key[hi_i] = k0;
+                    s_lab[lo_i] = l1; s_lab[hi_i] = l0;
+                    const float v0 = s_val[lo_i]; s_val[lo_i] = s_val[hi_i]; s_val[hi_i] = v0;
+                }
+            }
+            __syncthreads();
+        }
+    }
+    for (int i = tid; i < a.k; i += 256) {
+        const bool real = i < size && s_key[i] != 0u;
+        a.out_scores[q * a.k + i] = real ? s_val[i] : -__builtin_inff();
+        a.out_ids[q * a.k + i] = real ? s_lab[i] : -1;
+    }
+}
+
 }  // namespace
+
+hipError_t launch_cascade_rescore(const CascadeArgs& a, int64_t nq, hipStream_t st) {
+    if (nq <= 0) return hipSuccess;
+    int size = 1;
+    while (size < a.n_keep) size <<= 1;
+    const size_t lds = (size_t)size * 16;
+    hipLaunchKernelGGL(k_cascade_rescore, dim3((unsigned)nq), dim3(256), lds, st, a);
+    return hipGetLastError();
+}
 
 hipError_t launch_rerank(const RerankArgs& a, int64_t nq, hipStream_t st) {
     if (nq <= 0) return hipSuccess;

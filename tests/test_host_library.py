@@ -150,3 +150,17 @@ def test_refined_codebook_matches_oracle_and_its_grid_counts_exactly(b, d):
     for nudge in (0.0, -0.2, 0.2):
         cell = np.clip(np.trunc(x.astype(np.float64) + nudge), 0, cells - 1).astype(np.int64)
         np.testing.assert_array_equal(index[cell] + (v >= boundary[cell]), np.searchsorted(bd, v, side="right"))
+
+
+@pytest.mark.parametrize("b,d,beta,sign_bit", [(4, 128, 2, False), (5, 96, 4, True), (3, 16, 1, False), (4, 96, 4, False)])
+def test_coarsened_codebook_matches_oracle(b, d, beta, sign_bit):
+    """Cascade pass-1 table (Appendix "Cascade search"): conditional means of the merged bins."""
+    import paper_2605_17415_amd as pkg
+    c, tau = orc.lloyd_max_codebook(b, d)
+    want = orc.coarsened_codebook(c, tau, d, beta)
+    got = pkg.ivftq_build_coarsened_codebook(b, d, beta, sign_bit)
+    np.testing.assert_allclose(got, want, rtol=0, atol=3e-8)
+    with pytest.raises(pkg.IvftqError):
+        pkg.ivftq_build_coarsened_codebook(b, d, b + 1, sign_bit)
+    with pytest.raises(pkg.IvftqError):
+        pkg.ivftq_build_coarsened_codebook(b, d, 0, sign_bit)
