@@ -1066,6 +1066,10 @@ ivftq_status search_core(ivftq_index* ix, const float* q_dev, int64_t nq, int np
     const bool batched = tq > 0 && nprobe > 1 &&
                          (ix->search_mode == 2 || (ix->search_mode == 0 && qc * nprobe >= (int64_t)16 * ix->nlist));
     const int cap = std::min(2048, std::max(512, 16 * k));
+    // error bound of a residual sum taken from the leading float16 parts alone (threshold pass)
+    float cmax = 0.f;
+    for (float v : ix->h_cb) cmax = std::max(cmax, std::fabs(v));
+    const float kappa = screen_kappa(ix->d, cmax);
 
     HIP_TRY(ix->w_S.ensure((size_t)qc * ldS * sizeof(float)));
     HIP_TRY(ix->w_scores.ensure((size_t)qc * m_stride * sizeof(float)));
@@ -1146,6 +1150,7 @@ ivftq_status search_core(ivftq_index* ix, const float* q_dev, int64_t nq, int np
         ba.store = ix->store(); ba.np = nprobe; ba.L = ix->nlist;
         ba.cand_score = ix->w_cscore.as<float>(); ba.cand_slot = ix->w_cslot.as<int64_t>();
         ba.cand_cnt = ix->w_ccnt.as<int32_t>(); ba.cap = cap;
+        ba.acc0 = kappa * kSplitScale * kSplitScale;
         ba.scores = ix->w_scores.as<float>(); ba.m_stride = m_stride; ba.cand_off = ix->w_candoff.as<int32_t>();
         const int max_tiles = (int)(np_items / tq) + ix->nlist;
         // 2. every score of the nearest lists, then their top-k: the k-th is the query's threshold
@@ -1166,6 +1171,9 @@ ivftq_status search_core(ivftq_index* ix, const float* q_dev, int64_t nq, int np
         ma.first_scores = ix->w_fscores.as<float>(); ma.first_ids = ix->w_fids.as<int64_t>();
         ma.cand_score = ix->w_cscore.as<float>(); ma.cand_slot = ix->w_cslot.as<int64_t>();
         ma.cand_cnt = ix->w_ccnt.as<int32_t>(); ma.cap = cap; ma.ids = labels;
+        ma.kappa = kappa;
+        ma.z = ix->w_z.as<float>(); ma.z_pitch = ix->dp; ma.d = ix->d; ma.b = ix->b; ma.cb = cb;
+        ma.coarse = ix->w_coarse.as<float>(); ma.np = nprobe; ma.store = ix->store();
         ma.k = k; ma.out_scores = scores_dev + q0 * k; ma.out_ids = ids_dev + q0 * k;
         ma.gate = ix->w_gate.as<int32_t>();
         HIP_TRY(timed(ix, st, P_MERGE, [&] { return launch_merge(ma, cnt, st); }));

@@ -153,7 +153,7 @@ struct BatchCfg {
     static constexpr int TQ = NQ * 32;
     static constexpr int LDH = DP + 8;            // halves per panel row: 16-byte pad keeps b128 reads conflict free
     static constexpr int PT = 1 << (2 * B);       // entries of the code-pair tables
-    static constexpr size_t lds_bytes = (size_t)TQ * LDH * 2 * sizeof(uint16_t) + 3 * TQ * sizeof(float) + 2 * PT * 4;   // panels + per-query words + pair tables
+    static constexpr size_t lds_bytes = (size_t)TQ * LDH * 2 * sizeof(uint16_t) + 4 * TQ * sizeof(float) + 2 * PT * 4;   // panels + per-query words + pair tables
 };
 
 // WAVES = wavefronts per workgroup, OCC = wavefronts per SIMD the register budget is set for.
@@ -161,6 +161,10 @@ struct BatchCfg {
 // column operand, so a lane holds one vector's scores against 16 queries and the stores of a
 // query's scores coalesce.  Otherwise (threshold pass) the roles are swapped: a lane holds one
 // query's scores against 16 vectors and needs that query's coarse term and threshold only once.
+// The threshold pass multiplies the leading float16 parts only (one product instead of three): the
+// accumulator starts at acc0 = 2^20 * kappa, kappa bounding the error of such a sum for a unit query, so
+// what is compared with the threshold and appended is an upper bound of the true score (true score in
+// [u - 2*kappa*gamma, u]); k_merge re-scores from the packed codes the few that can still matter.
 template <int DP, int B, int NQ, int WAVES, int OCC, bool DENSE>
 __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(OCC)))
 void k_batch_scan(BatchScanArgs a) {
@@ -173,7 +177,8 @@ void k_batch_scan(BatchScanArgs a) {
     float* s_coarse = reinterpret_cast<float*>(zl + Cfg::TQ * Cfg::LDH);   // [TQ]
     float* s_thr = s_coarse + Cfg::TQ;                              // [TQ] threshold, or (dense) offset of the pair's scores
     int32_t* s_q = reinterpret_cast<int32_t*>(s_thr + Cfg::TQ);     // [TQ]
-    uint32_t* tab_h = reinterpret_cast<uint32_t*>(s_q + Cfg::TQ);   // [PT] hi parts of a code pair, packed
+    int32_t* s_p = s_q + Cfg::TQ;                                   // [TQ] probe rank of the pair
+    uint32_t* tab_h = reinterpret_cast<uint32_t*>(s_p + Cfg::TQ);   // [PT] hi parts of a code pair, packed
     uint32_t* tab_l = tab_h + Cfg::PT;                              // [PT] lo parts
 
     const int tid = threadIdx.x;
@@ -198,16 +203,18 @@ void k_batch_scan(BatchScanArgs a) {
 
     // stage the query panel and the code-pair tables
     for (int e = tid; e < Cfg::TQ; e += NT) {
-        int32_t q = -1;
+        int32_t q = -1, pr = 0;
         float sc = 0.f, th = __builtin_inff();
         if (e < nq_tile) {
             const int32_t it = a.pairs[pair0 + e];
             q = it / a.np;
+            pr = it - q * a.np;
             sc = a.coarse[it];
             if (DENSE) th = __int_as_float(a.cand_off[(int64_t)q * (a.np + 1) + (it - q * a.np)]);
             else th = a.thresh[(int64_t)q * a.thresh_stride];
         }
         s_q[e] = q;
+        s_p[e] = pr;
         s_coarse[e] = sc;
         s_thr[e] = th;
     }
@@ -222,7 +229,7 @@ void k_batch_scan(BatchScanArgs a) {
             lp |= (uint32_t)__builtin_bit_cast(uint16_t, lo) << (16 * t);
         }
         tab_h[e] = hp;
-        tab_l[e] = lp;
+        if (DENSE) tab_l[e] = lp;
     }
     __syncthreads();
     for (int e = tid; e < Cfg::TQ * (DP / 8); e += NT) {           // 16-byte pieces
@@ -231,10 +238,10 @@ void k_batch_scan(BatchScanArgs a) {
         const int32_t q = s_q[r];
         if (q >= 0) {
             vh = *reinterpret_cast<const uint4*>(a.zh + (int64_t)q * a.z_pitch + c8 * 8);
-            vl = *reinterpret_cast<const uint4*>(a.zl + (int64_t)q * a.z_pitch + c8 * 8);
+            if (DENSE) vl = *reinterpret_cast<const uint4*>(a.zl + (int64_t)q * a.z_pitch + c8 * 8);
         }
         *reinterpret_cast<uint4*>(zh + r * Cfg::LDH + c8 * 8) = vh;
-        *reinterpret_cast<uint4*>(zl + r * Cfg::LDH + c8 * 8) = vl;
+        if (DENSE) *reinterpret_cast<uint4*>(zl + r * Cfg::LDH + c8 * 8) = vl;
     }
     __syncthreads();
 
@@ -293,7 +300,7 @@ void k_batch_scan(BatchScanArgs a) {
             for (int t = 0; t < 4; ++t) {
                 const uint32_t idx = (uint32_t)(chunk >> (2 * B * t)) & (uint32_t)(Cfg::PT - 1);
                 hv[t] = tab_h[idx];
-                lv[t] = tab_l[idx];
+                lv[t] = DENSE ? tab_l[idx] : 0u;
             }
             ah[kb] = __builtin_bit_cast(half8, make_uint4(hv[0], hv[1], hv[2], hv[3]));
             al[kb] = __builtin_bit_cast(half8, make_uint4(lv[0], lv[1], lv[2], lv[3]));
@@ -308,12 +315,16 @@ void k_batch_scan(BatchScanArgs a) {
         for (int qt = 0; qt < n_qt; ++qt) {
             floatx16 acc;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+            for (int r = 0; r < 16; ++r) acc[r] = DENSE ? 0.f : a.acc0;
             const uint16_t* bhq = bh_base + qt * 32 * Cfg::LDH;
             const uint16_t* blq = bl_base + qt * 32 * Cfg::LDH;
 #pragma unroll
             for (int kb = 0; kb < KB; ++kb) {
                 const half8 bh = *reinterpret_cast<const half8*>(bhq + 16 * kb);
+                if (!DENSE) {
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah[kb], bh, acc, 0, 0, 0);
+                    continue;
+                }
                 const half8 bl = *reinterpret_cast<const half8*>(blq + 16 * kb);
                 if (DENSE) {
                     acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(bh, ah[kb], acc, 0, 0, 0);
@@ -344,7 +355,7 @@ void k_batch_scan(BatchScanArgs a) {
             float best = -__builtin_inff();
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                sc[r] = fmaf(g[r], acc[r], sq);    // NaN (row beyond the list) never passes
+                sc[r] = fmaf(g[r], acc[r], sq);    // upper bound of the score; NaN (row beyond the list) never passes
                 best = fmaxf(best, sc[r]);         // fmaxf ignores NaN
             }
             if (best >= th && q >= 0) {            // rare: some row of this lane reaches the threshold
@@ -355,7 +366,7 @@ void k_batch_scan(BatchScanArgs a) {
                         const int pos = atomicAdd(&a.cand_cnt[q], 1);
                         if (pos < a.cap) {
                             a.cand_score[(int64_t)q * a.cap + pos] = sc[r];
-                            a.cand_slot[(int64_t)q * a.cap + pos] = base_slot + v;
+                            a.cand_slot[(int64_t)q * a.cap + pos] = (base_slot + v) | ((int64_t)s_p[e] << kCandProbeShift);
                         }
                     }
                 }
@@ -378,10 +389,44 @@ __device__ __forceinline__ uint32_t okey(float f) {
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
+// ---- merge: first-pass top-k and threshold-pass candidates -> the k best --------------------------
+//
+// One workgroup per query.  First-pass entries carry exact scores; a candidate carries an upper bound u
+// of its score, the score itself lying in [u - 2*kappa*gamma, u].  All entries are sorted by upper bound;
+// with e the largest 2*kappa*gamma among the candidates, R = (k-th largest upper bound) - e is a lower
+// bound of the k-th largest score, so only the entries with u >= R (a prefix of the sorted order, a few
+// more than k) can be among the k best.  Those are re-scored from the packed codes in float32 (each
+// wavefront takes entries in turn, lane j sums coordinates j, j+64, ...), sorted again by (score desc,
+// label asc) and the k best written.  A query whose candidate list overflowed is appended to the gate list.
+__device__ __forceinline__ void merge_sort_desc(uint32_t* s_key, float* s_val, int64_t* s_lab, uint8_t* s_flag,
+                                                int size, int tid, bool by_label) {
+    for (int sz = 2; sz <= size; sz <<= 1) {
+        for (int stride = sz >> 1; stride > 0; stride >>= 1) {
+            for (int i = tid; i < size / 2; i += 256) {
+                const int lo_i = 2 * i - (i & (stride - 1));
+                const int hi_i = lo_i + stride;
+                const bool up = ((lo_i & sz) == 0);
+                const uint32_t k0 = s_key[lo_i], k1 = s_key[hi_i];
+                const int64_t l0 = s_lab[lo_i], l1 = s_lab[hi_i];
+                const bool first_before = (k0 > k1) || (k0 == k1 && (!by_label || l0 <= l1));
+                if (first_before != up) {
+                    s_key[lo_i] = k1; s_key[hi_i] = k0;
+                    s_lab[lo_i] = l1; s_lab[hi_i] = l0;
+                    const float t = s_val[lo_i]; s_val[lo_i] = s_val[hi_i]; s_val[hi_i] = t;
+                    const uint8_t f = s_flag[lo_i]; s_flag[lo_i] = s_flag[hi_i]; s_flag[hi_i] = f;
+                }
+            }
+            __syncthreads();
+        }
+    }
+}
+
 __global__ __launch_bounds__(256) void k_merge(MergeArgs a) {
     extern __shared__ unsigned char smem[];
+    __shared__ float s_emax;
+    __shared__ int s_prefix;
     const int64_t q = blockIdx.x;
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int cnt = a.cand_cnt[q];
     const bool overflow = cnt > a.cap;
     if (tid == 0 && overflow) a.gate[1 + atomicAdd(&a.gate[0], 1)] = (int32_t)q;   // listed for the exact pass
@@ -391,44 +436,87 @@ __global__ __launch_bounds__(256) void k_merge(MergeArgs a) {
     while (size < total) size <<= 1;
     uint32_t* s_key = reinterpret_cast<uint32_t*>(smem);
     float* s_val = reinterpret_cast<float*>(s_key + size);
-    int64_t* s_lab = reinterpret_cast<int64_t*>(s_val + size);
+    int64_t* s_lab = reinterpret_cast<int64_t*>(s_val + size);     // label, or (flag 1) the packed slot of a candidate
+    uint8_t* s_flag = reinterpret_cast<uint8_t*>(s_lab + size);    // 1: candidate whose score is still an upper bound
+    if (tid == 0) { s_emax = 0.f; s_prefix = 0; }
+    __syncthreads();
+    float emax = 0.f;
     for (int i = tid; i < size; i += 256) {
         float v = -__builtin_inff();
         int64_t lab = INT64_MAX;
         uint32_t key = 0;
+        uint8_t flag = 0;
         if (i < a.k) {
             lab = a.first_ids[q * a.k + i];
             v = a.first_scores[q * a.k + i];
             if (lab >= 0) key = okey(v); else lab = INT64_MAX;
         } else if (i < total) {
             v = a.cand_score[q * a.cap + (i - a.k)];
-            const int64_t slot = a.cand_slot[q * a.cap + (i - a.k)];
-            lab = a.ids ? a.ids[slot] : slot;
+            lab = a.cand_slot[q * a.cap + (i - a.k)];
+            const int64_t slot = lab & (((int64_t)1 << kCandProbeShift) - 1);
+            emax = fmaxf(emax, 2.f * a.kappa * __half2float(__ushort_as_half(a.store.gamma[slot])));
             key = okey(v);
+            flag = 1;
         }
-        s_key[i] = key; s_val[i] = v; s_lab[i] = lab;
+        s_key[i] = key; s_val[i] = v; s_lab[i] = lab; s_flag[i] = flag;
+    }
+    for (int o = 32; o > 0; o >>= 1) emax = fmaxf(emax, __shfl_xor(emax, o));
+    if (lane == 0) atomicMax(reinterpret_cast<int*>(&s_emax), __float_as_int(emax));     // non-negative floats order as ints
+    __syncthreads();
+    merge_sort_desc(s_key, s_val, s_lab, s_flag, size, tid, false);
+    // the prefix that can still hold one of the k best
+    const bool have_k = a.k <= size && s_key[a.k - 1] != 0u;
+    const float bound = have_k ? s_val[a.k - 1] - s_emax : -__builtin_inff();
+    for (int i = tid; i < size; i += 256) {
+        const bool in = s_key[i] != 0u && s_val[i] >= bound;
+        const bool next_in = i + 1 < size && s_key[i + 1] != 0u && s_val[i + 1] >= bound;
+        if (in && !next_in) s_prefix = i + 1;
     }
     __syncthreads();
-    for (int sz = 2; sz <= size; sz <<= 1) {
-        for (int stride = sz >> 1; stride > 0; stride >>= 1) {
-            for (int i = tid; i < size / 2; i += 256) {
-                const int lo_i = 2 * i - (i & (stride - 1));
-                const int hi_i = lo_i + stride;
-                const bool up = ((lo_i & sz) == 0);
-                const uint32_t k0 = s_key[lo_i], k1 = s_key[hi_i];
-                const int64_t l0 = s_lab[lo_i], l1 = s_lab[hi_i];
-                const bool first_before = (k0 > k1) || (k0 == k1 && l0 <= l1);
-                if (first_before != up) {
-                    s_key[lo_i] = k1; s_key[hi_i] = k0;
-                    s_lab[lo_i] = l1; s_lab[hi_i] = l0;
-                    const float t = s_val[lo_i]; s_val[lo_i] = s_val[hi_i]; s_val[hi_i] = t;
-                }
+    const int prefix = s_prefix;
+    // exact scores and labels for the candidates in the prefix
+    float zr[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const int j = lane + 64 * e;
+        zr[e] = j < a.d ? a.z[q * a.z_pitch + j] : 0.f;
+    }
+    const uint32_t mask = (1u << a.b) - 1u;
+    for (int i = wave; i < prefix; i += 4) {
+        if (!s_flag[i]) continue;                 // wavefront-uniform
+        const int64_t packed = s_lab[i];
+        const int64_t slot = packed & (((int64_t)1 << kCandProbeShift) - 1);
+        const int pr = (int)(packed >> kCandProbeShift);
+        const uint32_t* wp = a.store.codes + (slot >> 6) * a.store.words * 64 + (slot & 63);
+        float acc = 0.f;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int j = lane + 64 * e;
+            if (j < a.d) {
+                const int bit = j * a.b, w = bit >> 5, o = bit & 31;
+                uint32_t v = wp[(int64_t)w * 64] >> o;
+                if (o + a.b > 32) v |= wp[(int64_t)(w + 1) * 64] << (32 - o);
+                acc += zr[e] * a.cb[v & mask];
             }
-            __syncthreads();
+        }
+        for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
+        if (lane == 0) {
+            const float sc = a.coarse[q * a.np + pr] + __half2float(__ushort_as_half(a.store.gamma[slot])) * acc;
+            s_val[i] = sc;
+            s_key[i] = okey(sc);
+            s_lab[i] = a.ids ? a.ids[slot] : slot;
+            s_flag[i] = 0;
         }
     }
+    __syncthreads();
+    // entries beyond the prefix are out; sort the prefix (padded to a power of two) by exact score, then label
+    int psize = 1;
+    while (psize < prefix) psize <<= 1;
+    for (int i = prefix + tid; i < psize; i += 256) { s_key[i] = 0u; s_val[i] = -__builtin_inff(); s_lab[i] = INT64_MAX; s_flag[i] = 0; }
+    __syncthreads();
+    merge_sort_desc(s_key, s_val, s_lab, s_flag, psize, tid, true);
     for (int i = tid; i < a.k; i += 256) {
-        const bool real = s_key[i] != 0;
+        const bool real = i < prefix && s_key[i] != 0u;
         a.out_scores[q * a.k + i] = real ? s_val[i] : -__builtin_inff();
         a.out_ids[q * a.k + i] = real ? s_lab[i] : -1;
     }
@@ -521,7 +609,7 @@ hipError_t launch_merge(const MergeArgs& a, int64_t nq, hipStream_t st) {
     if (nq <= 0) return hipSuccess;
     int size = 1;
     while (size < a.k + a.cap) size <<= 1;
-    const size_t lds = (size_t)size * 16;
+    const size_t lds = (size_t)size * 17;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_merge),

@@ -1,6 +1,7 @@
 // Internal launcher declarations shared by the HIP translation units of libivftq.
 // Nothing here is part of the public ABI (see include/ivftq.h for that).
 #pragma once
+#include <cmath>
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
@@ -218,16 +219,30 @@ struct BatchScanArgs {
     const float* thresh; int thresh_stride;   // threshold of query q at thresh[q*thresh_stride]
     ListStore store; int np; int L;
     int bucket_lo, bucket_hi;            // buckets this launch covers
+    // threshold mode: cand_score = upper bound of the score (see acc0), cand_slot = slot | probe rank << kCandProbeShift
     float* cand_score; int64_t* cand_slot; int32_t* cand_cnt; int cap;
+    float acc0;                          // 2^20 * kappa: start value of the threshold pass's accumulators
     // dense mode (the nearest lists): every score goes to scores[q*m_stride + cand_off[q][p] + v]
     int dense; float* scores; int64_t m_stride; const int32_t* cand_off;
 };
 hipError_t launch_batch_scan(const BatchScanArgs& a, int d, int b, int max_tiles, hipStream_t st);
 
+constexpr int kCandProbeShift = 48;      // a candidate's probe rank sits above its slot number (slots < 2^48, ranks < 2^12)
+
+// kappa with |sum_j z_j c_j - 2^-20 sum_j fp16(1024 z_j) fp16(1024 c_j)| <= kappa for |z| <= 1 and
+// codebook values of magnitude <= cmax in d coordinates (each leading part is within 2^-11 relative
+// of its value, Cauchy-Schwarz, |c| <= sqrt(d) cmax), with room for float32 accumulation.
+inline float screen_kappa(int d, float cmax) { return (0x1p-10f + 0x1p-16f) * 1.002f * sqrtf((float)d) * cmax; }
+
 struct MergeArgs {
-    const float* first_scores; const int64_t* first_ids;     // [nq][k] from the streaming pass
+    const float* first_scores; const int64_t* first_ids;     // [nq][k] from the streaming pass (exact scores)
+    // candidates of the threshold pass: upper bounds u of the score (true score in [u - 2*kappa*gamma, u])
     const float* cand_score; const int64_t* cand_slot; const int32_t* cand_cnt; int cap;
-    const int64_t* ids;                                       // labels by slot
+    float kappa;
+    const float* z; int z_pitch; int d; int b; const float* cb;   // rotated queries (float32) and levels, for re-scoring
+    const float* coarse; int np;                                  // [nq][np] coarse terms
+    ListStore store;
+    const int64_t* ids;                                       // labels by slot (null: the slot is the label)
     int k; float* out_scores; int64_t* out_ids;
     int32_t* gate;                                            // [1 + nq]: count (cleared by the caller), then the queries whose candidate list overflowed
 };
