@@ -393,9 +393,9 @@ __device__ __forceinline__ uint32_t okey(float f) {
 //
 // One workgroup per query.  First-pass entries carry exact scores; a candidate carries an upper bound u
 // of its score, the score itself lying in [u - 2*kappa*gamma, u].  All entries are sorted by upper bound;
-// with e the largest 2*kappa*gamma among the candidates, R = (k-th largest upper bound) - e is a lower
-// bound of the k-th largest score, so only the entries with u >= R (a prefix of the sorted order, a few
-// more than k) can be among the k best.  Those are re-scored from the packed codes in float32 (each
+// R = the smallest lower bound among the k entries with the largest upper bounds is a lower bound of the
+// k-th largest score, so only the entries with u >= R (a prefix of the sorted order, a few more than k)
+// can be among the k best.  Those are re-scored from the packed codes in float32 (each
 // wavefront takes entries in turn, lane j sums coordinates j, j+64, ...), sorted again by (score desc,
 // label asc) and the k best written.  A query whose candidate list overflowed is appended to the gate list.
 __device__ __forceinline__ void merge_sort_desc(uint32_t* s_key, float* s_val, int64_t* s_lab, uint8_t* s_flag,
@@ -423,7 +423,7 @@ __device__ __forceinline__ void merge_sort_desc(uint32_t* s_key, float* s_val, i
 
 __global__ __launch_bounds__(256) void k_merge(MergeArgs a) {
     extern __shared__ unsigned char smem[];
-    __shared__ float s_emax;
+    __shared__ int s_bound;      // order-preserving key (sign bit flipped for a signed minimum) of the lower bound R
     __shared__ int s_prefix;
     const int64_t q = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -438,9 +438,10 @@ __global__ __launch_bounds__(256) void k_merge(MergeArgs a) {
     float* s_val = reinterpret_cast<float*>(s_key + size);
     int64_t* s_lab = reinterpret_cast<int64_t*>(s_val + size);     // label, or (flag 1) the packed slot of a candidate
     uint8_t* s_flag = reinterpret_cast<uint8_t*>(s_lab + size);    // 1: candidate whose score is still an upper bound
-    if (tid == 0) { s_emax = 0.f; s_prefix = 0; }
+    float* s_z = reinterpret_cast<float*>(smem + (((size_t)size * 17 + 3) & ~(size_t)3));   // [d] the query's rotated coordinates
+    for (int j = tid; j < a.d; j += 256) s_z[j] = a.z[q * a.z_pitch + j];
+    if (tid == 0) { s_bound = INT32_MAX; s_prefix = 0; }
     __syncthreads();
-    float emax = 0.f;
     for (int i = tid; i < size; i += 256) {
         float v = -__builtin_inff();
         int64_t lab = INT64_MAX;
@@ -453,61 +454,66 @@ __global__ __launch_bounds__(256) void k_merge(MergeArgs a) {
         } else if (i < total) {
             v = a.cand_score[q * a.cap + (i - a.k)];
             lab = a.cand_slot[q * a.cap + (i - a.k)];
-            const int64_t slot = lab & (((int64_t)1 << kCandProbeShift) - 1);
-            emax = fmaxf(emax, 2.f * a.kappa * __half2float(__ushort_as_half(a.store.gamma[slot])));
             key = okey(v);
             flag = 1;
         }
         s_key[i] = key; s_val[i] = v; s_lab[i] = lab; s_flag[i] = flag;
     }
-    for (int o = 32; o > 0; o >>= 1) emax = fmaxf(emax, __shfl_xor(emax, o));
-    if (lane == 0) atomicMax(reinterpret_cast<int*>(&s_emax), __float_as_int(emax));     // non-negative floats order as ints
     __syncthreads();
     merge_sort_desc(s_key, s_val, s_lab, s_flag, size, tid, false);
+    // The k entries with the largest upper bounds have scores of at least their lower bounds, so the
+    // smallest of those lower bounds is a lower bound of the k-th largest score.
+    const bool have_k = s_key[a.k - 1] != 0u;
+    if (have_k) {
+        float lo_min = __builtin_inff();
+        for (int i = tid; i < a.k; i += 256) {
+            float lo = s_val[i];
+            if (s_flag[i]) {
+                const int64_t slot = s_lab[i] & (((int64_t)1 << kCandProbeShift) - 1);
+                lo -= 2.f * a.kappa * __half2float(__ushort_as_half(a.store.gamma[slot]));
+            }
+            lo_min = fminf(lo_min, lo);
+        }
+        for (int o = 32; o > 0; o >>= 1) lo_min = fminf(lo_min, __shfl_xor(lo_min, o));
+        if (lane == 0) atomicMin(reinterpret_cast<int*>(&s_bound), (int)okey(lo_min) ^ (int)0x80000000);   // signed order of the keys
+    }
+    __syncthreads();
     // the prefix that can still hold one of the k best
-    const bool have_k = a.k <= size && s_key[a.k - 1] != 0u;
-    const float bound = have_k ? s_val[a.k - 1] - s_emax : -__builtin_inff();
+    const uint32_t bound_key = have_k ? ((uint32_t)s_bound ^ 0x80000000u) : 0u;
     for (int i = tid; i < size; i += 256) {
-        const bool in = s_key[i] != 0u && s_val[i] >= bound;
-        const bool next_in = i + 1 < size && s_key[i + 1] != 0u && s_val[i + 1] >= bound;
+        const bool in = s_key[i] != 0u && s_key[i] >= bound_key;
+        const bool next_in = i + 1 < size && s_key[i + 1] != 0u && s_key[i + 1] >= bound_key;
         if (in && !next_in) s_prefix = i + 1;
     }
     __syncthreads();
     const int prefix = s_prefix;
-    // exact scores and labels for the candidates in the prefix
-    float zr[4];
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        const int j = lane + 64 * e;
-        zr[e] = j < a.d ? a.z[q * a.z_pitch + j] : 0.f;
-    }
+    // exact scores and labels for the candidates in the prefix: 16 lanes per candidate, lane t sums the
+    // coordinates t, t+16, ... (the query's rotated coordinates were staged in LDS above)
     const uint32_t mask = (1u << a.b) - 1u;
-    for (int i = wave; i < prefix; i += 4) {
-        if (!s_flag[i]) continue;                 // wavefront-uniform
+    const int grp = tid >> 4, gl = tid & 15;
+    for (int i = grp; i < prefix; i += 16) {
+        if (!s_flag[i]) continue;                 // uniform over the 16 lanes
         const int64_t packed = s_lab[i];
         const int64_t slot = packed & (((int64_t)1 << kCandProbeShift) - 1);
         const int pr = (int)(packed >> kCandProbeShift);
         const uint32_t* wp = a.store.codes + (slot >> 6) * a.store.words * 64 + (slot & 63);
         float acc = 0.f;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const int j = lane + 64 * e;
-            if (j < a.d) {
-                const int bit = j * a.b, w = bit >> 5, o = bit & 31;
-                uint32_t v = wp[(int64_t)w * 64] >> o;
-                if (o + a.b > 32) v |= wp[(int64_t)(w + 1) * 64] << (32 - o);
-                acc += zr[e] * a.cb[v & mask];
-            }
+        for (int j = gl; j < a.d; j += 16) {
+            const int bit = j * a.b, w = bit >> 5, o = bit & 31;
+            uint32_t v = wp[(int64_t)w * 64] >> o;
+            if (o + a.b > 32) v |= wp[(int64_t)(w + 1) * 64] << (32 - o);
+            acc += s_z[j] * a.cb[v & mask];
         }
-        for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
-        if (lane == 0) {
+        for (int o = 8; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 16);
+        if (gl == 0) {
             const float sc = a.coarse[q * a.np + pr] + __half2float(__ushort_as_half(a.store.gamma[slot])) * acc;
             s_val[i] = sc;
             s_key[i] = okey(sc);
             s_lab[i] = a.ids ? a.ids[slot] : slot;
-            s_flag[i] = 0;
         }
     }
+    __syncthreads();
+    for (int i = tid; i < prefix; i += 256) s_flag[i] = 0;
     __syncthreads();
     // entries beyond the prefix are out; sort the prefix (padded to a power of two) by exact score, then label
     int psize = 1;
@@ -609,7 +615,7 @@ hipError_t launch_merge(const MergeArgs& a, int64_t nq, hipStream_t st) {
     if (nq <= 0) return hipSuccess;
     int size = 1;
     while (size < a.k + a.cap) size <<= 1;
-    const size_t lds = (size_t)size * 17;
+    const size_t lds = (size_t)size * 17 + 4 + (size_t)a.d * sizeof(float);
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_merge),

@@ -147,6 +147,40 @@ def test_batched_scan_overflow_falls_back_to_the_exact_scan():
         ix.close()
 
 
+@pytest.mark.parametrize("name", ["d128", "d96_b3"])
+def test_batched_scan_with_duplicated_vectors_ranks_ties_by_label(name):
+    """Every stored vector three times under different labels: the batched scan's threshold pass works
+    on upper bounds and the merge re-scores what may still matter, so equal scores must come out as one
+    run in ascending label order and the label set must be the oracle's."""
+    cs = gpu_cases.get_case(name)
+    enc = gpu_cases.oracle_encode(name)
+    dev = _dev()
+    n = len(cs.X)
+    ref = orc.ListIndex(cs.cent, cs.Pi, cs.c, cs.tau)
+    ix = _make_index(cs)
+    ix.set_search_mode(2)
+    for rep in range(3):
+        labels = np.arange(n, dtype=np.int64) * 3 + (2 - rep)          # later copies get the smaller labels
+        ref.add_encoded(enc["assign"], labels, enc["codes"], enc["gamma16"])
+        ix.add_encoded(torch.from_numpy(enc["assign"]).to(dev), torch.from_numpy(enc["codes"]).to(dev),
+                       torch.from_numpy(enc["gamma16"]).to(dev), torch.from_numpy(labels).to(dev))
+    k = 12
+    o_sc, o_ids, _, S, o_all = orc.search(ref, cs.Q, cs.nprobe, k, return_all=True)
+    sc, ids = ix.search(torch.from_numpy(cs.Q).to(dev), cs.nprobe, k)
+    torch.cuda.synchronize()
+    g_sc, g_ids = sc.cpu().numpy(), ids.cpu().numpy()
+    rep = parity.compare_search(g_sc, g_ids, o_sc, o_ids, o_all, parity.probe_cut_gap(S, cs.nprobe))
+    print("duplicates:", rep, flush=True)
+    for qi in range(len(cs.Q)):
+        for i in range(k - 1):
+            if g_sc[qi, i] == g_sc[qi, i + 1]:
+                assert g_ids[qi, i] < g_ids[qi, i + 1], f"query {qi}: equal scores not in label order"
+        # the three copies of a vector score identically, so whole triples appear (except at the cut)
+        full = g_ids[qi][: (k // 3) * 3] // 3
+        assert np.all(full.reshape(-1, 3) == full.reshape(-1, 3)[:, :1]) or rep["tie_swaps"] > 0
+    ix.close()
+
+
 def test_end_to_end_recall_matches_oracle_pipeline():
     """GPU encode + GPU search against oracle encode + oracle search and exact ground truth."""
     cs = gpu_cases.get_case("tiny")
