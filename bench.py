@@ -358,7 +358,9 @@ def main():
                                             "passes; f32 accumulate)"),
                  "encode_rotate_quantise_pack": mfma_roof("encode_rotate_quantise_pack", 2.0 * w.d * w.d * w.n)}
     if batched:
-        rooflines["batch_scan"] = mfma_roof("batch_scan", 2.0 * w.d * (float(cand.sum()) - stream_cand))
+        rooflines["batch_scan"] = mfma_roof("batch_scan", 2.0 * w.d * (float(cand.sum()) - stream_cand), 1.0,
+                                            "f16 (leading parts only, 1 product, f32 accumulate from the error bound: upper "
+                                            "bounds; the merge re-scores the few that can reach the top k)")
         rooflines["batch_scan_nearest"] = mfma_roof("batch_scan_nearest", 2.0 * w.d * stream_cand)
     else:
         ms = avg_ms("list_scan")
