@@ -250,9 +250,11 @@ __device__ __forceinline__ float max3_raw(float a, float b, float c) {
         }                                                                                                   \
     }
 
-template <int DP, int R>
+// VEC4: rows are read 16 bytes at a time (d % 4 == 0 and x 16-byte aligned); a template parameter so that
+// each instantiation carries one loading path only (with both, the loads of the prologue spill).
+template <int DP, int R, bool VEC4>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(IVFTQ_SCREEN_WAVES))) void k_coarse_screen(
-    const float* __restrict__ x, int64_t n, int d, int vec4, const uint16_t* __restrict__ cent_h, int cent_pitch,
+    const float* __restrict__ x, int64_t n, int d, const uint16_t* __restrict__ cent_h, int cent_pitch,
     int L, int Lpad, int32_t* __restrict__ assign, int32_t* __restrict__ row_list,
     unsigned long long* __restrict__ row_key, int* __restrict__ row_count) {
     using Cfg = CoarseCfg<DP>;
@@ -270,7 +272,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(IVFTQ_SCREE
     for (int r = 0; r < R; ++r) {
         const int64_t row = row0 + 32 * r + j;
         half8 unused[KB];
-        good[r] = load_rows<DP>(x, row, row < n, d, vec4, half, bh[r], unused);
+        good[r] = load_rows<DP>(x, row, row < n, d, VEC4 ? 1 : 0, half, bh[r], unused);
         __builtin_amdgcn_sched_barrier(0);          // one tile's float32 values at a time in registers
     }
     float best[R], second[R];
@@ -468,8 +470,11 @@ hipError_t run_screened(const float* x, int64_t n, int d, const uint16_t* cent_h
     const size_t lds_screen = screen_lds_bytes<DP>();
     const size_t lds = (size_t)2 * kTN * CoarseCfg<DP>::LDH * sizeof(uint16_t);
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_coarse_screen<DP, RS>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_coarse_screen<DP, RS, true>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_screen);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_coarse_screen<DP, RS, false>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_screen);
         if (e == hipSuccess)
             e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_coarse_resolve<DP>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -478,8 +483,12 @@ hipError_t run_screened(const float* x, int64_t n, int d, const uint16_t* cent_h
     }
     const int vec4 = (d % 4 == 0) && (reinterpret_cast<uintptr_t>(x) % 16 == 0);
     const int64_t blocks_s = (n + 4 * 32 * RS - 1) / (4 * 32 * RS);
-    hipLaunchKernelGGL((k_coarse_screen<DP, RS>), dim3((unsigned)blocks_s), dim3(256), lds_screen, st, x, n, d, vec4,
-                       cent_h, cent_pitch, L, Lpad, assign, row_list, row_key, row_count);
+    if (vec4)
+        hipLaunchKernelGGL((k_coarse_screen<DP, RS, true>), dim3((unsigned)blocks_s), dim3(256), lds_screen, st, x, n, d,
+                           cent_h, cent_pitch, L, Lpad, assign, row_list, row_key, row_count);
+    else
+        hipLaunchKernelGGL((k_coarse_screen<DP, RS, false>), dim3((unsigned)blocks_s), dim3(256), lds_screen, st, x, n, d,
+                           cent_h, cent_pitch, L, Lpad, assign, row_list, row_key, row_count);
     // the undecided rows: about four centroid stages per workgroup, at most 512 x 16 workgroups
     const int stages = Lpad / kTN;
     const int ysplit = std::min(16, (stages + 3) / 4);
