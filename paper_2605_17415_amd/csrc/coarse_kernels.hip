@@ -63,10 +63,10 @@ __device__ __forceinline__ bool load_rows(const float* __restrict__ x, int64_t r
     return good;
 }
 
-// R = 32-row tiles per wavefront.
-template <int DP, int R>
+// R = 32-row tiles per wavefront.  VEC4: rows are read 16 bytes at a time (d % 4 == 0, x 16-byte aligned).
+template <int DP, int R, bool VEC4>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k_coarse(
-    int mode, const float* __restrict__ x, int64_t n, int d, int vec4, const uint16_t* __restrict__ cent_h,
+    int mode, const float* __restrict__ x, int64_t n, int d, const uint16_t* __restrict__ cent_h,
     const uint16_t* __restrict__ cent_l, int cent_pitch, const float* __restrict__ bias, int L, int Lpad,
     int32_t* __restrict__ assign, float* __restrict__ best_out, float* __restrict__ scores,
     int64_t ld_scores, int* __restrict__ flag) {
@@ -86,7 +86,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const int64_t row = row0 + 32 * r + j;
-        good[r] = load_rows<DP>(x, row, row < n, d, vec4, half, bh[r], bl[r]);
+        good[r] = load_rows<DP>(x, row, row < n, d, VEC4 ? 1 : 0, half, bh[r], bl[r]);
         if (row < n && !good[r] && half == 0) atomicOr(flag, 1);
     }
 
@@ -508,8 +508,11 @@ hipError_t run(int mode, const float* x, int64_t n, int d, const uint16_t* cent_
     static bool attr_set = false;
     const size_t lds = CoarseCfg<DP>::lds_bytes;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_coarse<DP, R>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_coarse<DP, R, true>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_coarse<DP, R, false>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
@@ -521,8 +524,12 @@ hipError_t run(int mode, const float* x, int64_t n, int d, const uint16_t* cent_
     int ysplit = 1;
     if (mode == 1)
         while (blocks * ysplit < 512 && ysplit * 2 <= Lpad / kTN) ysplit *= 2;
-    hipLaunchKernelGGL((k_coarse<DP, R>), dim3((unsigned)blocks, (unsigned)ysplit), dim3(256), lds, st, mode, x, n, d, vec4, cent_h,
-                       cent_l, cent_pitch, bias, L, Lpad, assign, best, scores, ld_scores, flag);
+    if (vec4)
+        hipLaunchKernelGGL((k_coarse<DP, R, true>), dim3((unsigned)blocks, (unsigned)ysplit), dim3(256), lds, st, mode, x, n, d,
+                           cent_h, cent_l, cent_pitch, bias, L, Lpad, assign, best, scores, ld_scores, flag);
+    else
+        hipLaunchKernelGGL((k_coarse<DP, R, false>), dim3((unsigned)blocks, (unsigned)ysplit), dim3(256), lds, st, mode, x, n, d,
+                           cent_h, cent_l, cent_pitch, bias, L, Lpad, assign, best, scores, ld_scores, flag);
     return hipGetLastError();
 }
 
