@@ -208,10 +208,10 @@ constexpr float kScreenMargin = 2.2e-3f;
 constexpr float kScreenNone = -3.0e38f;     // below every score, finite so that tagging its low bits keeps it a number
 
 #ifndef IVFTQ_SCREEN_NT
-#define IVFTQ_SCREEN_NT 4
+#define IVFTQ_SCREEN_NT 2
 #endif
 #ifndef IVFTQ_SCREEN_WAVES
-#define IVFTQ_SCREEN_WAVES 2
+#define IVFTQ_SCREEN_WAVES 3
 #endif
 // 32-centroid tiles per LDS stage of the screening pass (two stages are resident)
 template <int DP>
@@ -253,7 +253,7 @@ __device__ __forceinline__ float max3_raw(float a, float b, float c) {
 // VEC4: rows are read 16 bytes at a time (d % 4 == 0 and x 16-byte aligned); a template parameter so that
 // each instantiation carries one loading path only (with both, the loads of the prologue spill).
 template <int DP, int R, bool VEC4>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(IVFTQ_SCREEN_WAVES))) void k_coarse_screen(
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((DP <= 128 || R == 1) ? IVFTQ_SCREEN_WAVES : 2))) void k_coarse_screen(
     const float* __restrict__ x, int64_t n, int d, const uint16_t* __restrict__ cent_h, int cent_pitch,
     int L, int Lpad, int32_t* __restrict__ assign, int32_t* __restrict__ row_list,
     unsigned long long* __restrict__ row_key, int* __restrict__ row_count) {
@@ -588,10 +588,13 @@ hipError_t launch_coarse_screened(const float* x, int64_t n, int d, const uint16
                                   unsigned long long* row_key, int* row_count, hipStream_t st) {
     if (n <= 0) return hipSuccess;
     switch (coarse_dp(d)) {
-#define IVFTQ_CASE(DPV) \
-    case DPV: return run_screened<DPV, 2>(x, n, d, cent_h, cent_l, cent_pitch, L, Lpad, assign, flag, row_list, row_key, row_count, st);
-        IVFTQ_CASE(32) IVFTQ_CASE(64) IVFTQ_CASE(96) IVFTQ_CASE(128) IVFTQ_CASE(160)
-        IVFTQ_CASE(192) IVFTQ_CASE(208) IVFTQ_CASE(224) IVFTQ_CASE(256)
+#ifndef IVFTQ_SCREEN_RBIG
+#define IVFTQ_SCREEN_RBIG 2
+#endif
+#define IVFTQ_CASE(DPV, RS) \
+    case DPV: return run_screened<DPV, RS>(x, n, d, cent_h, cent_l, cent_pitch, L, Lpad, assign, flag, row_list, row_key, row_count, st);
+        IVFTQ_CASE(32, 2) IVFTQ_CASE(64, 2) IVFTQ_CASE(96, 2) IVFTQ_CASE(128, 2) IVFTQ_CASE(160, IVFTQ_SCREEN_RBIG)
+        IVFTQ_CASE(192, IVFTQ_SCREEN_RBIG) IVFTQ_CASE(208, IVFTQ_SCREEN_RBIG) IVFTQ_CASE(224, IVFTQ_SCREEN_RBIG) IVFTQ_CASE(256, IVFTQ_SCREEN_RBIG)
 #undef IVFTQ_CASE
         default: return hipErrorInvalidValue;
     }
