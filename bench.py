@@ -417,7 +417,7 @@ def main():
     # cascade search (top bits first, 100 kept, full codes second): reported, not the headline
     cascade_info = None
     if not args.no_sweep and w.k <= 100 and w.b >= 2:
-        beta, keep = w.b - 1, 100
+        beta, keep = w.b - 1, min(2048, max(100, 4 * w.k))
         ts = []
         for _ in range(3):
             a, b = ev(), ev()
