@@ -411,17 +411,32 @@ __global__ __launch_bounds__(256) void k_select_small(SelectArgs a) {
         }
     }
     if (MODE == 1) {
-        // probe rank of each winner: the last p with cand_off[p] <= column.  The offsets are read
-        // 64 at a time, one per lane, and handed round with shuffles (no dependent loads).
+        // probe rank of each winner: the last p with cand_off[p] <= column.  Up to 256 probes the row of
+        // offsets is staged in the wavefront's LDS words (the histogram is no longer needed) and every
+        // winner bisects there; beyond that the offsets are handed round with shuffles, 64 at a time.
         const int32_t* off = a.cand_off + q * (a.np + 1);
         int rank = 0, rank_off = 0;
-        for (int base = 0; base < a.np; base += 64) {
-            const int p = base + lane;
-            const int32_t mine_off = p < a.np ? off[p] : INT32_MAX;
-            const int span = a.np - base < 64 ? a.np - base : 64;
-            for (int t = 0; t < span; ++t) {
-                const int32_t o = __shfl(mine_off, t);
-                if (o <= out_c) { rank = base + t; rank_off = o; }
+        if (a.np <= 256) {
+            int32_t* s_off = reinterpret_cast<int32_t*>(hist);
+            for (int p = lane; p < a.np; p += 64) s_off[p] = off[p];
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            int lo = 0, hi = a.np;               // off[0] = 0 <= column
+            while (hi - lo > 1) {
+                const int mid = (lo + hi) >> 1;
+                if (s_off[mid] <= out_c) lo = mid; else hi = mid;
+            }
+            rank = lo;
+            rank_off = s_off[lo];
+        } else {
+            for (int base = 0; base < a.np; base += 64) {
+                const int p = base + lane;
+                const int32_t mine_off = p < a.np ? off[p] : INT32_MAX;
+                const int span = a.np - base < 64 ? a.np - base : 64;
+                for (int t = 0; t < span; ++t) {
+                    const int32_t o = __shfl(mine_off, t);
+                    if (o <= out_c) { rank = base + t; rank_off = o; }
+                }
             }
         }
         if (out_c >= 0) {
@@ -429,21 +444,25 @@ __global__ __launch_bounds__(256) void k_select_small(SelectArgs a) {
             lab = a.ids ? a.ids[slot] : slot;
         }
     }
+    // order the winners by (value desc, label asc): a bitonic network over the first nsort >= take lanes
+    // (the others hold nothing); the value travels as its key and is decoded at the end
     uint32_t key = out_c >= 0 ? key_of(out_v) : 0u;
+    const int nsort = take <= 8 ? 8 : take <= 16 ? 16 : take <= 32 ? 32 : 64;
 #pragma unroll
     for (int size = 2; size <= 64; size <<= 1) {
+        if (size > nsort) break;
 #pragma unroll
         for (int stride = size >> 1; stride > 0; stride >>= 1) {
             const uint32_t ok = __shfl_xor(key, stride);
             const int64_t ol = __shfl_xor(lab, stride);
-            const float ov = __shfl_xor(out_v, stride);
             const bool lower = (lane & stride) == 0;     // this lane holds the earlier position of the pair
             const bool up = (lane & size) == 0;          // block sorted into final order (best first)
             const bool mine_first = (key > ok) || (key == ok && lab <= ol);
             const bool keep = (lower == up) ? mine_first : !mine_first;
-            if (!keep) { key = ok; lab = ol; out_v = ov; }
+            if (!keep) { key = ok; lab = ol; }
         }
     }
+    out_v = __uint_as_float((key & 0x80000000u) ? (key ^ 0x80000000u) : ~key);     // inverse of order_key
     if (lane < k) {
         const bool real = key != 0u;
         if (a.out_vals) a.out_vals[row * k + lane] = real ? out_v : ninf;
