@@ -328,8 +328,21 @@ __global__ __launch_bounds__(256) void k_select_small(SelectArgs a) {
 
     // radix search for the take-th largest key
     uint32_t prefix = 0, mask = 0, need = (uint32_t)take;
+    // Leading bytes that every key of the row shares (scores of one query usually share sign and exponent)
+    // need no pass: their histogram would be one bin that all lanes hit at once.
+    int top_shift = 24;
+    if (take > 0 && m <= NV * 64) {
+        const uint32_t first = __builtin_amdgcn_readfirstlane(keys[0]);
+        uint32_t diff = 0u;
+#pragma unroll
+        for (int e = 0; e < NV; ++e) diff |= (e * 64 + lane < m) ? (keys[e] ^ first) : 0u;
+        if (__ballot((diff >> 24) != 0u) == 0ull) {
+            prefix = first & 0xFF000000u; mask = 0xFF000000u; top_shift = 16;
+            if (__ballot((diff >> 16) != 0u) == 0ull) { prefix = first & 0xFFFF0000u; mask = 0xFFFF0000u; top_shift = 8; }
+        }
+    }
     if (take > 0) {
-        for (int shift = 24; shift >= 0; shift -= 8) {
+        for (int shift = top_shift; shift >= 0; shift -= 8) {
 #pragma unroll
             for (int e = 0; e < 4; ++e) hist[lane * 4 + e] = 0u;
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
