@@ -48,6 +48,11 @@ def test_assignment_near_ties_matches_oracle(d, L, b):
     cent = rng.standard_normal((L, d))
     cent[: L // 2] = cent[L // 2: 2 * (L // 2)] + 0.05 * rng.standard_normal((L // 2, d))   # close pairs
     cent = orc.normalize_rows(cent)
+    # two exact copies of earlier centroids (one inside a 64-centroid stage of its original, one in another
+    # share of the full-precision pass): equal scores, the smaller index must win
+    twins = {3: 40, 17: L - 2}
+    for first, copy in twins.items():
+        cent[copy] = cent[first]
     X = _near_tie_rows(cent, rng, 331)          # 331 per group: every kernel tile size leaves a ragged tail
     print(f"[screen] d={d} L={L} rows={len(X)}", flush=True)
     Pi = orc.haar_rotation_from_gaussian(rng.standard_normal((d, d)))
@@ -66,6 +71,9 @@ def test_assignment_near_ties_matches_oracle(d, L, b):
     # the construction puts rows on both sides of the screening margin
     assert 0 < undecided < len(X)
     assert rep["assign_near_tie_total"] > 0
+    g = assign.cpu().numpy()
+    assert not np.isin(g, list(twins.values())).any(), "an exact tie went to the larger index"
+    assert np.isin(g, list(twins.keys())).sum() >= 2
     # the same rows in a second call of a different size: the undecided list starts empty again
     half = len(X) // 2 + 7
     assign2, _, _ = ix.encode_only(x[:half].contiguous(), want_codes=False)
