@@ -214,9 +214,10 @@ ivftq_status ivftq_export_list(const ivftq_index* index, int list, int64_t* ids_
                                uint8_t* codes_host, uint16_t* gamma_host);
 /* Bytes of device memory the stored vectors occupy (codes + norms + labels, without slack). */
 int64_t ivftq_index_bytes(const ivftq_index* index);
-/* Scan strategy of ivftq_search: 0 = choose by shape (default), 1 = streaming scan only (one
- * workgroup per query and probed list), 2 = query-batched matrix-core scan whenever (d, b) is one
- * of its instantiated shapes.  Results obey the same contract in every mode. */
+/* Scan strategy of ivftq_search: 0 = default (the query-batched matrix-core scan whenever (d, b) is
+ * one of its instantiated shapes and nprobe > 1, else the streaming scan), 1 = streaming scan only
+ * (one workgroup per query and probed list), 2 = same as 0 (kept for callers that set it).  Results
+ * obey the same contract in every mode. */
 ivftq_status ivftq_set_search_mode(ivftq_index* index, int mode);
 /* Upper limit, in bytes, of the per-search score workspace (default 4 GiB); queries are processed
  * in as many passes as that allows. */

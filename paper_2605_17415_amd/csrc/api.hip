@@ -1060,11 +1060,11 @@ ivftq_status search_core(ivftq_index* ix, const float* q_dev, int64_t nq, int np
 
     // Scan strategy.  Streaming: one workgroup per (query, probed list), every score written, exact
     // selection.  Batched: pairs regrouped by list and scanned on the matrix cores against a
-    // threshold from the streaming scan of each query's nearest lists; pays off when each list is
-    // probed by many queries of the batch.
+    // threshold from each query's nearest lists.  Measured (1M x 128, nprobe 32) the batched path wins
+    // at every batch size down to one query (0.10 ms against 0.24 ms), because it de-quantises two codes
+    // per table look-up and leaves the sums to the matrix pipe, so it is taken whenever the shape is covered.
     const int tq = batch_tile_queries(ix->d, ix->b);
-    const bool batched = tq > 0 && nprobe > 1 &&
-                         (ix->search_mode == 2 || (ix->search_mode == 0 && qc * nprobe >= (int64_t)16 * ix->nlist));
+    const bool batched = tq > 0 && nprobe > 1 && ix->search_mode != 1;
     const int cap = std::min(2048, std::max(512, 16 * k));
     // error bound of a residual sum taken from the leading float16 parts alone (threshold pass)
     float cmax = 0.f;
