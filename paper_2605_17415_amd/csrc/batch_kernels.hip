@@ -201,6 +201,45 @@ void k_batch_scan(BatchScanArgs a) {
     const int n_l = a.store.list_size[l];
     if (n_l == 0 || nq_tile <= 0) return;
 
+    const int words = a.store.words;
+    const int64_t base_slot = a.store.list_off[l];
+    const int nslab = (n_l + 31) / 32;
+    const int n_qt = (nq_tile + 31) / 32;
+    const uint16_t* bh_base = zh + jl * Cfg::LDH + 8 * half;
+    const uint16_t* bl_base = zl + jl * Cfg::LDH + 8 * half;
+    constexpr float kUnscale = 1.f / (kSplitScale * kSplitScale);
+
+    // Raw words and norms of a slab are fetched one slab ahead so that their latency hides behind
+    // the matrix work of the current slab; the first slab's behind the staging below.
+    constexpr int NW = (B == 3 || B == 5) ? 2 : 1; // 24- and 40-bit chunks straddle two words
+    auto fetch = [&](int slab, uint32_t (&w)[KB][NW], uint32_t (&gp)[8]) {
+        const int v_mine = slab * 32 + jl;         // this lane de-quantises vector jl of the slab
+        const int64_t slot = base_slot + (v_mine < n_l ? v_mine : n_l - 1);
+        const uint32_t* wp = a.store.codes + (slot >> 6) * words * 64 + (slot & 63);
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb) {
+            const int wi = ((16 * kb + 8 * half) * B) >> 5;
+#pragma unroll
+            for (int e = 0; e < NW; ++e) w[kb][e] = (wi + e < words) ? wp[(int64_t)(wi + e) * 64] : 0u;
+        }
+        if (DENSE) {                               // float16 norm of the lane's own vector (NaN beyond the list)
+            gp[0] = v_mine < n_l ? (uint32_t)a.store.gamma[slot] : 0x7E00u;
+        } else {
+#pragma unroll
+            for (int r = 0; r < 16; r += 2) {      // float16 norms of the lane's 16 result rows, in pairs
+                const int v = slab * 32 + 8 * (r / 4) + 4 * half + (r % 4);      // even: the pair is 4-byte aligned
+                uint32_t pr = 0x7E007E00u;                                       // two float16 NaNs
+                if (v + 1 < n_l) pr = *reinterpret_cast<const uint32_t*>(a.store.gamma + base_slot + v);
+                else if (v < n_l) pr = (uint32_t)a.store.gamma[base_slot + v] | 0x7E000000u;
+                gp[r / 2] = pr;
+            }
+        }
+    };
+
+    uint32_t cw[KB][NW], cg[8], nw[KB][NW], ng[8];
+    int slab = wave;
+    if (slab < nslab) fetch(slab, cw, cg);
+
     // stage the query panel and the code-pair tables
     for (int e = tid; e < Cfg::TQ; e += NT) {
         int32_t q = -1, pr = 0;
@@ -245,44 +284,6 @@ void k_batch_scan(BatchScanArgs a) {
     }
     __syncthreads();
 
-    const int words = a.store.words;
-    const int64_t base_slot = a.store.list_off[l];
-    const int nslab = (n_l + 31) / 32;
-    const int n_qt = (nq_tile + 31) / 32;
-    const uint16_t* bh_base = zh + jl * Cfg::LDH + 8 * half;
-    const uint16_t* bl_base = zl + jl * Cfg::LDH + 8 * half;
-    constexpr float kUnscale = 1.f / (kSplitScale * kSplitScale);
-
-    // Raw words and norms of a slab are fetched one slab ahead so that their latency hides behind
-    // the matrix work of the current slab.
-    constexpr int NW = (B == 3 || B == 5) ? 2 : 1; // 24- and 40-bit chunks straddle two words
-    auto fetch = [&](int slab, uint32_t (&w)[KB][NW], uint32_t (&gp)[8]) {
-        const int v_mine = slab * 32 + jl;         // this lane de-quantises vector jl of the slab
-        const int64_t slot = base_slot + (v_mine < n_l ? v_mine : n_l - 1);
-        const uint32_t* wp = a.store.codes + (slot >> 6) * words * 64 + (slot & 63);
-#pragma unroll
-        for (int kb = 0; kb < KB; ++kb) {
-            const int wi = ((16 * kb + 8 * half) * B) >> 5;
-#pragma unroll
-            for (int e = 0; e < NW; ++e) w[kb][e] = (wi + e < words) ? wp[(int64_t)(wi + e) * 64] : 0u;
-        }
-        if (DENSE) {                               // float16 norm of the lane's own vector (NaN beyond the list)
-            gp[0] = v_mine < n_l ? (uint32_t)a.store.gamma[slot] : 0x7E00u;
-        } else {
-#pragma unroll
-            for (int r = 0; r < 16; r += 2) {      // float16 norms of the lane's 16 result rows, in pairs
-                const int v = slab * 32 + 8 * (r / 4) + 4 * half + (r % 4);      // even: the pair is 4-byte aligned
-                uint32_t pr = 0x7E007E00u;                                       // two float16 NaNs
-                if (v + 1 < n_l) pr = *reinterpret_cast<const uint32_t*>(a.store.gamma + base_slot + v);
-                else if (v < n_l) pr = (uint32_t)a.store.gamma[base_slot + v] | 0x7E000000u;
-                gp[r / 2] = pr;
-            }
-        }
-    };
-
-    uint32_t cw[KB][NW], cg[8], nw[KB][NW], ng[8];
-    int slab = wave;
-    if (slab < nslab) fetch(slab, cw, cg);
     while (slab < nslab) {
         const int next = slab + WAVES;
         if (next < nslab) fetch(next, nw, ng);
