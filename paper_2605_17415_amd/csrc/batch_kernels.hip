@@ -432,6 +432,13 @@ __global__ __launch_bounds__(256) void k_merge(MergeArgs a) {
     const bool overflow = cnt > a.cap;
     if (tid == 0 && overflow) a.gate[1 + atomicAdd(&a.gate[0], 1)] = (int32_t)q;   // listed for the exact pass
     if (overflow) return;                        // the exact streaming pass redoes this query
+    if (cnt == 0) {                              // nothing beat the threshold: the first pass's k best stand as they are
+        for (int i = tid; i < a.k; i += 256) {
+            a.out_scores[q * a.k + i] = a.first_scores[q * a.k + i];
+            a.out_ids[q * a.k + i] = a.first_ids[q * a.k + i];
+        }
+        return;
+    }
     const int total = a.k + cnt;
     int size = 1;
     while (size < total) size <<= 1;
