@@ -380,9 +380,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((DP <= 128 
 // row_key[position] through a 64-bit atomic maximum of (order-preserving score bits, ~index), which keeps
 // the smallest index among equal scores like the single-kernel argmax does.  A row without a usable norm
 // leaves its key at 0.
-template <int DP>
-__global__ __launch_bounds__(256) void k_coarse_resolve(
-    const float* __restrict__ x, int d, int vec4, const uint16_t* __restrict__ cent_h,
+template <int DP, bool VEC4>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k_coarse_resolve(
+    const float* __restrict__ x, int d, const uint16_t* __restrict__ cent_h,
     const uint16_t* __restrict__ cent_l, int cent_pitch, int L, int Lpad, const int32_t* __restrict__ row_list,
     const int* __restrict__ row_count, unsigned long long* __restrict__ row_key) {
     using Cfg = CoarseCfg<DP>;
@@ -403,7 +403,7 @@ __global__ __launch_bounds__(256) void k_coarse_resolve(
     for (int64_t rb = blockIdx.x; rb * 128 < n; rb += gridDim.x) {
         const int pos = (int)(rb * 128) + wave * 32 + j;
         half8 bh[KB], bl[KB];
-        const bool good = load_rows<DP>(x, pos < n ? (int64_t)row_list[pos] : 0, pos < n, d, vec4, half, bh, bl);
+        const bool good = load_rows<DP>(x, pos < n ? (int64_t)row_list[pos] : 0, pos < n, d, VEC4 ? 1 : 0, half, bh, bl);
         float best = -__builtin_inff();
         int best_idx = 0;
         for (int c0 = c_lo; c0 < c_hi; c0 += kTN) {
@@ -476,7 +476,10 @@ hipError_t run_screened(const float* x, int64_t n, int d, const uint16_t* cent_h
             e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_coarse_screen<DP, RS, false>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_screen);
         if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_coarse_resolve<DP>),
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_coarse_resolve<DP, true>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_coarse_resolve<DP, false>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         attr_set = true;
@@ -493,9 +496,13 @@ hipError_t run_screened(const float* x, int64_t n, int d, const uint16_t* cent_h
     const int stages = Lpad / kTN;
     const int ysplit = std::min(16, (stages + 3) / 4);
     const int64_t row_blocks = (n + 127) / 128;
-    hipLaunchKernelGGL((k_coarse_resolve<DP>), dim3((unsigned)std::min<int64_t>(row_blocks, 512), (unsigned)ysplit),
-                       dim3(256), lds, st, x, d, vec4, cent_h, cent_l, cent_pitch, L, Lpad,
-                       (const int32_t*)row_list, (const int*)row_count, row_key);
+    const dim3 grid_r((unsigned)std::min<int64_t>(row_blocks, 512), (unsigned)ysplit);
+    if (vec4)
+        hipLaunchKernelGGL((k_coarse_resolve<DP, true>), grid_r, dim3(256), lds, st, x, d, cent_h, cent_l, cent_pitch, L, Lpad,
+                           (const int32_t*)row_list, (const int*)row_count, row_key);
+    else
+        hipLaunchKernelGGL((k_coarse_resolve<DP, false>), grid_r, dim3(256), lds, st, x, d, cent_h, cent_l, cent_pitch, L, Lpad,
+                           (const int32_t*)row_list, (const int*)row_count, row_key);
     hipLaunchKernelGGL(k_coarse_resolve_write, dim3((unsigned)std::min<int64_t>((n + 255) / 256, 256)), dim3(256), 0, st,
                        (const int32_t*)row_list, (const int*)row_count, (const unsigned long long*)row_key, assign, flag);
     return hipGetLastError();
