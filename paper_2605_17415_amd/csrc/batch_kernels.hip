@@ -154,6 +154,7 @@ struct BatchCfg {
     static constexpr int LDH = DP + 8;            // halves per panel row: 16-byte pad keeps b128 reads conflict free
     static constexpr int PT = 1 << (2 * B);       // entries of the code-pair tables
     static constexpr size_t lds_bytes = (size_t)TQ * LDH * 2 * sizeof(uint16_t) + 4 * TQ * sizeof(float) + 2 * PT * 4;   // panels + per-query words + pair tables
+    static constexpr size_t lds_bytes_threshold = lds_bytes - (size_t)TQ * LDH * sizeof(uint16_t);                      // without the lo panel
 };
 
 // WAVES = wavefronts per workgroup, OCC = wavefronts per SIMD the register budget is set for.
@@ -174,7 +175,7 @@ void k_batch_scan(BatchScanArgs a) {
     extern __shared__ unsigned char lds_raw[];
     uint16_t* zh = reinterpret_cast<uint16_t*>(lds_raw);          // [TQ][LDH] hi parts of the rotated queries
     uint16_t* zl = zh + Cfg::TQ * Cfg::LDH;                         // [TQ][LDH] lo parts
-    float* s_coarse = reinterpret_cast<float*>(zl + Cfg::TQ * Cfg::LDH);   // [TQ]
+    float* s_coarse = reinterpret_cast<float*>(DENSE ? zl + Cfg::TQ * Cfg::LDH : zl);   // [TQ] (the threshold pass keeps no lo panel)
     float* s_thr = s_coarse + Cfg::TQ;                              // [TQ] threshold, or (dense) offset of the pair's scores
     int32_t* s_q = reinterpret_cast<int32_t*>(s_thr + Cfg::TQ);     // [TQ]
     int32_t* s_p = s_q + Cfg::TQ;                                   // [TQ] probe rank of the pair
@@ -536,23 +537,26 @@ __global__ __launch_bounds__(256) void k_merge(MergeArgs a) {
     }
 }
 
-template <int DP, int B, int NQ, int WAVES, int OCC>
+// WD, OD: wavefronts per workgroup and per SIMD of the dense pass; WT, OT: of the threshold pass (which is
+// lighter in registers and LDS, so smaller workgroups let several share a compute unit and overlap their set-up).
+template <int DP, int B, int NQ, int WD, int OD, int WT, int OT>
 hipError_t run_batch(const BatchScanArgs& a, int max_tiles, hipStream_t st) {
     static bool attr_set = false;
     const size_t lds = BatchCfg<DP, B, NQ>::lds_bytes;
+    const size_t lds_threshold = BatchCfg<DP, B, NQ>::lds_bytes_threshold;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_batch_scan<DP, B, NQ, WAVES, OCC, false>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_batch_scan<DP, B, NQ, WT, OT, false>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_threshold);
         if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_batch_scan<DP, B, NQ, WAVES, OCC, true>),
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_batch_scan<DP, B, NQ, WD, OD, true>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     if (a.dense)
-        hipLaunchKernelGGL((k_batch_scan<DP, B, NQ, WAVES, OCC, true>), dim3((unsigned)max_tiles), dim3(WAVES * 64), lds, st, a);
+        hipLaunchKernelGGL((k_batch_scan<DP, B, NQ, WD, OD, true>), dim3((unsigned)max_tiles), dim3(WD * 64), lds, st, a);
     else
-        hipLaunchKernelGGL((k_batch_scan<DP, B, NQ, WAVES, OCC, false>), dim3((unsigned)max_tiles), dim3(WAVES * 64), lds, st, a);
+        hipLaunchKernelGGL((k_batch_scan<DP, B, NQ, WT, OT, false>), dim3((unsigned)max_tiles), dim3(WT * 64), lds_threshold, st, a);
     return hipGetLastError();
 }
 
@@ -606,15 +610,26 @@ hipError_t launch_batch_scan(const BatchScanArgs& a, int d, int b, int max_tiles
 #ifndef IVFTQ_BATCH_OCC
 #define IVFTQ_BATCH_OCC 2
 #endif
-#define IVFTQ_BATCH(DPV, NQV, OCCV)                                                            \
-    if (dp == DPV) {                                                                           \
-        if (b == 2) return run_batch<DPV, 2, NQV, IVFTQ_BATCH_WAVES, OCCV>(a, max_tiles, st);  \
-        if (b == 3) return run_batch<DPV, 3, NQV, IVFTQ_BATCH_WAVES, OCCV>(a, max_tiles, st);  \
-        if (b == 4) return run_batch<DPV, 4, NQV, IVFTQ_BATCH_WAVES, OCCV>(a, max_tiles, st);  \
-        if (b == 5) return run_batch<DPV, 5, NQV, IVFTQ_BATCH_WAVES, OCCV>(a, max_tiles, st);  \
+#ifndef IVFTQ_BATCH_WAVES_T224
+#define IVFTQ_BATCH_WAVES_T224 4
+#endif
+#ifndef IVFTQ_BATCH_WAVES_T
+#define IVFTQ_BATCH_WAVES_T 4
+#endif
+#ifndef IVFTQ_BATCH_OCC_T
+#define IVFTQ_BATCH_OCC_T 3
+#endif
+#define IVFTQ_BATCH(DPV, NQV, OCCV, WT, OT)                                                                       \
+    if (dp == DPV) {                                                                                              \
+        if (b == 2) return run_batch<DPV, 2, NQV, IVFTQ_BATCH_WAVES, OCCV, WT, OT>(a, max_tiles, st);             \
+        if (b == 3) return run_batch<DPV, 3, NQV, IVFTQ_BATCH_WAVES, OCCV, WT, OT>(a, max_tiles, st);             \
+        if (b == 4) return run_batch<DPV, 4, NQV, IVFTQ_BATCH_WAVES, OCCV, WT, OT>(a, max_tiles, st);             \
+        if (b == 5) return run_batch<DPV, 5, NQV, IVFTQ_BATCH_WAVES, OCCV, WT, OT>(a, max_tiles, st);             \
     }
-    IVFTQ_BATCH(64, 4, IVFTQ_BATCH_OCC) IVFTQ_BATCH(96, 4, IVFTQ_BATCH_OCC)
-    IVFTQ_BATCH(128, 4, IVFTQ_BATCH_OCC) IVFTQ_BATCH(224, 2, 2)
+    IVFTQ_BATCH(64, 4, IVFTQ_BATCH_OCC, IVFTQ_BATCH_WAVES_T, IVFTQ_BATCH_OCC_T)
+    IVFTQ_BATCH(96, 4, IVFTQ_BATCH_OCC, IVFTQ_BATCH_WAVES_T, IVFTQ_BATCH_OCC_T)
+    IVFTQ_BATCH(128, 4, IVFTQ_BATCH_OCC, IVFTQ_BATCH_WAVES_T, IVFTQ_BATCH_OCC_T)
+    IVFTQ_BATCH(224, 2, 2, IVFTQ_BATCH_WAVES_T224, 2)
 #undef IVFTQ_BATCH
     return hipErrorInvalidValue;
 }
