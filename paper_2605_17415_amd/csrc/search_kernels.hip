@@ -331,11 +331,12 @@ __global__ __launch_bounds__(256) void k_select_small(SelectArgs a) {
     // Leading bytes that every key of the row shares (scores of one query usually share sign and exponent)
     // need no pass: their histogram would be one bin that all lanes hit at once.
     int top_shift = 24;
-    if (take > 0 && m <= NV * 64) {
+    if (take > 0) {
         const uint32_t first = __builtin_amdgcn_readfirstlane(keys[0]);
         uint32_t diff = 0u;
 #pragma unroll
         for (int e = 0; e < NV; ++e) diff |= (e * 64 + lane < m) ? (keys[e] ^ first) : 0u;
+        for (int i = NV * 64 + lane; i < m; i += 64) diff |= key_of(vals[i]) ^ first;      // columns beyond the registers
         if (__ballot((diff >> 24) != 0u) == 0ull) {
             prefix = first & 0xFF000000u; mask = 0xFF000000u; top_shift = 16;
             if (__ballot((diff >> 16) != 0u) == 0ull) { prefix = first & 0xFFFF0000u; mask = 0xFFFF0000u; top_shift = 8; }
