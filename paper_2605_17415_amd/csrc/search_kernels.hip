@@ -182,15 +182,28 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a) {
                 if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
             }
             __syncthreads();
-            if (tid == 0) {
-                uint32_t cum = 0;
-                int dgt = 255;
-                for (; dgt > 0; --dgt) {
-                    if (cum + hist[dgt] >= need) break;
-                    cum += hist[dgt];
+            if (wave == 0) {
+                // the digit where the count of keys with larger digits first reaches `need`: lane l owns the
+                // digits 4l .. 4l+3, a suffix sum over the lanes gives what lies above each lane
+                uint32_t h[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) h[e] = hist[lane * 4 + e];
+                const uint32_t own = h[0] + h[1] + h[2] + h[3];
+                uint32_t incl = own;
+#pragma unroll
+                for (int o = 1; o < 64; o <<= 1) {
+                    const uint32_t t = __shfl_down(incl, o);
+                    if (lane + o < 64) incl += t;
                 }
-                ctrl[0] = (uint32_t)dgt;
-                ctrl[1] = need - cum;
+                uint32_t above = incl - own;
+                int found = -1;
+                uint32_t before = 0;
+#pragma unroll
+                for (int e = 3; e >= 0; --e) {
+                    if (found < 0 && above < need && above + h[e] >= need) { found = lane * 4 + e; before = above; }
+                    above += h[e];
+                }
+                if (found >= 0) { ctrl[0] = (uint32_t)found; ctrl[1] = need - before; }   // exactly one lane (need >= 1)
             }
             __syncthreads();
             prefix |= ctrl[0] << shift;
@@ -207,11 +220,17 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a) {
     __syncthreads();
     const uint32_t n_above = (uint32_t)take - need;
     if (take > 0) {
-        for (int base = 0; base < m; base += 256) {
-            const int i = base + tid;
+        // Keys above the threshold go anywhere in the first n_above places (atomic counter).  Keys equal to it
+        // are taken in column order: each wavefront owns a contiguous quarter of the row, counts its ties in a
+        // first sweep and, once the counts of the wavefronts before it are known, places them in a second.
+        const int chunk = ((m + 3) / 4 + 63) & ~63;
+        const int w_begin = wave * chunk, w_end = (w_begin + chunk < m) ? w_begin + chunk : m;
+        uint32_t my_ties = 0;
+        for (int i0 = w_begin; i0 < w_end; i0 += 64) {
+            const int i = i0 + lane;
             uint32_t key = 0;
             bool above = false, tie = false;
-            if (i < m) {
+            if (i < w_end) {
                 key = order_key(vals[i]);
                 above = all || key > prefix;
                 tie = !all && key == prefix;
@@ -221,20 +240,27 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a) {
                 s_key[pos] = key;
                 s_col[pos] = (uint32_t)i;
             }
-            // ties in column order: ordered compaction across the workgroup
+            my_ties += (uint32_t)__popcll(__ballot(tie));
+        }
+        if (lane == 0) wave_cnt[wave] = my_ties;
+        __syncthreads();
+        uint32_t before = 0;
+        for (int w = 0; w < wave; ++w) before += wave_cnt[w];
+        for (int i0 = w_begin; i0 < w_end && before < need; i0 += 64) {
+            const int i = i0 + lane;
+            uint32_t key = 0;
+            bool tie = false;
+            if (i < w_end) {
+                key = order_key(vals[i]);
+                tie = !all && key == prefix;
+            }
             const uint64_t bal = __ballot(tie);
-            if (lane == 0) wave_cnt[wave] = (uint32_t)__popcll(bal);
-            __syncthreads();
-            uint32_t before = ctrl[3];
-            for (int w = 0; w < wave; ++w) before += wave_cnt[w];
             const uint32_t rank = before + (uint32_t)__popcll(bal & ((1ull << lane) - 1ull));
             if (tie && rank < need) {
                 s_key[n_above + rank] = key;
                 s_col[n_above + rank] = (uint32_t)i;
             }
-            __syncthreads();
-            if (tid == 0) ctrl[3] += wave_cnt[0] + wave_cnt[1] + wave_cnt[2] + wave_cnt[3];
-            __syncthreads();
+            before += (uint32_t)__popcll(bal);
         }
     }
     __syncthreads();
