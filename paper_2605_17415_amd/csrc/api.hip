@@ -1055,8 +1055,6 @@ ivftq_status search_core(ivftq_index* ix, const float* q_dev, int64_t nq, int np
     if (m_bound > INT32_MAX - 4) return fail(IVFTQ_UNSUPPORTED, "more than 2^31 candidates per query");
     const int64_t m_stride = std::max<int64_t>(4, round_up64(m_bound, 4));
     const int64_t ldS = round_up(ix->nlist, 4);
-    int64_t qc = ix->ws_limit / (4 * std::max(m_stride, ldS));
-    qc = std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(qc, nq), 32768));
 
     // Scan strategy.  Streaming: one workgroup per (query, probed list), every score written, exact
     // selection.  Batched: pairs regrouped by list and scanned on the matrix cores against a
@@ -1070,9 +1068,20 @@ ivftq_status search_core(ivftq_index* ix, const float* q_dev, int64_t nq, int np
     float cmax = 0.f;
     for (float v : ix->h_cb) cmax = std::max(cmax, std::fabs(v));
     const float kappa = screen_kappa(ix->d, cmax);
+    // Score rows.  The batched path stores scores of the dense prefix only (it stops at the first list that
+    // brings it to max(k, k*T/cap) vectors, so it is shorter than that plus the largest list); full-length
+    // rows are needed for the queries redone exactly, which take turns in gate_rows rows of the same buffer.
+    // The streaming path stores every score.  Queries per pass: as many as the workspace limit allows, since
+    // every pass walks every probed list again.
+    const int64_t need_max = std::max<int64_t>(k, (kPrefixFactorX2 * (int64_t)k * m_bound + 2 * cap - 1) / (2 * cap));
+    const int64_t row_stride = batched ? std::min<int64_t>(m_stride, round_up64(need_max + sizes[0], 4)) : m_stride;
+    int64_t qc = ix->ws_limit / (4 * std::max(row_stride, ldS));
+    qc = std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(qc, nq), 32768));
+    const int64_t gate_rows = std::max<int64_t>(1, std::min<int64_t>(qc, ix->ws_limit / (4 * m_stride)));
+    const int64_t score_floats = batched ? std::max(qc * row_stride, gate_rows * m_stride) : qc * m_stride;
 
     HIP_TRY(ix->w_S.ensure((size_t)qc * ldS * sizeof(float)));
-    HIP_TRY(ix->w_scores.ensure((size_t)qc * m_stride * sizeof(float)));
+    HIP_TRY(ix->w_scores.ensure((size_t)score_floats * sizeof(float)));
     HIP_TRY(ix->w_probe.ensure((size_t)qc * nprobe * sizeof(int32_t)));
     HIP_TRY(ix->w_coarse.ensure((size_t)qc * nprobe * sizeof(float)));
     HIP_TRY(ix->w_candoff.ensure((size_t)qc * (nprobe + 1) * sizeof(int32_t)));
@@ -1108,11 +1117,12 @@ ivftq_status search_core(ivftq_index* ix, const float* q_dev, int64_t nq, int np
         HIP_TRY(timed(ix, st, P_CAND_OFF, [&] {
             return launch_cand_offsets(ix->w_probe.as<int32_t>(), cnt, nprobe, ix->d_size.as<int32_t>(),
                                        ix->w_candoff.as<int32_t>(), k, cap, first, st); }));
-        auto stream_scan = [&](const int32_t* p_limit, const int32_t* gate, int blocks_per_query) {
+        auto stream_scan = [&](const int32_t* gate, int gate_begin, int blocks_per_query) {
             return launch_list_scan(ix->w_z.as<float>(), ix->dp, ix->d, ix->b, cb,
                                     ix->w_probe.as<int32_t>(), ix->w_coarse.as<float>(),
                                     ix->w_candoff.as<int32_t>(), nprobe, ix->store(), 0, cnt,
-                                    ix->w_scores.as<float>(), m_stride, p_limit, gate, blocks_per_query, st);
+                                    ix->w_scores.as<float>(), m_stride, nullptr, gate, gate_begin, (int)gate_rows,
+                                    blocks_per_query, st);
         };
         SelectArgs sa{};
         sa.vals = ix->w_scores.as<float>(); sa.stride = m_stride; sa.rows = cnt; sa.k = k;
@@ -1126,7 +1136,7 @@ ivftq_status search_core(ivftq_index* ix, const float* q_dev, int64_t nq, int np
             // workgroups per query: each builds the query's table once and walks its share of the probes;
             // fewer per query as the batch grows, as long as the launch still fills the chip
             const int per_query = (int)std::min<int64_t>(nprobe, std::max<int64_t>(1, kStreamWorkgroups / cnt));
-            HIP_TRY(timed(ix, st, P_LIST_SCAN, [&] { return stream_scan(nullptr, nullptr, per_query); }));
+            HIP_TRY(timed(ix, st, P_LIST_SCAN, [&] { return stream_scan(nullptr, 0, per_query); }));
             HIP_TRY(timed(ix, st, P_SELECT_TOPK, [&] { return launch_select(1, sa, st); }));
             continue;
         }
@@ -1151,16 +1161,14 @@ ivftq_status search_core(ivftq_index* ix, const float* q_dev, int64_t nq, int np
         ba.cand_score = ix->w_cscore.as<float>(); ba.cand_slot = ix->w_cslot.as<int64_t>();
         ba.cand_cnt = ix->w_ccnt.as<int32_t>(); ba.cap = cap;
         ba.acc0 = kappa * kSplitScale * kSplitScale;
-        ba.scores = ix->w_scores.as<float>(); ba.m_stride = m_stride; ba.cand_off = ix->w_candoff.as<int32_t>();
+        ba.scores = ix->w_scores.as<float>(); ba.m_stride = row_stride; ba.cand_off = ix->w_candoff.as<int32_t>();
         const int max_tiles = (int)(np_items / tq) + ix->nlist;
         // 2. every score of the nearest lists, then their top-k: the k-th is the query's threshold
         ba.dense = 1; ba.bucket_lo = 0; ba.bucket_hi = ix->nlist;
         HIP_TRY(timed(ix, st, P_BATCH_FIRST, [&] { return launch_batch_scan(ba, ix->d, ix->b, max_tiles, st); }));
         SelectArgs s1 = sa;
         s1.p_limit = first; s1.out_vals = ix->w_fscores.as<float>(); s1.out_i64 = ix->w_fids.as<int64_t>();
-        // the dense prefix stops at the first list that brings it to max(k, 2*k*T/cap) vectors
-        const int64_t need_max = std::max<int64_t>(k, (kPrefixFactorX2 * (int64_t)k * m_bound + 2 * cap - 1) / (2 * cap));
-        s1.m_bound = (int)std::min<int64_t>(m_stride, need_max + sizes[0]);
+        s1.stride = row_stride; s1.m_bound = (int)row_stride;
         HIP_TRY(timed(ix, st, P_SELECT_TOPK, [&] { return launch_select(1, s1, st); }));
         // 3. the other lists against the thresholds
         ba.dense = 0; ba.bucket_lo = ix->nlist; ba.bucket_hi = 2 * ix->nlist;
@@ -1177,10 +1185,13 @@ ivftq_status search_core(ivftq_index* ix, const float* q_dev, int64_t nq, int np
         ma.k = k; ma.out_scores = scores_dev + q0 * k; ma.out_ids = ids_dev + q0 * k;
         ma.gate = ix->w_gate.as<int32_t>();
         HIP_TRY(timed(ix, st, P_MERGE, [&] { return launch_merge(ma, cnt, st); }));
-        HIP_TRY(timed(ix, st, P_LIST_SCAN, [&] { return stream_scan(nullptr, ix->w_gate.as<int32_t>(), 8); }));
         SelectArgs s2 = sa;
-        s2.gate = ix->w_gate.as<int32_t>();
-        HIP_TRY(timed(ix, st, P_SELECT_TOPK, [&] { return launch_select(1, s2, st); }));
+        s2.gate = ix->w_gate.as<int32_t>(); s2.gate_rows = (int)gate_rows;
+        for (int64_t g0 = 0; g0 < cnt; g0 += gate_rows) {
+            s2.gate_begin = (int)g0;
+            HIP_TRY(timed(ix, st, P_LIST_SCAN, [&] { return stream_scan(ix->w_gate.as<int32_t>(), (int)g0, 8); }));
+            HIP_TRY(timed(ix, st, P_SELECT_TOPK, [&] { return launch_select(1, s2, st); }));
+        }
     }
     return IVFTQ_OK;
 }

@@ -149,14 +149,16 @@ hipError_t launch_inertia(const float* best, int64_t n, double* out, hipStream_t
 // max(k, 2*k*T/cap) vectors, T the query's candidate total; np if there is none
 hipError_t launch_cand_offsets(const int32_t* probe, int64_t nq, int np, const int32_t* list_size,
                                int32_t* cand_off, int k, int cap, int32_t* first, hipStream_t st);
-// scores[qi*m_stride + cand_off[q][p] + i] = coarse[q][p] + gamma_i * sum_j z_qj * C[code_ij]
+// scores[row*m_stride + cand_off[q][p] + i] = coarse[q][p] + gamma_i * sum_j z_qj * C[code_ij]
 hipError_t launch_list_scan(const float* z, int z_pitch, int d, int b, const float* cb,
                             const int32_t* probe, const float* coarse, const int32_t* cand_off,
                             int np, const ListStore& store, int64_t q_begin, int64_t q_count,
                             float* scores, int64_t m_stride, const int32_t* p_limit, const int32_t* gate,
-                            int blocks_per_query, hipStream_t st);
-// p_limit (may be null): only probes p < p_limit[q] are scanned.  gate (may be null): only the
-// gate[0] queries listed in gate[1..] are processed.  blocks_per_query: workgroups per query (0 = one per probe).
+                            int gate_begin, int gate_rows, int blocks_per_query, hipStream_t st);
+// p_limit (may be null): only probes p < p_limit[q] are scanned.  gate (may be null; row = the query's index
+// without it): of the gate[0] queries listed in gate[1..] only entries [gate_begin, gate_begin + gate_rows) are
+// processed, entry g into score row g - gate_begin, so a buffer of gate_rows rows serves any number of listed
+// queries in several launches.  blocks_per_query: workgroups per query (0 = one per probe).
 
 // Per row: the k largest of m values, sorted by (value desc, label asc).
 // mode 0 (probe selection): m = m_fixed for every row, label = column; writes int32 labels.
@@ -167,7 +169,8 @@ struct SelectArgs {
     int m_fixed;
     const int32_t* cand_off; const int32_t* probe; int np; int64_t q_begin;
     const int32_t* p_limit;   // mode 1: row q only has the candidates of probes p < p_limit[q] (null = all)
-    const int32_t* gate;      // gate[0] rows listed in gate[1..] are processed instead of all (null = all)
+    const int32_t* gate;      // null = all rows; else of the gate[0] rows listed in gate[1..] the entries
+    int gate_begin, gate_rows;   // [gate_begin, gate_begin + gate_rows) are processed, entry g reading vals row g - gate_begin
     const int64_t* list_off; const int64_t* ids;
     float* out_vals; int32_t* out_i32; int64_t* out_i64;
     int m_bound;      // mode 1: host-side upper bound of any row's length (0 = unknown); picks the kernel

@@ -55,14 +55,17 @@ __global__ __launch_bounds__(256) void k_list_scan(const float* __restrict__ z, 
                                                    ListStore store, int64_t q_begin,
                                                    float* __restrict__ scores, int64_t m_stride,
                                                    const int32_t* __restrict__ p_limit,
-                                                   const int32_t* __restrict__ gate) {
+                                                   const int32_t* __restrict__ gate, int gate_begin, int gate_rows) {
     constexpr int K = 1 << B;
     extern __shared__ float lut[];     // [d][K], or z[d] followed by C[K] when DIRECT
-    // gate (may be null): gate[0] queries, listed in gate[1..], are processed instead of all; the
-    // grid's y extent is then fixed and each workgroup row walks the list
-    const int64_t n_rows = gate ? gate[0] : gridDim.y;
-    for (int64_t row_i = blockIdx.y; row_i < n_rows; row_i += gridDim.y) {
+    // gate (may be null): of the gate[0] queries listed in gate[1..], entries [gate_begin, gate_begin +
+    // gate_rows) are processed instead of all queries, entry g writing score row g - gate_begin; the grid's
+    // y extent is then fixed and each workgroup row walks the list
+    int64_t n_rows = gridDim.y;
+    if (gate) n_rows = gate[0] < gate_begin + gate_rows ? gate[0] : gate_begin + gate_rows;
+    for (int64_t row_i = (gate ? gate_begin : 0) + blockIdx.y; row_i < n_rows; row_i += gridDim.y) {
     const int64_t qi = gate ? gate[1 + row_i] : row_i;     // index inside this pass
+    const int64_t score_row = gate ? row_i - gate_begin : qi;
     const int64_t q = q_begin + qi;
     const int p_end = p_limit ? p_limit[q] : np;
     if ((int)blockIdx.x >= p_end) continue;
@@ -86,7 +89,7 @@ __global__ __launch_bounds__(256) void k_list_scan(const float* __restrict__ z, 
     const int n_l = store.list_size[l];
     const float s_l = coarse[q * np + p];
     const int64_t base_slot = store.list_off[l];
-    float* out = scores + qi * m_stride + cand_off[q * (np + 1) + p];
+    float* out = scores + score_row * m_stride + cand_off[q * (np + 1) + p];
 
     for (int v = threadIdx.x; v < n_l; v += 256) {
         const int64_t slot = base_slot + v;
@@ -157,10 +160,11 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a) {
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     // gate (may be null): a.gate[0] rows, listed in a.gate[1..], are processed instead of all
-    const int64_t n_rows = a.gate ? a.gate[0] : a.rows;
-    for (int64_t row_i = blockIdx.x; row_i < n_rows; row_i += gridDim.x) {
+    int64_t n_rows = a.rows;
+    if (a.gate) n_rows = a.gate[0] < a.gate_begin + a.gate_rows ? a.gate[0] : a.gate_begin + a.gate_rows;
+    for (int64_t row_i = (a.gate ? a.gate_begin : 0) + blockIdx.x; row_i < n_rows; row_i += gridDim.x) {
     const int64_t row = a.gate ? a.gate[1 + row_i] : row_i;
-    const float* vals = a.vals + row * a.stride;
+    const float* vals = a.vals + (a.gate ? row_i - a.gate_begin : row) * a.stride;
     const int64_t q = a.q_begin + row;
     __syncthreads();                   // LDS of the previous row is no longer read
     const int m = (MODE == 0) ? a.m_fixed
@@ -330,15 +334,16 @@ template <int MODE, int NV>
 __global__ __launch_bounds__(256) void k_select_small(SelectArgs a) {
     __shared__ uint32_t s_work[4][256 + 64];             // per wavefront: 256 bins, 64 winning columns
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int64_t n_rows = a.gate ? a.gate[0] : a.rows;
-    for (int64_t row_i = (int64_t)blockIdx.x * 4 + wave; row_i < n_rows; row_i += (int64_t)gridDim.x * 4) {
+    int64_t n_rows = a.rows;
+    if (a.gate) n_rows = a.gate[0] < a.gate_begin + a.gate_rows ? a.gate[0] : a.gate_begin + a.gate_rows;
+    for (int64_t row_i = (a.gate ? a.gate_begin : 0) + (int64_t)blockIdx.x * 4 + wave; row_i < n_rows; row_i += (int64_t)gridDim.x * 4) {
     const int64_t row = a.gate ? a.gate[1 + row_i] : row_i;
     const int64_t q = a.q_begin + row;
     const int m = (MODE == 0) ? a.m_fixed
                               : a.cand_off[q * (a.np + 1) + (a.p_limit ? a.p_limit[q] : a.np)];
     const int k = a.k;
     const int take = m < k ? m : k;
-    const float* vals = a.vals + row * a.stride;
+    const float* vals = a.vals + (a.gate ? row_i - a.gate_begin : row) * a.stride;
     uint32_t* hist = s_work[wave];                                      // [256]
     int* win_col = reinterpret_cast<int*>(hist + 256);                  // [64]
     const float ninf = -__builtin_inff();
@@ -713,21 +718,21 @@ hipError_t launch_list_scan(const float* z, int z_pitch, int d, int b, const flo
                             const int32_t* probe, const float* coarse, const int32_t* cand_off,
                             int np, const ListStore& store, int64_t q_begin, int64_t q_count,
                             float* scores, int64_t m_stride, const int32_t* p_limit, const int32_t* gate,
-                            int blocks_per_query, hipStream_t st) {
+                            int gate_begin, int gate_rows, int blocks_per_query, hipStream_t st) {
     if (q_count <= 0) return hipSuccess;
     const size_t lut_bytes = (size_t)d * (1u << b) * sizeof(float);
     const bool direct = lut_bytes > 64 * 1024;
     const size_t lds = direct ? (size_t)(d + (1 << b)) * sizeof(float) : lut_bytes;
     // gated: a fixed number of workgroup rows walks the list of marked queries
-    dim3 grid((unsigned)(blocks_per_query > 0 ? blocks_per_query : np), (unsigned)(gate ? std::min<int64_t>(q_count, 256) : q_count));
+    dim3 grid((unsigned)(blocks_per_query > 0 ? blocks_per_query : np), (unsigned)(gate ? std::min<int64_t>(std::min<int64_t>(q_count, gate_rows), 256) : q_count));
 #define IVFTQ_SCAN(BV)                                                                              \
     case BV:                                                                                        \
         if (direct)                                                                                 \
             hipLaunchKernelGGL((k_list_scan<BV, true>), grid, dim3(256), lds, st, z, z_pitch, d, cb, probe, \
-                               coarse, cand_off, np, store, q_begin, scores, m_stride, p_limit, gate); \
+                               coarse, cand_off, np, store, q_begin, scores, m_stride, p_limit, gate, gate_begin, gate_rows); \
         else                                                                                        \
             hipLaunchKernelGGL((k_list_scan<BV, false>), grid, dim3(256), lds, st, z, z_pitch, d, cb, probe, \
-                               coarse, cand_off, np, store, q_begin, scores, m_stride, p_limit, gate); \
+                               coarse, cand_off, np, store, q_begin, scores, m_stride, p_limit, gate, gate_begin, gate_rows); \
         break;
     switch (b) {
         IVFTQ_SCAN(1) IVFTQ_SCAN(2) IVFTQ_SCAN(3) IVFTQ_SCAN(4)
@@ -745,7 +750,7 @@ hipError_t launch_select(int mode, const SelectArgs& a_in, hipStream_t st) {
     const int m_bound = mode == 0 ? a.m_fixed : a.m_bound;
     if (a.k <= 64 && m_bound > 0 && m_bound <= kSmallM) {
         const size_t lds = 0;
-        const unsigned blocks = (unsigned)((a.gate ? std::min<int64_t>(a.rows, 1024) : a.rows) + 3) / 4;
+        const unsigned blocks = (unsigned)((a.gate ? std::min<int64_t>(std::min<int64_t>(a.rows, a.gate_rows), 1024) : a.rows) + 3) / 4;
 #define IVFTQ_SMALL(NVV)                                                                            \
         if (mode == 0) hipLaunchKernelGGL((k_select_small<0, NVV>), dim3(blocks), dim3(256), lds, st, a);  \
         else hipLaunchKernelGGL((k_select_small<1, NVV>), dim3(blocks), dim3(256), lds, st, a);
@@ -756,7 +761,7 @@ hipError_t launch_select(int mode, const SelectArgs& a_in, hipStream_t st) {
     int kpad = 1;
     while (kpad < a.k) kpad <<= 1;
     const size_t lds = (256 + 8 + 4) * 4 + (size_t)kpad * 8 + 8 + (size_t)kpad * 8;
-    const unsigned wgs = (unsigned)(a.gate ? std::min<int64_t>(a.rows, 256) : a.rows);
+    const unsigned wgs = (unsigned)(a.gate ? std::min<int64_t>(std::min<int64_t>(a.rows, a.gate_rows), 256) : a.rows);
     if (mode == 0)
         hipLaunchKernelGGL(k_select<0>, dim3(wgs), dim3(256), lds, st, a);
     else

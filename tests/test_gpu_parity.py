@@ -147,6 +147,50 @@ def test_batched_scan_overflow_falls_back_to_the_exact_scan():
         ix.close()
 
 
+def test_many_overflowing_queries_take_turns_in_the_full_length_rows():
+    """Under a small workspace limit the batched path keeps short score rows (dense prefix) for all queries of
+    a pass and only a few full-length rows for the queries it has to redo exactly: nine queries overflow here
+    and three rows are available, so the exact pass runs in several turns.  Every query must match the oracle."""
+    cs = gpu_cases.get_case("tiny")
+    dev = _dev()
+    K = 1 << cs.b
+    Q = np.concatenate([np.repeat(cs.Q[:1], 9, axis=0), cs.Q[1:4]]).astype(np.float32)
+    Q[1:9] *= np.linspace(0.5, 3.0, 8, dtype=np.float32)[:, None]     # same direction: same answer after normalising
+    qn = orc.normalize_rows(Q[:1])
+    S = qn @ cs.cent.astype(np.float64).T
+    z = qn @ cs.Pi.astype(np.float64).T
+    order = np.argsort(-S[0])
+    rng = np.random.default_rng(1)
+    worst = np.where(z[0] > 0, 0, K - 1).astype(np.uint8)
+    assign = [np.full(20, order[0]), np.full(100, order[1])]
+    codes = [np.tile(worst, (120, 1))]
+    gamma = [np.ones(120)]
+    per_list = 12000                       # zero residual norm: every score equals the coarse term
+    for l in order[2:8]:
+        assign.append(np.full(per_list, l))
+        codes.append(rng.integers(0, K, (per_list, cs.d)).astype(np.uint8))
+        gamma.append(np.zeros(per_list))
+    assign = np.concatenate(assign).astype(np.int32)
+    codes = np.concatenate(codes)
+    gamma = np.concatenate(gamma).astype(np.float16)
+    ref = orc.ListIndex(cs.cent, cs.Pi, cs.c, cs.tau)
+    ref.add_encoded(assign, np.arange(len(assign), dtype=np.int64), codes, gamma)
+    o_sc, o_ids, _, S_all, o_all = orc.search(ref, Q, 8, 10, return_all=True)
+    ix = _make_index(cs)
+    ix.add_encoded(torch.from_numpy(assign).to(dev), torch.from_numpy(codes).to(dev), torch.from_numpy(gamma).to(dev))
+    ix.set_workspace_limit(1 << 20)        # 3 rows of 8 lists' length, 12 queries in one pass
+    print("[turns] search", flush=True)
+    sc, ids = ix.search(torch.from_numpy(Q).to(dev), 8, 10)
+    torch.cuda.synchronize()
+    rep = parity.compare_search(sc.cpu().numpy(), ids.cpu().numpy(), o_sc, o_ids, o_all, parity.probe_cut_gap(S_all, 8))
+    print("turns:", rep, flush=True)
+    ix.set_workspace_limit(1 << 32)        # one turn: same bits
+    sc2, ids2 = ix.search(torch.from_numpy(Q).to(dev), 8, 10)
+    torch.cuda.synchronize()
+    assert torch.equal(sc, sc2) and torch.equal(ids, ids2)
+    ix.close()
+
+
 @pytest.mark.parametrize("name", ["d128", "d96_b3"])
 def test_batched_scan_with_duplicated_vectors_ranks_ties_by_label(name):
     """Every stored vector three times under different labels: the batched scan's threshold pass works
