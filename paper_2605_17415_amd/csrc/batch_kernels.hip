@@ -562,11 +562,15 @@ hipError_t run_batch(const BatchScanArgs& a, int max_tiles, hipStream_t st) {
 
 }  // namespace
 
+#ifndef IVFTQ_BATCH_NQ224
+#define IVFTQ_BATCH_NQ224 4
+#endif
+
 int batch_tile_queries(int d, int b) {
     const int dp = rot_dp(d);
     if (b < 2 || b > 5) return 0;
     if (dp == 64 || dp == 96 || dp == 128) return 128;
-    if (dp == 224) return 64;
+    if (dp == 224) return 32 * IVFTQ_BATCH_NQ224;
     return 0;
 }
 
@@ -629,7 +633,7 @@ hipError_t launch_batch_scan(const BatchScanArgs& a, int d, int b, int max_tiles
     IVFTQ_BATCH(64, 4, IVFTQ_BATCH_OCC, IVFTQ_BATCH_WAVES_T, IVFTQ_BATCH_OCC_T)
     IVFTQ_BATCH(96, 4, IVFTQ_BATCH_OCC, IVFTQ_BATCH_WAVES_T, IVFTQ_BATCH_OCC_T)
     IVFTQ_BATCH(128, 4, IVFTQ_BATCH_OCC, IVFTQ_BATCH_WAVES_T, IVFTQ_BATCH_OCC_T)
-    IVFTQ_BATCH(224, 2, 2, IVFTQ_BATCH_WAVES_T224, 2)
+    IVFTQ_BATCH(224, IVFTQ_BATCH_NQ224, 2, IVFTQ_BATCH_WAVES_T224, 2)
 #undef IVFTQ_BATCH
     return hipErrorInvalidValue;
 }

@@ -146,6 +146,8 @@ __device__ __forceinline__ uint32_t order_key(float f) {
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
+constexpr int kSelU = 8;
+
 template <int MODE>
 __global__ __launch_bounds__(256) void k_select(SelectArgs a) {
     extern __shared__ unsigned char smem[];
@@ -174,6 +176,10 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a) {
 
     for (int i = tid; i < kpad; i += 256) { s_key[i] = 0u; s_col[i] = 0xFFFFFFFFu; s_lab[i] = INT64_MAX; }
 
+    // each wavefront owns a contiguous quarter [w_begin, w_end) of the row
+    const int chunk = ((m + 3) / 4 + 63) & ~63;
+    const int w_begin = wave * chunk < m ? wave * chunk : m;
+    const int w_end = (w_begin + chunk < m) ? w_begin + chunk : m;
     uint32_t prefix = 0, mask = 0;
     uint32_t need = (uint32_t)take;
     if (take > 0 && m > k) {
@@ -181,9 +187,20 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a) {
             const int shift = 24 - 8 * pass;
             hist[tid] = 0;
             __syncthreads();
-            for (int i = tid; i < m; i += 256) {
-                const uint32_t key = order_key(vals[i]);
-                if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+            // kSelU groups of 64 columns per step, their loads in flight together (the pass is bound by the
+            // latency of reading the row, not by its arithmetic)
+            for (int i0 = w_begin; i0 < w_end; i0 += 64 * kSelU) {
+                float v[kSelU];
+#pragma unroll
+                for (int u = 0; u < kSelU; ++u) {
+                    const int i = i0 + 64 * u + lane;
+                    v[u] = vals[i < w_end ? i : w_end - 1];
+                }
+#pragma unroll
+                for (int u = 0; u < kSelU; ++u) {
+                    const uint32_t key = order_key(v[u]);
+                    if (i0 + 64 * u + lane < w_end && (key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+                }
             }
             __syncthreads();
             if (wave == 0) {
@@ -227,30 +244,33 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a) {
         // Keys above the threshold go anywhere in the first n_above places (atomic counter).  Keys equal to it
         // are taken in column order: each wavefront owns a contiguous quarter of the row, counts its ties in a
         // first sweep and, once the counts of the wavefronts before it are known, places them in a second.
-        const int chunk = ((m + 3) / 4 + 63) & ~63;
-        const int w_begin = wave * chunk, w_end = (w_begin + chunk < m) ? w_begin + chunk : m;
         uint32_t my_ties = 0;
-        for (int i0 = w_begin; i0 < w_end; i0 += 64) {
-            const int i = i0 + lane;
-            uint32_t key = 0;
-            bool above = false, tie = false;
-            if (i < w_end) {
-                key = order_key(vals[i]);
-                above = all || key > prefix;
-                tie = !all && key == prefix;
+        for (int i0 = w_begin; i0 < w_end; i0 += 64 * kSelU) {
+            float v[kSelU];
+#pragma unroll
+            for (int u = 0; u < kSelU; ++u) {
+                const int i = i0 + 64 * u + lane;
+                v[u] = vals[i < w_end ? i : w_end - 1];
             }
-            if (above) {
-                const uint32_t pos = atomicAdd(&ctrl[2], 1u);
-                s_key[pos] = key;
-                s_col[pos] = (uint32_t)i;
+#pragma unroll
+            for (int u = 0; u < kSelU; ++u) {
+                const int i = i0 + 64 * u + lane;
+                const uint32_t key = order_key(v[u]);
+                const bool above = i < w_end && (all || key > prefix);
+                const bool tie = i < w_end && !all && key == prefix;
+                if (above) {
+                    const uint32_t pos = atomicAdd(&ctrl[2], 1u);
+                    s_key[pos] = key;
+                    s_col[pos] = (uint32_t)i;
+                }
+                my_ties += (uint32_t)__popcll(__ballot(tie));
             }
-            my_ties += (uint32_t)__popcll(__ballot(tie));
         }
         if (lane == 0) wave_cnt[wave] = my_ties;
         __syncthreads();
         uint32_t before = 0;
         for (int w = 0; w < wave; ++w) before += wave_cnt[w];
-        for (int i0 = w_begin; i0 < w_end && before < need; i0 += 64) {
+        for (int i0 = w_begin; i0 < w_end && before < need && my_ties > 0; i0 += 64) {
             const int i = i0 + lane;
             uint32_t key = 0;
             bool tie = false;
