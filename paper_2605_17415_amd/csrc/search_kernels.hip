@@ -146,7 +146,8 @@ __device__ __forceinline__ uint32_t order_key(float f) {
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
-constexpr int kSelU = 8;
+constexpr int kSelU = 8;        // groups of 64 columns loaded together by k_select
+constexpr int kSelSmallU = 4;   // and by k_select_small beyond its registers
 
 template <int MODE>
 __global__ __launch_bounds__(256) void k_select(SelectArgs a) {
@@ -387,7 +388,13 @@ __global__ __launch_bounds__(256) void k_select_small(SelectArgs a) {
         uint32_t diff = 0u;
 #pragma unroll
         for (int e = 0; e < NV; ++e) diff |= (e * 64 + lane < m) ? (keys[e] ^ first) : 0u;
-        for (int i = NV * 64 + lane; i < m; i += 64) diff |= key_of(vals[i]) ^ first;      // columns beyond the registers
+        for (int i0 = NV * 64; i0 < m; i0 += 64 * kSelSmallU) {                               // columns beyond the registers,
+            float v[kSelSmallU];                                                               // kSelSmallU loads in flight together
+#pragma unroll
+            for (int u = 0; u < kSelSmallU; ++u) { const int i = i0 + 64 * u + lane; v[u] = vals[i < m ? i : m - 1]; }
+#pragma unroll
+            for (int u = 0; u < kSelSmallU; ++u) diff |= key_of(v[u]) ^ first;                  // a clamped column repeats the last one
+        }
         if (__ballot((diff >> 24) != 0u) == 0ull) {
             prefix = first & 0xFF000000u; mask = 0xFF000000u; top_shift = 16;
             if (__ballot((diff >> 16) != 0u) == 0ull) { prefix = first & 0xFFFF0000u; mask = 0xFFFF0000u; top_shift = 8; }
@@ -402,9 +409,15 @@ __global__ __launch_bounds__(256) void k_select_small(SelectArgs a) {
 #pragma unroll
             for (int e = 0; e < NV; ++e)
                 if (e * 64 + lane < m && (keys[e] & mask) == prefix) atomicAdd(&hist[(keys[e] >> shift) & 255u], 1u);
-            for (int i = NV * 64 + lane; i < m; i += 64) {
-                const uint32_t key = key_of(vals[i]);
-                if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+            for (int i0 = NV * 64; i0 < m; i0 += 64 * kSelSmallU) {
+                float v[kSelSmallU];
+#pragma unroll
+                for (int u = 0; u < kSelSmallU; ++u) { const int i = i0 + 64 * u + lane; v[u] = vals[i < m ? i : m - 1]; }
+#pragma unroll
+                for (int u = 0; u < kSelSmallU; ++u) {
+                    const uint32_t key = key_of(v[u]);
+                    if (i0 + 64 * u + lane < m && (key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+                }
             }
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             __builtin_amdgcn_wave_barrier();
@@ -455,9 +468,13 @@ __global__ __launch_bounds__(256) void k_select_small(SelectArgs a) {
 #pragma unroll
         for (int e = 0; e < NV; ++e)
             if (e * 64 < m) place(e * 64 + lane, keys[e]);
-        for (int i0 = NV * 64; i0 < m; i0 += 64) {
-            const int i = i0 + lane;
-            place(i, i < m ? key_of(vals[i]) : 0u);
+        for (int i0 = NV * 64; i0 < m; i0 += 64 * kSelSmallU) {
+            float v[kSelSmallU];
+#pragma unroll
+            for (int u = 0; u < kSelSmallU; ++u) { const int i = i0 + 64 * u + lane; v[u] = vals[i < m ? i : m - 1]; }
+#pragma unroll
+            for (int u = 0; u < kSelSmallU; ++u)
+                if (i0 + 64 * u < m) place(i0 + 64 * u + lane, key_of(v[u]));
         }
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
