@@ -46,6 +46,9 @@ __global__ void k_cand_offsets(const int32_t* __restrict__ probe, int64_t nq, in
 // reads its packed words with 256-byte-per-wavefront coalesced loads and sums d table entries.
 // When the table would not fit LDS (large b and d) DIRECT keeps z and C separately and multiplies
 // per coordinate instead.
+#ifndef IVFTQ_SCAN_WU
+#define IVFTQ_SCAN_WU 8
+#endif
 template <int B, bool DIRECT>
 __global__ __launch_bounds__(256) void k_list_scan(const float* __restrict__ z, int z_pitch, int d,
                                                    const float* __restrict__ cb,
@@ -97,22 +100,25 @@ __global__ __launch_bounds__(256) void k_list_scan(const float* __restrict__ z, 
         float acc = 0.f;
         if constexpr (32 % B == 0) {
             constexpr int per = 32 / B;
-            int j = 0;
-            for (int w = 0; w < words; ++w) {
-                uint32_t word = wp[w * 64];
-                if (j + per <= d) {
+            constexpr int WU = IVFTQ_SCAN_WU;  // words fetched together: their latency overlaps
+            for (int w0 = 0; w0 < words; w0 += WU) {
+                uint32_t wd[WU];
 #pragma unroll
-                    for (int t = 0; t < per; ++t) {
-                        acc += term(j + t, word & (K - 1));
-                        word >>= B;
-                    }
-                } else {
-                    for (int t = 0; t < per && j + t < d; ++t) {
-                        acc += term(j + t, word & (K - 1));
-                        word >>= B;
+                for (int u = 0; u < WU; ++u) wd[u] = (w0 + u < words) ? wp[(w0 + u) * 64] : 0u;
+#pragma unroll
+                for (int u = 0; u < WU; ++u) {
+                    const int j = (w0 + u) * per;
+                    uint32_t word = wd[u];
+                    if (j + per <= d) {
+#pragma unroll
+                        for (int t = 0; t < per; ++t) acc += term(j + t, __builtin_amdgcn_ubfe(word, t * B, B));   // one bit-field extract per code
+                    } else {
+                        for (int t = 0; t < per && j + t < d; ++t) {
+                            acc += term(j + t, word & (K - 1));
+                            word >>= B;
+                        }
                     }
                 }
-                j += per;
             }
         } else {
             uint64_t buf = 0;
