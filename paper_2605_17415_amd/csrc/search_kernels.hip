@@ -121,16 +121,23 @@ __global__ __launch_bounds__(256) void k_list_scan(const float* __restrict__ z, 
                 }
             }
         } else {
-            uint64_t buf = 0;
-            int nb = 0, j = 0;
-            for (int w = 0; w < words; ++w) {
-                buf |= (uint64_t)wp[w * 64] << nb;
-                nb += 32;
-                while (nb >= B && j < d) {
-                    acc += term(j, (uint32_t)(buf & (K - 1)));
-                    buf >>= B;
-                    nb -= B;
-                    ++j;
+            // B words hold exactly 32 codes, at bit positions known at compile time: the words are fetched
+            // together and every code is one bit-field extract (two shifts where it straddles a word)
+            for (int w0 = 0; w0 < words; w0 += B) {
+                uint32_t wd[B + 1];
+#pragma unroll
+                for (int u = 0; u < B; ++u) wd[u] = (w0 + u < words) ? wp[(w0 + u) * 64] : 0u;
+                wd[B] = 0u;
+                const int j0 = (w0 / B) * 32;
+                const bool whole = j0 + 32 <= d;
+#pragma unroll
+                for (int t = 0; t < 32; ++t) {
+                    constexpr int kBits = B;
+                    const int wi = (t * kBits) >> 5, sh = (t * kBits) & 31;
+                    const uint32_t code = (sh + kBits <= 32)
+                        ? __builtin_amdgcn_ubfe(wd[wi], sh, kBits)
+                        : (((wd[wi] >> sh) | (wd[wi + 1] << (32 - sh))) & (uint32_t)(K - 1));
+                    if (whole || j0 + t < d) acc += term(j0 + t, code);
                 }
             }
         }
