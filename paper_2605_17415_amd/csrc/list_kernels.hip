@@ -30,15 +30,17 @@ __global__ __launch_bounds__(256) void k_segment_hist(const int32_t* __restrict_
     for (int l = threadIdx.x; l < L; l += 256) seg_hist[(int64_t)blockIdx.x * L + l] = hist[l];
 }
 
-// Column-wise exclusive running sum over segments.  A workgroup takes 64 lists; its 16 wavefronts
-// each take a sixteenth of the segments, so the two passes over a column run 16-wide.
+// Column-wise exclusive running sum over segments.  A workgroup takes 16 lists; its 1024 threads split the
+// segments into 64 parts (a sixteen-lane group per part), so each of the two passes over a column is 64 wide
+// and a launch has L/16 workgroups.
 __global__ __launch_bounds__(1024) void k_segment_scan(uint32_t* __restrict__ seg_hist, int nseg, int L,
                                                        uint32_t* __restrict__ batch_count) {
-    __shared__ uint32_t part_sum[16][64];
-    const int li = threadIdx.x & 63, part = threadIdx.x >> 6;
-    const int l = blockIdx.x * 64 + li;
-    const int chunk = (nseg + 15) / 16;
-    const int s0 = part * chunk, s1 = (s0 + chunk < nseg) ? s0 + chunk : nseg;
+    __shared__ uint32_t part_sum[64][16];
+    const int li = threadIdx.x & 15, part = threadIdx.x >> 4;
+    const int l = blockIdx.x * 16 + li;
+    const int chunk = (nseg + 63) / 64;
+    const int s0 = part * chunk < nseg ? part * chunk : nseg;
+    const int s1 = (s0 + chunk < nseg) ? s0 + chunk : nseg;
     uint32_t sum = 0;
     if (l < L)
         for (int s = s0; s < s1; ++s) sum += seg_hist[(int64_t)s * L + l];
@@ -52,7 +54,7 @@ __global__ __launch_bounds__(1024) void k_segment_scan(uint32_t* __restrict__ se
             seg_hist[(int64_t)s * L + l] = run;
             run += t;
         }
-        if (part == 15) batch_count[l] = run;
+        if (part == 63) batch_count[l] = run;
     }
 }
 
@@ -300,7 +302,7 @@ hipError_t launch_segment_hist(const int32_t* assign, int64_t n, int64_t seg_len
 }
 
 hipError_t launch_segment_scan(uint32_t* seg_hist, int nseg, int L, uint32_t* batch_count, hipStream_t st) {
-    hipLaunchKernelGGL(k_segment_scan, dim3((L + 63) / 64), dim3(1024), 0, st, seg_hist, nseg, L, batch_count);
+    hipLaunchKernelGGL(k_segment_scan, dim3((L + 15) / 16), dim3(1024), 0, st, seg_hist, nseg, L, batch_count);
     return hipGetLastError();
 }
 
