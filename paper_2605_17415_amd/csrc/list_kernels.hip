@@ -72,18 +72,22 @@ __global__ __launch_bounds__(64) void k_stable_rank(const int32_t* __restrict__ 
     __syncthreads();
     const int64_t begin = (int64_t)blockIdx.x * seg_len;
     const int64_t end = begin + seg_len < n ? begin + seg_len : n;
+    const int nbits = 32 - __builtin_clz((unsigned)L);                      // bits of the numbers 0 .. L
     for (int64_t g = begin; g < end; g += 64) {
         const int64_t i = g + lane;
         int key = (i < end) ? assign[i] : -1;
         if (key >= L) key = -1;
-        int lower = 0;
-        bool later = false;
-        for (int t = 0; t < 64; ++t) {
-            const int kt = __shfl(key, t);
-            const bool same = (kt == key);
-            lower += (same && t < lane) ? 1 : 0;
-            later = later || (same && t > lane);
+        // lanes holding the same cell number: one ballot per bit of the number narrows the set (rows without a
+        // cell carry the number L, which no other row has)
+        const uint32_t kbits = (uint32_t)(key >= 0 ? key : L);
+        uint64_t same = ~0ull;
+        for (int bit = 0; bit < nbits; ++bit) {
+            const bool set = (kbits >> bit) & 1u;
+            const uint64_t bal = __ballot(set);
+            same &= set ? bal : ~bal;
         }
+        const int lower = __popcll(same & ((1ull << lane) - 1ull));        // earlier rows of this group in the same cell
+        const bool later = (same >> lane) > 1ull;                          // a later row of the group is in it too
         uint32_t base = 0;
         if (key >= 0) {
             base = cnt[key];
