@@ -1,0 +1,98 @@
+"""Parity at the 10M x 96 configuration (nlist 4096, b=4, 10,000 queries, nprobe 32, k 10), in the launch
+configuration `bench.py --workload 10m_d96` times, on outputs the oracle computes one by one: the cell of
+200,000 sampled rows (with the first rows and the last partial tile), the stored codes and norms of whole
+lists, and every returned (label, score) of sampled queries."""
+import numpy as np
+import pytest
+
+import parity
+from oracle import ivftq_oracle as orc
+from workloads import synth
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+NPROBE, K = 32, 10
+
+
+@pytest.fixture(scope="module")
+def full():
+    import paper_2605_17415_amd as pkg
+    w = synth.config_10m_d96(4)
+    print("[fullsize 10M] generating 10M x 96", flush=True)
+    X, Q = synth.database(w), synth.queries(w)
+    rows = synth.train_sample_indices(w)[:100_000]
+    print("[fullsize 10M] oracle k-means (1 iteration on 100k sampled rows, 4096 cells)", flush=True)
+    cent, _ = orc.train_coarse(X[rows], w.nlist, 1, synth.kmeans_init_indices(w.seed, len(rows), w.nlist))
+    cent = cent.astype(np.float32)
+    Pi = orc.haar_rotation_from_gaussian(synth.gaussian_matrix(w.seed, w.d)).astype(np.float32)
+    c, tau = orc.codebook_fp32(w.b, w.d)
+    ix = pkg.Index(w.d, w.b, w.nlist)
+    ix.set_coarse(cent)
+    ix.set_rotation(Pi)
+    dev = torch.device("cuda:0")
+    xd = torch.from_numpy(X).to(dev)
+    print("[fullsize 10M] GPU encode_add of 10M rows and search of 10k queries", flush=True)
+    ix.encode_add(xd)
+    scores, ids = ix.search(torch.from_numpy(Q).to(dev), NPROBE, K)
+    g_assign, _, _ = ix.encode_only(xd, want_codes=False)
+    torch.cuda.synchronize()
+    del xd
+    yield dict(w=w, X=X, Q=Q, cent=cent, Pi=Pi, c=c, tau=tau, ix=ix, g_assign=g_assign.cpu().numpy(),
+               scores=scores.cpu().numpy(), ids=ids.cpu().numpy())
+    ix.close()
+
+
+def test_fullsize_10m_cells_and_stored_lists(full):
+    w, ix, g_assign = full["w"], full["ix"], full["g_assign"]
+    rng = np.random.default_rng(11)
+    sample = np.unique(np.concatenate([rng.choice(w.n, 200_000, replace=False), np.arange(w.n - 300, w.n), np.arange(300)]))
+    C64 = full["cent"].astype(np.float64)
+    near = bad = 0
+    for s in range(0, len(sample), 1 << 15):
+        part = sample[s:s + (1 << 15)]
+        sc = orc.normalize_rows(full["X"][part]) @ C64.T
+        a = np.argmax(sc, axis=1)
+        diff = np.flatnonzero(a != g_assign[part])
+        if len(diff):
+            top2 = np.partition(sc[diff], -2, axis=1)[:, -2:]
+            gap = top2[:, 1] - top2[:, 0]
+            near += int(np.sum(gap < parity.BOUNDARY_TOL))
+            bad += int(np.sum(gap >= parity.BOUNDARY_TOL))
+    print(f"cells of {len(sample)} sampled rows: {near} near-tie differences, {bad} others", flush=True)
+    assert bad == 0, "a sampled row went to another cell away from a near-tie"
+    # the stored lists hold exactly the rows given to them, in arrival order
+    sizes = np.array([ix.list_size(l) for l in range(w.nlist)])
+    np.testing.assert_array_equal(sizes, np.bincount(g_assign, minlength=w.nlist))
+    assert sizes.sum() == w.n
+    for l in (0, 1234, int(np.argmax(sizes)), w.nlist - 1):
+        ids_l, codes_l, gam_l = ix.export_list(l)
+        members = np.flatnonzero(g_assign == l)
+        np.testing.assert_array_equal(ids_l, members)
+        if len(members) == 0:
+            continue
+        # the oracle's encode of these rows: same cell (except at a near-tie), same codes and norms
+        enc = orc.encode(full["X"][members], full["cent"], full["Pi"], full["tau"])
+        rep = parity.compare_encode(enc, np.full(len(members), l, np.int32), codes_l, gam_l)
+        print(f"list {l} ({len(members)} rows):", rep, flush=True)
+
+
+def test_fullsize_10m_returned_scores_one_by_one(full):
+    rng = np.random.default_rng(12)
+    checked = near = 0
+    C = full["c"].astype(np.float64)
+    for q_row in rng.choice(full["w"].nq, 40, replace=False):
+        assert np.all(np.diff(full["scores"][q_row]) <= 0)
+        assert len(set(full["ids"][q_row].tolist())) == K
+        qn = orc.normalize_rows(full["Q"][q_row:q_row + 1])[0]
+        z = full["Pi"].astype(np.float64) @ qn
+        for lab, sc in zip(full["ids"][q_row], full["scores"][q_row]):
+            enc = orc.encode(full["X"][lab:lab + 1], full["cent"], full["Pi"], full["tau"])
+            if enc["bdist"].min() < parity.BOUNDARY_TOL or enc["gap"][0] < parity.BOUNDARY_TOL:
+                near += 1          # a code or the cell of this vector sits on a decision boundary
+                continue
+            ref = float(qn @ full["cent"][enc["assign"][0]].astype(np.float64)) + float(enc["gamma16"][0]) * float(np.sum(z * C[enc["codes"][0]]))
+            assert abs(sc - ref) <= parity.SCORE_RTOL * abs(ref) + parity.SCORE_ATOL, (q_row, lab, sc, ref)
+            checked += 1
+    print(f"returned scores checked one by one: {checked}, skipped near a boundary: {near}", flush=True)
+    assert checked > 300
