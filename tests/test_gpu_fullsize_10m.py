@@ -1,7 +1,8 @@
-"""Parity at the 10M x 96 configuration (nlist 4096, b=4, 10,000 queries, nprobe 32, k 10), in the launch
-configuration `bench.py --workload 10m_d96` times, on outputs the oracle computes one by one: the cell of
-200,000 sampled rows (with the first rows and the last partial tile), the stored codes and norms of whole
-lists, and every returned (label, score) of sampled queries."""
+"""Parity at the two 10M-row configurations (10M x 96: nprobe 32, k 10; 10M x 200 with shifted queries:
+nprobe 64, k 100; both nlist 4096, b=4, 10,000 queries), in the launch configurations `bench.py --workload
+10m_d96` and `10m_d200` time, on outputs the oracle computes one by one: the cell of 200,000 sampled rows
+(with the first rows and the last partial tile), the stored codes and norms of whole lists, and every
+returned (label, score) of sampled queries."""
 import numpy as np
 import pytest
 
@@ -12,14 +13,15 @@ from workloads import synth
 torch = pytest.importorskip("torch")
 pytestmark = pytest.mark.gpu
 
-NPROBE, K = 32, 10
+CONFIGS = {"10m_d96": (lambda: synth.config_10m_d96(4), 32, 10, 40), "10m_d200": (synth.config_10m_d200, 64, 100, 8)}
 
 
-@pytest.fixture(scope="module")
-def full():
+@pytest.fixture(scope="module", params=list(CONFIGS))
+def full(request):
     import paper_2605_17415_amd as pkg
-    w = synth.config_10m_d96(4)
-    print("[fullsize 10M] generating 10M x 96", flush=True)
+    make, NPROBE, K, n_queries = CONFIGS[request.param]
+    w = make()
+    print(f"[fullsize 10M] generating 10M x {w.d}", flush=True)
     X, Q = synth.database(w), synth.queries(w)
     rows = synth.train_sample_indices(w)[:100_000]
     print("[fullsize 10M] oracle k-means (1 iteration on 100k sampled rows, 4096 cells)", flush=True)
@@ -38,7 +40,7 @@ def full():
     g_assign, _, _ = ix.encode_only(xd, want_codes=False)
     torch.cuda.synchronize()
     del xd
-    yield dict(w=w, X=X, Q=Q, cent=cent, Pi=Pi, c=c, tau=tau, ix=ix, g_assign=g_assign.cpu().numpy(),
+    yield dict(k=K, n_queries=n_queries, w=w, X=X, Q=Q, cent=cent, Pi=Pi, c=c, tau=tau, ix=ix, g_assign=g_assign.cpu().numpy(),
                scores=scores.cpu().numpy(), ids=ids.cpu().numpy())
     ix.close()
 
@@ -81,9 +83,9 @@ def test_fullsize_10m_returned_scores_one_by_one(full):
     rng = np.random.default_rng(12)
     checked = near = 0
     C = full["c"].astype(np.float64)
-    for q_row in rng.choice(full["w"].nq, 40, replace=False):
+    for q_row in rng.choice(full["w"].nq, full["n_queries"], replace=False):
         assert np.all(np.diff(full["scores"][q_row]) <= 0)
-        assert len(set(full["ids"][q_row].tolist())) == K
+        assert len(set(full["ids"][q_row].tolist())) == full["k"]
         qn = orc.normalize_rows(full["Q"][q_row:q_row + 1])[0]
         z = full["Pi"].astype(np.float64) @ qn
         for lab, sc in zip(full["ids"][q_row], full["scores"][q_row]):
