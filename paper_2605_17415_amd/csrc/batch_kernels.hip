@@ -343,6 +343,9 @@ void k_batch_scan(BatchScanArgs a) {
                 const int v = slab * 32 + jl;
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
+                    // rows 4g .. 4g+3 belong to the queries 8g .. 8g+7 of this tile: a sparse tile (a list that
+                    // is among the nearest of few queries) skips the groups it has no query for
+                    if (qt * 32 + 8 * (r / 4) >= nq_tile) break;
                     const int e = qt * 32 + 8 * (r / 4) + 4 * half + (r % 4);
                     const int32_t q = s_q[e];
                     if (q >= 0 && v < n_l)
