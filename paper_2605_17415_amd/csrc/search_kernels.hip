@@ -162,13 +162,18 @@ __device__ __forceinline__ uint32_t order_key(float f) {
 constexpr int kSelU = 8;        // groups of 64 columns loaded together by k_select
 constexpr int kSelSmallU = 4;   // and by k_select_small beyond its registers
 
-template <int MODE>
+// COPIES: counters per digit in the histogram (a power of two; 8 pays for long rows, 1 for short ones, where
+// clearing and summing the copies costs more than the collisions they avoid).
+template <int MODE, int COPIES>
 __global__ __launch_bounds__(256) void k_select(SelectArgs a) {
+    constexpr int kHistCopies = COPIES;
     extern __shared__ unsigned char smem[];
     int kpad = 1;
     while (kpad < a.k) kpad <<= 1;
-    uint32_t* hist = reinterpret_cast<uint32_t*>(smem);               // [256]
-    uint32_t* ctrl = hist + 256;                                      // [8]
+    // kHistCopies counters per digit, chosen by lane: keys of one row often share their leading byte, and
+    // 64 lanes adding to one LDS word are served one after the other
+    uint32_t* hist = reinterpret_cast<uint32_t*>(smem);               // [256][kHistCopies]
+    uint32_t* ctrl = hist + 256 * kHistCopies;                        // [8]
     uint32_t* wave_cnt = ctrl + 8;                                    // [4]
     uint32_t* s_key = wave_cnt + 4;                                   // [kpad]
     uint32_t* s_col = s_key + kpad;                                   // [kpad]
@@ -199,7 +204,8 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a) {
     if (take > 0 && m > k) {
         for (int pass = 0; pass < 4; ++pass) {
             const int shift = 24 - 8 * pass;
-            hist[tid] = 0;
+#pragma unroll
+            for (int e = 0; e < kHistCopies; ++e) hist[tid + 256 * e] = 0;
             __syncthreads();
             // kSelU groups of 64 columns per step, their loads in flight together (the pass is bound by the
             // latency of reading the row, not by its arithmetic)
@@ -213,7 +219,8 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a) {
 #pragma unroll
                 for (int u = 0; u < kSelU; ++u) {
                     const uint32_t key = order_key(v[u]);
-                    if (i0 + 64 * u + lane < w_end && (key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+                    if (i0 + 64 * u + lane < w_end && (key & mask) == prefix)
+                        atomicAdd(&hist[((key >> shift) & 255u) * kHistCopies + (lane & (kHistCopies - 1))], 1u);
                 }
             }
             __syncthreads();
@@ -222,7 +229,11 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a) {
                 // digits 4l .. 4l+3, a suffix sum over the lanes gives what lies above each lane
                 uint32_t h[4];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) h[e] = hist[lane * 4 + e];
+                for (int e = 0; e < 4; ++e) {
+                    h[e] = 0;
+#pragma unroll
+                    for (int c = 0; c < kHistCopies; ++c) h[e] += hist[(lane * 4 + e) * kHistCopies + c];
+                }
                 const uint32_t own = h[0] + h[1] + h[2] + h[3];
                 uint32_t incl = own;
 #pragma unroll
@@ -814,12 +825,16 @@ hipError_t launch_select(int mode, const SelectArgs& a_in, hipStream_t st) {
     }
     int kpad = 1;
     while (kpad < a.k) kpad <<= 1;
-    const size_t lds = (256 + 8 + 4) * 4 + (size_t)kpad * 8 + 8 + (size_t)kpad * 8;
+    const int copies = (m_bound == 0 || m_bound > 8192) ? 8 : 1;
+    const size_t lds = (256 * copies + 8 + 4) * 4 + (size_t)kpad * 8 + 8 + (size_t)kpad * 8;
     const unsigned wgs = (unsigned)(a.gate ? std::min<int64_t>(std::min<int64_t>(a.rows, a.gate_rows), 256) : a.rows);
-    if (mode == 0)
-        hipLaunchKernelGGL(k_select<0>, dim3(wgs), dim3(256), lds, st, a);
-    else
-        hipLaunchKernelGGL(k_select<1>, dim3(wgs), dim3(256), lds, st, a);
+    if (copies == 8) {
+        if (mode == 0) hipLaunchKernelGGL((k_select<0, 8>), dim3(wgs), dim3(256), lds, st, a);
+        else hipLaunchKernelGGL((k_select<1, 8>), dim3(wgs), dim3(256), lds, st, a);
+    } else {
+        if (mode == 0) hipLaunchKernelGGL((k_select<0, 1>), dim3(wgs), dim3(256), lds, st, a);
+        else hipLaunchKernelGGL((k_select<1, 1>), dim3(wgs), dim3(256), lds, st, a);
+    }
     return hipGetLastError();
 }
 
