@@ -90,7 +90,10 @@ __global__ void k_pair_scatter(const int32_t* __restrict__ probe, const int32_t*
 // pairs, counts them per bucket in LDS, and touches each global counter once per bucket it met
 // (thousands of pairs hit the same few thousand counters, so per-pair global atomics serialise).
 // In the scatter step that one global atomic reserves the workgroup's range inside the bucket.
-constexpr int kPairChunk = 16384;
+#ifndef IVFTQ_PAIR_CHUNK
+#define IVFTQ_PAIR_CHUNK 4096
+#endif
+constexpr int kPairChunk = IVFTQ_PAIR_CHUNK;
 constexpr int kPairLdsBuckets = 16384;      // 2L must not exceed this (64 KB of LDS)
 
 __global__ __launch_bounds__(1024) void k_pair_count_lds(const int32_t* __restrict__ probe,
