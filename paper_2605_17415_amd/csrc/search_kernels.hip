@@ -15,27 +15,50 @@ namespace {
 
 // Also, when asked: first[q] = the number of leading probes whose lists are scored densely to find
 // the query's threshold (see the kernel), or np when all probed cells together hold too few vectors.
-__global__ void k_cand_offsets(const int32_t* __restrict__ probe, int64_t nq, int np,
-                               const int32_t* __restrict__ list_size, int32_t* __restrict__ cand_off,
-                               int k, int cap, int32_t* __restrict__ first) {
-    const int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+__global__ __launch_bounds__(256) void k_cand_offsets(const int32_t* __restrict__ probe, int64_t nq, int np,
+                                                      const int32_t* __restrict__ list_size, int32_t* __restrict__ cand_off,
+                                                      int k, int cap, int32_t* __restrict__ first) {
+    // one wavefront per query: 64 probes at a time, running sum over the lanes
+    const int lane = threadIdx.x & 63;
+    const int64_t q = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (q >= nq) return;
     int32_t run = 0;
-    for (int p = 0; p < np; ++p) {
-        cand_off[q * (np + 1) + p] = run;
-        run += list_size[probe[q * np + p]];
+    for (int p0 = 0; p0 < np; p0 += 64) {
+        const int p = p0 + lane;
+        const int32_t size = p < np ? list_size[probe[q * np + p]] : 0;
+        int32_t incl = size;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int32_t t = __shfl_up(incl, o);
+            if (lane >= o) incl += t;
+        }
+        if (p < np) cand_off[q * (np + 1) + p] = run + incl - size;
+        run += __shfl(incl, 63);
     }
-    cand_off[q * (np + 1) + np] = run;
+    if (lane == 0) cand_off[q * (np + 1) + np] = run;
     if (!first) return;
     // The k-th score of a prefix holding P of the query's T candidates is beaten by about
     // k*(T-P)/P of the others; the prefix is made long enough for that to be half the candidate
     // list's capacity (and at least k vectors, so that a threshold exists).
     int64_t need = (kPrefixFactorX2 * (int64_t)k * run + 2 * cap - 1) / (2 * cap);
     if (need < k) need = k;
+    // the first p >= 1 whose lists 0 .. p-1 together reach `need` (np when none does)
     int p1 = np;
-    for (int p = 1; p <= np; ++p)
-        if (cand_off[q * (np + 1) + p] >= need) { p1 = p; break; }
-    first[q] = p1;
+    int32_t run2 = 0;
+    for (int p0 = 0; p0 < np && p1 == np; p0 += 64) {
+        const int p = p0 + lane;
+        const int32_t size = p < np ? list_size[probe[q * np + p]] : 0;
+        int32_t incl = size;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int32_t t = __shfl_up(incl, o);
+            if (lane >= o) incl += t;
+        }
+        const uint64_t reached = __ballot(p < np && (int64_t)(run2 + incl) >= need);
+        if (reached) p1 = p0 + (int)__builtin_ctzll(reached) + 1;
+        run2 += __shfl(incl, 63);
+    }
+    if (lane == 0) first[q] = p1;
 }
 
 // ---- list scan: one workgroup per (query, probed list) ---------------------------------------
@@ -770,7 +793,7 @@ hipError_t launch_rerank(const RerankArgs& a, int64_t nq, hipStream_t st) {
 hipError_t launch_cand_offsets(const int32_t* probe, int64_t nq, int np, const int32_t* list_size,
                                int32_t* cand_off, int k, int cap, int32_t* first, hipStream_t st) {
     if (nq <= 0) return hipSuccess;
-    hipLaunchKernelGGL(k_cand_offsets, dim3((unsigned)((nq + 127) / 128)), dim3(128), 0, st, probe, nq, np,
+    hipLaunchKernelGGL(k_cand_offsets, dim3((unsigned)((nq + 3) / 4)), dim3(256), 0, st, probe, nq, np,
                        list_size, cand_off, k, cap, first);
     return hipGetLastError();
 }
