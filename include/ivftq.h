@@ -219,8 +219,9 @@ int64_t ivftq_index_bytes(const ivftq_index* index);
  * (one workgroup per query and probed list), 2 = same as 0 (kept for callers that set it).  Results
  * obey the same contract in every mode. */
 ivftq_status ivftq_set_search_mode(ivftq_index* index, int mode);
-/* Upper limit, in bytes, of the per-search score workspace (default 4 GiB); queries are processed
- * in as many passes as that allows. */
+/* Upper limit, in bytes, of the per-search score workspace (default 4 GiB, at least 1 MiB or
+ * IVFTQ_INVALID_ARG); queries are processed in as many passes as that allows.  A pass walks every
+ * probed list again, so fewer passes are faster; the results do not depend on the limit. */
 ivftq_status ivftq_set_workspace_limit(ivftq_index* index, int64_t bytes);
 
 /* ---- per-kernel timing (measurement aid) ------------------------------------------------ */
