@@ -37,9 +37,10 @@ __global__ __launch_bounds__(256) void k_cand_offsets(const int32_t* __restrict_
     }
     if (lane == 0) cand_off[q * (np + 1) + np] = run;
     if (!first) return;
-    // The k-th score of a prefix holding P of the query's T candidates is beaten by about
-    // k*(T-P)/P of the others; the prefix is made long enough for that to be half the candidate
-    // list's capacity (and at least k vectors, so that a threshold exists).
+    // Were the prefix a random sample of P of the query's T candidates, its k-th score would be beaten by
+    // about k*(T-P)/P of the others; P = f*k*T/cap (f = kPrefixFactorX2/2) keeps that near cap/f even then.
+    // The nearest lists hold the best candidates, so in practice far fewer pass (and a list that does
+    // overflow sends its query to the exact pass).  At least k vectors, so that a threshold exists.
     int64_t need = (kPrefixFactorX2 * (int64_t)k * run + 2 * cap - 1) / (2 * cap);
     if (need < k) need = k;
     // the first p >= 1 whose lists 0 .. p-1 together reach `need` (np when none does)
