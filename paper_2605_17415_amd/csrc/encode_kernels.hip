@@ -53,9 +53,12 @@ size_t encode_lds_bytes(int mode, int cells, int words) {
     return bytes;
 }
 
-template <int DP>
+// MODE 0: encode and store into the lists; 1: encode into flat arrays; 2: rotate queries only.  A template
+// parameter, so that each instantiation carries its own path only.
+template <int DP, int MODE>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2)))
-void k_encode(int mode, EncodeArgs a, int flags) {
+void k_encode(EncodeArgs a, int flags) {
+    constexpr int mode = MODE;
     using Cfg = EncCfg<DP>;
     constexpr int KB = Cfg::KB, NT = Cfg::NT, R = Cfg::R, LDH = Cfg::LDH, PF = Cfg::PF;
     extern __shared__ unsigned char lds_raw[];
@@ -285,13 +288,13 @@ void k_encode(int mode, EncodeArgs a, int flags) {
 #undef IVFTQ_FETCH_TILE
 #undef IVFTQ_STORE_TILE
 
-template <int DP>
-hipError_t run(int mode, const EncodeArgs& a, hipStream_t st) {
+template <int DP, int MODE>
+hipError_t run_mode(const EncodeArgs& a, hipStream_t st) {
     static size_t attr_lds = 0;
-    const size_t lds = encode_lds_bytes<DP>(mode, a.q_cells, a.store.words);
+    const size_t lds = encode_lds_bytes<DP>(MODE, a.q_cells, a.store.words);
     if (lds > 160 * 1024) return hipErrorInvalidValue;
     if (lds > attr_lds) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_encode<DP>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_encode<DP, MODE>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         attr_lds = lds;
@@ -301,8 +304,16 @@ hipError_t run(int mode, const EncodeArgs& a, hipStream_t st) {
     int flags = 0;
     if (a.d % 4 == 0 && reinterpret_cast<uintptr_t>(a.x) % 16 == 0) flags |= 1;
     if (a.d % 4 == 0 && reinterpret_cast<uintptr_t>(a.codes_flat) % 4 == 0) flags |= 2;
-    hipLaunchKernelGGL(k_encode<DP>, dim3((unsigned)blocks), dim3(256), lds, st, mode, a, flags);
+    hipLaunchKernelGGL((k_encode<DP, MODE>), dim3((unsigned)blocks), dim3(256), lds, st, a, flags);
     return hipGetLastError();
+}
+
+template <int DP>
+hipError_t run(int mode, const EncodeArgs& a, hipStream_t st) {
+    if (mode == 0) return run_mode<DP, 0>(a, st);
+    if (mode == 1) return run_mode<DP, 1>(a, st);
+    if (mode == 2) return run_mode<DP, 2>(a, st);
+    return hipErrorInvalidValue;
 }
 
 }  // namespace
