@@ -35,7 +35,7 @@ struct EncCfg {
     static constexpr int NT = DP / 32;
     static constexpr int LDH = DP + 8;                     // halves per LDS row of the Pi tile
 #ifndef IVFTQ_ENC_R2_MAX_DP
-#define IVFTQ_ENC_R2_MAX_DP 96
+#define IVFTQ_ENC_R2_MAX_DP 64
 #endif
     static constexpr int R = DP <= IVFTQ_ENC_R2_MAX_DP ? 2 : 1;   // 32-row tiles per wavefront (register budget)
     static constexpr int stage_halves = 2 * 32 * LDH;      // hi and lo parts of one 32-row tile of Pi
