@@ -19,6 +19,9 @@
  *     queued on it.  Calls that hand data back to the host, and ivftq_encode_add /
  *     ivftq_train_coarse (which size storage from device results), synchronise that stream
  *     before returning; ivftq_search and ivftq_encode_only return with work still queued.
+ *     Calls without a stream argument (ivftq_reset, ivftq_set_coarse, ivftq_set_rotation,
+ *     ivftq_export_list) first wait for the stream of the most recent call on the index that
+ *     took one; a caller who spreads one index over several streams orders them itself.
  *   - Every call returns an ivftq_status; nothing throws or aborts across this boundary.
  *     Arguments are validated before any kernel is launched.  ivftq_last_error() gives a
  *     thread-local message for the most recent failure.
@@ -37,6 +40,15 @@ extern "C" {
 #endif
 
 typedef struct ivftq_index ivftq_index; /* opaque, library-owned */
+
+/* Where an index gets its device memory (spec boundary: the caller's framework, e.g. PyTorch's
+ * caching allocator, provides device memory; the library provides the kernels).  alloc returns `bytes`
+ * bytes of device memory on the current device, aligned to at least 256 bytes, or NULL when it has
+ * none; release takes back a pointer that alloc returned.  Both get the ctx pointer given at creation.
+ * They are called from the thread that makes the library call, never from a kernel or another thread,
+ * and a NULL from alloc makes that call return IVFTQ_OOM with the stored vectors unchanged. */
+typedef void* (*ivftq_alloc_fn)(size_t bytes, void* ctx);
+typedef void (*ivftq_free_fn)(void* ptr, void* ctx);
 
 typedef int ivftq_status;
 enum {
@@ -89,17 +101,27 @@ ivftq_status ivftq_haar_from_gaussian(int d, const double* g, float* pi_out);
 /* ---- index life cycle ------------------------------------------------------------------ */
 
 /* New empty index on the current HIP device: builds the (b, d) codebook and a Haar rotation from
- * rotation_seed.  Coarse centroids must be trained or set before encoding or searching. */
-ivftq_status ivftq_create(int d, int b, int nlist, uint64_t rotation_seed, ivftq_index** out);
+ * rotation_seed.  Coarse centroids must be trained or set before encoding or searching.
+ * alloc_fn / free_fn / alloc_ctx: all device memory of the index (constants, inverted lists, work
+ * space) is obtained and returned through them; both NULL = hipMalloc / hipFree.  List storage
+ * grows by allocating the larger pool before the old one is released, work buffers by releasing
+ * first; everything is released by ivftq_destroy.  If alloc_fn returns NULL here the result is
+ * IVFTQ_OOM and *out stays NULL. */
+ivftq_status ivftq_create(int d, int b, int nlist, uint64_t rotation_seed, ivftq_alloc_fn alloc_fn,
+                          ivftq_free_fn free_fn, void* alloc_ctx, ivftq_index** out);
 /* The same with the sign-bit refinement switched on (sign_bit = 1): b Stage-1 bits + 1 refinement
  * bit are stored per coordinate, b + 1 <= 8.  Codes reported and accepted by the other calls are
  * then the merged ones, 2*code + s in [0, 2^(b+1)), and ivftq_get_codebook returns the tables of
  * ivftq_build_refined_codebook.  sign_bit = 0 is ivftq_create. */
 ivftq_status ivftq_create_refined(int d, int b, int sign_bit, int nlist, uint64_t rotation_seed,
+                                  ivftq_alloc_fn alloc_fn, ivftq_free_fn free_fn, void* alloc_ctx,
                                   ivftq_index** out);
+/* Waits for the whole device (work of any stream may still use the index's memory), then returns
+ * every buffer through free_fn. */
 ivftq_status ivftq_destroy(ivftq_index* index);
 /* Remove every stored vector.  Constants, the capacity already reserved for the lists and the
- * search workspace are kept, so the index can be filled again without allocating.  Synchronises. */
+ * search workspace are kept, so the index can be filled again without allocating.  Waits for the
+ * stream of the most recent call. */
 ivftq_status ivftq_reset(ivftq_index* index);
 
 /* Coarse partition (Section "Architecture", Indexing): Lloyd k-means on the L2-normalised rows of
@@ -107,7 +129,9 @@ ivftq_status ivftq_reset(ivftq_index* index);
  * centroids are L2-normalised.  init_rows_host: host, nlist distinct row numbers used as initial
  * centres, or NULL to draw them from `seed`.  An empty cell is re-seeded from a member of the
  * largest cell.  Needs n >= nlist.  inertia_out (host, may be NULL) receives the k-means
- * objective of the last assignment step.  Synchronises. */
+ * objective of the last assignment step.  The sums of an iteration are taken in a fixed order, so the
+ * same rows, initial rows and seed give the same centroids bit for bit on every run.  The index's
+ * centroids change only when the call succeeds.  Synchronises. */
 ivftq_status ivftq_train_coarse(ivftq_index* index, const float* x_dev, int64_t n, int niter,
                                 const int64_t* init_rows_host, uint64_t seed, double* inertia_out,
                                 void* stream);
@@ -210,8 +234,8 @@ ivftq_status ivftq_coarse_probe(ivftq_index* index, const float* q_dev, int64_t 
 int64_t ivftq_ntotal(const ivftq_index* index);
 ivftq_status ivftq_list_size(const ivftq_index* index, int list, int64_t* n_out);
 /* Copy one inverted list to the host in stored order.  ids_host: n int64; codes_host: n x d uint8
- * (unpacked bin numbers); gamma_host: n float16 bit patterns.  Any may be NULL.  Synchronises the
- * device. */
+ * (unpacked bin numbers); gamma_host: n float16 bit patterns.  Any may be NULL.  Waits for the
+ * stream of the most recent call. */
 ivftq_status ivftq_export_list(const ivftq_index* index, int list, int64_t* ids_host,
                                uint8_t* codes_host, uint16_t* gamma_host);
 /* Bytes of device memory the stored vectors occupy (codes + norms + labels, without slack). */
@@ -229,7 +253,7 @@ ivftq_status ivftq_set_workspace_limit(ivftq_index* index, int64_t bytes);
 /* ---- per-kernel timing (measurement aid) ------------------------------------------------ */
 
 /* While enabled, every kernel launch made for this index is bracketed by two HIP events recorded
- * on the launch stream.  ivftq_profile_read synchronises the device, adds up the elapsed time and
+ * on the launch stream.  ivftq_profile_read waits for the recorded events, adds up the elapsed time and
  * the number of launches per kernel class since the last read (ms_out, launches_out: host arrays
  * of ivftq_profile_kernel_count() entries) and clears the records.  Enabling or disabling clears
  * them too.  Kernel classes are named by ivftq_profile_kernel_name(id). */

@@ -24,8 +24,10 @@ _SIGNATURES = {
                                        C.POINTER(C.c_float), C.c_void_p, C.c_void_p]),
     "ivftq_haar_rotation": (C.c_int, [C.c_int, C.c_uint64, C.c_void_p]),
     "ivftq_haar_from_gaussian": (C.c_int, [C.c_int, C.c_void_p, C.c_void_p]),
-    "ivftq_create": (C.c_int, [C.c_int, C.c_int, C.c_int, C.c_uint64, C.POINTER(C.c_void_p)]),
-    "ivftq_create_refined": (C.c_int, [C.c_int, C.c_int, C.c_int, C.c_int, C.c_uint64, C.POINTER(C.c_void_p)]),
+    "ivftq_create": (C.c_int, [C.c_int, C.c_int, C.c_int, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p,
+                               C.POINTER(C.c_void_p)]),
+    "ivftq_create_refined": (C.c_int, [C.c_int, C.c_int, C.c_int, C.c_int, C.c_uint64, C.c_void_p, C.c_void_p,
+                                       C.c_void_p, C.POINTER(C.c_void_p)]),
     "ivftq_build_refined_codebook": (C.c_int, [C.c_int, C.c_int, C.c_void_p, C.c_void_p]),
     "ivftq_destroy": (C.c_int, [C.c_void_p]),
     "ivftq_reset": (C.c_int, [C.c_void_p]),
@@ -71,6 +73,10 @@ _SIGNATURES = {
 }
 
 _lib = None
+
+# ivftq_alloc_fn / ivftq_free_fn
+ALLOC_FN = C.CFUNCTYPE(C.c_void_p, C.c_size_t, C.c_void_p)
+FREE_FN = C.CFUNCTYPE(None, C.c_void_p, C.c_void_p)
 
 
 class IvftqError(RuntimeError):
@@ -216,16 +222,48 @@ def ivftq_version() -> str:
 # ---- index ---------------------------------------------------------------------------------------
 
 
-class Index:
-    """Owner of one ivftq_index handle.  Methods carry the C names minus the prefix."""
+def _torch_alloc(nbytes, ctx):
+    """ivftq_alloc_fn on PyTorch's caching allocator (current device, current stream); NULL when it is out of memory."""
+    try:
+        import torch
+        return torch.cuda.caching_allocator_alloc(int(nbytes))
+    except Exception:
+        return None
 
-    def __init__(self, d: int, b: int, nlist: int, rotation_seed: int = 0, sign_bit: bool = False):
+
+def _torch_free(ptr, ctx):
+    try:
+        import torch
+        torch.cuda.caching_allocator_delete(ptr)
+    except Exception:            # interpreter shutting down: the process is about to return the memory anyway
+        pass
+
+
+# the callback objects must outlive every index that holds their addresses
+TORCH_ALLOC = ALLOC_FN(_torch_alloc)
+TORCH_FREE = FREE_FN(_torch_free)
+
+
+class Index:
+    """Owner of one ivftq_index handle.  Methods carry the C names minus the prefix.
+
+    allocator: "torch" (default) = the index takes all its device memory from PyTorch's caching allocator;
+    "hip" = hipMalloc / hipFree inside the library; or a pair (ALLOC_FN, FREE_FN) of ctypes callbacks."""
+
+    def __init__(self, d: int, b: int, nlist: int, rotation_seed: int = 0, sign_bit: bool = False, allocator="torch"):
         self._lib = load_library()
         self._h = C.c_void_p()
-        if sign_bit:
-            _check(self._lib.ivftq_create_refined(d, b, 1, nlist, rotation_seed, C.byref(self._h)))
+        if allocator == "torch":
+            self._alloc = (TORCH_ALLOC, TORCH_FREE)
+        elif allocator == "hip":
+            self._alloc = (None, None)
         else:
-            _check(self._lib.ivftq_create(d, b, nlist, rotation_seed, C.byref(self._h)))
+            self._alloc = tuple(allocator)           # kept alive as long as the index
+        af, ff = (C.cast(f, C.c_void_p) if f is not None else None for f in self._alloc)
+        if sign_bit:
+            _check(self._lib.ivftq_create_refined(d, b, 1, nlist, rotation_seed, af, ff, None, C.byref(self._h)))
+        else:
+            _check(self._lib.ivftq_create(d, b, nlist, rotation_seed, af, ff, None, C.byref(self._h)))
         self.d, self.nlist = d, nlist
         self.b = b + (1 if sign_bit else 0)      # bits stored per coordinate
 

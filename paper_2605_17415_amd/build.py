@@ -29,7 +29,7 @@ def _hipcc() -> str:
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ_DIR, os.path.splitext(src)[0] + ".o")
     path = os.path.join(CSRC, src)
-    cmd = [_hipcc(), *COMMON, *os.environ.get("IVFTQ_EXTRA_FLAGS", "").split(), "-c", path, "-o", obj]
+    cmd = [_hipcc(), *COMMON, "-c", path, "-o", obj]
     if src.endswith(".hip"):
         cmd[1:1] = DEVICE_FLAGS
     else:

@@ -44,18 +44,41 @@ ivftq_status fail(ivftq_status code, const char* fmt, ...) {
                         #expr, hipGetErrorString(e_));                                        \
     } while (0)
 
-// Grow-only device buffer.
+// Where device memory comes from: the caller's callbacks (ivftq_create), or hipMalloc / hipFree
+// when none were given.
+struct Allocator {
+    ivftq_alloc_fn alloc = nullptr;
+    ivftq_free_fn free = nullptr;
+    void* ctx = nullptr;
+    void* get(size_t bytes) const {
+        if (alloc) return alloc(bytes, ctx);
+        void* p = nullptr;
+        if (hipMalloc(&p, bytes) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
+        return p;
+    }
+    void put(void* p) const {
+        if (!p) return;
+        if (alloc) free(p, ctx); else (void)hipFree(p);
+    }
+};
+const Allocator kHipAllocator{};
+
+// Grow-only device buffer.  Contents are not kept across a growth.
 struct DevBuf {
     void* p = nullptr;
     size_t bytes = 0;
+    const Allocator* al = &kHipAllocator;
+    DevBuf() = default;
+    explicit DevBuf(const Allocator* a) : al(a) {}
     hipError_t ensure(size_t need) {
         if (need <= bytes) return hipSuccess;
-        if (p) { (void)hipFree(p); p = nullptr; bytes = 0; }
-        hipError_t e = hipMalloc(&p, need);
-        if (e == hipSuccess) bytes = need; else p = nullptr;
-        return e;
+        release();
+        p = al->get(need);
+        if (!p) return hipErrorOutOfMemory;
+        bytes = need;
+        return hipSuccess;
     }
-    void release() { if (p) (void)hipFree(p); p = nullptr; bytes = 0; }
+    void release() { al->put(p); p = nullptr; bytes = 0; }
     template <class T> T* as() const { return static_cast<T*>(p); }
 };
 
@@ -75,12 +98,12 @@ struct PinnedBuf {
 
 // kernel classes for the optional per-launch timing
 enum ProfId { P_ASSIGN, P_COARSE_SCORES, P_ENCODE, P_ROTATE_Q, P_SEG_HIST, P_SEG_SCAN, P_RANK, P_PACK,
-              P_COPY_LISTS, P_SELECT_PROBE, P_CAND_OFF, P_LIST_SCAN, P_SELECT_TOPK, P_KMEANS_UPDATE,
+              P_COPY_LISTS, P_SELECT_PROBE, P_CAND_OFF, P_LIST_SCAN, P_SELECT_TOPK, P_KMEANS_UPDATE, P_KMEANS_SUMS,
               P_PAIR_GROUP, P_BATCH_FIRST, P_BATCH_SCAN, P_MERGE, P_CASCADE, P_COUNT };
 const char* const kProfNames[P_COUNT] = {"coarse_assign", "coarse_scores", "encode_rotate_quantise_pack",
                                          "rotate_queries", "segment_hist", "segment_scan", "stable_rank",
                                          "pack_scatter", "copy_lists", "select_probes", "cand_offsets",
-                                         "list_scan", "select_topk", "kmeans_update", "pair_grouping",
+                                         "list_scan", "select_topk", "kmeans_update", "kmeans_cell_sums", "pair_grouping",
                                          "batch_scan_nearest", "batch_scan", "merge_topk", "cascade_rescore"};
 struct ProfRec { int id; hipEvent_t a, b; };
 // Timing events are recycled process-wide: creating one per launch costs more than the launch.
@@ -118,12 +141,28 @@ struct ivftq_index {
     int cascade_beta = 0;
     DevBuf w_S, w_probe, w_coarse, w_z, w_candoff, w_scores;
     DevBuf w_sums, w_counts, w_zero, w_rows, w_dst, w_obj;
+    DevBuf t_cent, t_cent_h, t_cent_l, t_bias;   // k-means works on its own tables; the index's change only on success
     DevBuf w_zh, w_zl;
     DevBuf w_first, w_fscores, w_fids, w_pairs, w_pairoff, w_tileoff, w_cscore, w_cslot, w_ccnt, w_gate;
     int search_mode = 0;   // 0 auto, 1 streaming scan only, 2 batched scan whenever the shape allows
     int64_t ws_limit = (int64_t)4 << 30;
     bool prof_on = false;
     std::vector<ProfRec> prof;
+    Allocator alloc;                  // every DevBuf of the index draws from it
+    hipStream_t last_stream = nullptr;   // stream of the most recent call that took one (ivftq_reset and the host read-backs wait for it)
+
+    std::vector<DevBuf*> buffers() {
+        return {&cent, &cent_h, &cent_l, &pi_h, &pi_l, &bias, &pi, &cb, &q_grid, &codes, &gamma, &ids, &d_off, &d_size, &w_assign,
+                &w_slot, &w_order, &w_hist, &w_count, &w_base, &w_flag, &w_best, &w_undecided, &cb_cascade, &w_keep, &w_keep_scores,
+                &w_S, &w_probe, &w_coarse, &w_z, &w_candoff, &w_scores, &w_sums, &w_counts, &w_zero, &w_rows, &w_dst, &w_obj,
+                &t_cent, &t_cent_h, &t_cent_l, &t_bias, &w_first, &w_fscores, &w_fids, &w_pairs, &w_pairoff, &w_tileoff, &w_cscore,
+                &w_cslot, &w_ccnt, &w_gate, &w_zh, &w_zl};
+    }
+    explicit ivftq_index(const Allocator& a) : alloc(a) {
+        for (DevBuf* bfr : buffers()) bfr->al = &alloc;
+    }
+    ivftq_index(const ivftq_index&) = delete;
+    ivftq_index& operator=(const ivftq_index&) = delete;
 
     ListStore store() const {
         ListStore s;
@@ -137,12 +176,7 @@ struct ivftq_index {
     }
     ~ivftq_index() {
         for (ProfRec& r : prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
-        for (DevBuf* bfr : {&cent, &cent_h, &cent_l, &pi_h, &pi_l, &bias, &pi, &cb, &q_grid, &codes, &gamma, &ids, &d_off, &d_size, &w_assign,
-                            &w_slot, &w_order, &w_hist, &w_count, &w_base, &w_flag, &w_best, &w_undecided, &cb_cascade, &w_keep, &w_keep_scores, &w_S, &w_probe, &w_coarse,
-                            &w_z, &w_candoff, &w_scores, &w_sums, &w_counts, &w_zero, &w_rows, &w_dst, &w_obj,
-                            &w_first, &w_fscores, &w_fids, &w_pairs, &w_pairoff, &w_tileoff, &w_cscore,
-                            &w_cslot, &w_ccnt, &w_gate, &w_zh, &w_zl})
-            bfr->release();
+        for (DevBuf* bfr : buffers()) bfr->release();
         pin.release();
     }
 };
@@ -186,11 +220,12 @@ ivftq_status upload_coarse(ivftq_index* ix) {
     std::vector<float> padded((size_t)ix->lpad * ix->dp, 0.f);
     for (int l = 0; l < ix->nlist; ++l)
         std::memcpy(&padded[(size_t)l * ix->dp], &ix->h_cent[(size_t)l * ix->d], sizeof(float) * ix->d);
+    HIP_TRY(hipStreamSynchronize(ix->last_stream));      // nothing queued earlier may still read the old table
     HIP_TRY(hipMemcpy(ix->cent.p, padded.data(), padded.size() * sizeof(float), hipMemcpyHostToDevice));
     std::vector<float> zero(ix->lpad, 0.f);
     HIP_TRY(hipMemcpy(ix->bias.p, zero.data(), zero.size() * sizeof(float), hipMemcpyHostToDevice));
     HIP_TRY(refresh_split(ix, nullptr));
-    HIP_TRY(hipDeviceSynchronize());
+    HIP_TRY(hipStreamSynchronize(nullptr));
     return IVFTQ_OK;
 }
 
@@ -203,10 +238,11 @@ ivftq_status upload_rotation(ivftq_index* ix) {
     std::vector<float> padded((size_t)ix->dp * ix->dp, 0.f);
     for (int i = 0; i < ix->d; ++i)
         std::memcpy(&padded[(size_t)i * ix->dp], &ix->h_pi[(size_t)i * ix->d], sizeof(float) * ix->d);
+    HIP_TRY(hipStreamSynchronize(ix->last_stream));
     HIP_TRY(hipMemcpy(ix->pi.p, padded.data(), padded.size() * sizeof(float), hipMemcpyHostToDevice));
     HIP_TRY(launch_split_rows(ix->pi.as<float>(), (int64_t)ix->dp * ix->dp, ix->pi_h.as<uint16_t>(),
                               ix->pi_l.as<uint16_t>(), nullptr));
-    HIP_TRY(hipDeviceSynchronize());
+    HIP_TRY(hipStreamSynchronize(nullptr));
     return IVFTQ_OK;
 }
 
@@ -225,7 +261,7 @@ ivftq_status ensure_capacity(ivftq_index* ix, const std::vector<int64_t>& need, 
         off[l] = total;
         total += cap[l];
     }
-    DevBuf ncodes, ngamma, nids, noff;
+    DevBuf ncodes(&ix->alloc), ngamma(&ix->alloc), nids(&ix->alloc), noff(&ix->alloc);
     hipError_t e = ncodes.ensure((size_t)total * ix->words * sizeof(uint32_t));
     if (e == hipSuccess) e = ngamma.ensure((size_t)total * sizeof(uint16_t));
     if (e == hipSuccess) e = nids.ensure((size_t)total * sizeof(int64_t));
@@ -255,6 +291,12 @@ ivftq_status ensure_capacity(ivftq_index* ix, const std::vector<int64_t>& need, 
 ivftq_status check_index(const ivftq_index* ix) {
     if (!ix) return fail(IVFTQ_INVALID_ARG, "index is NULL");
     return IVFTQ_OK;
+}
+
+// The stream a call works on; remembered so that calls without a stream argument know what to wait for.
+hipStream_t use_stream(ivftq_index* ix, void* stream) {
+    ix->last_stream = static_cast<hipStream_t>(stream);
+    return ix->last_stream;
 }
 
 }  // namespace
@@ -322,13 +364,17 @@ ivftq_status ivftq_haar_rotation(int d, uint64_t seed, float* pi_out) {
     return ivftq_haar_from_gaussian(d, g.data(), pi_out);
 }
 
-ivftq_status ivftq_create(int d, int b, int nlist, uint64_t rotation_seed, ivftq_index** out) {
-    return ivftq_create_refined(d, b, 0, nlist, rotation_seed, out);
+ivftq_status ivftq_create(int d, int b, int nlist, uint64_t rotation_seed, ivftq_alloc_fn alloc_fn,
+                          ivftq_free_fn free_fn, void* alloc_ctx, ivftq_index** out) {
+    return ivftq_create_refined(d, b, 0, nlist, rotation_seed, alloc_fn, free_fn, alloc_ctx, out);
 }
 
-ivftq_status ivftq_create_refined(int d, int b_stage1, int sign_bit, int nlist, uint64_t rotation_seed, ivftq_index** out) {
+ivftq_status ivftq_create_refined(int d, int b_stage1, int sign_bit, int nlist, uint64_t rotation_seed,
+                                  ivftq_alloc_fn alloc_fn, ivftq_free_fn free_fn, void* alloc_ctx, ivftq_index** out) {
     if (!out) return fail(IVFTQ_INVALID_ARG, "out is NULL");
     *out = nullptr;
+    if ((alloc_fn == nullptr) != (free_fn == nullptr))
+        return fail(IVFTQ_INVALID_ARG, "alloc_fn and free_fn must both be given or both be NULL");
     if (sign_bit != 0 && sign_bit != 1) return fail(IVFTQ_INVALID_ARG, "sign_bit=%d is neither 0 nor 1", sign_bit);
     if (b_stage1 < 1 || b_stage1 + sign_bit > 8)
         return fail(IVFTQ_INVALID_ARG, "b=%d (+%d sign bit) outside [1, 8] bits per coordinate", b_stage1, sign_bit);
@@ -337,7 +383,9 @@ ivftq_status ivftq_create_refined(int d, int b_stage1, int sign_bit, int nlist, 
     if (nlist < 1) return fail(IVFTQ_INVALID_ARG, "nlist=%d below 1", nlist);
     if (d > kMaxD) return fail(IVFTQ_UNSUPPORTED, "d=%d above %d", d, kMaxD);
     if (nlist > kMaxList) return fail(IVFTQ_UNSUPPORTED, "nlist=%d above %d", nlist, kMaxList);
-    ivftq_index* ix = new (std::nothrow) ivftq_index();
+    Allocator al;
+    al.alloc = alloc_fn; al.free = free_fn; al.ctx = alloc_ctx;
+    ivftq_index* ix = new (std::nothrow) ivftq_index(al);
     if (!ix) return fail(IVFTQ_OOM, "host allocation failed");
     ix->d = d; ix->b = b; ix->nlist = nlist; ix->K = 1 << b;
     ix->dp = rot_dp(d);
@@ -404,9 +452,9 @@ ivftq_status ivftq_destroy(ivftq_index* index) {
 
 ivftq_status ivftq_reset(ivftq_index* ix) {
     if (check_index(ix)) return IVFTQ_INVALID_ARG;
-    HIP_TRY(hipDeviceSynchronize());
     std::fill(ix->h_size.begin(), ix->h_size.end(), 0);
-    HIP_TRY(hipMemcpy(ix->d_size.p, ix->h_size.data(), ix->nlist * sizeof(int32_t), hipMemcpyHostToDevice));
+    HIP_TRY(launch_fill_u32(ix->d_size.as<uint32_t>(), ix->nlist, 0u, ix->last_stream));
+    HIP_TRY(hipStreamSynchronize(ix->last_stream));
     ix->ntotal = 0;
     return IVFTQ_OK;
 }
@@ -474,7 +522,7 @@ ivftq_status ivftq_set_workspace_limit(ivftq_index* ix, int64_t bytes) {
 
 ivftq_status ivftq_profile_enable(ivftq_index* ix, int on) {
     if (check_index(ix)) return IVFTQ_INVALID_ARG;
-    HIP_TRY(hipDeviceSynchronize());
+    for (const ProfRec& r : ix->prof) HIP_TRY(hipEventSynchronize(r.b));
     drop_profile(ix);
     ix->prof_on = on != 0;
     return IVFTQ_OK;
@@ -524,10 +572,10 @@ ivftq_status ivftq_measure_mfma_rate(int random_operands, double* tflops_out) {
 ivftq_status ivftq_profile_read(ivftq_index* ix, double* ms_out, int64_t* launches_out) {
     if (check_index(ix)) return IVFTQ_INVALID_ARG;
     if (!ms_out || !launches_out) return fail(IVFTQ_INVALID_ARG, "output pointer is NULL");
-    HIP_TRY(hipDeviceSynchronize());
     for (int i = 0; i < P_COUNT; ++i) { ms_out[i] = 0.0; launches_out[i] = 0; }
     for (const ProfRec& r : ix->prof) {
         float ms = 0.f;
+        HIP_TRY(hipEventSynchronize(r.b));
         HIP_TRY(hipEventElapsedTime(&ms, r.a, r.b));
         ms_out[r.id] += ms;
         launches_out[r.id] += 1;
@@ -556,7 +604,7 @@ ivftq_status ivftq_export_list(const ivftq_index* ix, int list, int64_t* ids_hos
     if (list < 0 || list >= ix->nlist) return fail(IVFTQ_INVALID_ARG, "list %d outside [0, %d)", list, ix->nlist);
     const int64_t n = ix->h_size[list];
     if (n == 0) return IVFTQ_OK;
-    HIP_TRY(hipDeviceSynchronize());
+    HIP_TRY(hipStreamSynchronize(ix->last_stream));
     const int64_t off = ix->h_off[list];
     if (ids_host)
         HIP_TRY(hipMemcpy(ids_host, ix->ids.as<int64_t>() + off, n * sizeof(int64_t), hipMemcpyDeviceToHost));
@@ -591,7 +639,7 @@ ivftq_status ivftq_train_coarse(ivftq_index* ix, const float* x_dev, int64_t n, 
     if (n < ix->nlist) return fail(IVFTQ_INVALID_ARG, "need at least nlist=%d training rows, got %lld", ix->nlist, (long long)n);
     if (niter < 0) return fail(IVFTQ_INVALID_ARG, "niter=%d is negative", niter);
     if (ix->ntotal > 0 && !ix->refreshing) return fail(IVFTQ_BAD_STATE, "centroids cannot change once vectors are stored");
-    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipStream_t st = use_stream(ix, stream);
     const int L = ix->nlist, d = ix->d, pitch = ix->dp;
 
     std::vector<int64_t> init(L);
@@ -613,24 +661,39 @@ ivftq_status ivftq_train_coarse(ivftq_index* ix, const float* x_dev, int64_t n, 
     std::vector<int32_t> dst(L);
     std::iota(dst.begin(), dst.end(), 0);
 
+    // The iterations run on tables of their own (t_*): the index keeps its centroids until training has succeeded.
+    const size_t table = (size_t)ix->lpad * pitch;
+    int64_t seg_len = round_up64((n + 1023) / 1024, 64);
+    const int nseg = (int)((n + seg_len - 1) / seg_len);
     HIP_TRY(ix->w_rows.ensure((size_t)L * sizeof(int64_t)));
     HIP_TRY(ix->w_dst.ensure((size_t)L * sizeof(int32_t)));
-    HIP_TRY(ix->w_sums.ensure((size_t)ix->lpad * pitch * sizeof(float)));
+    HIP_TRY(ix->w_sums.ensure(table * sizeof(float)));
     HIP_TRY(ix->w_counts.ensure((size_t)ix->lpad * sizeof(uint32_t)));
     HIP_TRY(ix->w_zero.ensure((size_t)ix->lpad * sizeof(uint32_t)));
     HIP_TRY(ix->w_assign.ensure((size_t)n * sizeof(int32_t)));
     HIP_TRY(ix->w_best.ensure((size_t)n * sizeof(float)));
     HIP_TRY(ix->w_obj.ensure(sizeof(double)));
+    HIP_TRY(ix->w_order.ensure((size_t)n * sizeof(int32_t)));
+    HIP_TRY(ix->w_hist.ensure((size_t)nseg * L * sizeof(uint32_t)));
+    HIP_TRY(ix->w_base.ensure((size_t)2 * L * sizeof(int64_t)));
+    HIP_TRY(ix->t_cent.ensure(table * sizeof(float)));
+    HIP_TRY(ix->t_cent_h.ensure(table * sizeof(uint16_t)));
+    HIP_TRY(ix->t_cent_l.ensure(table * sizeof(uint16_t)));
+    HIP_TRY(ix->t_bias.ensure((size_t)ix->lpad * sizeof(float)));
+    float* cent = ix->t_cent.as<float>();
+    float* bias = ix->t_bias.as<float>();
+    uint32_t* counts_dev = ix->w_counts.as<uint32_t>();
+    int64_t* cell_base = ix->w_base.as<int64_t>();
 
-    HIP_TRY(launch_fill_u32(ix->cent.as<uint32_t>(), (int64_t)ix->lpad * pitch, 0u, st));
+    HIP_TRY(launch_fill_u32(ix->t_cent.as<uint32_t>(), (int64_t)table, 0u, st));
     HIP_TRY(launch_fill_u32(ix->w_zero.as<uint32_t>(), ix->lpad, 0u, st));
+    HIP_TRY(launch_fill_u32(ix->w_counts.as<uint32_t>(), ix->lpad, 0u, st));
     HIP_TRY(launch_fill_u32(ix->w_flag.as<uint32_t>(), 1, 0u, st));
     HIP_TRY(hipMemcpyAsync(ix->w_rows.p, init.data(), L * sizeof(int64_t), hipMemcpyHostToDevice, st));
     HIP_TRY(hipMemcpyAsync(ix->w_dst.p, dst.data(), L * sizeof(int32_t), hipMemcpyHostToDevice, st));
-    HIP_TRY(launch_copy_rows_normalised(x_dev, d, ix->w_rows.as<int64_t>(), ix->w_dst.as<int32_t>(), L,
-                                        ix->cent.as<float>(), pitch, st));
-    HIP_TRY(timed(ix, st, P_KMEANS_UPDATE, [&] { return launch_kmeans_update(ix->cent.as<float>(), pitch, ix->w_sums.as<float>(), ix->w_zero.as<uint32_t>(),
-                                 ix->bias.as<float>(), L, ix->lpad, d, st); }));
+    HIP_TRY(launch_copy_rows_normalised(x_dev, d, ix->w_rows.as<int64_t>(), ix->w_dst.as<int32_t>(), L, cent, pitch, st));
+    HIP_TRY(timed(ix, st, P_KMEANS_UPDATE, [&] { return launch_kmeans_update(cent, pitch, ix->w_sums.as<float>(), ix->w_zero.as<uint32_t>(),
+                                 bias, L, ix->lpad, d, st); }));
     HIP_TRY(hipStreamSynchronize(st));
 
     std::vector<uint32_t> counts(L);
@@ -638,16 +701,20 @@ ivftq_status ivftq_train_coarse(ivftq_index* ix, const float* x_dev, int64_t n, 
     uint64_t rs = seed ^ 0x1234567887654321ull;
     double inertia = std::nan("");
     for (int it = 0; it < niter; ++it) {
-        HIP_TRY(launch_fill_u32(ix->w_sums.as<uint32_t>(), (int64_t)ix->lpad * pitch, 0u, st));
-        HIP_TRY(launch_fill_u32(ix->w_counts.as<uint32_t>(), ix->lpad, 0u, st));
-        HIP_TRY(refresh_split(ix, st));
-        HIP_TRY(timed(ix, st, P_ASSIGN, [&] { return launch_coarse(0, x_dev, n, d, ix->cent_h.as<uint16_t>(), ix->cent_l.as<uint16_t>(), pitch, ix->bias.as<float>(), L, ix->lpad,
+        HIP_TRY(launch_split_rows(cent, (int64_t)table, ix->t_cent_h.as<uint16_t>(), ix->t_cent_l.as<uint16_t>(), st));
+        HIP_TRY(timed(ix, st, P_ASSIGN, [&] { return launch_coarse(0, x_dev, n, d, ix->t_cent_h.as<uint16_t>(), ix->t_cent_l.as<uint16_t>(), pitch, bias, L, ix->lpad,
                               ix->w_assign.as<int32_t>(), ix->w_best.as<float>(), nullptr, 0,
                               ix->w_flag.as<int>(), st); }));
-        HIP_TRY(launch_kmeans_accumulate(x_dev, n, d, ix->w_assign.as<int32_t>(), ix->w_sums.as<float>(), pitch,
-                                         ix->w_counts.as<uint32_t>(), st));
-        HIP_TRY(timed(ix, st, P_KMEANS_UPDATE, [&] { return launch_kmeans_update(ix->cent.as<float>(), pitch, ix->w_sums.as<float>(),
-                                     ix->w_counts.as<uint32_t>(), ix->bias.as<float>(), L, ix->lpad, d, st); }));
+        // Sums per cell in a fixed order (two runs give the same bits): the rows are grouped by cell with the
+        // stable counting sort of the append path, then one workgroup adds up the rows of a cell.
+        HIP_TRY(timed(ix, st, P_SEG_HIST, [&] { return launch_segment_hist(ix->w_assign.as<int32_t>(), n, seg_len, nseg, L, ix->w_hist.as<uint32_t>(), st); }));
+        HIP_TRY(timed(ix, st, P_SEG_SCAN, [&] { return launch_segment_scan(ix->w_hist.as<uint32_t>(), nseg, L, counts_dev, st); }));
+        HIP_TRY(launch_exclusive_scan(counts_dev, L, cell_base, st));
+        HIP_TRY(timed(ix, st, P_RANK, [&] { return launch_stable_rank(ix->w_assign.as<int32_t>(), n, seg_len, nseg, L, ix->w_hist.as<uint32_t>(), nullptr,
+                                   nullptr, cell_base, ix->w_order.as<int32_t>(), st); }));
+        HIP_TRY(timed(ix, st, P_KMEANS_SUMS, [&] { return launch_kmeans_cell_sums(x_dev, d, ix->w_order.as<int32_t>(), cell_base, counts_dev, L,
+                                        ix->w_sums.as<float>(), pitch, st); }));
+        HIP_TRY(timed(ix, st, P_KMEANS_UPDATE, [&] { return launch_kmeans_update(cent, pitch, ix->w_sums.as<float>(), counts_dev, bias, L, ix->lpad, d, st); }));
         if (it == niter - 1) HIP_TRY(launch_inertia(ix->w_best.as<float>(), n, ix->w_obj.as<double>(), st));
         HIP_TRY(hipMemcpyAsync(counts.data(), ix->w_counts.p, L * sizeof(uint32_t), hipMemcpyDeviceToHost, st));
         int flag = 0;
@@ -670,16 +737,19 @@ ivftq_status ivftq_train_coarse(ivftq_index* ix, const float* x_dev, int64_t n, 
             HIP_TRY(hipMemcpy(ix->w_rows.p, rows.data(), rows.size() * sizeof(int64_t), hipMemcpyHostToDevice));
             HIP_TRY(hipMemcpy(ix->w_dst.p, empty.data(), empty.size() * sizeof(int32_t), hipMemcpyHostToDevice));
             HIP_TRY(launch_copy_rows_normalised(x_dev, d, ix->w_rows.as<int64_t>(), ix->w_dst.as<int32_t>(),
-                                                (int)empty.size(), ix->cent.as<float>(), pitch, st));
-            HIP_TRY(timed(ix, st, P_KMEANS_UPDATE, [&] { return launch_kmeans_update(ix->cent.as<float>(), pitch, ix->w_sums.as<float>(),
-                                         ix->w_zero.as<uint32_t>(), ix->bias.as<float>(), L, ix->lpad, d, st); }));
+                                                (int)empty.size(), cent, pitch, st));
+            HIP_TRY(timed(ix, st, P_KMEANS_UPDATE, [&] { return launch_kmeans_update(cent, pitch, ix->w_sums.as<float>(),
+                                         ix->w_zero.as<uint32_t>(), bias, L, ix->lpad, d, st); }));
             HIP_TRY(hipStreamSynchronize(st));
         }
     }
-    HIP_TRY(launch_normalise_centroids(ix->cent.as<float>(), pitch, ix->bias.as<float>(), L, d, st));
-    HIP_TRY(refresh_split(ix, st));
+    HIP_TRY(launch_normalise_centroids(cent, pitch, bias, L, d, st));
     std::vector<float> padded((size_t)L * pitch);
-    HIP_TRY(hipMemcpyAsync(padded.data(), ix->cent.p, padded.size() * sizeof(float), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipMemcpyAsync(padded.data(), cent, padded.size() * sizeof(float), hipMemcpyDeviceToHost, st));
+    // success: the index takes the new table over (same stream, so later calls on it see the new centroids)
+    HIP_TRY(hipMemcpyAsync(ix->cent.p, cent, table * sizeof(float), hipMemcpyDeviceToDevice, st));
+    HIP_TRY(launch_fill_u32(ix->bias.as<uint32_t>(), ix->lpad, 0u, st));
+    HIP_TRY(refresh_split(ix, st));
     HIP_TRY(hipStreamSynchronize(st));
     for (int l = 0; l < L; ++l)
         std::memcpy(&ix->h_cent[(size_t)l * d], &padded[(size_t)l * pitch], sizeof(float) * d);
@@ -776,7 +846,7 @@ ivftq_status assign_rows(ivftq_index* ix, const float* x_dev, int64_t n, int32_t
 ivftq_status ivftq_assign_undecided(ivftq_index* ix, int64_t* count_out, void* stream) {
     if (check_index(ix)) return IVFTQ_INVALID_ARG;
     if (!count_out) return fail(IVFTQ_INVALID_ARG, "count_out is NULL");
-    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipStream_t st = use_stream(ix, stream);
     int v = 0;
     HIP_TRY(hipMemcpyAsync(&v, ix->w_flag.as<int>() + 1, sizeof(int), hipMemcpyDeviceToHost, st));
     HIP_TRY(hipStreamSynchronize(st));
@@ -792,7 +862,7 @@ ivftq_status ivftq_encode_only(ivftq_index* ix, const float* x_dev, int64_t n, i
     if (!x_dev) return fail(IVFTQ_INVALID_ARG, "x_dev is NULL");
     if (!ix->has_coarse) return fail(IVFTQ_BAD_STATE, "coarse centroids not trained or set");
     if (n > ((int64_t)1 << 31) - 1) return fail(IVFTQ_UNSUPPORTED, "more than 2^31-1 rows in one call");
-    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipStream_t st = use_stream(ix, stream);
     HIP_TRY(ix->w_assign.ensure((size_t)n * sizeof(int32_t)));
     int32_t* assign = assign_dev ? assign_dev : ix->w_assign.as<int32_t>();
     { ivftq_status sa = assign_rows(ix, x_dev, n, assign, st); if (sa != IVFTQ_OK) return sa; }
@@ -817,7 +887,7 @@ ivftq_status ivftq_encode_add(ivftq_index* ix, const float* x_dev, int64_t n, co
     if (!x_dev) return fail(IVFTQ_INVALID_ARG, "x_dev is NULL");
     if (!ix->has_coarse) return fail(IVFTQ_BAD_STATE, "coarse centroids not trained or set");
     if (n > ((int64_t)1 << 31) - 1) return fail(IVFTQ_UNSUPPORTED, "more than 2^31-1 rows in one call");
-    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipStream_t st = use_stream(ix, stream);
     const int L = ix->nlist;
 
     // 1. coarse assignment
@@ -852,7 +922,7 @@ ivftq_status ivftq_add_encoded(ivftq_index* ix, int64_t n, const int32_t* assign
     if (!assign_dev || !codes_dev || !gamma_dev) return fail(IVFTQ_INVALID_ARG, "input pointer is NULL");
     if (!ix->has_coarse) return fail(IVFTQ_BAD_STATE, "coarse centroids not trained or set");
     if (n > ((int64_t)1 << 31) - 1) return fail(IVFTQ_UNSUPPORTED, "more than 2^31-1 rows in one call");
-    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipStream_t st = use_stream(ix, stream);
     HIP_TRY(ix->w_slot.ensure((size_t)n * sizeof(int64_t)));
     HIP_TRY(launch_fill_u32(ix->w_flag.as<uint32_t>(), 1, 0u, st));
     std::vector<int64_t> need;
@@ -871,6 +941,7 @@ namespace {
 
 struct ScopedBuf {
     DevBuf b;
+    explicit ScopedBuf(const Allocator* a) : b(a) {}
     ~ScopedBuf() { b.release(); }
 };
 
@@ -905,7 +976,7 @@ ivftq_status ivftq_reconstruct(ivftq_index* ix, float* x_out_dev, int64_t* ids_o
     if (check_index(ix)) return IVFTQ_INVALID_ARG;
     if (!x_out_dev) return fail(IVFTQ_INVALID_ARG, "x_out_dev is NULL");
     if (ix->ntotal == 0) return IVFTQ_OK;
-    return reconstruct_all(ix, x_out_dev, ids_out_dev, static_cast<hipStream_t>(stream));
+    return reconstruct_all(ix, x_out_dev, ids_out_dev, use_stream(ix, stream));
 }
 
 ivftq_status ivftq_reencode(ivftq_index* ix, const float* centroids_host, void* stream) {
@@ -914,9 +985,9 @@ ivftq_status ivftq_reencode(ivftq_index* ix, const float* centroids_host, void* 
     if (!ix->has_coarse) return fail(IVFTQ_BAD_STATE, "no coarse centroids yet");
     for (size_t i = 0; i < (size_t)ix->nlist * ix->d; ++i)
         if (!std::isfinite(centroids_host[i])) return fail(IVFTQ_INVALID_ARG, "non-finite centroid value");
-    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipStream_t st = use_stream(ix, stream);
     const int64_t n = ix->ntotal;
-    ScopedBuf xh, lab;
+    ScopedBuf xh(&ix->alloc), lab(&ix->alloc);
     if (n > 0) {
         HIP_TRY(xh.b.ensure((size_t)n * ix->d * sizeof(float)));
         HIP_TRY(lab.b.ensure((size_t)n * sizeof(int64_t)));
@@ -935,10 +1006,10 @@ ivftq_status ivftq_refresh_coarse(ivftq_index* ix, int64_t sample_n, int niter, 
     if (!ix->has_coarse || ix->ntotal == 0) return fail(IVFTQ_BAD_STATE, "nothing stored to refresh from");
     if (sample_n < ix->nlist) return fail(IVFTQ_INVALID_ARG, "sample of %lld below nlist=%d", (long long)sample_n, ix->nlist);
     if (niter < 0) return fail(IVFTQ_INVALID_ARG, "niter=%d is negative", niter);
-    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipStream_t st = use_stream(ix, stream);
     const int L = ix->nlist;
     const int64_t n = ix->ntotal;
-    ScopedBuf xh, lab, sample, rows;
+    ScopedBuf xh(&ix->alloc), lab(&ix->alloc), sample(&ix->alloc), rows(&ix->alloc);
     HIP_TRY(xh.b.ensure((size_t)n * ix->d * sizeof(float)));
     HIP_TRY(lab.b.ensure((size_t)n * sizeof(int64_t)));
     ivftq_status s = reconstruct_all(ix, xh.b.as<float>(), lab.b.as<int64_t>(), st);
@@ -961,15 +1032,10 @@ ivftq_status ivftq_refresh_coarse(ivftq_index* ix, int64_t sample_n, int niter, 
     HIP_TRY(hipMemcpyAsync(rows.b.p, pick.data(), pick.size() * sizeof(int64_t), hipMemcpyHostToDevice, st));
     HIP_TRY(launch_gather_rows(xh.b.as<float>(), ix->d, rows.b.as<int64_t>(), (int64_t)pick.size(), sample.b.as<float>(), st));
     HIP_TRY(hipStreamSynchronize(st));
-    const std::vector<float> old_cent = ix->h_cent;
     ix->refreshing = true;
     s = ivftq_train_coarse(ix, sample.b.as<float>(), (int64_t)pick.size(), niter, init_rows_host, seed, inertia_out, st);
     ix->refreshing = false;
-    if (s != IVFTQ_OK) {                      // keep the index as it was: old centroids, lists untouched
-        ix->h_cent = old_cent;
-        (void)upload_coarse(ix);
-        return s;
-    }
+    if (s != IVFTQ_OK) return s;              // a failed training leaves centroids and lists as they were
     return readd_all(ix, xh.b.as<float>(), lab.b.as<int64_t>(), n, st);
 }
 
@@ -1018,7 +1084,7 @@ ivftq_status ivftq_coarse_probe(ivftq_index* ix, const float* q_dev, int64_t nq,
     ivftq_status s = check_query_args(ix, q_dev, nq, nprobe);
     if (s != IVFTQ_OK) return s;
     if (nq == 0) return IVFTQ_OK;
-    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipStream_t st = use_stream(ix, stream);
     const int64_t ldS = round_up(ix->nlist, 4);
     const int64_t qc = std::max<int64_t>(1, std::min<int64_t>(nq, ix->ws_limit / (ldS * 4)));
     HIP_TRY(ix->w_S.ensure((size_t)qc * ldS * sizeof(float)));
@@ -1045,7 +1111,7 @@ ivftq_status search_core(ivftq_index* ix, const float* q_dev, int64_t nq, int np
     if (k > kMaxK) return fail(IVFTQ_UNSUPPORTED, "k=%d above %d", k, kMaxK);
     if (nq == 0) return IVFTQ_OK;
     if (!scores_dev || !ids_dev) return fail(IVFTQ_INVALID_ARG, "output pointer is NULL");
-    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipStream_t st = use_stream(ix, stream);
 
     // upper bound of candidates per query: the nprobe largest lists
     std::vector<int32_t> sizes(ix->h_size);
@@ -1228,7 +1294,7 @@ ivftq_status ivftq_search_cascade(ivftq_index* ix, const float* q_dev, int64_t n
     if (n_keep > kMaxK) return fail(IVFTQ_UNSUPPORTED, "n_keep=%d above %d", n_keep, kMaxK);
     if (nq == 0) return IVFTQ_OK;
     if (!scores_dev || !ids_dev) return fail(IVFTQ_INVALID_ARG, "output pointer is NULL");
-    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipStream_t st = use_stream(ix, stream);
 
     // pass-1 table over the full code: entry e holds the value of the merged bin e >> (bits - beta)
     if (ix->cascade_beta != beta) {

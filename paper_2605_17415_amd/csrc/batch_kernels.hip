@@ -90,10 +90,7 @@ __global__ void k_pair_scatter(const int32_t* __restrict__ probe, const int32_t*
 // pairs, counts them per bucket in LDS, and touches each global counter once per bucket it met
 // (thousands of pairs hit the same few thousand counters, so per-pair global atomics serialise).
 // In the scatter step that one global atomic reserves the workgroup's range inside the bucket.
-#ifndef IVFTQ_PAIR_CHUNK
-#define IVFTQ_PAIR_CHUNK 4096
-#endif
-constexpr int kPairChunk = IVFTQ_PAIR_CHUNK;
+constexpr int kPairChunk = 4096;
 constexpr int kPairLdsBuckets = 16384;      // 2L must not exceed this (64 KB of LDS)
 
 __global__ __launch_bounds__(1024) void k_pair_count_lds(const int32_t* __restrict__ probe,
@@ -547,18 +544,12 @@ __global__ __launch_bounds__(256) void k_merge(MergeArgs a) {
 // lighter in registers and LDS, so smaller workgroups let several share a compute unit and overlap their set-up).
 template <int DP, int B, int NQ, int WD, int OD, int WT, int OT>
 hipError_t run_batch(const BatchScanArgs& a, int max_tiles, hipStream_t st) {
-    static bool attr_set = false;
+    static LdsLimit lim_threshold, lim_dense;
     const size_t lds = BatchCfg<DP, B, NQ>::lds_bytes;
     const size_t lds_threshold = BatchCfg<DP, B, NQ>::lds_bytes_threshold;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_batch_scan<DP, B, NQ, WT, OT, false>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_threshold);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_batch_scan<DP, B, NQ, WD, OD, true>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    hipError_t e = a.dense ? lim_dense.ensure(reinterpret_cast<const void*>(k_batch_scan<DP, B, NQ, WD, OD, true>), lds)
+                           : lim_threshold.ensure(reinterpret_cast<const void*>(k_batch_scan<DP, B, NQ, WT, OT, false>), lds_threshold);
+    if (e != hipSuccess) return e;
     if (a.dense)
         hipLaunchKernelGGL((k_batch_scan<DP, B, NQ, WD, OD, true>), dim3((unsigned)max_tiles), dim3(WD * 64), lds, st, a);
     else
@@ -568,15 +559,11 @@ hipError_t run_batch(const BatchScanArgs& a, int max_tiles, hipStream_t st) {
 
 }  // namespace
 
-#ifndef IVFTQ_BATCH_NQ224
-#define IVFTQ_BATCH_NQ224 4
-#endif
-
 int batch_tile_queries(int d, int b) {
     const int dp = rot_dp(d);
     if (b < 2 || b > 5) return 0;
     if (dp == 64 || dp == 96 || dp == 128) return 128;
-    if (dp == 224) return 32 * IVFTQ_BATCH_NQ224;
+    if (dp == 224) return 128;
     return 0;
 }
 
@@ -588,15 +575,11 @@ hipError_t launch_pair_grouping(const int32_t* probe, const int32_t* first, int6
     hipError_t e = launch_fill_u32(count, 2 * L, 0u, st);
     if (e != hipSuccess) return e;
     if (2 * L <= kPairLdsBuckets) {
-        static bool attr_set = false;
-        if (!attr_set) {
-            const int most = kPairLdsBuckets * (int)sizeof(uint32_t);
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_pair_count_lds), hipFuncAttributeMaxDynamicSharedMemorySize, most);
-            if (e == hipSuccess)
-                e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_pair_scatter_lds), hipFuncAttributeMaxDynamicSharedMemorySize, most);
-            if (e != hipSuccess) return e;
-            attr_set = true;
-        }
+        static LdsLimit lim_count, lim_scatter;
+        const size_t most = (size_t)kPairLdsBuckets * sizeof(uint32_t);
+        e = lim_count.ensure(reinterpret_cast<const void*>(k_pair_count_lds), most);
+        if (e == hipSuccess) e = lim_scatter.ensure(reinterpret_cast<const void*>(k_pair_scatter_lds), most);
+        if (e != hipSuccess) return e;
         const unsigned blocks = (unsigned)((n + kPairChunk - 1) / kPairChunk);
         const size_t lds = (size_t)2 * L * sizeof(uint32_t);
         hipLaunchKernelGGL(k_pair_count_lds, dim3(blocks), dim3(1024), lds, st, probe, first, nq, np, L, count);
@@ -614,32 +597,19 @@ hipError_t launch_pair_grouping(const int32_t* probe, const int32_t* first, int6
 hipError_t launch_batch_scan(const BatchScanArgs& a, int d, int b, int max_tiles, hipStream_t st) {
     if (max_tiles <= 0) return hipSuccess;
     const int dp = rot_dp(d);
-#ifndef IVFTQ_BATCH_WAVES
-#define IVFTQ_BATCH_WAVES 8
-#endif
-#ifndef IVFTQ_BATCH_OCC
-#define IVFTQ_BATCH_OCC 2
-#endif
-#ifndef IVFTQ_BATCH_WAVES_T224
-#define IVFTQ_BATCH_WAVES_T224 4
-#endif
-#ifndef IVFTQ_BATCH_WAVES_T
-#define IVFTQ_BATCH_WAVES_T 4
-#endif
-#ifndef IVFTQ_BATCH_OCC_T
-#define IVFTQ_BATCH_OCC_T 3
-#endif
+    // <coordinates, queries per tile / 32, wavefronts per SIMD of the dense pass, wavefronts per workgroup and per
+    // SIMD of the threshold pass>; the dense pass runs eight wavefronts per workgroup
 #define IVFTQ_BATCH(DPV, NQV, OCCV, WT, OT)                                                                       \
     if (dp == DPV) {                                                                                              \
-        if (b == 2) return run_batch<DPV, 2, NQV, IVFTQ_BATCH_WAVES, OCCV, WT, OT>(a, max_tiles, st);             \
-        if (b == 3) return run_batch<DPV, 3, NQV, IVFTQ_BATCH_WAVES, OCCV, WT, OT>(a, max_tiles, st);             \
-        if (b == 4) return run_batch<DPV, 4, NQV, IVFTQ_BATCH_WAVES, OCCV, WT, OT>(a, max_tiles, st);             \
-        if (b == 5) return run_batch<DPV, 5, NQV, IVFTQ_BATCH_WAVES, OCCV, WT, OT>(a, max_tiles, st);             \
+        if (b == 2) return run_batch<DPV, 2, NQV, 8, OCCV, WT, OT>(a, max_tiles, st);             \
+        if (b == 3) return run_batch<DPV, 3, NQV, 8, OCCV, WT, OT>(a, max_tiles, st);             \
+        if (b == 4) return run_batch<DPV, 4, NQV, 8, OCCV, WT, OT>(a, max_tiles, st);             \
+        if (b == 5) return run_batch<DPV, 5, NQV, 8, OCCV, WT, OT>(a, max_tiles, st);             \
     }
-    IVFTQ_BATCH(64, 4, IVFTQ_BATCH_OCC, IVFTQ_BATCH_WAVES_T, IVFTQ_BATCH_OCC_T)
-    IVFTQ_BATCH(96, 4, IVFTQ_BATCH_OCC, IVFTQ_BATCH_WAVES_T, IVFTQ_BATCH_OCC_T)
-    IVFTQ_BATCH(128, 4, IVFTQ_BATCH_OCC, IVFTQ_BATCH_WAVES_T, IVFTQ_BATCH_OCC_T)
-    IVFTQ_BATCH(224, IVFTQ_BATCH_NQ224, 2, IVFTQ_BATCH_WAVES_T224, 2)
+    IVFTQ_BATCH(64, 4, 2, 4, 3)
+    IVFTQ_BATCH(96, 4, 2, 4, 3)
+    IVFTQ_BATCH(128, 4, 2, 4, 3)
+    IVFTQ_BATCH(224, 4, 2, 4, 2)
 #undef IVFTQ_BATCH
     return hipErrorInvalidValue;
 }
@@ -649,13 +619,9 @@ hipError_t launch_merge(const MergeArgs& a, int64_t nq, hipStream_t st) {
     int size = 1;
     while (size < a.k + a.cap) size <<= 1;
     const size_t lds = (size_t)size * 17 + 4 + (size_t)a.d * sizeof(float);
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_merge),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static LdsLimit lim;
+    const hipError_t e = lim.ensure(reinterpret_cast<const void*>(k_merge), 128 * 1024);
+    if (e != hipSuccess) return e;
     hipLaunchKernelGGL(k_merge, dim3((unsigned)nq), dim3(256), lds, st, a);
     return hipGetLastError();
 }

@@ -207,15 +207,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
 constexpr float kScreenMargin = 2.2e-3f;
 constexpr float kScreenNone = -3.0e38f;     // below every score, finite so that tagging its low bits keeps it a number
 
-#ifndef IVFTQ_SCREEN_NT
-#define IVFTQ_SCREEN_NT 2
-#endif
-#ifndef IVFTQ_SCREEN_WAVES
-#define IVFTQ_SCREEN_WAVES 3
-#endif
 // 32-centroid tiles per LDS stage of the screening pass (two stages are resident)
 template <int DP>
-constexpr int screen_nt() { return DP <= 128 ? IVFTQ_SCREEN_NT : 2; }
+constexpr int screen_nt() { return 2; }
 
 template <int DP>
 constexpr size_t screen_lds_bytes() { return (size_t)2 * screen_nt<DP>() * 32 * CoarseCfg<DP>::LDH * sizeof(uint16_t); }
@@ -253,7 +247,7 @@ __device__ __forceinline__ float max3_raw(float a, float b, float c) {
 // VEC4: rows are read 16 bytes at a time (d % 4 == 0 and x 16-byte aligned); a template parameter so that
 // each instantiation carries one loading path only (with both, the loads of the prologue spill).
 template <int DP, int R, bool VEC4>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((DP <= 128 || R == 1) ? IVFTQ_SCREEN_WAVES : 2))) void k_coarse_screen(
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((DP <= 128 || R == 1) ? 3 : 2))) void k_coarse_screen(
     const float* __restrict__ x, int64_t n, int d, const uint16_t* __restrict__ cent_h, int cent_pitch,
     int L, int Lpad, int32_t* __restrict__ assign, int32_t* __restrict__ row_list,
     unsigned long long* __restrict__ row_key, int* __restrict__ row_count) {
@@ -466,25 +460,16 @@ template <int DP, int RS>
 hipError_t run_screened(const float* x, int64_t n, int d, const uint16_t* cent_h, const uint16_t* cent_l, int cent_pitch,
                         int L, int Lpad, int32_t* assign, int* flag, int32_t* row_list, unsigned long long* row_key,
                         int* row_count, hipStream_t st) {
-    static bool attr_set = false;
+    static LdsLimit lim_screen[2], lim_resolve[2];
     const size_t lds_screen = screen_lds_bytes<DP>();
     const size_t lds = (size_t)2 * kTN * CoarseCfg<DP>::LDH * sizeof(uint16_t);
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_coarse_screen<DP, RS, true>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_screen);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_coarse_screen<DP, RS, false>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_screen);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_coarse_resolve<DP, true>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_coarse_resolve<DP, false>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
     const int vec4 = (d % 4 == 0) && (reinterpret_cast<uintptr_t>(x) % 16 == 0);
+    hipError_t e = vec4 ? lim_screen[1].ensure(reinterpret_cast<const void*>(k_coarse_screen<DP, RS, true>), lds_screen)
+                        : lim_screen[0].ensure(reinterpret_cast<const void*>(k_coarse_screen<DP, RS, false>), lds_screen);
+    if (e == hipSuccess)
+        e = vec4 ? lim_resolve[1].ensure(reinterpret_cast<const void*>(k_coarse_resolve<DP, true>), lds)
+                 : lim_resolve[0].ensure(reinterpret_cast<const void*>(k_coarse_resolve<DP, false>), lds);
+    if (e != hipSuccess) return e;
     const int64_t blocks_s = (n + 4 * 32 * RS - 1) / (4 * 32 * RS);
     if (vec4)
         hipLaunchKernelGGL((k_coarse_screen<DP, RS, true>), dim3((unsigned)blocks_s), dim3(256), lds_screen, st, x, n, d,
@@ -512,20 +497,14 @@ template <int DP, int R>
 hipError_t run(int mode, const float* x, int64_t n, int d, const uint16_t* cent_h, const uint16_t* cent_l,
                int cent_pitch, const float* bias, int L, int Lpad, int32_t* assign, float* best, float* scores,
                int64_t ld_scores, int* flag, hipStream_t st) {
-    static bool attr_set = false;
+    static LdsLimit lim[2];
     const size_t lds = CoarseCfg<DP>::lds_bytes;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_coarse<DP, R, true>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_coarse<DP, R, false>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
     const int64_t rows_per_wg = 4 * 32 * R;
     const int64_t blocks = (n + rows_per_wg - 1) / rows_per_wg;
     const int vec4 = (d % 4 == 0) && (reinterpret_cast<uintptr_t>(x) % 16 == 0);
+    const hipError_t e = vec4 ? lim[1].ensure(reinterpret_cast<const void*>(k_coarse<DP, R, true>), lds)
+                              : lim[0].ensure(reinterpret_cast<const void*>(k_coarse<DP, R, false>), lds);
+    if (e != hipSuccess) return e;
     // score mode: every (row, centroid) result is independent, so when the rows alone do not fill
     // the chip the centroid stages are split over gridDim.y as well
     int ysplit = 1;
@@ -595,13 +574,10 @@ hipError_t launch_coarse_screened(const float* x, int64_t n, int d, const uint16
                                   unsigned long long* row_key, int* row_count, hipStream_t st) {
     if (n <= 0) return hipSuccess;
     switch (coarse_dp(d)) {
-#ifndef IVFTQ_SCREEN_RBIG
-#define IVFTQ_SCREEN_RBIG 2
-#endif
 #define IVFTQ_CASE(DPV, RS) \
     case DPV: return run_screened<DPV, RS>(x, n, d, cent_h, cent_l, cent_pitch, L, Lpad, assign, flag, row_list, row_key, row_count, st);
-        IVFTQ_CASE(32, 2) IVFTQ_CASE(64, 2) IVFTQ_CASE(96, 2) IVFTQ_CASE(128, 2) IVFTQ_CASE(160, IVFTQ_SCREEN_RBIG)
-        IVFTQ_CASE(192, IVFTQ_SCREEN_RBIG) IVFTQ_CASE(208, IVFTQ_SCREEN_RBIG) IVFTQ_CASE(224, IVFTQ_SCREEN_RBIG) IVFTQ_CASE(256, IVFTQ_SCREEN_RBIG)
+        IVFTQ_CASE(32, 2) IVFTQ_CASE(64, 2) IVFTQ_CASE(96, 2) IVFTQ_CASE(128, 2) IVFTQ_CASE(160, 2)
+        IVFTQ_CASE(192, 2) IVFTQ_CASE(208, 2) IVFTQ_CASE(224, 2) IVFTQ_CASE(256, 2)
 #undef IVFTQ_CASE
         default: return hipErrorInvalidValue;
     }

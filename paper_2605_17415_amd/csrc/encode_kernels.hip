@@ -34,10 +34,7 @@ struct EncCfg {
     static constexpr int KB = DP / 16;
     static constexpr int NT = DP / 32;
     static constexpr int LDH = DP + 8;                     // halves per LDS row of the Pi tile
-#ifndef IVFTQ_ENC_R2_MAX_DP
-#define IVFTQ_ENC_R2_MAX_DP 64
-#endif
-    static constexpr int R = DP <= IVFTQ_ENC_R2_MAX_DP ? 2 : 1;   // 32-row tiles per wavefront (register budget)
+    static constexpr int R = DP <= 64 ? 2 : 1;   // 32-row tiles per wavefront (register budget)
     static constexpr int stage_halves = 2 * 32 * LDH;      // hi and lo parts of one 32-row tile of Pi
     static constexpr int PF = (32 * (DP / 8) + 255) / 256; // 16-byte pieces of one part a thread stages
     static constexpr size_t pi_bytes = (size_t)2 * stage_halves * sizeof(uint16_t);
@@ -290,15 +287,11 @@ void k_encode(EncodeArgs a, int flags) {
 
 template <int DP, int MODE>
 hipError_t run_mode(const EncodeArgs& a, hipStream_t st) {
-    static size_t attr_lds = 0;
+    static LdsLimit lim;
     const size_t lds = encode_lds_bytes<DP>(MODE, a.q_cells, a.store.words);
     if (lds > 160 * 1024) return hipErrorInvalidValue;
-    if (lds > attr_lds) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_encode<DP, MODE>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        attr_lds = lds;
-    }
+    const hipError_t e = lim.ensure(reinterpret_cast<const void*>(k_encode<DP, MODE>), lds);
+    if (e != hipSuccess) return e;
     const int rows_per_wg = 4 * 32 * EncCfg<DP>::R;
     const int64_t blocks = (a.n + rows_per_wg - 1) / rows_per_wg;
     int flags = 0;

@@ -4,6 +4,7 @@
 #include <cmath>
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cstdint>
 
 namespace ivftq {
@@ -13,10 +14,7 @@ constexpr int kRowsPerWG = 128;      // data rows one workgroup of the contracti
 constexpr int kMaxD = 256;
 constexpr int kMaxList = 16384;
 constexpr int kMaxK = 2048;
-#ifndef IVFTQ_PREFIX_X2
-#define IVFTQ_PREFIX_X2 2
-#endif
-constexpr int kPrefixFactorX2 = IVFTQ_PREFIX_X2;   // twice the factor f in: dense prefix >= f * k * T / cap vectors
+constexpr int kPrefixFactorX2 = 2;   // twice the factor f in: dense prefix >= f * k * T / cap vectors
 constexpr int kStreamWorkgroups = 8192;             // workgroups the streaming scan aims to launch at least
 constexpr int kMaxGridCells = 4096;  // entries of the quantiser's uniform-grid index (32 KB of LDS)
 
@@ -24,6 +22,27 @@ constexpr int kMaxGridCells = 4096;  // entries of the quantiser's uniform-grid 
 // lo = fp16(V - hi).  hi + lo equals V to about 2^-22 relative; the factor keeps lo in the normal
 // float16 range for every |v| > 2.4e-4 (below that lo is at most 6e-8 of v's scale).
 constexpr float kSplitScale = 1024.f;
+
+// Raises a kernel's dynamic-LDS limit where a launch needs more than the default.  The attribute belongs
+// to a (kernel, device) pair, so what has been set is remembered per device (one object per kernel);
+// two threads that race here both set it, which is harmless.
+class LdsLimit {
+  public:
+    hipError_t ensure(const void* kernel, size_t bytes) {
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return e;
+        if (dev < 0 || dev >= kDevices) return hipErrorInvalidDevice;
+        if (bytes <= set_[dev].load(std::memory_order_acquire)) return hipSuccess;
+        e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+        if (e == hipSuccess) set_[dev].store(bytes, std::memory_order_release);
+        return e;
+    }
+
+  private:
+    static constexpr int kDevices = 64;
+    std::atomic<size_t> set_[kDevices] = {};
+};
 
 inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
 inline int64_t round_up64(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
@@ -104,7 +123,8 @@ hipError_t launch_segment_hist(const int32_t* assign, int64_t n, int64_t seg_len
                                uint32_t* seg_hist, hipStream_t st);
 // in place: seg_hist[s][l] <- sum_{s'<s} seg_hist[s'][l];  batch_count[l] <- column total
 hipError_t launch_segment_scan(uint32_t* seg_hist, int nseg, int L, uint32_t* batch_count, hipStream_t st);
-// slot[i] = list_base[l] + (rank of row i among the batch rows of list l, in input order).
+// slot[i] = list_base[l] + (rank of row i among the batch rows of list l, in input order); slot and
+// list_base may be null when only the order is wanted.
 // order (may be null): the batch's rows grouped by list, lists ascending, input order inside a list:
 // order[batch_base[l] + rank] = i, with batch_base the exclusive running sum of the batch's rows per list.
 hipError_t launch_stable_rank(const int32_t* assign, int64_t n, int64_t seg_len, int nseg, int L,
@@ -128,9 +148,12 @@ hipError_t launch_gather_rows(const float* src, int d, const int64_t* idx, int64
 
 // ---- k-means pieces ---------------------------------------------------------------------------
 
-// sums[l][j] += x~_ij, counts[l] += 1 over rows with assign l (atomics); obj += best terms
-hipError_t launch_kmeans_accumulate(const float* x, int64_t n, int d, const int32_t* assign,
-                                    float* sums, int pitch, uint32_t* counts, hipStream_t st);
+// out[l] = sum of count[l'] over l' < l (L <= kMaxList)
+hipError_t launch_exclusive_scan(const uint32_t* count, int L, int64_t* out, hipStream_t st);
+// sums[l][j] = sum of x~_ij over the rows order[base[l] .. base[l] + count[l]) of cell l, added in a fixed
+// order (bit-reproducible); rows are normalised on the fly
+hipError_t launch_kmeans_cell_sums(const float* x, int d, const int32_t* order, const int64_t* base,
+                                   const uint32_t* count, int L, float* sums, int pitch, hipStream_t st);
 // cent[l] = sums[l]/counts[l] for non-empty cells; bias[l] = -|cent_l|^2/2 (padding rows: bias -inf)
 hipError_t launch_kmeans_update(float* cent, int pitch, const float* sums, const uint32_t* counts,
                                 float* bias, int L, int Lpad, int d, hipStream_t st);

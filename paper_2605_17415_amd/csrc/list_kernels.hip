@@ -91,9 +91,9 @@ __global__ __launch_bounds__(64) void k_stable_rank(const int32_t* __restrict__ 
         uint32_t base = 0;
         if (key >= 0) {
             base = cnt[key];
-            slot[i] = list_base[key] + (int64_t)(base + lower);
+            if (slot) slot[i] = list_base[key] + (int64_t)(base + lower);
             if (order) order[batch_base[key] + (int64_t)(base + lower)] = (int32_t)i;
-        } else if (i < end) {
+        } else if (i < end && slot) {
             slot[i] = -1;
         }
         __syncthreads();
@@ -154,22 +154,63 @@ __global__ void k_fill_u32(uint32_t* p, int64_t n, uint32_t v) {
 
 // ---- k-means ------------------------------------------------------------------------------------
 
-// One wavefront per row: normalise and add into the cell's running sum.
-__global__ __launch_bounds__(256) void k_kmeans_accumulate(const float* __restrict__ x, int64_t n, int d,
-                                                           const int32_t* __restrict__ assign,
-                                                           float* __restrict__ sums, int pitch,
-                                                           uint32_t* __restrict__ counts) {
-    const int lane = threadIdx.x & 63;
-    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (row >= n) return;
-    const int a = assign[row];
-    if (a < 0) return;
-    float n2 = 0.f;
-    for (int j = lane; j < d; j += 64) { const float v = x[row * d + j]; n2 += v * v; }
-    for (int o = 32; o > 0; o >>= 1) n2 += __shfl_xor(n2, o);
-    const float nrm = sqrtf(n2);
-    for (int j = lane; j < d; j += 64) atomicAdd(&sums[(int64_t)a * pitch + j], x[row * d + j] / nrm);
-    if (lane == 0) atomicAdd(&counts[a], 1u);
+// out[l] = sum of count[l'] over l' < l, for up to 16384 entries, by one workgroup.
+__global__ __launch_bounds__(1024) void k_exclusive_scan(const uint32_t* __restrict__ count, int L,
+                                                         int64_t* __restrict__ out) {
+    __shared__ int64_t part[1024];
+    const int per = (L + 1023) / 1024;
+    const int lo = threadIdx.x * per < L ? threadIdx.x * per : L;
+    const int hi = lo + per < L ? lo + per : L;
+    int64_t sum = 0;
+    for (int l = lo; l < hi; ++l) sum += count[l];
+    part[threadIdx.x] = sum;
+    __syncthreads();
+    for (int o = 1; o < 1024; o <<= 1) {            // inclusive running sum over the 1024 parts
+        const int64_t add = threadIdx.x >= o ? part[threadIdx.x - o] : 0;
+        __syncthreads();
+        part[threadIdx.x] += add;
+        __syncthreads();
+    }
+    int64_t run = part[threadIdx.x] - sum;
+    for (int l = lo; l < hi; ++l) { out[l] = run; run += count[l]; }
+}
+
+// Sum of the normalised rows of each cell, in a fixed order: workgroup l walks the rows
+// order[base[l] .. base[l] + count[l]) of its cell, wavefront w taking every fourth row from the w-th on,
+// a lane the coordinates lane, lane + 64, ...; the four partial sums are then added in the order 0, 1, 2, 3.
+// Nothing depends on scheduling, so the same input gives the same bits on every run.
+__global__ __launch_bounds__(256) void k_kmeans_cell_sums(const float* __restrict__ x, int d,
+                                                          const int32_t* __restrict__ order,
+                                                          const int64_t* __restrict__ base,
+                                                          const uint32_t* __restrict__ count,
+                                                          float* __restrict__ sums, int pitch) {
+    __shared__ float part[4][kMaxD];
+    const int l = blockIdx.x, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int64_t first = base[l];
+    const int cnt = (int)count[l];
+    float acc[kMaxD / 64];
+#pragma unroll
+    for (int t = 0; t < kMaxD / 64; ++t) acc[t] = 0.f;
+    for (int p = wave; p < cnt; p += 4) {
+        const float* row = x + (int64_t)order[first + p] * d;
+        float v[kMaxD / 64];
+        float n2 = 0.f;
+#pragma unroll
+        for (int t = 0; t < kMaxD / 64; ++t) {
+            const int j = lane + 64 * t;
+            v[t] = j < d ? row[j] : 0.f;
+            n2 += v[t] * v[t];
+        }
+        for (int o = 32; o > 0; o >>= 1) n2 += __shfl_xor(n2, o);
+        const float nrm = sqrtf(n2);
+#pragma unroll
+        for (int t = 0; t < kMaxD / 64; ++t) acc[t] += v[t] / nrm;
+    }
+#pragma unroll
+    for (int t = 0; t < kMaxD / 64; ++t) part[wave][lane + 64 * t] = acc[t];
+    __syncthreads();
+    for (int j = threadIdx.x; j < d; j += 256)
+        sums[(int64_t)l * pitch + j] = ((part[0][j] + part[1][j]) + part[2][j]) + part[3][j];
 }
 
 __global__ __launch_bounds__(64) void k_kmeans_update(float* __restrict__ cent, int pitch,
@@ -341,10 +382,16 @@ hipError_t launch_fill_u32(uint32_t* p, int64_t n, uint32_t v, hipStream_t st) {
     return hipGetLastError();
 }
 
-hipError_t launch_kmeans_accumulate(const float* x, int64_t n, int d, const int32_t* assign,
-                                    float* sums, int pitch, uint32_t* counts, hipStream_t st) {
-    hipLaunchKernelGGL(k_kmeans_accumulate, dim3((unsigned)((n + 3) / 4)), dim3(256), 0, st, x, n, d,
-                       assign, sums, pitch, counts);
+hipError_t launch_exclusive_scan(const uint32_t* count, int L, int64_t* out, hipStream_t st) {
+    if (L < 1 || L > kMaxList) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(k_exclusive_scan, dim3(1), dim3(1024), 0, st, count, L, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_kmeans_cell_sums(const float* x, int d, const int32_t* order, const int64_t* base,
+                                   const uint32_t* count, int L, float* sums, int pitch, hipStream_t st) {
+    if (d > kMaxD) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(k_kmeans_cell_sums, dim3(L), dim3(256), 0, st, x, d, order, base, count, sums, pitch);
     return hipGetLastError();
 }
 

@@ -70,9 +70,6 @@ __global__ __launch_bounds__(256) void k_cand_offsets(const int32_t* __restrict_
 // reads its packed words with 256-byte-per-wavefront coalesced loads and sums d table entries.
 // When the table would not fit LDS (large b and d) DIRECT keeps z and C separately and multiplies
 // per coordinate instead.
-#ifndef IVFTQ_SCAN_WU
-#define IVFTQ_SCAN_WU 8
-#endif
 template <int B, bool DIRECT>
 __global__ __launch_bounds__(256) void k_list_scan(const float* __restrict__ z, int z_pitch, int d,
                                                    const float* __restrict__ cb,
@@ -124,7 +121,7 @@ __global__ __launch_bounds__(256) void k_list_scan(const float* __restrict__ z, 
         float acc = 0.f;
         if constexpr (32 % B == 0) {
             constexpr int per = 32 / B;
-            constexpr int WU = IVFTQ_SCAN_WU;  // words fetched together: their latency overlaps
+            constexpr int WU = 8;  // words fetched together: their latency overlaps
             for (int w0 = 0; w0 < words; w0 += WU) {
                 uint32_t wd[WU];
 #pragma unroll

@@ -6,8 +6,11 @@ Agreement is defined as:
     cases are counted and reported;
   * when the residual is tiny the float32 rounding of x~ (relative 2^-24 per coordinate, about
     6e-9 absolute) is magnified by 1/gamma in the unit residual, so the boundary tolerance of a row
-    is max(1e-5, 4e-7/gamma): it only exceeds 1e-5 for gamma < 0.04, i.e. a vector that nearly
-    coincides with its centroid, whose residual direction is rounding noise in any precision;
+    is max(1e-5, 4e-7/gamma), capped at 1e-3: it only exceeds 1e-5 for gamma < 0.04, i.e. a vector
+    that nearly coincides with its centroid.  Below gamma = 4e-4 (where the cap would bind) the residual
+    is within a thousand roundings of zero and its direction is noise in any precision: the codes of
+    such a row are not compared, only its norm (to 4e-7 absolute).  Both kinds of row are counted, their
+    share of the rows is printed, and a comparison fails when it exceeds EXCUSED_ROWS_MAX;
   * the float16 norm is bit-exact unless the double-precision norm sits within 2e-6 (relative) of
     the midpoint between two neighbouring float16 values, where float32 and float64 may round apart,
     or the norm itself is at the float32 noise floor (a vector that coincides with its centroid: the
@@ -23,6 +26,9 @@ BOUNDARY_TOL = 1e-5
 SCORE_RTOL = 1e-4
 SCORE_ATOL = 1e-6
 NOISE_FLOOR = 4e-7     # absolute float32 rounding noise of a normalised coordinate, with margin
+ROW_TOL_CAP = 1e-3     # no row's boundary tolerance is wider than this ...
+DEGENERATE_GAMMA = NOISE_FLOOR / ROW_TOL_CAP   # ... a residual norm below this (4e-4) has no direction to compare
+EXCUSED_ROWS_MAX = 2e-3   # largest share of rows that may fall under the widened rule (plus 2 rows for small cases)
 
 
 def compare_encode(enc, g_assign, g_codes, g_gamma16):
@@ -37,9 +43,10 @@ def compare_encode(enc, g_assign, g_codes, g_gamma16):
     report = dict(rows=n, assign_near_tie_mismatch=len(a_bad),
                   assign_near_tie_total=int(np.sum(enc["gap"] < BOUNDARY_TOL)))
     if g_codes is not None:
-        diff = (g_codes != enc["codes"]) & same[:, None]
+        degenerate = enc["gamma"] < DEGENERATE_GAMMA
+        diff = (g_codes != enc["codes"]) & (same & ~degenerate)[:, None]
         rows, cols = np.nonzero(diff)
-        row_tol = np.maximum(BOUNDARY_TOL, NOISE_FLOOR / np.maximum(enc["gamma"], 1e-300))
+        row_tol = np.minimum(ROW_TOL_CAP, np.maximum(BOUNDARY_TOL, NOISE_FLOOR / np.maximum(enc["gamma"], 1e-300)))
         far = enc["bdist"][rows, cols] >= row_tol[rows]
         assert not np.any(far), (f"{int(far.sum())} codes differ away from a decision boundary, first at "
                                  f"row {rows[far][0]} coord {cols[far][0]}")
@@ -48,14 +55,19 @@ def compare_encode(enc, g_assign, g_codes, g_gamma16):
         assert np.all(step[regular] <= 1), "a near-boundary code differs by more than one bin"
         report["code_near_boundary_mismatch"] = int(np.sum(regular))
         report["code_near_boundary_total"] = int(np.sum(enc["bdist"] < BOUNDARY_TOL))
-        report["tiny_residual_rows"] = int(np.sum(row_tol > BOUNDARY_TOL))
+        report["tiny_residual_rows"] = int(np.sum((row_tol > BOUNDARY_TOL) & ~degenerate))
         report["tiny_residual_code_mismatch"] = int(np.sum(~regular))
+        report["degenerate_rows"] = int(np.sum(degenerate))
+        excused = report["tiny_residual_rows"] + report["degenerate_rows"]
+        report["widened_rule_share"] = excused / max(n, 1)
+        assert excused <= 2 + EXCUSED_ROWS_MAX * n, \
+            f"{excused} of {n} rows fall under the widened tolerance for tiny residuals: too many to excuse"
     if g_gamma16 is not None:
         g = np.asarray(g_gamma16).view(np.float16) if g_gamma16.dtype != np.float16 else g_gamma16
         bad = np.flatnonzero((g.view(np.uint16) != enc["gamma16"].view(np.uint16)) & same)
         for i in bad:
             lo, hi = sorted((float(g[i]), float(enc["gamma16"][i])))
-            if abs(float(g[i]) - enc["gamma"][i]) <= NOISE_FLOOR:
+            if enc["gamma"][i] < DEGENERATE_GAMMA and abs(float(g[i]) - enc["gamma"][i]) <= NOISE_FLOOR:
                 continue                                   # a norm at the rounding-noise floor
             assert abs(int(g[i].view(np.uint16)) - int(enc["gamma16"][i].view(np.uint16))) == 1, \
                 f"float16 norm of row {i} off by more than one step"

@@ -24,10 +24,11 @@ def _make_index(cs):
     ix = _pkg().Index(cs.d, cs.b_stage1, cs.nlist, sign_bit=cs.sign_bit)
     ix.set_coarse(cs.cent)
     ix.set_rotation(cs.Pi)
-    # the library's own (b, d) codebook must be the oracle's
+    # the library's own (b, d) codebook must be the oracle's, bit for bit: both sides quantise against
+    # the same float32 boundaries and reconstruct from the same float32 levels
     c, tau = ix.get_codebook()
-    np.testing.assert_allclose(c, cs.c, rtol=0, atol=2e-8)
-    np.testing.assert_allclose(tau, cs.tau, rtol=0, atol=2e-8)
+    np.testing.assert_array_equal(c, cs.c.astype(np.float32))
+    np.testing.assert_array_equal(tau, cs.tau.astype(np.float32))
     return ix
 
 

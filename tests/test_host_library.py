@@ -40,6 +40,10 @@ def test_codebook_matches_oracle(b, d):
     assert c.dtype == np.float32 and c.shape == (1 << b,) and tau.shape == ((1 << b) - 1,)
     np.testing.assert_allclose(c, oc, rtol=6e-8, atol=2e-8)       # float32 rounding of a float64 value
     np.testing.assert_allclose(tau, otau, rtol=6e-8, atol=2e-8)
+    # ... and the float32 tables both sides work with are the same bits
+    oc32, otau32 = orc.codebook_fp32(b, d)
+    np.testing.assert_array_equal(c, oc32)
+    np.testing.assert_array_equal(tau, otau32)
     assert np.all(np.diff(c) > 0)
     assert tau[len(tau) // 2] == 0.0                        # the middle boundary is exactly zero
     np.testing.assert_array_equal(c, -c[::-1])
@@ -90,12 +94,12 @@ def test_own_rotation_is_orthogonal_and_seeded():
 def test_create_rejects_bad_arguments_before_touching_a_device():
     lib = pkg.load_library()
     h = ctypes.c_void_p()
-    assert lib.ivftq_create(64, 0, 8, 0, ctypes.byref(h)) == 1       # b out of range
-    assert lib.ivftq_create(4, 4, 8, 0, ctypes.byref(h)) == 1        # d too small
-    assert lib.ivftq_create(64, 4, 0, 0, ctypes.byref(h)) == 1       # nlist too small
-    assert lib.ivftq_create(64, 4, 8, 0, None) == 1                  # NULL out pointer
-    assert lib.ivftq_create(4096, 4, 8, 0, ctypes.byref(h)) == 6     # d beyond the limit
-    assert lib.ivftq_create(64, 4, 1 << 20, 0, ctypes.byref(h)) == 6 # nlist beyond the limit
+    assert lib.ivftq_create(64, 0, 8, 0, None, None, None, ctypes.byref(h)) == 1       # b out of range
+    assert lib.ivftq_create(4, 4, 8, 0, None, None, None, ctypes.byref(h)) == 1        # d too small
+    assert lib.ivftq_create(64, 4, 0, 0, None, None, None, ctypes.byref(h)) == 1       # nlist too small
+    assert lib.ivftq_create(64, 4, 8, 0, None, None, None, None) == 1                  # NULL out pointer
+    assert lib.ivftq_create(4096, 4, 8, 0, None, None, None, ctypes.byref(h)) == 6     # d beyond the limit
+    assert lib.ivftq_create(64, 4, 1 << 20, 0, None, None, None, ctypes.byref(h)) == 6 # nlist beyond the limit
     assert not h.value
     assert lib.ivftq_ntotal(None) == -1
     assert lib.ivftq_destroy(None) == 0
@@ -136,7 +140,7 @@ def test_refined_codebook_matches_oracle_and_its_grid_counts_exactly(b, d):
     lv, bd = pkg.ivftq_build_refined_codebook(b, d)
     olv, obd = orc.refined_codebook_fp32(b, d)
     np.testing.assert_array_equal(bd, obd)                  # float32 Stage-1 centroids and boundaries, interleaved
-    np.testing.assert_allclose(lv, olv, rtol=6e-8, atol=2e-8)
+    np.testing.assert_array_equal(lv, olv)                  # the same float32 levels, bit for bit
     assert np.all(np.diff(bd) > 0) and np.all(np.diff(lv) > 0)
     c, tau = pkg.ivftq_build_codebook(b, d)
     np.testing.assert_array_equal(bd[0::2], c)
@@ -164,3 +168,29 @@ def test_coarsened_codebook_matches_oracle(b, d, beta, sign_bit):
         pkg.ivftq_build_coarsened_codebook(b, d, b + 1, sign_bit)
     with pytest.raises(pkg.IvftqError):
         pkg.ivftq_build_coarsened_codebook(b, d, 0, sign_bit)
+
+
+def test_create_reports_oom_when_the_allocator_callback_refuses():
+    """No device is touched before the first allocation, so this runs without a GPU: a callback that
+    returns NULL gives IVFTQ_OOM and no handle; giving only one of the two callbacks is an argument error."""
+    lib = pkg.load_library()
+    calls = []
+
+    def refuse(nbytes, ctx):
+        calls.append(int(nbytes))
+        return None
+
+    freed = []
+    alloc_cb = pkg.ALLOC_FN(refuse)
+    free_cb = pkg.FREE_FN(lambda p, ctx: freed.append(p))
+    handle = ctypes.c_void_p(12345)
+    status = lib.ivftq_create(96, 4, 64, 1, ctypes.cast(alloc_cb, ctypes.c_void_p), ctypes.cast(free_cb, ctypes.c_void_p),
+                              None, ctypes.byref(handle))
+    assert status == pkg.binding.OOM and handle.value is None
+    assert len(calls) == 1 and calls[0] == 64 * 96 * 4 and freed == []
+    assert b"memory" in lib.ivftq_last_error().lower() or len(lib.ivftq_last_error()) > 0
+    status = lib.ivftq_create(96, 4, 64, 1, ctypes.cast(alloc_cb, ctypes.c_void_p), None, None, ctypes.byref(handle))
+    assert status == pkg.binding.INVALID_ARG and handle.value is None
+    with pytest.raises(pkg.IvftqError) as e:
+        pkg.Index(96, 4, 64, allocator=(alloc_cb, free_cb))
+    assert e.value.status == pkg.binding.OOM
