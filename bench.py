@@ -6,12 +6,15 @@ One step = one pass of the whole hot path over one batch of synthetic input:
                 (normalise, coarse assignment, residual rotation, quantise, pack, list append)
   search half : ivftq_search of the query batch (coarse scoring, probe selection, query rotation,
                 list scan, top-k)
-on the 1M x 128 workload (1,000-component Gaussian mixture, nlist=1024 trained on a 100k sample,
-b=4, 10,000 queries, k=10).  Inputs are resident in device memory before the timed region.
+The default workload is the 10M x 96 one (4,096-component anisotropic mixture of unit vectors,
+nlist=4096 trained on a 500k sample, b=4, 10,000 queries, k=10, nprobe 32): the shape of the
+paper's 10M image-descriptor runs (table "Recall@10 on million-scale benchmarks", Section
+"Streaming ingestion at scale").  Inputs are resident in device memory before the timed region.
 
 Prints ONE JSON line.  `value` is search QPS at the primary nprobe; encode vectors/s, recall@10,
 the nprobe sweep, the roofline of the dominant kernel and the CPU oracle's throughput on a bounded
-sample ride along in the same object.
+sample ride along in the same object, and so do (default run only) the same measurement on the
+10M x 200 workload (k=100, shifted queries, nprobe 64) and a search on unclustered input.
 """
 from __future__ import annotations
 
@@ -30,6 +33,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_F16_PEAK_TFLOPS = 2500.0  # dense fp16 matrix peak: the contractions run on the fp16 pipe
 SPLIT_PASSES = 3               # each product is issued as hi*hi + hi*lo + lo*hi (fp32-accurate)
+DTYPE = "f16-split products, f32 accumulate (f32-accurate)"
 
 
 def exact_ground_truth(torch, xd, qd, k, q_chunk=1000, x_chunk=1 << 20):
@@ -53,16 +57,17 @@ def exact_ground_truth(torch, xd, qd, k, q_chunk=1000, x_chunk=1 << 20):
     return torch.cat(out).cpu().numpy()
 
 
-def stored_traffic(kernel: str, nprobe: int):
-    """HBM-side bytes per launch of `kernel`, as measured by the rocprofv3 --pmc runs whose summary
-    is committed under profiles/ (FETCH_SIZE and WRITE_SIZE, scaled by a plain copy); None if that
-    summary does not cover this kernel and nprobe."""
-    path = os.path.join(ROOT, "profiles", f"{kernel}_1m_d128_nprobe{nprobe}_traffic.txt")   # 1M workload only
+def stored_traffic(workload: str, nprobe: int, kernel: str):
+    """HBM-side bytes per launch of `kernel` on `workload`, from the committed summary of the two
+    rocprofv3 --pmc runs of this very command (FETCH_SIZE, then WRITE_SIZE, each scaled by what the
+    same counter reads for a plain copy of known size): profiles/hbm_traffic_<workload>_nprobe<N>.txt,
+    lines `<kernel class> <bytes per launch>`.  None when that run has not been summarised."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}_nprobe{nprobe}.txt")
     if not os.path.exists(path):
         return None
     for line in open(path):
         parts = line.split()
-        if len(parts) == 2 and parts[0] == "traffic_bytes":
+        if len(parts) == 2 and parts[0] == kernel:
             return float(parts[1])
     return None
 
@@ -74,36 +79,67 @@ def recall(found, truth):
     return hits / truth.size
 
 
+def host_description():
+    model = "unknown"
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.lower().startswith("model name"):
+                model = line.split(":", 1)[1].strip()
+                break
+    except OSError:
+        pass
+    try:
+        usable = len(os.sched_getaffinity(0))
+    except AttributeError:
+        usable = os.cpu_count() or 1
+    return model, os.cpu_count() or 1, usable
+
+
 def cpu_baseline(w, X, Q, nprobe, full_cand_per_query):
-    """The oracle, as it stands, on a bounded sample of the same workload (host cores)."""
+    """The oracle, as it stands, on a bounded sample of the same workload, on the host's cores: once with
+    the thread pool numpy's BLAS brings up by itself, once held to one thread."""
+    from threadpoolctl import threadpool_info, threadpool_limits
+
     from oracle import ivftq_oracle as orc
     from workloads import synth
-    try:
-        from threadpoolctl import threadpool_info
-        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
-    except Exception:
-        threads = 1
-    n_s, q_s = 500_000, 3000
-    Xs = X[:n_s]
-    cent, _ = orc.train_coarse(Xs[:20_000], w.nlist, 2, synth.kmeans_init_indices(w.seed, 20_000, w.nlist))
+    model, nproc, usable = host_description()
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    n_s = min(len(X), 4 << 18)                                   # 1,048,576 rows
+    q_s = min(len(Q), 1000)
+    n_1, q_1 = min(n_s, 1 << 16), min(q_s, 100)                  # the single-thread leg: 65,536 rows, 100 queries
+    train = min(n_s, 40_000)
+    cent, _ = orc.train_coarse(X[:train], w.nlist, 1, synth.kmeans_init_indices(w.seed, train, w.nlist))
     Pi = orc.haar_rotation_from_gaussian(synth.gaussian_matrix(w.seed, w.d))
     c, tau = orc.lloyd_max_codebook(w.b, w.d)
     idx = orc.ListIndex(cent, Pi, c, tau)
     t0 = time.perf_counter()
-    idx.add(Xs)
+    idx.add(X[:n_s])
     t_enc = time.perf_counter() - t0
     t0 = time.perf_counter()
     _, _, probes, _ = orc.search(idx, Q[:q_s], nprobe, w.k)
     t_search = time.perf_counter() - t0
     scanned = sum(len(idx.ids[l]) for row in probes for l in row)
-    cand_per_s = scanned / t_search
+    with threadpool_limits(limits=1):
+        one = orc.ListIndex(cent, Pi, c, tau)
+        t0 = time.perf_counter()
+        one.add(X[:n_1])
+        t_enc1 = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        _, _, probes1, _ = orc.search(idx, Q[:q_1], nprobe, w.k)
+        t_search1 = time.perf_counter() - t0
+    scanned1 = sum(len(idx.ids[l]) for row in probes1 for l in row)
     return {
-        "value": cand_per_s / full_cand_per_query, "unit": "queries/s", "cores": int(threads), "kind": "oracle",
-        "sample": (f"oracle index over the first {n_s} database rows (own 2-iteration k-means, nlist={w.nlist}), "
-                   f"{q_s} queries at nprobe={nprobe}: {scanned} candidates scored in {t_search:.2f}s; rate scaled "
-                   f"to the {full_cand_per_query:.0f} candidates/query of the full index"),
+        "value": scanned / t_search / full_cand_per_query, "unit": "queries/s", "cores": int(threads), "kind": "oracle",
+        "sample": (f"oracle index over the first {n_s} rows of the workload (own 1-iteration k-means on {train} rows, "
+                   f"nlist={w.nlist}), {q_s} queries at nprobe={nprobe}: {scanned} candidates scored in {t_search:.2f}s; "
+                   f"rate scaled to the {full_cand_per_query:.0f} candidates/query of the full index"),
         "encode_vectors_per_s": n_s / t_enc,
         "encode_sample": f"oracle encode+append of {n_s} rows in {t_enc:.2f}s",
+        "single_thread": {"value": scanned1 / t_search1 / full_cand_per_query, "unit": "queries/s",
+                          "encode_vectors_per_s": n_1 / t_enc1,
+                          "sample": f"{q_1} queries in {t_search1:.2f}s, encode of {n_1} rows in {t_enc1:.2f}s, BLAS pool held to 1 thread"},
+        "cpu_model": model, "nproc": nproc, "usable_cpus": usable,
+        "note": "numpy float64; the threads are those of numpy's BLAS pool (matrix products), the rest of the oracle is single-threaded",
     }
 
 
@@ -176,11 +212,11 @@ def run_streaming(args, torch, pkg, synth):
     total = ix.ntotal()
     ix.close()
     rate = [bs / (ms * 1e-3) for ms in insert_ms]
-    out = {
+    return {
         "metric": f"streaming insert vectors/s (100k-row batches, no retraining) + recall@10 drift (nprobe={nprobe}, k={w.k})",
         "value": float(np.mean(rate)) if rate else None, "unit": "vectors/s", "n_gpus": 1, "steps": nb, "warmup": 0,
         "ms_per_step": float(np.mean(insert_ms)) if insert_ms else None, "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f16-split products, f32 accumulate (f32-accurate)", "data": "synthetic",
+        "vs_baseline": None, "dtype": DTYPE, "data": "synthetic",
         "config": {"workload": f"streaming ingest: {w.d}-d unit-norm mixture, nlist={w.nlist} trained on the first {n0} rows, "
                                f"{nb} batches of {bs}, b={w.b}, {w.nq} queries after every batch", "nprobe": nprobe, "k": w.k},
         "initial_encode_vectors_per_s": n0 / (first_ms * 1e-3), "ntotal": int(total),
@@ -192,54 +228,23 @@ def run_streaming(args, torch, pkg, synth):
         "search_qps_last": w.nq / (search_ms[-1] * 1e-3) if search_ms else None,
         "wall_s": time.perf_counter() - t0,
     }
-    print(json.dumps(out))
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=5)
-    ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--nprobe", type=int, default=None, help="primary nprobe (default: 32, or the workload's second value)")
-    ap.add_argument("--workload", default="1m", choices=["1m", "10m_d96", "10m_d200", "stream_d96"],
-                    help="1m is the benchmark workload; the 10M ones are for scale checks; stream_d96 is the "
-                         "streaming-ingest run (1M rows, then 100k-row batches)")
-    ap.add_argument("--stream-batches", type=int, default=90)
-    ap.add_argument("--bits", type=int, default=4)
-    ap.add_argument("--sign-bit", action="store_true",
-                    help="store the sign-bit refinement as well (bits + 1 stored per coordinate; not the default workload)")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-sweep", action="store_true")
-    ap.add_argument("--copy-calibration", action="store_true",
-                    help="only run a plain 1 GiB device-to-device copy 5 times (reference for HBM byte counters)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py measures one GPU only: this build has no multi-GPU path (run with --gpus 1)",
-              file=sys.stderr)
-        sys.exit(2)
+def workload_label(w, key):
+    if key == "1m":
+        return "1M x 128 fp32, 1000-component Gaussian mixture, nlist=1024 (k-means on a 100k sample), b=4, 10000 queries, k=10"
+    if key == "10m_d96":
+        return (f"10M x 96 fp32 unit-norm, 4096-component anisotropic Gaussian mixture, nlist=4096 (k-means on a 500k sample), "
+                f"b={w.b}, 10000 queries, k=10")
+    if key == "10m_d200":
+        return ("10M x 200 fp32, 4096-component anisotropic Gaussian mixture, queries shifted by 0.5 sigma with twice the "
+                "variance, nlist=4096 (k-means on a 500k sample), b=4, 10000 queries, k=100")
+    return f"{w.name}: {w.n} x {w.d}, nlist={w.nlist}, b={w.b}, {w.nq} queries, k={w.k}"
 
-    import torch
 
-    import paper_2605_17415_amd as pkg
-    from workloads import synth
-
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
+def run_workload(torch, pkg, synth, key, w, nprobe, steps, warmup, sign_bit=False, extras=True, want_cpu=True):
+    """Times `steps` steps of the whole hot path on workload `w` and returns the result object."""
     dev = torch.device("cuda:0")
-    if args.copy_calibration:
-        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
-        dst = torch.empty_like(src)
-        for _ in range(5):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        print(json.dumps({"copy_bytes_read": 1 << 30, "copy_bytes_written": 1 << 30, "launches": 5}))
-        return
-    if args.workload == "stream_d96":
-        run_streaming(args, torch, pkg, synth)
-        return
-    w = {"1m": synth.config_1m, "10m_d96": lambda: synth.config_10m_d96(args.bits),
-         "10m_d200": synth.config_10m_d200}[args.workload]()
-    if args.nprobe is None:
-        args.nprobe = 32 if args.workload == "1m" else w.nprobe[1]
     t_setup = time.perf_counter()
     X = synth.database(w)
     Q = synth.queries(w)
@@ -254,32 +259,29 @@ def main():
     t_train = time.perf_counter() - t0
     cent = trainer.get_coarse()
     trainer.close()
+    del sample
     truth = exact_ground_truth(torch, xd, qd, w.k)
     torch.cuda.synchronize()
     t_setup = time.perf_counter() - t_setup
 
-    def new_index():
-        ix = pkg.Index(w.d, w.b, w.nlist, rotation_seed=w.seed, sign_bit=args.sign_bit)
-        ix.set_coarse(cent)
-        return ix
-
+    ix = pkg.Index(w.d, w.b, w.nlist, rotation_seed=w.seed, sign_bit=sign_bit)
+    ix.set_coarse(cent)
     scores = torch.empty((w.nq, w.k), dtype=torch.float32, device=dev)
     ids = torch.empty((w.nq, w.k), dtype=torch.int64, device=dev)
     ev = lambda: torch.cuda.Event(enable_timing=True)
 
-    def step(ix):
+    def step():
         a, b, c = ev(), ev(), ev()
         a.record()
         ix.encode_add(xd)
         b.record()
-        ix.search(qd, args.nprobe, w.k, out_scores=scores, out_ids=ids)
+        ix.search(qd, nprobe, w.k, out_scores=scores, out_ids=ids)
         c.record()
         return a, b, c
 
-    ix = new_index()
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         ix.reset()
-        step(ix)
+        step()
         torch.cuda.synchronize()
 
     def timed_steps(profile):
@@ -289,9 +291,9 @@ def main():
         ix.profile_enable(profile)
         torch.cuda.synchronize()
         wall0 = time.perf_counter()
-        for _ in range(args.steps):
+        for _ in range(steps):
             ix.reset()
-            a, b, c = step(ix)
+            a, b, c = step()
             torch.cuda.synchronize()
             enc.append(a.elapsed_time(b))
             sea.append(b.elapsed_time(c))
@@ -316,40 +318,41 @@ def main():
     vps = w.n / enc_t
 
     # algorithmic work
-    probe, _ = ix.coarse_probe(qd, args.nprobe)
+    probe, _ = ix.coarse_probe(qd, nprobe)
     probe = probe.cpu().numpy()
     sizes = np.array([ix.list_size(l) for l in range(w.nlist)], dtype=np.int64)
     per_probe = sizes[probe]                                   # [nq, nprobe] vectors behind each probe
     cand = per_probe.sum(axis=1)
-    stored_bits = w.b + (1 if args.sign_bit else 0)
+    stored_bits = w.b + (1 if sign_bit else 0)
     bytes_per_vec = (stored_bits * w.d + 7) // 8 + 2
     scan_bytes = float(cand.sum()) * bytes_per_vec             # every probed vector's codes + norm, once per query
     csum = np.cumsum(per_probe, axis=1)
-    first = np.minimum((csum < w.k).sum(axis=1) + 1, args.nprobe)      # probes the streaming pass covers
+    first = np.minimum((csum < w.k).sum(axis=1) + 1, nprobe)           # probes the dense pass covers at least
     stream_cand = float(np.take_along_axis(csum, (first - 1)[:, None], axis=1).sum())
     assign_flops = 2.0 * w.d * w.nlist * w.n
-    per_step = {k: v[0] / args.steps for k, v in prof.items()}
+    per_step = {k: v[0] / steps for k, v in prof.items()}
 
     def avg_ms(name):
         t = prof.get(name)
         return t[0] / t[1] if t and t[1] else None
+
+    # what a loop of nothing but the fp16 MFMA instruction reaches on this device: with constant operands
+    # (close to the nominal peak) and with random operand bits (the chip lowers its clock under real data)
+    mfma_const = pkg.ivftq_measure_mfma_rate(False)
+    mfma_random = pkg.ivftq_measure_mfma_rate(True)
 
     def mfma_roof(kernel, flops, passes=SPLIT_PASSES, dtype_note="f16 (3 split passes per product, f32 accumulate)"):
         ms = avg_ms(kernel)
         if not ms:
             return None
         r = {"kernel": kernel, "bound": "mfma", "achieved": flops / (ms * 1e-3) / 1e12, "peak": MFMA_F16_PEAK_TFLOPS,
-             "unit": "TFLOP/s", "traffic": stored_traffic(kernel, args.nprobe) if args.workload == "1m" else None, "algorithmic_flops_per_launch": flops, "avg_launch_ms": ms,
-             "mfma_dtype": dtype_note}
+             "unit": "TFLOP/s", "traffic": stored_traffic(key, nprobe, kernel) if not sign_bit else None,
+             "algorithmic_flops_per_launch": flops, "avg_launch_ms": ms, "mfma_dtype": dtype_note}
         r["frac"] = r["achieved"] / r["peak"]
         r["issued_frac"] = passes * r["frac"]            # share of the fp16 pipe's peak actually issued
         r["issued_vs_measured_pipe_rate"] = passes * r["achieved"] / mfma_random
         return r
 
-    # what a loop of nothing but the fp16 MFMA instruction reaches on this device: with constant operands
-    # (close to the nominal peak) and with random operand bits (the chip lowers its clock under real data)
-    mfma_const = pkg.ivftq_measure_mfma_rate(False)
-    mfma_random = pkg.ivftq_measure_mfma_rate(True)
     batched = "batch_scan" in prof
     # the assignment screens every row with one product and redoes the undecided rows with all three
     undecided = ix.assign_undecided() / float(w.n)
@@ -365,7 +368,7 @@ def main():
     else:
         ms = avg_ms("list_scan")
         r = {"kernel": "list_scan", "bound": "hbm", "achieved": scan_bytes / (ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
-             "unit": "GB/s", "traffic": stored_traffic("list_scan", args.nprobe),
+             "unit": "GB/s", "traffic": stored_traffic(key, nprobe, "list_scan"),
              "algorithmic_bytes_per_launch": scan_bytes, "avg_launch_ms": ms}
         r["frac"] = r["achieved"] / r["peak"]
         rooflines["list_scan"] = r
@@ -381,94 +384,85 @@ def main():
                   "algorithmic_bytes_per_step": scan_bytes, "ms_per_step": scan_stage_ms}
     scan_stage["frac"] = scan_stage["achieved"] / scan_stage["peak"]
 
-    sweep = []
-    if not args.no_sweep:
-        for npb in w.nprobe:
-            ts = []
-            for _ in range(3):
-                a, b = ev(), ev()
-                a.record()
-                ix.search(qd, npb, w.k, out_scores=scores, out_ids=ids)
-                b.record()
-                torch.cuda.synchronize()
-                ts.append(a.elapsed_time(b))
-            sweep.append({"nprobe": npb, "qps": w.nq / (float(np.median(ts)) / 1e3),
-                          "recall_at_10": recall(ids.cpu().numpy(), truth)})
-
-    # optional re-ranking on raw vectors: the 50 best by estimate re-scored exactly (reported, not the headline)
-    rerank_info = None
-    if not args.no_sweep and w.k <= 50:
-        r = 50
-        sc_r = torch.empty((w.nq, r), dtype=torch.float32, device=dev)
-        id_r = torch.empty((w.nq, r), dtype=torch.int64, device=dev)
+    def median_ms(fn, reps=3):
         ts = []
-        for _ in range(3):
+        for _ in range(reps):
             a, b = ev(), ev()
             a.record()
-            ix.search(qd, args.nprobe, r, out_scores=sc_r, out_ids=id_r)
-            _, rr_ids = pkg.ivftq_rerank(qd, xd, id_r, w.k)
+            fn()
             b.record()
             torch.cuda.synchronize()
             ts.append(a.elapsed_time(b))
-        rerank_info = {"candidates": r, "qps": w.nq / (float(np.median(ts)) / 1e3),
-                       "recall_at_10": recall(rr_ids.cpu().numpy(), truth),
-                       "note": "ivftq_search with k=50, then ivftq_rerank on the raw rows (kept by the caller)"}
+        return float(np.median(ts))
 
-    # the per-query streaming scan (what a small batch gets): its list scan against the HBM roofline
-    streaming_info = None
-    if not args.no_sweep:
+    sweep = []
+    for npb in w.nprobe:
+        ms = median_ms(lambda: ix.search(qd, npb, w.k, out_scores=scores, out_ids=ids))
+        sweep.append({"nprobe": npb, "qps": w.nq / (ms / 1e3), "recall_at_k": recall(ids.cpu().numpy(), truth)})
+
+    rerank_info = cascade_info = streaming_info = None
+    if extras:
+        # optional re-ranking on raw vectors: the 50 best by estimate re-scored exactly (reported, not the headline)
+        if w.k <= 50:
+            r = 50
+            sc_r = torch.empty((w.nq, r), dtype=torch.float32, device=dev)
+            id_r = torch.empty((w.nq, r), dtype=torch.int64, device=dev)
+            holder = {}
+
+            def rr():
+                ix.search(qd, nprobe, r, out_scores=sc_r, out_ids=id_r)
+                holder["ids"] = pkg.ivftq_rerank(qd, xd, id_r, w.k)[1]
+            ms = median_ms(rr)
+            rerank_info = {"candidates": r, "qps": w.nq / (ms / 1e3), "recall_at_k": recall(holder["ids"].cpu().numpy(), truth),
+                           "note": "ivftq_search with k=50, then ivftq_rerank on the raw rows (kept by the caller)"}
+
+        # the per-query streaming scan (what a small batch gets): its list scan against the HBM roofline
         nq_s = min(256, w.nq)
         qs = qd[:nq_s].contiguous()
         ix.set_search_mode(1)
         for _ in range(2):
-            ix.search(qs, args.nprobe, w.k)
+            ix.search(qs, nprobe, w.k)
         torch.cuda.synchronize()
-        ix.profile_enable(True); ix.profile_read()
+        ix.profile_enable(True)
+        ix.profile_read()
         a, b = ev(), ev()
         a.record()
         for _ in range(5):
-            ix.search(qs, args.nprobe, w.k)
+            ix.search(qs, nprobe, w.k)
         b.record()
         torch.cuda.synchronize()
-        ps = ix.profile_read(); ix.profile_enable(False)
+        ps = ix.profile_read()
+        ix.profile_enable(False)
         ix.set_search_mode(0)
         ls_ms = ps["list_scan"][0] / ps["list_scan"][1]
         bytes_s = float(cand[:nq_s].sum()) * bytes_per_vec
         streaming_info = {"nq": nq_s, "qps": nq_s / (a.elapsed_time(b) / 5 / 1e3), "list_scan_ms": ls_ms,
                           "roofline": {"kernel": "list_scan", "bound": "hbm", "achieved": bytes_s / (ls_ms * 1e-3) / 1e9,
                                        "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": bytes_s / (ls_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                                       "algorithmic_bytes_per_launch": bytes_s, "traffic": None},
+                                       "algorithmic_bytes_per_launch": bytes_s,
+                                       "traffic": stored_traffic(key, nprobe, "list_scan_streaming")},
                           "note": "ivftq_set_search_mode(1): one workgroup group per (query, probed list), every candidate's "
                                   "packed codes and norm streamed once per query"}
 
-    # cascade search (top bits first, 100 kept, full codes second): reported, not the headline
-    cascade_info = None
-    if not args.no_sweep and w.k <= 100 and w.b >= 2:
-        beta, keep = w.b - 1, min(2048, max(100, 4 * w.k))
-        ts = []
-        for _ in range(3):
-            a, b = ev(), ev()
-            a.record()
-            _, c_ids = ix.search_cascade(qd, args.nprobe, w.k, beta, keep)
-            b.record()
-            torch.cuda.synchronize()
-            ts.append(a.elapsed_time(b))
-        cascade_info = {"beta": beta, "n_keep": keep, "qps": w.nq / (float(np.median(ts)) / 1e3),
-                        "recall_at_10": recall(c_ids.cpu().numpy(), truth),
-                        "note": "pass 1 on the top beta Stage-1 bits with the coarsened codebook, pass 2 on the stored codes; "
-                                "the packed layout is not bit-sliced, so pass 1 streams the same bytes as the plain scan"}
+        # cascade search (top bits first, a shortlist kept, full codes second): reported, not the headline
+        if w.k <= 100 and w.b >= 2:
+            beta, keep = w.b - 1, min(2048, max(100, 4 * w.k))
+            holder = {}
+
+            def cs():
+                holder["ids"] = ix.search_cascade(qd, nprobe, w.k, beta, keep)[1]
+            ms = median_ms(cs)
+            cascade_info = {"beta": beta, "n_keep": keep, "qps": w.nq / (ms / 1e3),
+                            "recall_at_k": recall(holder["ids"].cpu().numpy(), truth)}
 
     out = {
-        "metric": f"search QPS at recall@10 (nprobe={args.nprobe}, k={w.k}) + encode vectors/s",
-        "value": qps, "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": wall / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f16-split products, f32 accumulate (f32-accurate)", "data": "synthetic",
-        "config": {"workload": ("1M x 128 fp32, 1000-component Gaussian mixture, nlist=1024 (k-means on a 100k "
-                                "sample), b=4, 10000 queries, k=10") if args.workload == "1m" else
-                               f"{w.name}: {w.n} x {w.d}, nlist={w.nlist}, b={w.b}, {w.nq} queries, k={w.k}",
-                   "nprobe": args.nprobe, "n": w.n, "d": w.d,
-                   "nlist": w.nlist, "b": w.b, "sign_bit": bool(args.sign_bit), "nq": w.nq, "k": w.k},
-        "recall_at_10": rec,
+        "metric": f"search QPS at recall@{w.k} (nprobe={nprobe}, k={w.k}) + encode vectors/s",
+        "value": qps, "unit": "queries/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": wall / steps * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": DTYPE, "data": "synthetic",
+        "config": {"workload": workload_label(w, key), "nprobe": nprobe, "n": w.n, "d": w.d,
+                   "nlist": w.nlist, "b": w.b, "sign_bit": bool(sign_bit), "nq": w.nq, "k": w.k},
+        "recall_at_k": rec,
         "search_ms": search_t * 1e3, "encode_ms": enc_t * 1e3, "encode_vectors_per_s": vps,
         "candidates_per_query": float(cand.mean()),
         "index_bytes": ix.index_bytes(),
@@ -481,9 +475,112 @@ def main():
         "sweep": sweep, "rerank": rerank_info, "cascade": cascade_info, "streaming_scan": streaming_info,
         "setup_s": t_setup, "train_coarse_s": t_train,
     }
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, X, Q, args.nprobe, float(cand.mean()))
     ix.close()
+    del xd, qd
+    torch.cuda.empty_cache()
+    if want_cpu:
+        out["cpu_baseline"] = cpu_baseline(w, X, Q, nprobe, float(cand.mean()))
+    return out
+
+
+def run_unclustered(torch, pkg, n, d, nlist, b, nq, nprobe, k, seed=42):
+    """Search time on input with no cluster structure at all (every coordinate i.i.d. Gaussian, drawn on the
+    device): the batched scan's threshold pass then lets many more candidates through than on a mixture.
+    Timing only; results are checked against exact ground truth for recall."""
+    dev = torch.device("cuda:0")
+    g = torch.Generator(device=dev)
+    g.manual_seed(seed)
+    xd = torch.randn((n, d), generator=g, device=dev, dtype=torch.float32)
+    qd = torch.randn((nq, d), generator=g, device=dev, dtype=torch.float32)
+    ix = pkg.Index(d, b, nlist, rotation_seed=seed)
+    sample = xd[:: max(1, n // 500_000)][:500_000].contiguous()
+    ix.train_coarse(sample, 10, seed=seed)
+    del sample
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    a0, a1 = ev(), ev()
+    a0.record()
+    ix.encode_add(xd)
+    a1.record()
+    scores = torch.empty((nq, k), dtype=torch.float32, device=dev)
+    ids = torch.empty((nq, k), dtype=torch.int64, device=dev)
+    for _ in range(2):
+        ix.search(qd, nprobe, k, out_scores=scores, out_ids=ids)
+    torch.cuda.synchronize()
+    ts = []
+    for _ in range(5):
+        a, bb = ev(), ev()
+        a.record()
+        ix.search(qd, nprobe, k, out_scores=scores, out_ids=ids)
+        bb.record()
+        torch.cuda.synchronize()
+        ts.append(a.elapsed_time(bb))
+    truth = exact_ground_truth(torch, xd, qd, k)
+    out = {"workload": f"{n} x {d} i.i.d. Gaussian rows (no clusters), nlist={nlist}, b={b}, {nq} queries, nprobe={nprobe}, k={k}",
+           "search_ms": float(np.median(ts)), "qps": nq / (float(np.median(ts)) / 1e3),
+           "encode_ms_first_call": a0.elapsed_time(a1), "recall_at_k": recall(ids.cpu().numpy(), truth)}
+    ix.close()
+    del xd, qd
+    torch.cuda.empty_cache()
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--nprobe", type=int, default=None, help="primary nprobe (default: the workload's second value, 32 for 1m and 10m_d96)")
+    ap.add_argument("--workload", default="10m_d96", choices=["1m", "10m_d96", "10m_d200", "stream_d96"],
+                    help="10m_d96 is the benchmark workload; stream_d96 is the streaming-ingest run (1M rows, then 100k-row batches)")
+    ap.add_argument("--stream-batches", type=int, default=90)
+    ap.add_argument("--bits", type=int, default=4)
+    ap.add_argument("--sign-bit", action="store_true",
+                    help="store the sign-bit refinement as well (bits + 1 stored per coordinate; not the default workload)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--only", action="store_true",
+                    help="the named workload alone: leave out the 10M x 200 result, the unclustered search and the extras "
+                         "(what the rocprofv3 summaries under profiles/ are taken from)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain 1 GiB device-to-device copy 5 times (reference for HBM byte counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only: this build has no multi-GPU path (run with --gpus 1)",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2605_17415_amd as pkg
+    from workloads import synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": 1 << 30, "copy_bytes_written": 1 << 30, "launches": 5}))
+        return
+    if args.workload == "stream_d96":
+        print(json.dumps(run_streaming(args, torch, pkg, synth)))
+        return
+    w = {"1m": synth.config_1m, "10m_d96": lambda: synth.config_10m_d96(args.bits),
+         "10m_d200": synth.config_10m_d200}[args.workload]()
+    nprobe = args.nprobe if args.nprobe is not None else (32 if args.workload == "1m" else w.nprobe[1])
+    t0 = time.perf_counter()
+    out = run_workload(torch, pkg, synth, args.workload, w, nprobe, args.steps, args.warmup, sign_bit=args.sign_bit,
+                       extras=not args.only, want_cpu=not args.no_cpu_baseline)
+    default_run = args.workload == "10m_d96" and not args.only and not args.sign_bit and args.bits == 4
+    if default_run:
+        # the other 10M configuration (inner-product search with out-of-distribution queries, k = 100) and a
+        # search on unclustered input of the benchmark's shape, in the same line
+        w2 = synth.config_10m_d200()
+        out["also_10m_d200"] = run_workload(torch, pkg, synth, "10m_d200", w2, w2.nprobe[1], min(args.steps, 5), min(args.warmup, 2),
+                                            extras=False, want_cpu=False)
+        out["unclustered_10m_d96"] = run_unclustered(torch, pkg, w.n, w.d, w.nlist, w.b, w.nq, nprobe, w.k)
+    out["wall_s"] = time.perf_counter() - t0
     print(json.dumps(out))
 
 

@@ -218,8 +218,11 @@ ivftq_status ivftq_refresh_coarse(ivftq_index* index, int64_t sample_n, int nite
  * vectors of the nprobe cells with the largest <q~, c~_l>.  Equal scores are ordered by label.
  * Queries with fewer than k candidates are padded with label -1 and score -infinity.
  * Asynchronous on `stream`; uses workspace owned by the index, which only grows: once a call of the
- * same (nq, nprobe, k) has run on the index as it stands, further calls allocate nothing, do not synchronise with the host and
- * issue kernel launches only, so they may be recorded into a HIP graph. */
+ * same (nq, nprobe, k) has run on the index as it stands, further calls allocate nothing, do not
+ * synchronise with the host and issue kernel launches only, so they may be recorded into a HIP graph.
+ * A later call that needs more workspace (more queries, probes or results, or a larger index)
+ * replaces the buffers, and graphs recorded before it must not be replayed any more: run the
+ * largest shape once before recording. */
 ivftq_status ivftq_search(ivftq_index* index, const float* q_dev, int64_t nq, int nprobe, int k,
                           float* scores_dev, int64_t* ids_dev, void* stream);
 

@@ -31,8 +31,10 @@ DEGENERATE_GAMMA = NOISE_FLOOR / ROW_TOL_CAP   # ... a residual norm below this 
 EXCUSED_ROWS_MAX = 2e-3   # largest share of rows that may fall under the widened rule (plus 2 rows for small cases)
 
 
-def compare_encode(enc, g_assign, g_codes, g_gamma16):
-    """enc: oracle encode dict.  Returns a report dict; raises AssertionError on a real mismatch."""
+def compare_encode(enc, g_assign, g_codes, g_gamma16, max_excused=None):
+    """enc: oracle encode dict.  Returns a report dict; raises AssertionError on a real mismatch.
+    max_excused: how many rows may fall under the widened rule for tiny residuals (default: 2 rows plus
+    EXCUSED_ROWS_MAX of all rows; a case whose construction puts rows on their centroids says how many)."""
     n = len(enc["assign"])
     a_bad = np.flatnonzero(g_assign != enc["assign"])
     unexplained = [int(i) for i in a_bad if enc["gap"][i] >= BOUNDARY_TOL]
@@ -60,7 +62,7 @@ def compare_encode(enc, g_assign, g_codes, g_gamma16):
         report["degenerate_rows"] = int(np.sum(degenerate))
         excused = report["tiny_residual_rows"] + report["degenerate_rows"]
         report["widened_rule_share"] = excused / max(n, 1)
-        assert excused <= 2 + EXCUSED_ROWS_MAX * n, \
+        assert excused <= (2 + EXCUSED_ROWS_MAX * n if max_excused is None else max_excused), \
             f"{excused} of {n} rows fall under the widened tolerance for tiny residuals: too many to excuse"
     if g_gamma16 is not None:
         g = np.asarray(g_gamma16).view(np.float16) if g_gamma16.dtype != np.float16 else g_gamma16

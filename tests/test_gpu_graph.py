@@ -1,7 +1,8 @@
-"""GPU: ivftq_search recorded into a HIP graph (after one eager call of the same shape, which sizes the
-workspace; the search makes no allocation, no host synchronisation and no memset after that) and replayed.
-Every replay is compared with the eager result for the same queries, with eager searches of other shapes and
-new query values between the replays."""
+"""GPU: ivftq_search recorded into a HIP graph (after eager calls of every shape the program uses, which
+size the workspace; the search makes no allocation, no host synchronisation and no memset after that) and
+replayed.  Every replay is compared with the eager result for the same queries, with eager searches of
+other shapes and new query values between the replays.  (A call that makes the workspace grow moves it,
+which invalidates graphs recorded before: hence the sizing calls come first.)"""
 import numpy as np
 import pytest
 
@@ -24,7 +25,8 @@ def test_search_replays_from_a_graph(nq):
     q = Q[:nq].clone()
     out_s = torch.empty((nq, cs.k), dtype=torch.float32, device=dev)
     out_i = torch.empty((nq, cs.k), dtype=torch.int64, device=dev)
-    ix.search(q, cs.nprobe, cs.k, out_scores=out_s, out_ids=out_i)       # eager: sizes the workspace
+    ix.search(Q[:200], max(1, cs.nprobe // 2), cs.k)                     # eager, every shape used below: sizes the workspace
+    ix.search(q, cs.nprobe, cs.k, out_scores=out_s, out_ids=out_i)
     torch.cuda.synchronize()
     print(f"[graph] capture nq={nq}", flush=True)
     g = torch.cuda.CUDAGraph()

@@ -49,7 +49,9 @@ def test_random_shape_matches_oracle(seed):
     x = torch.from_numpy(X).to(dev)
     assign, codes, gamma = ix.encode_only(x)
     torch.cuda.synchronize()
-    rep = parity.compare_encode(enc, assign.cpu().numpy(), codes.cpu().numpy(), gamma.cpu().numpy())
+    # with a few hundred rows in up to 200 cells some cells hold a single row, which then is its own centroid
+    # (zero residual): at most one such row per cell
+    rep = parity.compare_encode(enc, assign.cpu().numpy(), codes.cpu().numpy(), gamma.cpu().numpy(), max_excused=L)
     print("encode:", rep, flush=True)
 
     # search on the oracle's codes, both scan strategies
