@@ -176,6 +176,19 @@ ivftq_status ivftq_encode_only(ivftq_index* index, const float* x_dev, int64_t n
                                int32_t* assign_dev, uint8_t* codes_dev, uint16_t* gamma_dev,
                                void* stream);
 
+/* ivftq_encode_only for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and bit-identical
+ * outputs, but the work arrays of the coarse assignment (and the cell numbers when assign_dev is NULL)
+ * live in a static device array inside the library, 1 MiB + 256 bytes on every GPU the library has run
+ * on, instead of the index's grow-only buffers: the call allocates and frees nothing (no hipMalloc, no
+ * allocator callback) and issues kernel launches only.  n <= 65536, else IVFTQ_UNSUPPORTED and nothing
+ * is launched.  All calls on one GPU share that array (whatever index they are for), so two calls that
+ * overlap in time on one GPU race: keep them on one stream or order them.  ivftq_assign_undecided does
+ * not cover this call.  Asynchronous. */
+ivftq_status ivftq_encode_only_noalloc(ivftq_index* index, const float* x_dev, int64_t n,
+                                       int32_t* assign_dev, uint8_t* codes_dev, uint16_t* gamma_dev,
+                                       void* stream);
+
 /* Re-ranking on raw vectors (same section: optional).  For each of the nq queries the r candidate
  * labels cand_ids_dev[q*r ..] (e.g. the ids ivftq_search returned for k = r; -1 and labels outside
  * [0, n_rows) are skipped, repeats count once) are scored exactly, <q~, x~> from the raw rows

@@ -43,6 +43,8 @@ _SIGNATURES = {
                                     C.c_void_p]),
     "ivftq_encode_only": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p,
                                     C.c_void_p]),
+    "ivftq_encode_only_noalloc": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p,
+                                            C.c_void_p]),
     "ivftq_rerank": (C.c_int, [C.c_int, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int, C.c_int,
                                C.c_void_p, C.c_void_p, C.c_void_p]),
     "ivftq_reconstruct": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
@@ -358,6 +360,13 @@ class Index:
         _check(self._lib.ivftq_encode_only(self._h, _dev_ptr(x, torch.float32, "x"), n, _dev_ptr(assign),
                                            _dev_ptr(codes), _dev_ptr(gamma), _stream_ptr(stream)))
         return assign, codes, gamma
+
+    def encode_only_noalloc(self, x, assign, codes, gamma, stream=None):
+        """ivftq_encode_only into caller-provided device tensors (any may be None), nothing allocated."""
+        import torch
+        _check(self._lib.ivftq_encode_only_noalloc(self._h, _dev_ptr(x, torch.float32, "x"), x.shape[0],
+                                                   _dev_ptr(assign, torch.int32, "assign"), _dev_ptr(codes, torch.uint8, "codes"),
+                                                   _dev_ptr(gamma, torch.float16, "gamma"), _stream_ptr(stream)))
 
     # search
     def reconstruct(self, stream=None):

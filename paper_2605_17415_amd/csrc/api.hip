@@ -117,6 +117,40 @@ uint64_t splitmix(uint64_t& s) {
     return z ^ (z >> 31);
 }
 
+// Scratch of the allocation-free entry point (ivftq_encode_only_noalloc): the work arrays of the coarse
+// assignment for up to kNoAllocRows rows.  Layout: 256 bytes of flags and counters | 8-byte keys | int32 row
+// numbers | int32 cell numbers.  Every GPU the library runs on holds its own copy until the process ends.
+constexpr int64_t kNoAllocRows = 65536;
+constexpr size_t kNoAllocBytes = 256 + (size_t)kNoAllocRows * (8 + 4 + 4);
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+}  // namespace
+
+static __device__ __align__(256) unsigned char scratch[kNoAllocBytes];
+
+namespace {
+
+// Device address of `scratch` on the current device (looked up once per device; in host code the array's
+// name is only a handle for this look-up, never an address).
+hipError_t scratch_on_current_device(void** out) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!ptr) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
+}
+
 }  // namespace
 
 struct ivftq_index {
@@ -437,6 +471,7 @@ ivftq_status ivftq_create_refined(int d, int b_stage1, int sign_bit, int nlist, 
     if (e == hipSuccess) e = hipMemcpy(ix->cb.p, ix->h_cb.data(), ix->K * sizeof(float), hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemcpy(ix->d_size.p, zeros.data(), nlist * sizeof(int32_t), hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemset(ix->d_off.p, 0, (size_t)nlist * sizeof(int64_t));
+    if (e == hipSuccess) { void* unused = nullptr; e = scratch_on_current_device(&unused); }
     if ((s = guard(e, "device set-up")) != IVFTQ_OK) { delete ix; return s; }
     if ((s = upload_rotation(ix)) != IVFTQ_OK) { delete ix; return s; }
     *out = ix;
@@ -875,6 +910,43 @@ ivftq_status ivftq_encode_only(ivftq_index* ix, const float* x_dev, int64_t n, i
         a.assign = assign;
         a.codes_flat = codes_dev; a.gamma_flat = gamma_dev;
         HIP_TRY(timed(ix, st, P_ENCODE, [&] { return launch_encode(1, a, st); }));
+    }
+    return IVFTQ_OK;
+}
+
+ivftq_status ivftq_encode_only_noalloc(ivftq_index* ix, const float* x_dev, int64_t n, int32_t* assign_dev,
+                                       uint8_t* codes_dev, uint16_t* gamma_dev, void* stream) {
+    if (check_index(ix)) return IVFTQ_INVALID_ARG;
+    if (n < 0) return fail(IVFTQ_INVALID_ARG, "n=%lld is negative", (long long)n);
+    if (n > kNoAllocRows)
+        return fail(IVFTQ_UNSUPPORTED, "n=%lld above the %lld rows the static scratch of ivftq_encode_only_noalloc holds",
+                    (long long)n, (long long)kNoAllocRows);
+    if (n == 0) return IVFTQ_OK;
+    if (!x_dev) return fail(IVFTQ_INVALID_ARG, "x_dev is NULL");
+    if (!ix->has_coarse) return fail(IVFTQ_BAD_STATE, "coarse centroids not trained or set");
+    hipStream_t st = use_stream(ix, stream);
+    void* base = nullptr;
+    HIP_TRY(scratch_on_current_device(&base));
+    unsigned char* sp = static_cast<unsigned char*>(base);
+    int* flags = reinterpret_cast<int*>(sp);                                          // [0] bad norm, [1] undecided rows
+    unsigned long long* row_key = reinterpret_cast<unsigned long long*>(sp + 256);
+    int32_t* row_list = reinterpret_cast<int32_t*>(sp + 256 + (size_t)kNoAllocRows * 8);
+    int32_t* own_assign = reinterpret_cast<int32_t*>(sp + 256 + (size_t)kNoAllocRows * 12);
+    int32_t* assign = assign_dev ? assign_dev : own_assign;
+    // the scratch keeps the previous call's contents: the counters start from zero, the keys and row numbers
+    // are written before they are read (one entry per listed row)
+    HIP_TRY(launch_fill_u32(reinterpret_cast<uint32_t*>(flags), 2, 0u, st));
+    HIP_TRY(launch_coarse_screened(x_dev, n, ix->d, ix->cent_h.as<uint16_t>(), ix->cent_l.as<uint16_t>(), ix->dp,
+                                   ix->nlist, ix->lpad, assign, flags, row_list, row_key, flags + 1, st));
+    if (codes_dev || gamma_dev) {
+        EncodeArgs a{};
+        a.x = x_dev; a.n = n; a.d = ix->d; a.b = ix->b;
+        a.cent = ix->cent.as<float>(); a.cent_pitch = ix->dp;
+        a.pi_h = ix->pi_h.as<uint16_t>(); a.pi_l = ix->pi_l.as<uint16_t>();
+        a.q_grid = ix->q_grid.as<float2>(); a.q_cells = ix->q_cells; a.q_scale = ix->q_scale; a.q_offset = ix->q_offset;
+        a.assign = assign;
+        a.codes_flat = codes_dev; a.gamma_flat = gamma_dev;
+        HIP_TRY(launch_encode(1, a, st));
     }
     return IVFTQ_OK;
 }
