@@ -26,10 +26,15 @@ fewer than k candidates pad with id -1 and score -inf; the stored norm is the
 norm of r (not of Pi r), rounded to nearest-even float16; the reconstruction
 uses the plain centroid values with no de-biasing factor.
 
-Parity status: codebook, rotation, encode, search, reconstruction and exact
-k-NN are pinned by tests/test_oracle_*.py against closed forms, invariants and
-brute force.  k-means (train_coarse) is PARITY UNPINNED beyond its invariants:
-the paper fixes neither initialisation, iteration count nor empty-cell rule.
+  raw metrics   not in the paper (it keeps every vector on the unit sphere):
+                <q,x> = |q||x|<q~,x~> and |q-x|^2 = |q|^2+|x|^2-2|q||x|<q~,x~>
+                applied to the estimate of <q~,x~>, with |x| stored as float32.
+
+Parity status: codebook, rotation, k-means, encode, search, raw-metric search,
+reconstruction and exact k-NN are pinned by tests/test_oracle_*.py against
+closed forms, hand-derived cases, invariants and brute force.  The reading of
+k-means (Euclidean Lloyd iterations from given rows, empty cells re-seeded from
+the largest cell) is the build's: the paper only names k-means.
 """
 from __future__ import annotations
 
@@ -441,6 +446,77 @@ def search(index: ListIndex, Q, nprobe: int, k: int, return_all: bool = False):
     if return_all:
         return scores, ids, probes, S, everything
     return scores, ids, probes, S
+
+
+# --------------------------------------------------------------------------
+# Raw metrics: inner product and squared L2 distance of un-normalised vectors
+# --------------------------------------------------------------------------
+#
+# The paper normalises everything, so that cosine, inner product and L2 rank alike.  For inputs whose
+# lengths matter one more number per vector is kept, |x| as float32, and the estimate s^ of <q~, x~>
+# is turned into the metric by the identities of the header.  Probing is unchanged.
+
+
+def raw_norms_fp32(X):
+    """|x| of every row, computed in double and rounded to the float32 that is stored."""
+    X = np.asarray(X, dtype=np.float64)
+    return np.sqrt(np.sum(X * X, axis=1)).astype(np.float32)
+
+
+def metric_value(s_hat, xnorm, qnorm, metric: str):
+    """Estimated <q, x> ('ip') or |q - x|^2 ('l2') from the estimate s_hat of <q~, x~>."""
+    s_hat = np.asarray(s_hat, dtype=np.float64)
+    xnorm = np.asarray(xnorm, dtype=np.float64)
+    if metric == "ip":
+        return qnorm * xnorm * s_hat
+    if metric == "l2":
+        return qnorm * qnorm + xnorm * xnorm - 2.0 * qnorm * xnorm * s_hat
+    raise ValueError(metric)
+
+
+def search_raw(index: ListIndex, xnorm_by_id, Q, nprobe: int, k: int, metric: str, return_all: bool = False):
+    """Search of a raw-metric index.  xnorm_by_id[label] = stored float32 |x| of that vector.  Candidates are
+    those of `search` (same probes, same estimates); they are ranked by the metric value, best first
+    (ip: largest, l2: smallest; ties -> smaller id), padded with (-1, -inf) or (-1, +inf).
+    Returns (values [nq, k], ids [nq, k], probes, coarse scores[, per-query (ids, values)])."""
+    Q = np.asarray(Q)
+    nq = Q.shape[0]
+    qnorm = np.sqrt(np.sum(np.asarray(Q, dtype=np.float64) ** 2, axis=1))
+    _, _, probes, S, everything = search(index, Q, nprobe, 1, return_all=True)
+    worst = -np.inf if metric == "ip" else np.inf
+    values = np.full((nq, k), worst)
+    ids = np.full((nq, k), -1, dtype=np.int64)
+    all_out = []
+    for qi in range(nq):
+        cid, s_hat = everything[qi]
+        val = metric_value(s_hat, np.asarray(xnorm_by_id)[cid], qnorm[qi], metric) if len(cid) else np.empty(0)
+        key = -val if metric == "ip" else val
+        top = np.lexsort((cid, key))[:k]
+        values[qi, :len(top)] = val[top]
+        ids[qi, :len(top)] = cid[top]
+        all_out.append((cid, val))
+    if return_all:
+        return values, ids, probes, S, all_out
+    return values, ids, probes, S
+
+
+def exact_topk_raw(X, Q, k: int, metric: str):
+    """Exact k best of the raw metric, straight from its definition (ties -> smaller id)."""
+    X = np.asarray(X, dtype=np.float64)
+    Q = np.asarray(Q, dtype=np.float64)
+    ids = np.empty((Q.shape[0], k), dtype=np.int64)
+    vals = np.empty((Q.shape[0], k))
+    for qi in range(Q.shape[0]):
+        if metric == "ip":
+            v = X @ Q[qi]
+            key = -v
+        else:
+            diff = X - Q[qi][None, :]
+            v = np.sum(diff * diff, axis=1)
+            key = v
+        top = np.lexsort((np.arange(len(v)), key))[:k]
+        ids[qi], vals[qi] = top, v[top]
+    return vals, ids
 
 
 # --------------------------------------------------------------------------
