@@ -61,6 +61,13 @@ enum {
     IVFTQ_UNSUPPORTED = 6    /* a size beyond the limits listed above */
 };
 
+/* What ivftq_search ranks by and returns (ivftq_set_metric). */
+enum {
+    IVFTQ_METRIC_COSINE = 0, /* the paper's setting: estimated <q~, x~> of the normalised vectors, descending */
+    IVFTQ_METRIC_IP = 1,     /* estimated <q, x> of the raw vectors, descending */
+    IVFTQ_METRIC_L2 = 2      /* estimated |q - x|^2 of the raw vectors, ascending */
+};
+
 /* ---- constants fixed by (b, d, seed): no device needed -------------------------------- */
 
 /* Lloyd-Max codebook for the coordinate density of a uniform point on the unit sphere in R^d,
@@ -254,13 +261,33 @@ ivftq_status ivftq_list_size(const ivftq_index* index, int list, int64_t* n_out)
  * stream of the most recent call. */
 ivftq_status ivftq_export_list(const ivftq_index* index, int list, int64_t* ids_host,
                                uint8_t* codes_host, uint16_t* gamma_host);
-/* Bytes of device memory the stored vectors occupy (codes + norms + labels, without slack). */
+/* Bytes of device memory the stored vectors occupy (codes + norms + labels, without slack; with a raw
+ * metric 4 more per vector). */
 int64_t ivftq_index_bytes(const ivftq_index* index);
 /* Scan strategy of ivftq_search: 0 = default (the query-batched matrix-core scan whenever (d, b) is
  * one of its instantiated shapes and nprobe > 1, else the streaming scan), 1 = streaming scan only
  * (one workgroup per query and probed list), 2 = same as 0 (kept for callers that set it).  Results
  * obey the same contract in every mode. */
 ivftq_status ivftq_set_search_mode(ivftq_index* index, int mode);
+/* Raw metrics.  The paper puts every vector on the unit sphere (Section "Architecture", Indexing), where
+ * inner product, cosine and L2 rank alike; this switch serves inputs whose lengths matter, with nothing
+ * but one stored float32 per vector, |x|, beside the paper's record: from the estimate s^ of <q~, x~>,
+ *     <q, x> = |q| |x| s^          and          |q - x|^2 = |q|^2 + |x|^2 - 2 |q| |x| s^.
+ * Cells are still probed by <q~, c~_l> and the codes are those of the normalised vector.  Switching
+ * between cosine and a raw metric needs an empty index (BAD_STATE otherwise); between IP and L2 it
+ * is free.  With a raw metric: ivftq_encode_add stores |x| too, encoded vectors are appended with
+ * ivftq_add_encoded_raw, ivftq_search returns metric values (L2: smallest first, missing results
+ * +infinity) from the streaming scan, and ivftq_search_cascade, ivftq_reencode and
+ * ivftq_refresh_coarse return IVFTQ_UNSUPPORTED. */
+ivftq_status ivftq_set_metric(ivftq_index* index, int metric);
+/* ivftq_add_encoded for an index with a raw metric: xnorm_dev holds n float32 norms |x| (device). */
+ivftq_status ivftq_add_encoded_raw(ivftq_index* index, int64_t n, const int32_t* assign_dev,
+                                   const uint8_t* codes_dev, const uint16_t* gamma_dev,
+                                   const float* xnorm_dev, const int64_t* ids_dev, void* stream);
+/* The stored norms of one list in stored order (host, n float32); BAD_STATE for a cosine index.
+ * Waits for the stream of the most recent call. */
+ivftq_status ivftq_export_norms(const ivftq_index* index, int list, float* norms_host);
+
 /* Upper limit, in bytes, of the per-search score workspace (default 4 GiB, at least 1 MiB or
  * IVFTQ_INVALID_ARG); queries are processed in as many passes as that allows.  A pass walks every
  * probed list again, so fewer passes are faster; the results do not depend on the limit. */

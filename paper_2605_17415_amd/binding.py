@@ -15,6 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("IVFTQ_LIB") or os.path.join(_HERE, "libivftq.so")   # IVFTQ_LIB: load another build
 
 OK, INVALID_ARG, BAD_STATE, OOM, HIP_ERROR, ZERO_NORM, UNSUPPORTED = range(7)
+METRIC_COSINE, METRIC_IP, METRIC_L2 = range(3)
 STATUS_NAMES = ["OK", "INVALID_ARG", "BAD_STATE", "OOM", "HIP_ERROR", "ZERO_NORM", "UNSUPPORTED"]
 
 # every symbol include/ivftq.h declares, with its ctypes signature
@@ -61,6 +62,10 @@ _SIGNATURES = {
     "ivftq_index_bytes": (C.c_int64, [C.c_void_p]),
     "ivftq_set_workspace_limit": (C.c_int, [C.c_void_p, C.c_int64]),
     "ivftq_set_search_mode": (C.c_int, [C.c_void_p, C.c_int]),
+    "ivftq_set_metric": (C.c_int, [C.c_void_p, C.c_int]),
+    "ivftq_add_encoded_raw": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                        C.c_void_p]),
+    "ivftq_export_norms": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p]),
     "ivftq_profile_enable": (C.c_int, [C.c_void_p, C.c_int]),
     "ivftq_profile_read": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
     "ivftq_profile_kernel_count": (C.c_int, []),
@@ -316,6 +321,9 @@ class Index:
     def set_search_mode(self, mode: int):
         _check(self._lib.ivftq_set_search_mode(self._h, mode))
 
+    def set_metric(self, metric: int):
+        _check(self._lib.ivftq_set_metric(self._h, metric))
+
     def set_workspace_limit(self, nbytes: int):
         _check(self._lib.ivftq_set_workspace_limit(self._h, nbytes))
 
@@ -349,6 +357,17 @@ class Index:
                                            _dev_ptr(codes, torch.uint8, "codes"),
                                            _dev_ptr(gamma, torch.float16, "gamma"),
                                            _dev_ptr(ids, torch.int64, "ids"), _stream_ptr(stream)))
+
+    def add_encoded_raw(self, assign, codes, gamma, xnorm, ids=None, stream=None):
+        import torch
+        n = assign.shape[0]
+        if codes.shape != (n, self.d) or gamma.shape != (n,) or xnorm.shape != (n,):
+            raise ValueError("codes must be n x d, gamma and xnorm n")
+        _check(self._lib.ivftq_add_encoded_raw(self._h, n, _dev_ptr(assign, torch.int32, "assign"),
+                                               _dev_ptr(codes, torch.uint8, "codes"),
+                                               _dev_ptr(gamma, torch.float16, "gamma"),
+                                               _dev_ptr(xnorm, torch.float32, "xnorm"),
+                                               _dev_ptr(ids, torch.int64, "ids"), _stream_ptr(stream)))
 
     def encode_only(self, x, want_codes: bool = True, stream=None):
         """(assign int32 [n], codes uint8 [n, d] or None, gamma float16 [n]) as device tensors."""
@@ -455,6 +474,13 @@ class Index:
         n = C.c_int64()
         _check(self._lib.ivftq_list_size(self._h, l, C.byref(n)))
         return n.value
+
+    def export_norms(self, l: int) -> np.ndarray:
+        """float32 [n]: the stored |x| of list l in stored order (raw metrics only)."""
+        norms = np.empty(self.list_size(l), np.float32)
+        if len(norms):
+            _check(self._lib.ivftq_export_norms(self._h, l, _np_ptr(norms)))
+        return norms
 
     def export_list(self, l: int):
         """(ids int64 [n], codes uint8 [n, d], gamma float16 [n]) as numpy arrays in stored order."""

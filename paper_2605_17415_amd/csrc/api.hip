@@ -164,6 +164,9 @@ struct ivftq_index {
     DevBuf cent, cent_h, cent_l, bias, pi, pi_h, pi_l, cb, q_grid;   // cent_h/cent_l: split float16 form of cent
     // list storage
     DevBuf codes, gamma, ids, d_off, d_size;
+    DevBuf xnorm;          // |x| per slot, kept only for a raw metric (ivftq_set_metric)
+    int metric = IVFTQ_METRIC_COSINE;
+    DevBuf w_qnorm;        // |q| per query of the current search pass
     std::vector<int64_t> h_off, h_cap;
     std::vector<int32_t> h_size;
     int64_t pool_slots = 0;
@@ -186,7 +189,7 @@ struct ivftq_index {
     hipStream_t last_stream = nullptr;   // stream of the most recent call that took one (ivftq_reset and the host read-backs wait for it)
 
     std::vector<DevBuf*> buffers() {
-        return {&cent, &cent_h, &cent_l, &pi_h, &pi_l, &bias, &pi, &cb, &q_grid, &codes, &gamma, &ids, &d_off, &d_size, &w_assign,
+        return {&cent, &cent_h, &cent_l, &pi_h, &pi_l, &bias, &pi, &cb, &q_grid, &codes, &gamma, &ids, &xnorm, &w_qnorm, &d_off, &d_size, &w_assign,
                 &w_slot, &w_order, &w_hist, &w_count, &w_base, &w_flag, &w_best, &w_undecided, &cb_cascade, &w_keep, &w_keep_scores,
                 &w_S, &w_probe, &w_coarse, &w_z, &w_candoff, &w_scores, &w_sums, &w_counts, &w_zero, &w_rows, &w_dst, &w_obj,
                 &t_cent, &t_cent_h, &t_cent_l, &t_bias, &w_first, &w_fscores, &w_fids, &w_pairs, &w_pairoff, &w_tileoff, &w_cscore,
@@ -203,6 +206,7 @@ struct ivftq_index {
         s.codes = codes.as<uint32_t>();
         s.gamma = gamma.as<uint16_t>();
         s.ids = ids.as<int64_t>();
+        s.xnorm = metric != IVFTQ_METRIC_COSINE ? xnorm.as<float>() : nullptr;
         s.list_off = d_off.as<int64_t>();
         s.list_size = d_size.as<int32_t>();
         s.words = words;
@@ -295,13 +299,15 @@ ivftq_status ensure_capacity(ivftq_index* ix, const std::vector<int64_t>& need, 
         off[l] = total;
         total += cap[l];
     }
-    DevBuf ncodes(&ix->alloc), ngamma(&ix->alloc), nids(&ix->alloc), noff(&ix->alloc);
+    const bool raw = ix->metric != IVFTQ_METRIC_COSINE;
+    DevBuf ncodes(&ix->alloc), ngamma(&ix->alloc), nids(&ix->alloc), noff(&ix->alloc), nxnorm(&ix->alloc);
     hipError_t e = ncodes.ensure((size_t)total * ix->words * sizeof(uint32_t));
     if (e == hipSuccess) e = ngamma.ensure((size_t)total * sizeof(uint16_t));
     if (e == hipSuccess) e = nids.ensure((size_t)total * sizeof(int64_t));
     if (e == hipSuccess) e = noff.ensure((size_t)ix->nlist * sizeof(int64_t));
+    if (e == hipSuccess && raw) e = nxnorm.ensure((size_t)total * sizeof(float));
     if (e != hipSuccess) {
-        ncodes.release(); ngamma.release(); nids.release(); noff.release();
+        ncodes.release(); ngamma.release(); nids.release(); noff.release(); nxnorm.release();
         return fail(IVFTQ_OOM, "growing list storage to %lld slots: %s", (long long)total, hipGetErrorString(e));
     }
     HIP_TRY(hipMemcpyAsync(noff.p, off.data(), off.size() * sizeof(int64_t), hipMemcpyHostToDevice, st));
@@ -310,12 +316,13 @@ ivftq_status ensure_capacity(ivftq_index* ix, const std::vector<int64_t>& need, 
         to.codes = ncodes.as<uint32_t>();
         to.gamma = ngamma.as<uint16_t>();
         to.ids = nids.as<int64_t>();
+        to.xnorm = raw ? nxnorm.as<float>() : nullptr;
         to.list_off = noff.as<int64_t>();
         HIP_TRY(timed(ix, st, P_COPY_LISTS, [&] { return launch_copy_lists(from, to, ix->nlist, st); }));
     }
     HIP_TRY(hipStreamSynchronize(st));   // `off` is pageable host memory; old pool is about to be freed
-    ix->codes.release(); ix->gamma.release(); ix->ids.release(); ix->d_off.release();
-    ix->codes = ncodes; ix->gamma = ngamma; ix->ids = nids; ix->d_off = noff;
+    ix->codes.release(); ix->gamma.release(); ix->ids.release(); ix->d_off.release(); ix->xnorm.release();
+    ix->codes = ncodes; ix->gamma = ngamma; ix->ids = nids; ix->d_off = noff; ix->xnorm = nxnorm;
     ix->h_cap = cap;
     ix->h_off = off;
     ix->pool_slots = total;
@@ -548,6 +555,33 @@ ivftq_status ivftq_set_search_mode(ivftq_index* ix, int mode) {
     return IVFTQ_OK;
 }
 
+ivftq_status ivftq_set_metric(ivftq_index* ix, int metric) {
+    if (check_index(ix)) return IVFTQ_INVALID_ARG;
+    if (metric != IVFTQ_METRIC_COSINE && metric != IVFTQ_METRIC_IP && metric != IVFTQ_METRIC_L2)
+        return fail(IVFTQ_INVALID_ARG, "metric %d is none of IVFTQ_METRIC_COSINE / _IP / _L2", metric);
+    const bool raw_now = ix->metric != IVFTQ_METRIC_COSINE, raw_then = metric != IVFTQ_METRIC_COSINE;
+    if (raw_now != raw_then && ix->ntotal > 0)
+        return fail(IVFTQ_BAD_STATE, "vectors are stored %s their norms: the metric can only change between inner product and L2",
+                    raw_now ? "with" : "without");
+    if (raw_now != raw_then) {       // the (empty) lists are laid out again at the next append, with or without norms
+        std::fill(ix->h_cap.begin(), ix->h_cap.end(), 0);
+        ix->pool_slots = 0;
+    }
+    ix->metric = metric;
+    return IVFTQ_OK;
+}
+
+ivftq_status ivftq_export_norms(const ivftq_index* ix, int list, float* norms_host) {
+    if (check_index(ix)) return IVFTQ_INVALID_ARG;
+    if (list < 0 || list >= ix->nlist || !norms_host) return fail(IVFTQ_INVALID_ARG, "bad list number or NULL output");
+    if (ix->metric == IVFTQ_METRIC_COSINE) return fail(IVFTQ_BAD_STATE, "the index keeps no norms (cosine metric)");
+    const int64_t n = ix->h_size[list];
+    if (n == 0) return IVFTQ_OK;
+    HIP_TRY(hipStreamSynchronize(ix->last_stream));
+    HIP_TRY(hipMemcpy(norms_host, ix->xnorm.as<float>() + ix->h_off[list], n * sizeof(float), hipMemcpyDeviceToHost));
+    return IVFTQ_OK;
+}
+
 ivftq_status ivftq_set_workspace_limit(ivftq_index* ix, int64_t bytes) {
     if (check_index(ix)) return IVFTQ_INVALID_ARG;
     if (bytes < (1 << 20)) return fail(IVFTQ_INVALID_ARG, "workspace limit below 1 MiB");
@@ -623,7 +657,7 @@ int64_t ivftq_ntotal(const ivftq_index* ix) { return ix ? ix->ntotal : -1; }
 
 int64_t ivftq_index_bytes(const ivftq_index* ix) {
     if (!ix) return -1;
-    return ix->ntotal * ((int64_t)ix->words * 4 + 2 + 8);
+    return ix->ntotal * ((int64_t)ix->words * 4 + 2 + 8 + (ix->metric != IVFTQ_METRIC_COSINE ? 4 : 0));
 }
 
 ivftq_status ivftq_list_size(const ivftq_index* ix, int list, int64_t* n_out) {
@@ -986,8 +1020,10 @@ ivftq_status ivftq_encode_add(ivftq_index* ix, const float* x_dev, int64_t n, co
     return commit_rows(ix, need, n, st);
 }
 
-ivftq_status ivftq_add_encoded(ivftq_index* ix, int64_t n, const int32_t* assign_dev, const uint8_t* codes_dev,
-                               const uint16_t* gamma_dev, const int64_t* ids_dev, void* stream) {
+namespace {
+
+ivftq_status add_encoded_rows(ivftq_index* ix, int64_t n, const int32_t* assign_dev, const uint8_t* codes_dev,
+                              const uint16_t* gamma_dev, const float* xnorm_dev, const int64_t* ids_dev, void* stream) {
     if (check_index(ix)) return IVFTQ_INVALID_ARG;
     if (n < 0) return fail(IVFTQ_INVALID_ARG, "n=%lld is negative", (long long)n);
     if (n == 0) return IVFTQ_OK;
@@ -1000,9 +1036,26 @@ ivftq_status ivftq_add_encoded(ivftq_index* ix, int64_t n, const int32_t* assign
     std::vector<int64_t> need;
     ivftq_status s = place_rows(ix, assign_dev, n, false, false, need, st);
     if (s != IVFTQ_OK) return s;
-    HIP_TRY(timed(ix, st, P_PACK, [&] { return launch_pack_scatter(codes_dev, gamma_dev, ids_dev, ix->ntotal, ix->w_slot.as<int64_t>(), n, ix->d,
+    HIP_TRY(timed(ix, st, P_PACK, [&] { return launch_pack_scatter(codes_dev, gamma_dev, xnorm_dev, ids_dev, ix->ntotal, ix->w_slot.as<int64_t>(), n, ix->d,
                                 ix->b, ix->store(), st); }));
     return commit_rows(ix, need, n, st);
+}
+
+}  // namespace
+
+ivftq_status ivftq_add_encoded(ivftq_index* ix, int64_t n, const int32_t* assign_dev, const uint8_t* codes_dev,
+                               const uint16_t* gamma_dev, const int64_t* ids_dev, void* stream) {
+    if (ix && ix->metric != IVFTQ_METRIC_COSINE)
+        return fail(IVFTQ_BAD_STATE, "the index keeps a raw metric: its vectors need their norms (ivftq_add_encoded_raw)");
+    return add_encoded_rows(ix, n, assign_dev, codes_dev, gamma_dev, nullptr, ids_dev, stream);
+}
+
+ivftq_status ivftq_add_encoded_raw(ivftq_index* ix, int64_t n, const int32_t* assign_dev, const uint8_t* codes_dev,
+                                   const uint16_t* gamma_dev, const float* xnorm_dev, const int64_t* ids_dev, void* stream) {
+    if (ix && ix->metric == IVFTQ_METRIC_COSINE)
+        return fail(IVFTQ_BAD_STATE, "the index keeps no norms (cosine metric): use ivftq_add_encoded");
+    if (ix && n > 0 && !xnorm_dev) return fail(IVFTQ_INVALID_ARG, "xnorm_dev is NULL");
+    return add_encoded_rows(ix, n, assign_dev, codes_dev, gamma_dev, xnorm_dev, ids_dev, stream);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1055,6 +1108,8 @@ ivftq_status ivftq_reencode(ivftq_index* ix, const float* centroids_host, void* 
     if (check_index(ix)) return IVFTQ_INVALID_ARG;
     if (!centroids_host) return fail(IVFTQ_INVALID_ARG, "centroids_host is NULL");
     if (!ix->has_coarse) return fail(IVFTQ_BAD_STATE, "no coarse centroids yet");
+    if (ix->metric != IVFTQ_METRIC_COSINE && ix->ntotal > 0)
+        return fail(IVFTQ_UNSUPPORTED, "re-encoding does not carry the stored norms of a raw-metric index");
     for (size_t i = 0; i < (size_t)ix->nlist * ix->d; ++i)
         if (!std::isfinite(centroids_host[i])) return fail(IVFTQ_INVALID_ARG, "non-finite centroid value");
     hipStream_t st = use_stream(ix, stream);
@@ -1076,6 +1131,8 @@ ivftq_status ivftq_refresh_coarse(ivftq_index* ix, int64_t sample_n, int niter, 
                                   uint64_t seed, double* inertia_out, void* stream) {
     if (check_index(ix)) return IVFTQ_INVALID_ARG;
     if (!ix->has_coarse || ix->ntotal == 0) return fail(IVFTQ_BAD_STATE, "nothing stored to refresh from");
+    if (ix->metric != IVFTQ_METRIC_COSINE)
+        return fail(IVFTQ_UNSUPPORTED, "re-encoding does not carry the stored norms of a raw-metric index");
     if (sample_n < ix->nlist) return fail(IVFTQ_INVALID_ARG, "sample of %lld below nlist=%d", (long long)sample_n, ix->nlist);
     if (niter < 0) return fail(IVFTQ_INVALID_ARG, "niter=%d is negative", niter);
     hipStream_t st = use_stream(ix, stream);
@@ -1200,7 +1257,8 @@ ivftq_status search_core(ivftq_index* ix, const float* q_dev, int64_t nq, int np
     // at every batch size down to one query (0.10 ms against 0.24 ms), because it de-quantises two codes
     // per table look-up and leaves the sums to the matrix pipe, so it is taken whenever the shape is covered.
     const int tq = batch_tile_queries(ix->d, ix->b);
-    const bool batched = tq > 0 && nprobe > 1 && ix->search_mode != 1;
+    const int metric = ix->metric;      // a raw metric ranks by a per-vector transform of the estimate: streaming scan only
+    const bool batched = tq > 0 && nprobe > 1 && ix->search_mode != 1 && metric == IVFTQ_METRIC_COSINE;
     const int cap = std::min(2048, std::max(512, 16 * k));
     // error bound of a residual sum taken from the leading float16 parts alone (threshold pass)
     float cmax = 0.f;
@@ -1224,6 +1282,7 @@ ivftq_status search_core(ivftq_index* ix, const float* q_dev, int64_t nq, int np
     HIP_TRY(ix->w_coarse.ensure((size_t)qc * nprobe * sizeof(float)));
     HIP_TRY(ix->w_candoff.ensure((size_t)qc * (nprobe + 1) * sizeof(int32_t)));
     HIP_TRY(ix->w_z.ensure((size_t)qc * ix->dp * sizeof(float)));
+    if (metric) HIP_TRY(ix->w_qnorm.ensure((size_t)qc * sizeof(float)));
     const int64_t n_pairs = qc * nprobe;
     if (batched) {
         HIP_TRY(ix->w_zh.ensure((size_t)qc * ix->dp * sizeof(uint16_t)));
@@ -1250,6 +1309,7 @@ ivftq_status search_core(ivftq_index* ix, const float* q_dev, int64_t nq, int np
         ea.x = q; ea.n = cnt; ea.d = ix->d; ea.b = ix->b;
         ea.pi_h = ix->pi_h.as<uint16_t>(); ea.pi_l = ix->pi_l.as<uint16_t>(); ea.zout = ix->w_z.as<float>();
         if (batched) { ea.zh_out = ix->w_zh.as<uint16_t>(); ea.zl_out = ix->w_zl.as<uint16_t>(); }
+        if (metric) ea.norm_out = ix->w_qnorm.as<float>();
         HIP_TRY(timed(ix, st, P_ROTATE_Q, [&] { return launch_encode(2, ea, st); }));
         int32_t* first = batched ? ix->w_first.as<int32_t>() : nullptr;
         HIP_TRY(timed(ix, st, P_CAND_OFF, [&] {
@@ -1260,7 +1320,7 @@ ivftq_status search_core(ivftq_index* ix, const float* q_dev, int64_t nq, int np
                                     ix->w_probe.as<int32_t>(), ix->w_coarse.as<float>(),
                                     ix->w_candoff.as<int32_t>(), nprobe, ix->store(), 0, cnt,
                                     ix->w_scores.as<float>(), m_stride, nullptr, gate, gate_begin, (int)gate_rows,
-                                    blocks_per_query, st);
+                                    blocks_per_query, metric, ix->w_qnorm.as<float>(), st);
         };
         SelectArgs sa{};
         sa.vals = ix->w_scores.as<float>(); sa.stride = m_stride; sa.rows = cnt; sa.k = k;
@@ -1276,6 +1336,7 @@ ivftq_status search_core(ivftq_index* ix, const float* q_dev, int64_t nq, int np
             const int per_query = (int)std::min<int64_t>(nprobe, std::max<int64_t>(1, kStreamWorkgroups / cnt));
             HIP_TRY(timed(ix, st, P_LIST_SCAN, [&] { return stream_scan(nullptr, 0, per_query); }));
             HIP_TRY(timed(ix, st, P_SELECT_TOPK, [&] { return launch_select(1, sa, st); }));
+            HIP_TRY(launch_metric_finish(scores_dev + q0 * k, cnt, k, metric, ix->w_qnorm.as<float>(), st));
             continue;
         }
 
@@ -1360,6 +1421,7 @@ ivftq_status ivftq_search_cascade(ivftq_index* ix, const float* q_dev, int64_t n
                                   int n_keep, float* scores_dev, int64_t* ids_dev, void* stream) {
     ivftq_status s = check_query_args(ix, q_dev, nq, nprobe);
     if (s != IVFTQ_OK) return s;
+    if (ix->metric != IVFTQ_METRIC_COSINE) return fail(IVFTQ_UNSUPPORTED, "the cascade search ranks by the cosine estimate only");
     const int b1 = ix->b - (ix->sign_bit ? 1 : 0);
     if (beta < 1 || beta > b1) return fail(IVFTQ_INVALID_ARG, "beta=%d outside [1, %d]", beta, b1);
     if (k < 1 || k > n_keep) return fail(IVFTQ_INVALID_ARG, "k=%d outside [1, n_keep=%d]", k, n_keep);

@@ -75,7 +75,7 @@ void k_encode(EncodeArgs a, int flags) {
     // ---- this lane's rows: x~, residual against the assigned centroid, gamma, split unit residual
     half8 bh[R][KB], bl[R][KB];
     int64_t row_of[R];
-    float gamma[R];
+    float gamma[R], xnorm[R];
     bool valid[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) {
@@ -92,6 +92,8 @@ void k_encode(EncodeArgs a, int flags) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) v[kb][e] *= inv_n;
         gamma[r] = 0.f;
+        xnorm[r] = good ? sqrtf(n2) : 0.f;
+        if (mode == 2 && a.norm_out && valid[r] && half == 0) a.norm_out[row_of[r]] = xnorm[r];
         if (mode != 2) {
             const int cell = valid[r] ? a.assign[row_of[r]] : -1;
             float c[KB][8];
@@ -266,6 +268,7 @@ void k_encode(EncodeArgs a, int flags) {
     const bool mine = (R == 2) ? (half ? valid[R - 1] : valid[0]) : valid[0];
     const int64_t my_row = (R == 2 && half) ? row_of[R - 1] : row_of[0];
     const float my_gamma = (R == 2 && half) ? gamma[R - 1] : gamma[0];
+    const float my_xnorm = (R == 2 && half) ? xnorm[R - 1] : xnorm[0];
     const int64_t slot = mine ? a.slot[my_row] : -1;
     if (slot >= 0) {
         const uint32_t* src = my_pack + (32 * my_r + j) * pitch;
@@ -278,6 +281,7 @@ void k_encode(EncodeArgs a, int flags) {
         if (R == 2 || half == 0) {
             a.store.gamma[slot] = __half_as_ushort(__float2half_rn(my_gamma));
             a.store.ids[slot] = a.labels ? a.labels[my_row] : a.label_base + my_row;
+            if (a.store.xnorm) a.store.xnorm[slot] = my_xnorm;
         }
     }
 }

@@ -61,6 +61,7 @@ struct ListStore {
     uint32_t* codes;
     uint16_t* gamma;          // float16 bit patterns, one per slot
     int64_t* ids;             // labels, one per slot
+    float* xnorm;             // |x| of the raw input row, one per slot; null unless the index keeps a raw metric
     const int64_t* list_off;  // [nlist] first slot of each list (multiple of 64)
     const int32_t* list_size; // [nlist] vectors stored in each list
     int words;
@@ -111,6 +112,7 @@ struct EncodeArgs {
     // mode 2
     float* zout;
     uint16_t* zh_out; uint16_t* zl_out;   // optional: split float16 form of 1024*z (see split_scaled)
+    float* norm_out;                      // optional (mode 2): |x_i| of every input row
 };
 
 
@@ -131,7 +133,8 @@ hipError_t launch_stable_rank(const int32_t* assign, int64_t n, int64_t seg_len,
                               const uint32_t* seg_hist, const int64_t* list_base, int64_t* slot,
                               const int64_t* batch_base, int32_t* order, hipStream_t st);
 // pack already-quantised rows (codes: n x d bytes, one bin number each) into their storage slots
-hipError_t launch_pack_scatter(const uint8_t* codes, const uint16_t* gamma, const int64_t* labels,
+// xnorm (may be null): raw norms of the rows, stored when the store keeps them
+hipError_t launch_pack_scatter(const uint8_t* codes, const uint16_t* gamma, const float* xnorm, const int64_t* labels,
                                int64_t label_base, const int64_t* slot, int64_t n, int d, int b,
                                const ListStore& store, hipStream_t st);
 // copy every list from one pool layout to another (same words per vector)
@@ -177,7 +180,13 @@ hipError_t launch_list_scan(const float* z, int z_pitch, int d, int b, const flo
                             const int32_t* probe, const float* coarse, const int32_t* cand_off,
                             int np, const ListStore& store, int64_t q_begin, int64_t q_count,
                             float* scores, int64_t m_stride, const int32_t* p_limit, const int32_t* gate,
-                            int gate_begin, int gate_rows, int blocks_per_query, hipStream_t st);
+                            int gate_begin, int gate_rows, int blocks_per_query, int metric, const float* qnorm,
+                            hipStream_t st);
+// metric 0: the score is the estimate s^ of <q~, x~> itself.  Raw metrics (the store keeps |x|, qnorm[q] = |q|):
+// the scan writes a key that ranks like the metric and launch_metric_finish turns the selected keys into values:
+//   metric 1 (inner product): key = |x| s^,                 value = |q| key            (descending)
+//   metric 2 (squared L2):    key = 2 |x| |q| s^ - |x|^2,   value = |q|^2 - key        (ascending; missing: +inf)
+hipError_t launch_metric_finish(float* scores, int64_t nq, int k, int metric, const float* qnorm, hipStream_t st);
 // p_limit (may be null): only probes p < p_limit[q] are scanned.  gate (may be null; row = the query's index
 // without it): of the gate[0] queries listed in gate[1..] only entries [gate_begin, gate_begin + gate_rows) are
 // processed, entry g into score row g - gate_begin, so a buffer of gate_rows rows serves any number of listed

@@ -117,11 +117,13 @@ __global__ __launch_bounds__(256) void k_copy_lists(ListStore from, ListStore to
     for (int64_t e = (int64_t)blockIdx.y * 256 + threadIdx.x; e < size; e += (int64_t)gridDim.y * 256) {
         to.gamma[dst + e] = from.gamma[src + e];
         to.ids[dst + e] = from.ids[src + e];
+        if (to.xnorm) to.xnorm[dst + e] = from.xnorm ? from.xnorm[src + e] : 0.f;
     }
 }
 
 __global__ __launch_bounds__(256) void k_pack_scatter(const uint8_t* __restrict__ codes,
                                                       const uint16_t* __restrict__ gamma,
+                                                      const float* __restrict__ xnorm,
                                                       const int64_t* __restrict__ labels, int64_t label_base,
                                                       const int64_t* __restrict__ slot, int64_t n, int d,
                                                       int b, ListStore store) {
@@ -144,6 +146,7 @@ __global__ __launch_bounds__(256) void k_pack_scatter(const uint8_t* __restrict_
     if (w == 0) {
         store.gamma[s] = gamma[row];
         store.ids[s] = labels ? labels[row] : label_base + row;
+        if (store.xnorm) store.xnorm[s] = xnorm ? xnorm[row] : 0.f;
     }
 }
 
@@ -364,12 +367,12 @@ hipError_t launch_copy_lists(const ListStore& from, const ListStore& to, int L, 
     return hipGetLastError();
 }
 
-hipError_t launch_pack_scatter(const uint8_t* codes, const uint16_t* gamma, const int64_t* labels,
+hipError_t launch_pack_scatter(const uint8_t* codes, const uint16_t* gamma, const float* xnorm, const int64_t* labels,
                                int64_t label_base, const int64_t* slot, int64_t n, int d, int b,
                                const ListStore& store, hipStream_t st) {
     if (n <= 0) return hipSuccess;
     const int64_t items = n * store.words;
-    hipLaunchKernelGGL(k_pack_scatter, dim3((unsigned)((items + 255) / 256)), dim3(256), 0, st, codes, gamma,
+    hipLaunchKernelGGL(k_pack_scatter, dim3((unsigned)((items + 255) / 256)), dim3(256), 0, st, codes, gamma, xnorm,
                        labels, label_base, slot, n, d, b, store);
     return hipGetLastError();
 }

@@ -79,7 +79,8 @@ __global__ __launch_bounds__(256) void k_list_scan(const float* __restrict__ z, 
                                                    ListStore store, int64_t q_begin,
                                                    float* __restrict__ scores, int64_t m_stride,
                                                    const int32_t* __restrict__ p_limit,
-                                                   const int32_t* __restrict__ gate, int gate_begin, int gate_rows) {
+                                                   const int32_t* __restrict__ gate, int gate_begin, int gate_rows,
+                                                   int metric, const float* __restrict__ qnorm) {
     constexpr int K = 1 << B;
     extern __shared__ float lut[];     // [d][K], or z[d] followed by C[K] when DIRECT
     // gate (may be null): of the gate[0] queries listed in gate[1..], entries [gate_begin, gate_begin +
@@ -93,6 +94,7 @@ __global__ __launch_bounds__(256) void k_list_scan(const float* __restrict__ z, 
     const int64_t q = q_begin + qi;
     const int p_end = p_limit ? p_limit[q] : np;
     if ((int)blockIdx.x >= p_end) continue;
+    const float qn = metric ? qnorm[q] : 1.f;
     __syncthreads();                   // the table of the previous query is no longer read
 
     if constexpr (DIRECT) {
@@ -163,10 +165,23 @@ __global__ __launch_bounds__(256) void k_list_scan(const float* __restrict__ z, 
             }
         }
         const float g = __half2float(__ushort_as_half(store.gamma[slot]));
-        out[v] = s_l + g * acc;
+        float sc = s_l + g * acc;
+        if (metric) {                  // ranking key of a raw metric (see launch_metric_finish)
+            const float xn = store.xnorm[slot];
+            sc = metric == 1 ? xn * sc : fmaf(2.f * xn * qn, sc, -xn * xn);
+        }
+        out[v] = sc;
     }
     }
     }
+}
+
+// Selected ranking keys of a raw metric -> metric values (keys of missing results are -inf).
+__global__ void k_metric_finish(float* __restrict__ scores, int64_t nq, int k, int metric, const float* __restrict__ qnorm) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= nq * k) return;
+    const float qn = qnorm[i / k], key = scores[i];
+    scores[i] = metric == 1 ? qn * key : qn * qn - key;       // -inf stays -inf (inner product) or becomes +inf (distance)
 }
 
 // ---- selection: k largest of a row ------------------------------------------------------------
@@ -800,8 +815,10 @@ hipError_t launch_list_scan(const float* z, int z_pitch, int d, int b, const flo
                             const int32_t* probe, const float* coarse, const int32_t* cand_off,
                             int np, const ListStore& store, int64_t q_begin, int64_t q_count,
                             float* scores, int64_t m_stride, const int32_t* p_limit, const int32_t* gate,
-                            int gate_begin, int gate_rows, int blocks_per_query, hipStream_t st) {
+                            int gate_begin, int gate_rows, int blocks_per_query, int metric, const float* qnorm,
+                            hipStream_t st) {
     if (q_count <= 0) return hipSuccess;
+    if (metric && (!qnorm || !store.xnorm)) return hipErrorInvalidValue;
     const size_t lut_bytes = (size_t)d * (1u << b) * sizeof(float);
     const bool direct = lut_bytes > 64 * 1024;
     const size_t lds = direct ? (size_t)(d + (1 << b)) * sizeof(float) : lut_bytes;
@@ -811,10 +828,10 @@ hipError_t launch_list_scan(const float* z, int z_pitch, int d, int b, const flo
     case BV:                                                                                        \
         if (direct)                                                                                 \
             hipLaunchKernelGGL((k_list_scan<BV, true>), grid, dim3(256), lds, st, z, z_pitch, d, cb, probe, \
-                               coarse, cand_off, np, store, q_begin, scores, m_stride, p_limit, gate, gate_begin, gate_rows); \
+                               coarse, cand_off, np, store, q_begin, scores, m_stride, p_limit, gate, gate_begin, gate_rows, metric, qnorm); \
         else                                                                                        \
             hipLaunchKernelGGL((k_list_scan<BV, false>), grid, dim3(256), lds, st, z, z_pitch, d, cb, probe, \
-                               coarse, cand_off, np, store, q_begin, scores, m_stride, p_limit, gate, gate_begin, gate_rows); \
+                               coarse, cand_off, np, store, q_begin, scores, m_stride, p_limit, gate, gate_begin, gate_rows, metric, qnorm); \
         break;
     switch (b) {
         IVFTQ_SCAN(1) IVFTQ_SCAN(2) IVFTQ_SCAN(3) IVFTQ_SCAN(4)
@@ -822,6 +839,12 @@ hipError_t launch_list_scan(const float* z, int z_pitch, int d, int b, const flo
         default: return hipErrorInvalidValue;
     }
 #undef IVFTQ_SCAN
+    return hipGetLastError();
+}
+
+hipError_t launch_metric_finish(float* scores, int64_t nq, int k, int metric, const float* qnorm, hipStream_t st) {
+    if (nq <= 0 || metric == 0) return hipSuccess;
+    hipLaunchKernelGGL(k_metric_finish, dim3((unsigned)((nq * k + 255) / 256)), dim3(256), 0, st, scores, nq, k, metric, qnorm);
     return hipGetLastError();
 }
 
