@@ -309,13 +309,26 @@ const char* ivftq_profile_kernel_name(int id);
  * candidate of the probed lists from the top `beta` bits of each stored Stage-1 code, reconstructed
  * with the coarsened codebook below, and keeps the n_keep best per query; pass 2 scores those with
  * the full stored codes (Stage 1 and, if the index has it, the sign bit) and returns the k best,
- * outputs as ivftq_search.  1 <= beta <= Stage-1 bits, k <= n_keep <= 2048.  Pass 1 reads the same
- * packed words as the ordinary scan (the layout is not bit-sliced), so on this library it costs what
- * ivftq_search costs at k = n_keep: a statement of the method, not a shortcut.  With n_keep at least
- * the number of candidates, or beta equal to the Stage-1 bits, the result is that of ivftq_search.
- * Candidates that tie in pass 1 at the n_keep-th place are kept in slot order. */
+ * outputs as ivftq_search.  1 <= beta <= Stage-1 bits, k <= n_keep <= 2048.  If the index keeps a
+ * plane of exactly the top beta bits (ivftq_set_cascade_plane) pass 1 reads that plane, beta/b of the
+ * bytes of the full codes; otherwise it reads the full codes through a table that ignores the low
+ * bits.  The two give the same scores.  With n_keep at least the number of candidates, or beta equal
+ * to the Stage-1 bits, the result is that of ivftq_search.  Candidates that tie in pass 1 at the
+ * n_keep-th place are kept in slot order. */
 ivftq_status ivftq_search_cascade(ivftq_index* index, const float* q_dev, int64_t nq, int nprobe, int k,
                                   int beta, int n_keep, float* scores_dev, int64_t* ids_dev, void* stream);
+
+/* MSB-first storage for the cascade search (same appendix, "Cascade algorithm"): beside the packed
+ * codes the index keeps the top beta bits of every coordinate once more, packed the same way in
+ * ceil(beta*d/32) words per vector, so that pass 1 streams only those.  beta = 0 switches the plane
+ * off (the default).  1 <= beta <= Stage-1 bits and beta < stored bits, else IVFTQ_INVALID_ARG; the
+ * index must be empty (IVFTQ_BAD_STATE otherwise).  Costs beta*d more bits per vector (see
+ * ivftq_index_bytes); every append path fills the plane, every other call ignores it. */
+ivftq_status ivftq_set_cascade_plane(ivftq_index* index, int beta);
+/* The plane's content for one list in stored order: head_codes_host gets n x d uint8, each the top
+ * beta bits of the coordinate's code.  BAD_STATE without a plane.  Waits for the stream of the most
+ * recent call. */
+ivftq_status ivftq_export_cascade_plane(const ivftq_index* index, int list, uint8_t* head_codes_host);
 
 /* The coarsened codebook of pass 1 (host only): values_out[g], g < 2^beta, is the mean of the
  * sphere-coordinate density over the union of the 2^(b-beta) Stage-1 bins whose codes start with g

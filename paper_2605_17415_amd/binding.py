@@ -63,6 +63,8 @@ _SIGNATURES = {
     "ivftq_set_workspace_limit": (C.c_int, [C.c_void_p, C.c_int64]),
     "ivftq_set_search_mode": (C.c_int, [C.c_void_p, C.c_int]),
     "ivftq_set_metric": (C.c_int, [C.c_void_p, C.c_int]),
+    "ivftq_set_cascade_plane": (C.c_int, [C.c_void_p, C.c_int]),
+    "ivftq_export_cascade_plane": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p]),
     "ivftq_add_encoded_raw": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                         C.c_void_p]),
     "ivftq_export_norms": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p]),
@@ -323,6 +325,16 @@ class Index:
 
     def set_metric(self, metric: int):
         _check(self._lib.ivftq_set_metric(self._h, metric))
+
+    def set_cascade_plane(self, beta: int):
+        _check(self._lib.ivftq_set_cascade_plane(self._h, beta))
+
+    def export_cascade_plane(self, l: int) -> np.ndarray:
+        """uint8 [n, d]: the top-bit plane of list l in stored order."""
+        out = np.empty((self.list_size(l), self.d), np.uint8)
+        if len(out):
+            _check(self._lib.ivftq_export_cascade_plane(self._h, l, _np_ptr(out)))
+        return out
 
     def set_workspace_limit(self, nbytes: int):
         _check(self._lib.ivftq_set_workspace_limit(self._h, nbytes))

@@ -165,6 +165,8 @@ struct ivftq_index {
     // list storage
     DevBuf codes, gamma, ids, d_off, d_size;
     DevBuf xnorm;          // |x| per slot, kept only for a raw metric (ivftq_set_metric)
+    DevBuf head;           // top plane_beta bits of every code once more, packed alike (ivftq_set_cascade_plane); unused when plane_beta == 0
+    int plane_beta = 0, head_words = 0;
     int metric = IVFTQ_METRIC_COSINE;
     DevBuf w_qnorm;        // |q| per query of the current search pass
     std::vector<int64_t> h_off, h_cap;
@@ -189,7 +191,7 @@ struct ivftq_index {
     hipStream_t last_stream = nullptr;   // stream of the most recent call that took one (ivftq_reset and the host read-backs wait for it)
 
     std::vector<DevBuf*> buffers() {
-        return {&cent, &cent_h, &cent_l, &pi_h, &pi_l, &bias, &pi, &cb, &q_grid, &codes, &gamma, &ids, &xnorm, &w_qnorm, &d_off, &d_size, &w_assign,
+        return {&cent, &cent_h, &cent_l, &pi_h, &pi_l, &bias, &pi, &cb, &q_grid, &codes, &gamma, &ids, &xnorm, &head, &w_qnorm, &d_off, &d_size, &w_assign,
                 &w_slot, &w_order, &w_hist, &w_count, &w_base, &w_flag, &w_best, &w_undecided, &cb_cascade, &w_keep, &w_keep_scores,
                 &w_S, &w_probe, &w_coarse, &w_z, &w_candoff, &w_scores, &w_sums, &w_counts, &w_zero, &w_rows, &w_dst, &w_obj,
                 &t_cent, &t_cent_h, &t_cent_l, &t_bias, &w_first, &w_fscores, &w_fids, &w_pairs, &w_pairoff, &w_tileoff, &w_cscore,
@@ -210,6 +212,17 @@ struct ivftq_index {
         s.list_off = d_off.as<int64_t>();
         s.list_size = d_size.as<int32_t>();
         s.words = words;
+        s.head = plane_beta ? head.as<uint32_t>() : nullptr;
+        s.head_words = head_words;
+        s.head_shift = plane_beta ? b - plane_beta : 0;
+        return s;
+    }
+    // The top-bit plane seen as a store of plane_beta-bit codes (same slots, norms and labels).
+    ListStore head_store() const {
+        ListStore s = store();
+        s.codes = head.as<uint32_t>();
+        s.words = head_words;
+        s.head = nullptr; s.head_words = 0; s.head_shift = 0;
         return s;
     }
     ~ivftq_index() {
@@ -300,14 +313,15 @@ ivftq_status ensure_capacity(ivftq_index* ix, const std::vector<int64_t>& need, 
         total += cap[l];
     }
     const bool raw = ix->metric != IVFTQ_METRIC_COSINE;
-    DevBuf ncodes(&ix->alloc), ngamma(&ix->alloc), nids(&ix->alloc), noff(&ix->alloc), nxnorm(&ix->alloc);
+    DevBuf ncodes(&ix->alloc), ngamma(&ix->alloc), nids(&ix->alloc), noff(&ix->alloc), nxnorm(&ix->alloc), nhead(&ix->alloc);
     hipError_t e = ncodes.ensure((size_t)total * ix->words * sizeof(uint32_t));
     if (e == hipSuccess) e = ngamma.ensure((size_t)total * sizeof(uint16_t));
     if (e == hipSuccess) e = nids.ensure((size_t)total * sizeof(int64_t));
     if (e == hipSuccess) e = noff.ensure((size_t)ix->nlist * sizeof(int64_t));
     if (e == hipSuccess && raw) e = nxnorm.ensure((size_t)total * sizeof(float));
+    if (e == hipSuccess && ix->plane_beta) e = nhead.ensure((size_t)total * ix->head_words * sizeof(uint32_t));
     if (e != hipSuccess) {
-        ncodes.release(); ngamma.release(); nids.release(); noff.release(); nxnorm.release();
+        ncodes.release(); ngamma.release(); nids.release(); noff.release(); nxnorm.release(); nhead.release();
         return fail(IVFTQ_OOM, "growing list storage to %lld slots: %s", (long long)total, hipGetErrorString(e));
     }
     HIP_TRY(hipMemcpyAsync(noff.p, off.data(), off.size() * sizeof(int64_t), hipMemcpyHostToDevice, st));
@@ -317,12 +331,13 @@ ivftq_status ensure_capacity(ivftq_index* ix, const std::vector<int64_t>& need, 
         to.gamma = ngamma.as<uint16_t>();
         to.ids = nids.as<int64_t>();
         to.xnorm = raw ? nxnorm.as<float>() : nullptr;
+        to.head = ix->plane_beta ? nhead.as<uint32_t>() : nullptr;
         to.list_off = noff.as<int64_t>();
         HIP_TRY(timed(ix, st, P_COPY_LISTS, [&] { return launch_copy_lists(from, to, ix->nlist, st); }));
     }
     HIP_TRY(hipStreamSynchronize(st));   // `off` is pageable host memory; old pool is about to be freed
-    ix->codes.release(); ix->gamma.release(); ix->ids.release(); ix->d_off.release(); ix->xnorm.release();
-    ix->codes = ncodes; ix->gamma = ngamma; ix->ids = nids; ix->d_off = noff; ix->xnorm = nxnorm;
+    ix->codes.release(); ix->gamma.release(); ix->ids.release(); ix->d_off.release(); ix->xnorm.release(); ix->head.release();
+    ix->codes = ncodes; ix->gamma = ngamma; ix->ids = nids; ix->d_off = noff; ix->xnorm = nxnorm; ix->head = nhead;
     ix->h_cap = cap;
     ix->h_off = off;
     ix->pool_slots = total;
@@ -571,6 +586,45 @@ ivftq_status ivftq_set_metric(ivftq_index* ix, int metric) {
     return IVFTQ_OK;
 }
 
+ivftq_status ivftq_set_cascade_plane(ivftq_index* ix, int beta) {
+    if (check_index(ix)) return IVFTQ_INVALID_ARG;
+    const int b1 = ix->b - (ix->sign_bit ? 1 : 0);
+    if (beta < 0 || beta > b1 || (beta != 0 && beta >= ix->b))
+        return fail(IVFTQ_INVALID_ARG, "beta=%d: a plane of the top bits needs 1 <= beta <= %d Stage-1 bits and fewer bits than the %d stored (0 = none)",
+                    beta, b1, ix->b);
+    if (ix->ntotal > 0) return fail(IVFTQ_BAD_STATE, "the layout cannot change once vectors are stored");
+    if (beta == ix->plane_beta) return IVFTQ_OK;
+    ix->plane_beta = beta;
+    ix->head_words = beta ? code_words(beta, ix->d) : 0;
+    std::fill(ix->h_cap.begin(), ix->h_cap.end(), 0);      // the (empty) lists are laid out again at the next append
+    ix->pool_slots = 0;
+    return IVFTQ_OK;
+}
+
+ivftq_status ivftq_export_cascade_plane(const ivftq_index* ix, int list, uint8_t* head_codes_host) {
+    if (check_index(ix)) return IVFTQ_INVALID_ARG;
+    if (list < 0 || list >= ix->nlist || !head_codes_host) return fail(IVFTQ_INVALID_ARG, "bad list number or NULL output");
+    if (!ix->plane_beta) return fail(IVFTQ_BAD_STATE, "the index keeps no plane of top bits");
+    const int64_t n = ix->h_size[list];
+    if (n == 0) return IVFTQ_OK;
+    HIP_TRY(hipStreamSynchronize(ix->last_stream));
+    const int64_t off = ix->h_off[list], nblk = (n + 63) / 64;
+    const int hw = ix->head_words, beta = ix->plane_beta;
+    std::vector<uint32_t> raw((size_t)nblk * hw * 64);
+    HIP_TRY(hipMemcpy(raw.data(), ix->head.as<uint32_t>() + (off / 64) * hw * 64, raw.size() * sizeof(uint32_t), hipMemcpyDeviceToHost));
+    const uint32_t mask = (1u << beta) - 1u;
+    for (int64_t v = 0; v < n; ++v) {
+        const uint32_t* blk = &raw[(size_t)(v / 64) * hw * 64 + (v % 64)];
+        for (int j = 0; j < ix->d; ++j) {
+            const int bit = j * beta, w = bit >> 5, sh = bit & 31;
+            uint64_t two = blk[(size_t)w * 64];
+            if (w + 1 < hw) two |= (uint64_t)blk[(size_t)(w + 1) * 64] << 32;
+            head_codes_host[v * ix->d + j] = (uint8_t)((two >> sh) & mask);
+        }
+    }
+    return IVFTQ_OK;
+}
+
 ivftq_status ivftq_export_norms(const ivftq_index* ix, int list, float* norms_host) {
     if (check_index(ix)) return IVFTQ_INVALID_ARG;
     if (list < 0 || list >= ix->nlist || !norms_host) return fail(IVFTQ_INVALID_ARG, "bad list number or NULL output");
@@ -657,7 +711,8 @@ int64_t ivftq_ntotal(const ivftq_index* ix) { return ix ? ix->ntotal : -1; }
 
 int64_t ivftq_index_bytes(const ivftq_index* ix) {
     if (!ix) return -1;
-    return ix->ntotal * ((int64_t)ix->words * 4 + 2 + 8 + (ix->metric != IVFTQ_METRIC_COSINE ? 4 : 0));
+    return ix->ntotal * ((int64_t)(ix->words + (ix->plane_beta ? ix->head_words : 0)) * 4 + 2 + 8 +
+                         (ix->metric != IVFTQ_METRIC_COSINE ? 4 : 0));
 }
 
 ivftq_status ivftq_list_size(const ivftq_index* ix, int list, int64_t* n_out) {
@@ -1233,7 +1288,8 @@ namespace {
 // The search proper.  cb: the 2^b reconstruction values the scans use; labels: label of every slot, or
 // null to return slot numbers instead (pass 1 of the cascade search, which needs to find the codes again).
 ivftq_status search_core(ivftq_index* ix, const float* q_dev, int64_t nq, int nprobe, int k, const float* cb,
-                         const int64_t* labels, float* scores_dev, int64_t* ids_dev, void* stream) {
+                         const ListStore& codes_store, int bits, const int64_t* labels, float* scores_dev,
+                         int64_t* ids_dev, void* stream) {
     ivftq_status s = check_query_args(ix, q_dev, nq, nprobe);
     if (s != IVFTQ_OK) return s;
     if (k < 1) return fail(IVFTQ_INVALID_ARG, "k=%d below 1", k);
@@ -1256,7 +1312,7 @@ ivftq_status search_core(ivftq_index* ix, const float* q_dev, int64_t nq, int np
     // threshold from each query's nearest lists.  Measured (1M x 128, nprobe 32) the batched path wins
     // at every batch size down to one query (0.10 ms against 0.24 ms), because it de-quantises two codes
     // per table look-up and leaves the sums to the matrix pipe, so it is taken whenever the shape is covered.
-    const int tq = batch_tile_queries(ix->d, ix->b);
+    const int tq = batch_tile_queries(ix->d, bits);
     const int metric = ix->metric;      // a raw metric ranks by a per-vector transform of the estimate: streaming scan only
     const bool batched = tq > 0 && nprobe > 1 && ix->search_mode != 1 && metric == IVFTQ_METRIC_COSINE;
     const int cap = std::min(2048, std::max(512, 16 * k));
@@ -1316,9 +1372,9 @@ ivftq_status search_core(ivftq_index* ix, const float* q_dev, int64_t nq, int np
             return launch_cand_offsets(ix->w_probe.as<int32_t>(), cnt, nprobe, ix->d_size.as<int32_t>(),
                                        ix->w_candoff.as<int32_t>(), k, cap, first, st); }));
         auto stream_scan = [&](const int32_t* gate, int gate_begin, int blocks_per_query) {
-            return launch_list_scan(ix->w_z.as<float>(), ix->dp, ix->d, ix->b, cb,
+            return launch_list_scan(ix->w_z.as<float>(), ix->dp, ix->d, bits, cb,
                                     ix->w_probe.as<int32_t>(), ix->w_coarse.as<float>(),
-                                    ix->w_candoff.as<int32_t>(), nprobe, ix->store(), 0, cnt,
+                                    ix->w_candoff.as<int32_t>(), nprobe, codes_store, 0, cnt,
                                     ix->w_scores.as<float>(), m_stride, nullptr, gate, gate_begin, (int)gate_rows,
                                     blocks_per_query, metric, ix->w_qnorm.as<float>(), st);
         };
@@ -1356,7 +1412,7 @@ ivftq_status search_core(ivftq_index* ix, const float* q_dev, int64_t nq, int np
         ba.pairs = ix->w_pairs.as<int32_t>(); ba.pair_off = ix->w_pairoff.as<int64_t>();
         ba.tile_off = ix->w_tileoff.as<int32_t>();
         ba.coarse = ix->w_coarse.as<float>();
-        ba.store = ix->store(); ba.np = nprobe; ba.L = ix->nlist;
+        ba.store = codes_store; ba.np = nprobe; ba.L = ix->nlist;
         ba.cand_score = ix->w_cscore.as<float>(); ba.cand_slot = ix->w_cslot.as<int64_t>();
         ba.cand_cnt = ix->w_ccnt.as<int32_t>(); ba.cap = cap;
         ba.acc0 = kappa * kSplitScale * kSplitScale;
@@ -1364,7 +1420,7 @@ ivftq_status search_core(ivftq_index* ix, const float* q_dev, int64_t nq, int np
         const int max_tiles = (int)(np_items / tq) + ix->nlist;
         // 2. every score of the nearest lists, then their top-k: the k-th is the query's threshold
         ba.dense = 1; ba.bucket_lo = 0; ba.bucket_hi = ix->nlist;
-        HIP_TRY(timed(ix, st, P_BATCH_FIRST, [&] { return launch_batch_scan(ba, ix->d, ix->b, max_tiles, st); }));
+        HIP_TRY(timed(ix, st, P_BATCH_FIRST, [&] { return launch_batch_scan(ba, ix->d, bits, max_tiles, st); }));
         SelectArgs s1 = sa;
         s1.p_limit = first; s1.out_vals = ix->w_fscores.as<float>(); s1.out_i64 = ix->w_fids.as<int64_t>();
         s1.stride = row_stride; s1.m_bound = (int)row_stride;
@@ -1372,15 +1428,15 @@ ivftq_status search_core(ivftq_index* ix, const float* q_dev, int64_t nq, int np
         // 3. the other lists against the thresholds
         ba.dense = 0; ba.bucket_lo = ix->nlist; ba.bucket_hi = 2 * ix->nlist;
         ba.thresh = ix->w_fscores.as<float>() + (k - 1); ba.thresh_stride = k;
-        HIP_TRY(timed(ix, st, P_BATCH_SCAN, [&] { return launch_batch_scan(ba, ix->d, ix->b, max_tiles, st); }));
+        HIP_TRY(timed(ix, st, P_BATCH_SCAN, [&] { return launch_batch_scan(ba, ix->d, bits, max_tiles, st); }));
         // 4. merge; a query whose candidate list overflowed is redone by the exact streaming scan
         MergeArgs ma{};
         ma.first_scores = ix->w_fscores.as<float>(); ma.first_ids = ix->w_fids.as<int64_t>();
         ma.cand_score = ix->w_cscore.as<float>(); ma.cand_slot = ix->w_cslot.as<int64_t>();
         ma.cand_cnt = ix->w_ccnt.as<int32_t>(); ma.cap = cap; ma.ids = labels;
         ma.kappa = kappa;
-        ma.z = ix->w_z.as<float>(); ma.z_pitch = ix->dp; ma.d = ix->d; ma.b = ix->b; ma.cb = cb;
-        ma.coarse = ix->w_coarse.as<float>(); ma.np = nprobe; ma.store = ix->store();
+        ma.z = ix->w_z.as<float>(); ma.z_pitch = ix->dp; ma.d = ix->d; ma.b = bits; ma.cb = cb;
+        ma.coarse = ix->w_coarse.as<float>(); ma.np = nprobe; ma.store = codes_store;
         ma.k = k; ma.out_scores = scores_dev + q0 * k; ma.out_ids = ids_dev + q0 * k;
         ma.gate = ix->w_gate.as<int32_t>();
         HIP_TRY(timed(ix, st, P_MERGE, [&] { return launch_merge(ma, cnt, st); }));
@@ -1402,7 +1458,7 @@ extern "C" {
 ivftq_status ivftq_search(ivftq_index* ix, const float* q_dev, int64_t nq, int nprobe, int k,
                           float* scores_dev, int64_t* ids_dev, void* stream) {
     if (check_index(ix)) return IVFTQ_INVALID_ARG;
-    return search_core(ix, q_dev, nq, nprobe, k, ix->cb.as<float>(), ix->ids.as<int64_t>(), scores_dev, ids_dev, stream);
+    return search_core(ix, q_dev, nq, nprobe, k, ix->cb.as<float>(), ix->store(), ix->b, ix->ids.as<int64_t>(), scores_dev, ids_dev, stream);
 }
 
 ivftq_status ivftq_build_coarsened_codebook(int b, int sign_bit, int d, int beta, float* values_out) {
@@ -1430,22 +1486,28 @@ ivftq_status ivftq_search_cascade(ivftq_index* ix, const float* q_dev, int64_t n
     if (!scores_dev || !ids_dev) return fail(IVFTQ_INVALID_ARG, "output pointer is NULL");
     hipStream_t st = use_stream(ix, stream);
 
-    // pass-1 table over the full code: entry e holds the value of the merged bin e >> (bits - beta)
-    if (ix->cascade_beta != beta) {
+    // Pass 1 ranks by the top beta bits of every code.  With a plane of exactly those bits the scan reads the plane
+    // (beta-bit codes, the coarsened codebook as their table); otherwise it reads the full codes through a table
+    // whose entry e holds the value of the merged bin e >> (bits - beta).  Both give the same scores.
+    const bool plane = ix->plane_beta == beta;
+    const int key = plane ? -beta : beta;
+    if (ix->cascade_beta != key) {
         std::vector<double> lv(ix->h_cb.begin(), ix->h_cb.end()), bd(ix->h_tau.begin(), ix->h_tau.end()), cc;
         if (!build_coarsened_levels(ix->d, lv, bd, beta, cc)) return fail(IVFTQ_INVALID_ARG, "no coarsened codebook for these parameters");
         std::vector<float> table(ix->K);
-        for (int e = 0; e < ix->K; ++e) table[e] = (float)cc[e >> (ix->b - beta)];
+        for (int e = 0; e < ix->K; ++e) table[e] = plane ? (e < (1 << beta) ? (float)cc[e] : 0.f) : (float)cc[e >> (ix->b - beta)];
         HIP_TRY(ix->cb_cascade.ensure((size_t)ix->K * sizeof(float)));
         HIP_TRY(hipMemcpyAsync(ix->cb_cascade.p, table.data(), table.size() * sizeof(float), hipMemcpyHostToDevice, st));
         HIP_TRY(hipStreamSynchronize(st));       // table is a local
-        ix->cascade_beta = beta;
+        ix->cascade_beta = key;
     }
     HIP_TRY(ix->w_keep.ensure((size_t)nq * n_keep * sizeof(int64_t)));
     HIP_TRY(ix->w_keep_scores.ensure((size_t)nq * n_keep * sizeof(float)));
     // pass 1: the ordinary search on the coarsened values, n_keep slots per query
-    s = search_core(ix, q_dev, nq, nprobe, n_keep, ix->cb_cascade.as<float>(), nullptr,
-                    ix->w_keep_scores.as<float>(), ix->w_keep.as<int64_t>(), stream);
+    s = plane ? search_core(ix, q_dev, nq, nprobe, n_keep, ix->cb_cascade.as<float>(), ix->head_store(), beta, nullptr,
+                            ix->w_keep_scores.as<float>(), ix->w_keep.as<int64_t>(), stream)
+              : search_core(ix, q_dev, nq, nprobe, n_keep, ix->cb_cascade.as<float>(), ix->store(), ix->b, nullptr,
+                            ix->w_keep_scores.as<float>(), ix->w_keep.as<int64_t>(), stream);
     if (s != IVFTQ_OK) return s;
     // pass 2: the kept candidates on the full codes.  Probes, coarse terms and rotated queries are
     // recomputed per chunk by search_core, so they are produced once more here for all queries.

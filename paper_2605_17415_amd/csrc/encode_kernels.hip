@@ -43,10 +43,11 @@ struct EncCfg {
 inline int pack_pitch(int words) { return (words + 1) | 1; }   // odd and > words: room for a spill word
 
 template <int DP>
-size_t encode_lds_bytes(int mode, int cells, int words) {
+size_t encode_lds_bytes(int mode, int cells, int words, int head_words) {
     size_t bytes = EncCfg<DP>::pi_bytes;
     if (mode != 2) bytes += (size_t)cells * 8;
     if (mode == 0) bytes += (size_t)4 * 32 * EncCfg<DP>::R * pack_pitch(words) * 4;
+    if (mode == 0 && head_words > 0) bytes += (size_t)4 * 32 * EncCfg<DP>::R * pack_pitch(head_words) * 4;
     return bytes;
 }
 
@@ -70,6 +71,9 @@ void k_encode(EncodeArgs a, int flags) {
     const int d = a.d, b = a.b;
     const int words = a.store.words;
     const int pitch = (words + 1) | 1;
+    const int head_words = (mode == 0 && a.store.head) ? a.store.head_words : 0;   // top-bit plane kept as well
+    const int pitch_h = (head_words + 1) | 1;
+    const int beta = b - a.store.head_shift;
     const int64_t pos0 = ((int64_t)blockIdx.x * 4 + wave) * (32 * R);
 
     // ---- this lane's rows: x~, residual against the assigned centroid, gamma, split unit residual
@@ -127,8 +131,12 @@ void k_encode(EncodeArgs a, int flags) {
     if (mode != 2)
         for (int e = tid; e < a.q_cells; e += 256) grid_s[e] = a.q_grid[e];
     uint32_t* my_pack = pack_s + (size_t)wave * (32 * R) * pitch;
-    if (mode == 0)
+    uint32_t* my_head = pack_s + (size_t)4 * (32 * R) * pitch + (size_t)wave * (32 * R) * pitch_h;
+    if (mode == 0) {
         for (int e = lane; e < 32 * R * pitch; e += 64) my_pack[e] = 0u;
+        if (head_words)
+            for (int e = lane; e < 32 * R * pitch_h; e += 64) my_head[e] = 0u;
+    }
 
     // Staging of one 32-row tile of Pi: thread `tid` moves the 16-byte pieces tid, tid + 256, ...
     uint4 pf_h[PF], pf_l[PF];
@@ -244,6 +252,17 @@ void k_encode(EncodeArgs a, int flags) {
                         const uint32_t hi = sh ? chunk >> (32 - sh) : 0u;
                         if (lo) atomicOr(wp, lo);
                         if (hi) atomicOr(wp + 1, hi);
+                        if (head_words) {      // the same four codes cut down to their top beta bits, packed likewise
+                            const int hs = a.store.head_shift;
+                            const uint32_t ch = (code[0] >> hs) | ((code[1] >> hs) << beta) | ((code[2] >> hs) << (2 * beta)) |
+                                                ((code[3] >> hs) << (3 * beta));
+                            const int hbit = c0 * beta, hsh = hbit & 31;
+                            uint32_t* hp = my_head + (32 * r + j) * pitch_h + (hbit >> 5);
+                            const uint32_t hlo = ch << hsh;
+                            const uint32_t hhi = hsh ? ch >> (32 - hsh) : 0u;
+                            if (hlo) atomicOr(hp, hlo);
+                            if (hhi) atomicOr(hp + 1, hhi);
+                        }
                     }
                 }
             }
@@ -278,6 +297,15 @@ void k_encode(EncodeArgs a, int flags) {
         } else {
             for (int w = half; w < words; w += 2) dst[(int64_t)w * 64] = src[w];
         }
+        if (head_words) {
+            const uint32_t* hsrc = my_head + (32 * my_r + j) * pitch_h;
+            uint32_t* hdst = a.store.head + (slot >> 6) * (int64_t)head_words * 64 + (slot & 63);
+            if (R == 2) {
+                for (int w = 0; w < head_words; ++w) hdst[(int64_t)w * 64] = hsrc[w];
+            } else {
+                for (int w = half; w < head_words; w += 2) hdst[(int64_t)w * 64] = hsrc[w];
+            }
+        }
         if (R == 2 || half == 0) {
             a.store.gamma[slot] = __half_as_ushort(__float2half_rn(my_gamma));
             a.store.ids[slot] = a.labels ? a.labels[my_row] : a.label_base + my_row;
@@ -292,7 +320,7 @@ void k_encode(EncodeArgs a, int flags) {
 template <int DP, int MODE>
 hipError_t run_mode(const EncodeArgs& a, hipStream_t st) {
     static LdsLimit lim;
-    const size_t lds = encode_lds_bytes<DP>(MODE, a.q_cells, a.store.words);
+    const size_t lds = encode_lds_bytes<DP>(MODE, a.q_cells, a.store.words, a.store.head ? a.store.head_words : 0);
     if (lds > 160 * 1024) return hipErrorInvalidValue;
     const hipError_t e = lim.ensure(reinterpret_cast<const void*>(k_encode<DP, MODE>), lds);
     if (e != hipSuccess) return e;

@@ -65,6 +65,9 @@ struct ListStore {
     const int64_t* list_off;  // [nlist] first slot of each list (multiple of 64)
     const int32_t* list_size; // [nlist] vectors stored in each list
     int words;
+    // Optional second copy of the top (b - head_shift) bits of every code, packed the same way in head_words
+    // words per vector (pass 1 of the cascade search reads these instead of the full codes); null = not kept.
+    uint32_t* head; int head_words; int head_shift;
 };
 
 // ---- contraction kernels (split float16 MFMA) --------------------------------------------------------

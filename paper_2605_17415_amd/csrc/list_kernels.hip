@@ -114,6 +114,13 @@ __global__ __launch_bounds__(256) void k_copy_lists(ListStore from, ListStore to
     uint32_t* t = to.codes + (dst >> 6) * words * 64;
     for (int64_t e = (int64_t)blockIdx.y * 256 + threadIdx.x; e < total_words; e += (int64_t)gridDim.y * 256)
         t[e] = s[e];
+    if (to.head && from.head) {
+        const int64_t head_total = nblk * from.head_words * 64;
+        const uint32_t* hs = from.head + (src >> 6) * from.head_words * 64;
+        uint32_t* ht = to.head + (dst >> 6) * from.head_words * 64;
+        for (int64_t e = (int64_t)blockIdx.y * 256 + threadIdx.x; e < head_total; e += (int64_t)gridDim.y * 256)
+            ht[e] = hs[e];
+    }
     for (int64_t e = (int64_t)blockIdx.y * 256 + threadIdx.x; e < size; e += (int64_t)gridDim.y * 256) {
         to.gamma[dst + e] = from.gamma[src + e];
         to.ids[dst + e] = from.ids[src + e];
@@ -143,6 +150,17 @@ __global__ __launch_bounds__(256) void k_pack_scatter(const uint8_t* __restrict_
         word |= sh >= 0 ? (code << sh) : (code >> (-sh));
     }
     store.codes[((s >> 6) * words + w) * 64 + (s & 63)] = word;
+    if (store.head && w < store.head_words) {      // word w of the top-bit plane: coordinate j at bits [j*beta, j*beta + beta)
+        const int beta = b - store.head_shift;
+        uint32_t hword = 0;
+        for (int j = (32 * w) / beta; j < d; ++j) {
+            const int sh = j * beta - 32 * w;
+            if (sh >= 32) break;
+            const uint32_t code = (uint32_t)c[j] >> store.head_shift;
+            hword |= sh >= 0 ? (code << sh) : (code >> (-sh));
+        }
+        store.head[((s >> 6) * store.head_words + w) * 64 + (s & 63)] = hword;
+    }
     if (w == 0) {
         store.gamma[s] = gamma[row];
         store.ids[s] = labels ? labels[row] : label_base + row;

@@ -18,13 +18,14 @@ torch = pytest.importorskip("torch")
 pytestmark = pytest.mark.gpu
 
 
-def _index(cs, mode):
+def _index(cs, mode, plane_beta=0):
     import paper_2605_17415_amd as pkg
     enc = gpu_cases.oracle_encode(cs.name)
     ix = pkg.Index(cs.d, cs.b_stage1, cs.nlist, sign_bit=cs.sign_bit)
     ix.set_coarse(cs.cent)
     ix.set_rotation(cs.Pi)
     ix.set_search_mode(mode)
+    ix.set_cascade_plane(plane_beta)
     dev = torch.device("cuda:0")
     ix.add_encoded(torch.from_numpy(enc["assign"]).to(dev), torch.from_numpy(enc["codes"]).to(dev),
                    torch.from_numpy(enc["gamma16"]).to(dev))
@@ -35,10 +36,14 @@ CASES = [("tiny", 1, 2, 40), ("d128", 1, 3, 100), ("d128", 2, 2, 100), ("d96_b3s
          ("d128_b4s", 2, 3, 100), ("d100_b5", 1, 4, 100), ("d200", 2, 1, 30)]
 
 
+@pytest.mark.parametrize("plane", [False, True])
 @pytest.mark.parametrize("name,mode,beta,n_keep", CASES)
-def test_cascade_matches_oracle_on_the_same_codes(name, mode, beta, n_keep):
+def test_cascade_matches_oracle_on_the_same_codes(name, mode, beta, n_keep, plane):
+    """plane: the index keeps the top beta bits of every code in a plane of their own and pass 1 reads that."""
     import paper_2605_17415_amd as pkg
     cs = gpu_cases.get_case(name)
+    if plane and beta >= cs.b:
+        pytest.skip("a plane of all stored bits would be the codes themselves")
     oidx = gpu_cases.oracle_index(name)
     k = min(cs.k, n_keep)
     print(f"[cascade {name}] mode={mode} beta={beta} n_keep={n_keep} k={k} nq={len(cs.Q)}", flush=True)
@@ -51,11 +56,21 @@ def test_cascade_matches_oracle_on_the_same_codes(name, mode, beta, n_keep):
     _, _, _, S, o_all = orc.search(oidx, cs.Q, cs.nprobe, k, return_all=True)
     gap = parity.probe_cut_gap(S, cs.nprobe)
 
-    ix = _index(cs, mode)
+    ix = _index(cs, mode, beta if plane else 0)
     q = torch.from_numpy(cs.Q).to("cuda:0")
     scores, ids = ix.search_cascade(q, cs.nprobe, k, beta, n_keep)
     torch.cuda.synchronize()
     g_sc, g_ids = scores.cpu().numpy(), ids.cpu().numpy()
+    if plane:
+        # the plane holds the top beta bits of the stored codes, and reading it changes nothing in the result
+        for l in (0, cs.nlist // 2, cs.nlist - 1):
+            np.testing.assert_array_equal(ix.export_cascade_plane(l), ix.export_list(l)[1] >> (cs.b - beta))
+        flat = _index(cs, mode, 0)
+        f_sc, f_ids = flat.search_cascade(q, cs.nprobe, k, beta, n_keep)
+        torch.cuda.synchronize()
+        assert torch.equal(f_ids, ids) and torch.equal(f_sc, scores)
+        assert ix.index_bytes() == flat.index_bytes() + len(cs.X) * 4 * ((beta * cs.d + 31) // 32)
+        flat.close()
 
     strict, loose = [], []
     for qi in range(len(cs.Q)):
@@ -113,3 +128,49 @@ def test_cascade_argument_checks():
     torch.cuda.synchronize()
     assert torch.all(ids == -1) and torch.all(torch.isinf(sc))
     ix.close()
+
+
+@pytest.mark.parametrize("name,beta", [("d96_b4", 3), ("d128", 2), ("d96_b3s", 3), ("d70_b6", 4), ("d200", 1)])
+def test_plane_written_by_encode_add_and_kept_through_growth(name, beta):
+    """The encode kernel fills the plane itself: after several appends (the pool grows and is copied) the
+    plane still is the top beta bits of the stored codes, list by list, and the plain search ignores it."""
+    import paper_2605_17415_amd as pkg
+    cs = gpu_cases.get_case(name)
+    dev = torch.device("cuda:0")
+    x = torch.from_numpy(cs.X).to(dev)
+    q = torch.from_numpy(cs.Q).to(dev)
+    with_plane = pkg.Index(cs.d, cs.b_stage1, cs.nlist, sign_bit=cs.sign_bit)
+    plain = pkg.Index(cs.d, cs.b_stage1, cs.nlist, sign_bit=cs.sign_bit)
+    for ix in (with_plane, plain):
+        ix.set_coarse(cs.cent)
+        ix.set_rotation(cs.Pi)
+    with_plane.set_cascade_plane(beta)
+    cuts = [0, 1, 700, 5000, len(cs.X)]
+    for a, b in zip(cuts[:-1], cuts[1:]):
+        with_plane.encode_add(x[a:b])
+    plain.encode_add(x)
+    for l in range(cs.nlist):
+        ids, codes, gamma = with_plane.export_list(l)
+        ids0, codes0, gamma0 = plain.export_list(l)
+        np.testing.assert_array_equal(ids, ids0)
+        np.testing.assert_array_equal(codes, codes0)
+        np.testing.assert_array_equal(with_plane.export_cascade_plane(l), codes >> (cs.b - beta))
+    s1, i1 = with_plane.search(q, cs.nprobe, cs.k)
+    s0, i0 = plain.search(q, cs.nprobe, cs.k)
+    c1 = with_plane.search_cascade(q, cs.nprobe, cs.k, beta, 4 * cs.k)
+    c0 = plain.search_cascade(q, cs.nprobe, cs.k, beta, 4 * cs.k)
+    torch.cuda.synchronize()
+    assert torch.equal(i1, i0) and torch.equal(s1, s0)
+    assert torch.equal(c1[1], c0[1]) and torch.equal(c1[0], c0[0])
+    # layout changes are refused once vectors are stored; bad widths always
+    with pytest.raises(pkg.IvftqError) as e:
+        with_plane.set_cascade_plane(0)
+    assert e.value.status == pkg.binding.BAD_STATE
+    empty = pkg.Index(cs.d, cs.b_stage1, cs.nlist, sign_bit=cs.sign_bit)
+    for bad in (-1, cs.b_stage1 + 1, cs.b):
+        with pytest.raises(pkg.IvftqError):
+            empty.set_cascade_plane(bad)
+    with pytest.raises(pkg.IvftqError):
+        plain.export_cascade_plane(0)
+    for ix in (with_plane, plain, empty):
+        ix.close()
