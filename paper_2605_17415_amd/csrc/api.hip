@@ -349,6 +349,14 @@ ivftq_status check_index(const ivftq_index* ix) {
     return IVFTQ_OK;
 }
 
+// Rows per segment of the stable counting sort (one wavefront ranks a segment, one histogram row of L counters
+// per segment): as many segments as keep the chip busy (up to 4096), at least 128 rows each, and at most
+// 16M counters in all.
+int64_t segment_length(int64_t n, int L) {
+    const int64_t max_segments = std::max<int64_t>(64, std::min<int64_t>(4096, ((int64_t)16 << 20) / L));
+    return round_up64(std::max<int64_t>((n + max_segments - 1) / max_segments, 128), 64);
+}
+
 // The stream a call works on; remembered so that calls without a stream argument know what to wait for.
 hipStream_t use_stream(ivftq_index* ix, void* stream) {
     ix->last_stream = static_cast<hipStream_t>(stream);
@@ -787,7 +795,7 @@ ivftq_status ivftq_train_coarse(ivftq_index* ix, const float* x_dev, int64_t n, 
 
     // The iterations run on tables of their own (t_*): the index keeps its centroids until training has succeeded.
     const size_t table = (size_t)ix->lpad * pitch;
-    int64_t seg_len = round_up64((n + 1023) / 1024, 64);
+    const int64_t seg_len = segment_length(n, L);
     const int nseg = (int)((n + seg_len - 1) / seg_len);
     HIP_TRY(ix->w_rows.ensure((size_t)L * sizeof(int64_t)));
     HIP_TRY(ix->w_dst.ensure((size_t)L * sizeof(int32_t)));
@@ -835,7 +843,7 @@ ivftq_status ivftq_train_coarse(ivftq_index* ix, const float* x_dev, int64_t n, 
         HIP_TRY(timed(ix, st, P_SEG_SCAN, [&] { return launch_segment_scan(ix->w_hist.as<uint32_t>(), nseg, L, counts_dev, st); }));
         HIP_TRY(launch_exclusive_scan(counts_dev, L, cell_base, st));
         HIP_TRY(timed(ix, st, P_RANK, [&] { return launch_stable_rank(ix->w_assign.as<int32_t>(), n, seg_len, nseg, L, ix->w_hist.as<uint32_t>(), nullptr,
-                                   nullptr, cell_base, ix->w_order.as<int32_t>(), st); }));
+                                   nullptr, cell_base, ix->w_order.as<int32_t>(), nullptr, st); }));
         HIP_TRY(timed(ix, st, P_KMEANS_SUMS, [&] { return launch_kmeans_cell_sums(x_dev, d, ix->w_order.as<int32_t>(), cell_base, counts_dev, L,
                                         ix->w_sums.as<float>(), pitch, st); }));
         HIP_TRY(timed(ix, st, P_KMEANS_UPDATE, [&] { return launch_kmeans_update(cent, pitch, ix->w_sums.as<float>(), counts_dev, bias, L, ix->lpad, d, st); }));
@@ -892,12 +900,12 @@ namespace {
 ivftq_status place_rows(ivftq_index* ix, const int32_t* assign, int64_t n, bool zero_norm_flag, bool want_order,
                         std::vector<int64_t>& need, hipStream_t st) {
     const int L = ix->nlist;
-    int64_t seg_len = round_up64((n + 1023) / 1024, 64);
+    const int64_t seg_len = segment_length(n, L);
     const int nseg = (int)((n + seg_len - 1) / seg_len);
     HIP_TRY(ix->w_hist.ensure((size_t)nseg * L * sizeof(uint32_t)));
     HIP_TRY(ix->w_count.ensure((size_t)L * sizeof(uint32_t)));
     HIP_TRY(ix->w_base.ensure((size_t)2 * L * sizeof(int64_t)));
-    if (want_order) HIP_TRY(ix->w_order.ensure((size_t)n * sizeof(int32_t)));
+    if (want_order) HIP_TRY(ix->w_order.ensure((size_t)n * sizeof(int2)));
     HIP_TRY(timed(ix, st, P_SEG_HIST, [&] { return launch_segment_hist(assign, n, seg_len, nseg, L, ix->w_hist.as<uint32_t>(), st); }));
     HIP_TRY(timed(ix, st, P_SEG_SCAN, [&] { return launch_segment_scan(ix->w_hist.as<uint32_t>(), nseg, L, ix->w_count.as<uint32_t>(), st); }));
     // pinned staging: [L u32 batch counts | 16 B flag | 2L i64 bases | L i32 list sizes]
@@ -932,9 +940,11 @@ ivftq_status place_rows(ivftq_index* ix, const int32_t* assign, int64_t n, bool 
         run += count[l];
     }
     HIP_TRY(hipMemcpyAsync(ix->w_base.p, base, (size_t)2 * L * sizeof(int64_t), hipMemcpyHostToDevice, st));
+    // encode_add takes the rows in list order and derives their slots from the position (order_cell); add_encoded
+    // packs in input order and needs the slot of every row
     HIP_TRY(timed(ix, st, P_RANK, [&] { return launch_stable_rank(assign, n, seg_len, nseg, L, ix->w_hist.as<uint32_t>(), ix->w_base.as<int64_t>(),
-                               ix->w_slot.as<int64_t>(), ix->w_base.as<int64_t>() + L,
-                               want_order ? ix->w_order.as<int32_t>() : nullptr, st); }));
+                               want_order ? nullptr : ix->w_slot.as<int64_t>(), ix->w_base.as<int64_t>() + L,
+                               nullptr, want_order ? ix->w_order.as<int2>() : nullptr, st); }));
     return IVFTQ_OK;
 }
 
@@ -1053,7 +1063,6 @@ ivftq_status ivftq_encode_add(ivftq_index* ix, const float* x_dev, int64_t n, co
 
     // 1. coarse assignment
     HIP_TRY(ix->w_assign.ensure((size_t)n * sizeof(int32_t)));
-    HIP_TRY(ix->w_slot.ensure((size_t)n * sizeof(int64_t)));
     { ivftq_status sa = assign_rows(ix, x_dev, n, ix->w_assign.as<int32_t>(), st); if (sa != IVFTQ_OK) return sa; }
 
     // 2.-4. room for the new vectors and the stable position of every row
@@ -1066,10 +1075,10 @@ ivftq_status ivftq_encode_add(ivftq_index* ix, const float* x_dev, int64_t n, co
     a.cent = ix->cent.as<float>(); a.cent_pitch = ix->dp;
     a.pi_h = ix->pi_h.as<uint16_t>(); a.pi_l = ix->pi_l.as<uint16_t>();
         a.q_grid = ix->q_grid.as<float2>(); a.q_cells = ix->q_cells; a.q_scale = ix->q_scale; a.q_offset = ix->q_offset;
-    a.assign = ix->w_assign.as<int32_t>();
     a.store = ix->store();
-    a.slot = ix->w_slot.as<int64_t>();
-    a.order = ix->w_order.as<int32_t>();       // rows in list order: neighbouring lanes store to neighbouring slots
+    a.order_cell = ix->w_order.as<int2>();     // rows in list order: neighbouring lanes store to neighbouring slots
+    a.list_base = ix->w_base.as<int64_t>();
+    a.batch_base = ix->w_base.as<int64_t>() + L;
     a.labels = ids_dev; a.label_base = ix->ntotal;
     HIP_TRY(timed(ix, st, P_ENCODE, [&] { return launch_encode(0, a, st); }));
     return commit_rows(ix, need, n, st);

@@ -79,13 +79,22 @@ void k_encode(EncodeArgs a, int flags) {
     // ---- this lane's rows: x~, residual against the assigned centroid, gamma, split unit residual
     half8 bh[R][KB], bl[R][KB];
     int64_t row_of[R];
+    int cell_of[R];
     float gamma[R], xnorm[R];
     bool valid[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const int64_t pos = pos0 + 32 * r + j;
         valid[r] = pos < a.n;
-        row_of[r] = valid[r] ? (a.order ? (int64_t)a.order[pos] : pos) : 0;
+        row_of[r] = valid[r] ? pos : 0;
+        cell_of[r] = -1;
+        if (mode == 0 && valid[r]) {
+            const int2 oc = a.order_cell[pos];
+            row_of[r] = oc.x;
+            cell_of[r] = oc.y;
+        } else if (mode == 1 && valid[r]) {
+            cell_of[r] = a.assign[pos];
+        }
         float v[KB][8];
         load_row_blocks<KB>(a.x + row_of[r] * (int64_t)d, valid[r], d, vec4, half, v);
         const float n2 = row_norm2<KB>(v);
@@ -99,7 +108,7 @@ void k_encode(EncodeArgs a, int flags) {
         xnorm[r] = good ? sqrtf(n2) : 0.f;
         if (mode == 2 && a.norm_out && valid[r] && half == 0) a.norm_out[row_of[r]] = xnorm[r];
         if (mode != 2) {
-            const int cell = valid[r] ? a.assign[row_of[r]] : -1;
+            const int cell = cell_of[r];
             float c[KB][8];
             load_row_blocks<KB>(a.cent + (int64_t)(cell < 0 ? 0 : cell) * a.cent_pitch, cell >= 0, DP, 1, half, c);
 #pragma unroll
@@ -286,9 +295,11 @@ void k_encode(EncodeArgs a, int flags) {
     const int my_r = (R == 2) ? half : 0;
     const bool mine = (R == 2) ? (half ? valid[R - 1] : valid[0]) : valid[0];
     const int64_t my_row = (R == 2 && half) ? row_of[R - 1] : row_of[0];
+    const int my_cell = (R == 2 && half) ? cell_of[R - 1] : cell_of[0];
+    const int64_t my_pos = pos0 + 32 * my_r + j;
     const float my_gamma = (R == 2 && half) ? gamma[R - 1] : gamma[0];
     const float my_xnorm = (R == 2 && half) ? xnorm[R - 1] : xnorm[0];
-    const int64_t slot = mine ? a.slot[my_row] : -1;
+    const int64_t slot = (mine && my_cell >= 0) ? a.list_base[my_cell] + (my_pos - a.batch_base[my_cell]) : -1;
     if (slot >= 0) {
         const uint32_t* src = my_pack + (32 * my_r + j) * pitch;
         uint32_t* dst = a.store.codes + (slot >> 6) * (int64_t)words * 64 + (slot & 63);

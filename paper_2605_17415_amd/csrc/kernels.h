@@ -99,17 +99,19 @@ hipError_t launch_mfma_peak(const uint16_t* operands, float* out, int blocks, in
 // mode 1: same, but write unpacked codes / fp16 norms to flat arrays (any may be null)
 // mode 2: z_i = Pi x~_i written to zout[i*DP + j] (no centroid, no quantiser)
 // q_grid: the quantiser's uniform-grid index (host_math.h), q_cells entries of (boundary, index bits).
-// order (may be null): row processed at position p is order[p] (rows grouped by list, so that the
-// stores of neighbouring lanes fall into neighbouring slots); null = input order.
+// order_cell (mode 0): position p of the batch in list order holds row order_cell[p].x, which belongs to list
+// order_cell[p].y and goes to slot list_base[l] + p - batch_base[l] (neighbouring lanes store to neighbouring
+// slots, and neither the cell nor the slot of a row has to be fetched by row number).  Modes 1 and 2 take the
+// rows in input order and read assign[row].
 struct EncodeArgs {
     const float* x; int64_t n; int d; int b;
     const float* cent; int cent_pitch;
     const uint16_t* pi_h; const uint16_t* pi_l;   // split float16 form of Pi, [DP][DP]
     const float2* q_grid; int q_cells; float q_scale, q_offset;
     const int32_t* assign;
-    const int32_t* order;
     // mode 0
-    ListStore store; const int64_t* slot; const int64_t* labels; int64_t label_base;
+    const int2* order_cell; const int64_t* list_base; const int64_t* batch_base;
+    ListStore store; const int64_t* labels; int64_t label_base;
     // mode 1
     uint8_t* codes_flat; uint16_t* gamma_flat;
     // mode 2
@@ -132,9 +134,10 @@ hipError_t launch_segment_scan(uint32_t* seg_hist, int nseg, int L, uint32_t* ba
 // list_base may be null when only the order is wanted.
 // order (may be null): the batch's rows grouped by list, lists ascending, input order inside a list:
 // order[batch_base[l] + rank] = i, with batch_base the exclusive running sum of the batch's rows per list.
+// order_cell (may be null): the same order with the list beside the row, order_cell[...] = (i, l).
 hipError_t launch_stable_rank(const int32_t* assign, int64_t n, int64_t seg_len, int nseg, int L,
                               const uint32_t* seg_hist, const int64_t* list_base, int64_t* slot,
-                              const int64_t* batch_base, int32_t* order, hipStream_t st);
+                              const int64_t* batch_base, int32_t* order, int2* order_cell, hipStream_t st);
 // pack already-quantised rows (codes: n x d bytes, one bin number each) into their storage slots
 // xnorm (may be null): raw norms of the rows, stored when the store keeps them
 hipError_t launch_pack_scatter(const uint8_t* codes, const uint16_t* gamma, const float* xnorm, const int64_t* labels,

@@ -65,7 +65,7 @@ __global__ __launch_bounds__(64) void k_stable_rank(const int32_t* __restrict__ 
                                                     const int64_t* __restrict__ list_base,
                                                     int64_t* __restrict__ slot,
                                                     const int64_t* __restrict__ batch_base,
-                                                    int32_t* __restrict__ order) {
+                                                    int32_t* __restrict__ order, int2* __restrict__ order_cell) {
     extern __shared__ uint32_t cnt[];
     const int lane = threadIdx.x;
     for (int l = lane; l < L; l += 64) cnt[l] = seg_hist[(int64_t)blockIdx.x * L + l];
@@ -93,6 +93,7 @@ __global__ __launch_bounds__(64) void k_stable_rank(const int32_t* __restrict__ 
             base = cnt[key];
             if (slot) slot[i] = list_base[key] + (int64_t)(base + lower);
             if (order) order[batch_base[key] + (int64_t)(base + lower)] = (int32_t)i;
+            if (order_cell) order_cell[batch_base[key] + (int64_t)(base + lower)] = make_int2((int)i, key);
         } else if (i < end && slot) {
             slot[i] = -1;
         }
@@ -374,9 +375,9 @@ hipError_t launch_segment_scan(uint32_t* seg_hist, int nseg, int L, uint32_t* ba
 
 hipError_t launch_stable_rank(const int32_t* assign, int64_t n, int64_t seg_len, int nseg, int L,
                               const uint32_t* seg_hist, const int64_t* list_base, int64_t* slot,
-                              const int64_t* batch_base, int32_t* order, hipStream_t st) {
+                              const int64_t* batch_base, int32_t* order, int2* order_cell, hipStream_t st) {
     hipLaunchKernelGGL(k_stable_rank, dim3(nseg), dim3(64), (size_t)L * 4, st, assign, n, seg_len, L,
-                       seg_hist, list_base, slot, batch_base, order);
+                       seg_hist, list_base, slot, batch_base, order, order_cell);
     return hipGetLastError();
 }
 
