@@ -341,6 +341,15 @@ ivftq_status ivftq_build_coarsened_codebook(int b, int sign_bit, int d, int beta
  * the full-precision one either way).  Waits for `stream`. */
 ivftq_status ivftq_assign_undecided(ivftq_index* index, int64_t* count_out, void* stream);
 
+/* Measurement aid: what the query-batched scan of the most recent ivftq_search / ivftq_search_cascade on this
+ * index did in its last pass over the queries (Section "Architecture", Search; beyond each query's nearest lists the scan keeps only the
+ * candidates whose upper bound reaches the k-th best score of those lists): queries_out = queries of that pass
+ * (0 when the streaming scan ran), redone_out = those whose candidate list overflowed and that were redone by
+ * the exact streaming scan, max_candidates_out / mean_candidates_out = candidates collected per query.  Any
+ * output may be NULL.  Waits for `stream`. */
+ivftq_status ivftq_scan_stats(ivftq_index* index, int64_t* queries_out, int64_t* redone_out,
+                              int64_t* max_candidates_out, double* mean_candidates_out, void* stream);
+
 /* Measurement aid: the rate (TFLOP/s, 2*32*32*16 flop per instruction) that a loop of nothing but
  * v_mfma_f32_32x32x16_f16, the instruction every contraction of this library uses, reaches on the
  * current device, two wavefronts per SIMD, operands in registers.  random_operands != 0: operands

@@ -76,6 +76,8 @@ _SIGNATURES = {
                                        C.c_void_p, C.c_void_p, C.c_void_p]),
     "ivftq_build_coarsened_codebook": (C.c_int, [C.c_int, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_float)]),
     "ivftq_assign_undecided": (C.c_int, [C.c_void_p, C.POINTER(C.c_int64), C.c_void_p]),
+    "ivftq_scan_stats": (C.c_int, [C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.POINTER(C.c_int64),
+                                   C.POINTER(C.c_double), C.c_void_p]),
     "ivftq_measure_mfma_rate": (C.c_int, [C.c_int, C.POINTER(C.c_double)]),
     "ivftq_last_error": (C.c_char_p, []),
     "ivftq_version": (C.c_char_p, []),
@@ -474,6 +476,12 @@ class Index:
         out = C.c_int64(0)
         _check(self._lib.ivftq_assign_undecided(self._h, C.byref(out), _stream_ptr(stream)))
         return out.value
+
+    def scan_stats(self, stream=None) -> dict:
+        """Candidates per query and queries redone exactly in the last pass of the most recent batched search."""
+        nq, redone, mx, mean = C.c_int64(0), C.c_int64(0), C.c_int64(0), C.c_double(0)
+        _check(self._lib.ivftq_scan_stats(self._h, C.byref(nq), C.byref(redone), C.byref(mx), C.byref(mean), _stream_ptr(stream)))
+        return {"queries": nq.value, "redone_exactly": redone.value, "max_candidates": mx.value, "mean_candidates": mean.value}
 
     # inspection
     def ntotal(self) -> int:

@@ -183,6 +183,7 @@ struct ivftq_index {
     DevBuf t_cent, t_cent_h, t_cent_l, t_bias;   // k-means works on its own tables; the index's change only on success
     DevBuf w_zh, w_zl;
     DevBuf w_first, w_fscores, w_fids, w_pairs, w_pairoff, w_tileoff, w_cscore, w_cslot, w_ccnt, w_gate;
+    int64_t last_batched_queries = 0;   // queries of the last pass of the most recent batched search (ivftq_scan_stats)
     int search_mode = 0;   // 0 auto, 1 streaming scan only, 2 batched scan whenever the shape allows
     int64_t ws_limit = (int64_t)4 << 30;
     bool prof_on = false;
@@ -977,6 +978,30 @@ ivftq_status assign_rows(ivftq_index* ix, const float* x_dev, int64_t n, int32_t
 
 }  // namespace
 
+ivftq_status ivftq_scan_stats(ivftq_index* ix, int64_t* queries_out, int64_t* redone_out, int64_t* max_candidates_out,
+                              double* mean_candidates_out, void* stream) {
+    if (check_index(ix)) return IVFTQ_INVALID_ARG;
+    hipStream_t st = use_stream(ix, stream);
+    const int64_t n = ix->last_batched_queries;
+    if (queries_out) *queries_out = n;
+    if (redone_out) *redone_out = 0;
+    if (max_candidates_out) *max_candidates_out = 0;
+    if (mean_candidates_out) *mean_candidates_out = 0.0;
+    if (n <= 0) return IVFTQ_OK;
+    std::vector<int32_t> cnt(n);
+    int32_t gated = 0;
+    HIP_TRY(hipMemcpyAsync(cnt.data(), ix->w_ccnt.p, n * sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipMemcpyAsync(&gated, ix->w_gate.p, sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    int64_t mx = 0;
+    double sum = 0.0;
+    for (int32_t c : cnt) { mx = std::max<int64_t>(mx, c); sum += c; }
+    if (redone_out) *redone_out = gated;
+    if (max_candidates_out) *max_candidates_out = mx;
+    if (mean_candidates_out) *mean_candidates_out = sum / (double)n;
+    return IVFTQ_OK;
+}
+
 ivftq_status ivftq_assign_undecided(ivftq_index* ix, int64_t* count_out, void* stream) {
     if (check_index(ix)) return IVFTQ_INVALID_ARG;
     if (!count_out) return fail(IVFTQ_INVALID_ARG, "count_out is NULL");
@@ -1396,6 +1421,7 @@ ivftq_status search_core(ivftq_index* ix, const float* q_dev, int64_t nq, int np
         sa.m_bound = (int)m_stride;
 
         if (!batched) {
+            ix->last_batched_queries = 0;
             // workgroups per query: each builds the query's table once and walks its share of the probes;
             // fewer per query as the batch grows, as long as the launch still fills the chip
             const int per_query = (int)std::min<int64_t>(nprobe, std::max<int64_t>(1, kStreamWorkgroups / cnt));
@@ -1406,6 +1432,7 @@ ivftq_status search_core(ivftq_index* ix, const float* q_dev, int64_t nq, int np
         }
 
         // 1. (query, probe) pairs bucketed by list; the nearest lists of each query in their own buckets
+        ix->last_batched_queries = cnt;
         const int64_t np_items = cnt * nprobe;
         HIP_TRY(timed(ix, st, P_PAIR_GROUP, [&] {
             hipError_t e = launch_pair_grouping(ix->w_probe.as<int32_t>(), first, cnt, nprobe, ix->nlist, tq,
