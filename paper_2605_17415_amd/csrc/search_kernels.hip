@@ -410,6 +410,7 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a) {
 // memory in each pass.  A wavefront needs little LDS, so many rows are in flight per compute unit.  A final bitonic pass over the lanes orders the winners by (value desc, label asc).
 
 constexpr int kSmallM = 16384;
+constexpr int kShortcutTake = 32;     // the lane-maxima short cut pays up to this many winners (beyond, too many keys reach the bound)
 
 template <int MODE, int NV>
 __global__ __launch_bounds__(256) void k_select_small(SelectArgs a) {
@@ -438,6 +439,84 @@ __global__ __launch_bounds__(256) void k_select_small(SelectArgs a) {
         keys[e] = key_of(vals[i < m ? i : 0]);
     }
 
+    // Short cut.  The take-th largest of the 64 lane maxima is reached by at least `take` keys (one per lane
+    // that holds such a maximum), so every winner is among the keys that reach it; there are seldom many more
+    // than `take` of them.  When at most 64 do, they are compacted into the lanes, sorted by (key desc, column
+    // asc) and the first `take` are the winners: the same set as the radix search below would pick.
+    bool done = false;
+    if (take > 0 && take <= kShortcutTake) {
+        uint32_t lane_max = 0u;
+#pragma unroll
+        for (int e = 0; e < NV; ++e) lane_max = (e * 64 + lane < m && keys[e] > lane_max) ? keys[e] : lane_max;
+        for (int i0 = NV * 64; i0 < m; i0 += 64 * kSelSmallU) {
+            float v[kSelSmallU];
+#pragma unroll
+            for (int u = 0; u < kSelSmallU; ++u) { const int i = i0 + 64 * u + lane; v[u] = vals[i < m ? i : m - 1]; }
+#pragma unroll
+            for (int u = 0; u < kSelSmallU; ++u) {
+                const uint32_t key = key_of(v[u]);
+                lane_max = (i0 + 64 * u + lane < m && key > lane_max) ? key : lane_max;
+            }
+        }
+        uint32_t sorted = lane_max;                      // the lane maxima in descending order over the lanes
+#pragma unroll
+        for (int size = 2; size <= 64; size <<= 1) {
+#pragma unroll
+            for (int stride = size >> 1; stride > 0; stride >>= 1) {
+                const uint32_t other = __shfl_xor(sorted, stride);
+                const bool lower = (lane & stride) == 0, up = (lane & size) == 0;
+                const bool keep = (lower == up) ? (sorted >= other) : (sorted <= other);
+                sorted = keep ? sorted : other;
+            }
+        }
+        const uint32_t reach = __shfl(sorted, take - 1);
+        if (reach != 0u) {
+            uint32_t* c_key = hist;                      // [64] keys that reach it, [64] their columns
+            int* c_col = reinterpret_cast<int*>(hist + 64);
+            uint32_t count = 0;
+            auto collect = [&](int i, uint32_t key) {
+                const bool in = i < m && key >= reach;
+                const uint64_t b = __ballot(in);
+                const uint32_t pos = count + (uint32_t)__popcll(b & (((uint64_t)1 << lane) - 1));
+                if (in && pos < 64u) { c_key[pos] = key; c_col[pos] = i; }
+                count += (uint32_t)__popcll(b);
+            };
+#pragma unroll
+            for (int e = 0; e < NV; ++e)
+                if (e * 64 < m) collect(e * 64 + lane, keys[e]);
+            for (int i0 = NV * 64; i0 < m && count <= 64u; i0 += 64 * kSelSmallU) {
+                float v[kSelSmallU];
+#pragma unroll
+                for (int u = 0; u < kSelSmallU; ++u) { const int i = i0 + 64 * u + lane; v[u] = vals[i < m ? i : m - 1]; }
+#pragma unroll
+                for (int u = 0; u < kSelSmallU; ++u)
+                    if (i0 + 64 * u < m) collect(i0 + 64 * u + lane, key_of(v[u]));
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            if (count <= 64u) {
+                uint32_t ck = lane < (int)count ? c_key[lane] : 0u;
+                int cc = lane < (int)count ? c_col[lane] : INT32_MAX;
+#pragma unroll
+                for (int size = 2; size <= 64; size <<= 1) {
+#pragma unroll
+                    for (int stride = size >> 1; stride > 0; stride >>= 1) {
+                        const uint32_t ok = __shfl_xor(ck, stride);
+                        const int oc = __shfl_xor(cc, stride);
+                        const bool lower = (lane & stride) == 0, up = (lane & size) == 0;
+                        const bool mine_first = (ck > ok) || (ck == ok && cc <= oc);
+                        const bool keep = (lower == up) ? mine_first : !mine_first;
+                        if (!keep) { ck = ok; cc = oc; }
+                    }
+                }
+                if (lane < take) win_col[lane] = cc;
+                done = true;
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();         // the words of `hist` are free again
+        }
+    }
+    if (!done) {
     // radix search for the take-th largest key
     uint32_t prefix = 0, mask = 0, need = (uint32_t)take;
     // Leading bytes that every key of the row shares (scores of one query usually share sign and exponent)
@@ -536,6 +615,7 @@ __global__ __launch_bounds__(256) void k_select_small(SelectArgs a) {
             for (int u = 0; u < kSelSmallU; ++u)
                 if (i0 + 64 * u < m) place(i0 + 64 * u + lane, key_of(v[u]));
         }
+    }
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
@@ -849,15 +929,16 @@ hipError_t launch_metric_finish(float* scores, int64_t nq, int k, int metric, co
 }
 
 // Longest row the one-wavefront-per-row kernel takes.  Probe selection (mode 0, every row has m_fixed values):
-// beyond the columns it holds in registers the workgroup-per-row kernel is faster (measured at 4096 cells:
-// 0.145 against 0.19 ms for 10,000 rows); result rows (mode 1) are mostly much shorter than their bound.
-constexpr int kSmallMax0 = 2048, kSmallMax1 = kSmallM;
+// beyond the columns it holds in registers the workgroup-per-row kernel is faster when the radix search runs
+// (measured at 4096 cells: 0.145 against 0.19 ms for 10,000 rows), the wavefront kernel when its short cut
+// applies (0.094 ms); result rows (mode 1) are mostly much shorter than their bound.
+constexpr int kSmallMax0 = 2048, kSmallMax0Shortcut = 8192, kSmallMax1 = kSmallM;
 hipError_t launch_select(int mode, const SelectArgs& a_in, hipStream_t st) {
     if (a_in.rows <= 0) return hipSuccess;
     SelectArgs a = a_in;
     // short rows and small k: the one-wavefront-per-row kernel
     const int m_bound = mode == 0 ? a.m_fixed : a.m_bound;
-    if (a.k <= 64 && m_bound > 0 && m_bound <= (mode == 0 ? kSmallMax0 : kSmallMax1)) {
+    if (a.k <= 64 && m_bound > 0 && m_bound <= (mode == 0 ? (a.k <= kShortcutTake ? kSmallMax0Shortcut : kSmallMax0) : kSmallMax1)) {
         const size_t lds = 0;
         const unsigned blocks = (unsigned)((a.gate ? std::min<int64_t>(std::min<int64_t>(a.rows, a.gate_rows), 1024) : a.rows) + 3) / 4;
 #define IVFTQ_SMALL(NVV)                                                                            \
