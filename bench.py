@@ -312,6 +312,7 @@ def run_workload(torch, pkg, synth, key, w, nprobe, steps, warmup, sign_bit=Fals
 
     found = ids.cpu().numpy()
     rec = recall(found, truth)
+    scan_stats = ix.scan_stats()                               # of the last timed search
     enc_t = float(np.mean(enc_ms)) / 1e3
     search_t = float(np.mean(search_ms)) / 1e3
     qps = w.nq / search_t
@@ -456,23 +457,30 @@ def run_workload(torch, pkg, synth, key, w, nprobe, steps, warmup, sign_bit=Fals
             ms = median_ms(lambda: cs(ix))
             cascade_info = {"beta": beta, "n_keep": keep, "qps": w.nq / (ms / 1e3),
                             "recall_at_k": recall(holder["ids"].cpu().numpy(), truth)}
-            ixp = pkg.Index(w.d, w.b, w.nlist, rotation_seed=w.seed, sign_bit=sign_bit)
-            ixp.set_coarse(cent)
-            ixp.set_cascade_plane(beta)
-            ixp.encode_add(xd)
-            cs(ixp)
-            ms_p = median_ms(lambda: cs(ixp))
-            ixp.set_search_mode(1)
-            ixp.search_cascade(qs, nprobe, w.k, beta, keep)
-            ms_ps = median_ms(lambda: ixp.search_cascade(qs, nprobe, w.k, beta, keep))
-            ix.set_search_mode(1)
-            ix.search_cascade(qs, nprobe, w.k, beta, keep)
-            ms_fs = median_ms(lambda: ix.search_cascade(qs, nprobe, w.k, beta, keep))
-            ix.set_search_mode(0)
-            cascade_info["with_plane"] = {"qps": w.nq / (ms_p / 1e3), "recall_at_k": recall(holder["ids"].cpu().numpy(), truth),
-                                          "index_bytes": ixp.index_bytes(),
-                                          "streaming_256_queries_ms": ms_ps, "streaming_256_queries_ms_without_plane": ms_fs}
-            ixp.close()
+            planes = {}
+            for pb in sorted({beta, max(1, w.b - 2)}, reverse=True):       # a plane of b-1 bits, and one of b-2
+                ixp = pkg.Index(w.d, w.b, w.nlist, rotation_seed=w.seed, sign_bit=sign_bit)
+                ixp.set_coarse(cent)
+                ixp.set_cascade_plane(pb)
+                ixp.encode_add(xd)
+                holder["ids"] = ixp.search_cascade(qd, nprobe, w.k, pb, keep)[1]
+                ms_p = median_ms(lambda: ixp.search_cascade(qd, nprobe, w.k, pb, keep))
+                rec_p = recall(holder["ids"].cpu().numpy(), truth)
+                ms_f = median_ms(lambda: ix.search_cascade(qd, nprobe, w.k, pb, keep))
+                # the streaming scan (bandwidth-side kernel) on 256 queries, with and without the plane
+                ixp.set_search_mode(1)
+                ix.set_search_mode(1)
+                ixp.search_cascade(qs, nprobe, w.k, pb, keep)
+                ix.search_cascade(qs, nprobe, w.k, pb, keep)
+                ms_ps = median_ms(lambda: ixp.search_cascade(qs, nprobe, w.k, pb, keep))
+                ms_fs = median_ms(lambda: ix.search_cascade(qs, nprobe, w.k, pb, keep))
+                ix.set_search_mode(0)
+                planes[f"beta_{pb}"] = {"qps_with_plane": w.nq / (ms_p / 1e3), "qps_without_plane": w.nq / (ms_f / 1e3),
+                                        "recall_at_k": rec_p, "index_bytes_with_plane": ixp.index_bytes(),
+                                        "streaming_256_queries_ms_with_plane": ms_ps,
+                                        "streaming_256_queries_ms_without_plane": ms_fs}
+                ixp.close()
+            cascade_info["planes"] = planes
 
     out = {
         "metric": f"search QPS at recall@{w.k} (nprobe={nprobe}, k={w.k}) + encode vectors/s",
@@ -484,6 +492,7 @@ def run_workload(torch, pkg, synth, key, w, nprobe, steps, warmup, sign_bit=Fals
         "recall_at_k": rec,
         "search_ms": search_t * 1e3, "encode_ms": enc_t * 1e3, "encode_vectors_per_s": vps,
         "candidates_per_query": float(cand.mean()),
+        "batched_scan": scan_stats,
         "index_bytes": ix.index_bytes(),
         "search_ms_with_kernel_events": float(np.mean(search_ms_p)), "encode_ms_with_kernel_events": float(np.mean(enc_ms_p)),
         "kernel_ms_per_step": per_step, "dominant_kernel": dominant, "assign_undecided_fraction": undecided,
@@ -543,6 +552,44 @@ def run_unclustered(torch, pkg, n, d, nlist, b, nq, nprobe, k, seed=42):
     return out
 
 
+def run_cascade_plane_check(args, torch, pkg, synth):
+    """Pass 1 of the cascade search through the streaming scan, with and without the plane of top bits: the two
+    list-scan kernels (codes of b bits, codes of beta bits) can then be told apart in a counter trace."""
+    dev = torch.device("cuda:0")
+    w = {"1m": synth.config_1m, "10m_d96": lambda: synth.config_10m_d96(args.bits), "10m_d200": synth.config_10m_d200}[args.workload]()
+    nprobe = args.nprobe if args.nprobe is not None else (32 if args.workload == "1m" else w.nprobe[1])
+    beta = args.cascade_plane_check
+    xd = torch.from_numpy(synth.database(w)).to(dev)
+    qs = torch.from_numpy(synth.queries(w, 256)).to(dev)
+    rows = synth.train_sample_indices(w)
+    out = {"workload": workload_label(w, args.workload), "nprobe": nprobe, "beta": beta, "queries": 256}
+    cent = None
+    for plane in (0, beta):
+        ix = pkg.Index(w.d, w.b, w.nlist, rotation_seed=w.seed)
+        if cent is None:
+            ix.train_coarse(xd[torch.from_numpy(rows).to(dev)].contiguous(), w.kmeans_iters,
+                            init_rows=synth.kmeans_init_indices(w.seed, len(rows), w.nlist))
+            cent = ix.get_coarse()
+        else:
+            ix.set_coarse(cent)
+        ix.set_cascade_plane(plane)
+        ix.set_search_mode(1)
+        ix.encode_add(xd)
+        keep = min(2048, max(100, 4 * w.k))
+        ts = []
+        for _ in range(3):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            ix.search_cascade(qs, nprobe, w.k, beta, keep)
+            b.record()
+            torch.cuda.synchronize()
+            ts.append(a.elapsed_time(b))
+        out["with_plane_ms" if plane else "without_plane_ms"] = float(np.median(ts))
+        out["index_bytes_with_plane" if plane else "index_bytes_without_plane"] = ix.index_bytes()
+        ix.close()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -559,6 +606,9 @@ def main():
     ap.add_argument("--only", action="store_true",
                     help="the named workload alone: leave out the 10M x 200 result, the unclustered search and the extras "
                          "(what the rocprofv3 summaries under profiles/ are taken from)")
+    ap.add_argument("--cascade-plane-check", type=int, default=0, metavar="BETA",
+                    help="only run the cascade search's pass 1 in streaming mode on 256 queries, 3 times on an index without "
+                         "and 3 times on one with a plane of the top BETA bits (for reading FETCH_SIZE of the two list scans)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy 5 times (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -584,6 +634,9 @@ def main():
         return
     if args.workload == "stream_d96":
         print(json.dumps(run_streaming(args, torch, pkg, synth)))
+        return
+    if args.cascade_plane_check:
+        print(json.dumps(run_cascade_plane_check(args, torch, pkg, synth)))
         return
     w = {"1m": synth.config_1m, "10m_d96": lambda: synth.config_10m_d96(args.bits),
          "10m_d200": synth.config_10m_d200}[args.workload]()
