@@ -16,10 +16,13 @@
 // multiplies are done and no rotated vector is ever held whole.
 //
 // Quantiser: code = #{i : rho >= tau_i} through the uniform-grid index of host_math.h (one
-// independent 8-byte LDS lookup and one comparison per coordinate, any b).  Codes are packed in
-// registers four at a time and merged into the row's words in LDS with ds_or, then written to the
-// row's storage slot.  Rows may be processed in list order (`order`), which makes the stores of a
-// wavefront land in consecutive slots.
+// independent 8-byte LDS lookup and one comparison per coordinate, any b; the comparison is taken on
+// the accumulator against the boundary times 2^20, an exact rescaling).  Codes are packed in registers
+// four at a time.  With b = 4 the two lanes of a row hold the two halves of each 32-bit word and
+// exchange them with one lane swap, with b = 8 a lane holds whole words; both store straight to the
+// row's slot.  Any other b (and an index that keeps the plane of top bits) merges the pieces into the
+// row's words in LDS with ds_or first.  Rows are processed in list order, which makes the stores of
+// a wavefront land in consecutive slots.
 #include <hip/hip_fp16.h>
 
 #include "kernels.h"
@@ -43,20 +46,23 @@ struct EncCfg {
 inline int pack_pitch(int words) { return (words + 1) | 1; }   // odd and > words: room for a spill word
 
 template <int DP>
-size_t encode_lds_bytes(int mode, int cells, int words, int head_words) {
+size_t encode_lds_bytes(int mode, int pack_b, int cells, int words, int head_words) {
     size_t bytes = EncCfg<DP>::pi_bytes;
     if (mode != 2) bytes += (size_t)cells * 8;
-    if (mode == 0) bytes += (size_t)4 * 32 * EncCfg<DP>::R * pack_pitch(words) * 4;
-    if (mode == 0 && head_words > 0) bytes += (size_t)4 * 32 * EncCfg<DP>::R * pack_pitch(head_words) * 4;
+    if (mode == 0 && pack_b == 0) bytes += (size_t)4 * 32 * EncCfg<DP>::R * pack_pitch(words) * 4;
+    if (mode == 0 && pack_b == 0 && head_words > 0) bytes += (size_t)4 * 32 * EncCfg<DP>::R * pack_pitch(head_words) * 4;
     return bytes;
 }
 
 // MODE 0: encode and store into the lists; 1: encode into flat arrays; 2: rotate queries only.  A template
-// parameter, so that each instantiation carries its own path only.
-template <int DP, int MODE>
+// parameter, so that each instantiation carries its own path only.  PACK_B (mode 0): 4 or 8 = the index
+// stores that many bits per coordinate and no plane of top bits, words are put together in registers;
+// 0 = any b, through LDS.
+template <int DP, int MODE, int PACK_B>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2)))
 void k_encode(EncodeArgs a, int flags) {
     constexpr int mode = MODE;
+    constexpr bool via_lds = MODE == 0 && PACK_B == 0;
     using Cfg = EncCfg<DP>;
     constexpr int KB = Cfg::KB, NT = Cfg::NT, R = Cfg::R, LDH = Cfg::LDH, PF = Cfg::PF;
     extern __shared__ unsigned char lds_raw[];
@@ -68,10 +74,10 @@ void k_encode(EncodeArgs a, int flags) {
     const int wave = tid >> 6, lane = tid & 63, half = lane >> 5, j = lane & 31;
     const int vec4 = flags & 1;          // rows of x can be read 16 bytes at a time
     const bool codes4 = flags & 2;       // rows of codes_flat can be written 4 bytes at a time
-    const int d = a.d, b = a.b;
+    const int d = a.d, b = PACK_B ? PACK_B : a.b;
     const int words = a.store.words;
     const int pitch = (words + 1) | 1;
-    const int head_words = (mode == 0 && a.store.head) ? a.store.head_words : 0;   // top-bit plane kept as well
+    const int head_words = (via_lds && a.store.head) ? a.store.head_words : 0;   // top-bit plane kept as well
     const int pitch_h = (head_words + 1) | 1;
     const int beta = b - a.store.head_shift;
     const int64_t pos0 = ((int64_t)blockIdx.x * 4 + wave) * (32 * R);
@@ -95,36 +101,35 @@ void k_encode(EncodeArgs a, int flags) {
         } else if (mode == 1 && valid[r]) {
             cell_of[r] = a.assign[pos];
         }
+        // A position past the end reads row 0 and an unassigned row reads centroid 0: what they compute
+        // is never stored, so nothing here is masked by validity.
         float v[KB][8];
-        load_row_blocks<KB>(a.x + row_of[r] * (int64_t)d, valid[r], d, vec4, half, v);
+        load_row_blocks<KB>(a.x + row_of[r] * (int64_t)d, true, d, vec4, half, v);
         const float n2 = row_norm2<KB>(v);
         const bool good = (n2 > 0.f) && (n2 < __builtin_inff());
         const float inv_n = good ? 1.f / sqrtf(n2) : 0.f;   // one division per row, then multiplies
-#pragma unroll
-        for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-            for (int e = 0; e < 8; ++e) v[kb][e] *= inv_n;
         gamma[r] = 0.f;
         xnorm[r] = good ? sqrtf(n2) : 0.f;
         if (mode == 2 && a.norm_out && valid[r] && half == 0) a.norm_out[row_of[r]] = xnorm[r];
+        float to_unit = inv_n;
         if (mode != 2) {
             const int cell = cell_of[r];
             float c[KB][8];
-            load_row_blocks<KB>(a.cent + (int64_t)(cell < 0 ? 0 : cell) * a.cent_pitch, cell >= 0, DP, 1, half, c);
+            load_row_blocks<KB>(a.cent + (int64_t)(cell < 0 ? 0 : cell) * a.cent_pitch, true, DP, 1, half, c);
 #pragma unroll
             for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
-                for (int e = 0; e < 8; ++e) v[kb][e] -= c[kb][e];
+                for (int e = 0; e < 8; ++e) v[kb][e] = fmaf(v[kb][e], inv_n, -c[kb][e]);      // r = x~ - c~
             const float g = sqrtf(row_norm2<KB>(v));
             // The rotation acts on the unit residual: the quantiser input does not depend on the scale
             // of r, and a unit vector keeps the split float16 form accurate however small r is.
-            const float inv_g = (g > 1e-30f) ? 1.f / g : 0.f;   // a zero residual quantises as rho = 0
-#pragma unroll
-            for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-                for (int e = 0; e < 8; ++e) v[kb][e] *= inv_g;
+            to_unit = (g > 1e-30f) ? 1.f / g : 0.f;   // a zero residual quantises as rho = 0
             gamma[r] = cell >= 0 ? g : 0.f;
         }
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[kb][e] *= to_unit;
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
@@ -138,10 +143,13 @@ void k_encode(EncodeArgs a, int flags) {
 
     // ---- LDS set-up: quantiser grid, cleared packing words, first tile of Pi
     if (mode != 2)
-        for (int e = tid; e < a.q_cells; e += 256) grid_s[e] = a.q_grid[e];
+        for (int e = tid; e < a.q_cells; e += 256) {      // boundaries in accumulator units
+            const float2 ent = a.q_grid[e];
+            grid_s[e] = make_float2(ent.x * (kSplitScale * kSplitScale), ent.y);
+        }
     uint32_t* my_pack = pack_s + (size_t)wave * (32 * R) * pitch;
     uint32_t* my_head = pack_s + (size_t)4 * (32 * R) * pitch + (size_t)wave * (32 * R) * pitch_h;
-    if (mode == 0) {
+    if (via_lds) {
         for (int e = lane; e < 32 * R * pitch; e += 64) my_pack[e] = 0u;
         if (head_words)
             for (int e = lane; e < 32 * R * pitch_h; e += 64) my_head[e] = 0u;
@@ -172,7 +180,25 @@ void k_encode(EncodeArgs a, int flags) {
 
     constexpr float kUnscale = 1.f / (kSplitScale * kSplitScale);
     const float q_scale = a.q_scale * kUnscale, q_offset = a.q_offset;
-    const int q_last = a.q_cells - 1;
+    const float q_last = (float)(a.q_cells - 1);
+
+    // mode 0 without LDS: where this lane's rows go.  Lane (j, half) stores half of the words of row j
+    // of every tile r.
+    uint32_t* direct_dst[R];
+    if (MODE == 0 && !via_lds) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int64_t pos = pos0 + 32 * r + j;
+            const int cell = cell_of[r];
+            const int64_t slot = (valid[r] && cell >= 0) ? a.list_base[cell] + (pos - a.batch_base[cell]) : -1;
+            direct_dst[r] = slot >= 0 ? a.store.codes + (slot >> 6) * (int64_t)words * 64 + (slot & 63) : nullptr;
+            if (slot >= 0 && half == 0) {
+                a.store.gamma[slot] = __half_as_ushort(__float2half_rn(gamma[r]));
+                a.store.ids[slot] = a.labels ? a.labels[row_of[r]] : a.label_base + row_of[r];
+                if (a.store.xnorm) a.store.xnorm[slot] = xnorm[r];
+            }
+        }
+    }
 
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
@@ -180,16 +206,13 @@ void k_encode(EncodeArgs a, int flags) {
         const uint16_t* ah_base = stage + (t & 1) * Cfg::stage_halves + j * LDH + 8 * half;
         const uint16_t* al_base = ah_base + 32 * LDH;
         floatx16 acc[R];
-#pragma unroll
-        for (int r = 0; r < R; ++r)
-#pragma unroll
-            for (int q = 0; q < 16; ++q) acc[r][q] = 0.f;
+        const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb) {
             const half8 ah = *reinterpret_cast<const half8*>(ah_base + 16 * kb);
             const half8 al = *reinterpret_cast<const half8*>(al_base + 16 * kb);
 #pragma unroll
-            for (int r = 0; r < R; ++r) acc[r] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah, bh[r][kb], acc[r], 0, 0, 0);
+            for (int r = 0; r < R; ++r) acc[r] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah, bh[r][kb], kb ? acc[r] : zero, 0, 0, 0);
 #pragma unroll
             for (int r = 0; r < R; ++r) acc[r] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah, bl[r][kb], acc[r], 0, 0, 0);
 #pragma unroll
@@ -223,9 +246,12 @@ void k_encode(EncodeArgs a, int flags) {
                 }
             }
         } else {
-            const bool ragged = 32 * t + 32 > d;      // some coordinates of this tile are padding
+            // d is within 32 of the padded width: only the last tile can hold padding, and only there can a
+            // word lie past the row's last one
+            const bool ragged = t == NT - 1 && 32 * t + 32 > d;
 #pragma unroll
             for (int r = 0; r < R; ++r) {
+                uint32_t chunk[4];                     // the four codes of group g, b bits each
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
                     const int c0 = 32 * t + 8 * g + 4 * half;
@@ -233,11 +259,9 @@ void k_encode(EncodeArgs a, int flags) {
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         const float av = acc[r][4 * g + e];
-                        const float rho = av * kUnscale;
-                        int cell = (int)fmaf(av, q_scale, q_offset);
-                        cell = cell < 0 ? 0 : (cell > q_last ? q_last : cell);
-                        const float2 ent = grid_s[cell];
-                        code[e] = (uint32_t)__float_as_int(ent.y) + (rho >= ent.x ? 1u : 0u);
+                        const float at = __builtin_amdgcn_fmed3f(fmaf(av, q_scale, q_offset), 0.f, q_last);
+                        const float2 ent = grid_s[(int)at];
+                        code[e] = (uint32_t)__float_as_int(ent.y) + (av >= ent.x ? 1u : 0u);
                         if (ragged && c0 + e >= d) code[e] = 0u;
                     }
                     if (mode == 1) {
@@ -251,14 +275,16 @@ void k_encode(EncodeArgs a, int flags) {
                                     if (c0 + e < d) out[e] = (uint8_t)code[e];
                             }
                         }
-                    } else {
-                        // four codes = 4b bits at bit c0*b of the row's little-endian bit string
-                        const uint32_t chunk = code[0] | (code[1] << b) | (code[2] << (2 * b)) | (code[3] << (3 * b));
+                        continue;
+                    }
+                    // four codes = 4b bits at bit c0*b of the row's little-endian bit string
+                    chunk[g] = code[0] | (code[1] << b) | (code[2] << (2 * b)) | (code[3] << (3 * b));
+                    if (via_lds) {
                         const int bit = c0 * b;
                         const int sh = bit & 31;
                         uint32_t* wp = my_pack + (32 * r + j) * pitch + (bit >> 5);
-                        const uint32_t lo = chunk << sh;
-                        const uint32_t hi = sh ? chunk >> (32 - sh) : 0u;
+                        const uint32_t lo = chunk[g] << sh;
+                        const uint32_t hi = sh ? chunk[g] >> (32 - sh) : 0u;
                         if (lo) atomicOr(wp, lo);
                         if (hi) atomicOr(wp + 1, hi);
                         if (head_words) {      // the same four codes cut down to their top beta bits, packed likewise
@@ -274,11 +300,30 @@ void k_encode(EncodeArgs a, int flags) {
                         }
                     }
                 }
+                if (MODE == 0 && PACK_B == 4) {
+                    // Word 4t + g of a row = group g of half 0 (low 16 bits) and of half 1 (high 16 bits).
+                    // v_permlane32_swap(a, b) gives lanes 0..31 (a, a of lane + 32) and lanes 32..63 (b of
+                    // lane - 32, b): with a = group g and b = group g + 2 a lane of half h ends up with both
+                    // parts of word 4t + g + 2h.
+#pragma unroll
+                    for (int g = 0; g < 2; ++g) {
+                        const auto sw = __builtin_amdgcn_permlane32_swap(chunk[g], chunk[g + 2], false, false);
+                        const uint32_t word = sw[0] | (sw[1] << 16);
+                        const int w = 4 * t + g + 2 * half;
+                        if (direct_dst[r] && (t < NT - 1 || w < words)) direct_dst[r][(int64_t)w * 64] = word;
+                    }
+                } else if (MODE == 0 && PACK_B == 8) {
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {      // a group is a whole word: 8t + 2g + half
+                        const int w = 8 * t + 2 * g + half;
+                        if (direct_dst[r] && (t < NT - 1 || w < words)) direct_dst[r][(int64_t)w * 64] = chunk[g];
+                    }
+                }
             }
         }
         if (t + 1 < NT) __syncthreads();
     }
-    if (mode == 2) return;
+    if (mode == 2 || (MODE == 0 && !via_lds)) return;
 
     if (mode == 1) {
 #pragma unroll
@@ -328,27 +373,33 @@ void k_encode(EncodeArgs a, int flags) {
 #undef IVFTQ_FETCH_TILE
 #undef IVFTQ_STORE_TILE
 
-template <int DP, int MODE>
+template <int DP, int MODE, int PACK_B>
 hipError_t run_mode(const EncodeArgs& a, hipStream_t st) {
     static LdsLimit lim;
-    const size_t lds = encode_lds_bytes<DP>(MODE, a.q_cells, a.store.words, a.store.head ? a.store.head_words : 0);
+    const size_t lds = encode_lds_bytes<DP>(MODE, PACK_B, a.q_cells, a.store.words, a.store.head ? a.store.head_words : 0);
     if (lds > 160 * 1024) return hipErrorInvalidValue;
-    const hipError_t e = lim.ensure(reinterpret_cast<const void*>(k_encode<DP, MODE>), lds);
+    const hipError_t e = lim.ensure(reinterpret_cast<const void*>(k_encode<DP, MODE, PACK_B>), lds);
     if (e != hipSuccess) return e;
     const int rows_per_wg = 4 * 32 * EncCfg<DP>::R;
     const int64_t blocks = (a.n + rows_per_wg - 1) / rows_per_wg;
     int flags = 0;
     if (a.d % 4 == 0 && reinterpret_cast<uintptr_t>(a.x) % 16 == 0) flags |= 1;
     if (a.d % 4 == 0 && reinterpret_cast<uintptr_t>(a.codes_flat) % 4 == 0) flags |= 2;
-    hipLaunchKernelGGL((k_encode<DP, MODE>), dim3((unsigned)blocks), dim3(256), lds, st, a, flags);
+    hipLaunchKernelGGL((k_encode<DP, MODE, PACK_B>), dim3((unsigned)blocks), dim3(256), lds, st, a, flags);
     return hipGetLastError();
 }
 
 template <int DP>
 hipError_t run(int mode, const EncodeArgs& a, hipStream_t st) {
-    if (mode == 0) return run_mode<DP, 0>(a, st);
-    if (mode == 1) return run_mode<DP, 1>(a, st);
-    if (mode == 2) return run_mode<DP, 2>(a, st);
+    if (mode == 0) {
+        // words put together in registers when a group of four codes is half a word or a whole one
+        // and only the codes themselves are stored
+        if (a.b == 4 && !a.store.head) return run_mode<DP, 0, 4>(a, st);
+        if (a.b == 8 && !a.store.head) return run_mode<DP, 0, 8>(a, st);
+        return run_mode<DP, 0, 0>(a, st);
+    }
+    if (mode == 1) return run_mode<DP, 1, 0>(a, st);
+    if (mode == 2) return run_mode<DP, 2, 0>(a, st);
     return hipErrorInvalidValue;
 }
 

@@ -29,7 +29,9 @@ __device__ __forceinline__ void split_scaled(float v, _Float16& hi, _Float16& lo
 
 // v[kb][e] = p[16*kb + 8*half + e] for a row of `len` floats at p (zero beyond len, or when the
 // row is not valid).  Every load is unconditional on a clamped index, so p must be readable even
-// for an invalid row.  vec4: len % 4 == 0 and p 16-byte aligned.
+// for an invalid row.  vec4: len % 4 == 0 and p 16-byte aligned.  The padded width 16*KB is the
+// smallest supported size that holds len, which is within 32 of it: only the last two blocks can
+// reach past len, the others are read without a test.
 template <int KB>
 __device__ __forceinline__ void load_row_blocks(const float* __restrict__ p, bool valid, int len, int vec4,
                                                 int half, float (&v)[KB][8]) {
@@ -42,8 +44,9 @@ __device__ __forceinline__ void load_row_blocks(const float* __restrict__ p, boo
             for (int e = 0; e < 2; ++e) {
                 const int c = 16 * kb + 8 * half + 4 * e;
                 const int i4 = c / 4;
-                const float4 t = q[i4 < last4 ? i4 : last4];
-                const bool in = valid && c < len;
+                const bool inside = 16 * kb + 16 <= 16 * KB - 32;      // known when the kernel is compiled
+                const float4 t = q[(inside || i4 < last4) ? i4 : last4];
+                const bool in = valid && (inside || c < len);
                 v[kb][4 * e] = in ? t.x : 0.f; v[kb][4 * e + 1] = in ? t.y : 0.f;
                 v[kb][4 * e + 2] = in ? t.z : 0.f; v[kb][4 * e + 3] = in ? t.w : 0.f;
             }
@@ -53,8 +56,9 @@ __device__ __forceinline__ void load_row_blocks(const float* __restrict__ p, boo
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const int c = 16 * kb + 8 * half + e;
-                const float t = p[c < len ? c : len - 1];
-                v[kb][e] = (valid && c < len) ? t : 0.f;
+                const bool inside = 16 * kb + 16 <= 16 * KB - 32;
+                const float t = p[(inside || c < len) ? c : len - 1];
+                v[kb][e] = (valid && (inside || c < len)) ? t : 0.f;
             }
     }
 }
