@@ -593,8 +593,8 @@ def run_cascade_plane_check(args, torch, pkg, synth):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=5)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--nprobe", type=int, default=None, help="primary nprobe (default: the workload's second value, 32 for 1m and 10m_d96)")
     ap.add_argument("--workload", default="10m_d96", choices=["1m", "10m_d96", "10m_d200", "stream_d96"],
                     help="10m_d96 is the benchmark workload; stream_d96 is the streaming-ingest run (1M rows, then 100k-row batches)")

@@ -25,6 +25,8 @@
 // a wavefront land in consecutive slots.
 #include <hip/hip_fp16.h>
 
+#include <algorithm>
+
 #include "kernels.h"
 #include "split_f16.h"
 
@@ -373,6 +375,170 @@ void k_encode(EncodeArgs a, int flags) {
 #undef IVFTQ_FETCH_TILE
 #undef IVFTQ_STORE_TILE
 
+// Encode-and-store for the common shapes (d <= 128 read 16 bytes at a time, 4 or 8 stored bits, no plane
+// of top bits): the same arithmetic as k_encode mode 0, organised so that nothing waits on anything else.
+// All of Pi (both float16 parts) stays in LDS for the life of the workgroup, so after the one barrier
+// that follows its load the four wavefronts run on their own.  A wavefront walks 32-row tiles
+// tile, tile + stride, ...; while it multiplies and quantises one tile the rows of its next tile are
+// already on their way into registers (their positions were fetched a tile earlier still), so the row
+// reads from HBM are in flight all the time instead of once per workgroup start.
+template <int DP>
+constexpr size_t resident_lds_bytes(int cells) { return (size_t)2 * DP * EncCfg<DP>::LDH * sizeof(uint16_t) + (size_t)cells * 8; }
+
+template <int DP, int PACK_B>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(DP <= 96 ? 3 : 2)))
+void k_encode_resident(EncodeArgs a, int64_t tiles) {
+    using Cfg = EncCfg<DP>;
+    constexpr int KB = Cfg::KB, NT = Cfg::NT, LDH = Cfg::LDH, b = PACK_B;
+    extern __shared__ unsigned char lds_raw[];
+    uint16_t* pi_hs = reinterpret_cast<uint16_t*>(lds_raw);                   // [DP][LDH] leading parts
+    uint16_t* pi_ls = pi_hs + DP * LDH;                                        // [DP][LDH] trailing parts
+    float2* grid_s = reinterpret_cast<float2*>(lds_raw + (size_t)2 * DP * LDH * sizeof(uint16_t));
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6, lane = tid & 63, half = lane >> 5, j = lane & 31;
+    const int d = a.d, words = a.store.words;
+    const int last4 = d / 4 - 1;
+
+    for (int e = tid; e < DP * (DP / 8); e += 256) {
+        const int r = e / (DP / 8), c8 = e % (DP / 8);
+        *reinterpret_cast<uint4*>(pi_hs + r * LDH + c8 * 8) = *reinterpret_cast<const uint4*>(a.pi_h + (int64_t)r * DP + c8 * 8);
+        *reinterpret_cast<uint4*>(pi_ls + r * LDH + c8 * 8) = *reinterpret_cast<const uint4*>(a.pi_l + (int64_t)r * DP + c8 * 8);
+    }
+    for (int e = tid; e < a.q_cells; e += 256) {          // boundaries in accumulator units
+        const float2 ent = a.q_grid[e];
+        grid_s[e] = make_float2(ent.x * (kSplitScale * kSplitScale), ent.y);
+    }
+    __syncthreads();
+
+    constexpr float kUnscale = 1.f / (kSplitScale * kSplitScale);
+    const float q_scale = a.q_scale * kUnscale, q_offset = a.q_offset;
+    const float q_last = (float)(a.q_cells - 1);
+    const int64_t stride = (int64_t)gridDim.x * 4;
+    int64_t tile = (int64_t)blockIdx.x * 4 + wave;
+
+    // (row, cell) of this lane's position in a tile; a position past the end reads row 0 and stores nothing
+    auto position = [&](int64_t t) {
+        const int64_t pos = t * 32 + j;
+        return (t < tiles && pos < a.n) ? a.order_cell[pos] : make_int2(0, -1);
+    };
+    // the lane's 16-byte pieces of a row: coordinates 16*kb + 8*half + 4*e (clamped inside the row)
+    float4 xr[KB][2];
+    auto fetch_row = [&](int row) {
+        const float4* q = reinterpret_cast<const float4*>(a.x + (int64_t)row * d);
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                const int i4 = (16 * kb + 8 * half + 4 * e) / 4;
+                const bool inside = 16 * kb + 16 <= 16 * KB - 32;
+                xr[kb][e] = q[(inside || i4 < last4) ? i4 : last4];
+            }
+    };
+    int2 oc = position(tile);
+    fetch_row(oc.x);
+    int2 oc_next = position(tile + stride);
+
+    for (; tile < tiles; tile += stride) {
+        const int64_t pos = tile * 32 + j;
+        const int row = oc.x, cell = oc.y;
+        // ---- x~, residual against the assigned centroid, gamma, split unit residual
+        float v[KB][8];
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                const int c = 16 * kb + 8 * half + 4 * e;
+                const bool in = 16 * kb + 16 <= 16 * KB - 32 || c < d;
+                v[kb][4 * e] = in ? xr[kb][e].x : 0.f; v[kb][4 * e + 1] = in ? xr[kb][e].y : 0.f;
+                v[kb][4 * e + 2] = in ? xr[kb][e].z : 0.f; v[kb][4 * e + 3] = in ? xr[kb][e].w : 0.f;
+            }
+        const float n2 = row_norm2<KB>(v);
+        const bool good = (n2 > 0.f) && (n2 < __builtin_inff());
+        const float inv_n = good ? 1.f / sqrtf(n2) : 0.f;
+        float c[KB][8];
+        load_row_blocks<KB>(a.cent + (int64_t)(cell < 0 ? 0 : cell) * a.cent_pitch, true, DP, 1, half, c);
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[kb][e] = fmaf(v[kb][e], inv_n, -c[kb][e]);          // r = x~ - c~
+        const float g = sqrtf(row_norm2<KB>(v));
+        const float to_unit = (g > 1e-30f) ? 1.f / g : 0.f;       // a zero residual quantises as rho = 0
+        half8 bh[KB], bl[KB];
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                _Float16 h, l;
+                const float u = v[kb][e] * to_unit;
+                split_scaled(u, h, l);
+                bh[kb][e] = h;
+                bl[kb][e] = l;
+            }
+        const int64_t slot = cell >= 0 ? a.list_base[cell] + (pos - a.batch_base[cell]) : -1;
+        uint32_t* dst = slot >= 0 ? a.store.codes + (slot >> 6) * (int64_t)words * 64 + (slot & 63) : nullptr;
+        if (slot >= 0 && half == 0) {
+            a.store.gamma[slot] = __half_as_ushort(__float2half_rn(g));
+            a.store.ids[slot] = a.labels ? a.labels[row] : a.label_base + row;
+            if (a.store.xnorm) a.store.xnorm[slot] = good ? sqrtf(n2) : 0.f;
+        }
+
+        // ---- the next tile's rows set off now and arrive while this tile is multiplied and quantised
+        oc = oc_next;
+        fetch_row(oc.x);
+        oc_next = position(tile + 2 * stride);
+
+        // This lane's place in a tile of Pi is the same for every row tile; hidden from the compiler, which
+        // would otherwise read all of Pi into registers once, ahead of the loop, and spill.
+        int pi_at = j * LDH + 8 * half;
+        asm volatile("" : "+v"(pi_at));
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            const uint16_t* ah_base = pi_hs + t * 32 * LDH + pi_at;
+            const uint16_t* al_base = pi_ls + t * 32 * LDH + pi_at;
+            floatx16 acc;
+            const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb) {
+                const half8 ah = *reinterpret_cast<const half8*>(ah_base + 16 * kb);
+                const half8 al = *reinterpret_cast<const half8*>(al_base + 16 * kb);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah, bh[kb], kb ? acc : zero, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah, bl[kb], acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(al, bh[kb], acc, 0, 0, 0);
+            }
+            const bool ragged = t == NT - 1 && 32 * t + 32 > d;      // only the last tile can hold padding
+            uint32_t chunk[4];
+#pragma unroll
+            for (int g4 = 0; g4 < 4; ++g4) {
+                const int c0 = 32 * t + 8 * g4 + 4 * half;
+                uint32_t code[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float av = acc[4 * g4 + e];
+                    const float at = __builtin_amdgcn_fmed3f(fmaf(av, q_scale, q_offset), 0.f, q_last);
+                    const float2 ent = grid_s[(int)at];
+                    code[e] = (uint32_t)__float_as_int(ent.y) + (av >= ent.x ? 1u : 0u);
+                    if (ragged && c0 + e >= d) code[e] = 0u;
+                }
+                chunk[g4] = code[0] | (code[1] << b) | (code[2] << (2 * b)) | (code[3] << (3 * b));
+            }
+            if (PACK_B == 4) {           // see k_encode: a lane of half h ends up with both parts of word 4t + g + 2h
+#pragma unroll
+                for (int g4 = 0; g4 < 2; ++g4) {
+                    const auto sw = __builtin_amdgcn_permlane32_swap(chunk[g4], chunk[g4 + 2], false, false);
+                    const int w = 4 * t + g4 + 2 * half;
+                    if (dst && (t < NT - 1 || w < words)) dst[(int64_t)w * 64] = sw[0] | (sw[1] << 16);
+                }
+            } else {
+#pragma unroll
+                for (int g4 = 0; g4 < 4; ++g4) {
+                    const int w = 8 * t + 2 * g4 + half;
+                    if (dst && (t < NT - 1 || w < words)) dst[(int64_t)w * 64] = chunk[g4];
+                }
+            }
+        }
+    }
+}
+
 template <int DP, int MODE, int PACK_B>
 hipError_t run_mode(const EncodeArgs& a, hipStream_t st) {
     static LdsLimit lim;
@@ -389,9 +555,38 @@ hipError_t run_mode(const EncodeArgs& a, hipStream_t st) {
     return hipGetLastError();
 }
 
+template <int DP, int PACK_B>
+hipError_t run_resident(const EncodeArgs& a, hipStream_t st) {
+    static LdsLimit lim;
+    static int units[16] = {0};         // compute units per device, asked once
+    const size_t lds = resident_lds_bytes<DP>(a.q_cells);
+    if (lds > 160 * 1024) return hipErrorInvalidValue;
+    hipError_t e = lim.ensure(reinterpret_cast<const void*>(k_encode_resident<DP, PACK_B>), lds);
+    if (e != hipSuccess) return e;
+    int dev = 0;
+    if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
+    int cus = (dev >= 0 && dev < 16) ? units[dev] : 0;
+    if (cus <= 0) {
+        if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
+        if (dev >= 0 && dev < 16) units[dev] = cus;
+    }
+    const int64_t tiles = (a.n + 31) / 32;
+    const int64_t resident = (int64_t)cus * (160 * 1024 / lds < 3 ? 160 * 1024 / lds : 3);   // workgroups the chip holds at once
+    const int64_t blocks = std::min<int64_t>((tiles + 3) / 4, resident);
+    hipLaunchKernelGGL((k_encode_resident<DP, PACK_B>), dim3((unsigned)blocks), dim3(256), lds, st, a, tiles);
+    return hipGetLastError();
+}
+
 template <int DP>
 hipError_t run(int mode, const EncodeArgs& a, hipStream_t st) {
     if (mode == 0) {
+        if constexpr (DP <= 128) {
+            const bool vec4 = a.d % 4 == 0 && reinterpret_cast<uintptr_t>(a.x) % 16 == 0;
+            if (vec4 && !a.store.head && a.n < (int64_t)1 << 31) {
+                if (a.b == 4) return run_resident<DP, 4>(a, st);
+                if (a.b == 8) return run_resident<DP, 8>(a, st);
+            }
+        }
         // words put together in registers when a group of four codes is half a word or a whole one
         // and only the codes themselves are stored
         if (a.b == 4 && !a.store.head) return run_mode<DP, 0, 4>(a, st);
