@@ -197,6 +197,7 @@ __device__ __forceinline__ uint32_t order_key(float f) {
 
 constexpr int kSelU = 8;        // groups of 64 columns loaded together by k_select
 constexpr int kSelSmallU = 4;   // and by k_select_small beyond its registers
+constexpr int kSelCand = 512;   // most keys the short cut of k_select sorts directly
 
 // COPIES: counters per digit in the histogram (a power of two; 8 pays for long rows, 1 for short ones, where
 // clearing and summing the copies costs more than the collisions they avoid).
@@ -214,6 +215,8 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a) {
     uint32_t* s_key = wave_cnt + 4;                                   // [kpad]
     uint32_t* s_col = s_key + kpad;                                   // [kpad]
     int64_t* s_lab = reinterpret_cast<int64_t*>(s_col + kpad);   // [kpad], 8-byte aligned: 268 + 2*kpad words
+    uint32_t* c_key = reinterpret_cast<uint32_t*>(s_lab + kpad);      // [kSelCand] keys of the short cut ...
+    uint32_t* c_col = c_key + kSelCand;                               // [kSelCand] ... and their columns
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     // gate (may be null): a.gate[0] rows, listed in a.gate[1..], are processed instead of all
@@ -237,7 +240,94 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a) {
     const int w_end = (w_begin + chunk < m) ? w_begin + chunk : m;
     uint32_t prefix = 0, mask = 0;
     uint32_t need = (uint32_t)take;
-    if (take > 0 && m > k) {
+    // Short cut.  Every thread takes the largest key of the columns tid, tid + 256, ...; at least `take`
+    // values reach the take-th largest of these 256 maxima, so it is a lower bound of the take-th largest
+    // value, and with the columns dealt out round-robin about -256 ln(1 - take/256) values reach it
+    // whatever the row looks like (127 for take = 100, 355 for 192; beyond that too many).  Those are gathered and sorted by (key desc, column asc): the first
+    // `take` of them are the winners the radix search below would pick (same rule for keys equal to the
+    // last one).  Two reads of the row instead of six; if more than kSelCand values reach the bound the
+    // radix search runs after all.
+    bool picked = false;
+    if (take > 0 && m > k && take <= 192 && m >= 2048) {
+        uint32_t best = 0;            // below every key of a number
+        for (int i0 = 0; i0 < m; i0 += 256 * kSelU) {
+            float v[kSelU];
+#pragma unroll
+            for (int u = 0; u < kSelU; ++u) {
+                const int i = i0 + 256 * u + tid;
+                v[u] = vals[i < m ? i : m - 1];
+            }
+#pragma unroll
+            for (int u = 0; u < kSelU; ++u) {
+                const uint32_t key = order_key(v[u]);
+                if (i0 + 256 * u + tid < m && key > best) best = key;
+            }
+        }
+        c_key[tid] = best;
+        if (tid == 0) { ctrl[4] = 0; ctrl[5] = 0; }
+        __syncthreads();
+        // rank of this thread's maximum among the 256 (larger first, thread number breaks ties)
+        uint32_t rank = 0;
+        for (int j = 0; j < 256; j += 4) {
+            const uint4 o = *reinterpret_cast<const uint4*>(c_key + j);
+            rank += (o.x > best || (o.x == best && j < tid)) ? 1u : 0u;
+            rank += (o.y > best || (o.y == best && j + 1 < tid)) ? 1u : 0u;
+            rank += (o.z > best || (o.z == best && j + 2 < tid)) ? 1u : 0u;
+            rank += (o.w > best || (o.w == best && j + 3 < tid)) ? 1u : 0u;
+        }
+        if (rank == (uint32_t)take - 1u) ctrl[4] = best;
+        __syncthreads();
+        const uint32_t bound = ctrl[4];
+        __syncthreads();               // the maxima are no longer read: c_key is filled anew
+        for (int i0 = 0; i0 < m; i0 += 256 * kSelU) {
+            float v[kSelU];
+#pragma unroll
+            for (int u = 0; u < kSelU; ++u) {
+                const int i = i0 + 256 * u + tid;
+                v[u] = vals[i < m ? i : m - 1];
+            }
+#pragma unroll
+            for (int u = 0; u < kSelU; ++u) {
+                const int i = i0 + 256 * u + tid;
+                const uint32_t key = order_key(v[u]);
+                if (i < m && key >= bound) {
+                    const uint32_t pos = atomicAdd(&ctrl[5], 1u);
+                    if (pos < (uint32_t)kSelCand) { c_key[pos] = key; c_col[pos] = (uint32_t)i; }
+                }
+            }
+        }
+        __syncthreads();
+        const uint32_t found = ctrl[5];
+        if (found <= (uint32_t)kSelCand) {          // uniform over the workgroup
+            int cpad = 1;
+            while (cpad < (int)found) cpad <<= 1;
+            for (int i = (int)found + tid; i < cpad; i += 256) { c_key[i] = 0u; c_col[i] = 0xFFFFFFFFu; }
+            __syncthreads();
+            for (int size = 2; size <= cpad; size <<= 1) {
+                for (int stride = size >> 1; stride > 0; stride >>= 1) {
+                    for (int i = tid; i < cpad / 2; i += 256) {
+                        const int lo_i = 2 * i - (i & (stride - 1));
+                        const int hi_i = lo_i + stride;
+                        const bool up = ((lo_i & size) == 0);
+                        const uint32_t k0 = c_key[lo_i], k1 = c_key[hi_i];
+                        const uint32_t c0 = c_col[lo_i], c1 = c_col[hi_i];
+                        const bool first_before = (k0 > k1) || (k0 == k1 && c0 <= c1);
+                        if (first_before != up) {
+                            c_key[lo_i] = k1; c_key[hi_i] = k0;
+                            c_col[lo_i] = c1; c_col[hi_i] = c0;
+                        }
+                    }
+                    __syncthreads();
+                }
+            }
+            for (int i = tid; i < take; i += 256) { s_key[i] = c_key[i]; s_col[i] = c_col[i]; }
+            picked = true;
+        }
+        __syncthreads();
+    }
+    if (picked) {
+        // winners are in place
+    } else if (take > 0 && m > k) {
         for (int pass = 0; pass < 4; ++pass) {
             const int shift = 24 - 8 * pass;
 #pragma unroll
@@ -301,7 +391,7 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a) {
     if (tid == 0) { ctrl[2] = 0; ctrl[3] = 0; }
     __syncthreads();
     const uint32_t n_above = (uint32_t)take - need;
-    if (take > 0) {
+    if (take > 0 && !picked) {
         // Keys above the threshold go anywhere in the first n_above places (atomic counter).  Keys equal to it
         // are taken in column order: each wavefront owns a contiguous quarter of the row, counts its ties in a
         // first sweep and, once the counts of the wavefronts before it are known, places them in a second.
@@ -951,7 +1041,7 @@ hipError_t launch_select(int mode, const SelectArgs& a_in, hipStream_t st) {
     int kpad = 1;
     while (kpad < a.k) kpad <<= 1;
     const int copies = (m_bound == 0 || m_bound > 8192) ? 8 : 1;
-    const size_t lds = (256 * copies + 8 + 4) * 4 + (size_t)kpad * 8 + 8 + (size_t)kpad * 8;
+    const size_t lds = (256 * copies + 8 + 4) * 4 + (size_t)kpad * 8 + 8 + (size_t)kpad * 8 + (size_t)kSelCand * 8;
     const unsigned wgs = (unsigned)(a.gate ? std::min<int64_t>(std::min<int64_t>(a.rows, a.gate_rows), 256) : a.rows);
     if (copies == 8) {
         if (mode == 0) hipLaunchKernelGGL((k_select<0, 8>), dim3(wgs), dim3(256), lds, st, a);

@@ -1,0 +1,59 @@
+"""Probe selection over thousands of cells with large nprobe (figure "Architecture", Search: the nprobe
+cells with the largest coarse scores), through `ivftq_coarse_probe`: the workgroup-per-row selection kernel
+with and without its short cut, against a float64 sort.  Half of the centroids are exact copies of others,
+so scores tie exactly across the cut and the rule "smallest cell number wins" is visible."""
+import numpy as np
+import pytest
+
+from oracle import ivftq_oracle as orc
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+TOL = 1e-5
+
+
+@pytest.mark.parametrize("L,nprobe", [(4096, 100), (4096, 128), (4096, 192), (4096, 200), (4096, 256), (2500, 150), (9000, 96)])
+def test_probe_selection_with_exact_ties(L, nprobe):
+    import paper_2605_17415_amd as pkg
+    d, nq = 32, 300
+    rs = np.random.Generator(np.random.Philox(key=[L, nprobe]))
+    base = rs.standard_normal((L // 2, d))
+    C = np.concatenate([base, base[: L - L // 2]])              # cell i + L/2 is a copy of cell i
+    C = (C / np.linalg.norm(C, axis=1, keepdims=True)).astype(np.float32)
+    Q = rs.standard_normal((nq, d)).astype(np.float32)
+    ix = pkg.Index(d, 4, L)
+    ix.set_coarse(C)
+    print(f"[select] L={L} nprobe={nprobe}", flush=True)
+    probe, coarse = ix.coarse_probe(torch.from_numpy(Q).to(DEV), nprobe)
+    torch.cuda.synchronize()
+    probe, coarse = probe.cpu().numpy(), coarse.cpu().numpy()
+    S = orc.normalize_rows(Q) @ orc.normalize_rows(C).T           # float64
+    rows = np.arange(nq)[:, None]
+    np.testing.assert_allclose(coarse, S[rows, probe], rtol=1e-5, atol=1e-6)
+    assert np.all(np.diff(coarse, axis=1) <= 0), "scores not descending"
+    half = L // 2
+    swaps = 0
+    for qi in range(nq):
+        got = probe[qi]
+        assert len(set(got.tolist())) == nprobe, "a cell is listed twice"
+        order = np.argsort(-S[qi], kind="stable")                 # score descending, cell number ascending
+        want = order[:nprobe]
+        kth = S[qi, want[-1]]
+        if set(got.tolist()) != set(want.tolist()):
+            # only cells whose score is within the tolerance of the cut may differ
+            for cell in set(got.tolist()) ^ set(want.tolist()):
+                assert abs(S[qi, cell] - kth) < TOL, f"query {qi}: cell {cell} differs away from the cut"
+            swaps += 1
+        # exact ties: a copy is never chosen without its original (the smaller number)
+        chosen = set(got.tolist())
+        for cell in got:
+            if cell >= half:
+                assert int(cell) - half in chosen, f"query {qi}: copy {cell} chosen without cell {cell - half}"
+        # equal scores are listed by ascending cell number
+        for a, b, ca, cb in zip(coarse[qi][:-1], coarse[qi][1:], got[:-1], got[1:]):
+            if a == b:
+                assert ca < cb, f"query {qi}: tied cells {ca}, {cb} out of order"
+    print(f"  rows whose set differs within the tolerance of the cut: {swaps} of {nq}", flush=True)
+    ix.close()
