@@ -68,3 +68,46 @@ def test_random_shape_matches_oracle(seed):
         print(f"search mode {mode}:", rs, flush=True)
         assert rs["probe_near_tie_excused"] <= max(1, nq // 10)
     ix.close()
+
+
+@pytest.mark.parametrize("d,b,L,n", [(32, 4, 5, 700), (64, 8, 33, 2100), (64, 4, 64, 4097), (96, 8, 31, 1500), (100, 4, 20, 2500),
+                                     (128, 8, 64, 3000), (128, 4, 129, 5000), (70, 4, 17, 900), (200, 8, 40, 1800), (160, 4, 9, 1000),
+                                     (96, 3, 32, 2000), (96, 5, 32, 2000), (255, 4, 12, 640), (24, 8, 3, 333)])
+def test_encode_add_stores_what_encode_only_returns(d, b, L, n):
+    """Every way the encode-and-store kernels put codes together (words assembled in registers for 4 and 8
+    bits, with the rotation resident in LDS up to 128 dimensions and streamed beyond, through LDS for other
+    bit widths; 16-byte and scalar row reads; padded last tiles) must store, list by list and in arrival
+    order, exactly the cell, codes and norm that `ivftq_encode_only` returns for the same rows, which the test
+    above holds against the oracle; two batches, the second ragged."""
+    import paper_2605_17415_amd as pkg
+    print(f"[encode_add vs encode_only] d={d} b={b} L={L} n={n}", flush=True)
+    rng = np.random.default_rng(d * 1000 + b * 10 + L)
+    means = rng.standard_normal((max(2, L), d))
+    X = (means[rng.integers(0, len(means), n)] + 0.5 * rng.standard_normal((n, d))).astype(np.float32)
+    cent, _ = orc.train_coarse(X, L, 1, synth.kmeans_init_indices(d + b, n, L))
+    Pi = orc.haar_rotation_from_gaussian(synth.gaussian_matrix(d + b, d)).astype(np.float32)
+    c, tau = orc.codebook_fp32(b, d)
+    enc = orc.encode(X, cent.astype(np.float32), Pi, tau)
+    dev = torch.device("cuda:0")
+    ix = pkg.Index(d, b, L)
+    ix.set_coarse(cent.astype(np.float32))
+    ix.set_rotation(Pi)
+    x = torch.from_numpy(X).to(dev)
+    assign, codes, gamma = ix.encode_only(x)
+    torch.cuda.synchronize()
+    assign, codes, gamma = assign.cpu().numpy(), codes.cpu().numpy(), gamma.cpu().numpy()
+    print("encode:", parity.compare_encode(enc, assign, codes, gamma, max_excused=L), flush=True)
+    cut = n // 2 + 13
+    ix.encode_add(x[:cut])
+    ix.encode_add(x[cut:])
+    assert ix.ntotal() == n
+    seen = 0
+    for l in range(L):
+        ids, lc, lg = ix.export_list(l)
+        want = np.flatnonzero(assign == l)
+        np.testing.assert_array_equal(ids, want)                        # arrival order
+        np.testing.assert_array_equal(lc, codes[want])
+        np.testing.assert_array_equal(lg.view(np.uint16), gamma[want].view(np.uint16))
+        seen += len(ids)
+    assert seen == n
+    ix.close()
