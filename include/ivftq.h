@@ -264,10 +264,11 @@ ivftq_status ivftq_export_list(const ivftq_index* index, int list, int64_t* ids_
 /* Bytes of device memory the stored vectors occupy (codes + norms + labels, without slack; with a raw
  * metric 4 more per vector). */
 int64_t ivftq_index_bytes(const ivftq_index* index);
-/* Scan strategy of ivftq_search: 0 = default (the query-batched matrix-core scan whenever (d, b) is
- * one of its instantiated shapes and nprobe > 1, else the streaming scan), 1 = streaming scan only
- * (one workgroup per query and probed list), 2 = same as 0 (kept for callers that set it).  Results
- * obey the same contract in every mode. */
+/* Scan strategy of ivftq_search: 0 = default (the query-batched matrix-core scan when (d, b) is one
+ * of its instantiated shapes, nprobe > 1 and the call brings at least 128 queries, else the streaming
+ * scan, whose shorter chain of kernels is faster for a handful of queries), 1 = streaming scan only
+ * (one workgroup per query and probed list), 2 = the batched scan wherever the shape allows, whatever
+ * the number of queries.  Results obey the same contract in every mode. */
 ivftq_status ivftq_set_search_mode(ivftq_index* index, int mode);
 /* Raw metrics.  The paper puts every vector on the unit sphere (Section "Architecture", Indexing), where
  * inner product, cosine and L2 rank alike; this switch serves inputs whose lengths matter, with nothing

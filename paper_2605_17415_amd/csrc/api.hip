@@ -1343,12 +1343,17 @@ ivftq_status search_core(ivftq_index* ix, const float* q_dev, int64_t nq, int np
 
     // Scan strategy.  Streaming: one workgroup per (query, probed list), every score written, exact
     // selection.  Batched: pairs regrouped by list and scanned on the matrix cores against a
-    // threshold from each query's nearest lists.  Measured (1M x 128, nprobe 32) the batched path wins
-    // at every batch size down to one query (0.10 ms against 0.24 ms), because it de-quantises two codes
-    // per table look-up and leaves the sums to the matrix pipe, so it is taken whenever the shape is covered.
+    // threshold from each query's nearest lists.  The batched path reads a list once per 128 queries
+    // instead of once per query, but it is a chain of about fourteen kernels: below kBatchedMinQueries
+    // the streaming scan's shorter chain finishes first (measured with nprobe 32 / 32 / 64 at 1M x 128,
+    // 10M x 96 and 10M x 200: 64 queries 0.12 / 0.22 / 0.57 ms streaming against 0.16 / 0.29 / 0.59 ms
+    // batched, 256 queries 0.22 / 0.44 / 1.33 against 0.18 / 0.40 / 0.86 ms).  Mode 2 asks for the batched
+    // path whatever the number of queries.
+    constexpr int64_t kBatchedMinQueries = 128;
     const int tq = batch_tile_queries(ix->d, bits);
     const int metric = ix->metric;      // a raw metric ranks by a per-vector transform of the estimate: streaming scan only
-    const bool batched = tq > 0 && nprobe > 1 && ix->search_mode != 1 && metric == IVFTQ_METRIC_COSINE;
+    const bool batched = tq > 0 && nprobe > 1 && ix->search_mode != 1 && metric == IVFTQ_METRIC_COSINE &&
+                         (ix->search_mode == 2 || nq >= kBatchedMinQueries);
     const int cap = std::min(2048, std::max(512, 16 * k));
     // error bound of a residual sum taken from the leading float16 parts alone (threshold pass)
     float cmax = 0.f;

@@ -83,6 +83,7 @@ def test_refusing_callback_gives_oom_and_leaves_the_index_unchanged():
     ix = pkg.Index(cs.d, cs.b_stage1, cs.nlist, sign_bit=cs.sign_bit, allocator=al.pair())
     ix.set_coarse(cs.cent)
     ix.set_rotation(cs.Pi)
+    ix.set_search_mode(2)          # the batched scan (its candidate buffers grow with k) although the case has few queries
     x = torch.from_numpy(cs.X).to(DEV)
     q = torch.from_numpy(cs.Q).to(DEV)
     half = len(cs.X) // 2
@@ -111,6 +112,7 @@ def test_refusing_callback_gives_oom_and_leaves_the_index_unchanged():
     ref = pkg.Index(cs.d, cs.b_stage1, cs.nlist, sign_bit=cs.sign_bit, allocator="hip")
     ref.set_coarse(cs.cent)
     ref.set_rotation(cs.Pi)
+    ref.set_search_mode(2)
     ref.encode_add(x)
     s2, i2 = ix.search(q, cs.nprobe, cs.k)
     s3, i3 = ref.search(q, cs.nprobe, cs.k)

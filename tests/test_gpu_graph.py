@@ -12,8 +12,10 @@ torch = pytest.importorskip("torch")
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("nq", [1, 48])
-def test_search_replays_from_a_graph(nq):
+@pytest.mark.parametrize("nq,mode", [(1, 0), (48, 0), (48, 2), (1, 2), (130, 0)])
+def test_search_replays_from_a_graph(nq, mode):
+    """mode 0 takes the streaming scan below 128 queries and the batched scan from there on; mode 2 the batched
+    scan at any size."""
     import paper_2605_17415_amd as pkg
     cs = gpu_cases.get_case("d128")
     dev = torch.device("cuda:0")
@@ -21,6 +23,7 @@ def test_search_replays_from_a_graph(nq):
     ix.set_coarse(cs.cent)
     ix.set_rotation(cs.Pi)
     ix.encode_add(torch.from_numpy(cs.X).to(dev))
+    ix.set_search_mode(mode)
     Q = torch.from_numpy(cs.Q).to(dev)
     q = Q[:nq].clone()
     out_s = torch.empty((nq, cs.k), dtype=torch.float32, device=dev)
@@ -28,7 +31,7 @@ def test_search_replays_from_a_graph(nq):
     ix.search(Q[:200], max(1, cs.nprobe // 2), cs.k)                     # eager, every shape used below: sizes the workspace
     ix.search(q, cs.nprobe, cs.k, out_scores=out_s, out_ids=out_i)
     torch.cuda.synchronize()
-    print(f"[graph] capture nq={nq}", flush=True)
+    print(f"[graph] capture nq={nq} mode={mode}", flush=True)
     g = torch.cuda.CUDAGraph()
     with torch.cuda.graph(g):
         ix.search(q, cs.nprobe, cs.k, out_scores=out_s, out_ids=out_i, stream=torch.cuda.current_stream())

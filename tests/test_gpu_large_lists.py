@@ -60,7 +60,7 @@ def test_many_cells_match_oracle(case):
     ix.add_encoded(torch.from_numpy(enc["assign"]).to(dev), torch.from_numpy(enc["codes"]).to(dev),
                    torch.from_numpy(enc["gamma16"]).to(dev))
     q = torch.from_numpy(Q).to(dev)
-    for mode in (0, 1):
+    for mode in (2, 1):
         print(f"[large lists] GPU search mode {mode}", flush=True)
         ix.set_search_mode(mode)
         sc, ids = ix.search(q, nprobe, k)

@@ -178,6 +178,7 @@ def test_many_overflowing_queries_take_turns_in_the_full_length_rows():
     ref.add_encoded(assign, np.arange(len(assign), dtype=np.int64), codes, gamma)
     o_sc, o_ids, _, S_all, o_all = orc.search(ref, Q, 8, 10, return_all=True)
     ix = _make_index(cs)
+    ix.set_search_mode(2)                  # the batched scan, although the call brings only twelve queries
     ix.add_encoded(torch.from_numpy(assign).to(dev), torch.from_numpy(codes).to(dev), torch.from_numpy(gamma).to(dev))
     ix.set_workspace_limit(1 << 20)        # 3 rows of 8 lists' length, 12 queries in one pass
     print("[turns] search", flush=True)

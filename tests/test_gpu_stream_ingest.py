@@ -81,7 +81,7 @@ def test_appended_batches_against_bulk_add_and_oracle():
         # search over identical stored codes against the oracle's search, both scan paths
         o_sc, o_ids, _, S, o_all = orc.search(ref, Q, NPROBE, K, return_all=True)
         gap = parity.probe_cut_gap(S, NPROBE)
-        for mode in (0, 1):
+        for mode in (2, 1):
             stored.set_search_mode(mode)
             sc, ids = stored.search(qd, NPROBE, K)
             torch.cuda.synchronize()
