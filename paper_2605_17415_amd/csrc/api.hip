@@ -183,6 +183,7 @@ struct ivftq_index {
     DevBuf t_cent, t_cent_h, t_cent_l, t_bias;   // k-means works on its own tables; the index's change only on success
     DevBuf w_zh, w_zl;
     DevBuf w_first, w_fscores, w_fids, w_pairs, w_pairoff, w_tileoff, w_cscore, w_cslot, w_ccnt, w_gate;
+    DevBuf w_stage_s, w_stage_i;      // survivors of the first step of a selection in two steps
     int64_t last_batched_queries = 0;   // queries of the last pass of the most recent batched search (ivftq_scan_stats)
     int search_mode = 0;   // 0 auto, 1 streaming scan only, 2 batched scan whenever the shape allows
     int64_t ws_limit = (int64_t)4 << 30;
@@ -196,7 +197,7 @@ struct ivftq_index {
                 &w_slot, &w_order, &w_hist, &w_count, &w_base, &w_flag, &w_best, &w_undecided, &cb_cascade, &w_keep, &w_keep_scores,
                 &w_S, &w_probe, &w_coarse, &w_z, &w_candoff, &w_scores, &w_sums, &w_counts, &w_zero, &w_rows, &w_dst, &w_obj,
                 &t_cent, &t_cent_h, &t_cent_l, &t_bias, &w_first, &w_fscores, &w_fids, &w_pairs, &w_pairoff, &w_tileoff, &w_cscore,
-                &w_cslot, &w_ccnt, &w_gate, &w_zh, &w_zl};
+                &w_cslot, &w_ccnt, &w_gate, &w_zh, &w_zl, &w_stage_s, &w_stage_i};
     }
     explicit ivftq_index(const Allocator& a) : alloc(a) {
         for (DevBuf* bfr : buffers()) bfr->al = &alloc;
@@ -1394,6 +1395,14 @@ ivftq_status search_core(ivftq_index* ix, const float* q_dev, int64_t nq, int np
         HIP_TRY(ix->w_ccnt.ensure((size_t)qc * sizeof(int32_t)));
         HIP_TRY(ix->w_gate.ensure((size_t)(qc + 1) * sizeof(int32_t)));
     }
+    // Streaming path with so few queries that one wavefront per score row would leave the chip idle (the
+    // selection then takes longer than the scan): select per (query, list) first.  Needs what the
+    // one-wavefront kernel takes: k <= 64 and lists and survivor rows within its reach.
+    const bool two_step = !batched && nq <= 64 && k <= 64 && nprobe > 1 && sizes[0] <= 16384 && (int64_t)nprobe * k <= 16384;
+    if (two_step) {
+        HIP_TRY(ix->w_stage_s.ensure((size_t)qc * nprobe * k * sizeof(float)));
+        HIP_TRY(ix->w_stage_i.ensure((size_t)qc * nprobe * k * sizeof(int64_t)));
+    }
 
     for (int64_t q0 = 0; q0 < nq; q0 += qc) {
         const int64_t cnt = std::min(qc, nq - q0);
@@ -1431,7 +1440,18 @@ ivftq_status search_core(ivftq_index* ix, const float* q_dev, int64_t nq, int np
             // fewer per query as the batch grows, as long as the launch still fills the chip
             const int per_query = (int)std::min<int64_t>(nprobe, std::max<int64_t>(1, kStreamWorkgroups / cnt));
             HIP_TRY(timed(ix, st, P_LIST_SCAN, [&] { return stream_scan(nullptr, 0, per_query); }));
-            HIP_TRY(timed(ix, st, P_SELECT_TOPK, [&] { return launch_select(1, sa, st); }));
+            if (two_step) {
+                // a handful of rows: one wavefront per (query, list) first, then one per query over the survivors
+                SelectArgs s_a = sa, s_b = sa;
+                s_a.rows = cnt * nprobe; s_a.m_bound = sizes[0];
+                s_a.out_vals = ix->w_stage_s.as<float>(); s_a.out_i64 = ix->w_stage_i.as<int64_t>();
+                s_b.vals = ix->w_stage_s.as<float>(); s_b.stride = (int64_t)nprobe * k; s_b.m_fixed = nprobe * k;
+                s_b.lab_in = ix->w_stage_i.as<int64_t>();
+                HIP_TRY(timed(ix, st, P_SELECT_TOPK, [&] { return launch_select(2, s_a, st); }));
+                HIP_TRY(timed(ix, st, P_SELECT_TOPK, [&] { return launch_select(3, s_b, st); }));
+            } else {
+                HIP_TRY(timed(ix, st, P_SELECT_TOPK, [&] { return launch_select(1, sa, st); }));
+            }
             HIP_TRY(launch_metric_finish(scores_dev + q0 * k, cnt, k, metric, ix->w_qnorm.as<float>(), st));
             continue;
         }

@@ -212,6 +212,10 @@ struct SelectArgs {
     const int64_t* list_off; const int64_t* ids;
     float* out_vals; int32_t* out_i32; int64_t* out_i64;
     int m_bound;      // mode 1: host-side upper bound of any row's length (0 = unknown); picks the kernel
+    // Selection in two steps (k <= 64, no gate): mode 2 treats `rows` = queries x np rows, row (q, p) being the
+    // stretch of probe p in score row q, and writes k (value, label) pairs per row (m_bound = longest list);
+    // mode 3 selects among the m_fixed = np * k survivors of a query, whose labels it reads from lab_in.
+    const int64_t* lab_in;
 };
 hipError_t launch_select(int mode, const SelectArgs& a, hipStream_t st);
 

@@ -500,6 +500,9 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a) {
 // every pass takes them from registers; columns beyond that (long rows are rare) are re-read from
 // memory in each pass.  A wavefront needs little LDS, so many rows are in flight per compute unit.  A final bitonic pass over the lanes orders the winners by (value desc, label asc).
 
+// MODE 2 and 3 are the two halves of a selection in two steps, for calls with so few rows that one wavefront
+// per row would leave the chip idle: MODE 2 takes the k best of every (query, probed list) stretch of a score
+// row, with labels, MODE 3 the k best of a query's np * k survivors (labels looked up, not computed).
 constexpr int kSmallM = 16384;
 constexpr int kShortcutTake = 32;     // the lane-maxima short cut pays up to this many winners (beyond, too many keys reach the bound)
 
@@ -511,12 +514,23 @@ __global__ __launch_bounds__(256) void k_select_small(SelectArgs a) {
     if (a.gate) n_rows = a.gate[0] < a.gate_begin + a.gate_rows ? a.gate[0] : a.gate_begin + a.gate_rows;
     for (int64_t row_i = (a.gate ? a.gate_begin : 0) + (int64_t)blockIdx.x * 4 + wave; row_i < n_rows; row_i += (int64_t)gridDim.x * 4) {
     const int64_t row = a.gate ? a.gate[1 + row_i] : row_i;
-    const int64_t q = a.q_begin + row;
-    const int m = (MODE == 0) ? a.m_fixed
-                              : a.cand_off[q * (a.np + 1) + (a.p_limit ? a.p_limit[q] : a.np)];
+    // MODE 2: row = (query, probe rank); the stretch of that list in the query's score row
+    const int64_t q = a.q_begin + (MODE == 2 ? row / a.np : row);
+    const int sub_p = MODE == 2 ? (int)(row % a.np) : 0;
+    int m, sub_off = 0;
+    if (MODE == 0 || MODE == 3) {
+        m = a.m_fixed;
+    } else if (MODE == 1) {
+        m = a.cand_off[q * (a.np + 1) + (a.p_limit ? a.p_limit[q] : a.np)];
+    } else {
+        const int32_t* off = a.cand_off + q * (a.np + 1);
+        sub_off = off[sub_p];
+        m = (a.p_limit && sub_p >= a.p_limit[q]) ? 0 : off[sub_p + 1] - sub_off;
+    }
     const int k = a.k;
     const int take = m < k ? m : k;
-    const float* vals = a.vals + (a.gate ? row_i - a.gate_begin : row) * a.stride;
+    const float* vals = MODE == 2 ? a.vals + (row / a.np) * a.stride + sub_off
+                                  : a.vals + (a.gate ? row_i - a.gate_begin : row) * a.stride;
     uint32_t* hist = s_work[wave];                                      // [256]
     int* win_col = reinterpret_cast<int*>(hist + 256);                  // [64]
     const float ninf = -__builtin_inff();
@@ -718,9 +732,13 @@ __global__ __launch_bounds__(256) void k_select_small(SelectArgs a) {
     if (out_c >= 0) {
         if (MODE == 0) {
             lab = out_c;
+        } else if (MODE == 2) {
+            const int64_t slot = a.list_off[a.probe[q * a.np + sub_p]] + out_c;
+            lab = a.ids ? a.ids[slot] : slot;
+        } else if (MODE == 3) {
+            lab = a.lab_in[row * a.m_fixed + out_c];
         } else {
             lab = 0;      // placeholder, resolved below by the whole wavefront
-
         }
     }
     if (MODE == 1) {
@@ -760,6 +778,7 @@ __global__ __launch_bounds__(256) void k_select_small(SelectArgs a) {
     // order the winners by (value desc, label asc): a bitonic network over the first nsort >= take lanes
     // (the others hold nothing); the value travels as its key and is decoded at the end
     uint32_t key = out_c >= 0 ? key_of(out_v) : 0u;
+    if (MODE == 3 && lab < 0) key = 0u;              // a survivor slot that the first step left empty
     const int nsort = take <= 8 ? 8 : take <= 16 ? 16 : take <= 32 ? 32 : 64;
 #pragma unroll
     for (int size = 2; size <= 64; size <<= 1) {
@@ -1030,6 +1049,19 @@ constexpr int kSmallMax0 = 2048, kSmallMax0Shortcut = 8192, kSmallMax1 = kSmallM
 hipError_t launch_select(int mode, const SelectArgs& a_in, hipStream_t st) {
     if (a_in.rows <= 0) return hipSuccess;
     SelectArgs a = a_in;
+    if (mode == 2 || mode == 3) {
+        if (a.k > 64 || a.gate || (mode == 3 && !a.lab_in)) return hipErrorInvalidValue;
+        const int bound = mode == 2 ? a.m_bound : a.m_fixed;
+        const unsigned blocks = (unsigned)((a.rows + 3) / 4);
+        if (mode == 2) {
+            if (bound <= 1536) hipLaunchKernelGGL((k_select_small<2, 16>), dim3(blocks), dim3(256), 0, st, a);
+            else hipLaunchKernelGGL((k_select_small<2, 32>), dim3(blocks), dim3(256), 0, st, a);
+        } else {
+            if (bound <= 1536) hipLaunchKernelGGL((k_select_small<3, 16>), dim3(blocks), dim3(256), 0, st, a);
+            else hipLaunchKernelGGL((k_select_small<3, 32>), dim3(blocks), dim3(256), 0, st, a);
+        }
+        return hipGetLastError();
+    }
     // short rows and small k: the one-wavefront-per-row kernel
     const int m_bound = mode == 0 ? a.m_fixed : a.m_bound;
     if (a.k <= 64 && m_bound > 0 && m_bound <= (mode == 0 ? (a.k <= kShortcutTake ? kSmallMax0Shortcut : kSmallMax0) : kSmallMax1)) {
