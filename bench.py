@@ -445,6 +445,32 @@ def run_workload(torch, pkg, synth, key, w, nprobe, steps, warmup, sign_bit=Fals
                           "note": "ivftq_set_search_mode(1): one workgroup group per (query, probed list), every candidate's "
                                   "packed codes and norm streamed once per query"}
 
+        # the same kernel with enough queries to fill the chip, and whole-search latency of small calls (mode 0
+        # takes the streaming path below 128 queries)
+        nq_l = min(2048, w.nq)
+        ql = qd[:nq_l].contiguous()
+        ix.set_search_mode(1)
+        for _ in range(2):
+            ix.search(ql, nprobe, w.k)
+        torch.cuda.synchronize()
+        ix.profile_enable(True)
+        ix.profile_read()
+        for _ in range(3):
+            ix.search(ql, nprobe, w.k)
+        torch.cuda.synchronize()
+        pl = ix.profile_read()
+        ix.profile_enable(False)
+        ix.set_search_mode(0)
+        ll_ms = pl["list_scan"][0] / pl["list_scan"][1]
+        bytes_l = float(cand[:nq_l].sum()) * bytes_per_vec
+        streaming_info["large_call"] = {"nq": nq_l, "list_scan_ms": ll_ms, "achieved": bytes_l / (ll_ms * 1e-3) / 1e9, "unit": "GB/s",
+                                        "frac": bytes_l / (ll_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+        lat = {}
+        for n_small in (1, 16, 64):
+            qsm = qd[:n_small].contiguous()
+            lat[str(n_small)] = median_ms(lambda: ix.search(qsm, nprobe, w.k), 9)
+        streaming_info["small_call_search_ms"] = lat
+
         # cascade search (top bits first, a shortlist kept, full codes second): reported, not the headline.
         # Once on the index as it is (pass 1 reads the full codes through a table that ignores the low bit) and
         # once on an index that keeps the top bits in a plane of their own (pass 1 reads only the plane).
