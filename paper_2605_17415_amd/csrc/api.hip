@@ -184,6 +184,7 @@ struct ivftq_index {
     DevBuf w_zh, w_zl;
     DevBuf w_first, w_fscores, w_fids, w_pairs, w_pairoff, w_tileoff, w_cscore, w_cslot, w_ccnt, w_gate;
     DevBuf w_stage_s, w_stage_i;      // survivors of the first step of a selection in two steps
+    DevBuf w_part;                    // partial results of a coarse assignment whose centroid stages are shared out
     int64_t last_batched_queries = 0;   // queries of the last pass of the most recent batched search (ivftq_scan_stats)
     int search_mode = 0;   // 0 auto, 1 streaming scan only, 2 batched scan whenever the shape allows
     int64_t ws_limit = (int64_t)4 << 30;
@@ -197,7 +198,7 @@ struct ivftq_index {
                 &w_slot, &w_order, &w_hist, &w_count, &w_base, &w_flag, &w_best, &w_undecided, &cb_cascade, &w_keep, &w_keep_scores,
                 &w_S, &w_probe, &w_coarse, &w_z, &w_candoff, &w_scores, &w_sums, &w_counts, &w_zero, &w_rows, &w_dst, &w_obj,
                 &t_cent, &t_cent_h, &t_cent_l, &t_bias, &w_first, &w_fscores, &w_fids, &w_pairs, &w_pairoff, &w_tileoff, &w_cscore,
-                &w_cslot, &w_ccnt, &w_gate, &w_zh, &w_zl, &w_stage_s, &w_stage_i};
+                &w_cslot, &w_ccnt, &w_gate, &w_zh, &w_zl, &w_stage_s, &w_stage_i, &w_part};
     }
     explicit ivftq_index(const Allocator& a) : alloc(a) {
         for (DevBuf* bfr : buffers()) bfr->al = &alloc;
@@ -964,15 +965,22 @@ ivftq_status commit_rows(ivftq_index* ix, const std::vector<int64_t>& need, int6
 // Coarse assignment of n rows (Algorithm "Encode", nearest centroid by inner product): screening pass
 // plus the exact pass over the rows it left undecided.  w_flag[0] = a row without a usable norm,
 // w_flag[1] = number of undecided rows.
+constexpr int64_t kScreenShareRows = 1 << 19;     // beyond this the row tiles alone fill the chip
 ivftq_status assign_rows(ivftq_index* ix, const float* x_dev, int64_t n, int32_t* assign, hipStream_t st) {
     // keys (8 bytes each) first, then the row numbers
     HIP_TRY(ix->w_undecided.ensure((size_t)n * (sizeof(unsigned long long) + sizeof(int32_t))));
+    // short batches share the centroid stages out over several workgroups and need room for the partial results
+    float* part = nullptr;
+    if (n <= kScreenShareRows) {
+        HIP_TRY(ix->w_part.ensure((size_t)n * kScreenMaxShares * 3 * sizeof(float)));
+        part = ix->w_part.as<float>();
+    }
     HIP_TRY(launch_fill_u32(ix->w_flag.as<uint32_t>(), 2, 0u, st));
     HIP_TRY(timed(ix, st, P_ASSIGN, [&] {
         return launch_coarse_screened(x_dev, n, ix->d, ix->cent_h.as<uint16_t>(), ix->cent_l.as<uint16_t>(), ix->dp,
                                       ix->nlist, ix->lpad, assign, ix->w_flag.as<int>(),
                                       reinterpret_cast<int32_t*>(ix->w_undecided.as<unsigned long long>() + n),
-                                      ix->w_undecided.as<unsigned long long>(), ix->w_flag.as<int>() + 1, st);
+                                      ix->w_undecided.as<unsigned long long>(), ix->w_flag.as<int>() + 1, part, st);
     }));
     return IVFTQ_OK;
 }
@@ -1062,7 +1070,7 @@ ivftq_status ivftq_encode_only_noalloc(ivftq_index* ix, const float* x_dev, int6
     // are written before they are read (one entry per listed row)
     HIP_TRY(launch_fill_u32(reinterpret_cast<uint32_t*>(flags), 2, 0u, st));
     HIP_TRY(launch_coarse_screened(x_dev, n, ix->d, ix->cent_h.as<uint16_t>(), ix->cent_l.as<uint16_t>(), ix->dp,
-                                   ix->nlist, ix->lpad, assign, flags, row_list, row_key, flags + 1, st));
+                                   ix->nlist, ix->lpad, assign, flags, row_list, row_key, flags + 1, nullptr, st));
     if (codes_dev || gamma_dev) {
         EncodeArgs a{};
         a.x = x_dev; a.n = n; a.d = ix->d; a.b = ix->b;

@@ -250,11 +250,16 @@ template <int DP, int R, bool VEC4>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((DP <= 128 || R == 1) ? 3 : 2))) void k_coarse_screen(
     const float* __restrict__ x, int64_t n, int d, const uint16_t* __restrict__ cent_h, int cent_pitch,
     int L, int Lpad, int32_t* __restrict__ assign, int32_t* __restrict__ row_list,
-    unsigned long long* __restrict__ row_key, int* __restrict__ row_count) {
+    unsigned long long* __restrict__ row_key, int* __restrict__ row_count, float* __restrict__ part) {
     using Cfg = CoarseCfg<DP>;
     constexpr int KB = Cfg::KB;
     extern __shared__ unsigned char lds_raw[];
     constexpr int NT = screen_nt<DP>(), TN = NT * 32;
+    // gridDim.y > 1 (short batches): workgroup (x, y) takes the y-th share of the centroid stages and leaves
+    // (best, second best, index) of every row in `part`; k_coarse_screen_join puts the shares together
+    const int n_stages = Lpad / TN, per_y = (n_stages + (int)gridDim.y - 1) / (int)gridDim.y;
+    const int c_lo = (int)blockIdx.y * per_y * TN < Lpad ? (int)blockIdx.y * per_y * TN : Lpad;
+    const int c_hi = c_lo + per_y * TN < Lpad ? c_lo + per_y * TN : Lpad;
     uint16_t* th = reinterpret_cast<uint16_t*>(lds_raw);            // [2][TN][LDH] hi parts of the centroids
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63, half = lane >> 5, j = lane & 31;
@@ -292,11 +297,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((DP <= 128 
         if (kChunks % 256 == 0 || e < kChunks)                                                      \
             *reinterpret_cast<uint4*>((BUF) + (e / (DP / 8)) * Cfg::LDH + (e % (DP / 8)) * 8) = pre[i]; \
     }
-    IVFTQ_SCREEN_FETCH(0)
+    IVFTQ_SCREEN_FETCH(c_lo)
     IVFTQ_SCREEN_STORE(th)
     __syncthreads();
     int stage = 0;
-    for (int c0 = 0; c0 < Lpad; c0 += TN, stage ^= 1) {
+    for (int c0 = c_lo; c0 < c_hi; c0 += TN, stage ^= 1) {
         IVFTQ_SCREEN_FETCH(c0 + TN)          // unconditional (indices are clamped): after the last stage it is unused
         const uint16_t* ah_base = th + stage * (TN * Cfg::LDH) + j * Cfg::LDH + 8 * half;
         float prev[R];
@@ -355,6 +360,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((DP <= 128 
         const float b2 = fmaxf(best[r], ob);
         if (ob > best[r]) idx = oi;
         const int64_t row = row0 + 32 * r + j;
+        if (gridDim.y > 1) {
+            if (row < n && half == 0) {
+                float* pp = part + (row * (int64_t)gridDim.y + blockIdx.y) * 3;
+                pp[0] = b2;
+                pp[1] = s2;
+                pp[2] = __int_as_float(good[r] ? idx : -1 - idx);
+            }
+            continue;
+        }
         if (row < n && half == 0) {
             const bool sure = good[r] && (b2 - s2 > kScreenMargin * kSplitScale * kSplitScale);
             assign[row] = idx;
@@ -367,6 +381,34 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((DP <= 128 
     }
 }
 #undef IVFTQ_SCREEN_TAKE
+
+// Shares of a row's screening pass put together: the best of the bests, and as second best the largest of
+// every share's second best and of the bests that lost; then the same decision as in the kernel itself.
+__global__ void k_coarse_screen_join(const float* __restrict__ part, int64_t n, int shares, int32_t* __restrict__ assign,
+                                     int32_t* __restrict__ row_list, unsigned long long* __restrict__ row_key,
+                                     int* __restrict__ row_count) {
+    const int64_t row = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (row >= n) return;
+    float best = kScreenNone, second = kScreenNone;
+    int idx = 0;
+    bool good = true;
+    for (int y = 0; y < shares; ++y) {
+        const float* pp = part + (row * shares + y) * 3;
+        const float b = pp[0], s2 = pp[1];
+        int i = __float_as_int(pp[2]);
+        if (i < 0) { good = false; i = -1 - i; }
+        if (b > best) { second = fmaxf(second, best); best = b; idx = i; }
+        else second = fmaxf(second, b);
+        second = fmaxf(second, s2);
+    }
+    const bool sure = good && (best - second > kScreenMargin * kSplitScale * kSplitScale);
+    assign[row] = idx;
+    if (!sure) {
+        const int pos = atomicAdd(row_count, 1);
+        row_list[pos] = (int32_t)row;
+        row_key[pos] = 0ull;
+    }
+}
 
 // The undecided rows of the screening pass, with all three products.  Workgroup (x, y) walks the row
 // blocks x, x + gridDim.x, ... of the list (128 rows each, one tile per wavefront) against the y-th share of
@@ -459,7 +501,7 @@ __global__ void k_coarse_resolve_write(const int32_t* __restrict__ row_list, con
 template <int DP, int RS>
 hipError_t run_screened(const float* x, int64_t n, int d, const uint16_t* cent_h, const uint16_t* cent_l, int cent_pitch,
                         int L, int Lpad, int32_t* assign, int* flag, int32_t* row_list, unsigned long long* row_key,
-                        int* row_count, hipStream_t st) {
+                        int* row_count, float* part, hipStream_t st) {
     static LdsLimit lim_screen[2], lim_resolve[2];
     const size_t lds_screen = screen_lds_bytes<DP>();
     const size_t lds = (size_t)2 * kTN * CoarseCfg<DP>::LDH * sizeof(uint16_t);
@@ -471,12 +513,22 @@ hipError_t run_screened(const float* x, int64_t n, int d, const uint16_t* cent_h
                  : lim_resolve[0].ensure(reinterpret_cast<const void*>(k_coarse_resolve<DP, false>), lds);
     if (e != hipSuccess) return e;
     const int64_t blocks_s = (n + 4 * 32 * RS - 1) / (4 * 32 * RS);
+    // A short batch gives few workgroups, each walking every centroid stage on its own (90 us at 4096
+    // centroids however few rows there are): with room for the partial results the stages are shared out
+    // over gridDim.y until about 1024 workgroups are in the launch, at least two stages each.
+    int shares = 1;
+    if (part)
+        while (shares < kScreenMaxShares && blocks_s * shares < 1024 && (Lpad / (screen_nt<DP>() * 32)) >= 4 * shares) shares *= 2;
+    const dim3 grid_s((unsigned)blocks_s, (unsigned)shares);
     if (vec4)
-        hipLaunchKernelGGL((k_coarse_screen<DP, RS, true>), dim3((unsigned)blocks_s), dim3(256), lds_screen, st, x, n, d,
-                           cent_h, cent_pitch, L, Lpad, assign, row_list, row_key, row_count);
+        hipLaunchKernelGGL((k_coarse_screen<DP, RS, true>), grid_s, dim3(256), lds_screen, st, x, n, d,
+                           cent_h, cent_pitch, L, Lpad, assign, row_list, row_key, row_count, part);
     else
-        hipLaunchKernelGGL((k_coarse_screen<DP, RS, false>), dim3((unsigned)blocks_s), dim3(256), lds_screen, st, x, n, d,
-                           cent_h, cent_pitch, L, Lpad, assign, row_list, row_key, row_count);
+        hipLaunchKernelGGL((k_coarse_screen<DP, RS, false>), grid_s, dim3(256), lds_screen, st, x, n, d,
+                           cent_h, cent_pitch, L, Lpad, assign, row_list, row_key, row_count, part);
+    if (shares > 1)
+        hipLaunchKernelGGL(k_coarse_screen_join, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, (const float*)part, n, shares,
+                           assign, row_list, row_key, row_count);
     // the undecided rows: about four centroid stages per workgroup, at most 512 x 16 workgroups
     const int stages = Lpad / kTN;
     const int ysplit = std::min(16, (stages + 3) / 4);
@@ -571,11 +623,11 @@ hipError_t launch_split_rows(const float* src, int64_t count, uint16_t* hi, uint
 
 hipError_t launch_coarse_screened(const float* x, int64_t n, int d, const uint16_t* cent_h, const uint16_t* cent_l,
                                   int cent_pitch, int L, int Lpad, int32_t* assign, int* flag, int32_t* row_list,
-                                  unsigned long long* row_key, int* row_count, hipStream_t st) {
+                                  unsigned long long* row_key, int* row_count, float* part, hipStream_t st) {
     if (n <= 0) return hipSuccess;
     switch (coarse_dp(d)) {
 #define IVFTQ_CASE(DPV, RS) \
-    case DPV: return run_screened<DPV, RS>(x, n, d, cent_h, cent_l, cent_pitch, L, Lpad, assign, flag, row_list, row_key, row_count, st);
+    case DPV: return run_screened<DPV, RS>(x, n, d, cent_h, cent_l, cent_pitch, L, Lpad, assign, flag, row_list, row_key, row_count, part, st);
         IVFTQ_CASE(32, 2) IVFTQ_CASE(64, 2) IVFTQ_CASE(96, 2) IVFTQ_CASE(128, 2) IVFTQ_CASE(160, 2)
         IVFTQ_CASE(192, 2) IVFTQ_CASE(208, 2) IVFTQ_CASE(224, 2) IVFTQ_CASE(256, 2)
 #undef IVFTQ_CASE

@@ -83,10 +83,12 @@ hipError_t launch_coarse(int mode, const float* x, int64_t n, int d, const uint1
 // The argmax of mode 0 (no bias) in two steps: a screening pass with the hi*hi products alone decides
 // every row whose best score is clearly ahead, the rest (listed in row_list, counted in *row_count,
 // which the caller clears) is redone with all three products.  assign as for launch_coarse.  row_list
-// and row_key are scratch arrays of n entries.
+// and row_key are scratch arrays of n entries.  part (may be null): 3 * kScreenMaxShares floats of scratch
+// per row; with it a short batch shares the centroid stages out over several workgroups per row tile.
+constexpr int kScreenMaxShares = 16;
 hipError_t launch_coarse_screened(const float* x, int64_t n, int d, const uint16_t* cent_h, const uint16_t* cent_l,
                                   int cent_pitch, int L, int Lpad, int32_t* assign, int* flag, int32_t* row_list,
-                                  unsigned long long* row_key, int* row_count, hipStream_t st);
+                                  unsigned long long* row_key, int* row_count, float* part, hipStream_t st);
 // hi[i], lo[i] = split float16 form of src[i]
 hipError_t launch_split_rows(const float* src, int64_t count, uint16_t* hi, uint16_t* lo, hipStream_t st);
 
