@@ -285,6 +285,13 @@ void k_batch_scan(BatchScanArgs a) {
     }
     __syncthreads();
 
+    // acc0 in every element, kept in registers for the whole kernel (hidden from the compiler, which would
+    // otherwise write the 16 registers anew from scalars for every tile)
+    floatx16 acc_init;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc_init[r] = DENSE ? 0.f : a.acc0;
+    if (!DENSE) asm volatile("" : "+v"(acc_init));
+
     while (slab < nslab) {
         const int next = slab + WAVES;
         if (next < nslab) fetch(next, nw, ng);
@@ -314,17 +321,27 @@ void k_batch_scan(BatchScanArgs a) {
             g[r] = kUnscale * __half2float(__ushort_as_half((uint16_t)((!DENSE && (r & 1)) ? (pr >> 16) : (pr & 0xFFFFu))));
         }
 
+        // threshold pass: the largest norm among this lane's rows, for a test of a whole tile at once
+        float g_max = 0.f;
+        if (!DENSE) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) g_max = fmaxf(g_max, g[r]);       // fmaxf ignores the NaN of rows beyond the list
+        }
+
         for (int qt = 0; qt < n_qt; ++qt) {
             floatx16 acc;
+            if (DENSE) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[r] = DENSE ? 0.f : a.acc0;
+                for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+            }
             const uint16_t* bhq = bh_base + qt * 32 * Cfg::LDH;
             const uint16_t* blq = bl_base + qt * 32 * Cfg::LDH;
 #pragma unroll
             for (int kb = 0; kb < KB; ++kb) {
                 const half8 bh = *reinterpret_cast<const half8*>(bhq + 16 * kb);
                 if (!DENSE) {
-                    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah[kb], bh, acc, 0, 0, 0);
+                    // the first product starts from the block that holds the error bound in every element
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah[kb], bh, kb ? acc : acc_init, 0, 0, 0);
                     continue;
                 }
                 const half8 bl = *reinterpret_cast<const half8*>(blq + 16 * kb);
@@ -356,21 +373,21 @@ void k_batch_scan(BatchScanArgs a) {
             const int e = qt * 32 + jl;
             const float sq = s_coarse[e], th = s_thr[e];
             const int32_t q = s_q[e];
-            float sc[16];
-            float best = -__builtin_inff();
+            // No row can reach the threshold unless the largest accumulator times the largest norm does:
+            // g_max >= g[r] >= 0 and a_max >= max(acc[r], 0), and a correctly rounded fused multiply-add never
+            // decreases when its exact value grows, so fmaf(g_max, a_max, sq) >= fmaf(g[r], acc[r], sq) for every r.
+            float a_max = 0.f;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                sc[r] = fmaf(g[r], acc[r], sq);    // upper bound of the score; NaN (row beyond the list) never passes
-                best = fmaxf(best, sc[r]);         // fmaxf ignores NaN
-            }
-            if (best >= th && q >= 0) {            // rare: some row of this lane reaches the threshold
+            for (int r = 0; r < 16; r += 2) a_max = fmaxf(fmaxf(a_max, acc[r]), acc[r + 1]);
+            if (fmaf(g_max, a_max, sq) >= th && q >= 0) {            // rare: some row of this lane may reach the threshold
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    if (sc[r] >= th) {
+                    const float sc_r = fmaf(g[r], acc[r], sq);       // upper bound of the score; NaN (row beyond the list) never passes
+                    if (sc_r >= th) {
                         const int v = slab * 32 + 8 * (r / 4) + 4 * half + (r % 4);
                         const int pos = atomicAdd(&a.cand_cnt[q], 1);
                         if (pos < a.cap) {
-                            a.cand_score[(int64_t)q * a.cap + pos] = sc[r];
+                            a.cand_score[(int64_t)q * a.cap + pos] = sc_r;
                             a.cand_slot[(int64_t)q * a.cap + pos] = (base_slot + v) | ((int64_t)s_p[e] << kCandProbeShift);
                         }
                     }
