@@ -287,10 +287,11 @@ void k_batch_scan(BatchScanArgs a) {
 
     // acc0 in every element, kept in registers for the whole kernel (hidden from the compiler, which would
     // otherwise write the 16 registers anew from scalars for every tile)
+    // (not for 3 and 5 stored bits, whose chunks straddle words and take the registers this would need)
     floatx16 acc_init;
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc_init[r] = DENSE ? 0.f : a.acc0;
-    if (!DENSE) asm volatile("" : "+v"(acc_init));
+    if (!DENSE && NW == 1) asm volatile("" : "+v"(acc_init));
 
     while (slab < nslab) {
         const int next = slab + WAVES;
@@ -314,85 +315,106 @@ void k_batch_scan(BatchScanArgs a) {
             ah[kb] = __builtin_bit_cast(half8, make_uint4(hv[0], hv[1], hv[2], hv[3]));
             al[kb] = __builtin_bit_cast(half8, make_uint4(lv[0], lv[1], lv[2], lv[3]));
         }
-        float g[16];                               // 2^-20 * norm per result row (NaN beyond the list)
+        if constexpr (!DENSE) {
+            // ---- threshold pass.  A lane holds one query's 16 accumulators per tile; row r is the vector
+            // 8*(r/4) + 4*half + r%4 of the slab, its norm the half r%2 of cg[r/2] (NaN beyond the list).
+            auto norm_of = [&](int r) -> float {
+                const uint32_t pr = cg[r / 2];
+                return kUnscale * __half2float(__ushort_as_half((uint16_t)((r & 1) ? (pr >> 16) : (pr & 0xFFFFu))));
+            };
+            // the largest norm among this lane's rows (packed float16 maxima, which skip the NaNs)
+            typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+            half2v gm = __builtin_bit_cast(half2v, cg[0]);
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const uint32_t pr = cg[DENSE ? 0 : r / 2];
-            g[r] = kUnscale * __half2float(__ushort_as_half((uint16_t)((!DENSE && (r & 1)) ? (pr >> 16) : (pr & 0xFFFFu))));
-        }
-
-        // threshold pass: the largest norm among this lane's rows, for a test of a whole tile at once
-        float g_max = 0.f;
-        if (!DENSE) {
+            for (int r = 1; r < 8; ++r) gm = __builtin_elementwise_max(gm, __builtin_bit_cast(half2v, cg[r]));
+            const float g_max = kUnscale * fmaxf((float)gm[0], (float)gm[1]);
+            // No row of a tile can reach the threshold unless the largest accumulator times the largest norm
+            // does: g_max >= g_r >= 0 and a_max >= max(acc_r, 0), and a correctly rounded fused multiply-add
+            // never decreases when its exact value grows, so fmaf(g_max, a_max, sq) >= fmaf(g_r, acc_r, sq).
+            auto take = [&](const floatx16& acc, int qt) {
+                const int e = qt * 32 + jl;
+                const float sq = s_coarse[e], th = s_thr[e];
+                const int32_t q = s_q[e];
+                float a_max = 0.f;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) g_max = fmaxf(g_max, g[r]);       // fmaxf ignores the NaN of rows beyond the list
-        }
-
+                for (int r = 0; r < 16; r += 2) a_max = fmaxf(fmaxf(a_max, acc[r]), acc[r + 1]);
+                if (fmaf(g_max, a_max, sq) >= th && q >= 0) {        // rare: some row of this lane may reach the threshold
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const float sc_r = fmaf(norm_of(r), acc[r], sq);   // upper bound of the score; NaN never passes
+                        if (sc_r >= th) {
+                            const int v = slab * 32 + 8 * (r / 4) + 4 * half + (r % 4);
+                            const int pos = atomicAdd(&a.cand_cnt[q], 1);
+                            if (pos < a.cap) {
+                                a.cand_score[(int64_t)q * a.cap + pos] = sc_r;
+                                a.cand_slot[(int64_t)q * a.cap + pos] = (base_slot + v) | ((int64_t)s_p[e] << kCandProbeShift);
+                            }
+                        }
+                    }
+                }
+            };
+            // two query tiles at a time: their products are independent, so one tile's matrix instructions
+            // and LDS reads fill the waits of the other's; the first product of a tile starts from the block
+            // that holds the error bound in every element
+            // (only where the register budget of the launch shape has room for a second accumulator block:
+            // at three wavefronts per SIMD it spilled and the pass took half as long again)
+            constexpr bool kPairs = OCC <= 2 && NW == 1;
+            int qt = 0;
+            for (; kPairs && qt + 1 < n_qt; qt += 2) {
+                const uint16_t* b0 = bh_base + qt * 32 * Cfg::LDH;
+                const uint16_t* b1 = b0 + 32 * Cfg::LDH;
+                floatx16 acc0, acc1;
+#pragma unroll
+                for (int kb = 0; kb < KB; ++kb) {
+                    const half8 h0 = *reinterpret_cast<const half8*>(b0 + 16 * kb);
+                    const half8 h1 = *reinterpret_cast<const half8*>(b1 + 16 * kb);
+                    acc0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah[kb], h0, kb ? acc0 : acc_init, 0, 0, 0);
+                    acc1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah[kb], h1, kb ? acc1 : acc_init, 0, 0, 0);
+                }
+                take(acc0, qt);
+                take(acc1, qt + 1);
+            }
+            for (; qt < n_qt; ++qt) {
+                const uint16_t* b0 = bh_base + qt * 32 * Cfg::LDH;
+                floatx16 acc0;
+#pragma unroll
+                for (int kb = 0; kb < KB; ++kb) {
+                    const half8 h0 = *reinterpret_cast<const half8*>(b0 + 16 * kb);
+                    acc0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah[kb], h0, kb ? acc0 : acc_init, 0, 0, 0);
+                }
+                take(acc0, qt);
+            }
+        } else {
+        float g[16];                               // 2^-20 * norm of this lane's vector (NaN beyond the list)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) g[r] = kUnscale * __half2float(__ushort_as_half((uint16_t)(cg[0] & 0xFFFFu)));
         for (int qt = 0; qt < n_qt; ++qt) {
             floatx16 acc;
-            if (DENSE) {
 #pragma unroll
-                for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-            }
+            for (int r = 0; r < 16; ++r) acc[r] = 0.f;
             const uint16_t* bhq = bh_base + qt * 32 * Cfg::LDH;
             const uint16_t* blq = bl_base + qt * 32 * Cfg::LDH;
 #pragma unroll
             for (int kb = 0; kb < KB; ++kb) {
                 const half8 bh = *reinterpret_cast<const half8*>(bhq + 16 * kb);
-                if (!DENSE) {
-                    // the first product starts from the block that holds the error bound in every element
-                    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah[kb], bh, kb ? acc : acc_init, 0, 0, 0);
-                    continue;
-                }
                 const half8 bl = *reinterpret_cast<const half8*>(blq + 16 * kb);
-                if (DENSE) {
-                    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(bh, ah[kb], acc, 0, 0, 0);
-                    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(bl, ah[kb], acc, 0, 0, 0);
-                    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(bh, al[kb], acc, 0, 0, 0);
-                } else {
-                    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah[kb], bh, acc, 0, 0, 0);
-                    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah[kb], bl, acc, 0, 0, 0);
-                    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(al[kb], bh, acc, 0, 0, 0);
-                }
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(bh, ah[kb], acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(bl, ah[kb], acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(bh, al[kb], acc, 0, 0, 0);
             }
-            if (DENSE) {
-                // result row r of this lane: query 8*(r/4) + 4*half + r%4 of the tile, vector jl of the slab
-                const int v = slab * 32 + jl;
+            // result row r of this lane: query 8*(r/4) + 4*half + r%4 of the tile, vector jl of the slab
+            const int v = slab * 32 + jl;
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    // rows 4g .. 4g+3 belong to the queries 8g .. 8g+7 of this tile: a sparse tile (a list that
-                    // is among the nearest of few queries) skips the groups it has no query for
-                    if (qt * 32 + 8 * (r / 4) >= nq_tile) break;
-                    const int e = qt * 32 + 8 * (r / 4) + 4 * half + (r % 4);
-                    const int32_t q = s_q[e];
-                    if (q >= 0 && v < n_l)
-                        a.scores[(int64_t)q * a.m_stride + __float_as_int(s_thr[e]) + v] = fmaf(g[r], acc[r], s_coarse[e]);
-                }
-                continue;
+            for (int r = 0; r < 16; ++r) {
+                // rows 4g .. 4g+3 belong to the queries 8g .. 8g+7 of this tile: a sparse tile (a list that
+                // is among the nearest of few queries) skips the groups it has no query for
+                if (qt * 32 + 8 * (r / 4) >= nq_tile) break;
+                const int e = qt * 32 + 8 * (r / 4) + 4 * half + (r % 4);
+                const int32_t q = s_q[e];
+                if (q >= 0 && v < n_l)
+                    a.scores[(int64_t)q * a.m_stride + __float_as_int(s_thr[e]) + v] = fmaf(g[r], acc[r], s_coarse[e]);
             }
-            const int e = qt * 32 + jl;
-            const float sq = s_coarse[e], th = s_thr[e];
-            const int32_t q = s_q[e];
-            // No row can reach the threshold unless the largest accumulator times the largest norm does:
-            // g_max >= g[r] >= 0 and a_max >= max(acc[r], 0), and a correctly rounded fused multiply-add never
-            // decreases when its exact value grows, so fmaf(g_max, a_max, sq) >= fmaf(g[r], acc[r], sq) for every r.
-            float a_max = 0.f;
-#pragma unroll
-            for (int r = 0; r < 16; r += 2) a_max = fmaxf(fmaxf(a_max, acc[r]), acc[r + 1]);
-            if (fmaf(g_max, a_max, sq) >= th && q >= 0) {            // rare: some row of this lane may reach the threshold
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const float sc_r = fmaf(g[r], acc[r], sq);       // upper bound of the score; NaN (row beyond the list) never passes
-                    if (sc_r >= th) {
-                        const int v = slab * 32 + 8 * (r / 4) + 4 * half + (r % 4);
-                        const int pos = atomicAdd(&a.cand_cnt[q], 1);
-                        if (pos < a.cap) {
-                            a.cand_score[(int64_t)q * a.cap + pos] = sc_r;
-                            a.cand_slot[(int64_t)q * a.cap + pos] = (base_slot + v) | ((int64_t)s_p[e] << kCandProbeShift);
-                        }
-                    }
-                }
-            }
+        }
         }
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb)
