@@ -1,4 +1,4 @@
-"""GPU parity with thousands of coarse cells and k up to 100: the shapes that take the workgroup-per-row
+"""GPU parity with thousands of coarse cells, or with few cells holding thousands of vectors each, and k up to 100: the shapes that take the workgroup-per-row
 selection (probe selection over more than 2048 cells, result selection with k > 64), 128-query tiles at
 d = 200 and many (list, tile) buckets in the batched scan.  Seeded synthetic mixtures; encode and search are
 compared with the oracle by the same rules as the fixed cases."""
@@ -17,6 +17,11 @@ CASES = [
     (96, 4096, 4, 200_000, 300, 32, 10, 0.0),
     (200, 2500, 4, 300_000, 200, 64, 100, 0.5),
     (64, 3000, 3, 150_000, 257, 16, 70, 0.0),
+    # few cells, long lists (thousands of vectors each): the dense pass of the batched scan stops at its depth and
+    # the threshold pass takes the rest of a query's nearest lists
+    (96, 64, 4, 200_000, 300, 8, 10, 0.0),
+    (200, 40, 4, 120_000, 150, 6, 100, 0.5),
+    (64, 16, 2, 60_000, 200, 16, 40, 0.0),
 ]
 
 
