@@ -122,7 +122,47 @@ __global__ __launch_bounds__(256) void k_list_scan(const float* __restrict__ z, 
         const int64_t slot = base_slot + v;
         const uint32_t* wp = store.codes + (slot >> 6) * words * 64 + (slot & 63);
         float acc = 0.f;
-        if constexpr (32 % B == 0) {
+        if constexpr (!DIRECT && (B == 2 || B == 4 || B == 8)) {
+            // Table lookups without address arithmetic.  The codes at even and at odd positions of a word are
+            // separated (two masks), the even ones shifted left by two; a bit-field extract that starts two bits
+            // below a code then yields the code times four, the byte offset of its table entry, because the bits
+            // below belong to a neighbour that the mask cleared.  The loop over the words is unrolled against the
+            // largest row the table fits, so the coordinate's part of the address is an immediate of the LDS read:
+            // per code one extract and one add, per word three mask operations.
+            constexpr int per = 32 / B;
+            constexpr int WU = 8;  // words fetched together: their latency overlaps
+            constexpr uint32_t kEven = B == 2 ? 0x33333333u : B == 4 ? 0x0F0F0F0Fu : 0x00FF00FFu;
+            // longest row: the table fits 64 KB (4K bytes per coordinate) and the library takes d <= 256
+            constexpr int kMaxCoords = (64 * 1024 / (K * 4)) < 256 ? (64 * 1024 / (K * 4)) : 256;
+            constexpr int kMaxWords = kMaxCoords * B / 32;
+            const char* lut_b = reinterpret_cast<const char*>(lut);
+#pragma unroll
+            for (int w0 = 0; w0 < kMaxWords; w0 += WU) {
+                if (w0 >= words) break;
+                uint32_t wd[WU];
+#pragma unroll
+                for (int u = 0; u < WU; ++u) wd[u] = (w0 + u < words) ? wp[(w0 + u) * 64] : 0u;
+#pragma unroll
+                for (int u = 0; u < WU; ++u) {
+                    const int j = (w0 + u) * per;
+                    uint32_t word = wd[u];
+                    if (j + per <= d) {
+                        const uint32_t ev = (word & kEven) << 2, od = word & ~kEven;
+#pragma unroll
+                        for (int t = 0; t < per; ++t) {
+                            const uint32_t off4 = (t & 1) ? __builtin_amdgcn_ubfe(od, t * B - 2, B + 2)
+                                                          : __builtin_amdgcn_ubfe(ev, t * B, B + 2);
+                            acc += *reinterpret_cast<const float*>(lut_b + (size_t)(j + t) * K * 4 + off4);
+                        }
+                    } else {
+                        for (int t = 0; t < per && j + t < d; ++t) {
+                            acc += term(j + t, word & (K - 1));
+                            word >>= B;
+                        }
+                    }
+                }
+            }
+        } else if constexpr (32 % B == 0) {
             constexpr int per = 32 / B;
             constexpr int WU = 8;  // words fetched together: their latency overlaps
             for (int w0 = 0; w0 < words; w0 += WU) {
