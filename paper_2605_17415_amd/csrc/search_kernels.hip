@@ -126,40 +126,60 @@ __global__ __launch_bounds__(256) void k_list_scan(const float* __restrict__ z, 
             // Table lookups without address arithmetic.  The codes at even and at odd positions of a word are
             // separated (two masks), the even ones shifted left by two; a bit-field extract that starts two bits
             // below a code then yields the code times four, the byte offset of its table entry, because the bits
-            // below belong to a neighbour that the mask cleared.  The loop over the words is unrolled against the
-            // largest row the table fits, so the coordinate's part of the address is an immediate of the LDS read:
-            // per code one extract and one add, per word three mask operations.
+            // below belong to a neighbour that the mask cleared.  Rows are walked in chunks of 32 coordinates, the
+            // chunk loop unrolled against the longest row the table fits, so the coordinate's part of the address
+            // is an immediate of the LDS read: per code one extract and one add, per word three mask operations.
+            // The next chunk's words are fetched before the current one is summed.  Words beyond the last whole
+            // chunk (d not a multiple of 32) take the plain loop below.
             constexpr int per = 32 / B;
-            constexpr int WU = 8;  // words fetched together: their latency overlaps
+            constexpr int CW = B;      // words per chunk of 32 codes
             constexpr uint32_t kEven = B == 2 ? 0x33333333u : B == 4 ? 0x0F0F0F0Fu : 0x00FF00FFu;
             // longest row: the table fits 64 KB (4K bytes per coordinate) and the library takes d <= 256
             constexpr int kMaxCoords = (64 * 1024 / (K * 4)) < 256 ? (64 * 1024 / (K * 4)) : 256;
-            constexpr int kMaxWords = kMaxCoords * B / 32;
-            const char* lut_b = reinterpret_cast<const char*>(lut);
+            constexpr int kMaxChunks = kMaxCoords / 32;
+            // The table's LDS address: lookups below address LDS by number (offset of the entry plus an
+            // immediate), which holds when the table starts at LDS address 0 -- it is this kernel's only
+            // shared array; were it ever placed elsewhere, every chunk takes the plain loop below instead.
+            typedef __attribute__((address_space(3))) const float lds_float;
+            uint32_t lut_at = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) float*)lut;
+            asm volatile("" : "+s"(lut_at));
+            // whole chunks of this row; opaque, so that the tests below stay scalar compares inside the loop
+            // instead of a set of flags computed ahead of it
+            int chunks = lut_at == 0 ? d >> 5 : 0;
+            asm volatile("" : "+s"(chunks));
+            uint32_t cur[CW];
+            if (chunks > 0) {
 #pragma unroll
-            for (int w0 = 0; w0 < kMaxWords; w0 += WU) {
-                if (w0 >= words) break;
-                uint32_t wd[WU];
+                for (int u = 0; u < CW; ++u) cur[u] = wp[u * 64];
+            }
 #pragma unroll
-                for (int u = 0; u < WU; ++u) wd[u] = (w0 + u < words) ? wp[(w0 + u) * 64] : 0u;
+            for (int c = 0; c < kMaxChunks; ++c) {
+                if (c >= chunks) break;
+                uint32_t nxt[CW];
+                if (c + 1 < chunks) {
 #pragma unroll
-                for (int u = 0; u < WU; ++u) {
-                    const int j = (w0 + u) * per;
-                    uint32_t word = wd[u];
-                    if (j + per <= d) {
-                        const uint32_t ev = (word & kEven) << 2, od = word & ~kEven;
+                    for (int u = 0; u < CW; ++u) nxt[u] = wp[((c + 1) * CW + u) * 64];
+                }
 #pragma unroll
-                        for (int t = 0; t < per; ++t) {
-                            const uint32_t off4 = (t & 1) ? __builtin_amdgcn_ubfe(od, t * B - 2, B + 2)
-                                                          : __builtin_amdgcn_ubfe(ev, t * B, B + 2);
-                            acc += *reinterpret_cast<const float*>(lut_b + (size_t)(j + t) * K * 4 + off4);
-                        }
-                    } else {
-                        for (int t = 0; t < per && j + t < d; ++t) {
-                            acc += term(j + t, word & (K - 1));
-                            word >>= B;
-                        }
+                for (int u = 0; u < CW; ++u) {
+                    uint32_t ev = (cur[u] & kEven) << 2, od = cur[u] & ~kEven;
+                    asm("" : "+v"(ev));      // keeps each lookup one bit-field extract: with the cleared bits
+                    asm("" : "+v"(od));      // known, the compiler rewrites it as a shift and a mask
+#pragma unroll
+                    for (int t = 0; t < per; ++t) {
+                        const uint32_t off4 = (t & 1) ? __builtin_amdgcn_ubfe(od, t * B - 2, B + 2)
+                                                      : __builtin_amdgcn_ubfe(ev, t * B, B + 2);
+                        acc += *(lds_float*)(off4 + (uint32_t)(((c * CW + u) * per + t) * K * 4));
                     }
+                }
+#pragma unroll
+                for (int u = 0; u < CW; ++u) cur[u] = nxt[u];
+            }
+            for (int w = chunks * CW; w < words; ++w) {
+                uint32_t word = wp[w * 64];
+                for (int t = 0, j = w * per; t < per && j < d; ++t, ++j) {
+                    acc += term(j, word & (K - 1));
+                    word >>= B;
                 }
             }
         } else if constexpr (32 % B == 0) {
