@@ -122,107 +122,89 @@ __global__ __launch_bounds__(256) void k_list_scan(const float* __restrict__ z, 
         const int64_t slot = base_slot + v;
         const uint32_t* wp = store.codes + (slot >> 6) * words * 64 + (slot & 63);
         float acc = 0.f;
-        if constexpr (!DIRECT && (B == 2 || B == 4 || B == 8)) {
-            // Table lookups without address arithmetic.  The codes at even and at odd positions of a word are
-            // separated (two masks), the even ones shifted left by two; a bit-field extract that starts two bits
-            // below a code then yields the code times four, the byte offset of its table entry, because the bits
-            // below belong to a neighbour that the mask cleared.  Rows are walked in chunks of 32 coordinates, the
-            // chunk loop unrolled against the longest row the table fits, so the coordinate's part of the address
-            // is an immediate of the LDS read: per code one extract and one add, per word three mask operations.
-            // The next chunk's words are fetched before the current one is summed.  Words beyond the last whole
-            // chunk (d not a multiple of 32) take the plain loop below.
-            constexpr int per = 32 / B;
-            constexpr int CW = B;      // words per chunk of 32 codes
-            constexpr uint32_t kEven = B == 2 ? 0x33333333u : B == 4 ? 0x0F0F0F0Fu : 0x00FF00FFu;
+        // A row is walked in chunks of 32 coordinates = B packed words, whose codes sit at bit positions known at
+        // compile time.
+        int chunks = 0;                // whole chunks summed by the table lookups below
+        if constexpr (!DIRECT && B >= 2) {   // (one-bit codes: the two bits below a code are not a single neighbour's)
+            // Table lookups without address arithmetic.  The codes of a word are split by the parity of their
+            // position into two masked copies, so that the bits below a code are zero; a bit-field extract that
+            // starts two bits below the code then yields the code times four, the byte offset of its table entry.
+            // The chunk loop is unrolled against the longest row the table fits, which makes the coordinate's part
+            // of the address an immediate of the LDS read: per code one extract, one read and one add, per word
+            // two masks.  (A code in the lowest two bits of a word is shifted up and masked instead, one that
+            // straddles two words is taken from the aligned pair.)  The next chunk's words are fetched before the
+            // current one is summed.  Coordinates beyond the last whole chunk take the loop further down.
             // longest row: the table fits 64 KB (4K bytes per coordinate) and the library takes d <= 256
             constexpr int kMaxCoords = (64 * 1024 / (K * 4)) < 256 ? (64 * 1024 / (K * 4)) : 256;
             constexpr int kMaxChunks = kMaxCoords / 32;
-            // The table's LDS address: lookups below address LDS by number (offset of the entry plus an
+            // The table's LDS address: the lookups address LDS by number (offset of the entry plus an
             // immediate), which holds when the table starts at LDS address 0 -- it is this kernel's only
-            // shared array; were it ever placed elsewhere, every chunk takes the plain loop below instead.
+            // shared array; were it ever placed elsewhere, every chunk takes the loop further down instead.
             typedef __attribute__((address_space(3))) const float lds_float;
             uint32_t lut_at = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) float*)lut;
             asm volatile("" : "+s"(lut_at));
-            // whole chunks of this row; opaque, so that the tests below stay scalar compares inside the loop
-            // instead of a set of flags computed ahead of it
-            int chunks = lut_at == 0 ? d >> 5 : 0;
+            // opaque, so that the tests below stay scalar compares inside the loop instead of a set of flags
+            // computed ahead of it
+            chunks = lut_at == 0 ? d >> 5 : 0;
             asm volatile("" : "+s"(chunks));
-            uint32_t cur[CW];
+            uint32_t cur[B];
             if (chunks > 0) {
 #pragma unroll
-                for (int u = 0; u < CW; ++u) cur[u] = wp[u * 64];
+                for (int u = 0; u < B; ++u) cur[u] = wp[u * 64];
             }
 #pragma unroll
             for (int c = 0; c < kMaxChunks; ++c) {
                 if (c >= chunks) break;
-                uint32_t nxt[CW];
+                uint32_t nxt[B];
                 if (c + 1 < chunks) {
 #pragma unroll
-                    for (int u = 0; u < CW; ++u) nxt[u] = wp[((c + 1) * CW + u) * 64];
+                    for (int u = 0; u < B; ++u) nxt[u] = wp[((c + 1) * B + u) * 64];
                 }
+                uint32_t par[B][2];    // word u with only its whole codes of even / odd position kept
 #pragma unroll
-                for (int u = 0; u < CW; ++u) {
-                    uint32_t ev = (cur[u] & kEven) << 2, od = cur[u] & ~kEven;
-                    asm("" : "+v"(ev));      // keeps each lookup one bit-field extract: with the cleared bits
-                    asm("" : "+v"(od));      // known, the compiler rewrites it as a shift and a mask
+                for (int u = 0; u < B; ++u) {
+                    uint32_t m[2] = {0u, 0u};
 #pragma unroll
-                    for (int t = 0; t < per; ++t) {
-                        const uint32_t off4 = (t & 1) ? __builtin_amdgcn_ubfe(od, t * B - 2, B + 2)
-                                                      : __builtin_amdgcn_ubfe(ev, t * B, B + 2);
-                        acc += *(lds_float*)(off4 + (uint32_t)(((c * CW + u) * per + t) * K * 4));
-                    }
+                    for (int t = 0; t < 32; ++t)
+                        if (((t * B) >> 5) == u && ((t * B) & 31) + B <= 32) m[t & 1] |= (uint32_t)(K - 1) << ((t * B) & 31);
+                    par[u][0] = cur[u] & m[0];
+                    par[u][1] = cur[u] & m[1];
+                    asm("" : "+v"(par[u][0]));   // keeps each lookup one bit-field extract: with the cleared
+                    asm("" : "+v"(par[u][1]));   // bits known, the compiler rewrites it as a shift and a mask
                 }
-#pragma unroll
-                for (int u = 0; u < CW; ++u) cur[u] = nxt[u];
-            }
-            for (int w = chunks * CW; w < words; ++w) {
-                uint32_t word = wp[w * 64];
-                for (int t = 0, j = w * per; t < per && j < d; ++t, ++j) {
-                    acc += term(j, word & (K - 1));
-                    word >>= B;
-                }
-            }
-        } else if constexpr (32 % B == 0) {
-            constexpr int per = 32 / B;
-            constexpr int WU = 8;  // words fetched together: their latency overlaps
-            for (int w0 = 0; w0 < words; w0 += WU) {
-                uint32_t wd[WU];
-#pragma unroll
-                for (int u = 0; u < WU; ++u) wd[u] = (w0 + u < words) ? wp[(w0 + u) * 64] : 0u;
-#pragma unroll
-                for (int u = 0; u < WU; ++u) {
-                    const int j = (w0 + u) * per;
-                    uint32_t word = wd[u];
-                    if (j + per <= d) {
-#pragma unroll
-                        for (int t = 0; t < per; ++t) acc += term(j + t, __builtin_amdgcn_ubfe(word, t * B, B));   // one bit-field extract per code
-                    } else {
-                        for (int t = 0; t < per && j + t < d; ++t) {
-                            acc += term(j + t, word & (K - 1));
-                            word >>= B;
-                        }
-                    }
-                }
-            }
-        } else {
-            // B words hold exactly 32 codes, at bit positions known at compile time: the words are fetched
-            // together and every code is one bit-field extract (two shifts where it straddles a word)
-            for (int w0 = 0; w0 < words; w0 += B) {
-                uint32_t wd[B + 1];
-#pragma unroll
-                for (int u = 0; u < B; ++u) wd[u] = (w0 + u < words) ? wp[(w0 + u) * 64] : 0u;
-                wd[B] = 0u;
-                const int j0 = (w0 / B) * 32;
-                const bool whole = j0 + 32 <= d;
 #pragma unroll
                 for (int t = 0; t < 32; ++t) {
-                    constexpr int kBits = B;
-                    const int wi = (t * kBits) >> 5, sh = (t * kBits) & 31;
-                    const uint32_t code = (sh + kBits <= 32)
-                        ? __builtin_amdgcn_ubfe(wd[wi], sh, kBits)
-                        : (((wd[wi] >> sh) | (wd[wi + 1] << (32 - sh))) & (uint32_t)(K - 1));
-                    if (whole || j0 + t < d) acc += term(j0 + t, code);
+                    const int wi = (t * B) >> 5, sh = (t * B) & 31;
+                    uint32_t off4;
+                    if (sh + B > 32)   // straddles: sh > 24
+                        off4 = __builtin_amdgcn_alignbit(cur[wi + 1 < B ? wi + 1 : wi], cur[wi], sh - 2) & ((uint32_t)(K - 1) << 2);
+                    else if (sh < 2)
+                        off4 = (cur[wi] << (2 - sh)) & ((uint32_t)(K - 1) << 2);
+                    else
+                        off4 = __builtin_amdgcn_ubfe(par[wi][t & 1], sh - 2, B + 2);
+                    acc += *(lds_float*)(off4 + (uint32_t)((c * 32 + t) * K * 4));
                 }
+#pragma unroll
+                for (int u = 0; u < B; ++u) cur[u] = nxt[u];
+            }
+        }
+        // the rest (a last chunk of fewer than 32 coordinates; every chunk when the table is not in LDS): every
+        // code is one bit-field extract (two shifts where it straddles a word) plus the address arithmetic
+        for (int w0 = chunks * B; w0 < words; w0 += B) {
+            uint32_t wd[B + 1];
+#pragma unroll
+            for (int u = 0; u < B; ++u) wd[u] = (w0 + u < words) ? wp[(w0 + u) * 64] : 0u;
+            wd[B] = 0u;
+            const int j0 = (w0 / B) * 32;
+            const bool whole = j0 + 32 <= d;
+#pragma unroll
+            for (int t = 0; t < 32; ++t) {
+                constexpr int kBits = B;
+                const int wi = (t * kBits) >> 5, sh = (t * kBits) & 31;
+                const uint32_t code = (sh + kBits <= 32)
+                    ? __builtin_amdgcn_ubfe(wd[wi], sh, kBits)
+                    : (((wd[wi] >> sh) | (wd[wi + 1] << (32 - sh))) & (uint32_t)(K - 1));
+                if (whole || j0 + t < d) acc += term(j0 + t, code);
             }
         }
         const float g = __half2float(__ushort_as_half(store.gamma[slot]));
