@@ -549,7 +549,10 @@ constexpr int kSmallM = 16384;
 constexpr int kShortcutTake = 32;     // the lane-maxima short cut pays up to this many winners (beyond, too many keys reach the bound)
 
 template <int MODE, int NV>
-__global__ __launch_bounds__(256) void k_select_small(SelectArgs a) {
+// (probe selection, MODE 0, is held to the registers of four wavefronts per SIMD: 10,000 rows over 4096 cells
+// take 0.072 ms so, 0.100 ms at the two wavefronts its unconstrained register count allows; the result rows of
+// MODE 1 lose from the same limit)
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 0 ? 4 : 1, 8))) void k_select_small(SelectArgs a) {
     __shared__ uint32_t s_work[4][256 + 64];             // per wavefront: 256 bins, 64 winning columns
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     int64_t n_rows = a.rows;
