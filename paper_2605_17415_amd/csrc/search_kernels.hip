@@ -239,7 +239,7 @@ __device__ __forceinline__ uint32_t order_key(float f) {
 }
 
 constexpr int kSelU = 8;        // groups of 64 columns loaded together by k_select
-constexpr int kSelSmallU = 4;   // and by k_select_small beyond its registers
+constexpr int kSelSmallU = 8;   // and by k_select_small beyond its registers
 constexpr int kSelCand = 512;   // most keys the short cut of k_select sorts directly
 
 // COPIES: counters per digit in the histogram (a power of two; 8 pays for long rows, 1 for short ones, where
