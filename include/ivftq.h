@@ -265,10 +265,12 @@ ivftq_status ivftq_export_list(const ivftq_index* index, int list, int64_t* ids_
  * metric 4 more per vector). */
 int64_t ivftq_index_bytes(const ivftq_index* index);
 /* Scan strategy of ivftq_search: 0 = default (the query-batched matrix-core scan when (d, b) is one
- * of its instantiated shapes, nprobe > 1 and the call brings at least 128 queries, else the streaming
- * scan, whose shorter chain of kernels is faster for a handful of queries), 1 = streaming scan only
- * (one workgroup per query and probed list), 2 = the batched scan wherever the shape allows, whatever
- * the number of queries.  Results obey the same contract in every mode. */
+ * of its instantiated shapes, nprobe > 1 and the call is large enough for it to pay: the bytes a
+ * per-query stream of the probed lists would read exceed 2.3 times the part of the index the call
+ * touches plus 0.25 GB, a few hundred queries on a 10M-vector index; else the streaming scan, whose
+ * shorter chain of kernels is faster for smaller calls), 1 = streaming scan only (a row of workgroups
+ * per query walks its probed lists), 2 = the batched scan wherever the shape allows, whatever the
+ * size of the call.  Results obey the same contract in every mode. */
 ivftq_status ivftq_set_search_mode(ivftq_index* index, int mode);
 /* Raw metrics.  The paper puts every vector on the unit sphere (Section "Architecture", Indexing), where
  * inner product, cosine and L2 rank alike; this switch serves inputs whose lengths matter, with nothing

@@ -1350,19 +1350,24 @@ ivftq_status search_core(ivftq_index* ix, const float* q_dev, int64_t nq, int np
     const int64_t m_stride = std::max<int64_t>(4, round_up64(m_bound, 4));
     const int64_t ldS = round_up(ix->nlist, 4);
 
-    // Scan strategy.  Streaming: one workgroup per (query, probed list), every score written, exact
-    // selection.  Batched: pairs regrouped by list and scanned on the matrix cores against a
-    // threshold from each query's nearest lists.  The batched path reads a list once per 128 queries
-    // instead of once per query, but it is a chain of about fourteen kernels: below kBatchedMinQueries
-    // the streaming scan's shorter chain finishes first (measured with nprobe 32 / 32 / 64 at 1M x 128,
-    // 10M x 96 and 10M x 200: 64 queries 0.12 / 0.22 / 0.57 ms streaming against 0.16 / 0.29 / 0.59 ms
-    // batched, 256 queries 0.22 / 0.44 / 1.33 against 0.18 / 0.40 / 0.86 ms).  Mode 2 asks for the batched
-    // path whatever the number of queries.
-    constexpr int64_t kBatchedMinQueries = 128;
+    // Scan strategy.  Streaming: a row of workgroups per query walks its probed lists, every score written,
+    // exact selection.  Batched: pairs regrouped by list and scanned on the matrix cores against a
+    // threshold from each query's nearest lists.  The streaming scan's time follows the bytes it reads, once
+    // per query; the batched path reads a list once per 128 queries, so its time follows the part of the
+    // index the call touches, but it is a chain of about fourteen kernels with a fixed cost of its own.
+    // Batched when the streamed bytes exceed kBatchedGain times the touched bytes plus kBatchedFixedBytes
+    // (measured crossovers with nprobe 32 / 32 / 64 at 1M x 128, 10M x 96, 10M x 200: about 200, 380 and
+    // 170 queries, i.e. 0.41 / 1.5 / 2.7 GB streamed against an index of 0.066 / 0.58 / 1.04 GB).  Mode 2
+    // asks for the batched path whatever the size of the call.
+    constexpr double kBatchedGain = 2.3, kBatchedFixedBytes = 0.25e9;
     const int tq = batch_tile_queries(ix->d, bits);
     const int metric = ix->metric;      // a raw metric ranks by a per-vector transform of the estimate: streaming scan only
+    const double vec_bytes = (double)codes_store.words * 4 + 2;
+    const double index_bytes = (double)ix->ntotal * vec_bytes;
+    const double streamed = (double)nq * nprobe * ((double)ix->ntotal / ix->nlist) * vec_bytes;
+    const double touched = index_bytes * std::min(1.0, (double)nq * nprobe / ix->nlist);
     const bool batched = tq > 0 && nprobe > 1 && ix->search_mode != 1 && metric == IVFTQ_METRIC_COSINE &&
-                         (ix->search_mode == 2 || nq >= kBatchedMinQueries);
+                         (ix->search_mode == 2 || streamed >= kBatchedGain * touched + kBatchedFixedBytes);
     const int cap = std::min(2048, std::max(512, 16 * k));
     // error bound of a residual sum taken from the leading float16 parts alone (threshold pass)
     float cmax = 0.f;
@@ -1427,12 +1432,12 @@ ivftq_status search_core(ivftq_index* ix, const float* q_dev, int64_t nq, int np
         HIP_TRY(timed(ix, st, P_CAND_OFF, [&] {
             return launch_cand_offsets(ix->w_probe.as<int32_t>(), cnt, nprobe, ix->d_size.as<int32_t>(),
                                        ix->w_candoff.as<int32_t>(), k, cap, first, st); }));
-        auto stream_scan = [&](const int32_t* gate, int gate_begin, int blocks_per_query) {
+        auto stream_scan = [&](const int32_t* gate, int gate_begin, int blocks_per_query, int slices = 1) {
             return launch_list_scan(ix->w_z.as<float>(), ix->dp, ix->d, bits, cb,
                                     ix->w_probe.as<int32_t>(), ix->w_coarse.as<float>(),
                                     ix->w_candoff.as<int32_t>(), nprobe, codes_store, 0, cnt,
                                     ix->w_scores.as<float>(), m_stride, nullptr, gate, gate_begin, (int)gate_rows,
-                                    blocks_per_query, metric, ix->w_qnorm.as<float>(), st);
+                                    blocks_per_query, slices, metric, ix->w_qnorm.as<float>(), st);
         };
         SelectArgs sa{};
         sa.vals = ix->w_scores.as<float>(); sa.stride = m_stride; sa.rows = cnt; sa.k = k;
@@ -1444,10 +1449,28 @@ ivftq_status search_core(ivftq_index* ix, const float* q_dev, int64_t nq, int np
 
         if (!batched) {
             ix->last_batched_queries = 0;
-            // workgroups per query: each builds the query's table once and walks its share of the probes;
-            // fewer per query as the batch grows, as long as the launch still fills the chip
-            const int per_query = (int)std::min<int64_t>(nprobe, std::max<int64_t>(1, kStreamWorkgroups / cnt));
-            HIP_TRY(timed(ix, st, P_LIST_SCAN, [&] { return stream_scan(nullptr, 0, per_query); }));
+            // Slices.  A call that reads more bytes than the packed index holds reads lists again and again, but
+            // the index (580 MB at 10M x 96) is larger than the 256 MB memory-side cache, so little of it would
+            // still be there.  Every list is therefore dealt out in rounds of 256 vectors to `slices` workgroups
+            // that the launch runs one slice after the other: each slice covers about kStreamSliceBytes of the
+            // index, which stay cached while all queries pass over them (10M x 96, 4096 queries: scan 3.37 ->
+            // 2.69 ms with 4 slices; 2 slices, 290 MB each, gain nothing; rounds of 64 vectors lose the gain).
+            const int64_t typical = std::max<int64_t>(1, ix->ntotal / ix->nlist * nprobe);     // candidates per query
+            const int64_t bytes_per_vec = (int64_t)codes_store.words * 4 + 2 + (metric ? 4 : 0);
+            const int64_t index_bytes = ix->ntotal * bytes_per_vec;
+            int64_t slices = 1;
+            if (cnt * typical * bytes_per_vec > index_bytes)
+                slices = std::max<int64_t>(1, std::min<int64_t>(64, (index_bytes + kStreamSliceBytes - 1) / kStreamSliceBytes));
+            // workgroups per query and slice: each builds the query's table once and walks its share of the
+            // probes; fewer per query as the batch grows, as long as the launch still fills the chip
+            const int per_query = (int)std::min<int64_t>(nprobe, std::max<int64_t>(1, kStreamWorkgroups / (cnt * slices)));
+            // a handful of queries: one workgroup per (query, list) leaves most of the chip idle and each walks
+            // its list in a dozen rounds, so the lists are split until about 2048 workgroups are in the launch
+            slices = std::max(slices, std::min<int64_t>(16, 2048 / ((int64_t)per_query * cnt)));
+            // and, while a share of a typical list still fills two rounds, until about 8192 are (64 queries at
+            // 10M x 96: scan 0.100 -> 0.070 ms)
+            slices = std::max(slices, std::min<int64_t>(kStreamWorkgroups / ((int64_t)per_query * cnt), ix->ntotal / ix->nlist / 512));
+            HIP_TRY(timed(ix, st, P_LIST_SCAN, [&] { return stream_scan(nullptr, 0, per_query, (int)slices); }));
             if (two_step) {
                 // a handful of rows: one wavefront per (query, list) first, then one per query over the survivors
                 SelectArgs s_a = sa, s_b = sa;

@@ -16,6 +16,7 @@ constexpr int kMaxList = 16384;
 constexpr int kMaxK = 2048;
 constexpr int kPrefixFactorX2 = 2;   // twice the factor f in: dense prefix >= f * k * T / cap vectors
 constexpr int kStreamWorkgroups = 8192;             // workgroups the streaming scan aims to launch at least
+constexpr int64_t kStreamSliceBytes = 150ll << 20;  // part of the packed index one slice of a large streaming scan covers
 constexpr int kMaxGridCells = 4096;  // entries of the quantiser's uniform-grid index (32 KB of LDS)
 
 // Split float16 form used by the float16 matrix-core kernels: V = 1024*v, hi = fp16(V),
@@ -188,7 +189,7 @@ hipError_t launch_list_scan(const float* z, int z_pitch, int d, int b, const flo
                             const int32_t* probe, const float* coarse, const int32_t* cand_off,
                             int np, const ListStore& store, int64_t q_begin, int64_t q_count,
                             float* scores, int64_t m_stride, const int32_t* p_limit, const int32_t* gate,
-                            int gate_begin, int gate_rows, int blocks_per_query, int metric, const float* qnorm,
+                            int gate_begin, int gate_rows, int blocks_per_query, int slices, int metric, const float* qnorm,
                             hipStream_t st);
 // metric 0: the score is the estimate s^ of <q~, x~> itself.  Raw metrics (the store keeps |x|, qnorm[q] = |q|):
 // the scan writes a key that ranks like the metric and launch_metric_finish turns the selected keys into values:
@@ -198,7 +199,8 @@ hipError_t launch_metric_finish(float* scores, int64_t nq, int k, int metric, co
 // p_limit (may be null): only probes p < p_limit[q] are scanned.  gate (may be null; row = the query's index
 // without it): of the gate[0] queries listed in gate[1..] only entries [gate_begin, gate_begin + gate_rows) are
 // processed, entry g into score row g - gate_begin, so a buffer of gate_rows rows serves any number of listed
-// queries in several launches.  blocks_per_query: workgroups per query (0 = one per probe).
+// queries in several launches.  blocks_per_query: workgroups per query (0 = one per probe), each
+// walking its share of the probes; slices (not with a gate): workgroups that share every list.
 
 // Per row: the k largest of m values, sorted by (value desc, label asc).
 // mode 0 (probe selection): m = m_fixed for every row, label = column; writes int32 labels.

@@ -117,7 +117,7 @@ __global__ __launch_bounds__(256) void k_list_scan(const float* __restrict__ z, 
     const int64_t base_slot = store.list_off[l];
     float* out = scores + score_row * m_stride + cand_off[q * (np + 1) + p];
 
-    // with few (query, list) pairs in the launch a list is shared out over gridDim.z workgroups
+    // a list is dealt out in rounds of 256 vectors to the gridDim.z workgroups that share it
     for (int v = threadIdx.x + 256 * (int)blockIdx.z; v < n_l; v += 256 * (int)gridDim.z) {
         const int64_t slot = base_slot + v;
         const uint32_t* wp = store.codes + (slot >> 6) * words * 64 + (slot & 63);
@@ -1050,7 +1050,7 @@ hipError_t launch_list_scan(const float* z, int z_pitch, int d, int b, const flo
                             const int32_t* probe, const float* coarse, const int32_t* cand_off,
                             int np, const ListStore& store, int64_t q_begin, int64_t q_count,
                             float* scores, int64_t m_stride, const int32_t* p_limit, const int32_t* gate,
-                            int gate_begin, int gate_rows, int blocks_per_query, int metric, const float* qnorm,
+                            int gate_begin, int gate_rows, int blocks_per_query, int slices, int metric, const float* qnorm,
                             hipStream_t st) {
     if (q_count <= 0) return hipSuccess;
     if (metric && (!qnorm || !store.xnorm)) return hipErrorInvalidValue;
@@ -1059,9 +1059,9 @@ hipError_t launch_list_scan(const float* z, int z_pitch, int d, int b, const flo
     const size_t lds = direct ? (size_t)(d + (1 << b)) * sizeof(float) : lut_bytes;
     // gated: a fixed number of workgroup rows walks the list of marked queries
     dim3 grid((unsigned)(blocks_per_query > 0 ? blocks_per_query : np), (unsigned)(gate ? std::min<int64_t>(std::min<int64_t>(q_count, gate_rows), 256) : q_count));
-    // a handful of queries: one workgroup per (query, list) leaves most of the chip idle and each walks its
-    // list in a dozen rounds, so the lists are split until about 2048 workgroups are in the launch
-    if (!gate) grid.z = (unsigned)std::max<int64_t>(1, std::min<int64_t>(16, 2048 / ((int64_t)grid.x * grid.y)));
+    // slices: every list is dealt out in rounds of 256 vectors to that many workgroups (grid z, the slowest
+    // dimension of the dispatch order: the launch works through the index one slice at a time)
+    if (!gate) grid.z = (unsigned)std::max(1, std::min(slices, 64));
 #define IVFTQ_SCAN(BV)                                                                              \
     case BV:                                                                                        \
         if (direct)                                                                                 \

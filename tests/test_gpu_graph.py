@@ -14,8 +14,8 @@ pytestmark = pytest.mark.gpu
 
 @pytest.mark.parametrize("nq,mode", [(1, 0), (48, 0), (48, 2), (1, 2), (130, 0)])
 def test_search_replays_from_a_graph(nq, mode):
-    """mode 0 takes the streaming scan below 128 queries and the batched scan from there on; mode 2 the batched
-    scan at any size."""
+    """mode 0 takes the streaming scan for calls of this size and the batched scan for large ones; mode 2 the
+    batched scan at any size."""
     import paper_2605_17415_amd as pkg
     cs = gpu_cases.get_case("d128")
     dev = torch.device("cuda:0")
