@@ -442,12 +442,12 @@ def run_workload(torch, pkg, synth, key, w, nprobe, steps, warmup, sign_bit=Fals
                                        "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": bytes_s / (ls_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                                        "algorithmic_bytes_per_launch": bytes_s,
                                        "traffic": stored_traffic(key, nprobe, "list_scan_streaming")},
-                          "note": "ivftq_set_search_mode(1): one workgroup group per (query, probed list), every candidate's "
-                                  "packed codes and norm streamed once per query"}
+                          "note": "ivftq_set_search_mode(1): a row of workgroups per query walks its probed lists, every "
+                                  "candidate's packed codes and norm streamed once per query"}
 
-        # the same kernel with enough queries to fill the chip, and whole-search latency of small calls (mode 0
-        # takes the streaming path below 128 queries)
-        nq_l = min(2048, w.nq)
+        # the same kernel on a call that reads the index many times over (the launch then works through it in
+        # cache-sized slices), and whole-search latency of small calls (which mode 0 gives to the streaming path)
+        nq_l = min(4096, w.nq)
         ql = qd[:nq_l].contiguous()
         ix.set_search_mode(1)
         for _ in range(2):
