@@ -226,13 +226,23 @@ void k_batch_scan(BatchScanArgs a) {
         if (DENSE) {                               // float16 norm of the lane's own vector (NaN beyond the list)
             gp[0] = v_mine < n_l ? (uint32_t)a.store.gamma[slot] : 0x7E00u;
         } else {
+            // float16 norms of the lane's 16 result rows: four runs of four consecutive vectors, 8 bytes each
+            // (8-byte aligned: lists start at multiples of 64 slots).  A list's slots reach to a multiple of 64,
+            // so the reads stay inside the array also in the last slab, whose rows beyond the list are then
+            // replaced by NaN.
+            const uint16_t* gb = a.store.gamma + base_slot + slab * 32 + 4 * half;
 #pragma unroll
-            for (int r = 0; r < 16; r += 2) {      // float16 norms of the lane's 16 result rows, in pairs
-                const int v = slab * 32 + 8 * (r / 4) + 4 * half + (r % 4);      // even: the pair is 4-byte aligned
-                uint32_t pr = 0x7E007E00u;                                       // two float16 NaNs
-                if (v + 1 < n_l) pr = *reinterpret_cast<const uint32_t*>(a.store.gamma + base_slot + v);
-                else if (v < n_l) pr = (uint32_t)a.store.gamma[base_slot + v] | 0x7E000000u;
-                gp[r / 2] = pr;
+            for (int g = 0; g < 4; ++g) {
+                const uint2 pr2 = *reinterpret_cast<const uint2*>(gb + 8 * g);
+                gp[2 * g] = pr2.x;
+                gp[2 * g + 1] = pr2.y;
+            }
+            if (slab * 32 + 32 > n_l) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int v = slab * 32 + 8 * (r / 4) + 4 * half + (r % 4);
+                    if (v >= n_l) gp[r / 2] = (r & 1) ? ((gp[r / 2] & 0xFFFFu) | 0x7E000000u) : ((gp[r / 2] & 0xFFFF0000u) | 0x7E00u);
+                }
             }
         }
     };
