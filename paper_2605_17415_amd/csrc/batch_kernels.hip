@@ -217,11 +217,23 @@ void k_batch_scan(BatchScanArgs a) {
         const int v_mine = slab * 32 + jl;         // this lane de-quantises vector jl of the slab
         const int64_t slot = base_slot + (v_mine < n_l ? v_mine : n_l - 1);
         const uint32_t* wp = a.store.codes + (slot >> 6) * words * 64 + (slot & 63);
+        if (NW == 1 && words * 32 >= DP * B) {     // rows as long as the panel (the same for every lane): every word
+#pragma unroll                                    // exists, plain loads at constant offsets with nothing in between
+            for (int kb = 0; kb < KB; ++kb) w[kb][0] = wp[(int64_t)(((16 * kb + 8 * half) * B) >> 5) * 64];
+        } else {
 #pragma unroll
-        for (int kb = 0; kb < KB; ++kb) {
-            const int wi = ((16 * kb + 8 * half) * B) >> 5;
+            for (int kb = 0; kb < KB; ++kb) {
+                const int wi = ((16 * kb + 8 * half) * B) >> 5;
+                // the words of both halves of the wavefront exist (again the same for every lane): plain loads;
+                // else (the padding beyond a row shorter than the panel) lane by lane
+                if ((((16 * kb + 8) * B) >> 5) + NW - 1 < words) {
 #pragma unroll
-            for (int e = 0; e < NW; ++e) w[kb][e] = (wi + e < words) ? wp[(int64_t)(wi + e) * 64] : 0u;
+                    for (int e = 0; e < NW; ++e) w[kb][e] = wp[(int64_t)(wi + e) * 64];
+                } else {
+#pragma unroll
+                    for (int e = 0; e < NW; ++e) w[kb][e] = (wi + e < words) ? wp[(int64_t)(wi + e) * 64] : 0u;
+                }
+            }
         }
         if (DENSE) {                               // float16 norm of the lane's own vector (NaN beyond the list)
             gp[0] = v_mine < n_l ? (uint32_t)a.store.gamma[slot] : 0x7E00u;
