@@ -340,8 +340,11 @@ void k_batch_scan(BatchScanArgs a) {
         if constexpr (!DENSE) {
             // ---- threshold pass.  A lane holds one query's 16 accumulators per tile; row r is the vector
             // 8*(r/4) + 4*half + r%4 of the slab, its norm the half r%2 of cg[r/2] (NaN beyond the list).
+            // (the register is hidden from the compiler at the point of use: it would otherwise convert all 16
+            // norms once per slab, ahead of the tiles, although only the rare tile with a candidate reads them)
             auto norm_of = [&](int r) -> float {
-                const uint32_t pr = cg[r / 2];
+                uint32_t pr = cg[r / 2];
+                if constexpr (DP <= 128) asm volatile("" : "+v"(pr));     // (beyond: measured slower, it spills)
                 return kUnscale * __half2float(__ushort_as_half((uint16_t)((r & 1) ? (pr >> 16) : (pr & 0xFFFFu))));
             };
             // the largest norm among this lane's rows (packed float16 maxima, which skip the NaNs)
