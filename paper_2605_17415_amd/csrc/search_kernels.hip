@@ -548,7 +548,9 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a) {
 constexpr int kSmallM = 16384;
 constexpr int kShortcutTake = 32;     // the lane-maxima short cut pays up to this many winners (beyond, too many keys reach the bound)
 
-template <int MODE, int NV>
+// WIDE: the instantiation for more than kShortcutTake winners (its second short cut costs the common case of
+// fewer winners a fifth of its speed when both sit in one kernel).
+template <int MODE, int NV, bool WIDE = false>
 // (probe selection, MODE 0, is held to the registers of four wavefronts per SIMD: 10,000 rows over 4096 cells
 // take 0.072 ms so, 0.100 ms at the two wavefronts its unconstrained register count allows; the result rows of
 // MODE 1 lose from the same limit)
@@ -660,6 +662,82 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MODE == 0 ?
                     }
                 }
                 if (lane < take) win_col[lane] = cc;
+                done = true;
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();         // the words of `hist` are free again
+        }
+    }
+    // The same idea for up to 64 winners, with two maxima per lane (over the even and over the odd 64-column
+    // blocks of the row): the take-th largest of these 128 is again reached by at least `take` keys, and by few
+    // more.  It is found by bisection on the key's bits (two ballots a bit); up to 128 keys that reach it are
+    // compacted into LDS and every one counts the keys that precede it in (key desc, column asc) order, which is
+    // its place among the winners.
+    if (WIDE && !done && take > kShortcutTake && take <= 64) {
+        uint32_t gm0 = 0u, gm1 = 0u;
+#pragma unroll
+        for (int e = 0; e < NV; ++e) {
+            const bool in = e * 64 + lane < m;
+            if (e & 1) gm1 = (in && keys[e] > gm1) ? keys[e] : gm1;
+            else gm0 = (in && keys[e] > gm0) ? keys[e] : gm0;
+        }
+        static_assert(NV % 2 == 0 && kSelSmallU % 2 == 0, "block parity below");
+        for (int i0 = NV * 64; i0 < m; i0 += 64 * kSelSmallU) {
+            float v[kSelSmallU];
+#pragma unroll
+            for (int u = 0; u < kSelSmallU; ++u) { const int i = i0 + 64 * u + lane; v[u] = vals[i < m ? i : m - 1]; }
+#pragma unroll
+            for (int u = 0; u < kSelSmallU; ++u) {
+                const uint32_t key = key_of(v[u]);
+                const bool in = i0 + 64 * u + lane < m;
+                if (u & 1) gm1 = (in && key > gm1) ? key : gm1;
+                else gm0 = (in && key > gm0) ? key : gm0;
+            }
+        }
+        uint32_t reach = 0u;
+        for (int bit = 31; bit >= 0; --bit) {
+            const uint32_t test = reach | (1u << bit);
+            const int cnt = __popcll(__ballot(gm0 >= test)) + __popcll(__ballot(gm1 >= test));
+            if (cnt >= take) reach = test;
+        }
+        if (reach != 0u) {
+            uint32_t* c_key = hist;                      // [128] keys that reach it, [128] their columns
+            int* c_col = reinterpret_cast<int*>(hist + 128);
+            uint32_t count = 0;
+            auto collect = [&](int i, uint32_t key) {
+                const bool in = i < m && key >= reach;
+                const uint64_t b = __ballot(in);
+                const uint32_t pos = count + (uint32_t)__popcll(b & (((uint64_t)1 << lane) - 1));
+                if (in && pos < 128u) { c_key[pos] = key; c_col[pos] = i; }
+                count += (uint32_t)__popcll(b);
+            };
+#pragma unroll
+            for (int e = 0; e < NV; ++e)
+                if (e * 64 < m) collect(e * 64 + lane, keys[e]);
+            for (int i0 = NV * 64; i0 < m && count <= 128u; i0 += 64 * kSelSmallU) {
+                float v[kSelSmallU];
+#pragma unroll
+                for (int u = 0; u < kSelSmallU; ++u) { const int i = i0 + 64 * u + lane; v[u] = vals[i < m ? i : m - 1]; }
+#pragma unroll
+                for (int u = 0; u < kSelSmallU; ++u)
+                    if (i0 + 64 * u < m) collect(i0 + 64 * u + lane, key_of(v[u]));
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            if (count <= 128u) {
+                const int n_c = (int)count;
+                const bool has0 = lane < n_c, has1 = lane + 64 < n_c;
+                const uint32_t k0 = has0 ? c_key[lane] : 0u, k1 = has1 ? c_key[lane + 64] : 0u;
+                const int c0 = has0 ? c_col[lane] : 0, c1 = has1 ? c_col[lane + 64] : 0;
+                int r0 = 0, r1 = 0;
+                for (int jj = 0; jj < n_c; ++jj) {
+                    const uint32_t kj = c_key[jj];
+                    const int cj = c_col[jj];
+                    r0 += (kj > k0 || (kj == k0 && cj < c0)) ? 1 : 0;
+                    r1 += (kj > k1 || (kj == k1 && cj < c1)) ? 1 : 0;
+                }
+                if (has0 && r0 < take) win_col[r0] = c0;
+                if (has1 && r1 < take) win_col[r1] = c1;
                 done = true;
             }
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -1087,10 +1165,10 @@ hipError_t launch_metric_finish(float* scores, int64_t nq, int k, int metric, co
 }
 
 // Longest row the one-wavefront-per-row kernel takes.  Probe selection (mode 0, every row has m_fixed values):
-// beyond the columns it holds in registers the workgroup-per-row kernel is faster when the radix search runs
-// (measured at 4096 cells: 0.145 against 0.19 ms for 10,000 rows), the wavefront kernel when its short cut
-// applies (0.094 ms); result rows (mode 1) are mostly much shorter than their bound.
-constexpr int kSmallMax0 = 2048, kSmallMax0Shortcut = 8192, kSmallMax1 = kSmallM;
+// its short cuts (up to 64 winners) beat the workgroup-per-row kernel well beyond the columns it holds in
+// registers (10,000 rows over 4096 cells: 0.069 ms for 32 winners, against 0.145 ms); result rows (mode 1)
+// are mostly much shorter than their bound.
+constexpr int kSmallMax0Shortcut = 8192, kSmallMax1 = kSmallM;
 hipError_t launch_select(int mode, const SelectArgs& a_in, hipStream_t st) {
     if (a_in.rows <= 0) return hipSuccess;
     SelectArgs a = a_in;
@@ -1109,11 +1187,13 @@ hipError_t launch_select(int mode, const SelectArgs& a_in, hipStream_t st) {
     }
     // short rows and small k: the one-wavefront-per-row kernel
     const int m_bound = mode == 0 ? a.m_fixed : a.m_bound;
-    if (a.k <= 64 && m_bound > 0 && m_bound <= (mode == 0 ? (a.k <= kShortcutTake ? kSmallMax0Shortcut : kSmallMax0) : kSmallMax1)) {
+    if (a.k <= 64 && m_bound > 0 && m_bound <= (mode == 0 ? kSmallMax0Shortcut : kSmallMax1)) {
         const size_t lds = 0;
         const unsigned blocks = (unsigned)((a.gate ? std::min<int64_t>(std::min<int64_t>(a.rows, a.gate_rows), 1024) : a.rows) + 3) / 4;
 #define IVFTQ_SMALL(NVV)                                                                            \
-        if (mode == 0) hipLaunchKernelGGL((k_select_small<0, NVV>), dim3(blocks), dim3(256), lds, st, a);  \
+        if (mode == 0 && a.k > kShortcutTake) hipLaunchKernelGGL((k_select_small<0, NVV, true>), dim3(blocks), dim3(256), lds, st, a);  \
+        else if (mode == 0) hipLaunchKernelGGL((k_select_small<0, NVV>), dim3(blocks), dim3(256), lds, st, a);  \
+        else if (a.k > kShortcutTake) hipLaunchKernelGGL((k_select_small<1, NVV, true>), dim3(blocks), dim3(256), lds, st, a);  \
         else hipLaunchKernelGGL((k_select_small<1, NVV>), dim3(blocks), dim3(256), lds, st, a);
         if (m_bound <= 1536) { IVFTQ_SMALL(16) } else { IVFTQ_SMALL(32) }
 #undef IVFTQ_SMALL

@@ -14,7 +14,7 @@ DEV = "cuda:0"
 TOL = 1e-5
 
 
-@pytest.mark.parametrize("L,nprobe", [(4096, 100), (4096, 128), (4096, 192), (4096, 200), (4096, 256), (2500, 150), (9000, 96)])
+@pytest.mark.parametrize("L,nprobe", [(4096, 33), (4096, 40), (4096, 64), (2500, 50), (8000, 64), (1200, 48), (4096, 100), (4096, 128), (4096, 192), (4096, 200), (4096, 256), (2500, 150), (9000, 96)])
 def test_probe_selection_with_exact_ties(L, nprobe):
     import paper_2605_17415_amd as pkg
     d, nq = 32, 300
