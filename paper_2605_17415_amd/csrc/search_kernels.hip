@@ -1195,7 +1195,7 @@ hipError_t launch_select(int mode, const SelectArgs& a_in, hipStream_t st) {
         else if (mode == 0) hipLaunchKernelGGL((k_select_small<0, NVV>), dim3(blocks), dim3(256), lds, st, a);  \
         else if (a.k > kShortcutTake) hipLaunchKernelGGL((k_select_small<1, NVV, true>), dim3(blocks), dim3(256), lds, st, a);  \
         else hipLaunchKernelGGL((k_select_small<1, NVV>), dim3(blocks), dim3(256), lds, st, a);
-        if (m_bound <= 1536) { IVFTQ_SMALL(16) } else { IVFTQ_SMALL(32) }
+        if (m_bound <= 1536 || mode == 1) { IVFTQ_SMALL(16) } else { IVFTQ_SMALL(32) }
 #undef IVFTQ_SMALL
         return hipGetLastError();
     }
