@@ -145,7 +145,7 @@ __global__ __launch_bounds__(256) void k_list_scan(const float* __restrict__ z, 
             asm volatile("" : "+s"(lut_at));
             // opaque, so that the tests below stay scalar compares inside the loop instead of a set of flags
             // computed ahead of it
-            chunks = lut_at == 0 ? d >> 5 : 0;
+            chunks = lut_at == 0 ? ((d >> 5) < kMaxChunks ? (d >> 5) : kMaxChunks) : 0;
             asm volatile("" : "+s"(chunks));
             uint32_t cur[B];
             if (chunks > 0) {

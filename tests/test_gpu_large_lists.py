@@ -65,7 +65,7 @@ def test_many_cells_match_oracle(case):
     ix.add_encoded(torch.from_numpy(enc["assign"]).to(dev), torch.from_numpy(enc["codes"]).to(dev),
                    torch.from_numpy(enc["gamma16"]).to(dev))
     q = torch.from_numpy(Q).to(dev)
-    for mode in (2, 1):
+    for mode in (2, 1, 0):
         print(f"[large lists] GPU search mode {mode}", flush=True)
         ix.set_search_mode(mode)
         sc, ids = ix.search(q, nprobe, k)
@@ -73,4 +73,14 @@ def test_many_cells_match_oracle(case):
         rs = parity.compare_search(sc.cpu().numpy(), ids.cpu().numpy(), o_sc, o_ids, o_all, gap)
         print(f"search mode {mode}:", rs, flush=True)
         assert rs["probe_near_tie_excused"] <= max(1, nq // 10)
+        if mode == 0:
+            # the default mode weighs the bytes a per-query stream would read against the index it touches:
+            # the batched scan is its choice exactly when they exceed 2.3 times the touched bytes plus 0.25 GB
+            vec_bytes = 4 * ((d * b + 31) // 32) + 2
+            streamed = nq * nprobe * (n / L) * vec_bytes
+            touched = n * vec_bytes * min(1.0, nq * nprobe / L)
+            expect_batched = streamed >= 2.3 * touched + 0.25e9
+            took_batched = ix.scan_stats()["queries"] == nq
+            print(f"  default mode: streamed {streamed / 1e6:.0f} MB, touched {touched / 1e6:.0f} MB -> batched {took_batched}", flush=True)
+            assert took_batched == expect_batched
     ix.close()
