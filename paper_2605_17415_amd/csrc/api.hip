@@ -1431,7 +1431,8 @@ ivftq_status search_core(ivftq_index* ix, const float* q_dev, int64_t nq, int np
         int32_t* first = batched ? ix->w_first.as<int32_t>() : nullptr;
         HIP_TRY(timed(ix, st, P_CAND_OFF, [&] {
             return launch_cand_offsets(ix->w_probe.as<int32_t>(), cnt, nprobe, ix->d_size.as<int32_t>(),
-                                       ix->w_candoff.as<int32_t>(), k, cap, first, st); }));
+                                       ix->w_candoff.as<int32_t>(), k, cap, first,
+                                       batched ? ix->w_ccnt.as<int32_t>() : nullptr, batched ? ix->w_gate.as<int32_t>() : nullptr, st); }));
         auto stream_scan = [&](const int32_t* gate, int gate_begin, int blocks_per_query, int slices = 1) {
             return launch_list_scan(ix->w_z.as<float>(), ix->dp, ix->d, bits, cb,
                                     ix->w_probe.as<int32_t>(), ix->w_coarse.as<float>(),
@@ -1495,8 +1496,6 @@ ivftq_status search_core(ivftq_index* ix, const float* q_dev, int64_t nq, int np
                                                 ix->w_count.as<uint32_t>(), ix->w_count.as<uint32_t>() + 2 * ix->nlist,
                                                 ix->w_pairoff.as<int64_t>(), ix->w_tileoff.as<int32_t>(),
                                                 ix->w_pairs.as<int32_t>(), st);
-            if (e == hipSuccess) e = launch_fill_u32(ix->w_ccnt.as<uint32_t>(), cnt, 0u, st);
-            if (e == hipSuccess) e = launch_fill_u32(ix->w_gate.as<uint32_t>(), 1, 0u, st);
             return e; }));
         BatchScanArgs ba{};
         ba.zh = ix->w_zh.as<uint16_t>(); ba.zl = ix->w_zl.as<uint16_t>(); ba.z_pitch = ix->dp;

@@ -181,9 +181,11 @@ hipError_t launch_inertia(const float* best, int64_t n, double* out, hipStream_t
 
 // cand_off[q*(np+1) + p] = sum_{p'<p} list_size[probe[q][p']]
 // first (may be null): first[q] = shortest probe prefix (>= 1 cell) holding at least
-// max(k, 2*k*T/cap) vectors, T the query's candidate total; np if there is none
+// max(k, 2*k*T/cap) vectors, T the query's candidate total; np if there is none.  With `first`, cand_cnt[q]
+// and gate[0] (each may be null) are set to zero: the counters the batched scan and its merge add to.
 hipError_t launch_cand_offsets(const int32_t* probe, int64_t nq, int np, const int32_t* list_size,
-                               int32_t* cand_off, int k, int cap, int32_t* first, hipStream_t st);
+                               int32_t* cand_off, int k, int cap, int32_t* first, int32_t* cand_cnt, int32_t* gate,
+                               hipStream_t st);
 // scores[row*m_stride + cand_off[q][p] + i] = coarse[q][p] + gamma_i * sum_j z_qj * C[code_ij]
 hipError_t launch_list_scan(const float* z, int z_pitch, int d, int b, const float* cb,
                             const int32_t* probe, const float* coarse, const int32_t* cand_off,

@@ -17,7 +17,8 @@ namespace {
 // the query's threshold (see the kernel), or np when all probed cells together hold too few vectors.
 __global__ __launch_bounds__(256) void k_cand_offsets(const int32_t* __restrict__ probe, int64_t nq, int np,
                                                       const int32_t* __restrict__ list_size, int32_t* __restrict__ cand_off,
-                                                      int k, int cap, int32_t* __restrict__ first) {
+                                                      int k, int cap, int32_t* __restrict__ first,
+                                                      int32_t* __restrict__ cand_cnt, int32_t* __restrict__ gate) {
     // one wavefront per query: 64 probes at a time, running sum over the lanes
     const int lane = threadIdx.x & 63;
     const int64_t q = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -59,7 +60,12 @@ __global__ __launch_bounds__(256) void k_cand_offsets(const int32_t* __restrict_
         if (reached) p1 = p0 + (int)__builtin_ctzll(reached) + 1;
         run2 += __shfl(incl, 63);
     }
-    if (lane == 0) first[q] = p1;
+    if (lane == 0) {
+        first[q] = p1;
+        // the counters of the batched scan start at zero (cleared here rather than by launches of their own)
+        if (cand_cnt) cand_cnt[q] = 0;
+        if (gate && q == 0) gate[0] = 0;
+    }
 }
 
 // ---- list scan: one workgroup per (query, probed list) ---------------------------------------
@@ -1117,10 +1123,11 @@ hipError_t launch_rerank(const RerankArgs& a, int64_t nq, hipStream_t st) {
 }
 
 hipError_t launch_cand_offsets(const int32_t* probe, int64_t nq, int np, const int32_t* list_size,
-                               int32_t* cand_off, int k, int cap, int32_t* first, hipStream_t st) {
+                               int32_t* cand_off, int k, int cap, int32_t* first, int32_t* cand_cnt, int32_t* gate,
+                               hipStream_t st) {
     if (nq <= 0) return hipSuccess;
     hipLaunchKernelGGL(k_cand_offsets, dim3((unsigned)((nq + 3) / 4)), dim3(256), 0, st, probe, nq, np,
-                       list_size, cand_off, k, cap, first);
+                       list_size, cand_off, k, cap, first, cand_cnt, gate);
     return hipGetLastError();
 }
 
