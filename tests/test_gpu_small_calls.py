@@ -1,7 +1,8 @@
-"""ivftq_search in its default mode across the sizes where it changes strategy (streaming scan with the
-selection in two steps up to 64 queries, streaming scan with one selection per query up to 127, the
-query-batched scan from 128 on), against the oracle on the same stored codes, and the same queries answered
-identically (labels, scores to rounding) whatever call they arrive in."""
+"""ivftq_search in its default mode across the call sizes where the streaming path changes strategy (selection in
+two steps up to 64 queries, one selection per query beyond; lists shared out over more workgroups the fewer
+queries there are), against the oracle on the same stored codes, and the same queries answered identically
+(labels, scores to rounding) whatever call they arrive in.  (Calls large enough for the default mode to take the
+query-batched scan are in test_gpu_large_lists.py and the full-size tests.)"""
 import numpy as np
 import pytest
 
