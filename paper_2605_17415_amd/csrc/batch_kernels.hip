@@ -623,11 +623,16 @@ hipError_t run_batch(const BatchScanArgs& a, int max_tiles, hipStream_t st) {
 
 }  // namespace
 
+// Panel width of the batched scan for rows of d coordinates: the padded width of the rotated queries (a multiple
+// of 32), except that 193 ... 208 coordinates take 13 blocks of 16 rather than 14 (d = 200: a fourteenth less to
+// de-quantise and multiply).
+static int batch_dp(int d) { return (d > 192 && d <= 208) ? 208 : rot_dp(d); }
+
 int batch_tile_queries(int d, int b) {
-    const int dp = rot_dp(d);
+    const int dp = batch_dp(d);
     if (b < 2 || b > 5) return 0;
     if (dp == 64 || dp == 96 || dp == 128) return 128;
-    if (dp == 224) return 128;
+    if (dp == 208 || dp == 224) return 128;
     return 0;
 }
 
@@ -660,7 +665,7 @@ hipError_t launch_pair_grouping(const int32_t* probe, const int32_t* first, int6
 
 hipError_t launch_batch_scan(const BatchScanArgs& a, int d, int b, int max_tiles, hipStream_t st) {
     if (max_tiles <= 0) return hipSuccess;
-    const int dp = rot_dp(d);
+    const int dp = batch_dp(d);
     // <coordinates, queries per tile / 32, wavefronts per SIMD of the dense pass, wavefronts per workgroup and per
     // SIMD of the threshold pass>; the dense pass runs eight wavefronts per workgroup
 #define IVFTQ_BATCH(DPV, NQV, OCCV, WT, OT)                                                                       \
@@ -673,6 +678,7 @@ hipError_t launch_batch_scan(const BatchScanArgs& a, int d, int b, int max_tiles
     IVFTQ_BATCH(64, 4, 2, 4, 3)
     IVFTQ_BATCH(96, 4, 2, 4, 3)
     IVFTQ_BATCH(128, 4, 2, 4, 3)
+    IVFTQ_BATCH(208, 4, 2, 4, 2)
     IVFTQ_BATCH(224, 4, 2, 4, 2)
 #undef IVFTQ_BATCH
     return hipErrorInvalidValue;
