@@ -217,9 +217,18 @@ void k_batch_scan(BatchScanArgs a) {
         const int v_mine = slab * 32 + jl;         // this lane de-quantises vector jl of the slab
         const int64_t slot = base_slot + (v_mine < n_l ? v_mine : n_l - 1);
         const uint32_t* wp = a.store.codes + (slot >> 6) * words * 64 + (slot & 63);
-        if (NW == 1 && words * 32 >= DP * B) {     // rows as long as the panel (the same for every lane): every word
-#pragma unroll                                    // exists, plain loads at constant offsets with nothing in between
+        // Blocks whose words exist for both halves of the wavefront (the same for every lane) are loaded at constant
+        // offsets with no tests in between: all of them when the rows are as long as the panel, all but the last
+        // for a row that ends inside the last block (d = 200 in a 208-wide panel); else block by block.
+        const int last_whole = ((16 * (KB - 1) + 8) * B) >> 5;      // first word of the last block's upper half
+        if (NW == 1 && last_whole < words) {
+#pragma unroll
             for (int kb = 0; kb < KB; ++kb) w[kb][0] = wp[(int64_t)(((16 * kb + 8 * half) * B) >> 5) * 64];
+        } else if (NW == 1 && KB > 1 && (((16 * (KB - 2) + 8) * B) >> 5) < words) {
+#pragma unroll
+            for (int kb = 0; kb < KB - 1; ++kb) w[kb][0] = wp[(int64_t)(((16 * kb + 8 * half) * B) >> 5) * 64];
+            const int wi = ((16 * (KB - 1) + 8 * half) * B) >> 5;
+            w[KB - 1][0] = wi < words ? wp[(int64_t)wi * 64] : 0u;
         } else {
 #pragma unroll
             for (int kb = 0; kb < KB; ++kb) {
