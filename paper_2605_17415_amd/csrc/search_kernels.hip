@@ -68,7 +68,7 @@ __global__ __launch_bounds__(256) void k_cand_offsets(const int32_t* __restrict_
     }
 }
 
-// ---- list scan: one workgroup per (query, probed list) ---------------------------------------
+// ---- list scan: a row of workgroups per query walks its probed lists ---------------------------
 //
 // The query's rotated coordinates and the 2^b centroid values are combined once per workgroup
 // into a table lut[j][e] = z_j * C[e] in LDS (the per-query ADC table the paper's own scan uses,
