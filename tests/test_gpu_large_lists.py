@@ -22,6 +22,11 @@ CASES = [
     (96, 64, 4, 200_000, 300, 8, 10, 0.0),
     (200, 40, 4, 120_000, 150, 6, 100, 0.5),
     (64, 16, 2, 60_000, 200, 16, 40, 0.0),
+    # 193 ... 208 coordinates: the batched scan's 208-wide panel (13 blocks of 16), rows that end inside and at
+    # the end of the last block, codes that straddle words (b = 3)
+    (193, 64, 2, 60_000, 150, 8, 10, 0.0),
+    (208, 64, 3, 60_000, 150, 8, 10, 0.0),
+    (205, 32, 4, 64_000, 100, 4, 100, 0.0),
 ]
 
 
